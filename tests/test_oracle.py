@@ -1,0 +1,392 @@
+"""Pins of the CPU oracle against what the thesis and the mathematics fix.
+
+No expected value below is produced by the oracle itself: they come from the
+thesis's worked figure (tests/golden/adc_figure.txt), from numpy float64 brute
+force on tiny inputs, from closed forms and from invariants.  CPU only.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pq_oracle as orc
+from paper_1712_02912_amd import datagen
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers (numpy, float64)
+def np_luts(queries, codebooks):
+    """Eq. (tables) written with numpy broadcasting in float64."""
+    nq, d = queries.shape
+    m, k, dsub = codebooks.shape
+    y = queries.astype(np.float64).reshape(nq, m, 1, dsub)
+    c = codebooks.astype(np.float64).reshape(1, m, k, dsub)
+    return ((y - c) ** 2).sum(-1)
+
+
+def unpack_u4(packed):
+    n, half = packed.shape
+    out = np.empty((n, 2 * half), np.uint8)
+    out[:, 0::2] = packed & 15
+    out[:, 1::2] = packed >> 4
+    return out
+
+
+def np_topk(values, ids, k):
+    """k smallest by (value, id) through a full lexicographic sort."""
+    order = np.lexsort((ids, values))[:k]
+    return values[order], ids[order]
+
+
+def small_problem(seed=0, n=1500, d=32, m=4, k=16, nq=5, ntrain=600):
+    mix = datagen.Mixture(d, 8, (0.0, 128.0), (8.0, 32.0), (0.0, 255.0), seed=seed + 1)
+    train = mix.sample(ntrain, seed + 2)
+    base = mix.sample(n, seed + 3)
+    queries = mix.sample(nq, seed + 4)
+    cb = orc.pq_train(train, m, k, 5, datagen.kmeans_init_idx(ntrain, m, k, seed + 5))
+    return mix, train, base, queries, cb
+
+
+# ----------------------------------------------------------------------------- worked example (Fig. ADC)
+def load_figure():
+    code, rows, total = None, {}, None
+    with open(os.path.join(GOLDEN, "adc_figure.txt")) as f:
+        for line in f:
+            tok = line.split()
+            if not tok or tok[0].startswith("#"):
+                continue
+            if tok[0] == "code":
+                code = np.array([int(t, 16) for t in tok[1:]], np.uint8)
+            elif tok[0] == "row":
+                rows[int(tok[1])] = [float(t) for t in tok[2:]]
+            elif tok[0] == "sum":
+                total = float(tok[1])
+    lut = np.full((8, 256), 1000.0, np.float32)  # elided columns: a value that would ruin the sum
+    for j, vals in rows.items():
+        lut[j, [0, 1, 2, 3, 4, 255]] = vals
+    return code, lut, total
+
+
+def test_worked_example_figure_adc():
+    code, lut, total = load_figure()
+    dist = orc.adc_all_f32(code[None, :], orc.CODES_U8, lut)
+    assert dist[0] == total == 26.0
+    # component 0 is the first byte: reversing the code must change the result
+    rev = orc.adc_all_f32(code[None, ::-1].copy(), orc.CODES_U8, lut)
+    assert rev[0] != total
+    # the same through the scan (heap) entry point
+    d, i = orc.adc_scan_topk_f32(code[None, :], orc.CODES_U8, lut[None], 1)
+    assert d[0, 0] == 26.0 and i[0, 0] == 0
+
+
+# ----------------------------------------------------------------------------- tables, Eq. (tables)
+def test_luts_bruteforce_and_cdist():
+    _, _, _, queries, cb = small_problem()
+    luts = orc.build_luts(queries, cb)
+    ref = np_luts(queries, cb)
+    np.testing.assert_allclose(luts, ref, rtol=1e-6)  # one rounding to float
+    assert np.all(luts == ref.astype(np.float32))
+    m, k, dsub = cb.shape
+    for j in range(m):  # independent library route: cdist in float64, squared
+        cd = torch.cdist(torch.from_numpy(queries[:, j * dsub:(j + 1) * dsub]).double(),
+                         torch.from_numpy(cb[j]).double()).numpy() ** 2
+        np.testing.assert_allclose(luts[:, j, :], cd, rtol=1e-5, atol=1e-6)
+
+
+def test_luts_asymmetric_in_operands():
+    # a transposed/swapped operand would show on a hand-made case
+    queries = np.array([[1.0, 2.0, 10.0, 20.0]], np.float32)  # m=2, dsub=2
+    cb = np.array([[[0.0, 0.0], [1.0, 2.0], [2.0, 4.0]],
+                   [[10.0, 20.0], [0.0, 0.0], [13.0, 24.0]]], np.float32)
+    luts = orc.build_luts(queries, cb)
+    assert luts.tolist() == [[[5.0, 0.0, 5.0], [0.0, 500.0, 25.0]]]
+
+
+# ----------------------------------------------------------------------------- encoder
+def test_encode_bruteforce_and_idempotent():
+    _, _, base, _, cb = small_problem()
+    codes = orc.pq_encode(base, cb)
+    m, k, dsub = cb.shape
+    for j in range(m):
+        sub = base[:, j * dsub:(j + 1) * dsub].astype(np.float64)
+        dist = ((sub[:, None, :] - cb[j].astype(np.float64)[None]) ** 2).sum(-1)
+        assert np.array_equal(codes[:, j], dist.argmin(1))
+    decoded = np.concatenate([cb[j][codes[:, j]] for j in range(m)], axis=1)
+    assert np.array_equal(orc.pq_encode(decoded, cb), codes)
+
+
+def test_kmeans_one_iteration_closed_form():
+    r = np.random.default_rng(3)
+    x = r.normal(size=(300, 3)).astype(np.float32)
+    init = np.array([5, 17, 100, 250], np.int64)
+    cent = orc.kmeans(x, 4, 1, init)
+    c0 = x[init].astype(np.float64)
+    assign = ((x[:, None, :].astype(np.float64) - c0[None]) ** 2).sum(-1).argmin(1)
+    for i in range(4):
+        np.testing.assert_allclose(cent[i], x[assign == i].astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
+
+
+def test_kmeans_separated_clusters_and_objective():
+    r = np.random.default_rng(4)
+    centers = np.array([[0, 0], [100, 0], [0, 100]], np.float64)
+    lab = r.integers(0, 3, 900)
+    x = (centers[lab] + r.normal(size=(900, 2))).astype(np.float32)
+    init = np.array([np.flatnonzero(lab == i)[0] for i in range(3)], np.int64)
+    cent = orc.kmeans(x, 3, 10, init)
+    for i in range(3):
+        np.testing.assert_allclose(cent[i], x[lab == i].astype(np.float64).mean(0), rtol=1e-5, atol=1e-5)
+
+    xs = r.normal(size=(500, 4)).astype(np.float32) * 10
+
+    def objective(c):
+        return ((xs[:, None, :].astype(np.float64) - c[None].astype(np.float64)) ** 2).sum(-1).min(1).sum()
+
+    ini = np.arange(8, dtype=np.int64)
+    objs = [objective(orc.kmeans(xs, 8, it, ini)) for it in (1, 2, 4, 8)]
+    assert all(a >= b - 1e-6 for a, b in zip(objs, objs[1:]))
+
+
+def test_kmeans_empty_cluster_reseeded():
+    # two identical initial centroids: the second cell is empty after the first assignment
+    x = np.array([[0.0], [0.0], [1.0], [10.0]], np.float32)
+    cent = orc.kmeans(x, 2, 1, np.array([0, 1], np.int64))
+    # cell 0 takes everything (mean 2.75); cell 1 is re-seeded with the farthest point (10)
+    assert cent[:, 0].tolist() == [2.75, 10.0]
+
+
+# ----------------------------------------------------------------------------- ADC, Eq. (adc1) / (adc2)
+def test_adc_equals_sum_of_subspace_distances():
+    _, _, base, queries, cb = small_problem()
+    codes = orc.pq_encode(base, cb)
+    luts = orc.build_luts(queries, cb)
+    m, k, dsub = cb.shape
+    decoded = np.concatenate([cb[j][codes[:, j]] for j in range(m)], axis=1).astype(np.float64)
+    for q in range(len(queries)):
+        got = orc.adc_all_f32(codes, orc.CODES_U8, luts[q])
+        # Eq. (adc2) straight from the codebooks, no table involved; equals ||y - decode(c)||^2
+        direct = ((queries[q].astype(np.float64)[None] - decoded) ** 2).sum(1)
+        np.testing.assert_allclose(got, direct, rtol=2e-6)
+
+
+def test_adc_m1_is_table_lookup_and_k1_is_constant():
+    r = np.random.default_rng(5)
+    lut = r.random((1, 256)).astype(np.float32)
+    codes = r.integers(0, 256, (500, 1), dtype=np.uint8)
+    assert np.array_equal(orc.adc_all_f32(codes, orc.CODES_U8, lut), lut[0][codes[:, 0]])
+    lut1 = r.random((6, 1)).astype(np.float32)
+    codes0 = np.zeros((50, 6), np.uint8)
+    d = orc.adc_all_f32(codes0, orc.CODES_U8, lut1)
+    assert np.all(d == np.float32(lut1.astype(np.float64).sum()))
+    # all-equal distances: top-k is the k smallest ids
+    dist, ids = orc.adc_scan_topk_f32(codes0, orc.CODES_U8, lut1[None], 7)
+    assert ids[0].tolist() == list(range(7))
+
+
+def test_packed_nibbles_match_unpacked_and_pair_merged_tables():
+    r = np.random.default_rng(6)
+    n, m = 4000, 16
+    packed = r.integers(0, 256, (n, m // 2), dtype=np.uint8)
+    unpacked = unpack_u4(packed)
+    assert np.array_equal(orc.pack_u4(unpacked), packed)
+    qlut = r.integers(0, 256, (m, 16), dtype=np.uint8)
+    got = orc.adc_all_u8(packed, orc.CODES_U4_PACKED, qlut)
+    ref = qlut[np.arange(m)[None, :], unpacked].astype(np.int64).sum(1)
+    assert np.array_equal(got, ref)
+    # unpacked one-index-per-byte format gives the same sums
+    assert np.array_equal(orc.adc_all_u8(unpacked, orc.CODES_U8, qlut), ref)
+    # pair-merged 256-entry tables: T[r][b] = Q[2r][b & 15] + Q[2r+1][b >> 4]
+    b = np.arange(256)
+    T = np.stack([qlut[2 * rr][b & 15].astype(np.int64) + qlut[2 * rr + 1][b >> 4] for rr in range(m // 2)])
+    assert np.array_equal(T[np.arange(m // 2)[None, :], packed].sum(1), ref)
+    # low nibble is the even component
+    one = np.array([[0x21] + [0] * 7], np.uint8)
+    lut = np.zeros((16, 16), np.float32)
+    lut[0, 1] = 3.0
+    lut[1, 2] = 5.0
+    assert orc.adc_all_f32(one, orc.CODES_U4_PACKED, lut)[0] == 8.0
+
+
+# ----------------------------------------------------------------------------- top-k (heap of Alg. 1)
+@pytest.mark.parametrize("topk", [1, 10, 100, 2000])
+def test_topk_heap_equals_full_sort(topk):
+    r = np.random.default_rng(7)
+    n = 1500
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts = r.random((3, 8, 256)).astype(np.float32)
+    luts[1] = np.round(luts[1] * 4)  # few distinct values: many exact ties
+    dist, ids = orc.adc_scan_topk_f32(codes, orc.CODES_U8, luts, topk)
+    for q in range(3):
+        alld = luts[q][np.arange(8)[None, :], codes].astype(np.float64).sum(1).astype(np.float32)
+        rd, ri = np_topk(alld, np.arange(n), topk)
+        got = min(topk, n)
+        assert np.array_equal(ids[q, :got], ri)
+        assert np.array_equal(dist[q, :got], rd)
+        assert np.all(ids[q, got:] == -1) and np.all(np.isinf(dist[q, got:]))
+
+
+def test_topk_u8_equals_full_sort_with_ties():
+    r = np.random.default_rng(8)
+    n = 3000
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = r.integers(0, 8, (2, 16, 16), dtype=np.uint8)  # small range: heavy ties
+    sums, ids = orc.adc_scan_topk_u8(packed, orc.CODES_U4_PACKED, qluts, 200)
+    un = unpack_u4(packed)
+    for q in range(2):
+        alls = qluts[q][np.arange(16)[None, :], un].astype(np.int64).sum(1)
+        rs, ri = np_topk(alls, np.arange(n), 200)
+        assert np.array_equal(ids[q], ri) and np.array_equal(sums[q], rs)
+    s2, i2 = orc.adc_scan_topk_u8(packed[:5], orc.CODES_U4_PACKED, qluts, 8)
+    assert np.all(i2[:, 5:] == -1) and np.all(s2[:, 5:] == np.iinfo(np.uint32).max)
+
+
+def test_scan_empty_database():
+    luts = np.ones((2, 8, 256), np.float32)
+    d, i = orc.adc_scan_topk_f32(np.empty((0, 8), np.uint8), orc.CODES_U8, luts, 4)
+    assert np.all(i == -1) and np.all(np.isinf(d))
+
+
+# ----------------------------------------------------------------------------- quantiser
+def test_quantizer_closed_form():
+    lut = np.zeros((1, 2, 4), np.float32)
+    lut[0, 0] = [0.0, 1.5, 254.9, 255.0]
+    lut[0, 1] = [300.0, 127.0, 2.0, 1e9]
+    q, qmin, scale = orc.quantize_luts(lut, np.array([255.0], np.float32))
+    assert qmin[0] == 0.0 and scale[0] == 1.0
+    assert q[0].tolist() == [[0, 1, 254, 255], [255, 127, 2, 255]]
+    # shifted and scaled: qmin = 10, qmax = 10 + 2*255 -> bins of width 2
+    lut2 = (lut * 2 + 10).astype(np.float32)
+    q2, qmin2, scale2 = orc.quantize_luts(lut2, np.array([520.0], np.float32))
+    assert qmin2[0] == 10.0 and scale2[0] == 0.5
+    assert q2[0].tolist() == [[0, 1, 254, 255], [255, 127, 2, 255]]
+
+
+def test_quantizer_degenerate_range():
+    lut = np.full((1, 2, 4), 3.0, np.float32)
+    for qmax in (3.0, 1.0, np.inf, np.nan):
+        q, qmin, scale = orc.quantize_luts(lut, np.array([qmax], np.float32))
+        assert scale[0] == 0.0 and np.all(q == 0) and qmin[0] == 3.0
+
+
+def test_quantizer_properties_and_lower_bound():
+    _, _, base, queries, cb = small_problem(m=4, k=16)
+    codes = orc.pq_encode(base, cb)
+    luts = orc.build_luts(queries, cb)
+    qmax = np.array([np.sort(orc.adc_all_f32(codes, orc.CODES_U8, luts[q]))[50] for q in range(len(queries))],
+                    np.float32)
+    q8, qmin, scale = orc.quantize_luts(luts, qmax)
+    m = cb.shape[0]
+    for q in range(len(queries)):
+        D = luts[q].astype(np.float64)
+        assert qmin[q] == luts[q].min()
+        assert q8[q].flat[luts[q].argmin()] == 0
+        assert np.all(q8[q][luts[q] >= qmax[q]] == 255)
+        order = np.argsort(D, axis=None)
+        assert np.all(np.diff(q8[q].flatten()[order].astype(int)) >= 0)  # monotone in D
+        t = (D - qmin[q]) * scale[q]
+        unclamped = q8[q] < 255
+        assert np.all(np.abs(np.floor(t[unclamped]) - q8[q][unclamped]) <= 1)  # float vs double floor
+        # lower bound: qmin*m + s/scale <= d (up to float rounding) for codes with no clamped entry
+        s = orc.adc_all_u8(codes, orc.CODES_U8, q8[q]).astype(np.float64)
+        d = orc.adc_all_f32(codes, orc.CODES_U8, luts[q]).astype(np.float64)
+        ok = (q8[q][np.arange(m)[None, :], codes] < 255).all(1)
+        lo = m * float(qmin[q]) + s / float(scale[q])
+        hi = m * float(qmin[q]) + (s + m) / float(scale[q])
+        assert ok.sum() > 20
+        assert np.all(lo[ok] <= d[ok] * (1 + 1e-5)) and np.all(d[ok] <= hi[ok] * (1 + 1e-5))
+
+
+def test_qmax_prescan_is_order_statistic():
+    _, _, base, queries, cb = small_problem()
+    codes = orc.pq_encode(base, cb)
+    luts = orc.build_luts(queries, cb)
+    for init, kq in ((200, 1), (200, 200), (300, 37), (5000, 100)):
+        got = orc.qmax_prescan(codes, orc.CODES_U8, luts, init, kq)
+        cnt = min(init, len(codes))
+        for q in range(len(queries)):
+            alld = np.sort(orc.adc_all_f32(codes[:cnt], orc.CODES_U8, luts[q]))
+            assert got[q] == alld[min(kq, cnt) - 1]
+
+
+# ----------------------------------------------------------------------------- rerank (two-pass)
+def test_rerank_bruteforce():
+    r = np.random.default_rng(9)
+    n = 2000
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts = r.random((3, 16, 16)).astype(np.float32)
+    cand = np.stack([r.choice(n, 300, replace=False) for _ in range(3)]).astype(np.int64)
+    cand[1, 10:20] = -1
+    dist, ids = orc.rerank_f32(packed, orc.CODES_U4_PACKED, luts, cand, 50)
+    un = unpack_u4(packed)
+    for q in range(3):
+        c = cand[q][cand[q] >= 0]
+        dd = luts[q][np.arange(16)[None, :], un[c]].astype(np.float64).sum(1).astype(np.float32)
+        rd, ri = np_topk(dd, c, 50)
+        assert np.array_equal(ids[q], ri) and np.array_equal(dist[q], rd)
+
+
+# ----------------------------------------------------------------------------- IVFADC
+def make_ivf(seed=11, n=3000, d=16, m=4, k=16, nlist=12, nq=6):
+    mix = datagen.Mixture(d, 6, (0.0, 128.0), (8.0, 32.0), (0.0, 255.0), seed=seed)
+    base = mix.sample(n, seed + 1)
+    queries = mix.sample(nq, seed + 2)
+    coarse = orc.kmeans(base, nlist, 4, np.arange(nlist, dtype=np.int64) * 7)
+    assign = ((base[:, None, :].astype(np.float64) - coarse[None].astype(np.float64)) ** 2).sum(-1).argmin(1)
+    resid = base - coarse[assign]
+    cb = orc.pq_train(resid, m, k, 4, datagen.kmeans_init_idx(n, m, k, seed + 3))
+    order = np.argsort(assign, kind="stable")
+    codes = orc.pq_encode(resid[order], cb)
+    sizes = np.bincount(assign, minlength=nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    return base, queries, coarse, cb, codes, order.astype(np.int64), offsets, assign[order]
+
+
+def test_ivf_all_lists_equals_bruteforce():
+    base, queries, coarse, cb, codes, ids, offsets, list_of = make_ivf()
+    nlist = len(coarse)
+    m = cb.shape[0]
+    dist, got_ids = orc.ivf_search(queries, coarse, offsets, codes, ids, cb, orc.CODES_U8, nlist, 20)
+    decoded = np.concatenate([cb[j][codes[:, j]] for j in range(m)], axis=1).astype(np.float64)
+    for q in range(len(queries)):
+        resid_q = (queries[q][None, :] - coarse[list_of]).astype(np.float64)  # float residual, as the oracle reads it
+        dd = ((resid_q - decoded) ** 2).sum(1)
+        rd, ri = np_topk(dd.astype(np.float32), ids, 20)
+        np.testing.assert_allclose(dist[q], rd, rtol=2e-6)
+        assert set(got_ids[q]) == set(ri)
+
+
+def test_ivf_probe_order_and_partial_probe():
+    base, queries, coarse, cb, codes, ids, offsets, list_of = make_ivf()
+    probes, pd = orc.ivf_probe(queries, coarse, 3)
+    cd = ((queries[:, None, :].astype(np.float64) - coarse[None].astype(np.float64)) ** 2).sum(-1)
+    assert np.array_equal(probes, np.argsort(cd, axis=1, kind="stable")[:, :3])
+    np.testing.assert_allclose(pd, np.sort(cd, axis=1)[:, :3], rtol=1e-6)
+    # nprobe = 3: only codes of the three probed lists may be returned, positions as ids
+    dist, got = orc.ivf_scan(queries, coarse, offsets, codes, None, cb, orc.CODES_U8, probes, 15)
+    for q in range(len(queries)):
+        assert np.all(np.isin(list_of[got[q]], probes[q]))
+
+
+def test_ivf_single_list_zero_centroid_is_flat_scan():
+    _, _, base, queries, cb = small_problem()
+    codes = orc.pq_encode(base, cb)
+    coarse = np.zeros((1, base.shape[1]), np.float32)
+    offsets = np.array([0, len(codes)], np.int64)
+    d1, i1 = orc.ivf_search(queries, coarse, offsets, codes, None, cb, orc.CODES_U8, 1, 30)
+    d2, i2 = orc.adc_scan_topk_f32(codes, orc.CODES_U8, orc.build_luts(queries, cb), 30)
+    assert np.array_equal(i1, i2) and np.array_equal(d1, d2)
+
+
+# ----------------------------------------------------------------------------- input generators
+def test_datagen_is_seeded_and_shaped():
+    mix = datagen.sift_like()
+    a, b = mix.sample(100, 1), mix.sample(100, 1)
+    assert np.array_equal(a, b) and a.dtype == np.float32 and a.shape == (100, 128)
+    assert a.min() >= 0 and a.max() <= 255
+    sizes = datagen.zipf_list_sizes(10 ** 6, 1024)
+    assert sizes.sum() == 10 ** 6 and sizes.min() > 0 and sizes.max() > 50 * sizes.min()
+    c = datagen.random_codes(1000, 8)
+    assert c.shape == (1000, 8) and c.dtype == np.uint8
+    cb = datagen.sampled_codebooks(mix, 8, 256)
+    assert cb.shape == (8, 256, 16)

@@ -1,0 +1,136 @@
+/*
+ * pq_adc.h -- C ABI of libpqadc: product-quantization ADC search on one MI355X (gfx950).
+ *
+ * The entry points follow the three-step search of the thesis (Section 2.3.3 "ANN
+ * Search", Alg. 1): Index (ivf_adc_search), Tables (pq_build_luts, optionally followed
+ * by pq_quantize_luts) and Scan (pq_adc_scan_topk), plus the second pass of the
+ * two-pass search of Section 6.3 / Alg. 5 (pq_rerank_f32).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller (for instance the
+ *     storage of torch tensors).  The library reads inputs, writes outputs and keeps
+ *     no pointer past the call.  Arrays are dense, row-major, in the shapes given.
+ *   - Work is enqueued on the HIP stream the context was created with and is
+ *     asynchronous: results are valid after that stream is synchronised.
+ *   - The context owns a device workspace that grows on demand (hipMalloc inside the
+ *     call when a larger one is needed, otherwise no allocation).  One context must
+ *     not be used from two host threads at once.
+ *   - Return value: PQ_OK (0) or a negative pq_status.  On error nothing has been
+ *     enqueued and outputs are untouched; pq_last_error() gives a message owned by
+ *     the context (valid until the next call on it).  No exception crosses the ABI.
+ *   - Codes: a code is m sub-quantizer indexes (Section 2.3.1).  PQ_CODES_U8 stores
+ *     one index per byte, component 0 first (m bytes per code).  PQ_CODES_U4_PACKED
+ *     stores two 4-bit indexes per byte, component 2r in bits 0-3 and component 2r+1
+ *     in bits 4-7 of byte r (m/2 bytes per code; Section 5.2.2, Alg. 3).
+ *   - Ids returned by the flat scan are positions in the code array (Alg. 1 keeps
+ *     (i, d) pairs with i the list position).
+ *   - Top-k order: ascending by (value, id); among equal values the smaller id wins,
+ *     which is what Alg. 1's heap with strict "<" replacement yields when the list is
+ *     scanned in order.  If fewer than topk codes exist the tail is padded with
+ *     (+inf or UINT32_MAX, -1).
+ */
+#ifndef PQ_ADC_H
+#define PQ_ADC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PQ_OK = 0,
+    PQ_EINVAL = -1,       /* null pointer, non-positive size, bad enum            */
+    PQ_ESHAPE = -2,       /* sizes inconsistent with each other (d % m, nprobe..) */
+    PQ_EUNSUPPORTED = -3, /* valid request outside what the kernels cover         */
+    PQ_EHIP = -4,         /* a HIP runtime call failed                            */
+    PQ_ENOMEM = -5        /* workspace allocation failed                          */
+} pq_status;
+
+typedef enum { PQ_CODES_U8 = 0, PQ_CODES_U4_PACKED = 1 } pq_code_fmt;
+typedef enum { PQ_LUT_F32 = 0, PQ_LUT_U8 = 1 } pq_lut_fmt;
+
+typedef struct pq_ctx pq_ctx;
+
+/* Create a context on `device` using `hip_stream` (a hipStream_t, borrowed; NULL = the
+ * default stream).  *out is set on success. */
+int pq_create(pq_ctx **out, int device, void *hip_stream);
+/* Free the context and its workspace (synchronises the stream first). */
+int pq_destroy(pq_ctx *ctx);
+const char *pq_last_error(const pq_ctx *ctx);
+/* Library version string, static storage. */
+const char *pq_version(void);
+
+/* Tables step, Eq. (tables) of Section 2.3.3:  luts[q][j][i] = || y_q^j - C^j[i] ||^2,
+ * sub-space j = dimensions j*d/m .. (j+1)*d/m-1.
+ *   queries   [nq][d] f32, codebooks [m][k][d/m] f32  ->  luts [nq][m][k] f32.
+ * Requires d % m == 0, 1 <= k <= 65536. */
+int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
+                  float *luts);
+
+/* 8-bit quantisation of each query's tables (Sections 4.2.4, 5.2.1; Section 6.3 Step 1.2
+ * for the unsigned 0..254 + 255 range).  Per query q:
+ *   qmin  = min over all m*k entries;  range = qmax[q] - qmin;
+ *   scale = (range > 0 and finite) ? 255 / range : 0;
+ *   qluts = t >= 255 ? 255 : floor(t),  t = (luts - qmin) * scale      (all in f32)
+ *   luts [nq][m][k] f32, qmax [nq] f32 -> qluts [nq][m][k] u8, qmin_out [nq], scale_out [nq]
+ * (the last two may be NULL). */
+int pq_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, const float *qmax, uint8_t *qluts,
+                     float *qmin_out, float *scale_out);
+
+/* Upper quantisation bound (Sections 4.2.4 / 5.2.1: distance to a temporary neighbour
+ * found by a float ADC scan of the first `init` codes; Section 6.3 Step 1.2: greatest
+ * distance among the first r2 codes).  qmax_out[q] = kq-th smallest float ADC distance
+ * among the first min(init, n) codes (kq clipped to that count).  Requires init <= 4096. */
+int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq,
+                    int m, int k, int init, int kq, float *qmax_out);
+
+/* Scan step (Alg. 1 `scan` + `adc`, Eq. (adc1); Alg. 3 `quick_adc_scan` for packed
+ * 4-bit codes with quantised tables):  value[q][i] = sum_j luts[q][j][code_i[j]], and the
+ * topk smallest (value, i) per query.
+ *   codes [n][code_bytes] u8; luts [nq][m][k] f32 (PQ_LUT_F32) or u8 (PQ_LUT_U8);
+ *   out_val [nq][topk] f32 (float tables) or u32 (u8 tables, plain integer sums, no
+ *   saturation); out_ids [nq][topk] i64.
+ * Covered: (U8 codes, F32 tables, k = 256, m = 8 or 16), (U4 codes, U8 tables, k = 16,
+ * m = 16), and any (U8 | U4 codes, F32 | U8 tables) with m*k <= 8192 through a slower
+ * general kernel.  1 <= topk <= 1024, 0 <= n < 2^32. */
+int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
+                     pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);
+
+/* Second pass of the two-pass search (Alg. 5 `rerank`): float ADC of the given
+ * candidates and the topk smallest (distance, id).
+ *   cand_ids [nq][ncand] i64, positions into codes; negative entries are skipped.
+ *   out_dist [nq][topk] f32, out_ids [nq][topk] i64.  1 <= topk <= ncand <= 4096. */
+int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq,
+                  int m, int k, const int64_t *cand_ids, int ncand, int topk, float *out_dist,
+                  int64_t *out_ids);
+
+/* Inverted lists of an IVFADC index (Section 2.3.2): nlist coarse centroids; the codes
+ * of list l are rows list_offsets[l] .. list_offsets[l+1]-1 of `codes`, which encode the
+ * residuals x - centroid_l.  ids may be NULL (id = row number). */
+typedef struct {
+    const float *coarse_centroids; /* [nlist][d] f32, device */
+    const int64_t *list_offsets;   /* [nlist+1] i64, device, non-decreasing, [0] = 0 */
+    const uint8_t *codes;          /* [ntotal][code_bytes], device, grouped by list */
+    const int64_t *ids;            /* [ntotal] i64, device, or NULL */
+    int nlist;
+    int d;
+    int64_t ntotal;
+} ivf_lists;
+
+/* Index + Tables + Scan of Section 2.3.3 with an inverted index: for each query the
+ * nprobe lists with the closest centroids (ties: smaller list id), tables of the query
+ * residual y - centroid_l per probed list, ADC over the codes of those lists, topk
+ * smallest (distance, id) overall.  probe_out [nq][nprobe] i32 may be NULL; when given
+ * it receives the probed lists in ascending (distance, list id) order.
+ * Covered: U8 codes, k = 256, m = 8 or 16; 1 <= nprobe <= min(nlist, 1024);
+ * 1 <= topk <= 128; ntotal < 2^32. */
+int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
+                   const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
+                   int32_t *probe_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQ_ADC_H */

@@ -1,0 +1,197 @@
+// Tables step (Eq. (tables) of Section 2.3.3), 8-bit table quantisation (Sections 4.2.4,
+// 5.2.1, 6.3 Step 1.2), the qmax pre-scan and the rerank pass of the two-pass search
+// (Section 6.3, Alg. 5).
+#include "pq_internal.h"
+#include "topk_device.h"
+
+namespace pq {
+
+// ------------------------------------------------------------------------------------------
+// Direct form  D[q][j][i] = sum_t (y[q][j*dsub+t] - C[j][i][t])^2  in f32.  All terms are
+// non-negative, so the relative error is bounded by about (dsub+1) * 2^-24.
+// Block = (tile of 16 queries) x (one sub-space j) x (tile of 64 centroids): the centroid
+// tile and the query sub-vectors are staged in LDS in slabs of 32 dimensions.
+constexpr int LUT_TQ = 16, LUT_TC = 64, LUT_TD = 32;
+
+__global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict__ queries,
+                                                         const float *__restrict__ codebooks, int nq, int d, int m,
+                                                         int k, float *__restrict__ luts) {
+    __shared__ float sc[LUT_TC][LUT_TD + 1];
+    __shared__ float sy[LUT_TQ][LUT_TD + 1];
+    const int dsub = d / m;
+    const int j = blockIdx.y;
+    const int c0 = blockIdx.x * LUT_TC;
+    const int q0 = blockIdx.z * LUT_TQ;
+    const int ci = threadIdx.x & 63;        // centroid within tile
+    const int qi = threadIdx.x >> 6;        // 0..3: this thread handles queries qi, qi+4, qi+8, qi+12
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t0 = 0; t0 < dsub; t0 += LUT_TD) {
+        const int td = dsub - t0 < LUT_TD ? dsub - t0 : LUT_TD;
+        for (int e = threadIdx.x; e < LUT_TC * LUT_TD; e += 256) {
+            const int c = e / LUT_TD, t = e % LUT_TD;
+            sc[c][t] = (c0 + c < k && t < td) ? codebooks[((size_t)j * k + c0 + c) * dsub + t0 + t] : 0.f;
+        }
+        for (int e = threadIdx.x; e < LUT_TQ * LUT_TD; e += 256) {
+            const int q = e / LUT_TD, t = e % LUT_TD;
+            sy[q][t] = (q0 + q < nq && t < td) ? queries[(size_t)(q0 + q) * d + j * dsub + t0 + t] : 0.f;
+        }
+        __syncthreads();
+        for (int t = 0; t < td; ++t) {
+            const float c = sc[ci][t];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float diff = sy[qi + 4 * r][t] - c;
+                acc[r] = fmaf(diff, diff, acc[r]);
+            }
+        }
+        __syncthreads();
+    }
+    if (c0 + ci < k) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int q = q0 + qi + 4 * r;
+            if (q < nq) luts[((size_t)q * m + j) * k + c0 + ci] = acc[r];
+        }
+    }
+}
+
+int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
+                      float *luts) {
+    dim3 grid((k + LUT_TC - 1) / LUT_TC, m, (nq + LUT_TQ - 1) / LUT_TQ);
+    if (grid.y > 65535 || grid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/16 above 65535");
+    build_luts_kernel<<<grid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// One block per query.  The float operation sequence (subtract, divide, subtract, multiply,
+// floor, clamp) is fixed by the definition so that the bytes are reproducible.
+__global__ __launch_bounds__(256) void quantize_luts_kernel(const float *__restrict__ luts, int per,
+                                                            const float *__restrict__ qmax,
+                                                            uint8_t *__restrict__ qluts, float *qmin_out,
+                                                            float *scale_out) {
+    __shared__ float red[4];
+    const int q = blockIdx.x;
+    const float *D = luts + (size_t)q * per;
+    float mn = __builtin_inff();
+    bool has_nan = false;
+    for (int e = threadIdx.x; e < per; e += 256) {
+        const float v = D[e];
+        mn = v < mn ? v : mn;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const float other = __shfl_xor(mn, o);
+        mn = other < mn ? other : mn;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mn;
+    __syncthreads();
+    float qmin = red[0];
+    for (int w = 1; w < 4; ++w) qmin = red[w] < qmin ? red[w] : qmin;
+    (void)has_nan;
+    const float range = __fsub_rn(qmax[q], qmin);
+    float scale = 0.f;
+    if (range > 0.f && range < __builtin_inff()) scale = __fdiv_rn(255.0f, range);
+    for (int e = threadIdx.x; e < per; e += 256) {
+        const float t = __fmul_rn(__fsub_rn(D[e], qmin), scale);
+        qluts[(size_t)q * per + e] = t >= 255.0f ? (uint8_t)255 : (uint8_t)floorf(t);
+    }
+    if (threadIdx.x == 0) {
+        if (qmin_out) qmin_out[q] = qmin;
+        if (scale_out) scale_out[q] = scale;
+    }
+}
+
+int launch_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, const float *qmax, uint8_t *qluts,
+                         float *qmin_out, float *scale_out) {
+    if (nq == 0) return PQ_OK;
+    quantize_luts_kernel<<<nq, 256, 0, ctx->stream>>>(luts, m * k, qmax, qluts, qmin_out, scale_out);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Float ADC of one stored code with one query's tables (global memory), Eq. (adc1).
+__device__ __forceinline__ float adc_one(const uint8_t *code, int cf, const float *lut, int m, int k) {
+    float dist = 0.f;
+    for (int j = 0; j < m; ++j) {
+        int idx;
+        if (cf == PQ_CODES_U4_PACKED) {
+            const uint32_t byte = code[j >> 1];
+            idx = (j & 1) ? (byte >> 4) : (byte & 15u);
+        } else {
+            idx = code[j];
+        }
+        if (idx < k) dist += lut[(size_t)j * k + idx];
+    }
+    return dist;
+}
+
+// One block per query: distances of the first `cnt` codes (cnt <= 4096) into LDS keys,
+// bitonic sort, take the kq-th.
+__global__ __launch_bounds__(256) void qmax_prescan_kernel(const uint8_t *__restrict__ codes, int cnt, int cb,
+                                                           int cf, const float *__restrict__ luts, int m, int k,
+                                                           int kq, int n2, float *qmax_out) {
+    extern __shared__ uint64_t skeys[];
+    const int q = blockIdx.x;
+    const float *lut = luts + (size_t)q * m * k;
+    for (int i = threadIdx.x; i < n2; i += 256) {
+        uint64_t key = KEY_EMPTY;
+        if (i < cnt) key = ((uint64_t)f32_to_ord(adc_one(codes + (size_t)i * cb, cf, lut, m, k)) << 32) | (uint32_t)i;
+        skeys[i] = key;
+    }
+    block_bitonic_sort(skeys, n2);
+    if (threadIdx.x == 0) qmax_out[q] = ord_to_f32((uint32_t)(skeys[kq - 1] >> 32));
+}
+
+int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m,
+                        int k, int init, int kq, float *qmax_out) {
+    const int cnt = (int)(init < n ? init : n);
+    if (kq > cnt) kq = cnt;
+    int n2 = 64;
+    while (n2 < cnt) n2 <<= 1;
+    const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
+    qmax_prescan_kernel<<<nq, 256, (size_t)n2 * 8, ctx->stream>>>(codes, cnt, cb, cf, luts, m, k, kq, n2, qmax_out);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// One block per query: float ADC of the candidates, sort by (distance, id), write topk.
+__global__ __launch_bounds__(256) void rerank_kernel(const uint8_t *__restrict__ codes, int64_t n, int cb, int cf,
+                                                     const float *__restrict__ luts, int m, int k,
+                                                     const int64_t *__restrict__ cand, int ncand, int n2, int topk,
+                                                     float *out_dist, int64_t *out_ids) {
+    extern __shared__ uint64_t skeys[];
+    const int q = blockIdx.x;
+    const float *lut = luts + (size_t)q * m * k;
+    for (int i = threadIdx.x; i < n2; i += 256) {
+        uint64_t key = KEY_EMPTY;
+        if (i < ncand) {
+            const int64_t id = cand[(size_t)q * ncand + i];
+            if (id >= 0 && id < n)
+                key = ((uint64_t)f32_to_ord(adc_one(codes + (size_t)id * cb, cf, lut, m, k)) << 32) | (uint32_t)id;
+        }
+        skeys[i] = key;
+    }
+    block_bitonic_sort(skeys, n2);
+    for (int i = threadIdx.x; i < topk; i += 256) {
+        const uint64_t key = skeys[i];
+        const bool empty = key == KEY_EMPTY;
+        out_dist[(size_t)q * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
+        out_ids[(size_t)q * topk + i] = empty ? -1 : (int64_t)(uint32_t)key;
+    }
+}
+
+int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m, int k,
+                  const int64_t *cand, int ncand, int topk, float *out_dist, int64_t *out_ids) {
+    int n2 = 64;
+    while (n2 < ncand) n2 <<= 1;
+    const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
+    if (nq == 0) return PQ_OK;
+    rerank_kernel<<<nq, 256, (size_t)n2 * 8, ctx->stream>>>(codes, n, cb, cf, luts, m, k, cand, ncand, n2, topk,
+                                                             out_dist, out_ids);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+}  // namespace pq

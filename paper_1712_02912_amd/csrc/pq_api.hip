@@ -1,0 +1,180 @@
+// C-ABI entry points of libpqadc: argument validation, context and workspace handling.
+// The kernels and their launchers live in the other translation units.
+#include <stdarg.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "pq_internal.h"
+
+namespace pq {
+
+int fail(pq_ctx *ctx, int code, const char *fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+int hip_fail(pq_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, PQ_EHIP, "HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+}
+
+int ws_reserve(pq_ctx *ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return PQ_OK;
+    // kernels already enqueued may still use the old workspace
+    PQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) {
+        PQ_HIP(ctx, hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    const size_t want = align_up(bytes + bytes / 4, (size_t)1 << 20);
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, PQ_ENOMEM, "workspace allocation of %zu bytes failed: %s", want, hipGetErrorString(e));
+    }
+    ctx->ws = p;
+    ctx->ws_bytes = want;
+    return PQ_OK;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace pq
+
+using namespace pq;
+
+extern "C" {
+
+const char *pq_version(void) { return "pqadc-gfx950 0.1"; }
+
+int pq_create(pq_ctx **out, int device, void *hip_stream) {
+    if (!out) return PQ_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return PQ_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return PQ_EHIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return PQ_EHIP;
+    pq_ctx *ctx = (pq_ctx *)calloc(1, sizeof(pq_ctx));
+    if (!ctx) return PQ_ENOMEM;
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    strcpy(ctx->err, "no error");
+    *out = ctx;
+    return PQ_OK;
+}
+
+int pq_destroy(pq_ctx *ctx) {
+    if (!ctx) return PQ_EINVAL;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    free(ctx);
+    return PQ_OK;
+}
+
+const char *pq_last_error(const pq_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
+                  float *luts) {
+    if (!ctx) return PQ_EINVAL;
+    if (nq < 0 || d <= 0 || m <= 0 || k <= 0) return fail(ctx, PQ_EINVAL, "build_luts: sizes must be positive");
+    if (d % m != 0) return fail(ctx, PQ_ESHAPE, "build_luts: d=%d is not a multiple of m=%d", d, m);
+    if (k > 65536) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: k=%d above 65536", k);
+    if (nq == 0) return PQ_OK;
+    if (!queries || !codebooks || !luts) return fail(ctx, PQ_EINVAL, "build_luts: null pointer");
+    return launch_build_luts(ctx, queries, codebooks, nq, d, m, k, luts);
+}
+
+int pq_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, const float *qmax, uint8_t *qluts,
+                     float *qmin_out, float *scale_out) {
+    if (!ctx) return PQ_EINVAL;
+    if (nq < 0 || m <= 0 || k <= 0) return fail(ctx, PQ_EINVAL, "quantize_luts: sizes must be positive");
+    if ((int64_t)m * k > (1 << 24)) return fail(ctx, PQ_EUNSUPPORTED, "quantize_luts: m*k too large");
+    if (nq == 0) return PQ_OK;
+    if (!luts || !qmax || !qluts) return fail(ctx, PQ_EINVAL, "quantize_luts: null pointer");
+    return launch_quantize_luts(ctx, luts, nq, m, k, qmax, qluts, qmin_out, scale_out);
+}
+
+static int check_codes(pq_ctx *ctx, const char *who, int cf, int m, int k) {
+    if (cf != PQ_CODES_U8 && cf != PQ_CODES_U4_PACKED) return fail(ctx, PQ_EINVAL, "%s: bad code format %d", who, cf);
+    if (m <= 0 || k <= 0) return fail(ctx, PQ_EINVAL, "%s: m and k must be positive", who);
+    if (cf == PQ_CODES_U4_PACKED && (m % 2 != 0 || k > 16))
+        return fail(ctx, PQ_ESHAPE, "%s: packed 4-bit codes need even m and k <= 16 (m=%d k=%d)", who, m, k);
+    if (cf == PQ_CODES_U8 && k > 256) return fail(ctx, PQ_ESHAPE, "%s: one-byte indexes need k <= 256 (k=%d)", who, k);
+    return PQ_OK;
+}
+
+int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq, int m,
+                    int k, int init, int kq, float *qmax_out) {
+    if (!ctx) return PQ_EINVAL;
+    int rc = check_codes(ctx, "qmax_prescan", cf, m, k);
+    if (rc) return rc;
+    if (nq < 0 || n <= 0 || init <= 0 || kq <= 0) return fail(ctx, PQ_EINVAL, "qmax_prescan: n, init, kq must be positive");
+    if (init > 4096) return fail(ctx, PQ_EUNSUPPORTED, "qmax_prescan: init=%d above 4096", init);
+    if (nq == 0) return PQ_OK;
+    if (!codes || !luts || !qmax_out) return fail(ctx, PQ_EINVAL, "qmax_prescan: null pointer");
+    return launch_qmax_prescan(ctx, codes, n, cf, luts, nq, m, k, init, kq, qmax_out);
+}
+
+int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts, pq_lut_fmt lf,
+                     int nq, int m, int k, int topk, void *out_val, int64_t *out_ids) {
+    if (!ctx) return PQ_EINVAL;
+    int rc = check_codes(ctx, "adc_scan_topk", cf, m, k);
+    if (rc) return rc;
+    if (lf != PQ_LUT_F32 && lf != PQ_LUT_U8) return fail(ctx, PQ_EINVAL, "adc_scan_topk: bad table format %d", lf);
+    if (nq < 0 || n < 0) return fail(ctx, PQ_EINVAL, "adc_scan_topk: negative size");
+    if (topk < 1) return fail(ctx, PQ_EINVAL, "adc_scan_topk: topk must be at least 1");
+    if (topk > 1024) return fail(ctx, PQ_EUNSUPPORTED, "adc_scan_topk: topk=%d above 1024", topk);
+    if (n >= ((int64_t)1 << 32)) return fail(ctx, PQ_EUNSUPPORTED, "adc_scan_topk: n must be below 2^32");
+    if (nq == 0) return PQ_OK;
+    if (!luts || !out_val || !out_ids || (n > 0 && !codes)) return fail(ctx, PQ_EINVAL, "adc_scan_topk: null pointer");
+    if (!aligned16(codes)) return fail(ctx, PQ_EINVAL, "adc_scan_topk: codes must be 16-byte aligned");
+    return launch_scan(ctx, codes, n, cf, luts, lf, nq, m, k, topk, out_val, out_ids);
+}
+
+int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq, int m,
+                  int k, const int64_t *cand_ids, int ncand, int topk, float *out_dist, int64_t *out_ids) {
+    if (!ctx) return PQ_EINVAL;
+    int rc = check_codes(ctx, "rerank_f32", cf, m, k);
+    if (rc) return rc;
+    if (nq < 0 || n < 0 || ncand < 1 || topk < 1) return fail(ctx, PQ_EINVAL, "rerank_f32: bad size");
+    if (topk > ncand) return fail(ctx, PQ_ESHAPE, "rerank_f32: topk=%d above ncand=%d", topk, ncand);
+    if (ncand > 4096) return fail(ctx, PQ_EUNSUPPORTED, "rerank_f32: ncand=%d above 4096", ncand);
+    if (n >= ((int64_t)1 << 32)) return fail(ctx, PQ_EUNSUPPORTED, "rerank_f32: n must be below 2^32");
+    if (nq == 0) return PQ_OK;
+    if (!luts || !cand_ids || !out_dist || !out_ids || (n > 0 && !codes)) return fail(ctx, PQ_EINVAL, "rerank_f32: null pointer");
+    return launch_rerank(ctx, codes, n, cf, luts, nq, m, k, cand_ids, ncand, topk, out_dist, out_ids);
+}
+
+int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
+                   const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
+                   int32_t *probe_out) {
+    if (!ctx) return PQ_EINVAL;
+    if (!lists) return fail(ctx, PQ_EINVAL, "ivf_adc_search: null lists");
+    int rc = check_codes(ctx, "ivf_adc_search", cf, m, k);
+    if (rc) return rc;
+    if (lists->nlist <= 0 || lists->d <= 0 || lists->ntotal < 0 || nq < 0)
+        return fail(ctx, PQ_EINVAL, "ivf_adc_search: bad size");
+    if (lists->d % m != 0) return fail(ctx, PQ_ESHAPE, "ivf_adc_search: d=%d is not a multiple of m=%d", lists->d, m);
+    if (nprobe < 1 || nprobe > lists->nlist)
+        return fail(ctx, PQ_ESHAPE, "ivf_adc_search: nprobe=%d outside 1..nlist=%d", nprobe, lists->nlist);
+    if (topk < 1) return fail(ctx, PQ_EINVAL, "ivf_adc_search: topk must be at least 1");
+    if (nprobe > 1024 || topk > 128 || cf != PQ_CODES_U8 || k != 256 || (m != 8 && m != 16))
+        return fail(ctx, PQ_EUNSUPPORTED, "ivf_adc_search: covered are U8 codes, k=256, m in {8,16}, nprobe<=1024, topk<=128");
+    if (lists->ntotal >= ((int64_t)1 << 32)) return fail(ctx, PQ_EUNSUPPORTED, "ivf_adc_search: ntotal must be below 2^32");
+    if (nq == 0) return PQ_OK;
+    if (!lists->coarse_centroids || !lists->list_offsets || !codebooks || !queries || !out_dist || !out_ids ||
+        (lists->ntotal > 0 && !lists->codes))
+        return fail(ctx, PQ_EINVAL, "ivf_adc_search: null pointer");
+    if (!aligned16(lists->codes)) return fail(ctx, PQ_EINVAL, "ivf_adc_search: codes must be 16-byte aligned");
+    return launch_ivf(ctx, lists, codebooks, m, k, cf, queries, nq, nprobe, topk, out_dist, out_ids, probe_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Internal declarations shared by the translation units of libpqadc (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "pq_adc.h"
+
+struct pq_ctx {
+    int device;
+    hipStream_t stream;
+    void *ws;          // device workspace, grown on demand
+    size_t ws_bytes;
+    int num_cu;
+    char err[512];
+};
+
+namespace pq {
+
+// ---- host helpers -----------------------------------------------------------------
+int fail(pq_ctx *ctx, int code, const char *fmt, ...);
+int hip_fail(pq_ctx *ctx, hipError_t e, const char *what);
+// Make the workspace at least `bytes` large; returns PQ_OK or an error already recorded.
+int ws_reserve(pq_ctx *ctx, size_t bytes);
+
+#define PQ_HIP(ctx, call)                                                \
+    do {                                                                 \
+        hipError_t e__ = (call);                                         \
+        if (e__ != hipSuccess) return pq::hip_fail((ctx), e__, #call);   \
+    } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers implemented in the kernel files -------------------------------------
+int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
+                      float *luts);
+int launch_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, const float *qmax,
+                         uint8_t *qluts, float *qmin_out, float *scale_out);
+int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m,
+                        int k, int init, int kq, float *qmax_out);
+int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m, int k,
+                  const int64_t *cand, int ncand, int topk, float *out_dist, int64_t *out_ids);
+int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, int lf, int nq, int m,
+                int k, int topk, void *out_val, int64_t *out_ids);
+int launch_ivf(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, int cf,
+               const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
+               int32_t *probe_out);
+
+}  // namespace pq

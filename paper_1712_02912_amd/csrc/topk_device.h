@@ -1,0 +1,105 @@
+// Device-side building blocks of the top-k selection used by the scan kernels.
+//
+// A candidate is one 64-bit key: (ordered value << 32) | id.  Unsigned comparison of keys
+// is the total order (value, id) of Alg. 1's heap, so "the k smallest keys" is exactly the
+// content of that heap after the scan.  For float values the upper word is the usual
+// order-preserving map of IEEE-754 bits to unsigned integers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pq {
+
+constexpr uint64_t KEY_EMPTY = ~0ull;
+
+__device__ __forceinline__ uint32_t f32_to_ord(float f) {
+    uint32_t b = __float_as_uint(f);
+    return b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
+}
+__device__ __forceinline__ float ord_to_f32(uint32_t o) {
+    uint32_t b = o ^ ((o >> 31) ? 0x80000000u : 0xffffffffu);
+    return __uint_as_float(b);
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int mask_prefix(uint64_t mask) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Scratch buffers are written and read back by different lanes (and, at the end of a block,
+// different waves): go through the device-coherent level for both directions.
+__device__ __forceinline__ void key_store(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t key_load(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// k-th smallest (1-based) of the wave's 64*E keys, by bitwise bisection on the key value:
+// the smallest v with count(key <= v) >= k.  Every lane must call it; the result is uniform.
+// If fewer than k non-empty keys exist the result is KEY_EMPTY.
+template <int E>
+__device__ __forceinline__ uint64_t wave_select_kth(const uint64_t (&key)[E], int k) {
+    uint64_t v = 0;
+    for (int bit = 63; bit >= 0; --bit) {
+        const uint64_t trial = v | ((1ull << bit) - 1ull);
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) c += __popcll(__ballot(key[e] <= trial));
+        if (c < k) v |= (1ull << bit);
+    }
+    return v;
+}
+
+// Keep the k smallest of buf[0..cnt) (cnt <= 64*E) in buf[0..min(cnt,k)), in no particular
+// order.  Returns the k-th smallest key (KEY_EMPTY if cnt < k) and updates cnt.
+template <int E>
+__device__ __forceinline__ uint64_t wave_compact(uint64_t *buf, int &cnt, int k) {
+    const int lane = lane_id();
+    __threadfence();  // the appends of every lane have reached the coherent level
+    uint64_t key[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const int idx = e * 64 + lane;
+        key[e] = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
+    }
+    const uint64_t kth = wave_select_kth<E>(key, k);
+    int base = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const bool keep = key[e] <= kth && key[e] != KEY_EMPTY;
+        const uint64_t mask = __ballot(keep);
+        if (keep) key_store(buf + base + mask_prefix(mask), key[e]);
+        base += __popcll(mask);
+    }
+    cnt = base;
+    return kth;
+}
+
+// Append the lanes with `pass` set to buf at position cnt (uniform).  Returns the new count.
+__device__ __forceinline__ int wave_append(uint64_t *buf, int cnt, bool pass, uint64_t key) {
+    const uint64_t mask = __ballot(pass);
+    if (pass) key_store(buf + cnt + mask_prefix(mask), key);
+    return cnt + __popcll(mask);
+}
+
+// In-LDS bitonic sort (ascending) of n2 keys, n2 a power of two, by the whole block.
+__device__ inline void block_bitonic_sort(uint64_t *s, int n2) {
+    for (int size = 2; size <= n2; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < (n2 >> 1); i += blockDim.x) {
+                const int lo = 2 * i - (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool asc = (lo & size) == 0;
+                const uint64_t a = s[lo], b = s[hi];
+                if ((a > b) == asc) { s[lo] = b; s[hi] = a; }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace pq

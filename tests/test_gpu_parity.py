@@ -1,0 +1,285 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Float distances: 1e-5 relative, top-k sets identical up to ties inside that band.
+Integer sums, quantised tables and ids: bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pq_oracle as orc
+from paper_1712_02912_amd import binding, datagen
+from util import RTOL, check_exact_topk, check_float_topk, sift_pq
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = binding.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+# ----------------------------------------------------------------------------- Tables step
+@pytest.mark.parametrize("m,k,d,nq", [(8, 256, 128, 16), (16, 16, 128, 37), (16, 256, 960, 21), (4, 7, 20, 3),
+                                       (1, 256, 16, 1), (8, 1, 64, 5)])
+def test_build_luts(ctx, m, k, d, nq):
+    r = np.random.default_rng(m * 1000 + k)
+    mix = datagen.sift_like() if d == 128 else None
+    queries = mix.sample(nq, 5) if mix else (r.random((nq, d)).astype(np.float32))
+    cb = datagen.sampled_codebooks(mix, m, k) if mix else r.random((m, k, d // m)).astype(np.float32)
+    ref = orc.build_luts(queries, cb)
+    got = host(ctx.pq_build_luts(dev(queries), dev(cb)))
+    assert got.shape == ref.shape
+    np.testing.assert_allclose(got, ref, rtol=4e-6, atol=1e-30)  # (dsub+1)*2^-24 at dsub=60 is 3.6e-6
+
+
+def test_build_luts_exact_zero_distance(ctx):
+    cb = np.arange(2 * 4 * 3, dtype=np.float32).reshape(2, 4, 3)
+    queries = np.concatenate([cb[0, 2], cb[1, 1]])[None, :]
+    got = host(ctx.pq_build_luts(dev(queries), dev(cb)))
+    assert got[0, 0, 2] == 0.0 and got[0, 1, 1] == 0.0
+    assert np.array_equal(got, orc.build_luts(queries, cb))  # small integers: exact in float
+
+
+# ----------------------------------------------------------------------------- quantiser
+@pytest.mark.parametrize("m,k", [(16, 16), (8, 256), (3, 5)])
+def test_quantize_luts_bit_exact(ctx, m, k):
+    r = np.random.default_rng(11)
+    nq = 33
+    luts = (r.random((nq, m, k)) * 1000 + 3).astype(np.float32)
+    qmax = (luts.min(axis=(1, 2)) + r.random(nq) * 2000).astype(np.float32)
+    qmax[0] = luts[0].min()          # empty range
+    qmax[1] = np.inf
+    qmax[2] = luts[2].min() - 1.0    # negative range
+    ref_q, ref_min, ref_scale = orc.quantize_luts(luts, qmax)
+    q, qmin, scale = ctx.pq_quantize_luts(dev(luts), dev(qmax))
+    assert np.array_equal(host(q), ref_q)
+    assert np.array_equal(host(qmin), ref_min)
+    assert np.array_equal(host(scale), ref_scale)
+
+
+def test_qmax_prescan(ctx):
+    _, queries, cb, codes16 = sift_pq(16, 16, 100000, 16)
+    packed = orc.pack_u4(codes16)
+    luts = ctx.pq_build_luts(dev(queries), dev(cb))
+    luts_h = host(luts)
+    for init, kq in ((200, 1), (1000, 1000), (4096, 1000), (3000, 77)):
+        got = host(ctx.pq_qmax_prescan(dev(packed), binding.CODES_U4_PACKED, luts, init, kq))
+        ref = orc.qmax_prescan(packed, orc.CODES_U4_PACKED, luts_h, init, kq)
+        np.testing.assert_allclose(got, ref, rtol=2e-6)
+
+
+# ----------------------------------------------------------------------------- float scan
+def run_float_scan(ctx, codes, fmt, luts_h, topk):
+    d, i = ctx.pq_adc_scan_topk(dev(codes) if len(codes) else torch.empty((0, codes.shape[1]), dtype=torch.uint8, device="cuda"),
+                                fmt, dev(luts_h), topk)
+    gd, gi = host(d), host(i)
+    od, oi = orc.adc_scan_topk_f32(codes, fmt, luts_h, topk)
+    for q in range(luts_h.shape[0]):
+        check_float_topk(gd[q], gi[q], od[q], oi[q], codes, fmt, luts_h[q], len(codes))
+    return gd, gi, od, oi
+
+
+def test_scan_config0_pq8x8(ctx):
+    """Config 0: d=128 mixture, 8x8 trained codebooks, N=100k encoded codes, 16 queries, top-100."""
+    _, queries, cb, codes = sift_pq(8, 256, 100000, 16)
+    luts_h = host(ctx.pq_build_luts(dev(queries), dev(cb)))
+    gd, gi, od, oi = run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # with GPU-built tables fed to both sides the id lists agree except inside rounding ties
+    assert (gi == oi).mean() > 0.98
+
+
+@pytest.mark.parametrize("n", [0, 1, 63, 127, 128, 129, 1023, 1025, 8191, 8193, 50001])
+@pytest.mark.parametrize("nq,topk", [(1, 1), (3, 10), (5, 100), (8, 128)])
+def test_scan_f32_ragged(ctx, n, nq, topk):
+    r = np.random.default_rng(n * 7 + nq)
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = (r.random((nq, 8, 256)) * 100).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, topk)
+
+
+@pytest.mark.parametrize("topk", [129, 500, 1024])
+def test_scan_f32_large_topk(ctx, topk):
+    r = np.random.default_rng(topk)
+    n = 30011
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = (r.random((6, 8, 256)) * 100).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, topk)
+
+
+def test_scan_f32_pq16x8(ctx):
+    r = np.random.default_rng(3)
+    n = 70007
+    codes = r.integers(0, 256, (n, 16), dtype=np.uint8)
+    luts_h = r.random((7, 16, 256)).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+
+
+def test_scan_f32_many_chunks_and_groups(ctx):
+    """Several chunks per query and several query groups: exercises the shared bounds and the merge."""
+    r = np.random.default_rng(4)
+    n = 1_000_003
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = (r.random((13, 8, 256)) * 10).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+
+
+def test_scan_f32_all_equal_and_ties(ctx):
+    n = 20000
+    codes = np.zeros((n, 8), np.uint8)
+    luts_h = np.ones((2, 8, 256), np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), 50)
+    assert np.array_equal(host(i), np.tile(np.arange(50), (2, 1)))  # equal values: smallest ids
+    assert np.all(host(d) == 8.0)
+    # few distinct values (exact in float, so ties are exact and the (value, id) order is unique)
+    r = np.random.default_rng(5)
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = r.integers(0, 3, (3, 8, 256)).astype(np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), 100)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, luts_h, 100)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+
+
+def test_scan_f32_descending_order_worst_case(ctx):
+    """Distances strictly decreasing with position: every code beats the current bound."""
+    n = 40000
+    codes = np.zeros((n, 8), np.uint8)
+    idx = np.arange(n)
+    codes[:, 0] = idx % 256
+    codes[:, 1] = idx // 256
+    lut = np.zeros((1, 8, 256), np.float32)
+    lut[0, 0] = 255 - np.arange(256)
+    lut[0, 1] = (255 - np.arange(256)) * 256.0
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(lut), 100)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, lut, 100)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+
+
+@pytest.mark.parametrize("m,k,fmt", [(4, 16, orc.CODES_U8), (32, 16, orc.CODES_U4_PACKED), (2, 256, orc.CODES_U8),
+                                     (16, 16, orc.CODES_U4_PACKED)])
+def test_scan_f32_general_shapes(ctx, m, k, fmt):
+    r = np.random.default_rng(m + k)
+    n = 9001
+    cb = m // 2 if fmt == orc.CODES_U4_PACKED else m
+    hi = 256 if fmt == orc.CODES_U4_PACKED else k
+    codes = r.integers(0, hi, (n, cb), dtype=np.uint8)
+    luts_h = r.random((3, m, k)).astype(np.float32)
+    run_float_scan(ctx, codes, fmt, luts_h, 20)
+
+
+# ----------------------------------------------------------------------------- integer scan
+def run_int_scan(ctx, codes, fmt, qluts_h, topk):
+    s, i = ctx.pq_adc_scan_topk(dev(codes), fmt, dev(qluts_h), topk)
+    os_, oi = orc.adc_scan_topk_u8(codes, fmt, qluts_h, topk)
+    gs, gi = host(s), host(i)
+    check_exact_topk(gs, gi, os_, oi)
+
+
+@pytest.mark.parametrize("n", [1, 127, 129, 4097, 60001])
+@pytest.mark.parametrize("nq,topk", [(1, 1), (7, 100), (9, 128), (3, 1000)])
+def test_scan_u4_bit_exact(ctx, n, nq, topk):
+    r = np.random.default_rng(n + nq)
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = r.integers(0, 256, (nq, 16, 16), dtype=np.uint8)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, topk)
+
+
+def test_scan_u4_heavy_ties_and_extremes(ctx):
+    r = np.random.default_rng(6)
+    n = 200_003
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = r.integers(0, 4, (10, 16, 16), dtype=np.uint8)      # sums in 0..48: thousands of ties
+    qluts[1] = 255                                               # every sum = 4080
+    qluts[2] = 0
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 100)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 1000)
+
+
+def test_scan_u8_general_shapes(ctx):
+    r = np.random.default_rng(8)
+    codes = r.integers(0, 256, (5003, 8), dtype=np.uint8)
+    qluts = r.integers(0, 256, (4, 8, 256), dtype=np.uint8)
+    run_int_scan(ctx, codes, orc.CODES_U8, qluts, 64)
+    packed = r.integers(0, 256, (5003, 4), dtype=np.uint8)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, r.integers(0, 256, (2, 8, 16), dtype=np.uint8), 10)
+
+
+# ----------------------------------------------------------------------------- config 2 pipeline
+def test_quick_adc_pipeline_config2_small(ctx):
+    """16x4 codes: tables -> qmax pre-scan -> 8-bit tables -> integer scan top-1000 -> float rerank top-100.
+
+    Stage-wise parity: each oracle stage is fed the GPU output of the previous stage, so that
+    float rounding in the tables cannot move an integer decision.
+    """
+    _, queries, cb, codes16 = sift_pq(16, 16, 100000, 16)
+    packed = orc.pack_u4(codes16)
+    fmt = orc.CODES_U4_PACKED
+    dpacked = dev(packed)
+    luts = ctx.pq_build_luts(dev(queries), dev(cb))
+    qmax = ctx.pq_qmax_prescan(dpacked, fmt, luts, 2000, 1000)
+    qluts, qmin, scale = ctx.pq_quantize_luts(luts, qmax)
+    sums, cand = ctx.pq_adc_scan_topk(dpacked, fmt, qluts, 1000)
+    dist, ids = ctx.pq_rerank_f32(dpacked, fmt, luts, cand, 100)
+    luts_h, qmax_h, qluts_h, cand_h = host(luts), host(qmax), host(qluts), host(cand)
+    np.testing.assert_allclose(luts_h, orc.build_luts(queries, cb), rtol=4e-6)
+    ref_q, ref_min, ref_scale = orc.quantize_luts(luts_h, qmax_h)
+    assert np.array_equal(qluts_h, ref_q) and np.array_equal(host(qmin), ref_min) and np.array_equal(host(scale), ref_scale)
+    os_, oi = orc.adc_scan_topk_u8(packed, fmt, qluts_h, 1000)
+    check_exact_topk(host(sums), cand_h, os_, oi)
+    od, oid = orc.rerank_f32(packed, fmt, luts_h, cand_h, 100)
+    gd, gi = host(dist), host(ids)
+    for q in range(len(queries)):
+        np.testing.assert_allclose(gd[q], od[q], rtol=RTOL)
+        exact = orc.adc_all_f32(packed[gi[q]], fmt, luts_h[q])
+        np.testing.assert_allclose(gd[q], exact, rtol=RTOL)
+        assert np.all(exact <= od[q][-1] * (1 + RTOL))
+    # none of the top-1000 candidates has a clamped table entry (qmax = 1000-th distance of the pre-scan)
+    un = np.stack([packed & 15, packed >> 4], axis=2).reshape(len(packed), 16)
+    for q in range(len(queries)):
+        assert np.all(qluts_h[q][np.arange(16)[None, :], un[cand_h[q, :100]]] < 255)
+
+
+def test_rerank_matches_oracle(ctx):
+    r = np.random.default_rng(10)
+    n = 5000
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = r.random((4, 8, 256)).astype(np.float32)
+    cand = np.stack([r.choice(n, 300, replace=False) for _ in range(4)]).astype(np.int64)
+    cand[2, 5:9] = -1
+    d, i = ctx.pq_rerank_f32(dev(codes), binding.CODES_U8, dev(luts_h), dev(cand), 40)
+    od, oi = orc.rerank_f32(codes, orc.CODES_U8, luts_h, cand, 40)
+    assert np.array_equal(host(i), oi)
+    np.testing.assert_allclose(host(d), od, rtol=RTOL)
+
+
+# ----------------------------------------------------------------------------- error handling
+def test_errors_are_reported_not_raised_in_kernels(ctx):
+    codes = torch.zeros((10, 8), dtype=torch.uint8, device="cuda")
+    luts = torch.zeros((1, 8, 256), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.PqError) as e:
+        ctx.pq_adc_scan_topk(codes, binding.CODES_U8, luts, 0)
+    assert e.value.code == -1
+    with pytest.raises(binding.PqError) as e:
+        ctx.pq_adc_scan_topk(codes, binding.CODES_U8, luts, 5000)
+    assert e.value.code == -3
+    with pytest.raises(binding.PqError) as e:
+        ctx.pq_build_luts(torch.zeros((1, 10), device="cuda"), torch.zeros((3, 4, 3), device="cuda"))
+    assert e.value.code == -2
+    with pytest.raises(binding.PqError) as e:
+        ctx.pq_adc_scan_topk(codes[:, :4].contiguous(), binding.CODES_U4_PACKED, torch.zeros((1, 7, 16), device="cuda"), 5)
+    assert e.value.code == -2
+    # the context stays usable
+    d, i = ctx.pq_adc_scan_topk(codes, binding.CODES_U8, luts, 3)
+    assert host(i).tolist() == [[0, 1, 2]]

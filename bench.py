@@ -1,0 +1,174 @@
+"""Benchmark of the ADC-scan hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+  PQ 8x8 (default workload, BASELINE config 1): tables for 1000 queries, float ADC scan of
+  25 M codes, top-100.
+The 16x4 Quick-ADC-style pipeline (config 2: tables, qmax pre-scan, 8-bit tables, integer scan
+to top-1000, float rerank to top-100) is timed the same way and reported in "pq16x4".
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def read_traffic(name):
+    """Per-launch HBM bytes measured with rocprofv3 --pmc, stored as text under profiles/."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(codes_h, luts_h, gpu_dist, gpu_ids, sample_q, topk):
+    """Time the oracle's scan on the host cores for the first sample_q queries; check the GPU result on them."""
+    from oracle import pq_oracle as orc
+    threads = orc.set_threads(0)
+    luts_s = np.ascontiguousarray(luts_h[:sample_q])
+    t0 = time.perf_counter()
+    od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, luts_s, topk)
+    dt = time.perf_counter() - t0
+    ok = bool(np.allclose(gpu_dist[:sample_q], od, rtol=1e-5, atol=0) and (gpu_ids[:sample_q] == oi).mean() > 0.98)
+    return {"value": codes_h.shape[0] * sample_q / dt / 1e9, "unit": "G codes/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample_q} of the queries over all {codes_h.shape[0]} codes, {dt:.1f} s wall",
+            "gpu_matches_oracle_on_sample": ok}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--n", type=int, default=25_000_000)
+    ap.add_argument("--nq", type=int, default=1000)
+    ap.add_argument("--topk", type=int, default=100)
+    ap.add_argument("--cpu-queries", type=int, default=512)
+    ap.add_argument("--skip-16x4", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain copy kernel of this many MiB (counter calibration under rocprofv3)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1712_02912_amd import binding, datagen
+
+    ctx = binding.Context(0)
+    mix = datagen.sift_like()
+    queries_h = mix.sample(args.nq, datagen.SEED_QUERIES)
+    queries = torch.from_numpy(queries_h).cuda()
+
+    def sync():
+        torch.cuda.synchronize()
+
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        ctx.pq_calibration_copy(src, dst)
+        sync()
+        del src, dst
+
+    # ---------------------------------------------------------------- PQ 8x8 float scan
+    cb8 = torch.from_numpy(datagen.sampled_codebooks(mix, 8, 256)).cuda()
+    codes8_h = datagen.random_codes(args.n, 8)
+    codes8 = torch.from_numpy(codes8_h).cuda()
+    out = (torch.empty((args.nq, args.topk), dtype=torch.float32, device="cuda"),
+           torch.empty((args.nq, args.topk), dtype=torch.int64, device="cuda"))
+
+    def step8():
+        luts = ctx.pq_build_luts(queries, cb8)
+        ctx.pq_adc_scan_topk(codes8, binding.CODES_U8, luts, args.topk, out=out)
+        return luts
+
+    ctx.pq_set_profiling(True)
+    for _ in range(args.warmup):
+        step8()
+    sync()
+    kernel_ms = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        luts8 = step8()
+        kernel_ms.append(None)
+    sync()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # kernel duration from the events the library records on its own stream (last launch of the timed region,
+    # then a few more launches outside the timed region for an average)
+    durs = [ctx.pq_last_scan_kernel_ms()]
+    for _ in range(3):
+        step8()
+        durs.append(ctx.pq_last_scan_kernel_ms())
+    scan_ms = float(np.mean(durs))
+    alg_bytes = float(args.n) * 8 * args.nq
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    result = {
+        "metric": "adc_codes_scanned_per_s", "value": args.n * args.nq / (ms_per_step * 1e-3) / 1e9,
+        "unit": "G codes/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "PQ 8x8 float ADC scan (BASELINE config 1): N=%d uniform random codes, %d queries, "
+                               "fp32 LUTs 8x256 built each step, top-%d" % (args.n, args.nq, args.topk)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("scan_f32_pq8x8_config1_pmc.txt"),
+                     "kernel": "scan_f32_kernel<8>", "kernel_ms": scan_ms,
+                     "algorithmic_bytes": alg_bytes,
+                     "note": "algorithmic bytes = 8 B per code per query pass; 4 queries share each code fetched, "
+                             "so HBM traffic is below the algorithmic figure (see DESIGN.md)"},
+    }
+
+    # ---------------------------------------------------------------- PQ 16x4 Quick-ADC-style pipeline
+    if not args.skip_16x4:
+        cb16 = torch.from_numpy(datagen.sampled_codebooks(mix, 16, 16)).cuda()
+        codes4 = torch.from_numpy(datagen.random_codes(args.n, 8, seed=datagen.SEED_CODES + 1)).cuda()
+        fmt = binding.CODES_U4_PACKED
+
+        def step16():
+            luts = ctx.pq_build_luts(queries, cb16)
+            qmax = ctx.pq_qmax_prescan(codes4, fmt, luts, 2000, 1000)
+            qluts, _, _ = ctx.pq_quantize_luts(luts, qmax)
+            _, cand = ctx.pq_adc_scan_topk(codes4, fmt, qluts, 1000)
+            return ctx.pq_rerank_f32(codes4, fmt, luts, cand, args.topk)
+
+        for _ in range(args.warmup):
+            step16()
+        sync()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step16()
+        sync()
+        ms16 = (time.perf_counter() - t0) * 1e3 / args.steps
+        scan16_ms = ctx.pq_last_scan_kernel_ms()
+        ach16 = alg_bytes / (scan16_ms * 1e-3) / 1e9
+        result["pq16x4"] = {"value": args.n * args.nq / (ms16 * 1e-3) / 1e9, "unit": "G codes/s", "ms_per_step": ms16,
+                            "dtype": "u8 tables, integer sums", "workload": "PQ 16x4 packed codes (BASELINE config 2): "
+                            "tables, qmax pre-scan, 8-bit tables, integer scan top-1000, fp32 rerank top-%d" % args.topk,
+                            "roofline": {"bound": "hbm", "achieved": ach16, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": "scan_u4_kernel", "kernel_ms": scan16_ms,
+                                         "traffic": read_traffic("scan_u4_pq16x4_config2_pmc.txt")}}
+        del codes4
+
+    # ---------------------------------------------------------------- oracle on the host cores
+    if not args.skip_cpu:
+        sync()
+        result["cpu_baseline"] = cpu_baseline(codes8_h, luts8.cpu().numpy(), out[0].cpu().numpy(), out[1].cpu().numpy(),
+                                              min(args.cpu_queries, args.nq), args.topk)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

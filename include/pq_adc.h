@@ -62,6 +62,16 @@ const char *pq_last_error(const pq_ctx *ctx);
 /* Library version string, static storage. */
 const char *pq_version(void);
 
+/* Measurement aid: when enabled, pq_adc_scan_topk brackets its scan kernel (the kernel that
+ * streams the codes; not the small set-up and merge kernels) with HIP events on the context's
+ * stream.  pq_last_scan_kernel_ms waits for that kernel and returns its duration. */
+int pq_set_profiling(pq_ctx *ctx, int enable);
+int pq_last_scan_kernel_ms(pq_ctx *ctx, float *ms);
+/* Measurement aid: plain device-to-device copy of `bytes` bytes (multiple of 16, both pointers
+ * 16-byte aligned) by one kernel.  Its known traffic (bytes read + bytes written) calibrates
+ * the hardware counters that are read for the scan kernels. */
+int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes);
+
 /* Tables step, Eq. (tables) of Section 2.3.3:  luts[q][j][i] = || y_q^j - C^j[i] ||^2,
  * sub-space j = dimensions j*d/m .. (j+1)*d/m-1.
  *   queries   [nq][d] f32, codebooks [m][k][d/m] f32  ->  luts [nq][m][k] f32.

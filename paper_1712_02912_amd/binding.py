@@ -21,7 +21,8 @@ LUT_F32 = 0
 LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
-           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search"]
+           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_set_profiling",
+           "pq_last_scan_kernel_ms", "pq_calibration_copy"]
 
 _lib = None
 
@@ -53,6 +54,9 @@ def load():
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
+    lib.pq_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
+    lib.pq_set_profiling.argtypes = [vp, ci]
+    lib.pq_last_scan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     for name in EXPORTS:
         if name not in ("pq_last_error", "pq_version"):
             getattr(lib, name).restype = ci
@@ -107,6 +111,19 @@ class Context:
     def _check(self, rc):
         if rc != 0:
             raise PqError(rc, self.lib.pq_last_error(self.handle).decode())
+
+    def pq_set_profiling(self, enable):
+        self._check(self.lib.pq_set_profiling(self.handle, 1 if enable else 0))
+
+    def pq_last_scan_kernel_ms(self):
+        ms = ctypes.c_float()
+        self._check(self.lib.pq_last_scan_kernel_ms(self.handle, ctypes.byref(ms)))
+        return ms.value
+
+    def pq_calibration_copy(self, src, dst):
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() == nbytes
+        self._check(self.lib.pq_calibration_copy(self.handle, _ptr(src), _ptr(dst), nbytes))
 
     # -- Tables step -------------------------------------------------------------------------
     def pq_build_luts(self, queries, codebooks):

@@ -47,6 +47,15 @@ static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace pq
 
+namespace pq {
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                               size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace pq
+
 using namespace pq;
 
 extern "C" {
@@ -75,7 +84,38 @@ int pq_destroy(pq_ctx *ctx) {
     if (!ctx) return PQ_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
+    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     free(ctx);
+    return PQ_OK;
+}
+
+int pq_set_profiling(pq_ctx *ctx, int enable) {
+    if (!ctx) return PQ_EINVAL;
+    if (enable && !ctx->ev_begin) {
+        PQ_HIP(ctx, hipEventCreate(&ctx->ev_begin));
+        PQ_HIP(ctx, hipEventCreate(&ctx->ev_end));
+    }
+    ctx->profiling = enable ? 1 : 0;
+    ctx->ev_valid = 0;
+    return PQ_OK;
+}
+
+int pq_last_scan_kernel_ms(pq_ctx *ctx, float *ms) {
+    if (!ctx || !ms) return PQ_EINVAL;
+    if (!ctx->ev_valid) return fail(ctx, PQ_EINVAL, "no profiled scan kernel recorded");
+    PQ_HIP(ctx, hipEventSynchronize(ctx->ev_end));
+    PQ_HIP(ctx, hipEventElapsedTime(ms, ctx->ev_begin, ctx->ev_end));
+    return PQ_OK;
+}
+
+int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes) {
+    if (!ctx) return PQ_EINVAL;
+    if (!src || !dst || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))
+        return fail(ctx, PQ_EINVAL, "calibration_copy: need 16-byte aligned pointers and size");
+    if (bytes == 0) return PQ_OK;
+    calibration_copy_kernel<<<ctx->num_cu * 16, 256, 0, ctx->stream>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+    PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }
 

@@ -12,6 +12,9 @@ struct pq_ctx {
     void *ws;          // device workspace, grown on demand
     size_t ws_bytes;
     int num_cu;
+    int profiling;              // bracket the scan kernel with events
+    hipEvent_t ev_begin, ev_end;
+    int ev_valid;
     char err[512];
 };
 

@@ -554,8 +554,13 @@ static int run_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, const void *lu
     const int ntau = ngroups * qb;
     init_tau_kernel<<<(ntau + 255) / 256, 256, 0, ctx->stream>>>(a.tau_global, ntau, tau_init);
     PQ_HIP(ctx, hipGetLastError());
+    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     rc = launch(a, (int)nblocks);
     if (rc) return rc;
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
+        ctx->ev_valid = 1;
+    }
     const int n2 = next_pow2((int)nchunks * kpad);
     const int mthreads = n2 / 2 < 1024 ? (n2 / 2 < 64 ? 64 : n2 / 2) : 1024;
     if (val_u32)

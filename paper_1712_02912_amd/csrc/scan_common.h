@@ -1,0 +1,96 @@
+// Declarations shared by the scan kernels: value traits, per-wave selection state, launch
+// arguments of the tuned kernels and the host-side launchers.
+#pragma once
+#include <stdlib.h>
+
+#include "pq_internal.h"
+#include "topk_device.h"
+
+namespace pq {
+
+constexpr int TUNED_WAVES = 16;
+constexpr int TUNED_THREADS = TUNED_WAVES * 64;
+constexpr int HIST_BITS = 12;
+constexpr int HIST_BINS = 1 << HIST_BITS;
+constexpr int HIST_SHIFT = 14;             // float path: bin width in units of the ordered value
+constexpr uint32_t TAU_REF_UNSET = 0xffffffffu;
+
+struct TunedArgs {
+    const uint8_t *codes;
+    int64_t n;
+    int64_t chunk_codes;     // multiple of the block tile
+    int nchunks;
+    int ngroups;
+    int nitems;              // nchunks * ngroups, item = chunk * ngroups + group
+    const void *luts;        // [nq][m][k] f32 or u8
+    int nq;
+    int topk;
+    uint32_t *work_counter;  // next item to hand out
+    uint32_t *tau_global;    // [ngroups*QB] best bound known per query, ordered-value domain
+    uint32_t *ncand;         // [ngroups*QB] number of insert events per query
+    uint32_t *refresh_mark;  // [ngroups*QB] value of ncand when the histogram was last evaluated
+    uint32_t *tau_ref;       // [ngroups*QB] reference value of the histogram bins (float path), UNSET at first
+    uint32_t *hist;          // [ngroups*QB][HIST_BINS] values of the candidates inserted
+    uint64_t *scratch;       // [nblocks][TUNED_WAVES][QB][CAP]
+    uint64_t *partial;       // [nitems][QB][KPAD]
+};
+
+static inline int env_int(const char *name, int dflt) {
+    const char *s = getenv(name);
+    return s && *s ? atoi(s) : dflt;
+}
+
+int launch_merge_topk(pq_ctx *ctx, const uint64_t *partial, int nchunks, int ngroups, int qb, int kpad, int nq,
+                      int topk, bool val_u32, void *out_val, int64_t *out_ids);
+int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
+                      void *out_val, int64_t *out_ids);
+
+// ------------------------------------------------------------------------------------------
+// Value traits: how the accumulated value of one (code, query) pair maps to the ordered
+// 32-bit domain used in keys and shared thresholds.
+struct F32Val {
+    typedef float type;
+    static __device__ __forceinline__ uint32_t to_ord(float v) { return f32_to_ord(v); }
+    static __device__ __forceinline__ float from_ord(uint32_t o) { return ord_to_f32(o); }
+    static __device__ __forceinline__ uint32_t ord_inf() { return f32_to_ord(__builtin_inff()); }
+};
+struct U32Val {
+    typedef uint32_t type;
+    static __device__ __forceinline__ uint32_t to_ord(uint32_t v) { return v; }
+    static __device__ __forceinline__ uint32_t from_ord(uint32_t o) { return o; }
+    static __device__ __forceinline__ uint32_t ord_inf() { return 0x7fffu; }  // above any sum of 16 bytes
+};
+
+// Per-wave selection state for QB queries.  Everything here is wave-uniform.
+template <class V, int QB, int E>
+struct WaveTopK {
+    static constexpr int CAP = 64 * E;
+    uint64_t *buf[QB];
+    int cnt[QB];
+    uint32_t own_ord[QB];            // k-th smallest value of the wave's own list (ord_inf if not full)
+    typename V::type tau[QB];        // candidates satisfy value < tau
+    int k;
+
+    __device__ __forceinline__ void set_tau(int q, uint32_t shared_ord) {
+        // foreign bound prunes with "<=": value < shared+1 in the ordered domain
+        const uint32_t loose = shared_ord == 0xffffffffu ? shared_ord : shared_ord + 1u;
+        const uint32_t eff = own_ord[q] < loose ? own_ord[q] : loose;
+        tau[q] = V::from_ord(eff);
+    }
+
+    // insert the lanes with pass set; returns true if the wave's own bound changed
+    __device__ __forceinline__ bool insert(int q, bool pass, typename V::type val, uint32_t id) {
+        const uint64_t key = ((uint64_t)V::to_ord(val) << 32) | id;
+        cnt[q] = wave_append(buf[q], cnt[q], pass, key);
+        if (cnt[q] > CAP - 64) {
+            const uint64_t kth = wave_compact<E>(buf[q], cnt[q], k);
+            if (kth != KEY_EMPTY) {
+                own_ord[q] = (uint32_t)(kth >> 32);
+                return true;
+            }
+        }
+        return false;
+    }
+};
+
+}  // namespace pq

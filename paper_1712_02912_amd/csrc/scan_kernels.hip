@@ -1,24 +1,20 @@
-// Scan step: ADC over a contiguous code array with top-k selection (Alg. 1 `scan`/`adc`,
-// Eq. (adc1); Alg. 3 `quick_adc_scan` for packed 4-bit codes with 8-bit tables).
+// Scan step (Alg. 1 `scan`/`adc`, Eq. (adc1)): the general kernel for shapes outside the tuned
+// ones, the kernel that merges the per-block candidate lists into the final top-k, and the
+// dispatcher behind pq_adc_scan_topk.
 //
-// Work decomposition.  The code array is cut into chunks; the queries into groups of QB.
-// One block (8 waves) scans one chunk for one group: the group's tables sit in LDS with the
-// QB queries interleaved per entry, so that one LDS read of 16 bytes serves QB queries for
-// the same code byte, and every code byte fetched from HBM is used QB times.  Each lane owns
-// whole codes (one 16-byte load per iteration): row-major codes are already coalesced, no
-// transposed block layout is needed.
-//
-// Top-k.  Each wave keeps, per query, a candidate buffer in device scratch and a threshold.
-// A code is a candidate if its value is below the threshold; when a buffer is nearly full
-// the wave selects its k smallest keys, keeps them and lowers its threshold to the k-th.
-// Thresholds are shared (block LDS and a per-query device word, atomic min) so that waves
-// and later blocks prune with the best bound known.  A bound learnt from another wave is
-// the k-th smallest of a different subset: codes equal to it may still belong to the
-// result, so foreign bounds prune with "<=" and the wave's own with "<" (the wave meets
-// ids in increasing order, so a later code equal to its own k-th key can never replace it).
-// At the end of the block the 8 wave lists of each query are merged to one list of k keys;
-// a second kernel sorts the lists of all chunks of a query and writes the result.
+// Top-k in the general kernel.  Each wave keeps a candidate buffer in device scratch and a
+// threshold.  A code is a candidate if its value is below the threshold; when the buffer is
+// nearly full the wave selects its k smallest keys, keeps them and lowers its threshold to the
+// k-th.  Thresholds are shared (block LDS and a per-query device word, atomic min).  A bound
+// learnt from another wave is the k-th smallest of a different subset: codes equal to it may
+// still belong to the result, so foreign bounds prune with "<=" and the wave's own with "<"
+// (the wave meets ids in increasing order, so a later code equal to its own k-th key can never
+// replace it).  At the end of the block the 8 wave lists are merged to one list of k keys; the
+// merge kernel sorts the lists of all chunks of a query and writes the result.
+#include <type_traits>
+
 #include "pq_internal.h"
+#include "scan_common.h"
 #include "topk_device.h"
 
 namespace pq {
@@ -38,54 +34,6 @@ struct ScanArgs {
     uint32_t *tau_global;  // [ngroups*QB], ordered-value domain
     uint64_t *scratch;     // [nblocks][SCAN_WAVES][QB][CAP]
     uint64_t *partial;     // [nchunks*ngroups][QB][KPAD]
-};
-
-// ------------------------------------------------------------------------------------------
-// Value traits: how the accumulated value of one (code, query) pair maps to the ordered
-// 32-bit domain used in keys and shared thresholds.
-struct F32Val {
-    typedef float type;
-    static __device__ __forceinline__ uint32_t to_ord(float v) { return f32_to_ord(v); }
-    static __device__ __forceinline__ float from_ord(uint32_t o) { return ord_to_f32(o); }
-    static __device__ __forceinline__ uint32_t ord_inf() { return f32_to_ord(__builtin_inff()); }
-};
-struct U32Val {
-    typedef uint32_t type;
-    static __device__ __forceinline__ uint32_t to_ord(uint32_t v) { return v; }
-    static __device__ __forceinline__ uint32_t from_ord(uint32_t o) { return o; }
-    static __device__ __forceinline__ uint32_t ord_inf() { return 0x7fffu; }  // above any sum of 16 bytes
-};
-
-// Per-wave selection state for QB queries.  Everything here is wave-uniform.
-template <class V, int QB, int E>
-struct WaveTopK {
-    static constexpr int CAP = 64 * E;
-    uint64_t *buf[QB];
-    int cnt[QB];
-    uint32_t own_ord[QB];            // k-th smallest value of the wave's own list (ord_inf if not full)
-    typename V::type tau[QB];        // candidates satisfy value < tau
-    int k;
-
-    __device__ __forceinline__ void set_tau(int q, uint32_t shared_ord) {
-        // foreign bound prunes with "<=": value < shared+1 in the ordered domain
-        const uint32_t loose = shared_ord == 0xffffffffu ? shared_ord : shared_ord + 1u;
-        const uint32_t eff = own_ord[q] < loose ? own_ord[q] : loose;
-        tau[q] = V::from_ord(eff);
-    }
-
-    // insert the lanes with pass set; returns true if the wave's own bound changed
-    __device__ __forceinline__ bool insert(int q, bool pass, typename V::type val, uint32_t id) {
-        const uint64_t key = ((uint64_t)V::to_ord(val) << 32) | id;
-        cnt[q] = wave_append(buf[q], cnt[q], pass, key);
-        if (cnt[q] > CAP - 64) {
-            const uint64_t kth = wave_compact<E>(buf[q], cnt[q], k);
-            if (kth != KEY_EMPTY) {
-                own_ord[q] = (uint32_t)(kth >> 32);
-                return true;
-            }
-        }
-        return false;
-    }
 };
 
 // ------------------------------------------------------------------------------------------
@@ -112,286 +60,6 @@ __device__ __forceinline__ void block_merge_lists(uint64_t *block_scratch, int (
         uint64_t *out = out_item + (size_t)q * KPAD;
         for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// Float tables, one index per byte, 256 entries per table, MB = m = code bytes (8 or 16).
-// LDS: lut4[j*256 + i] = the entries (j, i) of the block's 4 queries.
-template <int MB, int E, int KPAD>
-__global__ __launch_bounds__(SCAN_THREADS) void scan_f32_kernel(ScanArgs a) {
-    constexpr int QB = 4;
-    constexpr int CPL = 16 / MB;          // codes per lane per tile
-    constexpr int TILE = 64 * CPL;        // codes per wave tile
-    constexpr int CAP = 64 * E;
-    extern __shared__ float4 lut4[];
-    __shared__ uint32_t tau_blk[QB];
-    __shared__ int wave_cnt[SCAN_WAVES][QB];
-
-    const int group = blockIdx.x % a.ngroups;
-    const int chunk = blockIdx.x / a.ngroups;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
-
-    // stage the tables: global [q][j*256+i] -> LDS [(j*256+i)][q]; queries past nq get +inf
-    {
-        const float *luts = (const float *)a.luts;
-        float *lds = (float *)lut4;
-        for (int q = 0; q < QB; ++q) {
-            const int gq = group * QB + q;
-            for (int e = threadIdx.x; e < MB * 256; e += SCAN_THREADS)
-                lds[e * QB + q] = gq < a.nq ? luts[(size_t)gq * (MB * 256) + e] : __builtin_inff();
-        }
-        if (threadIdx.x < QB) tau_blk[threadIdx.x] = a.tau_global[group * QB + threadIdx.x];
-    }
-    __syncthreads();
-
-    WaveTopK<F32Val, QB, E> st;
-    uint64_t *block_scratch = a.scratch + (size_t)blockIdx.x * SCAN_WAVES * QB * CAP;
-    st.k = a.topk;
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        st.buf[q] = block_scratch + (size_t)(wave * QB + q) * CAP;
-        st.cnt[q] = 0;
-        st.own_ord[q] = F32Val::ord_inf();
-        st.set_tau(q, tau_blk[q]);
-    }
-
-    const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
-    const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
-    const int64_t ntiles = cend > cbeg ? (cend - cbeg + TILE - 1) / TILE : 0;
-
-    auto load_tile = [&](int64_t t) -> uint4 {
-        const int64_t first = cbeg + t * TILE + (int64_t)lane * CPL;   // first code of this lane
-        uint4 c = make_uint4(0, 0, 0, 0);
-        if (first + CPL <= cend) {
-            c = *reinterpret_cast<const uint4 *>(a.codes + first * MB);
-        } else if (CPL == 2 && first < cend) {
-            const uint2 h = *reinterpret_cast<const uint2 *>(a.codes + first * MB);
-            c.x = h.x; c.y = h.y;
-        }
-        return c;
-    };
-
-    uint4 cur = make_uint4(0, 0, 0, 0);
-    if (wave < ntiles) cur = load_tile(wave);
-    int iter = 0;
-    for (int64_t t = wave; t < ntiles; t += SCAN_WAVES, ++iter) {
-        uint4 nxt = make_uint4(0, 0, 0, 0);
-        if (t + SCAN_WAVES < ntiles) nxt = load_tile(t + SCAN_WAVES);
-
-        const uint32_t w[4] = {cur.x, cur.y, cur.z, cur.w};
-        float d[CPL][QB];
-#pragma unroll
-        for (int h = 0; h < CPL; ++h) {
-#pragma unroll
-            for (int q = 0; q < QB; ++q) d[h][q] = 0.f;
-#pragma unroll
-            for (int j = 0; j < MB; ++j) {
-                const uint32_t word = w[h * (MB / 4) + j / 4];
-                const uint32_t b = (word >> (8 * (j & 3))) & 255u;
-                const float4 v = lut4[j * 256 + b];
-                d[h][0] += v.x; d[h][1] += v.y; d[h][2] += v.z; d[h][3] += v.w;
-            }
-        }
-        const int64_t first = cbeg + t * TILE + (int64_t)lane * CPL;
-        bool any = false;
-#pragma unroll
-        for (int h = 0; h < CPL; ++h) {
-            const bool valid = first + h < cend;
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                if (!valid) d[h][q] = __builtin_inff();
-                any |= d[h][q] < st.tau[q];
-            }
-        }
-        if (__ballot(any) != 0ull) {
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-#pragma unroll
-                for (int h = 0; h < CPL; ++h) {
-                    const bool pass = d[h][q] < st.tau[q];
-                    if (__ballot(pass) != 0ull) {
-                        if (st.insert(q, pass, d[h][q], (uint32_t)(first + h))) {
-                            atomicMin(&tau_blk[q], st.own_ord[q]);
-                            atomicMin(&a.tau_global[group * QB + q], st.own_ord[q]);
-                            st.set_tau(q, tau_blk[q]);
-                        }
-                    }
-                }
-            }
-        }
-        if ((iter & 15) == 15) {   // pick up bounds found by other waves and blocks
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                uint32_t s = tau_blk[q];
-                if ((iter & 63) == 63) {
-                    const uint32_t g = __hip_atomic_load(&a.tau_global[group * QB + q], __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-                    if (g < s) { atomicMin(&tau_blk[q], g); s = g; }
-                }
-                st.set_tau(q, s);
-            }
-        }
-        cur = nxt;
-    }
-
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        if (st.cnt[q] > st.k) wave_compact<E>(st.buf[q], st.cnt[q], st.k);
-        if (lane == 0) wave_cnt[wave][q] = st.cnt[q];
-    }
-    __threadfence();
-    __syncthreads();
-    block_merge_lists<QB, E, KPAD>(block_scratch, wave_cnt, a.topk,
-                                   a.partial + (size_t)blockIdx.x * QB * KPAD);
-}
-
-// ------------------------------------------------------------------------------------------
-// 8-bit tables, packed 4-bit indexes, m = 16 (8 bytes per code), 8 queries per block.
-// The 16 tables of 16 entries are merged in pairs when staged:
-//   T[r][byte] = Q[2r][byte & 15] + Q[2r+1][byte >> 4]          (r < 8, byte < 256)
-// so that one lookup per code byte gives the contribution of both nibbles; the integer
-// sums are unchanged.  Entries are 16 bits; LDS holds tab[r*256 + byte] = 8 queries x u16
-// (16 bytes), and the per-query sums (at most 16*255 = 4080) are accumulated as packed
-// pairs of 16-bit fields in 32-bit adds, which cannot carry across fields.
-template <int E, int KPAD>
-__global__ __launch_bounds__(SCAN_THREADS) void scan_u4_kernel(ScanArgs a) {
-    constexpr int QB = 8;
-    constexpr int CPL = 2, TILE = 128;
-    constexpr int CAP = 64 * E;
-    __shared__ uint4 tab[8 * 256];
-    __shared__ uint8_t qstage[QB][256];
-    __shared__ uint32_t tau_blk[QB];
-    __shared__ int wave_cnt[SCAN_WAVES][QB];
-
-    const int group = blockIdx.x % a.ngroups;
-    const int chunk = blockIdx.x / a.ngroups;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
-
-    {
-        const uint8_t *ql = (const uint8_t *)a.luts;
-        for (int e = threadIdx.x; e < QB * 256; e += SCAN_THREADS) {
-            const int q = e >> 8, gq = group * QB + q;
-            qstage[q][e & 255] = gq < a.nq ? ql[(size_t)gq * 256 + (e & 255)] : 0;
-        }
-        if (threadIdx.x < QB) tau_blk[threadIdx.x] = a.tau_global[group * QB + threadIdx.x];
-    }
-    __syncthreads();
-    {
-        uint16_t *t16 = (uint16_t *)tab;
-        for (int e = threadIdx.x; e < 8 * 256 * QB; e += SCAN_THREADS) {
-            const int q = e & 7, byte = (e >> 3) & 255, r = e >> 11;
-            const int gq = group * QB + q;
-            const uint32_t s = (uint32_t)qstage[q][(2 * r) * 16 + (byte & 15)] +
-                               (uint32_t)qstage[q][(2 * r + 1) * 16 + (byte >> 4)];
-            t16[e] = gq < a.nq ? (uint16_t)s : (uint16_t)0x0fff;   // padded queries never qualify
-        }
-    }
-    __syncthreads();
-
-    WaveTopK<U32Val, QB, E> st;
-    uint64_t *block_scratch = a.scratch + (size_t)blockIdx.x * SCAN_WAVES * QB * CAP;
-    st.k = a.topk;
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        st.buf[q] = block_scratch + (size_t)(wave * QB + q) * CAP;
-        st.cnt[q] = 0;
-        st.own_ord[q] = U32Val::ord_inf();
-        st.set_tau(q, tau_blk[q]);
-        if (group * QB + q >= a.nq) st.tau[q] = 0;
-    }
-
-    const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
-    const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
-    const int64_t ntiles = cend > cbeg ? (cend - cbeg + TILE - 1) / TILE : 0;
-
-    auto load_tile = [&](int64_t t) -> uint4 {
-        const int64_t first = cbeg + t * TILE + (int64_t)lane * CPL;
-        uint4 c = make_uint4(0, 0, 0, 0);
-        if (first + CPL <= cend) {
-            c = *reinterpret_cast<const uint4 *>(a.codes + first * 8);
-        } else if (first < cend) {
-            const uint2 h = *reinterpret_cast<const uint2 *>(a.codes + first * 8);
-            c.x = h.x; c.y = h.y;
-        }
-        return c;
-    };
-
-    uint4 cur = make_uint4(0, 0, 0, 0);
-    if (wave < ntiles) cur = load_tile(wave);
-    int iter = 0;
-    for (int64_t t = wave; t < ntiles; t += SCAN_WAVES, ++iter) {
-        uint4 nxt = make_uint4(0, 0, 0, 0);
-        if (t + SCAN_WAVES < ntiles) nxt = load_tile(t + SCAN_WAVES);
-
-        const uint32_t w[4] = {cur.x, cur.y, cur.z, cur.w};
-        uint32_t acc[CPL][4];   // acc[h][p] = sums of queries 2p (low half) and 2p+1 (high half)
-#pragma unroll
-        for (int h = 0; h < CPL; ++h) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) acc[h][p] = 0;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                const uint32_t word = w[h * 2 + r / 4];
-                const uint32_t b = (word >> (8 * (r & 3))) & 255u;
-                const uint4 v = tab[r * 256 + b];
-                acc[h][0] += v.x; acc[h][1] += v.y; acc[h][2] += v.z; acc[h][3] += v.w;
-            }
-        }
-        const int64_t first = cbeg + t * TILE + (int64_t)lane * CPL;
-        // fast test on packed fields: (x | 0x8000) - tau keeps bit 15 iff x >= tau
-        uint32_t allge = 0x80008000u;
-#pragma unroll
-        for (int h = 0; h < CPL; ++h) {
-            const bool valid = first + h < cend;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                if (!valid) acc[h][p] = 0x7fff7fffu;
-                const uint32_t taupk = st.tau[2 * p] | (st.tau[2 * p + 1] << 16);
-                allge &= (acc[h][p] | 0x80008000u) - taupk;
-            }
-        }
-        const bool any = (allge & 0x80008000u) != 0x80008000u;
-        if (__ballot(any) != 0ull) {
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-#pragma unroll
-                for (int h = 0; h < CPL; ++h) {
-                    const uint32_t x = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                    const bool pass = x < st.tau[q];
-                    if (__ballot(pass) != 0ull) {
-                        if (st.insert(q, pass, x, (uint32_t)(first + h))) {
-                            atomicMin(&tau_blk[q], st.own_ord[q]);
-                            atomicMin(&a.tau_global[group * QB + q], st.own_ord[q]);
-                            st.set_tau(q, tau_blk[q]);
-                        }
-                    }
-                }
-            }
-        }
-        if ((iter & 15) == 15) {
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                uint32_t s = tau_blk[q];
-                if ((iter & 63) == 63) {
-                    const uint32_t g = __hip_atomic_load(&a.tau_global[group * QB + q], __ATOMIC_RELAXED,
-                                                         __HIP_MEMORY_SCOPE_AGENT);
-                    if (g < s) { atomicMin(&tau_blk[q], g); s = g; }
-                }
-                if (group * QB + q < a.nq) st.set_tau(q, s);
-            }
-        }
-        cur = nxt;
-    }
-
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        if (st.cnt[q] > st.k) wave_compact<E>(st.buf[q], st.cnt[q], st.k);
-        if (lane == 0) wave_cnt[wave][q] = st.cnt[q];
-    }
-    __threadfence();
-    __syncthreads();
-    block_merge_lists<QB, E, KPAD>(block_scratch, wave_cnt, a.topk,
-                                   a.partial + (size_t)blockIdx.x * QB * KPAD);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -509,25 +177,38 @@ __global__ __launch_bounds__(1024) void merge_topk_kernel(const uint64_t *partia
 // ------------------------------------------------------------------------------------------
 static int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
-static int env_int(const char *name, int dflt) {
-    const char *s = getenv(name);
-    return s && *s ? atoi(s) : dflt;
+int launch_merge_topk(pq_ctx *ctx, const uint64_t *partial, int nchunks, int ngroups, int qb, int kpad, int nq,
+                      int topk, bool val_u32, void *out_val, int64_t *out_ids) {
+    const int n2 = next_pow2(nchunks * kpad);
+    if (n2 > 16384) return fail(ctx, PQ_EUNSUPPORTED, "merge: %d keys per query exceed the LDS sort", n2);
+    const int mthreads = n2 / 2 < 1024 ? (n2 / 2 < 64 ? 64 : n2 / 2) : 1024;
+    if (val_u32) {
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_topk_kernel<true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+        merge_topk_kernel<true><<<nq, mthreads, (size_t)n2 * 8, ctx->stream>>>(partial, nchunks, ngroups, qb, kpad, n2,
+                                                                               topk, out_val, out_ids);
+    } else {
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_topk_kernel<false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+        merge_topk_kernel<false><<<nq, mthreads, (size_t)n2 * 8, ctx->stream>>>(partial, nchunks, ngroups, qb, kpad, n2,
+                                                                                topk, out_val, out_ids);
+    }
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
 }
 
-template <class Launch>
-static int run_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk, int qb,
-                    int tile_codes, int kpad, int cap, bool val_u32, uint32_t tau_init, void *out_val,
-                    int64_t *out_ids, Launch launch) {
-    const int ngroups = (nq + qb - 1) / qb;
-    const int64_t block_tile = (int64_t)tile_codes * SCAN_WAVES;
+// General kernel: one block per (chunk, query).
+static int run_generic(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, bool lut_u8, int nq,
+                       int m, int k, int topk, void *out_val, int64_t *out_ids) {
+    const bool small = topk <= 128;
+    const int kpad = small ? 128 : 1024, cap = 2 * kpad, qb = 1;
+    const int ngroups = nq;
+    const int64_t block_tile = 64 * SCAN_WAVES;
     // enough blocks to keep every CU busy for several rounds, but chunks of at least 8 block tiles
-    const int target_blocks = env_int("PQ_SCAN_TARGET_BLOCKS", 16 * ctx->num_cu);
-    int64_t nchunks = (target_blocks + ngroups - 1) / ngroups;
+    int64_t nchunks = (16 * ctx->num_cu + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
     const int64_t max_by_merge = 16384 / kpad;
     if (nchunks > max_by_n) nchunks = max_by_n;
-    if (nchunks > max_by_merge) nchunks = max_by_merge;
-    if (env_int("PQ_SCAN_CHUNKS", 0) > 0) nchunks = env_int("PQ_SCAN_CHUNKS", 0);
     if (nchunks > max_by_merge) nchunks = max_by_merge;
     if (nchunks < 1) nchunks = 1;
     int64_t chunk_codes = (n + nchunks - 1) / nchunks;
@@ -552,85 +233,35 @@ static int run_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, const void *lu
     a.partial = (uint64_t *)(ws + tau_bytes + scratch_bytes);
 
     const int ntau = ngroups * qb;
-    init_tau_kernel<<<(ntau + 255) / 256, 256, 0, ctx->stream>>>(a.tau_global, ntau, tau_init);
+    init_tau_kernel<<<(ntau + 255) / 256, 256, 0, ctx->stream>>>(a.tau_global, ntau,
+                                                                 lut_u8 ? 0xfffffffeu : 0xff800000u /* ordered +inf */);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    rc = launch(a, (int)nblocks);
-    if (rc) return rc;
+    hipStream_t s = ctx->stream;
+    if (lut_u8) {
+        if (small) scan_generic_kernel<true, 4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
+        else scan_generic_kernel<true, 32, 1024><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
+    } else {
+        if (small) scan_generic_kernel<false, 4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
+        else scan_generic_kernel<false, 32, 1024><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
+    }
+    PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
         ctx->ev_valid = 1;
     }
-    const int n2 = next_pow2((int)nchunks * kpad);
-    const int mthreads = n2 / 2 < 1024 ? (n2 / 2 < 64 ? 64 : n2 / 2) : 1024;
-    if (val_u32)
-        merge_topk_kernel<true><<<nq, mthreads, (size_t)n2 * 8, ctx->stream>>>(a.partial, (int)nchunks, ngroups, qb, kpad, n2, topk, out_val, out_ids);
-    else
-        merge_topk_kernel<false><<<nq, mthreads, (size_t)n2 * 8, ctx->stream>>>(a.partial, (int)nchunks, ngroups, qb, kpad, n2, topk, out_val, out_ids);
-    PQ_HIP(ctx, hipGetLastError());
-    return PQ_OK;
-}
-
-template <class K>
-static int set_lds(pq_ctx *ctx, K kernel, size_t bytes) {
-    PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-    return PQ_OK;
+    return launch_merge_topk(ctx, a.partial, (int)nchunks, ngroups, qb, kpad, nq, topk, lut_u8, out_val, out_ids);
 }
 
 int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, int lf, int nq, int m, int k,
                 int topk, void *out_val, int64_t *out_ids) {
-    const bool small = topk <= 128;
-    const int kpad = small ? 128 : 1024;
-    const int cap = 2 * kpad;
-    hipStream_t s = ctx->stream;
-    {
-        int rc = set_lds(ctx, merge_topk_kernel<true>, 131072);
-        if (!rc) rc = set_lds(ctx, merge_topk_kernel<false>, 131072);
-        if (rc) return rc;
-    }
-    if (cf == PQ_CODES_U8 && lf == PQ_LUT_F32 && k == 256 && (m == 8 || m == 16)) {
-        const size_t lds = (size_t)m * 256 * 16;
-        auto launch = [&](const ScanArgs &a, int nblocks) -> int {
-#define PQ_LAUNCH_F32(MB, E, KP)                                                                  \
-    do {                                                                                          \
-        int rc_ = set_lds(ctx, scan_f32_kernel<MB, E, KP>, lds);                                  \
-        if (rc_) return rc_;                                                                      \
-        scan_f32_kernel<MB, E, KP><<<nblocks, SCAN_THREADS, lds, s>>>(a);                         \
-    } while (0)
-            if (m == 8) { if (small) PQ_LAUNCH_F32(8, 4, 128); else PQ_LAUNCH_F32(8, 32, 1024); }
-            else { if (small) PQ_LAUNCH_F32(16, 4, 128); else PQ_LAUNCH_F32(16, 32, 1024); }
-#undef PQ_LAUNCH_F32
-            PQ_HIP(ctx, hipGetLastError());
-            return PQ_OK;
-        };
-        return run_scan(ctx, codes, n, luts, nq, topk, 4, m == 8 ? 128 : 64, kpad, cap, false,
-                        0xff800000u /* ordered +inf */, out_val, out_ids, launch);
-    }
-    if (cf == PQ_CODES_U4_PACKED && lf == PQ_LUT_U8 && k == 16 && m == 16) {
-        auto launch = [&](const ScanArgs &a, int nblocks) -> int {
-            if (small) scan_u4_kernel<4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a);
-            else scan_u4_kernel<32, 1024><<<nblocks, SCAN_THREADS, 0, s>>>(a);
-            PQ_HIP(ctx, hipGetLastError());
-            return PQ_OK;
-        };
-        return run_scan(ctx, codes, n, luts, nq, topk, 8, 128, kpad, cap, true, 0x7fffu, out_val, out_ids, launch);
-    }
-    if ((int64_t)m * k <= 8192) {
-        const bool u8 = lf == PQ_LUT_U8;
-        auto launch = [&](const ScanArgs &a, int nblocks) -> int {
-            if (u8) {
-                if (small) scan_generic_kernel<true, 4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
-                else scan_generic_kernel<true, 32, 1024><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
-            } else {
-                if (small) scan_generic_kernel<false, 4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
-                else scan_generic_kernel<false, 32, 1024><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);
-            }
-            PQ_HIP(ctx, hipGetLastError());
-            return PQ_OK;
-        };
-        return run_scan(ctx, codes, n, luts, nq, topk, 1, 64, kpad, cap, u8, u8 ? 0xfffffffeu : 0xff800000u, out_val,
-                        out_ids, launch);
-    }
+    const bool general = env_int("PQ_SCAN_FORCE_GENERAL", 0) != 0;
+    if (!general && cf == PQ_CODES_U8 && lf == PQ_LUT_F32 && k == 256 && (m == 8 || m == 16))
+        return launch_scan_tuned(ctx, m == 8 ? 0 : 1, codes, n, luts, nq, topk, out_val, out_ids);
+    if (!general && cf == PQ_CODES_U4_PACKED && lf == PQ_LUT_U8 && k == 16 && m == 16)
+        return launch_scan_tuned(ctx, 2, codes, n, luts, nq, topk, out_val, out_ids);
+    if ((int64_t)m * k <= 8192)
+        return run_generic(ctx, codes, n, cf, luts, lf == PQ_LUT_U8, nq, m, k, topk, out_val, out_ids);
     return fail(ctx, PQ_EUNSUPPORTED, "scan: no kernel for m=%d k=%d code_fmt=%d lut_fmt=%d", m, k, cf, lf);
 }
 

@@ -1,0 +1,658 @@
+// Tuned scan kernels (Alg. 1 `scan`/`adc`, Eq. (adc1); Alg. 3 for packed 4-bit codes):
+//   F32_M8  : 8 float tables of 256 entries, 8-byte codes, 4 queries per block
+//   F32_M16 : 16 float tables of 256 entries, 16-byte codes, 4 queries per block
+//   U4_M16  : 16 tables of 16 bytes merged in pairs to 8 tables of 256 16-bit entries,
+//             8-byte packed codes, 8 queries per block
+//
+// LDS layout (64 KB).  Row b (256 bytes) holds, for code-byte value b, 16 slots of 16 bytes.
+// A slot is the entry of one table for all queries of the block (4 floats, or 8 x u16).
+// With 8 tables every table owns two slots (two copies), with 16 tables one.  The LDS
+// serves a 16-byte read of a wave in passes of 16 lanes that differ in the low four lane
+// bits, and two lanes of a pass collide unless they hit different 16-byte bank groups
+// (or the same address).  Lane l therefore reads slot ((l & 15) + S*s) & 15 at step s
+// (S = 2 with copies, 1 without): the 16 lanes of a pass always hit 16 different slots, so
+// every read is conflict-free whatever the code bytes are.  Each lane walks the tables in
+// its own rotated order, which only permutes the order of the float additions.
+//
+// Work distribution.  A fixed number of persistent blocks (two per CU) take work items
+// (chunk of codes x group of queries) from a device counter, chunk-major, so that blocks
+// running at the same time share code chunks in L2 and later chunks start with the bounds
+// the earlier ones found.
+//
+// Top-k.  Per wave and query a bounded candidate list in device scratch, as in the general
+// kernel, plus a per-query histogram of the values of the candidates inserted by any wave.
+// The smallest bin edge below which k candidates have been counted is a valid bound on the
+// k-th smallest value of the whole scan and is shared through one word per query.  Integer
+// sums index the bins directly.  Float values are binned by their distance, in ordered-bit
+// units, below a per-query reference (the first bound any wave publishes): bin width 2^14
+// units (about 0.2 % of the value), 4096 bins reaching down to 1/256 of the reference, smaller
+// values lumped in the first bin; candidates seen before the reference exists are not counted.
+#include <type_traits>
+
+#include "pq_internal.h"
+#include "scan_common.h"
+#include "topk_device.h"
+
+namespace pq {
+
+// Per-wave selection state kept in LDS: the scan loop itself only holds the thresholds in
+// registers; everything else is touched on the rare paths below.
+struct WaveState {
+    int cnt[8];
+    uint32_t own_ord[8];   // k-th smallest value of the wave's own list, ord_inf while not full
+};
+
+struct __align__(16) TunedSmem {
+    uint4 lut[4096];
+    uint8_t qstage[8][256];
+    WaveState ws[TUNED_WAVES];
+    uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
+    uint32_t tau_ref[8];   // histogram reference per query (float path)
+    // per item, written by thread 0
+    uint32_t *hist;        // histogram of query 0 of the group
+    uint32_t *ncand;
+    uint32_t *refresh_mark;
+    uint32_t *tau_global;
+    uint32_t *tau_ref_global;
+    int nvalid;            // queries of the group that exist
+    int topk;
+    int item;
+};
+
+// rotate the bytes of a 64-bit code right by r bytes (r in 0..7): byte s of the result is
+// byte (s + r) & 7 of the input
+__device__ __forceinline__ void rot8(uint32_t &lo, uint32_t &hi, bool swap, uint32_t sh) {
+    const uint32_t a = swap ? hi : lo, b = swap ? lo : hi;
+    lo = __builtin_amdgcn_alignbyte(b, a, sh);
+    hi = __builtin_amdgcn_alignbyte(a, b, sh);
+}
+
+// rotate the bytes of a 128-bit code right by r bytes (r in 0..15)
+__device__ __forceinline__ void rot16(uint32_t (&w)[4], uint32_t r) {
+    if (r & 8u) { uint32_t t = w[0]; w[0] = w[2]; w[2] = t; t = w[1]; w[1] = w[3]; w[3] = t; }
+    if (r & 4u) { const uint32_t t = w[0]; w[0] = w[1]; w[1] = w[2]; w[2] = w[3]; w[3] = t; }
+    const uint32_t sh = r & 3u;
+    const uint32_t a = w[0], b = w[1], c = w[2], d = w[3];
+    w[0] = __builtin_amdgcn_alignbyte(b, a, sh);
+    w[1] = __builtin_amdgcn_alignbyte(c, b, sh);
+    w[2] = __builtin_amdgcn_alignbyte(d, c, sh);
+    w[3] = __builtin_amdgcn_alignbyte(a, d, sh);
+}
+
+// LDS byte offset of the lookup for byte `pos` of `word`: (code byte << 8) | slot offset.
+// `bases` holds the slot offsets (slot * 16, below 256) of four consecutive steps.
+template <int POS>
+__device__ __forceinline__ uint32_t lut_offset(uint32_t word, uint32_t bases) {
+    // result byte 0 <- bases byte POS, byte 1 <- word byte POS, bytes 2 and 3 <- 0
+    constexpr uint32_t sel = 0x0c0c0000u | ((4u + POS) << 8) | (uint32_t)POS;
+    return __builtin_amdgcn_perm(word, bases, sel);
+}
+
+// smallest histogram bin b with count(bins <= b) >= k, or HIST_BINS if fewer than k counted
+__device__ __forceinline__ int hist_threshold(const uint32_t *hist, int k) {
+    const int lane = lane_id();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const uint4 *h4 = reinterpret_cast<const uint4 *>(hist) + lane * (HIST_BINS / 64 / 4);
+    uint32_t tot = 0;
+#pragma unroll 4
+    for (int i = 0; i < HIST_BINS / 64 / 4; ++i) {
+        const uint4 v = h4[i];
+        tot += v.x + v.y + v.z + v.w;
+    }
+    uint32_t incl = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    const uint64_t reach = __ballot(incl >= (uint32_t)k);
+    if (reach == 0ull) return HIST_BINS;
+    const int first = __builtin_ctzll(reach);
+    // every lane locates the crossing inside its own 64 bins; only lane `first` has a meaningful need
+    const uint32_t need = (uint32_t)k - (incl - tot);
+    uint32_t cum = 0;
+    int bin = HIST_BINS;
+#pragma unroll 2
+    for (int i = 0; i < HIST_BINS / 64 / 4; ++i) {
+        const uint4 v = h4[i];
+        const uint32_t e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            cum += e[t];
+            if (bin == HIST_BINS && cum >= need) bin = lane * (HIST_BINS / 64) + i * 4 + t;
+        }
+    }
+    return __shfl(bin, first);
+}
+
+enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2 };
+
+__device__ __forceinline__ void publish_bound(TunedSmem *sm, int q, uint32_t ord) {
+    atomicMin(&sm->tau_blk[q], ord);
+    atomicMin(&sm->tau_global[q], ord);
+}
+
+// Rare path of the scan loop: the candidate list of query q of this wave is nearly full.  Keep
+// its k smallest keys, make the k-th the wave's own bound and share it.  Returns the new count.
+template <int E, bool IS_U4>
+__device__ __noinline__ int scan_compact(TunedSmem *sm, uint64_t *buf, int cnt, int q) {
+    const int lane = lane_id();
+    WaveState *ws = &sm->ws[threadIdx.x >> 6];
+    const uint64_t kth = wave_compact<E>(buf, cnt, sm->topk);
+    if (kth != KEY_EMPTY) {
+        const uint32_t kord = (uint32_t)(kth >> 32);
+        if (lane == 0) ws->own_ord[q] = kord;
+        publish_bound(sm, q, kord);
+        if (!IS_U4 && sm->tau_ref[q] == TAU_REF_UNSET) {
+            // the first bound published for a query becomes the reference of its histogram
+            uint32_t expected = TAU_REF_UNSET;
+            __hip_atomic_compare_exchange_strong(&sm->tau_ref_global[q], &expected, kord, __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t now = expected == TAU_REF_UNSET ? kord : expected;
+            if (lane == 0) sm->tau_ref[q] = now;
+        }
+    }
+    return cnt;
+}
+
+// Periodic path (one wave per query and period): pick up the best bound published for query q
+// by any block and, if enough candidates arrived since the histogram was last evaluated and no
+// other wave is already doing it, recompute the bound from the histogram.
+constexpr uint32_t REFRESH_MIN_NEW = 16;
+template <bool IS_U4>
+__device__ __noinline__ void scan_refresh(TunedSmem *sm, int q) {
+    const uint32_t g = __hip_atomic_load(&sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane_id() == 0) atomicMin(&sm->tau_blk[q], g);
+    uint32_t ref = 0;
+    if (!IS_U4) {
+        ref = __builtin_amdgcn_readfirstlane(sm->tau_ref[q]);
+        if (ref == TAU_REF_UNSET) {
+            ref = __builtin_amdgcn_readfirstlane(
+                __hip_atomic_load(&sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            if (ref == TAU_REF_UNSET) return;
+            if (lane_id() == 0) sm->tau_ref[q] = ref;
+        }
+    }
+    const uint32_t n = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(&sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const uint32_t mark = __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(&sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    if (n - mark < REFRESH_MIN_NEW) return;
+    uint32_t won = 0;
+    if (lane_id() == 0) {
+        uint32_t expected = mark;
+        won = __hip_atomic_compare_exchange_strong(&sm->refresh_mark[q], &expected, n, __ATOMIC_RELAXED,
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? 1u : 0u;
+    }
+    if (__builtin_amdgcn_readfirstlane(won) == 0u) return;
+    const int bin = hist_threshold(sm->hist + (size_t)q * HIST_BINS, sm->topk);
+    if (bin < HIST_BINS) {
+        // every value counted in bins <= bin is at or below this edge
+        const uint32_t edge = IS_U4 ? (uint32_t)bin : ref - ((uint32_t)(HIST_BINS - 1 - bin) << HIST_SHIFT);
+        publish_bound(sm, q, edge);
+    }
+}
+
+// End of item, per wave: leave at most k keys in every list.
+template <int QB, int E>
+__device__ __noinline__ void scan_finish_wave(TunedSmem *sm, uint64_t *wave_buf) {
+    constexpr int CAP = 64 * E;
+    WaveState *ws = &sm->ws[threadIdx.x >> 6];
+    for (int q = 0; q < QB; ++q) {
+        int cnt = ws->cnt[q];
+        if (cnt > sm->topk) {
+            wave_compact<E>(wave_buf + (size_t)q * CAP, cnt, sm->topk);
+            if (lane_id() == 0) ws->cnt[q] = cnt;
+        }
+    }
+}
+
+// End of item, wave q < QB: fold the lists of all waves for query q into the list of wave 0
+// and write KPAD keys (padded with KEY_EMPTY) to out.
+template <int QB, int E, int KPAD>
+__device__ __noinline__ void scan_merge_item(TunedSmem *sm, uint64_t *block_scratch, uint64_t *out) {
+    constexpr int CAP = 64 * E;
+    const int q = threadIdx.x >> 6, lane = lane_id();
+    const int k = sm->topk;
+    uint64_t *acc = block_scratch + (size_t)q * CAP;   // list of wave 0
+    int cnt = sm->ws[0].cnt[q];
+    for (int w = 1; w < TUNED_WAVES; ++w) {
+        const uint64_t *src = block_scratch + (size_t)(w * QB + q) * CAP;
+        const int cw = sm->ws[w].cnt[q];
+        if (cw == 0) continue;
+        for (int i = lane; i < cw; i += 64) key_store(acc + cnt + i, key_load(src + i));
+        cnt += cw;
+        if (cnt > k) wave_compact<E>(acc, cnt, k);
+    }
+    __threadfence();
+    for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
+}
+
+template <int KIND, int E, int KPAD>
+__global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void scan_tuned_kernel(TunedArgs a) {
+    constexpr bool IS_U4 = KIND == KIND_U4_M16;
+    constexpr int QB = IS_U4 ? 8 : 4;
+    constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;     // tables = lookups per code
+    constexpr int CB = NT;                                // code bytes (8 or 16)
+    constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
+    constexpr int SUB = 64 * CPL;                         // codes per wave sub-tile (one load per lane)
+    constexpr int BATCH = 1;                              // sub-tiles fetched together
+    constexpr int TILE = SUB * BATCH;                     // codes per wave tile
+    constexpr int CAP = 64 * E;
+    constexpr int SSTEP = NT == 8 ? 2 : 1;                // slot stride per step
+    constexpr int NACC = 4;                               // accumulators per code (4 floats or 4 packed pairs)
+    typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
+    typedef typename V::type val_t;
+    __shared__ TunedSmem sm;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keep it scalar
+    const int lane = lane_id();
+    const uint32_t lane15 = lane & 15;
+    const uint32_t rot = NT == 8 ? lane15 >> 1 : lane15;
+    const bool rot_swap = (rot & 4u) != 0;
+    uint32_t bases[NT / 4];
+#pragma unroll
+    for (int g = 0; g < NT / 4; ++g) {
+        bases[g] = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) bases[g] |= (((lane15 + SSTEP * (4 * g + p)) & 15u) << 4) << (8 * p);
+    }
+    const char *lut_bytes = reinterpret_cast<const char *>(sm.lut);
+    uint64_t *block_scratch = a.scratch + (size_t)blockIdx.x * TUNED_WAVES * QB * CAP;
+    uint64_t *wave_buf = block_scratch + (size_t)wave * QB * CAP;
+
+    for (;;) {
+        if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
+        __syncthreads();
+        const int item = sm.item;
+        if (item >= a.nitems) break;
+        const int group = item % a.ngroups;
+        const int chunk = item / a.ngroups;
+
+        // ---- stage the tables of the group's queries --------------------------------------
+        if constexpr (!IS_U4) {
+            const float *luts = (const float *)a.luts;
+            for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
+                const int j = e >> 8, byte = e & 255;
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int gq = group * QB + q;
+                    v[q] = gq < a.nq ? luts[(size_t)gq * (NT * 256) + e] : __builtin_inff();
+                }
+                const uint4 pk = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
+                                            __float_as_uint(v[3]));
+                if (NT == 8) { sm.lut[byte * 16 + 2 * j] = pk; sm.lut[byte * 16 + 2 * j + 1] = pk; }
+                else sm.lut[byte * 16 + j] = pk;
+            }
+        } else {
+            const uint8_t *ql = (const uint8_t *)a.luts;
+            for (int e = threadIdx.x; e < QB * 256; e += TUNED_THREADS) {
+                const int q = e >> 8, gq = group * QB + q;
+                sm.qstage[q][e & 255] = gq < a.nq ? ql[(size_t)gq * 256 + (e & 255)] : 0;
+            }
+            __syncthreads();
+            // pair-merged tables: T[r][byte] = Q[2r][byte & 15] + Q[2r+1][byte >> 4]
+            for (int e = threadIdx.x; e < 8 * 256; e += TUNED_THREADS) {
+                const int r = e >> 8, byte = e & 255;
+                uint32_t s[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int gq = group * QB + q;
+                    s[q] = gq < a.nq ? (uint32_t)sm.qstage[q][(2 * r) * 16 + (byte & 15)] +
+                                           (uint32_t)sm.qstage[q][(2 * r + 1) * 16 + (byte >> 4)]
+                                     : 0x0fffu;   // padded queries never qualify
+                }
+                const uint4 pk = make_uint4(s[0] | (s[1] << 16), s[2] | (s[3] << 16), s[4] | (s[5] << 16),
+                                            s[6] | (s[7] << 16));
+                sm.lut[byte * 16 + 2 * r] = pk;
+                sm.lut[byte * 16 + 2 * r + 1] = pk;
+            }
+        }
+        if (threadIdx.x < QB) {
+            sm.tau_blk[threadIdx.x] = __hip_atomic_load(&a.tau_global[group * QB + threadIdx.x], __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+            sm.tau_ref[threadIdx.x] = __hip_atomic_load(&a.tau_ref[group * QB + threadIdx.x], __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (threadIdx.x == 0) {
+            sm.hist = a.hist + (size_t)group * QB * HIST_BINS;
+            sm.ncand = a.ncand + group * QB;
+            sm.refresh_mark = a.refresh_mark + group * QB;
+            sm.tau_global = a.tau_global + group * QB;
+            sm.tau_ref_global = a.tau_ref + group * QB;
+            sm.nvalid = a.nq - group * QB < QB ? a.nq - group * QB : QB;
+            sm.topk = a.topk;
+        }
+        if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
+        __syncthreads();
+
+        const int nvalid_q = sm.nvalid;
+        uint32_t *const hist_q0 = a.hist + (size_t)group * QB * HIST_BINS;
+        uint32_t *const ncand_q0 = a.ncand + group * QB;
+        int cnt[QB];                       // length of this wave's candidate list per query (uniform)
+#pragma unroll
+        for (int q = 0; q < QB; ++q) cnt[q] = 0;
+        // thresholds in registers: a code is a candidate for query q if value < tau[q]
+        val_t tau[QB];
+        auto reload_tau = [&]() {
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                const uint32_t shared = sm.tau_blk[q];
+                const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
+                const uint32_t own = sm.ws[wave].own_ord[q];
+                tau[q] = V::from_ord(own < loose ? own : loose);
+                if (IS_U4 && q >= nvalid_q) tau[q] = 0;
+            }
+        };
+        reload_tau();
+
+        const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
+        const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
+        const int ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;          // codes of this chunk (below 2^31)
+        const int nsub = (ncodes + SUB - 1) / SUB;                         // sub-tiles, the last may be ragged
+        const int nfull = ncodes / TILE;                                   // tiles with every code present
+        const uint8_t *chunk_ptr = a.codes + cbeg * CB;
+
+        // the 16 bytes of this lane in each sub-tile of full tile t
+        auto load_full = [&](int t, uint4 (&c)[BATCH]) {
+#ifdef PQ_DBG_NOLOAD
+            t = 0;
+#endif
+            const uint8_t *p = chunk_ptr + (size_t)t * (TILE * CB) + lane * 16;
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) c[i] = *reinterpret_cast<const uint4 *>(p + i * (SUB * CB));
+        };
+        // one sub-tile past the full tiles (zeros for codes past the end of the chunk)
+        auto load_ragged = [&](int sidx) -> uint4 {
+            uint4 c = make_uint4(0, 0, 0, 0);
+            const uint8_t *p = chunk_ptr + (size_t)sidx * (SUB * CB) + lane * 16;
+            const int rem = ncodes - sidx * SUB;   // codes from the start of this sub-tile to the end of the chunk
+            if (lane * CPL + CPL <= rem) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (CPL == 2 && lane * CPL < rem) {
+                const uint2 h = *reinterpret_cast<const uint2 *>(p);
+                c.x = h.x; c.y = h.y;
+            }
+            return c;
+        };
+
+        // values of the CPL codes of this lane for the QB queries (4 accumulators per code)
+        auto compute = [&](uint4 c, val_t (&d)[CPL][NACC]) {
+            uint32_t w[4] = {c.x, c.y, c.z, c.w};
+            if constexpr (NT == 8) {
+                rot8(w[0], w[1], rot_swap, rot & 3u);
+                rot8(w[2], w[3], rot_swap, rot & 3u);
+            } else {
+                rot16(w, rot);
+            }
+#pragma unroll
+            for (int h = 0; h < CPL; ++h) {
+#pragma unroll
+                for (int s = 0; s < NT; ++s) {
+                    uint32_t off;
+                    const uint32_t word = w[h * (NT / 4) + (s >> 2)], bs = bases[s >> 2];
+                    switch (s & 3) {
+                        case 0: off = lut_offset<0>(word, bs); break;
+                        case 1: off = lut_offset<1>(word, bs); break;
+                        case 2: off = lut_offset<2>(word, bs); break;
+                        default: off = lut_offset<3>(word, bs); break;
+                    }
+                    const uint4 v = *reinterpret_cast<const uint4 *>(lut_bytes + off);
+                    if constexpr (IS_U4) {
+                        if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
+                        else { d[h][0] += v.x; d[h][1] += v.y; d[h][2] += v.z; d[h][3] += v.w; }
+                    } else {
+                        const float f0 = __uint_as_float(v.x), f1 = __uint_as_float(v.y), f2 = __uint_as_float(v.z),
+                                    f3 = __uint_as_float(v.w);
+                        if (s == 0) { d[h][0] = f0; d[h][1] = f1; d[h][2] = f2; d[h][3] = f3; }
+                        else { d[h][0] += f0; d[h][1] += f1; d[h][2] += f2; d[h][3] += f3; }
+                    }
+                }
+            }
+        };
+
+        // the wave that refreshes query my_q from the histogram, and when
+        const int my_q = wave % QB;
+        const int my_phase = 1 + 8 * my_q;
+        const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf();
+
+        int iter = 0;
+        auto process = [&](const uint4 cur, const int sidx) {
+            val_t d[CPL][NACC];
+            compute(cur, d);
+            // issue order inside the loop body: all address arithmetic, then every LDS read
+            // back to back, then the additions (the reads are independent of one another)
+            __builtin_amdgcn_sched_group_barrier(0x002, 8 + 2 * NT, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * NT * CPL / 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 8 * NT, 0);
+
+            uint64_t hit = 0;
+            if constexpr (IS_U4) {
+                // packed fields: (x | 0x8000) - tau keeps bit 15 iff x >= tau
+                uint32_t allge = 0x80008000u;
+#pragma unroll
+                for (int h = 0; h < CPL; ++h)
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp)
+                        allge &= (d[h][pp] | 0x80008000u) - (tau[2 * pp] | (tau[2 * pp + 1] << 16));
+                hit = __ballot((allge & 0x80008000u) != 0x80008000u);
+            } else {
+#ifdef PQ_DBG_MINTEST
+                bool any = false;
+#pragma unroll
+                for (int q = 0; q < QB; ++q) {
+                    float m = d[0][q];
+#pragma unroll
+                    for (int h = 1; h < CPL; ++h) m = fminf(m, d[h][q]);
+                    any |= m < tau[q];
+                }
+                hit = __ballot(any);
+#else
+#pragma unroll
+                for (int h = 0; h < CPL; ++h)
+#pragma unroll
+                    for (int q = 0; q < QB; ++q) hit |= __ballot(d[h][q] < tau[q]);
+#endif
+            }
+            bool changed = false;
+            if (hit != 0ull) {
+                // some lane has a candidate: append to the wave's lists, count in the histograms
+                const int in_chunk = sidx * SUB + lane * CPL;    // position of the lane's first code
+                const uint32_t first = (uint32_t)(cbeg + in_chunk);
+#pragma unroll
+                for (int q = 0; q < QB; ++q) {
+#pragma unroll
+                    for (int h = 0; h < CPL; ++h) {
+                        val_t x;
+                        if constexpr (IS_U4) x = (d[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                        else x = d[h][q];
+                        const bool pass = in_chunk + h < ncodes && x < tau[q];
+                        const uint64_t mask = __ballot(pass);
+                        if (mask == 0ull) continue;
+                        uint64_t *buf = wave_buf + (size_t)q * CAP;
+                        if (pass) {
+                            const uint32_t ord = V::to_ord(x);
+                            key_store(buf + cnt[q] + mask_prefix(mask), ((uint64_t)ord << 32) | (first + h));
+                            const uint32_t ref = IS_U4 ? 0u : sm.tau_ref[q];
+                            if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
+                                uint32_t bin;
+                                if (IS_U4) {
+                                    bin = ord < HIST_BINS ? ord : HIST_BINS - 1;
+                                } else {
+                                    const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                                    bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
+                                }
+                                __hip_atomic_fetch_add(&hist_q0[(size_t)q * HIST_BINS + bin], 1u, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                            }
+                        }
+                        cnt[q] += __popcll(mask);
+                        if (lane == 0)
+                            __hip_atomic_fetch_add(&ncand_q0[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (cnt[q] > CAP - 64) {
+                            cnt[q] = __builtin_amdgcn_readfirstlane(scan_compact<E, IS_U4>(&sm, buf, cnt[q], q));
+                            changed = true;
+                        }
+                    }
+                }
+            }
+            // bounds from the histogram: one wave per query and period (while the query had no
+            // bound at the start of the item: also at iterations 0, 1, 2, 4 .. 32)
+#ifndef PQ_DBG_NOREFRESH
+            const bool pow2 = cold_item && iter < 64 && (iter & (iter - 1)) == 0;
+            if (wave < QB && (pow2 || (iter & 63) == my_phase) && my_q < nvalid_q) scan_refresh<IS_U4>(&sm, my_q);
+            if (changed || iter < 64 || (iter & 7) == 7) reload_tau();
+#else
+            if (changed) reload_tau();
+#endif
+            ++iter;
+        };
+
+        // Full tiles, two register sets used in turn.  The next tile is requested only after the
+        // current one has arrived (the empty asm reads its last register), so that waiting for the
+        // current tile never waits for the one just requested; the loads are unconditional (past the
+        // last full tile they re-read it and the data is dropped).
+        if (nfull > 0) {
+            const int last_full = nfull - 1;
+            uint4 bufa[BATCH], bufb[BATCH];
+            load_full(wave < last_full ? wave : last_full, bufa);
+            for (int t = wave; t < nfull; t += 2 * TUNED_WAVES) {
+                asm volatile("" : "+v"(bufa[BATCH - 1].w) : : "memory");
+                load_full(t + TUNED_WAVES < last_full ? t + TUNED_WAVES : last_full, bufb);
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i) process(bufa[i], t * BATCH + i);
+                if (t + TUNED_WAVES >= nfull) break;
+                asm volatile("" : "+v"(bufb[BATCH - 1].w) : : "memory");
+                load_full(t + 2 * TUNED_WAVES < last_full ? t + 2 * TUNED_WAVES : last_full, bufa);
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i) process(bufb[i], (t + TUNED_WAVES) * BATCH + i);
+            }
+        }
+        // sub-tiles after the last full tile (the very last one may be ragged), dealt round-robin
+        for (int sidx = nfull * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) process(load_ragged(sidx), sidx);
+
+        // ---- end of item: merge the wave lists of each query ------------------------------------
+        if (lane == 0) {
+#pragma unroll
+            for (int q = 0; q < QB; ++q) sm.ws[wave].cnt[q] = cnt[q];
+        }
+        scan_finish_wave<QB, E>(&sm, wave_buf);
+        __threadfence();
+        __syncthreads();
+        if (wave < QB) scan_merge_item<QB, E, KPAD>(&sm, block_scratch, a.partial + ((size_t)item * QB + wave) * KPAD);
+        __syncthreads();
+    }
+}
+
+__global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_t *ncand, uint32_t *mark,
+                                  uint32_t *tau_ref, int ntau,
+                                  uint32_t tau_value, uint32_t *hist, size_t nhist) {
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    if (i0 == 0) *work_counter = 0;
+    for (size_t i = i0; i < (size_t)ntau; i += stride) { tau[i] = tau_value; ncand[i] = 0; mark[i] = 0; tau_ref[i] = TAU_REF_UNSET; }
+    for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
+}
+
+template <int KIND, int E, int KPAD>
+static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
+    if (env_int("PQ_DEBUG", 0)) {
+        int nb = -1;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, scan_tuned_kernel<KIND, E, KPAD>, TUNED_THREADS, 0);
+        fprintf(stderr, "[pq] scan_tuned kind=%d: occupancy %d blocks/CU (err %d), launching %d blocks, %d items, %d chunks\n",
+                KIND, nb, (int)e, nblocks, a.nitems, a.nchunks);
+    }
+    scan_tuned_kernel<KIND, E, KPAD><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
+                      void *out_val, int64_t *out_ids) {
+    const bool is_u4 = kind == KIND_U4_M16;
+    const int qb = is_u4 ? 8 : 4;
+    const int cb = kind == KIND_F32_M16 ? 16 : 8;
+    const int tile = 64 * (16 / cb) * 1;   // codes per wave tile (BATCH sub-tiles)
+    const bool small = topk <= 128;
+    const int kpad = small ? 128 : 1024;
+    const int cap = 2 * kpad;
+    const int ngroups = (nq + qb - 1) / qb;
+    const int64_t block_tile = (int64_t)tile * TUNED_WAVES;
+    const int nblocks_max = env_int("PQ_SCAN_BLOCKS", 2 * ctx->num_cu);
+
+    // several items per block for balance, chunks of at least 8 block tiles, merge limit 16384 keys per query
+    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 8) * nblocks_max + ngroups - 1) / ngroups;
+    const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
+    const int64_t max_by_merge = 16384 / kpad;
+    if (nchunks > max_by_n) nchunks = max_by_n;
+    if (nchunks > max_by_merge) nchunks = max_by_merge;
+    if (nchunks < 1) nchunks = 1;
+    int64_t chunk_codes = (n + nchunks - 1) / nchunks;
+    chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
+    if (chunk_codes < block_tile) chunk_codes = block_tile;
+    nchunks = n > 0 ? (n + chunk_codes - 1) / chunk_codes : 1;
+    const int64_t nitems = nchunks * ngroups;
+    if (nitems > 0x3fffffff) return fail(ctx, PQ_EUNSUPPORTED, "scan: too many work items (%lld)", (long long)nitems);
+    const int nblocks = (int)(nitems < nblocks_max ? nitems : nblocks_max);
+
+    const int ntau = ngroups * qb;
+    const size_t off_tau = 256;
+    const size_t off_ncand = off_tau + align_up((size_t)ntau * 4, 256);
+    const size_t off_mark = off_ncand + align_up((size_t)ntau * 4, 256);
+    const size_t off_ref = off_mark + align_up((size_t)ntau * 4, 256);
+    const size_t off_hist = off_ref + align_up((size_t)ntau * 4, 256);
+    const size_t nhist = (size_t)ntau * HIST_BINS;
+    const size_t off_scratch = off_hist + align_up(nhist * 4, 256);
+    const size_t off_partial = off_scratch + (size_t)nblocks * TUNED_WAVES * qb * cap * 8;
+    const size_t total = off_partial + (size_t)nitems * qb * kpad * 8;
+    int rc = ws_reserve(ctx, total);
+    if (rc) return rc;
+    uint8_t *ws = (uint8_t *)ctx->ws;
+
+    TunedArgs a;
+    a.codes = codes; a.n = n; a.chunk_codes = chunk_codes; a.nchunks = (int)nchunks; a.ngroups = ngroups;
+    a.nitems = (int)nitems; a.luts = luts; a.nq = nq; a.topk = topk;
+    a.work_counter = (uint32_t *)ws;
+    a.tau_global = (uint32_t *)(ws + off_tau);
+    a.ncand = (uint32_t *)(ws + off_ncand);
+    a.refresh_mark = (uint32_t *)(ws + off_mark);
+    a.tau_ref = (uint32_t *)(ws + off_ref);
+    a.hist = (uint32_t *)(ws + off_hist);
+    a.scratch = (uint64_t *)(ws + off_scratch);
+    a.partial = (uint64_t *)(ws + off_partial);
+
+    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
+                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, nhist);
+    PQ_HIP(ctx, hipGetLastError());
+    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    switch (kind) {
+        case KIND_F32_M8:
+            rc = small ? launch_kind<KIND_F32_M8, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024>(ctx, a, nblocks);
+            break;
+        case KIND_F32_M16:
+            rc = small ? launch_kind<KIND_F32_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024>(ctx, a, nblocks);
+            break;
+        default:
+            rc = small ? launch_kind<KIND_U4_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024>(ctx, a, nblocks);
+            break;
+    }
+    if (rc) return rc;
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
+        ctx->ev_valid = 1;
+    }
+    if (env_int("PQ_DEBUG", 0)) {
+        (void)hipStreamSynchronize(ctx->stream);
+        uint32_t *h = (uint32_t *)malloc((size_t)ntau * 4);
+        (void)hipMemcpy(h, a.ncand, (size_t)ntau * 4, hipMemcpyDeviceToHost);
+        unsigned long long sum = 0; uint32_t mx = 0;
+        for (int i = 0; i < nq; ++i) { sum += h[i]; mx = h[i] > mx ? h[i] : mx; }
+        fprintf(stderr, "[pq] insert events per query: mean %.1f max %u (n=%lld, topk=%d)\n", (double)sum / nq, mx, (long long)n, topk);
+        free(h);
+    }
+    return launch_merge_topk(ctx, a.partial, (int)nchunks, ngroups, qb, kpad, nq, topk, is_u4, out_val, out_ids);
+}
+
+}  // namespace pq

@@ -54,28 +54,57 @@ __device__ __forceinline__ uint64_t wave_select_kth(const uint64_t (&key)[E], in
 }
 
 // Keep the k smallest of buf[0..cnt) (cnt <= 64*E) in buf[0..min(cnt,k)), in no particular
-// order.  Returns the k-th smallest key (KEY_EMPTY if cnt < k) and updates cnt.
+// order.  Returns a key t with exactly min(cnt,k) keys <= t, at least the k-th smallest key
+// (KEY_EMPTY if cnt < k), and updates cnt.  Lists of up to 512 keys are held in registers;
+// longer ones are re-read from memory in every bisection step (rare path, few registers).
 template <int E>
 __device__ __forceinline__ uint64_t wave_compact(uint64_t *buf, int &cnt, int k) {
     const int lane = lane_id();
     __threadfence();  // the appends of every lane have reached the coherent level
-    uint64_t key[E];
+    if constexpr (E <= 8) {
+        uint64_t key[E];
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int idx = e * 64 + lane;
-        key[e] = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
-    }
-    const uint64_t kth = wave_select_kth<E>(key, k);
-    int base = 0;
+        for (int e = 0; e < E; ++e) {
+            const int idx = e * 64 + lane;
+            key[e] = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
+        }
+        const uint64_t kth = wave_select_kth<E>(key, k);
+        int base = 0;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const bool keep = key[e] <= kth && key[e] != KEY_EMPTY;
-        const uint64_t mask = __ballot(keep);
-        if (keep) key_store(buf + base + mask_prefix(mask), key[e]);
-        base += __popcll(mask);
+        for (int e = 0; e < E; ++e) {
+            const bool keep = key[e] <= kth && key[e] != KEY_EMPTY;
+            const uint64_t mask = __ballot(keep);
+            if (keep) key_store(buf + base + mask_prefix(mask), key[e]);
+            base += __popcll(mask);
+        }
+        cnt = base;
+        return kth;
+    } else {
+        uint64_t v = 0;
+        for (int bit = 63; bit >= 0; --bit) {
+            const uint64_t trial = v | ((1ull << bit) - 1ull);
+            int c = 0;
+            for (int e = 0; e < E; ++e) {
+                const int idx = e * 64 + lane;
+                const uint64_t key = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
+                c += __popcll(__ballot(key <= trial));
+            }
+            if (c == k) { v = trial; break; }   // exactly k keys at or below the trial: good enough
+            if (c < k) v |= (1ull << bit);
+        }
+        // in-place compaction, 64 keys per round: the write position never passes the read position
+        int base = 0;
+        for (int e = 0; e < E; ++e) {
+            const int idx = e * 64 + lane;
+            const uint64_t key = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
+            const bool keep = key <= v && key != KEY_EMPTY;
+            const uint64_t mask = __ballot(keep);
+            if (keep) key_store(buf + base + mask_prefix(mask), key);
+            base += __popcll(mask);
+        }
+        cnt = base;
+        return v;
     }
-    cnt = base;
-    return kth;
 }
 
 // Append the lanes with `pass` set to buf at position cnt (uniform).  Returns the new count.

@@ -97,8 +97,9 @@ def test_scan_config0_pq8x8(ctx):
     _, queries, cb, codes = sift_pq(8, 256, 100000, 16)
     luts_h = host(ctx.pq_build_luts(dev(queries), dev(cb)))
     gd, gi, od, oi = run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
-    # with GPU-built tables fed to both sides the id lists agree except inside rounding ties
-    assert (gi == oi).mean() > 0.98
+    # encoded data holds many identical codes: their distances tie up to the rounding of the float
+    # sum, so ids may swap inside the tolerance band, but the distance profile must match rank by rank
+    np.testing.assert_allclose(gd, od, rtol=RTOL)
 
 
 @pytest.mark.parametrize("n", [0, 1, 63, 127, 128, 129, 1023, 1025, 8191, 8193, 50001])

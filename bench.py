@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--n", type=int, default=25_000_000)
     ap.add_argument("--nq", type=int, default=1000)
     ap.add_argument("--topk", type=int, default=100)
+    ap.add_argument("--cand", type=int, default=1000, help="candidates kept by the 16x4 integer scan before the rerank")
     ap.add_argument("--cpu-queries", type=int, default=512)
     ap.add_argument("--skip-16x4", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
@@ -139,9 +140,9 @@ def main():
 
         def step16():
             luts = ctx.pq_build_luts(queries, cb16)
-            qmax = ctx.pq_qmax_prescan(codes4, fmt, luts, 2000, 1000)
+            qmax = ctx.pq_qmax_prescan(codes4, fmt, luts, 2 * args.cand, args.cand)
             qluts, _, _ = ctx.pq_quantize_luts(luts, qmax)
-            _, cand = ctx.pq_adc_scan_topk(codes4, fmt, qluts, 1000)
+            _, cand = ctx.pq_adc_scan_topk(codes4, fmt, qluts, args.cand)
             return ctx.pq_rerank_f32(codes4, fmt, luts, cand, args.topk)
 
         for _ in range(args.warmup):

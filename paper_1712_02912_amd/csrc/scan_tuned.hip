@@ -457,7 +457,7 @@ void scan_tuned_kernel(TunedArgs a) {
 #endif
             }
             bool changed = false;
-            if (hit != 0ull) {
+            if (__builtin_expect(hit != 0ull, 0)) {
                 // some lane has a candidate: append to the wave's lists, count in the histograms
                 const int in_chunk = sidx * SUB + lane * CPL;    // position of the lane's first code
                 const uint32_t first = (uint32_t)(cbeg + in_chunk);
@@ -491,7 +491,7 @@ void scan_tuned_kernel(TunedArgs a) {
                         cnt[q] += __popcll(mask);
                         if (lane == 0)
                             __hip_atomic_fetch_add(&ncand_q0[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (cnt[q] > CAP - 64) {
+                        if (__builtin_expect(cnt[q] > CAP - 64, 0)) {
                             cnt[q] = __builtin_amdgcn_readfirstlane(scan_compact<E, IS_U4>(&sm, buf, cnt[q], q));
                             changed = true;
                         }
@@ -502,7 +502,8 @@ void scan_tuned_kernel(TunedArgs a) {
             // bound at the start of the item: also at iterations 0, 1, 2, 4 .. 32)
 #ifndef PQ_DBG_NOREFRESH
             const bool pow2 = cold_item && iter < 64 && (iter & (iter - 1)) == 0;
-            if (wave < QB && (pow2 || (iter & 63) == my_phase) && my_q < nvalid_q) scan_refresh<IS_U4>(&sm, my_q);
+            if (__builtin_expect(wave < QB && (pow2 || (iter & 63) == my_phase) && my_q < nvalid_q, 0))
+                scan_refresh<IS_U4>(&sm, my_q);
             if (changed || iter < 64 || (iter & 7) == 7) reload_tau();
 #else
             if (changed) reload_tau();
@@ -558,12 +559,9 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
 
 template <int KIND, int E, int KPAD>
 static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
-    if (env_int("PQ_DEBUG", 0)) {
-        int nb = -1;
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, scan_tuned_kernel<KIND, E, KPAD>, TUNED_THREADS, 0);
-        fprintf(stderr, "[pq] scan_tuned kind=%d: occupancy %d blocks/CU (err %d), launching %d blocks, %d items, %d chunks\n",
-                KIND, nb, (int)e, nblocks, a.nitems, a.nchunks);
-    }
+    if (env_int("PQ_DEBUG", 0))
+        fprintf(stderr, "[pq] scan_tuned kind=%d: launching %d blocks, %d items, %d chunks\n", KIND, nblocks, a.nitems,
+                a.nchunks);
     scan_tuned_kernel<KIND, E, KPAD><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
@@ -580,10 +578,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int cap = 2 * kpad;
     const int ngroups = (nq + qb - 1) / qb;
     const int64_t block_tile = (int64_t)tile * TUNED_WAVES;
-    const int nblocks_max = env_int("PQ_SCAN_BLOCKS", 2 * ctx->num_cu);
+    // persistent blocks: one per CU (64 KB of tables and 16 waves of 128 registers fill a CU)
+    const int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
 
     // several items per block for balance, chunks of at least 8 block tiles, merge limit 16384 keys per query
-    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 8) * nblocks_max + ngroups - 1) / ngroups;
+    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
     const int64_t max_by_merge = 16384 / kpad;
     if (nchunks > max_by_n) nchunks = max_by_n;

@@ -15,6 +15,16 @@ constexpr int HIST_BINS = 1 << HIST_BITS;
 constexpr int HIST_SHIFT = 14;             // float path: bin width in units of the ordered value
 constexpr uint32_t TAU_REF_UNSET = 0xffffffffu;
 
+// One work item of the IVF search: a chunk of one inverted list for up to QB of the queries
+// that probe the list.
+struct IvfItem {
+    uint32_t code_begin;   // first row of the chunk, rounded down to a 16-byte boundary
+    uint32_t ncodes;       // rows from code_begin to the end of the chunk
+    uint32_t pair_pos;     // position in pairs_by_list of the item's first (query, list) pair
+    uint32_t skip_slots_chunk;   // bits 0-7: rows at the front that belong to the previous list,
+                                 // bits 8-15: number of pairs (slots), bits 16-31: chunk index in the list
+};
+
 struct TunedArgs {
     const uint8_t *codes;
     int64_t n;
@@ -32,7 +42,13 @@ struct TunedArgs {
     uint32_t *tau_ref;       // [ngroups*QB] reference value of the histogram bins (float path), UNSET at first
     uint32_t *hist;          // [ngroups*QB][HIST_BINS] values of the candidates inserted
     uint64_t *scratch;       // [nblocks][TUNED_WAVES][QB][CAP]
-    uint64_t *partial;       // [nitems][QB][KPAD]
+    uint64_t *partial;       // [nitems][QB][KPAD]; IVF: [number of (pair, chunk) lists][KPAD]
+    // IVF mode (item_tab != nullptr): items come from a table, every slot has its own tables
+    const IvfItem *item_tab;
+    const uint32_t *nitems_dev;      // number of items, computed on the device
+    const int32_t *pairs_by_list;    // pair = query * nprobe + rank, grouped by list
+    const uint32_t *pair_out;        // [npairs] index of the pair's first output list
+    int nprobe;
 };
 
 static inline int env_int(const char *name, int dflt) {

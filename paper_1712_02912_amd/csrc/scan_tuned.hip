@@ -42,22 +42,40 @@ struct WaveState {
     uint32_t own_ord[8];   // k-th smallest value of the wave's own list, ord_inf while not full
 };
 
+constexpr int RING_CAP = 96;      // entries per wave
+constexpr int RING_FLUSH = 32;    // flush when more than this many are parked (64 more always fit)
+constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
+
 struct __align__(16) TunedSmem {
     uint4 lut[4096];
     uint8_t qstage[8][256];
     WaveState ws[TUNED_WAVES];
+    // Per wave: lanes that found a candidate park their accumulators here; the entries are turned
+    // into list inserts in batches (scan_flush).  Entry = 8 accumulators + position of the lane's
+    // first code in the item (+ 3 words of padding: 48 bytes, 16-byte aligned).
+    uint32_t ring[TUNED_WAVES][RING_CAP][12];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
     uint32_t tau_ref[8];   // histogram reference per query (float path)
-    // per item, written by thread 0
-    uint32_t *hist;        // histogram of query 0 of the group
-    uint32_t *ncand;
-    uint32_t *refresh_mark;
-    uint32_t *tau_global;
-    uint32_t *tau_ref_global;
+    // per item, written at its start: where the state of the query in each slot lives
+    uint32_t *hist[8];
+    uint32_t *ncand[8];
+    uint32_t *refresh_mark[8];
+    uint32_t *tau_global[8];
+    uint32_t *tau_ref_global[8];
+    const void *slot_lut[8];   // tables of the slot's query (nullptr: empty slot)
+    uint64_t *slot_out[8];     // where the slot's KPAD result keys go
+    int64_t code_begin;        // first row scanned by the item
+    int ncodes;                // rows scanned
+    int skip;                  // leading rows that are not part of the item
     int nvalid;            // queries of the group that exist
     int topk;
     int item;
 };
+
+// The helpers below are real functions (kept out of line so that their registers do not weigh on
+// the scan loop); they address the block's shared structure through an LDS-qualified pointer.
+typedef __attribute__((address_space(3))) TunedSmem LdsSmem;
+typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 // rotate the bytes of a 64-bit code right by r bytes (r in 0..7): byte s of the result is
 // byte (s + r) & 7 of the input
@@ -127,17 +145,17 @@ __device__ __forceinline__ int hist_threshold(const uint32_t *hist, int k) {
 
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2 };
 
-__device__ __forceinline__ void publish_bound(TunedSmem *sm, int q, uint32_t ord) {
-    atomicMin(&sm->tau_blk[q], ord);
-    atomicMin(&sm->tau_global[q], ord);
+__device__ __forceinline__ void publish_bound(LdsSmem *sm, int q, uint32_t ord) {
+    __hip_atomic_fetch_min(&sm->tau_blk[q], ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    atomicMin(sm->tau_global[q], ord);
 }
 
 // Rare path of the scan loop: the candidate list of query q of this wave is nearly full.  Keep
 // its k smallest keys, make the k-th the wave's own bound and share it.  Returns the new count.
 template <int E, bool IS_U4>
-__device__ __noinline__ int scan_compact(TunedSmem *sm, uint64_t *buf, int cnt, int q) {
+__device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, int q) {
     const int lane = lane_id();
-    WaveState *ws = &sm->ws[threadIdx.x >> 6];
+    LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     const uint64_t kth = wave_compact<E>(buf, cnt, sm->topk);
     if (kth != KEY_EMPTY) {
         const uint32_t kord = (uint32_t)(kth >> 32);
@@ -146,7 +164,7 @@ __device__ __noinline__ int scan_compact(TunedSmem *sm, uint64_t *buf, int cnt, 
         if (!IS_U4 && sm->tau_ref[q] == TAU_REF_UNSET) {
             // the first bound published for a query becomes the reference of its histogram
             uint32_t expected = TAU_REF_UNSET;
-            __hip_atomic_compare_exchange_strong(&sm->tau_ref_global[q], &expected, kord, __ATOMIC_RELAXED,
+            __hip_atomic_compare_exchange_strong(sm->tau_ref_global[q], &expected, kord, __ATOMIC_RELAXED,
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const uint32_t now = expected == TAU_REF_UNSET ? kord : expected;
             if (lane == 0) sm->tau_ref[q] = now;
@@ -155,37 +173,108 @@ __device__ __noinline__ int scan_compact(TunedSmem *sm, uint64_t *buf, int cnt, 
     return cnt;
 }
 
+// Rare path of the scan loop: turn the `n` entries parked in the wave's ring into list inserts.
+// Lane e takes entry e (64 at a time).  For every query the candidates (value below the current
+// bound) are appended to the wave's list and counted in the query's histogram; a list that is
+// nearly full is compacted.  Entries are in scan order, so ids still reach a list in increasing order.
+template <class V, int QB, int E, int CPL, bool IS_U4>
+__device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) {
+    constexpr int CAP = 64 * E;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    LdsWaveState *ws = &sm->ws[wave];
+    const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
+    const uint32_t row0 = (uint32_t)sm->code_begin;
+    for (int base = 0; base < n; base += 64) {
+        const bool have = base + lane < n;
+        uint32_t acc[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        int pos = 0;
+        if (have) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[0][i] = sm->ring[wave][base + lane][i];
+                acc[1][i] = sm->ring[wave][base + lane][4 + i];
+            }
+            pos = (int)sm->ring[wave][base + lane][8];
+        }
+#pragma unroll 1
+        for (int q = 0; q < nvalid; ++q) {
+            // candidates satisfy value < eff: the wave's own bound is strict, the block's is "<="
+            const uint32_t shared = sm->tau_blk[q];
+            const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
+            const uint32_t own = ws->own_ord[q];
+            const uint32_t eff = own < loose ? own : loose;
+            uint64_t *buf = wave_buf + (size_t)q * CAP;
+            const uint32_t ref = IS_U4 ? 0u : sm->tau_ref[q];
+#pragma unroll
+            for (int h = 0; h < CPL; ++h) {
+                uint32_t ord;
+                if constexpr (IS_U4) {
+                    const int p = q >> 1;
+                    const uint32_t pk = p == 0 ? acc[h][0] : p == 1 ? acc[h][1] : p == 2 ? acc[h][2] : acc[h][3];
+                    ord = (pk >> (16 * (q & 1))) & 0xffffu;
+                } else {
+                    const uint32_t bits = q == 0 ? acc[h][0] : q == 1 ? acc[h][1] : q == 2 ? acc[h][2] : acc[h][3];
+                    ord = V::to_ord(__uint_as_float(bits));
+                }
+                const bool pass = have && pos + h >= skip && pos + h < ncodes && ord < eff;
+                const uint64_t mask = __ballot(pass);
+                if (mask == 0ull) continue;
+                int cnt = ws->cnt[q];
+                if (pass) {
+                    key_store(buf + cnt + mask_prefix(mask), ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
+                    if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
+                        uint32_t bin;
+                        if (IS_U4) {
+                            bin = ord < HIST_BINS ? ord : HIST_BINS - 1;
+                        } else {
+                            const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                            bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
+                        }
+                        __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                }
+                cnt += __popcll(mask);
+                if (cnt > CAP - 64) cnt = scan_compact<E, IS_U4>(sm, buf, cnt, q);
+                if (lane == 0) {
+                    ws->cnt[q] = cnt;
+                    __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)__popcll(mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+    }
+}
+
 // Periodic path (one wave per query and period): pick up the best bound published for query q
 // by any block and, if enough candidates arrived since the histogram was last evaluated and no
 // other wave is already doing it, recompute the bound from the histogram.
 constexpr uint32_t REFRESH_MIN_NEW = 16;
 template <bool IS_U4>
-__device__ __noinline__ void scan_refresh(TunedSmem *sm, int q) {
-    const uint32_t g = __hip_atomic_load(&sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane_id() == 0) atomicMin(&sm->tau_blk[q], g);
+__device__ __noinline__ void scan_refresh(LdsSmem *sm, int q) {
+    const uint32_t g = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane_id() == 0) __hip_atomic_fetch_min(&sm->tau_blk[q], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     uint32_t ref = 0;
     if (!IS_U4) {
         ref = __builtin_amdgcn_readfirstlane(sm->tau_ref[q]);
         if (ref == TAU_REF_UNSET) {
             ref = __builtin_amdgcn_readfirstlane(
-                __hip_atomic_load(&sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                __hip_atomic_load(sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
             if (ref == TAU_REF_UNSET) return;
             if (lane_id() == 0) sm->tau_ref[q] = ref;
         }
     }
     const uint32_t n = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(&sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        __hip_atomic_load(sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     const uint32_t mark = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(&sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        __hip_atomic_load(sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     if (n - mark < REFRESH_MIN_NEW) return;
     uint32_t won = 0;
     if (lane_id() == 0) {
         uint32_t expected = mark;
-        won = __hip_atomic_compare_exchange_strong(&sm->refresh_mark[q], &expected, n, __ATOMIC_RELAXED,
+        won = __hip_atomic_compare_exchange_strong(sm->refresh_mark[q], &expected, n, __ATOMIC_RELAXED,
                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ? 1u : 0u;
     }
     if (__builtin_amdgcn_readfirstlane(won) == 0u) return;
-    const int bin = hist_threshold(sm->hist + (size_t)q * HIST_BINS, sm->topk);
+    const int bin = hist_threshold(sm->hist[q], sm->topk);
     if (bin < HIST_BINS) {
         // every value counted in bins <= bin is at or below this edge
         const uint32_t edge = IS_U4 ? (uint32_t)bin : ref - ((uint32_t)(HIST_BINS - 1 - bin) << HIST_SHIFT);
@@ -195,9 +284,9 @@ __device__ __noinline__ void scan_refresh(TunedSmem *sm, int q) {
 
 // End of item, per wave: leave at most k keys in every list.
 template <int QB, int E>
-__device__ __noinline__ void scan_finish_wave(TunedSmem *sm, uint64_t *wave_buf) {
+__device__ __noinline__ void scan_finish_wave(LdsSmem *sm, uint64_t *wave_buf) {
     constexpr int CAP = 64 * E;
-    WaveState *ws = &sm->ws[threadIdx.x >> 6];
+    LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     for (int q = 0; q < QB; ++q) {
         int cnt = ws->cnt[q];
         if (cnt > sm->topk) {
@@ -210,7 +299,7 @@ __device__ __noinline__ void scan_finish_wave(TunedSmem *sm, uint64_t *wave_buf)
 // End of item, wave q < QB: fold the lists of all waves for query q into the list of wave 0
 // and write KPAD keys (padded with KEY_EMPTY) to out.
 template <int QB, int E, int KPAD>
-__device__ __noinline__ void scan_merge_item(TunedSmem *sm, uint64_t *block_scratch, uint64_t *out) {
+__device__ __noinline__ void scan_merge_item(LdsSmem *sm, uint64_t *block_scratch, uint64_t *out) {
     constexpr int CAP = 64 * E;
     const int q = threadIdx.x >> 6, lane = lane_id();
     const int k = sm->topk;
@@ -262,24 +351,76 @@ void scan_tuned_kernel(TunedArgs a) {
     uint64_t *block_scratch = a.scratch + (size_t)blockIdx.x * TUNED_WAVES * QB * CAP;
     uint64_t *wave_buf = block_scratch + (size_t)wave * QB * CAP;
 
+    const int nitems = a.item_tab ? (int)*a.nitems_dev : a.nitems;
     for (;;) {
         if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
         __syncthreads();
         const int item = sm.item;
-        if (item >= a.nitems) break;
-        const int group = item % a.ngroups;
-        const int chunk = item / a.ngroups;
+        if (item >= nitems) break;
 
-        // ---- stage the tables of the group's queries --------------------------------------
+        // ---- describe the item: rows to scan, and for every slot the query whose tables it holds ----
+        if (threadIdx.x < QB) {
+            const int s = threadIdx.x;
+            int qid = -1;                  // index of the query's threshold state, -1: empty slot
+            const void *lut = nullptr;
+            uint64_t *out = nullptr;
+            if (a.item_tab) {
+                const IvfItem it = a.item_tab[item];
+                const int nslots = (it.skip_slots_chunk >> 8) & 0xff;
+                if (s < nslots) {
+                    const int pair = a.pairs_by_list[it.pair_pos + s];
+                    qid = pair / a.nprobe;
+                    lut = (const float *)a.luts + (size_t)pair * (NT * 256);
+                    out = a.partial + ((size_t)a.pair_out[pair] + (it.skip_slots_chunk >> 16)) * KPAD;
+                }
+                if (s == 0) {
+                    sm.code_begin = it.code_begin;
+                    sm.ncodes = (int)it.ncodes;
+                    sm.skip = it.skip_slots_chunk & 0xff;
+                    sm.nvalid = nslots;
+                }
+            } else {
+                const int group = item % a.ngroups, chunk = item / a.ngroups;
+                const int gq = group * QB + s;
+                if (gq < a.nq) {
+                    qid = gq;
+                    lut = IS_U4 ? (const void *)((const uint8_t *)a.luts + (size_t)gq * 256)
+                                : (const void *)((const float *)a.luts + (size_t)gq * (NT * 256));
+                }
+                out = a.partial + ((size_t)item * QB + s) * KPAD;
+                if (s == 0) {
+                    const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
+                    const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
+                    sm.code_begin = cbeg;
+                    sm.ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;
+                    sm.skip = 0;
+                    sm.nvalid = a.nq - group * QB < QB ? a.nq - group * QB : QB;
+                }
+            }
+            const int sq = qid < 0 ? 0 : qid;
+            sm.slot_lut[s] = lut;
+            sm.slot_out[s] = out;
+            sm.hist[s] = a.hist + (size_t)sq * HIST_BINS;
+            sm.ncand[s] = a.ncand + sq;
+            sm.refresh_mark[s] = a.refresh_mark + sq;
+            sm.tau_global[s] = a.tau_global + sq;
+            sm.tau_ref_global[s] = a.tau_ref + sq;
+            sm.tau_blk[s] = qid < 0 ? 0u : __hip_atomic_load(&a.tau_global[sq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sm.tau_ref[s] = __hip_atomic_load(&a.tau_ref[sq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (s == 0) sm.topk = a.topk;
+        }
+        if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
+        __syncthreads();
+
+        // ---- stage the tables of the slots' queries -----------------------------------------------
         if constexpr (!IS_U4) {
-            const float *luts = (const float *)a.luts;
             for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
                 const int j = e >> 8, byte = e & 255;
                 float v[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int gq = group * QB + q;
-                    v[q] = gq < a.nq ? luts[(size_t)gq * (NT * 256) + e] : __builtin_inff();
+                    const float *lut = (const float *)sm.slot_lut[q];
+                    v[q] = lut ? lut[e] : __builtin_inff();   // empty slots never qualify
                 }
                 const uint4 pk = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
                                             __float_as_uint(v[3]));
@@ -287,10 +428,10 @@ void scan_tuned_kernel(TunedArgs a) {
                 else sm.lut[byte * 16 + j] = pk;
             }
         } else {
-            const uint8_t *ql = (const uint8_t *)a.luts;
             for (int e = threadIdx.x; e < QB * 256; e += TUNED_THREADS) {
-                const int q = e >> 8, gq = group * QB + q;
-                sm.qstage[q][e & 255] = gq < a.nq ? ql[(size_t)gq * 256 + (e & 255)] : 0;
+                const int q = e >> 8;
+                const uint8_t *ql = (const uint8_t *)sm.slot_lut[q];
+                sm.qstage[q][e & 255] = ql ? ql[e & 255] : 0;
             }
             __syncthreads();
             // pair-merged tables: T[r][byte] = Q[2r][byte & 15] + Q[2r+1][byte >> 4]
@@ -299,10 +440,9 @@ void scan_tuned_kernel(TunedArgs a) {
                 uint32_t s[8];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
-                    const int gq = group * QB + q;
-                    s[q] = gq < a.nq ? (uint32_t)sm.qstage[q][(2 * r) * 16 + (byte & 15)] +
-                                           (uint32_t)sm.qstage[q][(2 * r + 1) * 16 + (byte >> 4)]
-                                     : 0x0fffu;   // padded queries never qualify
+                    s[q] = sm.slot_lut[q] ? (uint32_t)sm.qstage[q][(2 * r) * 16 + (byte & 15)] +
+                                                (uint32_t)sm.qstage[q][(2 * r + 1) * 16 + (byte >> 4)]
+                                          : 0x0fffu;   // empty slots never qualify
                 }
                 const uint4 pk = make_uint4(s[0] | (s[1] << 16), s[2] | (s[3] << 16), s[4] | (s[5] << 16),
                                             s[6] | (s[7] << 16));
@@ -310,30 +450,10 @@ void scan_tuned_kernel(TunedArgs a) {
                 sm.lut[byte * 16 + 2 * r + 1] = pk;
             }
         }
-        if (threadIdx.x < QB) {
-            sm.tau_blk[threadIdx.x] = __hip_atomic_load(&a.tau_global[group * QB + threadIdx.x], __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-            sm.tau_ref[threadIdx.x] = __hip_atomic_load(&a.tau_ref[group * QB + threadIdx.x], __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (threadIdx.x == 0) {
-            sm.hist = a.hist + (size_t)group * QB * HIST_BINS;
-            sm.ncand = a.ncand + group * QB;
-            sm.refresh_mark = a.refresh_mark + group * QB;
-            sm.tau_global = a.tau_global + group * QB;
-            sm.tau_ref_global = a.tau_ref + group * QB;
-            sm.nvalid = a.nq - group * QB < QB ? a.nq - group * QB : QB;
-            sm.topk = a.topk;
-        }
-        if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
         __syncthreads();
 
         const int nvalid_q = sm.nvalid;
-        uint32_t *const hist_q0 = a.hist + (size_t)group * QB * HIST_BINS;
-        uint32_t *const ncand_q0 = a.ncand + group * QB;
-        int cnt[QB];                       // length of this wave's candidate list per query (uniform)
-#pragma unroll
-        for (int q = 0; q < QB; ++q) cnt[q] = 0;
+        int ring_cnt = 0;                  // entries parked in this wave's ring (uniform)
         // thresholds in registers: a code is a candidate for query q if value < tau[q]
         val_t tau[QB];
         auto reload_tau = [&]() {
@@ -348,18 +468,14 @@ void scan_tuned_kernel(TunedArgs a) {
         };
         reload_tau();
 
-        const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
-        const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
-        const int ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;          // codes of this chunk (below 2^31)
+        const int64_t cbeg = sm.code_begin;
+        const int ncodes = sm.ncodes;                                      // rows of this item (below 2^31)
         const int nsub = (ncodes + SUB - 1) / SUB;                         // sub-tiles, the last may be ragged
         const int nfull = ncodes / TILE;                                   // tiles with every code present
         const uint8_t *chunk_ptr = a.codes + cbeg * CB;
 
         // the 16 bytes of this lane in each sub-tile of full tile t
         auto load_full = [&](int t, uint4 (&c)[BATCH]) {
-#ifdef PQ_DBG_NOLOAD
-            t = 0;
-#endif
             const uint8_t *p = chunk_ptr + (size_t)t * (TILE * CB) + lane * 16;
 #pragma unroll
             for (int i = 0; i < BATCH; ++i) c[i] = *reinterpret_cast<const uint4 *>(p + i * (SUB * CB));
@@ -439,75 +555,40 @@ void scan_tuned_kernel(TunedArgs a) {
                         allge &= (d[h][pp] | 0x80008000u) - (tau[2 * pp] | (tau[2 * pp + 1] << 16));
                 hit = __ballot((allge & 0x80008000u) != 0x80008000u);
             } else {
-#ifdef PQ_DBG_MINTEST
-                bool any = false;
-#pragma unroll
-                for (int q = 0; q < QB; ++q) {
-                    float m = d[0][q];
-#pragma unroll
-                    for (int h = 1; h < CPL; ++h) m = fminf(m, d[h][q]);
-                    any |= m < tau[q];
-                }
-                hit = __ballot(any);
-#else
 #pragma unroll
                 for (int h = 0; h < CPL; ++h)
 #pragma unroll
                     for (int q = 0; q < QB; ++q) hit |= __ballot(d[h][q] < tau[q]);
-#endif
             }
             bool changed = false;
             if (__builtin_expect(hit != 0ull, 0)) {
-                // some lane has a candidate: append to the wave's lists, count in the histograms
-                const int in_chunk = sidx * SUB + lane * CPL;    // position of the lane's first code
-                const uint32_t first = (uint32_t)(cbeg + in_chunk);
-#pragma unroll
-                for (int q = 0; q < QB; ++q) {
-#pragma unroll
-                    for (int h = 0; h < CPL; ++h) {
-                        val_t x;
-                        if constexpr (IS_U4) x = (d[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                        else x = d[h][q];
-                        const bool pass = in_chunk + h < ncodes && x < tau[q];
-                        const uint64_t mask = __ballot(pass);
-                        if (mask == 0ull) continue;
-                        uint64_t *buf = wave_buf + (size_t)q * CAP;
-                        if (pass) {
-                            const uint32_t ord = V::to_ord(x);
-                            key_store(buf + cnt[q] + mask_prefix(mask), ((uint64_t)ord << 32) | (first + h));
-                            const uint32_t ref = IS_U4 ? 0u : sm.tau_ref[q];
-                            if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
-                                uint32_t bin;
-                                if (IS_U4) {
-                                    bin = ord < HIST_BINS ? ord : HIST_BINS - 1;
-                                } else {
-                                    const uint32_t below = (ref - ord) >> HIST_SHIFT;
-                                    bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
-                                }
-                                __hip_atomic_fetch_add(&hist_q0[(size_t)q * HIST_BINS + bin], 1u, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-                            }
-                        }
-                        cnt[q] += __popcll(mask);
-                        if (lane == 0)
-                            __hip_atomic_fetch_add(&ncand_q0[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if (__builtin_expect(cnt[q] > CAP - 64, 0)) {
-                            cnt[q] = __builtin_amdgcn_readfirstlane(scan_compact<E, IS_U4>(&sm, buf, cnt[q], q));
-                            changed = true;
-                        }
+                // park the accumulators of the lanes that have a candidate
+                if ((hit >> lane) & 1ull) {
+                    uint4 *e = reinterpret_cast<uint4 *>(sm.ring[wave][ring_cnt + mask_prefix(hit)]);
+                    if constexpr (IS_U4) {
+                        e[0] = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
+                        e[1] = make_uint4(d[CPL - 1][0], d[CPL - 1][1], d[CPL - 1][2], d[CPL - 1][3]);
+                    } else {
+                        e[0] = make_uint4(__float_as_uint(d[0][0]), __float_as_uint(d[0][1]), __float_as_uint(d[0][2]),
+                                          __float_as_uint(d[0][3]));
+                        e[1] = make_uint4(__float_as_uint(d[CPL - 1][0]), __float_as_uint(d[CPL - 1][1]),
+                                          __float_as_uint(d[CPL - 1][2]), __float_as_uint(d[CPL - 1][3]));
                     }
+                    e[2] = make_uint4((uint32_t)(sidx * SUB + lane * CPL), 0u, 0u, 0u);
                 }
+                ring_cnt += __popcll(hit);
+            }
+            if (__builtin_expect(ring_cnt > RING_FLUSH || (ring_cnt > 0 && (iter & (RING_PERIOD - 1)) == RING_PERIOD - 1), 0)) {
+                scan_flush<V, QB, E, CPL, IS_U4>((LdsSmem *)&sm, wave_buf, ring_cnt);
+                ring_cnt = 0;
+                changed = true;
             }
             // bounds from the histogram: one wave per query and period (while the query had no
             // bound at the start of the item: also at iterations 0, 1, 2, 4 .. 32)
-#ifndef PQ_DBG_NOREFRESH
             const bool pow2 = cold_item && iter < 64 && (iter & (iter - 1)) == 0;
             if (__builtin_expect(wave < QB && (pow2 || (iter & 63) == my_phase) && my_q < nvalid_q, 0))
-                scan_refresh<IS_U4>(&sm, my_q);
+                scan_refresh<IS_U4>((LdsSmem *)&sm, my_q);
             if (changed || iter < 64 || (iter & 7) == 7) reload_tau();
-#else
-            if (changed) reload_tau();
-#endif
             ++iter;
         };
 
@@ -535,14 +616,11 @@ void scan_tuned_kernel(TunedArgs a) {
         for (int sidx = nfull * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) process(load_ragged(sidx), sidx);
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
-        if (lane == 0) {
-#pragma unroll
-            for (int q = 0; q < QB; ++q) sm.ws[wave].cnt[q] = cnt[q];
-        }
-        scan_finish_wave<QB, E>(&sm, wave_buf);
+        if (ring_cnt > 0) scan_flush<V, QB, E, CPL, IS_U4>((LdsSmem *)&sm, wave_buf, ring_cnt);
+        scan_finish_wave<QB, E>((LdsSmem *)&sm, wave_buf);
         __threadfence();
         __syncthreads();
-        if (wave < QB) scan_merge_item<QB, E, KPAD>(&sm, block_scratch, a.partial + ((size_t)item * QB + wave) * KPAD);
+        if (wave < QB && sm.slot_out[wave] != nullptr) scan_merge_item<QB, E, KPAD>((LdsSmem *)&sm, block_scratch, sm.slot_out[wave]);
         __syncthreads();
     }
 }
@@ -621,6 +699,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     a.hist = (uint32_t *)(ws + off_hist);
     a.scratch = (uint64_t *)(ws + off_scratch);
     a.partial = (uint64_t *)(ws + off_partial);
+    a.item_tab = nullptr; a.nitems_dev = nullptr; a.pairs_by_list = nullptr; a.pair_out = nullptr; a.nprobe = 0;
 
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
                                                      is_u4 ? 0x7fffu : 0xff800000u, a.hist, nhist);

@@ -1,11 +1,439 @@
 // IVFADC search (Section 2.3.2; Index, Tables and Scan steps of Section 2.3.3).
+//
+// Per batch of queries:
+//   Index   distances from every query to the nlist coarse centroids (the Tables kernel with
+//           one "sub-space" covering all d dimensions), then the nprobe smallest (distance,
+//           list id) per query by a histogram select;
+//   Tables  residual y - centroid_l for each (query, probed list) pair and its m tables,
+//           Eq. (tables), materialised in the workspace;
+//   Scan    the pairs are grouped by list, every list is cut into chunks, and one work item
+//           = one chunk x up to 4 of the queries probing that list.  Items are ordered by
+//           list size class (largest first) and run by the persistent scan kernel; each
+//           (pair, chunk) leaves a list of k keys, and a merge kernel picks the k best of all
+//           lists of a query.  Bounds and candidate histograms are per query, so what one
+//           list establishes prunes the other lists of the same query.
+// Everything is sized from upper bounds, so the call enqueues without reading back from the
+// device.
 #include "pq_internal.h"
+#include "scan_common.h"
+#include "topk_device.h"
 
 namespace pq {
 
-int launch_ivf(pq_ctx *ctx, const ivf_lists *, const float *, int, int, int, const float *, int, int, int, float *,
-               int64_t *, int32_t *) {
-    return fail(ctx, PQ_EUNSUPPORTED, "ivf_adc_search: not built yet");
+constexpr int IVF_MAX_CHUNKS = 16;            // chunks per list (bounds the lists a query can own)
+constexpr int64_t IVF_CHUNK_TARGET = 1 << 18; // rows per chunk aimed at for long lists
+constexpr int IVF_QB = 4;                     // queries per work item (float tables)
+
+// ------------------------------------------------------------------------------------------
+// nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.
+// Histogram of the top 12 bits of the ordered value -> bin holding the nprobe-th; everything
+// in lower bins and in that bin is sorted in LDS.  If that is too much (heavy ties), bisection
+// on the 64-bit key over the whole row.
+constexpr int SEL_CAP = 4096;
+__global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__restrict__ dist, int nlist,
+                                                                int nprobe, int32_t *__restrict__ probes,
+                                                                int32_t *probe_out) {
+    __shared__ uint32_t hist[4096];
+    __shared__ uint64_t cand[SEL_CAP];
+    __shared__ uint32_t part[256];
+    __shared__ int s_bin, s_count;
+    __shared__ unsigned long long s_kth;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const float *row = dist + (size_t)q * nlist;
+    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+    if (tid == 0) { s_bin = 4095; s_count = 0; }
+    __syncthreads();
+    for (int i = tid; i < nlist; i += 256) atomicAdd(&hist[f32_to_ord(row[i]) >> 20], 1u);
+    __syncthreads();
+    // thread t owns bins 16t .. 16t+15
+    uint32_t mine = 0;
+    for (int b = 0; b < 16; ++b) mine += hist[tid * 16 + b];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cum = 0;
+        int t = 0;
+        for (; t < 256; ++t) { if (cum + part[t] >= (uint32_t)nprobe) break; cum += part[t]; }
+        int b = t * 16;
+        for (; b < t * 16 + 16 && b < 4096; ++b) { if (cum + hist[b] >= (uint32_t)nprobe) break; cum += hist[b]; }
+        s_bin = b < 4096 ? b : 4095;
+    }
+    __syncthreads();
+    const uint32_t bin = (uint32_t)s_bin;
+    for (int i = tid; i < nlist; i += 256) {
+        const uint32_t o = f32_to_ord(row[i]);
+        if ((o >> 20) <= bin) {
+            const int pos = atomicAdd(&s_count, 1);
+            if (pos < SEL_CAP) cand[pos] = ((uint64_t)o << 32) | (uint32_t)i;
+        }
+    }
+    __syncthreads();
+    int total = s_count;
+    if (total > SEL_CAP) {
+        // bisection: smallest key v with count(key <= v) >= nprobe
+        uint64_t v = 0;
+        for (int bit = 63; bit >= 0; --bit) {
+            const uint64_t trial = v | ((1ull << bit) - 1ull);
+            __syncthreads();
+            if (tid == 0) s_count = 0;
+            __syncthreads();
+            int c = 0;
+            for (int i = tid; i < nlist; i += 256) c += ((((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i) <= trial) ? 1 : 0;
+            atomicAdd(&s_count, c);
+            __syncthreads();
+            if (s_count < nprobe) v |= (1ull << bit);
+        }
+        __syncthreads();
+        if (tid == 0) { s_kth = v; s_count = 0; }
+        __syncthreads();
+        const uint64_t kth = s_kth;
+        for (int i = tid; i < nlist; i += 256) {
+            const uint64_t key = ((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i;
+            if (key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < SEL_CAP) cand[pos] = key; }
+        }
+        __syncthreads();
+        total = s_count;   // exactly nprobe (keys are unique)
+    }
+    int n2 = 64;
+    while (n2 < total) n2 <<= 1;
+    for (int i = total + tid; i < n2; i += 256) cand[i] = KEY_EMPTY;
+    block_bitonic_sort(cand, n2);
+    for (int r = tid; r < nprobe; r += 256) {
+        const int32_t l = (int32_t)(uint32_t)cand[r];
+        probes[(size_t)q * nprobe + r] = l;
+        if (probe_out) probe_out[(size_t)q * nprobe + r] = l;
+    }
+}
+
+// residual of query q for its r-th probed list: y - centroid (float)
+__global__ __launch_bounds__(256) void ivf_residual_kernel(const float *__restrict__ queries,
+                                                           const float *__restrict__ coarse,
+                                                           const int32_t *__restrict__ probes, int npairs, int nprobe,
+                                                           int d, float *__restrict__ resid) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)npairs * d) return;
+    const int p = (int)(i / d), t = (int)(i % d);
+    const int q = p / nprobe, l = probes[p];
+    resid[i] = queries[(size_t)q * d + t] - coarse[(size_t)l * d + t];
+}
+
+__global__ void ivf_zero_kernel(uint32_t *p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0;
+}
+
+__global__ void ivf_count_pairs_kernel(const int32_t *__restrict__ probes, int npairs, uint32_t *np) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < npairs) atomicAdd(&np[probes[p]], 1u);
+}
+
+__device__ __forceinline__ int ivf_chunks_of(int64_t size) {
+    if (size <= 0) return 0;
+    int64_t nc = (size + IVF_CHUNK_TARGET - 1) / IVF_CHUNK_TARGET;
+    return (int)(nc < 1 ? 1 : (nc > IVF_MAX_CHUNKS ? IVF_MAX_CHUNKS : nc));
+}
+
+// Single block.  From the number of pairs per list: where each list's pairs start
+// (pair_off), how many chunks it is cut into (nc), where its items start in the item table
+// (item_off; lists of a larger size class come first) and the number of items.
+__global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restrict__ np,
+                                                        const int64_t *__restrict__ list_offsets, int nlist,
+                                                        uint32_t *pair_off, uint32_t *nc_out, uint32_t *item_off,
+                                                        uint32_t *nitems_dev) {
+    __shared__ uint32_t scan[1024];
+    __shared__ uint32_t cls_items[32], cls_base[32], cls_cursor[32];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x;
+    if (tid < 32) { cls_items[tid] = 0; cls_cursor[tid] = 0; }
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int l0 = 0; l0 < nlist; l0 += 1024) {
+        const int l = l0 + tid;
+        const uint32_t v = l < nlist ? np[l] : 0u;
+        scan[tid] = v;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {
+            const uint32_t add = tid >= o ? scan[tid - o] : 0u;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        if (l < nlist) {
+            pair_off[l] = carry + scan[tid] - v;
+            const int64_t size = list_offsets[l + 1] - list_offsets[l];
+            const int nc = v > 0 ? ivf_chunks_of(size) : 0;
+            nc_out[l] = (uint32_t)nc;
+            const uint32_t items = ((v + IVF_QB - 1) / IVF_QB) * (uint32_t)nc;
+            if (items > 0) atomicAdd(&cls_items[63 - __builtin_clzll((unsigned long long)size)], items);
+        }
+        __syncthreads();
+        if (tid == 1023) carry += scan[1023];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        pair_off[nlist] = carry;
+        uint32_t run = 0;
+        for (int c = 31; c >= 0; --c) { cls_base[c] = run; run += cls_items[c]; }
+        *nitems_dev = run;
+    }
+    __syncthreads();
+    for (int l = tid; l < nlist; l += 1024) {
+        const uint32_t v = np[l];
+        const uint32_t items = ((v + IVF_QB - 1) / IVF_QB) * nc_out[l];
+        if (items > 0) {
+            const int64_t size = list_offsets[l + 1] - list_offsets[l];
+            const int c = 63 - __builtin_clzll((unsigned long long)size);
+            item_off[l] = cls_base[c] + atomicAdd(&cls_cursor[c], items);
+        } else {
+            item_off[l] = 0;
+        }
+    }
+}
+
+__global__ void ivf_fill_pairs_kernel(const int32_t *__restrict__ probes, int npairs,
+                                      const uint32_t *__restrict__ pair_off, uint32_t *fill, int32_t *pairs_by_list) {
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= npairs) return;
+    const int l = probes[p];
+    pairs_by_list[pair_off[l] + atomicAdd(&fill[l], 1u)] = p;
+}
+
+// one thread per list: write the list's items (group-major, chunks of a group consecutive)
+__global__ void ivf_fill_items_kernel(const uint32_t *__restrict__ pair_off, const uint32_t *__restrict__ nc_arr,
+                                      const uint32_t *__restrict__ item_off, const int64_t *__restrict__ list_offsets,
+                                      int nlist, int rows_per_16b, IvfItem *items) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= nlist) return;
+    const uint32_t npl = pair_off[l + 1] - pair_off[l];
+    const int nc = (int)nc_arr[l];
+    if (npl == 0 || nc == 0) return;
+    const int64_t beg = list_offsets[l], end = list_offsets[l + 1];
+    int64_t rpc = (end - beg + nc - 1) / nc;
+    rpc = (rpc + rows_per_16b - 1) / rows_per_16b * rows_per_16b;
+    const int ng = (int)((npl + IVF_QB - 1) / IVF_QB);
+    for (int g = 0; g < ng; ++g) {
+        const int nslots = (int)(npl - (uint32_t)g * IVF_QB < (uint32_t)IVF_QB ? npl - (uint32_t)g * IVF_QB : IVF_QB);
+        for (int c = 0; c < nc; ++c) {
+            int64_t cb = beg + (int64_t)c * rpc, ce = cb + rpc < end ? cb + rpc : end;
+            IvfItem it;
+            if (cb >= ce) { cb = ce = beg; }   // empty chunk (rounding): scans nothing, still leaves its empty list
+            const int64_t aligned = cb / rows_per_16b * rows_per_16b;
+            it.code_begin = (uint32_t)aligned;
+            it.ncodes = (uint32_t)(ce - aligned);
+            it.pair_pos = pair_off[l] + (uint32_t)g * IVF_QB;
+            it.skip_slots_chunk = (uint32_t)(cb - aligned) | ((uint32_t)nslots << 8) | ((uint32_t)c << 16);
+            items[item_off[l] + (uint32_t)g * nc + c] = it;
+        }
+    }
+}
+
+// one thread per query: lists (pair, chunk) the query owns, and each pair's first list relative to the query
+__global__ void ivf_pair_lists_kernel(const int32_t *__restrict__ probes, const uint32_t *__restrict__ nc_arr, int nq,
+                                      int nprobe, uint32_t *pair_rel, uint32_t *qlists) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= nq) return;
+    uint32_t run = 0;
+    for (int r = 0; r < nprobe; ++r) {
+        pair_rel[(size_t)q * nprobe + r] = run;
+        run += nc_arr[probes[(size_t)q * nprobe + r]];
+    }
+    qlists[q] = run;
+}
+
+// single block: exclusive scan of qlists -> qlist_off[nq+1], then absolute first list of every pair
+__global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__restrict__ qlists, int nq, int nprobe,
+                                                              uint32_t *qlist_off, uint32_t *pair_out) {
+    __shared__ uint32_t scan[1024];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int q0 = 0; q0 < nq; q0 += 1024) {
+        const int q = q0 + tid;
+        const uint32_t v = q < nq ? qlists[q] : 0u;
+        scan[tid] = v;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {
+            const uint32_t add = tid >= o ? scan[tid - o] : 0u;
+            __syncthreads();
+            scan[tid] += add;
+            __syncthreads();
+        }
+        if (q < nq) qlist_off[q] = carry + scan[tid] - v;
+        __syncthreads();
+        if (tid == 1023) carry += scan[1023];
+        __syncthreads();
+    }
+    if (tid == 0) qlist_off[nq] = carry;
+    __syncthreads();
+    const size_t npairs = (size_t)nq * nprobe;
+    for (size_t p = tid; p < npairs; p += 1024) pair_out[p] += qlist_off[p / nprobe];
+}
+
+// One block per query: the k smallest keys over all lists of the query.  Keys above the final
+// bound of the query cannot be in the result and are dropped before the sort.
+constexpr int MERGE_CAP = 8192;
+__global__ __launch_bounds__(1024) void ivf_merge_kernel(const uint64_t *__restrict__ partial,
+                                                         const uint32_t *__restrict__ qlist_off,
+                                                         const uint32_t *__restrict__ tau_global, int kpad, int topk,
+                                                         const int64_t *__restrict__ ids, float *out_dist,
+                                                         int64_t *out_ids) {
+    extern __shared__ uint64_t skeys[];
+    __shared__ int s_count;
+    __shared__ unsigned long long s_kth;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const uint64_t *mine = partial + (size_t)qlist_off[q] * kpad;
+    const size_t total = (size_t)(qlist_off[q + 1] - qlist_off[q]) * kpad;
+    const uint32_t tau = tau_global[q];
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    for (size_t i = tid; i < total; i += blockDim.x) {
+        const uint64_t key = mine[i];
+        if (key != KEY_EMPTY && (uint32_t)(key >> 32) <= tau) {
+            const int pos = atomicAdd(&s_count, 1);
+            if (pos < MERGE_CAP) skeys[pos] = key;
+        }
+    }
+    __syncthreads();
+    int kept = s_count;
+    if (kept > MERGE_CAP) {
+        // too many keys at or below the bound (massive ties): bisection for the topk-th key
+        uint64_t v = 0;
+        for (int bit = 63; bit >= 0; --bit) {
+            const uint64_t trial = v | ((1ull << bit) - 1ull);
+            __syncthreads();
+            if (tid == 0) s_count = 0;
+            __syncthreads();
+            int c = 0;
+            for (size_t i = tid; i < total; i += blockDim.x) c += mine[i] <= trial ? 1 : 0;
+            atomicAdd(&s_count, c);
+            __syncthreads();
+            if (s_count < topk) v |= (1ull << bit);
+        }
+        __syncthreads();
+        if (tid == 0) { s_kth = v; s_count = 0; }
+        __syncthreads();
+        const uint64_t kth = s_kth;
+        for (size_t i = tid; i < total; i += blockDim.x) {
+            const uint64_t key = mine[i];
+            if (key != KEY_EMPTY && key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < MERGE_CAP) skeys[pos] = key; }
+        }
+        __syncthreads();
+        kept = s_count < MERGE_CAP ? s_count : MERGE_CAP;
+    }
+    int n2 = 64;
+    while (n2 < kept) n2 <<= 1;
+    for (int i = kept + tid; i < n2; i += blockDim.x) skeys[i] = KEY_EMPTY;
+    block_bitonic_sort(skeys, n2);
+    for (int i = tid; i < topk; i += blockDim.x) {
+        const uint64_t key = i < n2 ? skeys[i] : KEY_EMPTY;
+        const bool empty = key == KEY_EMPTY;
+        const uint32_t row = (uint32_t)key;
+        out_dist[(size_t)q * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
+        out_ids[(size_t)q * topk + i] = empty ? -1 : (ids ? ids[row] : (int64_t)row);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
+               int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
+    (void)cf;
+    const int d = L->d, nlist = L->nlist;
+    const int kind = m == 8 ? 0 : 1;
+    const int kpad = 128;
+    const int rows_per_16b = 16 / m;
+    hipStream_t s = ctx->stream;
+
+    // queries per batch: bounds the materialised tables (nprobe * m * 256 floats per query) to about 1 GiB
+    const size_t lut_per_query = (size_t)nprobe * m * k * sizeof(float);
+    int qbatch = (int)(((size_t)1 << 30) / lut_per_query);
+    if (qbatch < 1) qbatch = 1;
+    if (qbatch > 2048) qbatch = 2048;
+    if (qbatch > nq) qbatch = nq;
+    const size_t npairs_max = (size_t)qbatch * nprobe;
+    const size_t max_items = (npairs_max / IVF_QB + (size_t)nlist + 1) * IVF_MAX_CHUNKS;
+    const size_t max_lists = npairs_max * IVF_MAX_CHUNKS;
+
+    // workspace carving (all offsets 256-byte aligned)
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; };
+    const size_t o_dist = take((size_t)qbatch * nlist * 4);
+    const size_t o_probes = take(npairs_max * 4);
+    const size_t o_resid = take(npairs_max * d * 4);
+    const size_t o_luts = take(npairs_max * m * k * 4);
+    const size_t o_np = take((size_t)nlist * 4);
+    const size_t o_fill = take((size_t)nlist * 4);
+    const size_t o_pairoff = take((size_t)(nlist + 1) * 4);
+    const size_t o_nc = take((size_t)nlist * 4);
+    const size_t o_itemoff = take((size_t)nlist * 4);
+    const size_t o_nitems = take(4);
+    const size_t o_pairs = take(npairs_max * 4);
+    const size_t o_items = take(max_items * sizeof(IvfItem));
+    const size_t o_pairout = take(npairs_max * 4);
+    const size_t o_qlists = take((size_t)qbatch * 4);
+    const size_t o_qlistoff = take((size_t)(qbatch + 1) * 4);
+    const size_t o_partial = take(max_lists * kpad * 8);
+    const size_t state_bytes = tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
+    const size_t o_state = take(state_bytes);
+    int rc = ws_reserve(ctx, off);
+    if (rc) return rc;
+    uint8_t *ws = (uint8_t *)ctx->ws;
+    float *dist = (float *)(ws + o_dist);
+    int32_t *probes = (int32_t *)(ws + o_probes);
+    float *resid = (float *)(ws + o_resid);
+    float *luts = (float *)(ws + o_luts);
+    uint32_t *np = (uint32_t *)(ws + o_np), *fill = (uint32_t *)(ws + o_fill);
+    uint32_t *pair_off = (uint32_t *)(ws + o_pairoff), *nc = (uint32_t *)(ws + o_nc);
+    uint32_t *item_off = (uint32_t *)(ws + o_itemoff), *nitems_dev = (uint32_t *)(ws + o_nitems);
+    int32_t *pairs_by_list = (int32_t *)(ws + o_pairs);
+    IvfItem *items = (IvfItem *)(ws + o_items);
+    uint32_t *pair_out = (uint32_t *)(ws + o_pairout), *qlists = (uint32_t *)(ws + o_qlists);
+    uint32_t *qlist_off = (uint32_t *)(ws + o_qlistoff);
+    uint64_t *partial = (uint64_t *)(ws + o_partial);
+
+    PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(ivf_merge_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
+    for (int q0 = 0; q0 < nq; q0 += qbatch) {
+        const int nqb = nq - q0 < qbatch ? nq - q0 : qbatch;
+        const int npairs = nqb * nprobe;
+        const float *qb = queries + (size_t)q0 * d;
+        // Index step
+        rc = launch_build_luts(ctx, qb, L->coarse_centroids, nqb, d, 1, nlist, dist);
+        if (rc) return rc;
+        ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes,
+                                                     probe_out ? probe_out + (size_t)q0 * nprobe : nullptr);
+        PQ_HIP(ctx, hipGetLastError());
+        // Tables step on the residuals
+        {
+            const size_t n = (size_t)npairs * d;
+            ivf_residual_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(qb, L->coarse_centroids, probes, npairs,
+                                                                            nprobe, d, resid);
+            PQ_HIP(ctx, hipGetLastError());
+        }
+        rc = launch_build_luts(ctx, resid, codebooks, npairs, d, m, k, luts);
+        if (rc) return rc;
+        // group the pairs by list, lay out the work items
+        ivf_zero_kernel<<<256, 256, 0, s>>>(np, (size_t)nlist);
+        ivf_zero_kernel<<<256, 256, 0, s>>>(fill, (size_t)nlist);
+        ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, np);
+        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev);
+        ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, pair_off, fill, pairs_by_list);
+        ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(pair_off, nc, item_off, L->list_offsets, nlist,
+                                                                  rows_per_16b, items);
+        ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
+        ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, nprobe, qlist_off, pair_out);
+        PQ_HIP(ctx, hipGetLastError());
+        // Scan step
+        uint32_t *tau_global = nullptr;
+        rc = launch_scan_items(ctx, kind, L->codes, luts, nqb, nprobe, topk, items, nitems_dev, pairs_by_list, pair_out,
+                               partial, ws + o_state, state_bytes, &tau_global);
+        if (rc) return rc;
+        ivf_merge_kernel<<<nqb, 1024, MERGE_CAP * 8, s>>>(partial, qlist_off, tau_global, kpad, topk, L->ids,
+                                                          out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
+        PQ_HIP(ctx, hipGetLastError());
+    }
+    return PQ_OK;
 }
 
 }  // namespace pq

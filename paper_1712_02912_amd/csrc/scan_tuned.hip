@@ -645,6 +645,82 @@ static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
     return PQ_OK;
 }
 
+struct StateLayout {
+    size_t off_tau, off_ncand, off_mark, off_ref, off_hist, off_scratch, total;
+    size_t nhist;
+};
+
+static StateLayout state_layout(int qb, int ntau, int cap, int nblocks) {
+    StateLayout L;
+    L.off_tau = 256;
+    L.off_ncand = L.off_tau + align_up((size_t)ntau * 4, 256);
+    L.off_mark = L.off_ncand + align_up((size_t)ntau * 4, 256);
+    L.off_ref = L.off_mark + align_up((size_t)ntau * 4, 256);
+    L.off_hist = L.off_ref + align_up((size_t)ntau * 4, 256);
+    L.nhist = (size_t)ntau * HIST_BINS;
+    L.off_scratch = L.off_hist + align_up(L.nhist * 4, 256);
+    L.total = L.off_scratch + (size_t)nblocks * TUNED_WAVES * qb * cap * 8;
+    return L;
+}
+
+static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
+    a.work_counter = (uint32_t *)ws;
+    a.tau_global = (uint32_t *)(ws + L.off_tau);
+    a.ncand = (uint32_t *)(ws + L.off_ncand);
+    a.refresh_mark = (uint32_t *)(ws + L.off_mark);
+    a.tau_ref = (uint32_t *)(ws + L.off_ref);
+    a.hist = (uint32_t *)(ws + L.off_hist);
+    a.scratch = (uint64_t *)(ws + L.off_scratch);
+}
+
+static int launch_by_kind(pq_ctx *ctx, int kind, bool small, const TunedArgs &a, int nblocks) {
+    switch (kind) {
+        case KIND_F32_M8:
+            return small ? launch_kind<KIND_F32_M8, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024>(ctx, a, nblocks);
+        case KIND_F32_M16:
+            return small ? launch_kind<KIND_F32_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024>(ctx, a, nblocks);
+        default:
+            return small ? launch_kind<KIND_U4_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024>(ctx, a, nblocks);
+    }
+}
+
+size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu) {
+    const int qb = kind == KIND_U4_M16 ? 8 : 4;
+    const int cap = 2 * (topk <= 128 ? 128 : 1024);
+    return state_layout(qb, nq, cap, num_cu).total;
+}
+
+int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
+                      const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
+                      const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
+                      uint32_t **tau_global_out) {
+    const int qb = kind == KIND_U4_M16 ? 8 : 4;
+    const bool small = topk <= 128;
+    const int cap = 2 * (small ? 128 : 1024);
+    const int nblocks = ctx->num_cu;
+    const StateLayout L = state_layout(qb, nq, cap, nblocks);
+    if (L.total > state_bytes) return fail(ctx, PQ_EINVAL, "scan_items: state region too small");
+    TunedArgs a;
+    a.codes = codes; a.n = 0; a.chunk_codes = 0; a.nchunks = 0; a.ngroups = 1; a.nitems = 0;
+    a.luts = luts; a.nq = nq; a.topk = topk;
+    bind_state(a, state, L);
+    a.partial = partial;
+    a.item_tab = items; a.nitems_dev = nitems_dev; a.pairs_by_list = pairs_by_list; a.pair_out = pair_out;
+    a.nprobe = nprobe;
+    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
+                                                     0xff800000u, a.hist, L.nhist);
+    PQ_HIP(ctx, hipGetLastError());
+    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    int rc = launch_by_kind(ctx, kind, small, a, nblocks);
+    if (rc) return rc;
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
+        ctx->ev_valid = 1;
+    }
+    *tau_global_out = a.tau_global;
+    return PQ_OK;
+}
+
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids) {
     const bool is_u4 = kind == KIND_U4_M16;
@@ -675,14 +751,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int nblocks = (int)(nitems < nblocks_max ? nitems : nblocks_max);
 
     const int ntau = ngroups * qb;
-    const size_t off_tau = 256;
-    const size_t off_ncand = off_tau + align_up((size_t)ntau * 4, 256);
-    const size_t off_mark = off_ncand + align_up((size_t)ntau * 4, 256);
-    const size_t off_ref = off_mark + align_up((size_t)ntau * 4, 256);
-    const size_t off_hist = off_ref + align_up((size_t)ntau * 4, 256);
-    const size_t nhist = (size_t)ntau * HIST_BINS;
-    const size_t off_scratch = off_hist + align_up(nhist * 4, 256);
-    const size_t off_partial = off_scratch + (size_t)nblocks * TUNED_WAVES * qb * cap * 8;
+    const StateLayout L = state_layout(qb, ntau, cap, nblocks);
+    const size_t off_partial = align_up(L.total, 256);
     const size_t total = off_partial + (size_t)nitems * qb * kpad * 8;
     int rc = ws_reserve(ctx, total);
     if (rc) return rc;
@@ -691,31 +761,15 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     TunedArgs a;
     a.codes = codes; a.n = n; a.chunk_codes = chunk_codes; a.nchunks = (int)nchunks; a.ngroups = ngroups;
     a.nitems = (int)nitems; a.luts = luts; a.nq = nq; a.topk = topk;
-    a.work_counter = (uint32_t *)ws;
-    a.tau_global = (uint32_t *)(ws + off_tau);
-    a.ncand = (uint32_t *)(ws + off_ncand);
-    a.refresh_mark = (uint32_t *)(ws + off_mark);
-    a.tau_ref = (uint32_t *)(ws + off_ref);
-    a.hist = (uint32_t *)(ws + off_hist);
-    a.scratch = (uint64_t *)(ws + off_scratch);
+    bind_state(a, ws, L);
     a.partial = (uint64_t *)(ws + off_partial);
     a.item_tab = nullptr; a.nitems_dev = nullptr; a.pairs_by_list = nullptr; a.pair_out = nullptr; a.nprobe = 0;
 
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
-                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, nhist);
+                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    switch (kind) {
-        case KIND_F32_M8:
-            rc = small ? launch_kind<KIND_F32_M8, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024>(ctx, a, nblocks);
-            break;
-        case KIND_F32_M16:
-            rc = small ? launch_kind<KIND_F32_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024>(ctx, a, nblocks);
-            break;
-        default:
-            rc = small ? launch_kind<KIND_U4_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024>(ctx, a, nblocks);
-            break;
-    }
+    rc = launch_by_kind(ctx, kind, small, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));

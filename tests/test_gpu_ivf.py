@@ -1,0 +1,124 @@
+"""IVFADC search (Index + Tables + Scan with an inverted index) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pq_oracle as orc
+from paper_1712_02912_amd import binding, datagen
+from util import RTOL, check_float_topk_ranked
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = binding.Context(0)
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_probes(queries, coarse, gpu_probes, nprobe):
+    """Probed lists equal the oracle's up to ties of the coarse distances inside 1e-6 relative."""
+    ref, ref_d = orc.ivf_probe(queries, coarse, nprobe)
+    cd = ((queries[:, None, :].astype(np.float64) - coarse[None].astype(np.float64)) ** 2).sum(-1)
+    for q in range(len(queries)):
+        if np.array_equal(gpu_probes[q], ref[q]):
+            continue
+        assert len(set(gpu_probes[q].tolist())) == nprobe
+        tau = cd[q][ref[q][-1]]
+        assert np.all(cd[q][gpu_probes[q]] <= tau * (1 + 1e-6))
+        np.testing.assert_allclose(cd[q][gpu_probes[q]], cd[q][ref[q]], rtol=1e-6)
+
+
+def run_ivf(ctx, queries, coarse, offsets, codes, ids, cb, nprobe, topk):
+    d, i, p = ctx.ivf_adc_search(dev(coarse), dev(offsets), dev(codes), None if ids is None else dev(ids), dev(cb),
+                                 binding.CODES_U8, dev(queries), nprobe, topk, return_probes=True)
+    torch.cuda.synchronize()
+    gd, gi, gp = d.cpu().numpy(), i.cpu().numpy(), p.cpu().numpy()
+    check_probes(queries, coarse, gp, nprobe)
+    # the scan is compared on the lists the GPU probed, so that a coarse tie cannot move the result
+    od, oi = orc.ivf_scan(queries, coarse, offsets, codes, ids, cb, orc.CODES_U8, gp, topk)
+    for q in range(len(queries)):
+        check_float_topk_ranked(gd[q], gi[q], od[q], oi[q])
+    return gd, gi
+
+
+def make_index(n, d, m, nlist, seed, ntrain=4000, encoded=True):
+    mix = datagen.Mixture(d, 16, (0.0, 128.0), (8.0, 32.0), (0.0, 255.0), seed=seed)
+    base = mix.sample(n, seed + 1)
+    coarse = orc.kmeans(base[:ntrain], nlist, 3, np.arange(nlist, dtype=np.int64) * (ntrain // nlist))
+    assign = ((base[:, None, :].astype(np.float32) - coarse[None]) ** 2).sum(-1).argmin(1)
+    resid = base - coarse[assign]
+    cb = orc.pq_train(resid[:ntrain], m, 256, 3, datagen.kmeans_init_idx(ntrain, m, 256, seed + 2))
+    order = np.argsort(assign, kind="stable")
+    codes = orc.pq_encode(resid[order], cb)
+    offsets = datagen.offsets_from_sizes(np.bincount(assign, minlength=nlist))
+    return mix, coarse, cb, codes, order.astype(np.int64), offsets
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_ivf_encoded_small(ctx, m):
+    mix, coarse, cb, codes, order, offsets = make_index(20000, 64, m, 40, seed=21 + m)
+    queries = mix.sample(13, 99)
+    for nprobe, topk in ((1, 10), (8, 100), (40, 128), (5, 1)):
+        run_ivf(ctx, queries, coarse, offsets, codes, order, cb, nprobe, topk)
+    run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 8, 50)
+
+
+def test_ivf_all_lists_equals_flat_scan_of_residual_tables(ctx):
+    """nprobe = nlist: every code is scanned once with the tables of its own list."""
+    mix, coarse, cb, codes, order, offsets = make_index(8000, 64, 8, 16, seed=31)
+    queries = mix.sample(6, 98)
+    gd, gi = run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 16, 20)
+    # brute force straight from the definition: || (y - centroid_l(n)) - decode(code_n) ||^2
+    list_of = np.repeat(np.arange(16), np.diff(offsets))
+    decoded = np.concatenate([cb[j][codes[:, j]] for j in range(8)], axis=1).astype(np.float64)
+    for q in range(len(queries)):
+        r = (queries[q][None, :] - coarse[list_of]).astype(np.float64)
+        dd = ((r - decoded) ** 2).sum(1)
+        np.testing.assert_allclose(gd[q], np.sort(dd)[:20], rtol=1e-5)
+
+
+def test_ivf_skewed_lists_many_chunks_and_empty_lists(ctx):
+    """Zipf-like list sizes with one list long enough to be cut into chunks, odd list boundaries, empty lists."""
+    r = np.random.default_rng(41)
+    d, m, nlist = 32, 8, 24
+    sizes = np.array([700_001, 90_003, 7, 0, 1, 33_333, 0, 129, 128, 127] + [1000 + 37 * i for i in range(14)])
+    offsets = datagen.offsets_from_sizes(sizes)
+    n = int(offsets[-1])
+    codes = r.integers(0, 256, (n, m), dtype=np.uint8)
+    coarse = (r.random((nlist, d)) * 100).astype(np.float32)
+    cb = (r.random((m, 256, d // m)) * 30).astype(np.float32)
+    queries = (r.random((9, d)) * 100).astype(np.float32)
+    ids = r.permutation(n).astype(np.int64)
+    run_ivf(ctx, queries, coarse, offsets, codes, ids, cb, 24, 100)
+    run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 6, 17)
+
+
+def test_ivf_fewer_codes_than_topk(ctx):
+    r = np.random.default_rng(43)
+    d, m, nlist = 16, 8, 4
+    offsets = datagen.offsets_from_sizes(np.array([3, 0, 2, 1]))
+    codes = r.integers(0, 256, (6, m), dtype=np.uint8)
+    coarse = r.random((nlist, d)).astype(np.float32)
+    cb = r.random((m, 256, d // m)).astype(np.float32)
+    queries = r.random((3, d)).astype(np.float32)
+    gd, gi = run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 4, 10)
+    assert np.all(gi[:, 6:] == -1) and np.all(np.isinf(gd[:, 6:]))
+
+
+def test_ivf_errors(ctx):
+    z = lambda *s, dt=torch.float32: torch.zeros(s, dtype=dt, device="cuda")
+    with pytest.raises(binding.PqError) as e:
+        ctx.ivf_adc_search(z(4, 16), z(5, dt=torch.int64), z(6, 8, dt=torch.uint8), None, z(8, 256, 2), binding.CODES_U8,
+                           z(1, 16), 5, 3)
+    assert e.value.code == -2      # nprobe > nlist
+    with pytest.raises(binding.PqError) as e:
+        ctx.ivf_adc_search(z(4, 16), z(5, dt=torch.int64), z(6, 4, dt=torch.uint8), None, z(4, 256, 4), binding.CODES_U8,
+                           z(1, 16), 2, 3)
+    assert e.value.code == -3      # m = 4 is outside the covered shapes

@@ -345,11 +345,12 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const int rows_per_16b = 16 / m;
     hipStream_t s = ctx->stream;
 
-    // queries per batch: bounds the materialised tables (nprobe * m * 256 floats per query) to about 1 GiB
-    const size_t lut_per_query = (size_t)nprobe * m * k * sizeof(float);
-    int qbatch = (int)(((size_t)1 << 30) / lut_per_query);
+    // queries per batch: keeps the per-query part of the workspace (coarse distances, residuals and
+    // tables of the nprobe pairs, upper bound of their result lists, histogram) within about 6 GiB
+    const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 +
+                             (size_t)IVF_MAX_CHUNKS * kpad * 8 + 64) + (size_t)HIST_BINS * 4 + 64;
+    int qbatch = (int)(((size_t)6 << 30) / per_query);
     if (qbatch < 1) qbatch = 1;
-    if (qbatch > 2048) qbatch = 2048;
     if (qbatch > nq) qbatch = nq;
     const size_t npairs_max = (size_t)qbatch * nprobe;
     const size_t max_items = (npairs_max / IVF_QB + (size_t)nlist + 1) * IVF_MAX_CHUNKS;

@@ -14,7 +14,7 @@
 // every read is conflict-free whatever the code bytes are.  Each lane walks the tables in
 // its own rotated order, which only permutes the order of the float additions.
 //
-// Work distribution.  A fixed number of persistent blocks (two per CU) take work items
+// Work distribution.  A fixed number of persistent blocks (one per CU) take work items
 // (chunk of codes x group of queries) from a device counter, chunk-major, so that blocks
 // running at the same time share code chunks in L2 and later chunks start with the bounds
 // the earlier ones found.
@@ -42,18 +42,17 @@ struct WaveState {
     uint32_t own_ord[8];   // k-th smallest value of the wave's own list, ord_inf while not full
 };
 
-constexpr int RING_CAP = 96;      // entries per wave
-constexpr int RING_FLUSH = 32;    // flush when more than this many are parked (64 more always fit)
+constexpr int RING_FLUSH = 32;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
+constexpr int RING_CAP = RING_FLUSH + 2 * 64 * 4;   // two tiles (of up to 4 sub-tiles of 64 lanes) fit behind an unflushed ring
 
 struct __align__(16) TunedSmem {
     uint4 lut[4096];
     uint8_t qstage[8][256];
+    // Per wave: lanes that found a candidate park the position of their 16 code bytes here; the
+    // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
+    uint32_t ring[TUNED_WAVES][RING_CAP];
     WaveState ws[TUNED_WAVES];
-    // Per wave: lanes that found a candidate park their accumulators here; the entries are turned
-    // into list inserts in batches (scan_flush).  Entry = 8 accumulators + position of the lane's
-    // first code in the item (+ 3 words of padding: 48 bytes, 16-byte aligned).
-    uint32_t ring[TUNED_WAVES][RING_CAP][12];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
     uint32_t tau_ref[8];   // histogram reference per query (float path)
     // per item, written at its start: where the state of the query in each slot lives
@@ -64,10 +63,11 @@ struct __align__(16) TunedSmem {
     uint32_t *tau_ref_global[8];
     const void *slot_lut[8];   // tables of the slot's query (nullptr: empty slot)
     uint64_t *slot_out[8];     // where the slot's KPAD result keys go
-    int64_t code_begin;        // first row scanned by the item
+    const uint8_t *chunk_ptr;  // first row scanned by the item
+    int64_t code_begin;        // its row number
     int ncodes;                // rows scanned
     int skip;                  // leading rows that are not part of the item
-    int nvalid;            // queries of the group that exist
+    int nvalid;                // slots in use
     int topk;
     int item;
 };
@@ -76,6 +76,9 @@ struct __align__(16) TunedSmem {
 // the scan loop); they address the block's shared structure through an LDS-qualified pointer.
 typedef __attribute__((address_space(3))) TunedSmem LdsSmem;
 typedef __attribute__((address_space(3))) WaveState LdsWaveState;
+
+
+enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2 };
 
 // rotate the bytes of a 64-bit code right by r bytes (r in 0..7): byte s of the result is
 // byte (s + r) & 7 of the input
@@ -104,6 +107,68 @@ __device__ __forceinline__ uint32_t lut_offset(uint32_t word, uint32_t bases) {
     // result byte 0 <- bases byte POS, byte 1 <- word byte POS, bytes 2 and 3 <- 0
     constexpr uint32_t sel = 0x0c0c0000u | ((4u + POS) << 8) | (uint32_t)POS;
     return __builtin_amdgcn_perm(word, bases, sel);
+}
+
+// What a lane needs to walk the tables in its own rotated order (see the layout note on top):
+// derived from the low four bits of the lane that holds the code bytes.
+template <int NT>
+struct LaneWalk {
+    uint32_t rot;            // bytes to rotate the code by
+    uint32_t bases[NT / 4];  // slot offsets of the NT steps, four per word
+    __device__ __forceinline__ explicit LaneWalk(uint32_t lane15) {
+        constexpr int SSTEP = NT == 8 ? 2 : 1;   // slot stride per step
+        rot = NT == 8 ? lane15 >> 1 : lane15;
+#pragma unroll
+        for (int g = 0; g < NT / 4; ++g) {
+            bases[g] = 0;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) bases[g] |= (((lane15 + SSTEP * (4 * g + p)) & 15u) << 4) << (8 * p);
+        }
+    }
+};
+
+// Accumulated values of the codes in the 16 bytes `c` (two 8-byte codes or one 16-byte code),
+// four accumulators per code: d[h][0..3] = the four queries' float sums, or the eight queries'
+// integer sums as four packed pairs.  `ld(offset)` returns the 16-byte LDS slot at that offset.
+template <int NT, bool IS_U4, class Ld>
+__device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &lw, Ld ld, uint32_t (&d)[16 / NT][4]) {
+    constexpr int CPL = 16 / NT;
+    uint32_t w[4] = {c.x, c.y, c.z, c.w};
+    if constexpr (NT == 8) {
+        const bool swap = (lw.rot & 4u) != 0;
+        rot8(w[0], w[1], swap, lw.rot & 3u);
+        rot8(w[2], w[3], swap, lw.rot & 3u);
+    } else {
+        rot16(w, lw.rot);
+    }
+#pragma unroll
+    for (int h = 0; h < CPL; ++h) {
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+            uint32_t off;
+            const uint32_t word = w[h * (NT / 4) + (s >> 2)], bs = lw.bases[s >> 2];
+            switch (s & 3) {
+                case 0: off = lut_offset<0>(word, bs); break;
+                case 1: off = lut_offset<1>(word, bs); break;
+                case 2: off = lut_offset<2>(word, bs); break;
+                default: off = lut_offset<3>(word, bs); break;
+            }
+            const uint4 v = ld(off);
+            if constexpr (IS_U4) {
+                if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
+                else { d[h][0] += v.x; d[h][1] += v.y; d[h][2] += v.z; d[h][3] += v.w; }
+            } else {
+                if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
+                else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t add = i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+                        d[h][i] = __float_as_uint(__uint_as_float(d[h][i]) + __uint_as_float(add));
+                    }
+                }
+            }
+        }
+    }
 }
 
 // smallest histogram bin b with count(bins <= b) >= k, or HIST_BINS if fewer than k counted
@@ -143,15 +208,13 @@ __device__ __forceinline__ int hist_threshold(const uint32_t *hist, int k) {
     return __shfl(bin, first);
 }
 
-enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2 };
-
 __device__ __forceinline__ void publish_bound(LdsSmem *sm, int q, uint32_t ord) {
     __hip_atomic_fetch_min(&sm->tau_blk[q], ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     atomicMin(sm->tau_global[q], ord);
 }
 
-// Rare path of the scan loop: the candidate list of query q of this wave is nearly full.  Keep
-// its k smallest keys, make the k-th the wave's own bound and share it.  Returns the new count.
+// Rare path: the candidate list of query q of this wave is nearly full.  Keep its k smallest
+// keys, make the k-th the wave's own bound and share it.  Returns the new count.
 template <int E, bool IS_U4>
 __device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, int q) {
     const int lane = lane_id();
@@ -173,31 +236,47 @@ __device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, in
     return cnt;
 }
 
-// Rare path of the scan loop: turn the `n` entries parked in the wave's ring into list inserts.
-// Lane e takes entry e (64 at a time).  For every query the candidates (value below the current
-// bound) are appended to the wave's list and counted in the query's histogram; a list that is
-// nearly full is compacted.  Entries are in scan order, so ids still reach a list in increasing order.
-template <class V, int QB, int E, int CPL, bool IS_U4>
+// Rare path of the scan loop: turn the `n` positions parked in the wave's ring into list inserts.
+// Lane e takes entry e (64 at a time): it reloads the 16 code bytes at that position and
+// recomputes their values exactly as the lane that parked them did (same rotation, same order
+// of additions).  For every query the candidates (value below the current bound) are appended
+// to the wave's list and counted in the query's histogram; a list that is nearly full is
+// compacted.  Entries are in scan order, so ids still reach a list in increasing order.
+template <int KIND, int E>
 __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) {
+    constexpr bool IS_U4 = KIND == KIND_U4_M16;
+    constexpr int QB = IS_U4 ? 8 : 4;
+    constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;
+    constexpr int CPL = 16 / NT;
     constexpr int CAP = 64 * E;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     LdsWaveState *ws = &sm->ws[wave];
     const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
     const uint32_t row0 = (uint32_t)sm->code_begin;
+    const uint8_t *chunk_ptr = sm->chunk_ptr;
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const __attribute__((address_space(3))) char *lut_bytes = (const __attribute__((address_space(3))) char *)sm->lut;
     for (int base = 0; base < n; base += 64) {
         const bool have = base + lane < n;
-        uint32_t acc[2][4] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
-        int pos = 0;
+        const int pos = have ? (int)sm->ring[wave][base + lane] : 0;   // position of the 16 bytes' first code
+        uint4 c = make_uint4(0, 0, 0, 0);
         if (have) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[0][i] = sm->ring[wave][base + lane][i];
-                acc[1][i] = sm->ring[wave][base + lane][4 + i];
-            }
-            pos = (int)sm->ring[wave][base + lane][8];
+            const uint8_t *p = chunk_ptr + (size_t)(pos / CPL) * 16;
+            if (pos + CPL <= ncodes) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (CPL == 2 && pos < ncodes) {   // last lane of a ragged chunk: only its first code exists
+                const uint2 half = *reinterpret_cast<const uint2 *>(p);
+                c.x = half.x; c.y = half.y;
+            }   // (lanes past the end of a ragged chunk park positions too: nothing to load, never inserted)
         }
+        const LaneWalk<NT> lw((uint32_t)(pos / CPL) & 15u);   // the parking lane's walk
+        uint32_t acc[CPL][4];
+        code_values<NT, IS_U4>(c, lw, [&](uint32_t off) {
+            const v4u v = *(const __attribute__((address_space(3))) v4u *)(lut_bytes + off);
+            return make_uint4(v.x, v.y, v.z, v.w);
+        }, acc);
 #pragma unroll 1
-        for (int q = 0; q < nvalid; ++q) {
+        for (int q = 0; q < nvalid && q < QB; ++q) {
             // candidates satisfy value < eff: the wave's own bound is strict, the block's is "<="
             const uint32_t shared = sm->tau_blk[q];
             const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
@@ -214,7 +293,7 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
                     ord = (pk >> (16 * (q & 1))) & 0xffffu;
                 } else {
                     const uint32_t bits = q == 0 ? acc[h][0] : q == 1 ? acc[h][1] : q == 2 ? acc[h][2] : acc[h][3];
-                    ord = V::to_ord(__uint_as_float(bits));
+                    ord = f32_to_ord(__uint_as_float(bits));
                 }
                 const bool pass = have && pos + h >= skip && pos + h < ncodes && ord < eff;
                 const uint64_t mask = __ballot(pass);
@@ -237,7 +316,8 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
                 if (cnt > CAP - 64) cnt = scan_compact<E, IS_U4>(sm, buf, cnt, q);
                 if (lane == 0) {
                     ws->cnt[q] = cnt;
-                    __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)__popcll(mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)__popcll(mask), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
@@ -313,11 +393,11 @@ __device__ __noinline__ void scan_merge_item(LdsSmem *sm, uint64_t *block_scratc
         cnt += cw;
         if (cnt > k) wave_compact<E>(acc, cnt, k);
     }
-    __threadfence();
+    if (cnt > 0) __threadfence();
     for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
 }
 
-template <int KIND, int E, int KPAD>
+template <int KIND, int E, int KPAD, int BATCH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void scan_tuned_kernel(TunedArgs a) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;
@@ -326,32 +406,23 @@ void scan_tuned_kernel(TunedArgs a) {
     constexpr int CB = NT;                                // code bytes (8 or 16)
     constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
     constexpr int SUB = 64 * CPL;                         // codes per wave sub-tile (one load per lane)
-    constexpr int BATCH = 1;                              // sub-tiles fetched together
+    // BATCH = sub-tiles fetched together: 1 when the codes are shared by many blocks through L2
+    // (flat scan), more when every block streams its own list from HBM (IVF)
     constexpr int TILE = SUB * BATCH;                     // codes per wave tile
     constexpr int CAP = 64 * E;
-    constexpr int SSTEP = NT == 8 ? 2 : 1;                // slot stride per step
-    constexpr int NACC = 4;                               // accumulators per code (4 floats or 4 packed pairs)
+    static_assert(RING_FLUSH + 2 * 64 * BATCH <= RING_CAP, "two tiles must fit behind a ring that was not flushed");
     typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
-    typedef typename V::type val_t;
     __shared__ TunedSmem sm;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keep it scalar
     const int lane = lane_id();
-    const uint32_t lane15 = lane & 15;
-    const uint32_t rot = NT == 8 ? lane15 >> 1 : lane15;
-    const bool rot_swap = (rot & 4u) != 0;
-    uint32_t bases[NT / 4];
-#pragma unroll
-    for (int g = 0; g < NT / 4; ++g) {
-        bases[g] = 0;
-#pragma unroll
-        for (int p = 0; p < 4; ++p) bases[g] |= (((lane15 + SSTEP * (4 * g + p)) & 15u) << 4) << (8 * p);
-    }
+    const LaneWalk<NT> lw((uint32_t)lane & 15u);
     const char *lut_bytes = reinterpret_cast<const char *>(sm.lut);
     uint64_t *block_scratch = a.scratch + (size_t)blockIdx.x * TUNED_WAVES * QB * CAP;
     uint64_t *wave_buf = block_scratch + (size_t)wave * QB * CAP;
 
     const int nitems = a.item_tab ? (int)*a.nitems_dev : a.nitems;
+    int gstep = 0;   // steps of this wave over all its items: paces the periodic bound refresh
     for (;;) {
         if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
         __syncthreads();
@@ -375,6 +446,7 @@ void scan_tuned_kernel(TunedArgs a) {
                 }
                 if (s == 0) {
                     sm.code_begin = it.code_begin;
+                    sm.chunk_ptr = a.codes + it.code_begin * CB;
                     sm.ncodes = (int)it.ncodes;
                     sm.skip = it.skip_slots_chunk & 0xff;
                     sm.nvalid = nslots;
@@ -392,6 +464,7 @@ void scan_tuned_kernel(TunedArgs a) {
                     const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
                     const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
                     sm.code_begin = cbeg;
+                    sm.chunk_ptr = a.codes + cbeg * CB;
                     sm.ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;
                     sm.skip = 0;
                     sm.nvalid = a.nq - group * QB < QB ? a.nq - group * QB : QB;
@@ -453,26 +526,33 @@ void scan_tuned_kernel(TunedArgs a) {
         __syncthreads();
 
         const int nvalid_q = sm.nvalid;
-        int ring_cnt = 0;                  // entries parked in this wave's ring (uniform)
-        // thresholds in registers: a code is a candidate for query q if value < tau[q]
-        val_t tau[QB];
+        int ring_cnt = 0;                  // positions parked in this wave's ring (uniform)
+        // Thresholds in registers: a code is a candidate for query q if value < tau[q].
+        // Float: the four thresholds as float bits; integer: the eight as four packed pairs.
+        uint32_t tau[4];
         auto reload_tau = [&]() {
+            uint32_t t[QB];
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
                 const uint32_t shared = sm.tau_blk[q];
                 const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
                 const uint32_t own = sm.ws[wave].own_ord[q];
-                tau[q] = V::from_ord(own < loose ? own : loose);
-                if (IS_U4 && q >= nvalid_q) tau[q] = 0;
+                const uint32_t eff = own < loose ? own : loose;
+                if constexpr (IS_U4) t[q] = q < nvalid_q ? eff : 0u;
+                else t[q] = __float_as_uint(ord_to_f32(eff));
+            }
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                if constexpr (IS_U4) tau[p] = t[2 * p] | (t[2 * p + 1] << 16);
+                else tau[p] = t[p];
             }
         };
         reload_tau();
 
-        const int64_t cbeg = sm.code_begin;
         const int ncodes = sm.ncodes;                                      // rows of this item (below 2^31)
         const int nsub = (ncodes + SUB - 1) / SUB;                         // sub-tiles, the last may be ragged
         const int nfull = ncodes / TILE;                                   // tiles with every code present
-        const uint8_t *chunk_ptr = a.codes + cbeg * CB;
+        const uint8_t *chunk_ptr = sm.chunk_ptr;
 
         // the 16 bytes of this lane in each sub-tile of full tile t
         auto load_full = [&](int t, uint4 (&c)[BATCH]) {
@@ -494,56 +574,16 @@ void scan_tuned_kernel(TunedArgs a) {
             return c;
         };
 
-        // values of the CPL codes of this lane for the QB queries (4 accumulators per code)
-        auto compute = [&](uint4 c, val_t (&d)[CPL][NACC]) {
-            uint32_t w[4] = {c.x, c.y, c.z, c.w};
-            if constexpr (NT == 8) {
-                rot8(w[0], w[1], rot_swap, rot & 3u);
-                rot8(w[2], w[3], rot_swap, rot & 3u);
-            } else {
-                rot16(w, rot);
-            }
-#pragma unroll
-            for (int h = 0; h < CPL; ++h) {
-#pragma unroll
-                for (int s = 0; s < NT; ++s) {
-                    uint32_t off;
-                    const uint32_t word = w[h * (NT / 4) + (s >> 2)], bs = bases[s >> 2];
-                    switch (s & 3) {
-                        case 0: off = lut_offset<0>(word, bs); break;
-                        case 1: off = lut_offset<1>(word, bs); break;
-                        case 2: off = lut_offset<2>(word, bs); break;
-                        default: off = lut_offset<3>(word, bs); break;
-                    }
-                    const uint4 v = *reinterpret_cast<const uint4 *>(lut_bytes + off);
-                    if constexpr (IS_U4) {
-                        if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
-                        else { d[h][0] += v.x; d[h][1] += v.y; d[h][2] += v.z; d[h][3] += v.w; }
-                    } else {
-                        const float f0 = __uint_as_float(v.x), f1 = __uint_as_float(v.y), f2 = __uint_as_float(v.z),
-                                    f3 = __uint_as_float(v.w);
-                        if (s == 0) { d[h][0] = f0; d[h][1] = f1; d[h][2] = f2; d[h][3] = f3; }
-                        else { d[h][0] += f0; d[h][1] += f1; d[h][2] += f2; d[h][3] += f3; }
-                    }
-                }
-            }
-        };
-
-        // the wave that refreshes query my_q from the histogram, and when
-        const int my_q = wave % QB;
-        const int my_phase = 1 + 8 * my_q;
-        const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf();
-
-        int iter = 0;
-        auto process = [&](const uint4 cur, const int sidx) {
-            val_t d[CPL][NACC];
-            compute(cur, d);
-            // issue order inside the loop body: all address arithmetic, then every LDS read
-            // back to back, then the additions (the reads are independent of one another)
+        // One sub-tile: values of this lane's codes for all queries, threshold test, and the
+        // positions of the lanes with a candidate parked in the ring.  No calls in here.
+        auto scan_sub = [&](const uint4 cur, const int sidx) {
+            uint32_t d[CPL][4];
+            code_values<NT, IS_U4>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
+            // issue order: all address arithmetic, then every LDS read back to back, then the
+            // additions (the reads are independent of one another)
             __builtin_amdgcn_sched_group_barrier(0x002, 8 + 2 * NT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * NT * CPL / 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, NT * CPL, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 8 * NT, 0);
-
             uint64_t hit = 0;
             if constexpr (IS_U4) {
                 // packed fields: (x | 0x8000) - tau keeps bit 15 iff x >= tau
@@ -551,75 +591,97 @@ void scan_tuned_kernel(TunedArgs a) {
 #pragma unroll
                 for (int h = 0; h < CPL; ++h)
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp)
-                        allge &= (d[h][pp] | 0x80008000u) - (tau[2 * pp] | (tau[2 * pp + 1] << 16));
+                    for (int pp = 0; pp < 4; ++pp) allge &= (d[h][pp] | 0x80008000u) - tau[pp];
                 hit = __ballot((allge & 0x80008000u) != 0x80008000u);
             } else {
 #pragma unroll
                 for (int h = 0; h < CPL; ++h)
 #pragma unroll
-                    for (int q = 0; q < QB; ++q) hit |= __ballot(d[h][q] < tau[q]);
+                    for (int q = 0; q < QB; ++q) hit |= __ballot(__uint_as_float(d[h][q]) < __uint_as_float(tau[q]));
             }
-            bool changed = false;
             if (__builtin_expect(hit != 0ull, 0)) {
-                // park the accumulators of the lanes that have a candidate
-                if ((hit >> lane) & 1ull) {
-                    uint4 *e = reinterpret_cast<uint4 *>(sm.ring[wave][ring_cnt + mask_prefix(hit)]);
-                    if constexpr (IS_U4) {
-                        e[0] = make_uint4(d[0][0], d[0][1], d[0][2], d[0][3]);
-                        e[1] = make_uint4(d[CPL - 1][0], d[CPL - 1][1], d[CPL - 1][2], d[CPL - 1][3]);
-                    } else {
-                        e[0] = make_uint4(__float_as_uint(d[0][0]), __float_as_uint(d[0][1]), __float_as_uint(d[0][2]),
-                                          __float_as_uint(d[0][3]));
-                        e[1] = make_uint4(__float_as_uint(d[CPL - 1][0]), __float_as_uint(d[CPL - 1][1]),
-                                          __float_as_uint(d[CPL - 1][2]), __float_as_uint(d[CPL - 1][3]));
-                    }
-                    e[2] = make_uint4((uint32_t)(sidx * SUB + lane * CPL), 0u, 0u, 0u);
-                }
+                if ((hit >> lane) & 1ull) sm.ring[wave][ring_cnt + mask_prefix(hit)] = (uint32_t)(sidx * SUB + lane * CPL);
                 ring_cnt += __popcll(hit);
             }
-            if (__builtin_expect(ring_cnt > RING_FLUSH || (ring_cnt > 0 && (iter & (RING_PERIOD - 1)) == RING_PERIOD - 1), 0)) {
-                scan_flush<V, QB, E, CPL, IS_U4>((LdsSmem *)&sm, wave_buf, ring_cnt);
+        };
+
+        // Everything that is not the scan itself happens between steps (a step = a pair of tiles in
+        // the main loop, one sub-tile in the tail): parked positions become list inserts, one wave
+        // per query re-evaluates the query's histogram now and then, thresholds are re-read.
+        const int my_q = wave % QB;             // the query this wave refreshes from the histogram
+        const int my_phase = 1 + 4 * my_q;
+        const bool refresher = wave < QB && my_q < nvalid_q;
+        const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf();
+        int step = 0;
+        auto flush_due = [&]() { return ring_cnt > RING_FLUSH || (ring_cnt > 0 && (step & (RING_PERIOD / 2 - 1)) == 0); };
+        // while the query had no bound when the item started: at steps 1, 2, 4 .. 32 as well
+        auto refresh_due = [&]() {
+            return refresher && ((gstep & 31) == my_phase || (cold_item && step <= 32 && (step & (step - 1)) == 0));
+        };
+        auto between_steps = [&]() {
+            bool changed = false;
+            if (flush_due()) {
+                scan_flush<KIND, E>((LdsSmem *)&sm, wave_buf, ring_cnt);
                 ring_cnt = 0;
                 changed = true;
             }
-            // bounds from the histogram: one wave per query and period (while the query had no
-            // bound at the start of the item: also at iterations 0, 1, 2, 4 .. 32)
-            const bool pow2 = cold_item && iter < 64 && (iter & (iter - 1)) == 0;
-            if (__builtin_expect(wave < QB && (pow2 || (iter & 63) == my_phase) && my_q < nvalid_q, 0))
-                scan_refresh<IS_U4>((LdsSmem *)&sm, my_q);
-            if (changed || iter < 64 || (iter & 7) == 7) reload_tau();
-            ++iter;
+            if (refresh_due()) scan_refresh<IS_U4>((LdsSmem *)&sm, my_q);
+            if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
 
         // Full tiles, two register sets used in turn.  The next tile is requested only after the
         // current one has arrived (the empty asm reads its last register), so that waiting for the
         // current tile never waits for the one just requested; the loads are unconditional (past the
-        // last full tile they re-read it and the data is dropped).
-        if (nfull > 0) {
+        // last full tile they re-read it and the data is dropped).  The inner loop holds no call.
+        int t = wave;   // next full tile of this wave
+        if (t < nfull) {
             const int last_full = nfull - 1;
             uint4 bufa[BATCH], bufb[BATCH];
-            load_full(wave < last_full ? wave : last_full, bufa);
-            for (int t = wave; t < nfull; t += 2 * TUNED_WAVES) {
-                asm volatile("" : "+v"(bufa[BATCH - 1].w) : : "memory");
-                load_full(t + TUNED_WAVES < last_full ? t + TUNED_WAVES : last_full, bufb);
+            load_full(t, bufa);
+            while (t + TUNED_WAVES < nfull) {
+                bool more;
+                do {
+                    asm volatile("" : "+v"(bufa[BATCH - 1].w) : : "memory");
+                    load_full(t + TUNED_WAVES, bufb);
 #pragma unroll
-                for (int i = 0; i < BATCH; ++i) process(bufa[i], t * BATCH + i);
-                if (t + TUNED_WAVES >= nfull) break;
-                asm volatile("" : "+v"(bufb[BATCH - 1].w) : : "memory");
-                load_full(t + 2 * TUNED_WAVES < last_full ? t + 2 * TUNED_WAVES : last_full, bufa);
+                    for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], t * BATCH + i);
+                    asm volatile("" : "+v"(bufb[BATCH - 1].w) : : "memory");
+                    load_full(t + 2 * TUNED_WAVES < last_full ? t + 2 * TUNED_WAVES : last_full, bufa);
 #pragma unroll
-                for (int i = 0; i < BATCH; ++i) process(bufb[i], (t + TUNED_WAVES) * BATCH + i);
+                    for (int i = 0; i < BATCH; ++i) scan_sub(bufb[i], (t + TUNED_WAVES) * BATCH + i);
+                    t += 2 * TUNED_WAVES;
+                    ++step;
+                    ++gstep;
+                    more = t + TUNED_WAVES < nfull;
+                    if (step < 32 || (step & 3) == 0) reload_tau();
+                } while (__builtin_expect(more && !flush_due() && !refresh_due(), 1));
+                between_steps();
+            }
+            if (t < nfull) {   // an odd tile left over: bufa holds it
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], t * BATCH + i);
+                ++step;
+                ++gstep;
+                between_steps();
             }
         }
         // sub-tiles after the last full tile (the very last one may be ragged), dealt round-robin
-        for (int sidx = nfull * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) process(load_ragged(sidx), sidx);
+        for (int sidx = nfull * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) {
+            scan_sub(load_ragged(sidx), sidx);
+            ++step;
+            ++gstep;
+            between_steps();
+        }
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
-        if (ring_cnt > 0) scan_flush<V, QB, E, CPL, IS_U4>((LdsSmem *)&sm, wave_buf, ring_cnt);
-        scan_finish_wave<QB, E>((LdsSmem *)&sm, wave_buf);
-        __threadfence();
-        __syncthreads();
+        if (ring_cnt > 0) scan_flush<KIND, E>((LdsSmem *)&sm, wave_buf, ring_cnt);
+        {
+            bool over = false;
+#pragma unroll
+            for (int q = 0; q < QB; ++q) over |= sm.ws[wave].cnt[q] > a.topk;
+            if (__builtin_expect(over, 0)) scan_finish_wave<QB, E>((LdsSmem *)&sm, wave_buf);
+        }
+        __syncthreads();   // (orders the waves' scratch writes within the block as well)
         if (wave < QB && sm.slot_out[wave] != nullptr) scan_merge_item<QB, E, KPAD>((LdsSmem *)&sm, block_scratch, sm.slot_out[wave]);
         __syncthreads();
     }
@@ -635,12 +697,9 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
     for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
 }
 
-template <int KIND, int E, int KPAD>
+template <int KIND, int E, int KPAD, int BATCH>
 static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
-    if (env_int("PQ_DEBUG", 0))
-        fprintf(stderr, "[pq] scan_tuned kind=%d: launching %d blocks, %d items, %d chunks\n", KIND, nblocks, a.nitems,
-                a.nchunks);
-    scan_tuned_kernel<KIND, E, KPAD><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
+    scan_tuned_kernel<KIND, E, KPAD, BATCH><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }
@@ -673,14 +732,19 @@ static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
     a.scratch = (uint64_t *)(ws + L.off_scratch);
 }
 
-static int launch_by_kind(pq_ctx *ctx, int kind, bool small, const TunedArgs &a, int nblocks) {
+// flat scans fetch one sub-tile per step, IVF items (streamed from HBM, short) four
+static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool ivf, const TunedArgs &a, int nblocks) {
+    if (ivf) {
+        if (kind == KIND_F32_M8) return launch_kind<KIND_F32_M8, 4, 128, 4>(ctx, a, nblocks);
+        return launch_kind<KIND_F32_M16, 4, 128, 4>(ctx, a, nblocks);
+    }
     switch (kind) {
         case KIND_F32_M8:
-            return small ? launch_kind<KIND_F32_M8, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_F32_M8, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024, 1>(ctx, a, nblocks);
         case KIND_F32_M16:
-            return small ? launch_kind<KIND_F32_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_F32_M16, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024, 1>(ctx, a, nblocks);
         default:
-            return small ? launch_kind<KIND_U4_M16, 4, 128>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_U4_M16, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024, 1>(ctx, a, nblocks);
     }
 }
 
@@ -698,6 +762,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     const bool small = topk <= 128;
     const int cap = 2 * (small ? 128 : 1024);
     const int nblocks = ctx->num_cu;
+    if (!small) return fail(ctx, PQ_EUNSUPPORTED, "scan_items: topk above 128");
     const StateLayout L = state_layout(qb, nq, cap, nblocks);
     if (L.total > state_bytes) return fail(ctx, PQ_EINVAL, "scan_items: state region too small");
     TunedArgs a;
@@ -711,7 +776,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
                                                      0xff800000u, a.hist, L.nhist);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    int rc = launch_by_kind(ctx, kind, small, a, nblocks);
+    int rc = launch_by_kind(ctx, kind, small, true, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
@@ -769,20 +834,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
                                                      is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    rc = launch_by_kind(ctx, kind, small, a, nblocks);
+    rc = launch_by_kind(ctx, kind, small, false, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
         ctx->ev_valid = 1;
-    }
-    if (env_int("PQ_DEBUG", 0)) {
-        (void)hipStreamSynchronize(ctx->stream);
-        uint32_t *h = (uint32_t *)malloc((size_t)ntau * 4);
-        (void)hipMemcpy(h, a.ncand, (size_t)ntau * 4, hipMemcpyDeviceToHost);
-        unsigned long long sum = 0; uint32_t mx = 0;
-        for (int i = 0; i < nq; ++i) { sum += h[i]; mx = h[i] > mx ? h[i] : mx; }
-        fprintf(stderr, "[pq] insert events per query: mean %.1f max %u (n=%lld, topk=%d)\n", (double)sum / nq, mx, (long long)n, topk);
-        free(h);
     }
     return launch_merge_topk(ctx, a.partial, (int)nchunks, ngroups, qb, kpad, nq, topk, is_u4, out_val, out_ids);
 }

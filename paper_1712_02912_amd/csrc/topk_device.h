@@ -84,6 +84,7 @@ __device__ __forceinline__ uint64_t wave_compact(uint64_t *buf, int &cnt, int k)
         for (int bit = 63; bit >= 0; --bit) {
             const uint64_t trial = v | ((1ull << bit) - 1ull);
             int c = 0;
+#pragma unroll 8
             for (int e = 0; e < E; ++e) {
                 const int idx = e * 64 + lane;
                 const uint64_t key = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;
@@ -94,6 +95,7 @@ __device__ __forceinline__ uint64_t wave_compact(uint64_t *buf, int &cnt, int k)
         }
         // in-place compaction, 64 keys per round: the write position never passes the read position
         int base = 0;
+#pragma unroll 4
         for (int e = 0; e < E; ++e) {
             const int idx = e * 64 + lane;
             const uint64_t key = idx < cnt ? key_load(buf + idx) : KEY_EMPTY;

@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--nq", type=int, default=1000)
     ap.add_argument("--topk", type=int, default=100)
     ap.add_argument("--cand", type=int, default=1000, help="candidates kept by the 16x4 integer scan before the rerank")
-    ap.add_argument("--cpu-queries", type=int, default=512)
+    ap.add_argument("--cpu-queries", type=int, default=1000, help="queries of the workload the oracle is timed on")
     ap.add_argument("--skip-16x4", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -102,20 +102,16 @@ def main():
     for _ in range(args.warmup):
         step8()
     sync()
+    # duration of the scan kernel of every timed step, from the HIP events the library records around the
+    # launch on its own stream (reading them waits for that step's kernel only)
     kernel_ms = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
         luts8 = step8()
-        kernel_ms.append(None)
+        kernel_ms.append(ctx.pq_last_scan_kernel_ms())
     sync()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    # kernel duration from the events the library records on its own stream (last launch of the timed region,
-    # then a few more launches outside the timed region for an average)
-    durs = [ctx.pq_last_scan_kernel_ms()]
-    for _ in range(3):
-        step8()
-        durs.append(ctx.pq_last_scan_kernel_ms())
-    scan_ms = float(np.mean(durs))
+    scan_ms = float(np.mean(kernel_ms))
     alg_bytes = float(args.n) * 8 * args.nq
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
     result = {
@@ -126,7 +122,7 @@ def main():
                                "fp32 LUTs 8x256 built each step, top-%d" % (args.n, args.nq, args.topk)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("scan_f32_pq8x8_config1_pmc.txt"),
-                     "kernel": "scan_f32_kernel<8>", "kernel_ms": scan_ms,
+                     "kernel": "scan_tuned_kernel<F32_M8, top<=128>", "kernel_ms": scan_ms,
                      "algorithmic_bytes": alg_bytes,
                      "note": "algorithmic bytes = 8 B per code per query pass; 4 queries share each code fetched, "
                              "so HBM traffic is below the algorithmic figure (see DESIGN.md)"},
@@ -148,18 +144,20 @@ def main():
         for _ in range(args.warmup):
             step16()
         sync()
+        kernel16_ms = []
         t0 = time.perf_counter()
         for _ in range(args.steps):
             step16()
+            kernel16_ms.append(ctx.pq_last_scan_kernel_ms())
         sync()
         ms16 = (time.perf_counter() - t0) * 1e3 / args.steps
-        scan16_ms = ctx.pq_last_scan_kernel_ms()
+        scan16_ms = float(np.mean(kernel16_ms))
         ach16 = alg_bytes / (scan16_ms * 1e-3) / 1e9
         result["pq16x4"] = {"value": args.n * args.nq / (ms16 * 1e-3) / 1e9, "unit": "G codes/s", "ms_per_step": ms16,
                             "dtype": "u8 tables, integer sums", "workload": "PQ 16x4 packed codes (BASELINE config 2): "
-                            "tables, qmax pre-scan, 8-bit tables, integer scan top-1000, fp32 rerank top-%d" % args.topk,
+                            "tables, qmax pre-scan, 8-bit tables, integer scan top-%d, fp32 rerank top-%d" % (args.cand, args.topk),
                             "roofline": {"bound": "hbm", "achieved": ach16, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": "scan_u4_kernel", "kernel_ms": scan16_ms,
+                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": "scan_tuned_kernel<U4_M16, top<=%d>" % (128 if args.cand <= 128 else 1024), "kernel_ms": scan16_ms,
                                          "traffic": read_traffic("scan_u4_pq16x4_config2_pmc.txt")}}
         del codes4
 

@@ -56,7 +56,7 @@ __device__ __forceinline__ void block_merge_lists(uint64_t *block_scratch, int (
             cnt += cw;
             if (cnt > k) wave_compact<E>(acc, cnt, k);
         }
-        __threadfence();
+        list_fence();
         uint64_t *out = out_item + (size_t)q * KPAD;
         for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
     }
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_generic_kernel(ScanArgs a, 
     }
     if (st.cnt[0] > st.k) wave_compact<E>(st.buf[0], st.cnt[0], st.k);
     if (lane == 0) wave_cnt[wave][0] = st.cnt[0];
-    __threadfence();
+    list_fence();
     __syncthreads();
     block_merge_lists<QB, E, KPAD>(block_scratch, wave_cnt, a.topk, a.partial + (size_t)blockIdx.x * QB * KPAD);
 }

@@ -275,31 +275,58 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
             const v4u v = *(const __attribute__((address_space(3))) v4u *)(lut_bytes + off);
             return make_uint4(v.x, v.y, v.z, v.w);
         }, acc);
-#pragma unroll 1
-        for (int q = 0; q < nvalid && q < QB; ++q) {
-            // candidates satisfy value < eff: the wave's own bound is strict, the block's is "<="
-            const uint32_t shared = sm->tau_blk[q];
+        // codes outside the item (and lanes without an entry) never qualify
+        bool ok[CPL];
+#pragma unroll
+        for (int h = 0; h < CPL; ++h) ok[h] = have && pos + h >= skip && pos + h < ncodes;
+        // candidates satisfy value < eff: the wave's own bound is strict, the block's is "<=".
+        // Lane q works out the bound of query q; the loop below picks it up with a lane read.
+        uint32_t eff_lane;
+        {
+            const int ql = lane & (QB - 1);
+            const uint32_t shared = sm->tau_blk[ql];
             const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
-            const uint32_t own = ws->own_ord[q];
-            const uint32_t eff = own < loose ? own : loose;
+            const uint32_t own = ws->own_ord[ql];
+            eff_lane = own < loose ? own : loose;
+        }
+        // bit h * QB + q of m: code h of this lane qualifies for query q
+        uint32_t m = 0;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const uint32_t eff = __builtin_amdgcn_readlane(eff_lane, q);
+#pragma unroll
+            for (int h = 0; h < CPL; ++h) {
+                uint32_t ord;
+                if constexpr (IS_U4) ord = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                else ord = f32_to_ord(__uint_as_float(acc[h][q]));
+                if (ok[h] && q < nvalid && ord < eff) m |= 1u << (h * QB + q);
+            }
+        }
+        uint32_t qmask = 0;   // queries with a qualifying code in any lane (uniform)
+#pragma unroll
+        for (int q = 0; q < QB; ++q)
+            if (__ballot((m & (((1u << QB) | 1u) << q)) != 0u) != 0ull) qmask |= 1u << q;
+        while (qmask != 0u) {
+            const int q = __builtin_ctz(qmask);
+            qmask &= qmask - 1u;
             uint64_t *buf = wave_buf + (size_t)q * CAP;
             const uint32_t ref = IS_U4 ? 0u : sm->tau_ref[q];
 #pragma unroll
             for (int h = 0; h < CPL; ++h) {
-                uint32_t ord;
-                if constexpr (IS_U4) {
-                    const int p = q >> 1;
-                    const uint32_t pk = p == 0 ? acc[h][0] : p == 1 ? acc[h][1] : p == 2 ? acc[h][2] : acc[h][3];
-                    ord = (pk >> (16 * (q & 1))) & 0xffffu;
-                } else {
-                    const uint32_t bits = q == 0 ? acc[h][0] : q == 1 ? acc[h][1] : q == 2 ? acc[h][2] : acc[h][3];
-                    ord = f32_to_ord(__uint_as_float(bits));
-                }
-                const bool pass = have && pos + h >= skip && pos + h < ncodes && ord < eff;
+                const bool pass = ((m >> (h * QB + q)) & 1u) != 0u;
                 const uint64_t mask = __ballot(pass);
                 if (mask == 0ull) continue;
                 int cnt = ws->cnt[q];
                 if (pass) {
+                    uint32_t ord;
+                    if constexpr (IS_U4) {
+                        const int pp = q >> 1;
+                        const uint32_t pk = pp == 0 ? acc[h][0] : pp == 1 ? acc[h][1] : pp == 2 ? acc[h][2] : acc[h][3];
+                        ord = (pk >> (16 * (q & 1))) & 0xffffu;
+                    } else {
+                        const uint32_t bits = q == 0 ? acc[h][0] : q == 1 ? acc[h][1] : q == 2 ? acc[h][2] : acc[h][3];
+                        ord = f32_to_ord(__uint_as_float(bits));
+                    }
                     key_store(buf + cnt + mask_prefix(mask), ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
                     if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
                         uint32_t bin;
@@ -393,7 +420,7 @@ __device__ __noinline__ void scan_merge_item(LdsSmem *sm, uint64_t *block_scratc
         cnt += cw;
         if (cnt > k) wave_compact<E>(acc, cnt, k);
     }
-    if (cnt > 0) __threadfence();
+    if (cnt > 0) list_fence();
     for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
 }
 
@@ -531,20 +558,21 @@ void scan_tuned_kernel(TunedArgs a) {
         // Float: the four thresholds as float bits; integer: the eight as four packed pairs.
         uint32_t tau[4];
         auto reload_tau = [&]() {
-            uint32_t t[QB];
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                const uint32_t shared = sm.tau_blk[q];
-                const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
-                const uint32_t own = sm.ws[wave].own_ord[q];
-                const uint32_t eff = own < loose ? own : loose;
-                if constexpr (IS_U4) t[q] = q < nvalid_q ? eff : 0u;
-                else t[q] = __float_as_uint(ord_to_f32(eff));
-            }
+            // lane q works out the bound of query q (own bound strict, the block's bound "<="),
+            // lane reads hand the values to the whole wave as scalars
+            const int ql = lane & (QB - 1);
+            const uint32_t shared = sm.tau_blk[ql];
+            const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
+            const uint32_t own = sm.ws[wave].own_ord[ql];
+            uint32_t eff = own < loose ? own : loose;
+            if constexpr (IS_U4) eff = ql < nvalid_q ? eff : 0u;
+            else eff = __float_as_uint(ord_to_f32(eff));
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if constexpr (IS_U4) tau[p] = t[2 * p] | (t[2 * p + 1] << 16);
-                else tau[p] = t[p];
+                if constexpr (IS_U4)
+                    tau[p] = __builtin_amdgcn_readlane(eff, 2 * p) | (__builtin_amdgcn_readlane(eff, 2 * p + 1) << 16);
+                else
+                    tau[p] = __builtin_amdgcn_readlane(eff, p);
             }
         };
         reload_tau();

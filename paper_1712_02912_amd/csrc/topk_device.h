@@ -28,14 +28,18 @@ __device__ __forceinline__ int mask_prefix(uint64_t mask) {
     return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// Scratch buffers are written and read back by different lanes (and, at the end of a block,
-// different waves): go through the device-coherent level for both directions.
+// Candidate lists in device scratch are written and read back by different lanes of a wave and,
+// when a block merges its lists, by different waves of the same block: never by another block.
+// Work-group scope is therefore enough, which keeps the lists in the caches of the block's own CU
+// and XCD (device scope would send every access, and every fence, past the L2 to memory).
 __device__ __forceinline__ void key_store(uint64_t *p, uint64_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 __device__ __forceinline__ uint64_t key_load(const uint64_t *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
+// orders the list accesses of the block's waves (stores before, loads after)
+__device__ __forceinline__ void list_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
 
 // k-th smallest (1-based) of the wave's 64*E keys, by bitwise bisection on the key value:
 // the smallest v with count(key <= v) >= k.  Every lane must call it; the result is uniform.
@@ -60,7 +64,7 @@ __device__ __forceinline__ uint64_t wave_select_kth(const uint64_t (&key)[E], in
 template <int E>
 __device__ __forceinline__ uint64_t wave_compact(uint64_t *buf, int &cnt, int k) {
     const int lane = lane_id();
-    __threadfence();  // the appends of every lane have reached the coherent level
+    list_fence();  // the appends of every lane are visible to the other lanes
     if constexpr (E <= 8) {
         uint64_t key[E];
 #pragma unroll

@@ -42,6 +42,8 @@ struct WaveState {
     uint32_t own_ord[8];   // k-th smallest value of the wave's own list, ord_inf while not full
 };
 
+// wave list capacity in units of 64 keys: 384 keys for results of up to 128, 2048 for up to 1024
+constexpr int E_SMALL = 6, E_LARGE = 32;
 constexpr int RING_FLUSH = 32;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
 constexpr int RING_CAP = RING_FLUSH + 2 * 64 * 4;   // two tiles (of up to 4 sub-tiles of 64 lanes) fit behind an unflushed ring
@@ -54,6 +56,7 @@ struct __align__(16) TunedSmem {
     uint32_t ring[TUNED_WAVES][RING_CAP];
     WaveState ws[TUNED_WAVES];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
+    int out_cnt[8];        // keys handed to the item's result list of each query so far
     uint32_t tau_ref[8];   // histogram reference per query (float path)
     // per item, written at its start: where the state of the query in each slot lives
     uint32_t *hist[8];
@@ -239,9 +242,10 @@ __device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, in
 // Rare path of the scan loop: turn the `n` positions parked in the wave's ring into list inserts.
 // Lane e takes entry e (64 at a time): it reloads the 16 code bytes at that position and
 // recomputes their values exactly as the lane that parked them did (same rotation, same order
-// of additions).  For every query the candidates (value below the current bound) are appended
-// to the wave's list and counted in the query's histogram; a list that is nearly full is
-// compacted.  Entries are in scan order, so ids still reach a list in increasing order.
+// of additions).  Every lane then appends the (value, id) keys of its own codes that are below
+// the current bound of a query to the wave's list of that query (slot from an LDS counter) and
+// counts them in the query's histogram.  Before a batch, a list that the batch could overflow
+// is cut to its k smallest keys.
 template <int KIND, int E>
 __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;
@@ -249,6 +253,7 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
     constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;
     constexpr int CPL = 16 / NT;
     constexpr int CAP = 64 * E;
+    static_assert(CAP - 64 * CPL >= 128 && (E <= 8 || CAP - 64 * CPL >= 1024), "a compacted list must leave room for one batch");
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     LdsWaveState *ws = &sm->ws[wave];
     const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
@@ -256,7 +261,16 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
     const uint8_t *chunk_ptr = sm->chunk_ptr;
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const __attribute__((address_space(3))) char *lut_bytes = (const __attribute__((address_space(3))) char *)sm->lut;
+    const int ql = lane & (QB - 1);
     for (int base = 0; base < n; base += 64) {
+        // room for 64 * CPL more keys in every list
+        uint32_t full = (uint32_t)__ballot(ws->cnt[ql] > CAP - 64 * CPL) & ((1u << QB) - 1u);
+        while (full != 0u) {
+            const int q = __builtin_ctz(full);
+            full &= full - 1u;
+            const int cnt = scan_compact<E, IS_U4>(sm, wave_buf + (size_t)q * CAP, ws->cnt[q], q);
+            if (lane == 0) ws->cnt[q] = cnt;
+        }
         const bool have = base + lane < n;
         const int pos = have ? (int)sm->ring[wave][base + lane] : 0;   // position of the 16 bytes' first code
         uint4 c = make_uint4(0, 0, 0, 0);
@@ -283,7 +297,6 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
         // Lane q works out the bound of query q; the loop below picks it up with a lane read.
         uint32_t eff_lane;
         {
-            const int ql = lane & (QB - 1);
             const uint32_t shared = sm->tau_blk[ql];
             const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
             const uint32_t own = ws->own_ord[ql];
@@ -302,51 +315,43 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
                 if (ok[h] && q < nvalid && ord < eff) m |= 1u << (h * QB + q);
             }
         }
-        uint32_t qmask = 0;   // queries with a qualifying code in any lane (uniform)
-#pragma unroll
-        for (int q = 0; q < QB; ++q)
-            if (__ballot((m & (((1u << QB) | 1u) << q)) != 0u) != 0ull) qmask |= 1u << q;
-        while (qmask != 0u) {
-            const int q = __builtin_ctz(qmask);
-            qmask &= qmask - 1u;
-            uint64_t *buf = wave_buf + (size_t)q * CAP;
-            const uint32_t ref = IS_U4 ? 0u : sm->tau_ref[q];
-#pragma unroll
-            for (int h = 0; h < CPL; ++h) {
-                const bool pass = ((m >> (h * QB + q)) & 1u) != 0u;
-                const uint64_t mask = __ballot(pass);
-                if (mask == 0ull) continue;
-                int cnt = ws->cnt[q];
-                if (pass) {
-                    uint32_t ord;
-                    if constexpr (IS_U4) {
-                        const int pp = q >> 1;
-                        const uint32_t pk = pp == 0 ? acc[h][0] : pp == 1 ? acc[h][1] : pp == 2 ? acc[h][2] : acc[h][3];
-                        ord = (pk >> (16 * (q & 1))) & 0xffffu;
-                    } else {
-                        const uint32_t bits = q == 0 ? acc[h][0] : q == 1 ? acc[h][1] : q == 2 ? acc[h][2] : acc[h][3];
-                        ord = f32_to_ord(__uint_as_float(bits));
-                    }
-                    key_store(buf + cnt + mask_prefix(mask), ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
-                    if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
-                        uint32_t bin;
-                        if (IS_U4) {
-                            bin = ord < HIST_BINS ? ord : HIST_BINS - 1;
-                        } else {
-                            const uint32_t below = (ref - ord) >> HIST_SHIFT;
-                            bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
-                        }
-                        __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                }
-                cnt += __popcll(mask);
-                if (cnt > CAP - 64) cnt = scan_compact<E, IS_U4>(sm, buf, cnt, q);
-                if (lane == 0) {
-                    ws->cnt[q] = cnt;
-                    __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)__popcll(mask), __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                }
+        // per lane: one key per set bit
+        uint32_t bits = m;
+        while (bits != 0u) {
+            const int b = __builtin_ctz(bits);
+            bits &= bits - 1u;
+            const int q = b & (QB - 1), h = b / QB;
+            const uint32_t lo = h == 0 ? acc[0][0] : acc[CPL - 1][0], l1 = h == 0 ? acc[0][1] : acc[CPL - 1][1];
+            const uint32_t l2 = h == 0 ? acc[0][2] : acc[CPL - 1][2], l3 = h == 0 ? acc[0][3] : acc[CPL - 1][3];
+            uint32_t ord;
+            if constexpr (IS_U4) {
+                const int pp = q >> 1;
+                const uint32_t pk = pp == 0 ? lo : pp == 1 ? l1 : pp == 2 ? l2 : l3;
+                ord = (pk >> (16 * (q & 1))) & 0xffffu;
+            } else {
+                ord = f32_to_ord(__uint_as_float(q == 0 ? lo : q == 1 ? l1 : q == 2 ? l2 : l3));
             }
+            const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+            key_store(wave_buf + (size_t)q * CAP + slot, ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
+            const uint32_t ref = IS_U4 ? 0u : sm->tau_ref[q];
+            if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
+                uint32_t bin;
+                if (IS_U4) {
+                    bin = ord < HIST_BINS ? ord : HIST_BINS - 1;
+                } else {
+                    const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                    bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
+                }
+                __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // candidates seen per query (paces the histogram evaluations)
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            int added = __popcll(__ballot((m >> q) & 1u));
+            if (CPL == 2) added += __popcll(__ballot((m >> (QB + q)) & 1u));
+            if (added != 0 && lane == 0)
+                __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -357,22 +362,23 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
 constexpr uint32_t REFRESH_MIN_NEW = 16;
 template <bool IS_U4>
 __device__ __noinline__ void scan_refresh(LdsSmem *sm, int q) {
+    // the four device words of the query are independent of one another: one round trip
     const uint32_t g = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t n_v = __hip_atomic_load(sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t mark_v = __hip_atomic_load(sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t ref_v = IS_U4 ? 0u : __hip_atomic_load(sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane_id() == 0) __hip_atomic_fetch_min(&sm->tau_blk[q], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     uint32_t ref = 0;
     if (!IS_U4) {
         ref = __builtin_amdgcn_readfirstlane(sm->tau_ref[q]);
         if (ref == TAU_REF_UNSET) {
-            ref = __builtin_amdgcn_readfirstlane(
-                __hip_atomic_load(sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            ref = __builtin_amdgcn_readfirstlane(ref_v);
             if (ref == TAU_REF_UNSET) return;
             if (lane_id() == 0) sm->tau_ref[q] = ref;
         }
     }
-    const uint32_t n = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    const uint32_t mark = __builtin_amdgcn_readfirstlane(
-        __hip_atomic_load(sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const uint32_t n = __builtin_amdgcn_readfirstlane(n_v);
+    const uint32_t mark = __builtin_amdgcn_readfirstlane(mark_v);
     if (n - mark < REFRESH_MIN_NEW) return;
     uint32_t won = 0;
     if (lane_id() == 0) {
@@ -399,6 +405,35 @@ __device__ __noinline__ void scan_finish_wave(LdsSmem *sm, uint64_t *wave_buf) {
         if (cnt > sm->topk) {
             wave_compact<E>(wave_buf + (size_t)q * CAP, cnt, sm->topk);
             if (lane_id() == 0) ws->cnt[q] = cnt;
+        }
+    }
+}
+
+// End of item, per wave: the keys of the wave's lists that are within the block's bound of their
+// query go straight to the item's result list of that query (position from a counter in LDS).
+// Keys above the bound cannot be among the k smallest.  If more than KPAD keys arrive for a query
+// the surplus is dropped here and the query is merged from the lists instead (scan_merge_item).
+template <int QB, int E, int KPAD>
+__device__ __noinline__ void scan_emit_wave(LdsSmem *sm, uint64_t *wave_buf) {
+    constexpr int CAP = 64 * E;
+    const int lane = lane_id();
+    LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
+    list_fence();
+    for (int q = 0; q < sm->nvalid && q < QB; ++q) {
+        const int cnt = ws->cnt[q];
+        if (cnt == 0) continue;
+        const uint32_t bound = sm->tau_blk[q];
+        uint64_t *out = sm->slot_out[q];
+        const uint64_t *buf = wave_buf + (size_t)q * CAP;
+        for (int i0 = 0; i0 < cnt; i0 += 64) {
+            const uint64_t key = i0 + lane < cnt ? key_load(buf + i0 + lane) : KEY_EMPTY;
+            const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound;
+            const uint64_t mask = __ballot(pass);
+            if (mask == 0ull) continue;
+            int at = 0;
+            if (lane == 0) at = __hip_atomic_fetch_add(&sm->out_cnt[q], __popcll(mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            at = __builtin_amdgcn_readfirstlane(at) + (int)mask_prefix(mask);
+            if (pass && at < KPAD) out[at] = key;
         }
     }
 }
@@ -510,6 +545,7 @@ void scan_tuned_kernel(TunedArgs a) {
             if (s == 0) sm.topk = a.topk;
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
+        if (threadIdx.x < 8) sm.out_cnt[threadIdx.x] = 0;
         __syncthreads();
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
@@ -636,15 +672,20 @@ void scan_tuned_kernel(TunedArgs a) {
         // Everything that is not the scan itself happens between steps (a step = a pair of tiles in
         // the main loop, one sub-tile in the tail): parked positions become list inserts, one wave
         // per query re-evaluates the query's histogram now and then, thresholds are re-read.
-        const int my_q = wave % QB;             // the query this wave refreshes from the histogram
-        const int my_phase = 1 + 4 * my_q;
-        const bool refresher = wave < QB && my_q < nvalid_q;
+        // Every wave takes its turn at refreshing one query from the device state: the 16 / QB waves
+        // that share a query alternate, so that each query is looked at every 32 steps of the block
+        // and no wave carries more of this work than another.
+        const int my_q = wave % QB;
+        const int my_phase = 1 + 4 * my_q + 32 * (wave / QB);
+        constexpr int REFRESH_MASK = 32 * (TUNED_WAVES / QB) - 1;
+        const bool refresher = my_q < nvalid_q;
         const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf();
         int step = 0;
         auto flush_due = [&]() { return ring_cnt > RING_FLUSH || (ring_cnt > 0 && (step & (RING_PERIOD / 2 - 1)) == 0); };
         // while the query had no bound when the item started: at steps 1, 2, 4 .. 32 as well
         auto refresh_due = [&]() {
-            return refresher && ((gstep & 31) == my_phase || (cold_item && step <= 32 && (step & (step - 1)) == 0));
+            return refresher && ((gstep & REFRESH_MASK) == my_phase ||
+                                 (wave < QB && cold_item && step <= 32 && (step & (step - 1)) == 0));
         };
         auto between_steps = [&]() {
             bool changed = false;
@@ -709,8 +750,17 @@ void scan_tuned_kernel(TunedArgs a) {
             for (int q = 0; q < QB; ++q) over |= sm.ws[wave].cnt[q] > a.topk;
             if (__builtin_expect(over, 0)) scan_finish_wave<QB, E>((LdsSmem *)&sm, wave_buf);
         }
+        scan_emit_wave<QB, E, KPAD>((LdsSmem *)&sm, wave_buf);
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
-        if (wave < QB && sm.slot_out[wave] != nullptr) scan_merge_item<QB, E, KPAD>((LdsSmem *)&sm, block_scratch, sm.slot_out[wave]);
+        if (wave < QB && sm.slot_out[wave] != nullptr) {
+            const int got = sm.out_cnt[wave];
+            if (__builtin_expect(got > KPAD, 0)) {
+                scan_merge_item<QB, E, KPAD>((LdsSmem *)&sm, block_scratch, sm.slot_out[wave]);
+            } else {
+                uint64_t *out = sm.slot_out[wave];
+                for (int i = got + lane; i < KPAD; i += 64) out[i] = KEY_EMPTY;
+            }
+        }
         __syncthreads();
     }
 }
@@ -763,22 +813,22 @@ static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
 // flat scans fetch one sub-tile per step, IVF items (streamed from HBM, short) four
 static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool ivf, const TunedArgs &a, int nblocks) {
     if (ivf) {
-        if (kind == KIND_F32_M8) return launch_kind<KIND_F32_M8, 4, 128, 4>(ctx, a, nblocks);
-        return launch_kind<KIND_F32_M16, 4, 128, 4>(ctx, a, nblocks);
+        if (kind == KIND_F32_M8) return launch_kind<KIND_F32_M8, E_SMALL, 128, 4>(ctx, a, nblocks);
+        return launch_kind<KIND_F32_M16, E_SMALL, 128, 4>(ctx, a, nblocks);
     }
     switch (kind) {
         case KIND_F32_M8:
-            return small ? launch_kind<KIND_F32_M8, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, 32, 1024, 1>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_F32_M8, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, E_LARGE, 1024, 1>(ctx, a, nblocks);
         case KIND_F32_M16:
-            return small ? launch_kind<KIND_F32_M16, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, 32, 1024, 1>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_F32_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
         default:
-            return small ? launch_kind<KIND_U4_M16, 4, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, 32, 1024, 1>(ctx, a, nblocks);
+            return small ? launch_kind<KIND_U4_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
     }
 }
 
 size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu) {
     const int qb = kind == KIND_U4_M16 ? 8 : 4;
-    const int cap = 2 * (topk <= 128 ? 128 : 1024);
+    const int cap = 64 * (topk <= 128 ? E_SMALL : E_LARGE);
     return state_layout(qb, nq, cap, num_cu).total;
 }
 
@@ -788,7 +838,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
                       uint32_t **tau_global_out) {
     const int qb = kind == KIND_U4_M16 ? 8 : 4;
     const bool small = topk <= 128;
-    const int cap = 2 * (small ? 128 : 1024);
+    const int cap = 64 * (small ? E_SMALL : E_LARGE);
     const int nblocks = ctx->num_cu;
     if (!small) return fail(ctx, PQ_EUNSUPPORTED, "scan_items: topk above 128");
     const StateLayout L = state_layout(qb, nq, cap, nblocks);
@@ -822,7 +872,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int tile = 64 * (16 / cb) * 1;   // codes per wave tile (BATCH sub-tiles)
     const bool small = topk <= 128;
     const int kpad = small ? 128 : 1024;
-    const int cap = 2 * kpad;
+    const int cap = 64 * (small ? E_SMALL : E_LARGE);
     const int ngroups = (nq + qb - 1) / qb;
     const int64_t block_tile = (int64_t)tile * TUNED_WAVES;
     // persistent blocks: one per CU (64 KB of tables and 16 waves of 128 registers fill a CU)

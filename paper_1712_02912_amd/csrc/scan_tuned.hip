@@ -650,13 +650,17 @@ void scan_tuned_kernel(TunedArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x002, 8 * NT, 0);
             uint64_t hit = 0;
             if constexpr (IS_U4) {
-                // packed fields: (x | 0x8000) - tau keeps bit 15 iff x >= tau
-                uint32_t allge = 0x80008000u;
+                // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold
+                // wraps (sets bit 15) iff one of them is below the threshold
+                typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+                uint32_t below = 0;
 #pragma unroll
-                for (int h = 0; h < CPL; ++h)
-#pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) allge &= (d[h][pp] | 0x80008000u) - tau[pp];
-                hit = __ballot((allge & 0x80008000u) != 0x80008000u);
+                for (int pp = 0; pp < 4; ++pp) {
+                    u16x2 v = __builtin_bit_cast(u16x2, d[0][pp]);
+                    if (CPL == 2) v = __builtin_elementwise_min(v, __builtin_bit_cast(u16x2, d[CPL - 1][pp]));
+                    below |= __builtin_bit_cast(uint32_t, (u16x2)(v - __builtin_bit_cast(u16x2, tau[pp])));
+                }
+                hit = __ballot((below & 0x80008000u) != 0u);
             } else {
 #pragma unroll
                 for (int h = 0; h < CPL; ++h)

@@ -49,6 +49,11 @@ struct TunedArgs {
     const int32_t *pairs_by_list;    // pair = query * nprobe + rank, grouped by list
     const uint32_t *pair_out;        // [npairs] index of the pair's first output list
     int nprobe;
+    // pruned float scan: 16-bit tables in slot order [group][entry][table] (8 queries x u16 each),
+    // and per query the sum of the table minima and the scale of the 16-bit tables
+    const uint4 *qtabs;
+    const float *prune_off;
+    const float *prune_scale;
 };
 
 static inline int env_int(const char *name, int dflt) {

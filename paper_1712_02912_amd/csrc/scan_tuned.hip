@@ -46,14 +46,19 @@ struct WaveState {
 constexpr int E_SMALL = 6, E_LARGE = 32;
 constexpr int RING_FLUSH = 32;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
-constexpr int RING_CAP = RING_FLUSH + 2 * 64 * 4;   // two tiles (of up to 4 sub-tiles of 64 lanes) fit behind an unflushed ring
 
-struct __align__(16) TunedSmem {
+// RING: ring entries per wave; FLUT: floats of plain per-query tables kept for exact values
+// (pruned float scan only)
+template <int RING, int FLUT>
+struct __align__(16) TunedSmemT {
     uint4 lut[4096];
     uint8_t qstage[8][256];
     // Per wave: lanes that found a candidate park the position of their 16 code bytes here; the
     // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
-    uint32_t ring[TUNED_WAVES][RING_CAP];
+    uint32_t ring[TUNED_WAVES][RING];
+    float flut[FLUT];        // [slot][table][entry], pruned float scan
+    float prune_off[8];      // per slot: sum of the table minima, and the scale of the 16-bit tables
+    float prune_scale[8];
     WaveState ws[TUNED_WAVES];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
     int out_cnt[8];        // keys handed to the item's result list of each query so far
@@ -73,15 +78,22 @@ struct __align__(16) TunedSmem {
     int nvalid;                // slots in use
     int topk;
     int item;
+    int group;                 // flat scan: query group of the item
 };
 
 // The helpers below are real functions (kept out of line so that their registers do not weigh on
-// the scan loop); they address the block's shared structure through an LDS-qualified pointer.
-typedef __attribute__((address_space(3))) TunedSmem LdsSmem;
+// the scan loop); they address the block's shared structure (SM, one of the TunedSmemT types)
+// through an LDS-qualified pointer.
+#define LDS_PTR(T) __attribute__((address_space(3))) T *
 typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 
-enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2 };
+// KIND_F32P_M8: the 8 x 256 float scan with pruning by 16-bit lower bounds (see scan_flush_pruned)
+enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3 };
+constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain float scan
+constexpr int PRUNE_INIT = 4096;           // codes looked at for the first bound of every query
+constexpr int PRUNE_MARGIN = 8;      // slack of the integer threshold, in table units
+constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the minima and the first bound
 
 // rotate the bytes of a 64-bit code right by r bytes (r in 0..7): byte s of the result is
 // byte (s + r) & 7 of the input
@@ -211,15 +223,16 @@ __device__ __forceinline__ int hist_threshold(const uint32_t *hist, int k) {
     return __shfl(bin, first);
 }
 
-__device__ __forceinline__ void publish_bound(LdsSmem *sm, int q, uint32_t ord) {
+template <class SM>
+__device__ __forceinline__ void publish_bound(LDS_PTR(SM) sm, int q, uint32_t ord) {
     __hip_atomic_fetch_min(&sm->tau_blk[q], ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     atomicMin(sm->tau_global[q], ord);
 }
 
 // Rare path: the candidate list of query q of this wave is nearly full.  Keep its k smallest
 // keys, make the k-th the wave's own bound and share it.  Returns the new count.
-template <int E, bool IS_U4>
-__device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, int q) {
+template <class SM, int E, bool INTVAL>
+__device__ __noinline__ int scan_compact(LDS_PTR(SM) sm, uint64_t *buf, int cnt, int q) {
     const int lane = lane_id();
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     const uint64_t kth = wave_compact<E>(buf, cnt, sm->topk);
@@ -227,7 +240,7 @@ __device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, in
         const uint32_t kord = (uint32_t)(kth >> 32);
         if (lane == 0) ws->own_ord[q] = kord;
         publish_bound(sm, q, kord);
-        if (!IS_U4 && sm->tau_ref[q] == TAU_REF_UNSET) {
+        if (!INTVAL && sm->tau_ref[q] == TAU_REF_UNSET) {
             // the first bound published for a query becomes the reference of its histogram
             uint32_t expected = TAU_REF_UNSET;
             __hip_atomic_compare_exchange_strong(sm->tau_ref_global[q], &expected, kord, __ATOMIC_RELAXED,
@@ -246,8 +259,8 @@ __device__ __noinline__ int scan_compact(LdsSmem *sm, uint64_t *buf, int cnt, in
 // the current bound of a query to the wave's list of that query (slot from an LDS counter) and
 // counts them in the query's histogram.  Before a batch, a list that the batch could overflow
 // is cut to its k smallest keys.
-template <int KIND, int E>
-__device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) {
+template <class SM, int KIND, int E>
+__device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;
     constexpr int QB = IS_U4 ? 8 : 4;
     constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;
@@ -268,7 +281,7 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
         while (full != 0u) {
             const int q = __builtin_ctz(full);
             full &= full - 1u;
-            const int cnt = scan_compact<E, IS_U4>(sm, wave_buf + (size_t)q * CAP, ws->cnt[q], q);
+            const int cnt = scan_compact<SM, E, IS_U4>(sm, wave_buf + (size_t)q * CAP, ws->cnt[q], q);
             if (lane == 0) ws->cnt[q] = cnt;
         }
         const bool have = base + lane < n;
@@ -356,12 +369,129 @@ __device__ __noinline__ void scan_flush(LdsSmem *sm, uint64_t *wave_buf, int n) 
     }
 }
 
+// Insert path of the pruned float scan.  The scan loop works on 16-bit tables
+//   L[j][b] = min(4095, floor((D[j][b] - min_b D[j][b]) * scale)),
+// whose sums are lower bounds (in table units, above the sum of the minima) of the float
+// distances: a code whose bound reaches the threshold derived from the query's current bound
+// cannot be a candidate, and almost every code is dismissed that way without a float operation
+// (the lower-bound pruning of PQ Fast Scan, Section 4.2, with tables that need no grouping).
+// Here the parked codes get their exact distances: the lane re-reads its codes, repeats the
+// integer test against the current thresholds, and for every (code, query) that still passes adds
+// the eight float entries in table order -- the order of the plain definition, Eq. (adc1) -- tests the
+// result against the float bound and appends it to the wave's list of the query.
+template <class SM, int E>
+__device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
+    constexpr int QB = 8, CPL = 2, CAP = 64 * E;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    LdsWaveState *ws = &sm->ws[wave];
+    const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
+    const uint32_t row0 = (uint32_t)sm->code_begin;
+    const uint8_t *chunk_ptr = sm->chunk_ptr;
+    typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+    const __attribute__((address_space(3))) char *lut_bytes = (const __attribute__((address_space(3))) char *)sm->lut;
+    const int ql = lane & (QB - 1);
+    for (int base = 0; base < n; base += 64) {
+        // room for 64 * CPL more keys in every list
+        uint32_t full = (uint32_t)__ballot(ws->cnt[ql] > CAP - 64 * CPL) & ((1u << QB) - 1u);
+        while (full != 0u) {
+            const int q = __builtin_ctz(full);
+            full &= full - 1u;
+            const int cnt = scan_compact<SM, E, false>(sm, wave_buf + (size_t)q * CAP, ws->cnt[q], q);
+            if (lane == 0) ws->cnt[q] = cnt;
+        }
+        const bool have = base + lane < n;
+        const int pos = have ? (int)sm->ring[wave][base + lane] : 0;   // position of the 16 bytes' first code
+        uint4 c = make_uint4(0, 0, 0, 0);
+        if (have) {
+            const uint8_t *p = chunk_ptr + (size_t)(pos / CPL) * 16;
+            if (pos + CPL <= ncodes) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (pos < ncodes) {   // last lane of a ragged chunk: only its first code exists
+                const uint2 half = *reinterpret_cast<const uint2 *>(p);
+                c.x = half.x; c.y = half.y;
+            }
+        }
+        const LaneWalk<8> lw((uint32_t)(pos / CPL) & 15u);
+        uint32_t acc[CPL][4];
+        code_values<8, true>(c, lw, [&](uint32_t off) {
+            const v4u v = *(const __attribute__((address_space(3))) v4u *)(lut_bytes + off);
+            return make_uint4(v.x, v.y, v.z, v.w);
+        }, acc);
+        bool ok[CPL];
+#pragma unroll
+        for (int h = 0; h < CPL; ++h) ok[h] = have && pos + h >= skip && pos + h < ncodes;
+        // lane q: float bound of query q (ordered bits) and the same bound in table units
+        uint32_t eff_lane, thr_lane;
+        {
+            const uint32_t shared = sm->tau_blk[ql];
+            const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
+            const uint32_t own = ws->own_ord[ql];
+            eff_lane = own < loose ? own : loose;
+            const float t = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sm->prune_scale[ql]) + (float)PRUNE_MARGIN;
+            thr_lane = (uint32_t)fmaxf(fminf(t, 32767.f), 0.f);
+        }
+        // bit h * QB + q of m: the lower bound of code h does not rule out query q
+        uint32_t m = 0;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const uint32_t thr = __builtin_amdgcn_readlane(thr_lane, q);
+#pragma unroll
+            for (int h = 0; h < CPL; ++h) {
+                const uint32_t lb = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                if (ok[h] && q < nvalid && lb < thr) m |= 1u << (h * QB + q);
+            }
+        }
+        // the float bounds as scalars (a lane read inside the divergent loop below would miss
+        // the lanes that have already left it)
+        uint32_t eff_q[QB];
+#pragma unroll
+        for (int q = 0; q < QB; ++q) eff_q[q] = __builtin_amdgcn_readlane(eff_lane, q);
+        uint32_t bits = m, inserted = 0;
+        while (bits != 0u) {
+            const int b = __builtin_ctz(bits);
+            bits &= bits - 1u;
+            const int q = b & (QB - 1), h = b / QB;
+            const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
+            const __attribute__((address_space(3))) float *fl = sm->flut + q * 2048;
+            float d = fl[w0 & 255u];
+            d += fl[256 + ((w0 >> 8) & 255u)];
+            d += fl[512 + ((w0 >> 16) & 255u)];
+            d += fl[768 + (w0 >> 24)];
+            d += fl[1024 + (w1 & 255u)];
+            d += fl[1280 + ((w1 >> 8) & 255u)];
+            d += fl[1536 + ((w1 >> 16) & 255u)];
+            d += fl[1792 + (w1 >> 24)];
+            const uint32_t ord = f32_to_ord(d);
+            uint32_t eff = eff_q[0];
+#pragma unroll
+            for (int i = 1; i < QB; ++i) eff = q == i ? eff_q[i] : eff;
+            if (ord < eff) {
+                inserted |= 1u << b;
+                const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                key_store(wave_buf + (size_t)q * CAP + slot, ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
+                const uint32_t ref = sm->tau_ref[q];
+                if (ref != TAU_REF_UNSET && ord <= ref) {
+                    const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                    const uint32_t bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
+                    __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const int added = __popcll(__ballot((inserted >> q) & 1u)) + __popcll(__ballot((inserted >> (QB + q)) & 1u));
+            if (added != 0 && lane == 0)
+                __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 // Periodic path (one wave per query and period): pick up the best bound published for query q
 // by any block and, if enough candidates arrived since the histogram was last evaluated and no
 // other wave is already doing it, recompute the bound from the histogram.
 constexpr uint32_t REFRESH_MIN_NEW = 16;
-template <bool IS_U4>
-__device__ __noinline__ void scan_refresh(LdsSmem *sm, int q) {
+template <class SM, bool IS_U4>
+__device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     // the four device words of the query are independent of one another: one round trip
     const uint32_t g = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t n_v = __hip_atomic_load(sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -396,8 +526,8 @@ __device__ __noinline__ void scan_refresh(LdsSmem *sm, int q) {
 }
 
 // End of item, per wave: leave at most k keys in every list.
-template <int QB, int E>
-__device__ __noinline__ void scan_finish_wave(LdsSmem *sm, uint64_t *wave_buf) {
+template <class SM, int QB, int E>
+__device__ __noinline__ void scan_finish_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) {
     constexpr int CAP = 64 * E;
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     for (int q = 0; q < QB; ++q) {
@@ -413,8 +543,8 @@ __device__ __noinline__ void scan_finish_wave(LdsSmem *sm, uint64_t *wave_buf) {
 // query go straight to the item's result list of that query (position from a counter in LDS).
 // Keys above the bound cannot be among the k smallest.  If more than KPAD keys arrive for a query
 // the surplus is dropped here and the query is merged from the lists instead (scan_merge_item).
-template <int QB, int E, int KPAD>
-__device__ __noinline__ void scan_emit_wave(LdsSmem *sm, uint64_t *wave_buf) {
+template <class SM, int QB, int E, int KPAD>
+__device__ __noinline__ void scan_emit_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) {
     constexpr int CAP = 64 * E;
     const int lane = lane_id();
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
@@ -440,8 +570,8 @@ __device__ __noinline__ void scan_emit_wave(LdsSmem *sm, uint64_t *wave_buf) {
 
 // End of item, wave q < QB: fold the lists of all waves for query q into the list of wave 0
 // and write KPAD keys (padded with KEY_EMPTY) to out.
-template <int QB, int E, int KPAD>
-__device__ __noinline__ void scan_merge_item(LdsSmem *sm, uint64_t *block_scratch, uint64_t *out) {
+template <class SM, int QB, int E, int KPAD>
+__device__ __noinline__ void scan_merge_item(LDS_PTR(SM) sm, uint64_t *block_scratch, uint64_t *out) {
     constexpr int CAP = 64 * E;
     const int q = threadIdx.x >> 6, lane = lane_id();
     const int k = sm->topk;
@@ -462,8 +592,10 @@ __device__ __noinline__ void scan_merge_item(LdsSmem *sm, uint64_t *block_scratc
 template <int KIND, int E, int KPAD, int BATCH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void scan_tuned_kernel(TunedArgs a) {
-    constexpr bool IS_U4 = KIND == KIND_U4_M16;
-    constexpr int QB = IS_U4 ? 8 : 4;
+    constexpr bool IS_U4 = KIND == KIND_U4_M16;           // values are integer sums
+    constexpr bool PRUNED = KIND == KIND_F32P_M8;         // float values, scan loop on 16-bit lower bounds
+    constexpr bool PACKED = IS_U4 || PRUNED;              // scan loop adds packed 16-bit entries, 8 queries
+    constexpr int QB = PACKED ? 8 : 4;
     constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;     // tables = lookups per code
     constexpr int CB = NT;                                // code bytes (8 or 16)
     constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
@@ -472,9 +604,11 @@ void scan_tuned_kernel(TunedArgs a) {
     // (flat scan), more when every block streams its own list from HBM (IVF)
     constexpr int TILE = SUB * BATCH;                     // codes per wave tile
     constexpr int CAP = 64 * E;
-    static_assert(RING_FLUSH + 2 * 64 * BATCH <= RING_CAP, "two tiles must fit behind a ring that was not flushed");
     typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
-    __shared__ TunedSmem sm;
+    // ring: two tiles fit behind a ring that was not flushed
+    typedef TunedSmemT<RING_FLUSH + 2 * 64 * BATCH, PRUNED ? 8 * 8 * 256 : 4> SM;
+    __shared__ SM sm;
+    LDS_PTR(SM) smp = (LDS_PTR(SM))&sm;
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keep it scalar
     const int lane = lane_id();
@@ -520,6 +654,9 @@ void scan_tuned_kernel(TunedArgs a) {
                     qid = gq;
                     lut = IS_U4 ? (const void *)((const uint8_t *)a.luts + (size_t)gq * 256)
                                 : (const void *)((const float *)a.luts + (size_t)gq * (NT * 256));
+                    if constexpr (PRUNED) { sm.prune_off[s] = a.prune_off[gq]; sm.prune_scale[s] = a.prune_scale[gq]; }
+                } else if constexpr (PRUNED) {
+                    sm.prune_off[s] = 0.f; sm.prune_scale[s] = 0.f;
                 }
                 out = a.partial + ((size_t)item * QB + s) * KPAD;
                 if (s == 0) {
@@ -529,6 +666,7 @@ void scan_tuned_kernel(TunedArgs a) {
                     sm.chunk_ptr = a.codes + cbeg * CB;
                     sm.ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;
                     sm.skip = 0;
+                    sm.group = group;
                     sm.nvalid = a.nq - group * QB < QB ? a.nq - group * QB : QB;
                 }
             }
@@ -549,7 +687,21 @@ void scan_tuned_kernel(TunedArgs a) {
         __syncthreads();
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
-        if constexpr (!IS_U4) {
+        if constexpr (PRUNED) {
+            // 16-bit tables of the group, prepared in slot order: [group][byte][table] x 8 queries
+            const uint4 *qt = a.qtabs + (size_t)sm.group * 2048;
+            for (int e = threadIdx.x; e < 2048; e += TUNED_THREADS) {
+                const uint4 pk = qt[e];
+                sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
+                sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
+            }
+            // float tables of the slots' queries, as they are: [slot][table][entry]
+            for (int e = threadIdx.x; e < 8 * 512; e += TUNED_THREADS) {
+                const float4 *lut = (const float4 *)sm.slot_lut[e >> 9];
+                const float inf = __builtin_inff();
+                reinterpret_cast<float4 *>(sm.flut)[e] = lut ? lut[e & 511] : make_float4(inf, inf, inf, inf);
+            }
+        } else if constexpr (!IS_U4) {
             for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
                 const int j = e >> 8, byte = e & 255;
                 float v[4];
@@ -601,11 +753,19 @@ void scan_tuned_kernel(TunedArgs a) {
             const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
             const uint32_t own = sm.ws[wave].own_ord[ql];
             uint32_t eff = own < loose ? own : loose;
-            if constexpr (IS_U4) eff = ql < nvalid_q ? eff : 0u;
-            else eff = __float_as_uint(ord_to_f32(eff));
+            if constexpr (IS_U4) {
+                eff = ql < nvalid_q ? eff : 0u;
+            } else if constexpr (PRUNED) {
+                // the bound in table units, rounded down, plus the slack that covers the rounding of
+                // the tables and of this conversion; no bound (or no scale) admits every sum
+                const float t = floorf((ord_to_f32(eff) - sm.prune_off[ql]) * sm.prune_scale[ql]) + (float)PRUNE_MARGIN;
+                eff = ql < nvalid_q ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
+            } else {
+                eff = __float_as_uint(ord_to_f32(eff));
+            }
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if constexpr (IS_U4)
+                if constexpr (PACKED)
                     tau[p] = __builtin_amdgcn_readlane(eff, 2 * p) | (__builtin_amdgcn_readlane(eff, 2 * p + 1) << 16);
                 else
                     tau[p] = __builtin_amdgcn_readlane(eff, p);
@@ -642,14 +802,14 @@ void scan_tuned_kernel(TunedArgs a) {
         // positions of the lanes with a candidate parked in the ring.  No calls in here.
         auto scan_sub = [&](const uint4 cur, const int sidx) {
             uint32_t d[CPL][4];
-            code_values<NT, IS_U4>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
+            code_values<NT, PACKED>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
             // issue order: all address arithmetic, then every LDS read back to back, then the
             // additions (the reads are independent of one another)
             __builtin_amdgcn_sched_group_barrier(0x002, 8 + 2 * NT, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, NT * CPL, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 8 * NT, 0);
             uint64_t hit = 0;
-            if constexpr (IS_U4) {
+            if constexpr (PACKED) {
                 // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold
                 // wraps (sets bit 15) iff one of them is below the threshold
                 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -694,11 +854,12 @@ void scan_tuned_kernel(TunedArgs a) {
         auto between_steps = [&]() {
             bool changed = false;
             if (flush_due()) {
-                scan_flush<KIND, E>((LdsSmem *)&sm, wave_buf, ring_cnt);
+                if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
+                else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
                 ring_cnt = 0;
                 changed = true;
             }
-            if (refresh_due()) scan_refresh<IS_U4>((LdsSmem *)&sm, my_q);
+            if (refresh_due()) scan_refresh<SM, IS_U4>(smp, my_q);
             if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
 
@@ -747,19 +908,22 @@ void scan_tuned_kernel(TunedArgs a) {
         }
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
-        if (ring_cnt > 0) scan_flush<KIND, E>((LdsSmem *)&sm, wave_buf, ring_cnt);
+        if (ring_cnt > 0) {
+            if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
+            else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
+        }
         {
             bool over = false;
 #pragma unroll
             for (int q = 0; q < QB; ++q) over |= sm.ws[wave].cnt[q] > a.topk;
-            if (__builtin_expect(over, 0)) scan_finish_wave<QB, E>((LdsSmem *)&sm, wave_buf);
+            if (__builtin_expect(over, 0)) scan_finish_wave<SM, QB, E>(smp, wave_buf);
         }
-        scan_emit_wave<QB, E, KPAD>((LdsSmem *)&sm, wave_buf);
+        scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
         if (wave < QB && sm.slot_out[wave] != nullptr) {
             const int got = sm.out_cnt[wave];
             if (__builtin_expect(got > KPAD, 0)) {
-                scan_merge_item<QB, E, KPAD>((LdsSmem *)&sm, block_scratch, sm.slot_out[wave]);
+                scan_merge_item<SM, QB, E, KPAD>(smp, block_scratch, sm.slot_out[wave]);
             } else {
                 uint64_t *out = sm.slot_out[wave];
                 for (int i = got + lane; i < KPAD; i += 64) out[i] = KEY_EMPTY;
@@ -769,14 +933,78 @@ void scan_tuned_kernel(TunedArgs a) {
     }
 }
 
+// tau0 (optional, [nq]): a bound already known per query (at least k codes are at or below it);
+// it seeds the shared bound and serves as the reference of the query's histogram.
 __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_t *ncand, uint32_t *mark,
                                   uint32_t *tau_ref, int ntau,
-                                  uint32_t tau_value, uint32_t *hist, size_t nhist) {
+                                  uint32_t tau_value, uint32_t *hist, size_t nhist, const float *tau0, int nq) {
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     if (i0 == 0) *work_counter = 0;
-    for (size_t i = i0; i < (size_t)ntau; i += stride) { tau[i] = tau_value; ncand[i] = 0; mark[i] = 0; tau_ref[i] = TAU_REF_UNSET; }
+    for (size_t i = i0; i < (size_t)ntau; i += stride) {
+        const bool seeded = tau0 != nullptr && i < (size_t)nq;
+        tau[i] = seeded ? f32_to_ord(tau0[i]) : tau_value;
+        tau_ref[i] = seeded ? f32_to_ord(tau0[i]) : TAU_REF_UNSET;
+        ncand[i] = 0;
+        mark[i] = 0;
+    }
     for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
+}
+
+// 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
+// Per query: off = sum over the tables of their minimum entry, scale = PRUNE_RANGE / (tau0 - off)
+// (0, which disables the pruning of that query, if tau0 leaves no usable range), and for every table
+// L[j][b] = min(4095, floor((D[j][b] - min_j) * scale)).  Output in the slot order of the scan
+// kernel: qtabs[group][b][j] holds entry b of table j for the 8 queries of the group.
+__global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
+                                                           int nq, uint4 *qtabs, float *off_out, float *scale_out) {
+    __shared__ float smin[8][8];
+    __shared__ float sscale[8];
+    const int group = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int r = wave * 16; r < wave * 16 + 16; ++r) {
+        const int q = r >> 3, j = r & 7, gq = group * 8 + q;
+        float v = __builtin_inff();
+        if (gq < nq) {
+            const float *t = luts + ((size_t)gq * 8 + j) * 256;
+            v = fminf(fminf(t[lane], t[lane + 64]), fminf(t[lane + 128], t[lane + 192]));
+        }
+        for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+        if (lane == 0) smin[q][j] = v;
+    }
+    __syncthreads();
+    if (tid < 8) {
+        const int gq = group * 8 + tid;
+        float scale = 0.f;
+        if (gq < nq) {
+            float off = 0.f;
+            for (int j = 0; j < 8; ++j) off += smin[tid][j];
+            const float range = tau0[gq] - off;
+            if (range > 0.f && range < 3.0e38f) {
+                scale = PRUNE_RANGE / range;
+                // the threshold conversion must stay accurate to a fraction of a table unit in fp32
+                if (!(tau0[gq] * scale * 1e-6f < 1.f)) scale = 0.f;
+            }
+            off_out[gq] = off;
+            scale_out[gq] = scale;
+        }
+        sscale[tid] = scale;
+    }
+    __syncthreads();
+    const int b = tid;
+    for (int j = 0; j < 8; ++j) {
+        uint32_t e[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int gq = group * 8 + q;
+            e[q] = 0x0fffu;   // no query in this slot
+            if (gq < nq) {
+                const float x = (luts[((size_t)gq * 8 + j) * 256 + b] - smin[q][j]) * sscale[q];
+                e[q] = (uint32_t)fminf(floorf(x), 4095.f);
+            }
+        }
+        qtabs[(size_t)group * 2048 + b * 8 + j] =
+            make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
 }
 
 template <int KIND, int E, int KPAD, int BATCH>
@@ -825,6 +1053,8 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool ivf, const Tun
             return small ? launch_kind<KIND_F32_M8, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, E_LARGE, 1024, 1>(ctx, a, nblocks);
         case KIND_F32_M16:
             return small ? launch_kind<KIND_F32_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
+        case KIND_F32P_M8:
+            return small ? launch_kind<KIND_F32P_M8, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32P_M8, E_LARGE, 1024, 1>(ctx, a, nblocks);
         default:
             return small ? launch_kind<KIND_U4_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
     }
@@ -854,8 +1084,9 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     a.partial = partial;
     a.item_tab = items; a.nitems_dev = nitems_dev; a.pairs_by_list = pairs_by_list; a.pair_out = pair_out;
     a.nprobe = nprobe;
+    a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
-                                                     0xff800000u, a.hist, L.nhist);
+                                                     0xff800000u, a.hist, L.nhist, nullptr, 0);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     int rc = launch_by_kind(ctx, kind, small, true, a, nblocks);
@@ -870,8 +1101,13 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
 
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids) {
+    int rc;
     const bool is_u4 = kind == KIND_U4_M16;
-    const int qb = is_u4 ? 8 : 4;
+    // The 8 x 256 float scan prunes with 16-bit lower bounds when the database is large enough to
+    // pay for the preparation (a bound per query from the first PRUNE_INIT codes, then the tables).
+    const bool prune = kind == KIND_F32_M8 && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
+    if (prune) kind = KIND_F32P_M8;
+    const int qb = is_u4 || prune ? 8 : 4;
     const int cb = kind == KIND_F32_M16 ? 16 : 8;
     const int tile = 64 * (16 / cb) * 1;   // codes per wave tile (BATCH sub-tiles)
     const bool small = topk <= 128;
@@ -900,8 +1136,12 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int ntau = ngroups * qb;
     const StateLayout L = state_layout(qb, ntau, cap, nblocks);
     const size_t off_partial = align_up(L.total, 256);
-    const size_t total = off_partial + (size_t)nitems * qb * kpad * 8;
-    int rc = ws_reserve(ctx, total);
+    const size_t off_tau0 = off_partial + align_up((size_t)nitems * qb * kpad * 8, 256);
+    const size_t off_poff = off_tau0 + align_up((size_t)ntau * 4, 256);
+    const size_t off_pscale = off_poff + align_up((size_t)ntau * 4, 256);
+    const size_t off_qtabs = off_pscale + align_up((size_t)ntau * 4, 256);
+    const size_t total = prune ? off_qtabs + (size_t)ngroups * 2048 * sizeof(uint4) : off_tau0;
+    rc = ws_reserve(ctx, total);
     if (rc) return rc;
     uint8_t *ws = (uint8_t *)ctx->ws;
 
@@ -912,8 +1152,20 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     a.partial = (uint64_t *)(ws + off_partial);
     a.item_tab = nullptr; a.nitems_dev = nullptr; a.pairs_by_list = nullptr; a.pair_out = nullptr; a.nprobe = 0;
 
+    a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
+    float *tau0 = nullptr;
+    if (prune) {
+        tau0 = (float *)(ws + off_tau0);
+        float *poff = (float *)(ws + off_poff), *pscale = (float *)(ws + off_pscale);
+        uint4 *qtabs = (uint4 *)(ws + off_qtabs);
+        rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, 8, 256, PRUNE_INIT, topk, tau0);
+        if (rc) return rc;
+        prune_tables_kernel<<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
+        PQ_HIP(ctx, hipGetLastError());
+        a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
+    }
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
-                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist);
+                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     rc = launch_by_kind(ctx, kind, small, false, a, nblocks);

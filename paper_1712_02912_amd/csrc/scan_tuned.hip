@@ -843,10 +843,12 @@ void scan_tuned_kernel(TunedArgs a) {
         const int my_phase = 1 + 4 * my_q + 32 * (wave / QB);
         constexpr int REFRESH_MASK = 32 * (TUNED_WAVES / QB) - 1;
         const bool refresher = my_q < nvalid_q;
-        const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf();
+        // Items that start without a useful bound: no bound at all, or (long result lists) the first
+        // item of a block, which only has the loose bound the launch was seeded with.
+        const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf() || (KPAD > 128 && a.item_tab == nullptr && gstep == 0);
         int step = 0;
         auto flush_due = [&]() { return ring_cnt > RING_FLUSH || (ring_cnt > 0 && (step & (RING_PERIOD / 2 - 1)) == 0); };
-        // while the query had no bound when the item started: at steps 1, 2, 4 .. 32 as well
+        // in cold items: at steps 1, 2, 4 .. 32 as well
         auto refresh_due = [&]() {
             return refresher && ((gstep & REFRESH_MASK) == my_phase ||
                                  (wave < QB && cold_item && step <= 32 && (step & (step - 1)) == 0));
@@ -949,6 +951,45 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
         mark[i] = 0;
     }
     for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
+}
+
+// First bound of the integer scan: one block per query adds up the 8-bit table entries of the
+// first `cnt` codes (two 4-bit indexes per byte), finds the smallest sum T with at least kq codes
+// at or below it, and stores it as the query's shared bound (the scan prunes with "<=" against it).
+__global__ __launch_bounds__(256) void u4_seed_kernel(const uint8_t *__restrict__ codes, int cnt,
+                                                      const uint8_t *__restrict__ qluts, int kq, uint32_t *tau_global) {
+    __shared__ uint32_t hist[4096];
+    __shared__ uint32_t part[256];
+    __shared__ uint8_t tab[256];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    tab[tid] = qluts[(size_t)q * 256 + tid];
+    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < cnt; i += 256) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+        uint32_t sum = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t byte = ((r < 4 ? c.x : c.y) >> (8 * (r & 3))) & 255u;
+            sum += (uint32_t)tab[(2 * r) * 16 + (byte & 15u)] + (uint32_t)tab[(2 * r + 1) * 16 + (byte >> 4)];
+        }
+        atomicAdd(&hist[sum], 1u);   // sum <= 16 * 255 < 4096
+    }
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int i = 0; i < 16; ++i) mine += hist[tid * 16 + i];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cum = 0;
+        int t = 0;
+        while (t < 256 && cum + part[t] < (uint32_t)kq) cum += part[t++];
+        if (t < 256) {
+            int b = t * 16;
+            while (cum + hist[b] < (uint32_t)kq) cum += hist[b++];
+            tau_global[q] = (uint32_t)b;
+        }
+    }
 }
 
 // 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
@@ -1167,6 +1208,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
                                                      is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq);
     PQ_HIP(ctx, hipGetLastError());
+    if (is_u4 && n >= PRUNE_MIN_N) {
+        u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT, (const uint8_t *)luts, topk,
+                                                    a.tau_global);
+        PQ_HIP(ctx, hipGetLastError());
+    }
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     rc = launch_by_kind(ctx, kind, small, false, a, nblocks);
     if (rc) return rc;

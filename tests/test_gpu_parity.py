@@ -181,6 +181,78 @@ def test_scan_f32_general_shapes(ctx, m, k, fmt):
 
 
 # ----------------------------------------------------------------------------- integer scan
+# ------------------------------------------------------------- 8x8 float scan, pruned path
+# Databases of 65536 codes and more take the scan that dismisses codes by 16-bit lower bounds
+# before any float work; these cases aim at what is specific to it.
+@pytest.mark.parametrize("n", [65535, 65536, 65537, 300_001])
+def test_scan_f32_pruned_path_sizes(ctx, n):
+    r = np.random.default_rng(n)
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = (r.random((11, 8, 256)) * 50 + r.random((11, 8, 1)) * 200).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+
+
+@pytest.mark.parametrize("topk", [1, 128, 129, 1000])
+def test_scan_f32_pruned_topk_range(ctx, topk):
+    r = np.random.default_rng(topk + 77)
+    codes = r.integers(0, 256, (200_003, 8), dtype=np.uint8)
+    luts_h = (r.random((5, 8, 256)) * 100).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, topk)
+
+
+def test_scan_f32_pruned_degenerate_tables(ctx):
+    r = np.random.default_rng(21)
+    n = 70_001
+    # (a) every code is the per-table minimiser: the first bound equals the sum of the minima,
+    #     which leaves no range for the 16-bit tables (nothing can be pruned)
+    luts_h = (r.random((3, 8, 256)) * 10 + 1).astype(np.float32)
+    codes = np.tile(luts_h[0].argmin(axis=1).astype(np.uint8), (n, 1))
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # (b) a large common offset with a tiny spread: too little fp32 resolution for a threshold
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = (1.0e7 + r.random((2, 8, 256))).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # (c) a huge dynamic range: most 16-bit entries clamp at their maximum
+    luts_h = np.exp(r.random((4, 8, 256)) * 30 - 10).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # (d) constant tables: all distances equal, the smallest ids win
+    luts_h = np.full((2, 8, 256), 3.0, np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), 100)
+    assert np.array_equal(host(i), np.tile(np.arange(100), (2, 1))) and np.all(host(d) == 24.0)
+    # (e) few distinct table values: exact float sums, massive exact ties, unique (value, id) order
+    luts_h = r.integers(0, 3, (9, 8, 256)).astype(np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), 100)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, luts_h, 100)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+
+
+def test_scan_f32_pruned_descending_order_worst_case(ctx):
+    """Distances strictly decreasing with position over 2^17 codes: every code beats the bound."""
+    n = 1 << 17
+    codes = np.zeros((n, 8), np.uint8)
+    idx = np.arange(n)
+    codes[:, 0] = idx % 256
+    codes[:, 1] = (idx // 256) % 256
+    codes[:, 2] = idx // 65536
+    lut = np.zeros((1, 8, 256), np.float32)
+    lut[0, 0] = 255 - np.arange(256)
+    lut[0, 1] = (255 - np.arange(256)) * 256.0
+    lut[0, 2] = (255 - np.arange(256)) * 65536.0
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(lut), 100)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, lut, 100)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+
+
+def test_scan_f32_pruned_encoded_duplicates(ctx):
+    """Encoded mixture data (many identical codes), 37 queries: not a multiple of the group size."""
+    _, queries, cb, codes = sift_pq(8, 256, 100000, 16)
+    mix = datagen.sift_like()
+    q2 = mix.sample(37, datagen.SEED_QUERIES + 5)
+    luts_h = host(ctx.pq_build_luts(dev(q2), dev(cb)))
+    gd, gi, od, oi = run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    np.testing.assert_allclose(gd, od, rtol=RTOL)
+
+
 def run_int_scan(ctx, codes, fmt, qluts_h, topk):
     s, i = ctx.pq_adc_scan_topk(dev(codes), fmt, dev(qluts_h), topk)
     os_, oi = orc.adc_scan_topk_u8(codes, fmt, qluts_h, topk)
@@ -284,3 +356,55 @@ def test_errors_are_reported_not_raised_in_kernels(ctx):
     # the context stays usable
     d, i = ctx.pq_adc_scan_topk(codes, binding.CODES_U8, luts, 3)
     assert host(i).tolist() == [[0, 1, 2]]
+
+
+# ----------------------------------------------------------------------------- full size (bench configuration)
+FULL_N, FULL_NQ = 25_000_000, 1000
+SAMPLE_Q = [0, 1, 7, 8, 123, 500, 640, 777, 998, 999]
+
+
+def test_full_size_config1_sampled(ctx):
+    """Config 1 as bench.py runs it (25 M random codes, 1000 queries, top-100): complete results of a
+    sample of the queries against the oracle."""
+    mix = datagen.sift_like()
+    queries = dev(mix.sample(FULL_NQ, datagen.SEED_QUERIES))
+    cb = dev(datagen.sampled_codebooks(mix, 8, 256))
+    codes_h = datagen.random_codes(FULL_N, 8)
+    luts = ctx.pq_build_luts(queries, cb)
+    d, i = ctx.pq_adc_scan_topk(dev(codes_h), binding.CODES_U8, luts, 100)
+    gd, gi, luts_h = host(d), host(i), host(luts)
+    od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, np.ascontiguousarray(luts_h[SAMPLE_Q]), 100)
+    for r, q in enumerate(SAMPLE_Q):
+        check_float_topk(gd[q], gi[q], od[r], oi[r], codes_h, orc.CODES_U8, luts_h[q], FULL_N)
+    # properties that hold for every query: ascending, ids valid and distinct
+    assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < FULL_N
+    assert all(len(set(row.tolist())) == 100 for row in gi[::50])
+
+
+def test_full_size_config2_sampled(ctx):
+    """Config 2 as bench.py runs it (25 M packed codes, 1000 queries, top-1000 by integer sums, rerank
+    to top-100): stage-wise parity on a sample of the queries."""
+    mix = datagen.sift_like()
+    queries = dev(mix.sample(FULL_NQ, datagen.SEED_QUERIES))
+    cb = dev(datagen.sampled_codebooks(mix, 16, 16))
+    packed_h = datagen.random_codes(FULL_N, 8, seed=datagen.SEED_CODES + 1)
+    fmt = orc.CODES_U4_PACKED
+    dpacked = dev(packed_h)
+    luts = ctx.pq_build_luts(queries, cb)
+    qmax = ctx.pq_qmax_prescan(dpacked, fmt, luts, 2000, 1000)
+    qluts, _, _ = ctx.pq_quantize_luts(luts, qmax)
+    sums, cand = ctx.pq_adc_scan_topk(dpacked, fmt, qluts, 1000)
+    dist, ids = ctx.pq_rerank_f32(dpacked, fmt, luts, cand, 100)
+    luts_h, qmax_h, qluts_h, cand_h = host(luts), host(qmax), host(qluts), host(cand)
+    ref_q, _, _ = orc.quantize_luts(np.ascontiguousarray(luts_h[SAMPLE_Q]), np.ascontiguousarray(qmax_h[SAMPLE_Q]))
+    assert np.array_equal(qluts_h[SAMPLE_Q], ref_q)
+    os_, oi = orc.adc_scan_topk_u8(packed_h, fmt, np.ascontiguousarray(qluts_h[SAMPLE_Q]), 1000)
+    check_exact_topk(host(sums)[SAMPLE_Q], cand_h[SAMPLE_Q], os_, oi)
+    od, oid = orc.rerank_f32(packed_h, fmt, np.ascontiguousarray(luts_h[SAMPLE_Q]), np.ascontiguousarray(cand_h[SAMPLE_Q]), 100)
+    gd, gi = host(dist), host(ids)
+    for r, q in enumerate(SAMPLE_Q):
+        np.testing.assert_allclose(gd[q], od[r], rtol=RTOL)
+        exact = orc.adc_all_f32(packed_h[gi[q]], fmt, luts_h[q])
+        np.testing.assert_allclose(gd[q], exact, rtol=RTOL)
+        assert np.all(exact <= od[r][-1] * (1 + RTOL))
+

@@ -271,70 +271,6 @@ __global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__
     for (size_t p = tid; p < npairs; p += 1024) pair_out[p] += qlist_off[p / nprobe];
 }
 
-// One block per query: the k smallest keys over all lists of the query.  Keys above the final
-// bound of the query cannot be in the result and are dropped before the sort.
-constexpr int MERGE_CAP = 8192;
-__global__ __launch_bounds__(1024) void ivf_merge_kernel(const uint64_t *__restrict__ partial,
-                                                         const uint32_t *__restrict__ qlist_off,
-                                                         const uint32_t *__restrict__ tau_global, int kpad, int topk,
-                                                         const int64_t *__restrict__ ids, float *out_dist,
-                                                         int64_t *out_ids) {
-    extern __shared__ uint64_t skeys[];
-    __shared__ int s_count;
-    __shared__ unsigned long long s_kth;
-    const int q = blockIdx.x, tid = threadIdx.x;
-    const uint64_t *mine = partial + (size_t)qlist_off[q] * kpad;
-    const size_t total = (size_t)(qlist_off[q + 1] - qlist_off[q]) * kpad;
-    const uint32_t tau = tau_global[q];
-    if (tid == 0) s_count = 0;
-    __syncthreads();
-    for (size_t i = tid; i < total; i += blockDim.x) {
-        const uint64_t key = mine[i];
-        if (key != KEY_EMPTY && (uint32_t)(key >> 32) <= tau) {
-            const int pos = atomicAdd(&s_count, 1);
-            if (pos < MERGE_CAP) skeys[pos] = key;
-        }
-    }
-    __syncthreads();
-    int kept = s_count;
-    if (kept > MERGE_CAP) {
-        // too many keys at or below the bound (massive ties): bisection for the topk-th key
-        uint64_t v = 0;
-        for (int bit = 63; bit >= 0; --bit) {
-            const uint64_t trial = v | ((1ull << bit) - 1ull);
-            __syncthreads();
-            if (tid == 0) s_count = 0;
-            __syncthreads();
-            int c = 0;
-            for (size_t i = tid; i < total; i += blockDim.x) c += mine[i] <= trial ? 1 : 0;
-            atomicAdd(&s_count, c);
-            __syncthreads();
-            if (s_count < topk) v |= (1ull << bit);
-        }
-        __syncthreads();
-        if (tid == 0) { s_kth = v; s_count = 0; }
-        __syncthreads();
-        const uint64_t kth = s_kth;
-        for (size_t i = tid; i < total; i += blockDim.x) {
-            const uint64_t key = mine[i];
-            if (key != KEY_EMPTY && key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < MERGE_CAP) skeys[pos] = key; }
-        }
-        __syncthreads();
-        kept = s_count < MERGE_CAP ? s_count : MERGE_CAP;
-    }
-    int n2 = 64;
-    while (n2 < kept) n2 <<= 1;
-    for (int i = kept + tid; i < n2; i += blockDim.x) skeys[i] = KEY_EMPTY;
-    block_bitonic_sort(skeys, n2);
-    for (int i = tid; i < topk; i += blockDim.x) {
-        const uint64_t key = i < n2 ? skeys[i] : KEY_EMPTY;
-        const bool empty = key == KEY_EMPTY;
-        const uint32_t row = (uint32_t)key;
-        out_dist[(size_t)q * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
-        out_ids[(size_t)q * topk + i] = empty ? -1 : (ids ? ids[row] : (int64_t)row);
-    }
-}
-
 // ------------------------------------------------------------------------------------------
 int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
@@ -393,8 +329,6 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     uint32_t *qlist_off = (uint32_t *)(ws + o_qlistoff);
     uint64_t *partial = (uint64_t *)(ws + o_partial);
 
-    PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(ivf_merge_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
     for (int q0 = 0; q0 < nq; q0 += qbatch) {
         const int nqb = nq - q0 < qbatch ? nq - q0 : qbatch;
         const int npairs = nqb * nprobe;
@@ -430,9 +364,9 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         rc = launch_scan_items(ctx, kind, L->codes, luts, nqb, nprobe, topk, items, nitems_dev, pairs_by_list, pair_out,
                                partial, ws + o_state, state_bytes, &tau_global);
         if (rc) return rc;
-        ivf_merge_kernel<<<nqb, 1024, MERGE_CAP * 8, s>>>(partial, qlist_off, tau_global, kpad, topk, L->ids,
-                                                          out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
-        PQ_HIP(ctx, hipGetLastError());
+        rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_global, kpad, nqb, topk, L->ids, false,
+                                   out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
+        if (rc) return rc;
     }
     return PQ_OK;
 }

@@ -63,6 +63,11 @@ static inline int env_int(const char *name, int dflt) {
 
 int launch_merge_topk(pq_ctx *ctx, const uint64_t *partial, int nchunks, int ngroups, int qb, int kpad, int nq,
                       int topk, bool val_u32, void *out_val, int64_t *out_ids);
+// merge of the per-query result lists of a scan that leaves a final bound per query in tau_global
+// (see merge_filtered_kernel); any number of lists
+int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *qlist_off, int nchunks, int ngroups, int qb,
+                          const uint32_t *tau_global, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
+                          void *out_val, int64_t *out_ids);
 // IVF: run the persistent scan kernel over a table of work items (see IvfItem).  `state` is a
 // caller-provided device region of tuned_state_bytes() bytes holding the per-query bounds,
 // histograms and the per-block candidate scratch; *tau_global_out receives the per-query bounds.

@@ -174,6 +174,101 @@ __global__ __launch_bounds__(1024) void merge_topk_kernel(const uint64_t *partia
     }
 }
 
+// One block per query: the k smallest keys over all result lists of the query, for scans that
+// leave a final bound per query (at least k keys are at or below it): keys above the bound cannot
+// be in the result and are dropped before the sort, so the number of lists is not limited by the
+// sort.  The lists of query gq are either lists qlist_off[gq] .. qlist_off[gq + 1] of `partial`
+// (inverted-list search) or, with qlist_off == nullptr, list (c * ngroups + gq / qb) * qb + gq % qb
+// for every chunk c (flat scan).  ids (optional) maps rows to the ids to return.
+constexpr int MERGE_CAP = 8192;
+template <bool VAL_U32>
+__global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__restrict__ partial,
+                                                              const uint32_t *__restrict__ qlist_off, int nchunks,
+                                                              int ngroups, int qb,
+                                                              const uint32_t *__restrict__ tau_global, int kpad, int topk,
+                                                              const int64_t *__restrict__ ids, void *out_val,
+                                                              int64_t *out_ids) {
+    extern __shared__ uint64_t skeys[];
+    __shared__ int s_count;
+    __shared__ unsigned long long s_kth;
+    const int gq = blockIdx.x, tid = threadIdx.x;
+    const size_t nlists = qlist_off ? (size_t)(qlist_off[gq + 1] - qlist_off[gq]) : (size_t)nchunks;
+    const size_t total = nlists * kpad;
+    auto key_at = [&](size_t i) -> uint64_t {
+        const size_t l = i / kpad, e = i % kpad;
+        const size_t list = qlist_off ? (size_t)qlist_off[gq] + l : (l * ngroups + gq / qb) * qb + gq % qb;
+        return partial[list * kpad + e];
+    };
+    const uint32_t tau = tau_global[gq];
+    if (tid == 0) s_count = 0;
+    __syncthreads();
+    for (size_t i = tid; i < total; i += blockDim.x) {
+        const uint64_t key = key_at(i);
+        if (key != KEY_EMPTY && (uint32_t)(key >> 32) <= tau) {
+            const int pos = atomicAdd(&s_count, 1);
+            if (pos < MERGE_CAP) skeys[pos] = key;
+        }
+    }
+    __syncthreads();
+    int kept = s_count;
+    if (kept > MERGE_CAP) {
+        // too many keys at or below the bound (massive ties): bisection for the topk-th key
+        uint64_t v = 0;
+        for (int bit = 63; bit >= 0; --bit) {
+            const uint64_t trial = v | ((1ull << bit) - 1ull);
+            __syncthreads();
+            if (tid == 0) s_count = 0;
+            __syncthreads();
+            int c = 0;
+            for (size_t i = tid; i < total; i += blockDim.x) c += key_at(i) <= trial ? 1 : 0;
+            atomicAdd(&s_count, c);
+            __syncthreads();
+            if (s_count < topk) v |= (1ull << bit);
+        }
+        __syncthreads();
+        if (tid == 0) { s_kth = v; s_count = 0; }
+        __syncthreads();
+        const uint64_t kth = s_kth;
+        for (size_t i = tid; i < total; i += blockDim.x) {
+            const uint64_t key = key_at(i);
+            if (key != KEY_EMPTY && key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < MERGE_CAP) skeys[pos] = key; }
+        }
+        __syncthreads();
+        kept = s_count < MERGE_CAP ? s_count : MERGE_CAP;
+    }
+    int n2 = 64;
+    while (n2 < kept) n2 <<= 1;
+    for (int i = kept + tid; i < n2; i += blockDim.x) skeys[i] = KEY_EMPTY;
+    block_bitonic_sort(skeys, n2);
+    for (int i = tid; i < topk; i += blockDim.x) {
+        const uint64_t key = i < n2 ? skeys[i] : KEY_EMPTY;
+        const bool empty = key == KEY_EMPTY;
+        const uint32_t row = (uint32_t)key;
+        if (VAL_U32) ((uint32_t *)out_val)[(size_t)gq * topk + i] = empty ? 0xffffffffu : (uint32_t)(key >> 32);
+        else ((float *)out_val)[(size_t)gq * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
+        out_ids[(size_t)gq * topk + i] = empty ? -1 : (ids ? ids[row] : (int64_t)row);
+    }
+}
+
+int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *qlist_off, int nchunks, int ngroups, int qb,
+                          const uint32_t *tau_global, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
+                          void *out_val, int64_t *out_ids) {
+    if (nq == 0) return PQ_OK;
+    if (val_u32) {
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
+        merge_filtered_kernel<true><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb, tau_global,
+                                                                             kpad, topk, ids, out_val, out_ids);
+    } else {
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<false>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
+        merge_filtered_kernel<false><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
+                                                                              tau_global, kpad, topk, ids, out_val, out_ids);
+    }
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 static int next_pow2(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 

@@ -490,6 +490,7 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
 // by any block and, if enough candidates arrived since the histogram was last evaluated and no
 // other wave is already doing it, recompute the bound from the histogram.
 constexpr uint32_t REFRESH_MIN_NEW = 16;
+
 template <class SM, bool IS_U4>
 __device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     // the four device words of the query are independent of one another: one round trip
@@ -525,14 +526,14 @@ __device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     }
 }
 
-// End of item, per wave: leave at most k keys in every list.
+// End of item, per wave: leave at most k keys in the lists of the queries in qmask.
 template <class SM, int QB, int E>
-__device__ __noinline__ void scan_finish_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) {
+__device__ __noinline__ void scan_finish_wave(LDS_PTR(SM) sm, uint64_t *wave_buf, uint32_t qmask) {
     constexpr int CAP = 64 * E;
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     for (int q = 0; q < QB; ++q) {
         int cnt = ws->cnt[q];
-        if (cnt > sm->topk) {
+        if (((qmask >> q) & 1u) != 0u && cnt > sm->topk) {
             wave_compact<E>(wave_buf + (size_t)q * CAP, cnt, sm->topk);
             if (lane_id() == 0) ws->cnt[q] = cnt;
         }
@@ -549,10 +550,15 @@ __device__ __noinline__ void scan_emit_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) 
     const int lane = lane_id();
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
     list_fence();
+    // lane q: the bound of query q, the better of the block's and the device's current one
+    const int ql = lane & (QB - 1);
+    const uint32_t dev_bound = __hip_atomic_load(sm->tau_global[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t blk_bound = sm->tau_blk[ql];
+    const uint32_t bound_lane = dev_bound < blk_bound ? dev_bound : blk_bound;
     for (int q = 0; q < sm->nvalid && q < QB; ++q) {
         const int cnt = ws->cnt[q];
         if (cnt == 0) continue;
-        const uint32_t bound = sm->tau_blk[q];
+        const uint32_t bound = __builtin_amdgcn_readlane(bound_lane, q);
         uint64_t *out = sm->slot_out[q];
         const uint64_t *buf = wave_buf + (size_t)q * CAP;
         for (int i0 = 0; i0 < cnt; i0 += 64) {
@@ -847,6 +853,7 @@ void scan_tuned_kernel(TunedArgs a) {
         // item of a block, which only has the loose bound the launch was seeded with.
         const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf() || (KPAD > 128 && a.item_tab == nullptr && gstep == 0);
         int step = 0;
+        int pressure = 0;   // positions this wave has flushed since it last refreshed a bound
         auto flush_due = [&]() { return ring_cnt > RING_FLUSH || (ring_cnt > 0 && (step & (RING_PERIOD / 2 - 1)) == 0); };
         // in cold items: at steps 1, 2, 4 .. 32 as well
         auto refresh_due = [&]() {
@@ -858,10 +865,15 @@ void scan_tuned_kernel(TunedArgs a) {
             if (flush_due()) {
                 if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
                 else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
+                pressure += ring_cnt;
                 ring_cnt = 0;
                 changed = true;
             }
-            if (refresh_due()) scan_refresh<SM, IS_U4>(smp, my_q);
+            // a wave that keeps finding candidates asks for a new bound without waiting for its turn
+            if (refresh_due() || (refresher && pressure >= KPAD / 2)) {
+                scan_refresh<SM, IS_U4>(smp, my_q);
+                pressure = 0;
+            }
             if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
 
@@ -914,21 +926,23 @@ void scan_tuned_kernel(TunedArgs a) {
             if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
             else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
         }
-        {
-            bool over = false;
-#pragma unroll
-            for (int q = 0; q < QB; ++q) over |= sm.ws[wave].cnt[q] > a.topk;
-            if (__builtin_expect(over, 0)) scan_finish_wave<SM, QB, E>(smp, wave_buf);
-        }
         scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
+        // queries whose result list overflowed (loose bounds, first items): cut every wave's list
+        // to its k smallest keys and merge the lists instead
+        uint32_t overflow = 0;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) overflow |= sm.out_cnt[q] > KPAD ? 1u << q : 0u;
+        if (__builtin_expect(overflow != 0u, 0)) {
+            scan_finish_wave<SM, QB, E>(smp, wave_buf, overflow);
+            __syncthreads();
+        }
         if (wave < QB && sm.slot_out[wave] != nullptr) {
-            const int got = sm.out_cnt[wave];
-            if (__builtin_expect(got > KPAD, 0)) {
+            if ((overflow >> wave) & 1u) {
                 scan_merge_item<SM, QB, E, KPAD>(smp, block_scratch, sm.slot_out[wave]);
             } else {
                 uint64_t *out = sm.slot_out[wave];
-                for (int i = got + lane; i < KPAD; i += 64) out[i] = KEY_EMPTY;
+                for (int i = sm.out_cnt[wave] + lane; i < KPAD; i += 64) out[i] = KEY_EMPTY;
             }
         }
         __syncthreads();
@@ -1159,12 +1173,10 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // persistent blocks: one per CU (64 KB of tables and 16 waves of 128 registers fill a CU)
     const int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
 
-    // several items per block for balance, chunks of at least 8 block tiles, merge limit 16384 keys per query
+    // several items per block for balance, chunks of at least 8 block tiles
     int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
-    const int64_t max_by_merge = 16384 / kpad;
     if (nchunks > max_by_n) nchunks = max_by_n;
-    if (nchunks > max_by_merge) nchunks = max_by_merge;
     if (nchunks < 1) nchunks = 1;
     int64_t chunk_codes = (n + nchunks - 1) / nchunks;
     chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
@@ -1220,7 +1232,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
         ctx->ev_valid = 1;
     }
-    return launch_merge_topk(ctx, a.partial, (int)nchunks, ngroups, qb, kpad, nq, topk, is_u4, out_val, out_ids);
+    return launch_merge_filtered(ctx, a.partial, nullptr, (int)nchunks, ngroups, qb, a.tau_global, kpad, nq, topk, nullptr, is_u4,
+                                 out_val, out_ids);
 }
 
 }  // namespace pq

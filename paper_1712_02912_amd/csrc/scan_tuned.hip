@@ -47,21 +47,20 @@ constexpr int E_SMALL = 6, E_LARGE = 32;
 constexpr int RING_FLUSH = 32;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
 
-// RING: ring entries per wave; FLUT: floats of plain per-query tables kept for exact values
-// (pruned float scan only)
-template <int RING, int FLUT>
+// RING: ring entries per wave
+template <int RING>
 struct __align__(16) TunedSmemT {
     uint4 lut[4096];
     uint8_t qstage[8][256];
     // Per wave: lanes that found a candidate park the position of their 16 code bytes here; the
     // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
     uint32_t ring[TUNED_WAVES][RING];
-    float flut[FLUT];        // [slot][table][entry], pruned float scan
     float prune_off[8];      // per slot: sum of the table minima, and the scale of the 16-bit tables
     float prune_scale[8];
     WaveState ws[TUNED_WAVES];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
     int out_cnt[8];        // keys handed to the item's result list of each query so far
+    uint32_t ncand_blk[8]; // candidates inserted by the block and not yet added to the query's device counter
     uint32_t tau_ref[8];   // histogram reference per query (float path)
     // per item, written at its start: where the state of the query in each slot lives
     uint32_t *hist[8];
@@ -90,6 +89,7 @@ typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 // KIND_F32P_M8: the 8 x 256 float scan with pruning by 16-bit lower bounds (see scan_flush_pruned)
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3 };
+constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
 constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain float scan
 constexpr int PRUNE_INIT = 4096;           // codes looked at for the first bound of every query
 constexpr int PRUNE_MARGIN = 8;      // slack of the integer threshold, in table units
@@ -364,7 +364,7 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
             int added = __popcll(__ballot((m >> q) & 1u));
             if (CPL == 2) added += __popcll(__ballot((m >> (QB + q)) & 1u));
             if (added != 0 && lane == 0)
-                __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 }
@@ -452,7 +452,7 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             bits &= bits - 1u;
             const int q = b & (QB - 1), h = b / QB;
             const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
-            const __attribute__((address_space(3))) float *fl = sm->flut + q * 2048;
+            const float *fl = (const float *)sm->slot_lut[q];   // the query's float tables [table][entry], in device memory
             float d = fl[w0 & 255u];
             d += fl[256 + ((w0 >> 8) & 255u)];
             d += fl[512 + ((w0 >> 16) & 255u)];
@@ -481,7 +481,7 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
         for (int q = 0; q < QB; ++q) {
             const int added = __popcll(__ballot((inserted >> q) & 1u)) + __popcll(__ballot((inserted >> (QB + q)) & 1u));
             if (added != 0 && lane == 0)
-                __hip_atomic_fetch_add(sm->ncand[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
 }
@@ -495,7 +495,12 @@ template <class SM, bool IS_U4>
 __device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     // the four device words of the query are independent of one another: one round trip
     const uint32_t g = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const uint32_t n_v = __hip_atomic_load(sm->ncand[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // (the block's own count of new candidates goes into the device counter on this occasion)
+    uint32_t n_v = 0;
+    if (lane_id() == 0) {
+        const uint32_t mine = __hip_atomic_exchange(&sm->ncand_blk[q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        n_v = __hip_atomic_fetch_add(sm->ncand[q], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+    }
     const uint32_t mark_v = __hip_atomic_load(sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t ref_v = IS_U4 ? 0u : __hip_atomic_load(sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (lane_id() == 0) __hip_atomic_fetch_min(&sm->tau_blk[q], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -612,7 +617,7 @@ void scan_tuned_kernel(TunedArgs a) {
     constexpr int CAP = 64 * E;
     typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
     // ring: two tiles fit behind a ring that was not flushed
-    typedef TunedSmemT<RING_FLUSH + 2 * 64 * BATCH, PRUNED ? 8 * 8 * 256 : 4> SM;
+    typedef TunedSmemT<RING_FLUSH + 2 * 64 * BATCH> SM;
     __shared__ SM sm;
     LDS_PTR(SM) smp = (LDS_PTR(SM))&sm;
 
@@ -689,7 +694,7 @@ void scan_tuned_kernel(TunedArgs a) {
             if (s == 0) sm.topk = a.topk;
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
-        if (threadIdx.x < 8) sm.out_cnt[threadIdx.x] = 0;
+        if (threadIdx.x < 8) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
         __syncthreads();
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
@@ -700,12 +705,6 @@ void scan_tuned_kernel(TunedArgs a) {
                 const uint4 pk = qt[e];
                 sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
                 sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
-            }
-            // float tables of the slots' queries, as they are: [slot][table][entry]
-            for (int e = threadIdx.x; e < 8 * 512; e += TUNED_THREADS) {
-                const float4 *lut = (const float4 *)sm.slot_lut[e >> 9];
-                const float inf = __builtin_inff();
-                reinterpret_cast<float4 *>(sm.flut)[e] = lut ? lut[e & 511] : make_float4(inf, inf, inf, inf);
             }
         } else if constexpr (!IS_U4) {
             for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
@@ -928,6 +927,8 @@ void scan_tuned_kernel(TunedArgs a) {
         }
         scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
+        if (wave == TUNED_WAVES - 1 && lane < QB && sm.ncand_blk[lane] != 0u)   // what the block has not reported yet
+            __hip_atomic_fetch_add(sm.ncand[lane], sm.ncand_blk[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // queries whose result list overflowed (loose bounds, first items): cut every wave's list
         // to its k smallest keys and merge the lists instead
         uint32_t overflow = 0;
@@ -1097,21 +1098,23 @@ static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
     a.scratch = (uint64_t *)(ws + L.off_scratch);
 }
 
-// flat scans fetch one sub-tile per step, IVF items (streamed from HBM, short) four
-static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool ivf, const TunedArgs &a, int nblocks) {
-    if (ivf) {
-        if (kind == KIND_F32_M8) return launch_kind<KIND_F32_M8, E_SMALL, 128, 4>(ctx, a, nblocks);
-        return launch_kind<KIND_F32_M16, E_SMALL, 128, 4>(ctx, a, nblocks);
+// BATCH (sub-tiles fetched together): one when the same codes serve many query groups at about the
+// same time and so come from the caches; four when they stream from HBM (inverted lists, scans
+// for few queries), which takes more bytes in flight per wave.
+template <int KIND>
+static int launch_kind_sized(pq_ctx *ctx, bool small, bool stream, const TunedArgs &a, int nblocks) {
+    if (stream) {
+        return small ? launch_kind<KIND, E_SMALL, 128, 4>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 4>(ctx, a, nblocks);
     }
+    return small ? launch_kind<KIND, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 1>(ctx, a, nblocks);
+}
+
+static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const TunedArgs &a, int nblocks) {
     switch (kind) {
-        case KIND_F32_M8:
-            return small ? launch_kind<KIND_F32_M8, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M8, E_LARGE, 1024, 1>(ctx, a, nblocks);
-        case KIND_F32_M16:
-            return small ? launch_kind<KIND_F32_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
-        case KIND_F32P_M8:
-            return small ? launch_kind<KIND_F32P_M8, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_F32P_M8, E_LARGE, 1024, 1>(ctx, a, nblocks);
-        default:
-            return small ? launch_kind<KIND_U4_M16, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND_U4_M16, E_LARGE, 1024, 1>(ctx, a, nblocks);
+        case KIND_F32_M8: return launch_kind_sized<KIND_F32_M8>(ctx, small, stream, a, nblocks);
+        case KIND_F32_M16: return launch_kind_sized<KIND_F32_M16>(ctx, small, stream, a, nblocks);
+        case KIND_F32P_M8: return launch_kind_sized<KIND_F32P_M8>(ctx, small, stream, a, nblocks);
+        default: return launch_kind_sized<KIND_U4_M16>(ctx, small, stream, a, nblocks);
     }
 }
 
@@ -1154,6 +1157,8 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     return PQ_OK;
 }
 
+static int ngroups_of(int nq, bool packed) { const int qb = packed ? 8 : 4; return (nq + qb - 1) / qb; }
+
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids) {
     int rc;
@@ -1164,7 +1169,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     if (prune) kind = KIND_F32P_M8;
     const int qb = is_u4 || prune ? 8 : 4;
     const int cb = kind == KIND_F32_M16 ? 16 : 8;
-    const int tile = 64 * (16 / cb) * 1;   // codes per wave tile (BATCH sub-tiles)
+    const int batch = ngroups_of(nq, is_u4 || prune) < STREAM_GROUPS ? 4 : 1;
+    const int tile = 64 * (16 / cb) * batch;   // codes per wave tile (BATCH sub-tiles)
     const bool small = topk <= 128;
     const int kpad = small ? 128 : 1024;
     const int cap = 64 * (small ? E_SMALL : E_LARGE);
@@ -1226,7 +1232,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    rc = launch_by_kind(ctx, kind, small, false, a, nblocks);
+    rc = launch_by_kind(ctx, kind, small, ngroups < STREAM_GROUPS, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));

@@ -89,6 +89,7 @@ typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 // KIND_F32P_M8: the 8 x 256 float scan with pruning by 16-bit lower bounds (see scan_flush_pruned)
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3 };
+constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
 constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
 constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain float scan
 constexpr int PRUNE_INIT = 4096;           // codes looked at for the first bound of every query
@@ -1007,6 +1008,55 @@ __global__ __launch_bounds__(256) void u4_seed_kernel(const uint8_t *__restrict_
     }
 }
 
+// Better first bound for scans in which many blocks start on the same query at once (few query
+// groups): one block per query looks at the first `cnt` codes, counts the float distances at or
+// below the bound known so far (tau0, from the first PRUNE_INIT codes, which are among the `cnt`)
+// in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
+// distances at or below it.  Distances are summed in table order, as everywhere on this path.
+__global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
+                                                              const float *__restrict__ luts, int k, float *tau0) {
+    __shared__ float tab[8 * 256];
+    __shared__ uint32_t hist[HIST_BINS];
+    __shared__ uint32_t part[256];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    for (int i = tid; i < 2048; i += 256) tab[i] = luts[(size_t)q * 2048 + i];
+    for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
+    __syncthreads();
+    const uint32_t ref = f32_to_ord(tau0[q]);
+    for (int i = tid; i < cnt; i += 256) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+        float d = tab[c.x & 255u];
+        d += tab[256 + ((c.x >> 8) & 255u)];
+        d += tab[512 + ((c.x >> 16) & 255u)];
+        d += tab[768 + (c.x >> 24)];
+        d += tab[1024 + (c.y & 255u)];
+        d += tab[1280 + ((c.y >> 8) & 255u)];
+        d += tab[1536 + ((c.y >> 16) & 255u)];
+        d += tab[1792 + (c.y >> 24)];
+        const uint32_t ord = f32_to_ord(d);
+        if (ord <= ref) {
+            const uint32_t below = (ref - ord) >> HIST_SHIFT;
+            atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cum = 0;
+        int t = 0;
+        while (t < 256 && cum + part[t] < (uint32_t)k) cum += part[t++];
+        if (t < 256) {
+            int b = t * (HIST_BINS / 256);
+            while (cum + hist[b] < (uint32_t)k) cum += hist[b++];
+            // every distance counted in bins <= b is at or below this edge
+            tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
+        }
+    }
+}
+
 // 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
 // Per query: off = sum over the tables of their minimum entry, scale = PRUNE_RANGE / (tau0 - off)
 // (0, which disables the pruning of that query, if tau0 leaves no usable range), and for every table
@@ -1219,6 +1269,10 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
         rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, 8, 256, PRUNE_INIT, topk, tau0);
         if (rc) return rc;
+        if (ngroups < STREAM_GROUPS) {
+            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, SEED_CODES_STREAM, (const float *)luts, topk, tau0);
+            PQ_HIP(ctx, hipGetLastError());
+        }
         prune_tables_kernel<<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
         PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
@@ -1227,8 +1281,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
                                                      is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq);
     PQ_HIP(ctx, hipGetLastError());
     if (is_u4 && n >= PRUNE_MIN_N) {
-        u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT, (const uint8_t *)luts, topk,
-                                                    a.tau_global);
+        const int seed_codes = ngroups < STREAM_GROUPS ? SEED_CODES_STREAM : (topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT);
+        u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, a.tau_global);
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));

@@ -77,6 +77,7 @@ struct __align__(16) TunedSmemT {
     int nvalid;                // slots in use
     int topk;
     int item;
+    int next_pair;             // next pair of tiles to hand to a wave
     int group;                 // flat scan: query group of the item
 };
 
@@ -696,6 +697,7 @@ void scan_tuned_kernel(TunedArgs a) {
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
         if (threadIdx.x < 8) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
+        if (threadIdx.x == 0) sm.next_pair = TUNED_WAVES;
         __syncthreads();
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
@@ -877,44 +879,45 @@ void scan_tuned_kernel(TunedArgs a) {
             if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
 
-        // Full tiles, two register sets used in turn.  The next tile is requested only after the
-        // current one has arrived (the empty asm reads its last register), so that waiting for the
-        // current tile never waits for the one just requested; the loads are unconditional (past the
-        // last full tile they re-read it and the data is dropped).  The inner loop holds no call.
-        int t = wave;   // next full tile of this wave
-        if (t < nfull) {
-            const int last_full = nfull - 1;
+        // Full tiles go in pairs, two register sets used in turn.  The next tile is requested only
+        // after the current one has arrived (the empty asm reads its last register), so that waiting
+        // for the current tile never waits for the one just requested; the loads are unconditional
+        // (past the last pair they re-read it and the data is dropped).  Pairs are handed out through
+        // a counter in LDS, one pair ahead, so that a wave held up by inserts or refreshes simply
+        // takes fewer pairs and the waves reach the end of the item together.  The inner loop holds
+        // no call.
+        const int npairs = nfull / 2;
+        int p = wave;   // the first pair of every wave is fixed, the counter starts behind them
+        if (p < npairs) {
             uint4 bufa[BATCH], bufb[BATCH];
-            load_full(t, bufa);
-            while (t + TUNED_WAVES < nfull) {
+            load_full(2 * p, bufa);
+            for (;;) {
                 bool more;
                 do {
+                    int next_v = 0;
+                    if (lane == 0) next_v = __hip_atomic_fetch_add(&sm.next_pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                     asm volatile("" : "+v"(bufa[BATCH - 1].w) : : "memory");
-                    load_full(t + TUNED_WAVES, bufb);
+                    load_full(2 * p + 1, bufb);
 #pragma unroll
-                    for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], t * BATCH + i);
+                    for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], 2 * p * BATCH + i);
+                    const int pn = __builtin_amdgcn_readfirstlane(next_v);
                     asm volatile("" : "+v"(bufb[BATCH - 1].w) : : "memory");
-                    load_full(t + 2 * TUNED_WAVES < last_full ? t + 2 * TUNED_WAVES : last_full, bufa);
+                    load_full(2 * (pn < npairs ? pn : npairs - 1), bufa);
 #pragma unroll
-                    for (int i = 0; i < BATCH; ++i) scan_sub(bufb[i], (t + TUNED_WAVES) * BATCH + i);
-                    t += 2 * TUNED_WAVES;
+                    for (int i = 0; i < BATCH; ++i) scan_sub(bufb[i], (2 * p + 1) * BATCH + i);
+                    p = pn;
                     ++step;
                     ++gstep;
-                    more = t + TUNED_WAVES < nfull;
+                    more = p < npairs;
                     if (step < 32 || (step & 3) == 0) reload_tau();
                 } while (__builtin_expect(more && !flush_due() && !refresh_due(), 1));
                 between_steps();
-            }
-            if (t < nfull) {   // an odd tile left over: bufa holds it
-#pragma unroll
-                for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], t * BATCH + i);
-                ++step;
-                ++gstep;
-                between_steps();
+                if (!more) break;
             }
         }
-        // sub-tiles after the last full tile (the very last one may be ragged), dealt round-robin
-        for (int sidx = nfull * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) {
+        // what is left after the pairs: at most one full tile and the sub-tiles behind it (the very
+        // last one may be ragged), dealt round-robin
+        for (int sidx = 2 * npairs * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) {
             scan_sub(load_ragged(sidx), sidx);
             ++step;
             ++gstep;

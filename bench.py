@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--skip-16x4", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--skip-streaming", action="store_true")
+    ap.add_argument("--ivf", action="store_true", help="also time ivf_adc_search on config 4 (allocates 8 GB of codes)")
+    ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
     ap.add_argument("--streaming-n", type=int, default=100_000_000)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (counter calibration under rocprofv3)")
@@ -184,6 +186,30 @@ def main():
                                     "frac_of_hbm_peak": gbs / HBM_PEAK_GBS, "G codes/s": ns * nq_s / (k_ms * 1e-3) / 1e9})
         result["streaming_pq8x8"] = stream
         del codes_s
+
+    # ---------------------------------------------------------------- IVF-ADC (BASELINE config 4), on request
+    if args.ivf:
+        nt, nlist, nq_i, nprobe = args.ivf_n, 65536, 10000, 64
+        coarse = torch.from_numpy(mix.sample(nlist, datagen.SEED_DATA + 7)).cuda()
+        sizes = datagen.zipf_list_sizes(nt, nlist)
+        offsets = torch.from_numpy(datagen.offsets_from_sizes(sizes)).cuda()
+        gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_CODES + 3)
+        codes_i = torch.randint(0, 256, (nt, 8), dtype=torch.uint8, device="cuda", generator=gen)
+        cb_r = cb8 * 0.25   # residual codebooks: same shape, smaller scale
+        q_i = torch.from_numpy(mix.sample(nq_i, datagen.SEED_QUERIES + 1)).cuda()
+        times = []
+        for _ in range(3):
+            sync()
+            t0 = time.perf_counter()
+            _, _, probes = ctx.ivf_adc_search(coarse, offsets, codes_i, None, cb_r, binding.CODES_U8, q_i, nprobe, args.topk,
+                                              return_probes=True)
+            sync()
+            times.append((time.perf_counter() - t0) * 1e3)
+        scanned = int(torch.from_numpy(sizes).cuda()[probes.long()].sum().item())
+        result["ivf_config4"] = {"workload": "N=%d codes in %d Zipf-sized lists, %d queries, nprobe %d, top-%d" %
+                                 (nt, nlist, nq_i, nprobe, args.topk), "ms_per_call": min(times[1:]),
+                                 "code_query_pairs": scanned, "G codes/s": scanned / (min(times[1:]) * 1e-3) / 1e9}
+        del codes_i
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.skip_cpu:

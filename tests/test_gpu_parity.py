@@ -358,6 +358,16 @@ def test_errors_are_reported_not_raised_in_kernels(ctx):
     assert host(i).tolist() == [[0, 1, 2]]
 
 
+def test_scan_f32_plain_loop_on_a_large_database(ctx, monkeypatch):
+    """The plain float loop (no pruning) normally serves small databases only; here it scans a large one."""
+    monkeypatch.setenv("PQ_SCAN_PRUNE", "0")
+    r = np.random.default_rng(31)
+    codes = r.integers(0, 256, (400_003, 8), dtype=np.uint8)
+    luts_h = (r.random((9, 8, 256)) * 100).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h[:2], 700)
+
+
 # ----------------------------------------------------------------------------- full size (bench configuration)
 FULL_N, FULL_NQ = 25_000_000, 1000
 SAMPLE_Q = [0, 1, 7, 8, 123, 500, 640, 777, 998, 999]
@@ -407,4 +417,22 @@ def test_full_size_config2_sampled(ctx):
         exact = orc.adc_all_f32(packed_h[gi[q]], fmt, luts_h[q])
         np.testing.assert_allclose(gd[q], exact, rtol=RTOL)
         assert np.all(exact <= od[r][-1] * (1 + RTOL))
+
+
+def test_config3_gist_like_16x8_sampled(ctx):
+    """Config 3 shape: d=960 mixture in [0,1], 16 x 256 codebooks (60 dims each), 1 M 16-byte codes, 1000
+    queries, top-100.  Tables against the oracle for a sample of queries (the oracle's table build is slow),
+    scan results for the same sample."""
+    mix = datagen.gist_like()
+    queries_h = mix.sample(FULL_NQ, datagen.SEED_QUERIES)
+    cb_h = datagen.sampled_codebooks(mix, 16, 256)
+    codes_h = datagen.random_codes(1_000_000, 16, seed=datagen.SEED_CODES + 4)
+    luts = ctx.pq_build_luts(dev(queries_h), dev(cb_h))
+    d, i = ctx.pq_adc_scan_topk(dev(codes_h), binding.CODES_U8, luts, 100)
+    luts_h, gd, gi = host(luts), host(d), host(i)
+    ref = orc.build_luts(np.ascontiguousarray(queries_h[SAMPLE_Q]), cb_h)
+    np.testing.assert_allclose(luts_h[SAMPLE_Q], ref, rtol=4e-6, atol=0)
+    od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, np.ascontiguousarray(luts_h[SAMPLE_Q]), 100)
+    for r, q in enumerate(SAMPLE_Q):
+        check_float_topk(gd[q], gi[q], od[r], oi[r], codes_h, orc.CODES_U8, luts_h[q], len(codes_h))
 

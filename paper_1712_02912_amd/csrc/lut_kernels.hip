@@ -6,6 +6,13 @@
 
 namespace pq {
 
+// tuning switch, on unless the variable is set to 0
+static bool env_flag_on(const char *name) {
+    const char *v = getenv(name);
+    return !(v && v[0] == '0');
+}
+
+
 // ------------------------------------------------------------------------------------------
 // Direct form  D[q][j][i] = sum_t (y[q][j*dsub+t] - C[j][i][t])^2  in f32.  All terms are
 // non-negative, so the relative error is bounded by about (dsub+1) * 2^-24.
@@ -55,8 +62,103 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
     }
 }
 
+// Matrix-core form of the Tables step (Eq. (tables)) for sub-vectors of 8 dimensions and more:
+//   ||y - c||^2 = ||y||^2 + ||c||^2 - 2 <y, c>,
+// with the inner products of 64 queries x 64 centroids per block on the fp64 matrix cores
+// (v_mfma_f64_16x16x4f64) and the norms accumulated next to them, everything in double.  Double
+// is what makes the expanded form safe: in fp32 the cancellation between the three terms costs
+// more than the 1e-5 this path may lose, in double it costs nothing that survives the final
+// rounding to float.  Entries that cancel almost completely (query on top of a centroid) are
+// recomputed from the differences, so that exact zeros stay exact.
+// Block: 256 threads = 4 waves in a 2 x 2 grid, each wave 32 x 32 outputs as 2 x 2 MFMA tiles.
+constexpr int MT = 64;   // queries and centroids per block
+constexpr int MK = 16;   // dimensions per LDS chunk
+__global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__restrict__ queries,
+                                                              const float *__restrict__ codebooks, int nq, int d, int m,
+                                                              int k, float *__restrict__ luts) {
+    typedef double double4_t __attribute__((ext_vector_type(4)));
+    __shared__ double ys[MK][MT + 2];
+    __shared__ double cs[MK][MT + 2];
+    __shared__ double ny[MT], nc[MT];
+    const int ds = d / m;
+    const int j = blockIdx.z, q0 = blockIdx.y * MT, c0 = blockIdx.x * MT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    const float *ybase = queries + (size_t)j * ds;                 // row q: + q * d
+    const float *cbase = codebooks + (size_t)j * k * ds;           // row c: + c * ds
+    double4_t acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = (double4_t){0.0, 0.0, 0.0, 0.0};
+    double norm = 0.0;   // thread t < 64: ||y_t||^2, thread 64 + t: ||c_t||^2
+    const int lrow = tid >> 2, lk = (tid & 3) * 4;   // this thread stages 4 consecutive dimensions of one row
+    for (int k0 = 0; k0 < ds; k0 += MK) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = k0 + lk + i;
+            const bool in = t < ds;
+            ys[lk + i][lrow] = in && q0 + lrow < nq ? (double)ybase[(size_t)(q0 + lrow) * d + t] : 0.0;
+            cs[lk + i][lrow] = in && c0 + lrow < k ? (double)cbase[(size_t)(c0 + lrow) * ds + t] : 0.0;
+        }
+        __syncthreads();
+        if (tid < 2 * MT) {
+            const double(*src)[MT + 2] = tid < MT ? ys : cs;
+            const int r = tid & (MT - 1);
+#pragma unroll
+            for (int kk = 0; kk < MK; ++kk) norm += src[kk][r] * src[kk][r];
+        }
+#pragma unroll
+        for (int ks = 0; ks < MK; ks += 4) {
+            double a[2], b[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[t] = ys[ks + (lane >> 4)][wy * 32 + t * 16 + (lane & 15)];
+                b[t] = cs[ks + (lane >> 4)][wx * 32 + t * 16 + (lane & 15)];
+            }
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    if (tid < MT) ny[tid] = norm;
+    else if (tid < 2 * MT) nc[tid - MT] = norm;
+    __syncthreads();
+    // lane l of an MFMA tile holds rows l / 16 + 4 * v (v = 0..3) of column l % 16
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int r = wy * 32 + ta * 16 + (lane >> 4) + 4 * v, c = wx * 32 + tb * 16 + (lane & 15);
+                const int q = q0 + r, ci = c0 + c;
+                if (q >= nq || ci >= k) continue;
+                const double sum = ny[r] + nc[c];
+                double dist = sum - 2.0 * acc[ta][tb][v];
+                if (dist < 1e-9 * sum) {   // nearly complete cancellation: take the plain definition
+                    dist = 0.0;
+                    for (int t = 0; t < ds; ++t) {
+                        const double df = (double)ybase[(size_t)q * d + t] - (double)cbase[(size_t)ci * ds + t];
+                        dist += df * df;
+                    }
+                }
+                luts[((size_t)q * m + j) * k + ci] = (float)dist;
+            }
+}
+
 int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                       float *luts) {
+    if (d / m >= 8 && env_flag_on("PQ_LUT_MFMA")) {
+        dim3 mgrid((k + MT - 1) / MT, (nq + MT - 1) / MT, m);
+        if (mgrid.y > 65535 || mgrid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/64 above 65535");
+        build_luts_mfma_kernel<<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
+        PQ_HIP(ctx, hipGetLastError());
+        return PQ_OK;
+    }
     dim3 grid((k + LUT_TC - 1) / LUT_TC, m, (nq + LUT_TQ - 1) / LUT_TQ);
     if (grid.y > 65535 || grid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/16 above 65535");
     build_luts_kernel<<<grid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);

@@ -93,15 +93,35 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
         for (int b = 0; b < 2; ++b) acc[a][b] = (double4_t){0.0, 0.0, 0.0, 0.0};
     double norm = 0.0;   // thread t < 64: ||y_t||^2, thread 64 + t: ||c_t||^2
     const int lrow = tid >> 2, lk = (tid & 3) * 4;   // this thread stages 4 consecutive dimensions of one row
+    const bool yrow_ok = q0 + lrow < nq, crow_ok = c0 + lrow < k;
+    const float *yrow = ybase + (size_t)(yrow_ok ? q0 + lrow : 0) * d;
+    const float *crow = cbase + (size_t)(crow_ok ? c0 + lrow : 0) * ds;
+    const bool vec = (ds & 3) == 0 && (d & 3) == 0;   // rows start on 16-byte boundaries
+    // the chunk after the one being multiplied waits in registers
+    float yv[4], cv[4];
+    auto fetch = [&](int k0) {
+        const int t = k0 + lk;
+        if (vec && t + 4 <= ds) {
+            const float4 a = *reinterpret_cast<const float4 *>(yrow + t), b = *reinterpret_cast<const float4 *>(crow + t);
+            yv[0] = a.x; yv[1] = a.y; yv[2] = a.z; yv[3] = a.w;
+            cv[0] = b.x; cv[1] = b.y; cv[2] = b.z; cv[3] = b.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                yv[i] = t + i < ds ? yrow[t + i] : 0.f;
+                cv[i] = t + i < ds ? crow[t + i] : 0.f;
+            }
+        }
+    };
+    fetch(0);
     for (int k0 = 0; k0 < ds; k0 += MK) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int t = k0 + lk + i;
-            const bool in = t < ds;
-            ys[lk + i][lrow] = in && q0 + lrow < nq ? (double)ybase[(size_t)(q0 + lrow) * d + t] : 0.0;
-            cs[lk + i][lrow] = in && c0 + lrow < k ? (double)cbase[(size_t)(c0 + lrow) * ds + t] : 0.0;
+            ys[lk + i][lrow] = yrow_ok ? (double)yv[i] : 0.0;
+            cs[lk + i][lrow] = crow_ok ? (double)cv[i] : 0.0;
         }
         __syncthreads();
+        if (k0 + MK < ds) fetch(k0 + MK);
         if (tid < 2 * MT) {
             const double(*src)[MT + 2] = tid < MT ? ys : cs;
             const int r = tid & (MT - 1);

@@ -271,6 +271,42 @@ __global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__
     for (size_t p = tid; p < npairs; p += 1024) pair_out[p] += qlist_off[p / nprobe];
 }
 
+// First bound per query: float ADC (table order) of up to IVF_SEED_CODES codes taken from the
+// query's probed lists in probe order, each with the tables of its (query, list) pair; the topk-th
+// smallest distance, enlarged by a few units of fp32 rounding because the scan adds the same
+// eight or sixteen entries in another order.  +inf if the lists hold fewer than topk codes.
+constexpr int IVF_SEED_CODES = 4096;
+__global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict__ codes,
+                                                       const int64_t *__restrict__ list_offsets,
+                                                       const int32_t *__restrict__ probes, const float *__restrict__ luts,
+                                                       int nprobe, int m, int topk, float *tau0) {
+    __shared__ uint64_t skeys[IVF_SEED_CODES];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    int count = 0;
+    for (int r = 0; r < nprobe && count < IVF_SEED_CODES; ++r) {
+        const int l = probes[(size_t)q * nprobe + r];
+        const int64_t beg = list_offsets[l], size = list_offsets[l + 1] - beg;
+        const int take = (int)(size < IVF_SEED_CODES - count ? size : IVF_SEED_CODES - count);
+        const float *lut = luts + ((size_t)q * nprobe + r) * m * 256;
+        for (int i = tid; i < take; i += 256) {
+            const uint8_t *c = codes + (size_t)(beg + i) * m;
+            float dist = 0.f;
+            for (int j = 0; j < m; ++j) dist += lut[j * 256 + c[j]];
+            skeys[count + i] = ((uint64_t)f32_to_ord(dist) << 32) | (uint32_t)(count + i);
+        }
+        count += take;
+    }
+    int n2 = 64;
+    while (n2 < count) n2 <<= 1;
+    for (int i = count + tid; i < n2; i += 256) skeys[i] = KEY_EMPTY;
+    block_bitonic_sort(skeys, n2);
+    if (tid == 0) {
+        float bound = __builtin_inff();
+        if (count >= topk) bound = ord_to_f32((uint32_t)(skeys[topk - 1] >> 32)) * (1.f + 4e-6f);
+        tau0[q] = bound;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
@@ -310,6 +346,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_pairout = take(npairs_max * 4);
     const size_t o_qlists = take((size_t)qbatch * 4);
     const size_t o_qlistoff = take((size_t)(qbatch + 1) * 4);
+    const size_t o_tau0 = take((size_t)qbatch * 4);
     const size_t o_partial = take(max_lists * kpad * 8);
     const size_t state_bytes = tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
     const size_t o_state = take(state_bytes);
@@ -359,10 +396,13 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
         ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, nprobe, qlist_off, pair_out);
         PQ_HIP(ctx, hipGetLastError());
-        // Scan step
+        // Scan step, seeded with a first bound per query
+        float *tau0 = (float *)(ws + o_tau0);
+        ivf_seed_kernel<<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, m, topk, tau0);
+        PQ_HIP(ctx, hipGetLastError());
         uint32_t *tau_global = nullptr;
         rc = launch_scan_items(ctx, kind, L->codes, luts, nqb, nprobe, topk, items, nitems_dev, pairs_by_list, pair_out,
-                               partial, ws + o_state, state_bytes, &tau_global);
+                               partial, ws + o_state, state_bytes, tau0, &tau_global);
         if (rc) return rc;
         rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_global, kpad, nqb, topk, L->ids, false,
                                    out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);

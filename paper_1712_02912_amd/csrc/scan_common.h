@@ -70,12 +70,13 @@ int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *
                           void *out_val, int64_t *out_ids);
 // IVF: run the persistent scan kernel over a table of work items (see IvfItem).  `state` is a
 // caller-provided device region of tuned_state_bytes() bytes holding the per-query bounds,
-// histograms and the per-block candidate scratch; *tau_global_out receives the per-query bounds.
+// histograms and the per-block candidate scratch; tau0 (optional, [nq]) seeds the per-query bounds
+// (+inf: none); *tau_global_out receives the per-query bounds.
 size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu);
 int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
-                      uint32_t **tau_global_out);
+                      const float *tau0, uint32_t **tau_global_out);
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids);
 

@@ -963,7 +963,7 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     if (i0 == 0) *work_counter = 0;
     for (size_t i = i0; i < (size_t)ntau; i += stride) {
-        const bool seeded = tau0 != nullptr && i < (size_t)nq;
+        const bool seeded = tau0 != nullptr && i < (size_t)nq && tau0[i] < __builtin_inff();
         tau[i] = seeded ? f32_to_ord(tau0[i]) : tau_value;
         tau_ref[i] = seeded ? f32_to_ord(tau0[i]) : TAU_REF_UNSET;
         ncand[i] = 0;
@@ -1180,7 +1180,7 @@ size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu) {
 int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
-                      uint32_t **tau_global_out) {
+                      const float *tau0, uint32_t **tau_global_out) {
     const int qb = kind == KIND_U4_M16 ? 8 : 4;
     const bool small = topk <= 128;
     const int cap = 64 * (small ? E_SMALL : E_LARGE);
@@ -1197,7 +1197,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     a.nprobe = nprobe;
     a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
-                                                     0xff800000u, a.hist, L.nhist, nullptr, 0);
+                                                     0xff800000u, a.hist, L.nhist, tau0, nq);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     int rc = launch_by_kind(ctx, kind, small, true, a, nblocks);

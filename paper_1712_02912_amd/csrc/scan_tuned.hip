@@ -89,6 +89,13 @@ typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 
 // KIND_F32P_M8: the 8 x 256 float scan with pruning by 16-bit lower bounds (see scan_flush_pruned)
+// the sort of `count` keys pads them to a power of two, which must fit as well
+__device__ __forceinline__ bool n2_fits(int count, int capacity) {
+    int n2 = 64;
+    while (n2 < count) n2 <<= 1;
+    return n2 <= capacity;
+}
+
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3 };
 constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
 constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
@@ -581,6 +588,43 @@ __device__ __noinline__ void scan_emit_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) 
     }
 }
 
+// End of item, whole block, for a query whose result list overflowed but whose keys within the
+// bound fit into the (now idle) ring memory: gather them there, sort them with the whole block
+// and write the KPAD smallest.  Every thread of the block must call it.
+template <class SM, int QB, int E, int KPAD>
+__device__ __noinline__ void scan_overflow_sort(LDS_PTR(SM) sm, uint64_t *wave_buf, int q) {
+    constexpr int CAP = 64 * E;
+    const int lane = lane_id();
+    LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
+    uint64_t *keys = (uint64_t *)&sm->ring[0][0];   // generic pointer into LDS
+    if (threadIdx.x == 0) sm->out_cnt[q] = 0;
+    __syncthreads();
+    const uint32_t dev_bound = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t blk_bound = sm->tau_blk[q];
+    const uint32_t bound = dev_bound < blk_bound ? dev_bound : blk_bound;   // never above the bound of the first pass
+    const int cnt = ws->cnt[q];
+    const uint64_t *buf = wave_buf + (size_t)q * CAP;
+    for (int i0 = 0; i0 < cnt; i0 += 64) {
+        const uint64_t key = i0 + lane < cnt ? key_load(buf + i0 + lane) : KEY_EMPTY;
+        const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound;
+        const uint64_t mask = __ballot(pass);
+        if (mask == 0ull) continue;
+        int at = 0;
+        if (lane == 0) at = __hip_atomic_fetch_add(&sm->out_cnt[q], __popcll(mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        at = __builtin_amdgcn_readfirstlane(at) + (int)mask_prefix(mask);
+        if (pass) keys[at] = key;
+    }
+    __syncthreads();
+    const int total = sm->out_cnt[q];
+    int n2 = 64;
+    while (n2 < total) n2 <<= 1;
+    for (int i = total + threadIdx.x; i < n2; i += TUNED_THREADS) keys[i] = KEY_EMPTY;
+    block_bitonic_sort(keys, n2);
+    uint64_t *out = sm->slot_out[q];
+    for (int i = threadIdx.x; i < KPAD; i += TUNED_THREADS) out[i] = i < n2 ? keys[i] : KEY_EMPTY;
+    __syncthreads();
+}
+
 // End of item, wave q < QB: fold the lists of all waves for query q into the list of wave 0
 // and write KPAD keys (padded with KEY_EMPTY) to out.
 template <class SM, int QB, int E, int KPAD>
@@ -935,9 +979,22 @@ void scan_tuned_kernel(TunedArgs a) {
             __hip_atomic_fetch_add(sm.ncand[lane], sm.ncand_blk[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // queries whose result list overflowed (loose bounds, first items): cut every wave's list
         // to its k smallest keys and merge the lists instead
-        uint32_t overflow = 0;
+        // Overflowed queries whose keys within the bound fit into the ring memory are sorted there;
+        // the others get every wave's list cut to its k smallest keys and the lists merged.
+        constexpr int RING_KEYS = (int)(sizeof(sm.ring) / 8) & ~63;
+        uint32_t overflow = 0, sortable = 0;
 #pragma unroll
-        for (int q = 0; q < QB; ++q) overflow |= sm.out_cnt[q] > KPAD ? 1u << q : 0u;
+        for (int q = 0; q < QB; ++q) {
+            const int got = sm.out_cnt[q];
+            if (got > KPAD) {
+                if (got <= RING_KEYS && n2_fits(got, RING_KEYS)) sortable |= 1u << q;
+                else overflow |= 1u << q;
+            }
+        }
+        if (__builtin_expect(sortable != 0u, 0)) {
+            for (int q = 0; q < QB; ++q)
+                if ((sortable >> q) & 1u) scan_overflow_sort<SM, QB, E, KPAD>(smp, wave_buf, q);
+        }
         if (__builtin_expect(overflow != 0u, 0)) {
             scan_finish_wave<SM, QB, E>(smp, wave_buf, overflow);
             __syncthreads();
@@ -945,7 +1002,7 @@ void scan_tuned_kernel(TunedArgs a) {
         if (wave < QB && sm.slot_out[wave] != nullptr) {
             if ((overflow >> wave) & 1u) {
                 scan_merge_item<SM, QB, E, KPAD>(smp, block_scratch, sm.slot_out[wave]);
-            } else {
+            } else if (!((sortable >> wave) & 1u)) {
                 uint64_t *out = sm.slot_out[wave];
                 for (int i = sm.out_cnt[wave] + lane; i < KPAD; i += 64) out[i] = KEY_EMPTY;
             }

@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--skip-streaming", action="store_true")
     ap.add_argument("--ivf", action="store_true", help="also time ivf_adc_search on config 4 (allocates 8 GB of codes)")
     ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
+    ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
     ap.add_argument("--streaming-n", type=int, default=100_000_000)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (counter calibration under rocprofv3)")
@@ -186,6 +187,26 @@ def main():
                                     "frac_of_hbm_peak": gbs / HBM_PEAK_GBS, "G codes/s": ns * nq_s / (k_ms * 1e-3) / 1e9})
         result["streaming_pq8x8"] = stream
         del codes_s
+
+    # ---------------------------------------------------------------- Tables step alone, on request
+    if args.lut_shapes:
+        shapes = {"config1": (1000, 128, 8, 256), "config3": (1000, 960, 16, 256), "config4_coarse": (10000, 128, 1, 65536),
+                  "config4_residual_tables_40k_pairs": (40000, 128, 8, 256)}
+        tables = {}
+        gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_DATA + 9)
+        for name, (nq_t, d_t, m_t, k_t) in shapes.items():
+            q_t = torch.rand((nq_t, d_t), device="cuda", generator=gen)
+            cb_t = torch.rand((m_t, k_t, d_t // m_t), device="cuda", generator=gen)
+            ctx.pq_build_luts(q_t, cb_t)
+            sync()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                ctx.pq_build_luts(q_t, cb_t)
+            sync()
+            ms = (time.perf_counter() - t0) * 1e3 / 5
+            tables[name] = {"nq": nq_t, "d": d_t, "m": m_t, "k": k_t, "ms": ms, "TFLOP/s (2*nq*d*k, fp64 MFMA)": 2.0 * nq_t * d_t * k_t / ms / 1e9,
+                            "frac_of_fp64_mfma_peak": 2.0 * nq_t * d_t * k_t / ms / 1e9 / 78.6}
+        result["tables_step"] = tables
 
     # ---------------------------------------------------------------- IVF-ADC (BASELINE config 4), on request
     if args.ivf:

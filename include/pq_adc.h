@@ -75,7 +75,9 @@ int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes);
 /* Tables step, Eq. (tables) of Section 2.3.3:  luts[q][j][i] = || y_q^j - C^j[i] ||^2,
  * sub-space j = dimensions j*d/m .. (j+1)*d/m-1.
  *   queries   [nq][d] f32, codebooks [m][k][d/m] f32  ->  luts [nq][m][k] f32.
- * Requires d % m == 0, 1 <= k <= 65536. */
+ * Requires d % m == 0, 1 <= k <= 65536.  Sub-vectors of 8 dimensions and more are handled in
+ * double precision on the matrix cores (expanded form, entries rounded once to f32); shorter
+ * ones by differences in f32. */
 int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                   float *luts);
 
@@ -104,7 +106,16 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
  *   saturation); out_ids [nq][topk] i64.
  * Covered: (U8 codes, F32 tables, k = 256, m = 8 or 16), (U4 codes, U8 tables, k = 16,
  * m = 16), and any (U8 | U4 codes, F32 | U8 tables) with m*k <= 8192 through a slower
- * general kernel.  1 <= topk <= 1024, 0 <= n < 2^32. */
+ * general kernel.  1 <= topk <= 1024, 0 <= n < 2^32; `codes` 16-byte aligned.
+ * Float sums add the m entries in fp32, in table order or in a rotation of it (the result
+ * differs from the exact sum by at most (m-1) * 2^-24 relative either way).  For m = 8,
+ * k = 256 and n >= 65536 the kernel first dismisses codes by integer lower bounds of their
+ * distances (the pruning idea of Section 4.2) and forms float sums only for the rest; the
+ * result is that of the plain definition.  Integer sums are exact.
+ * Switches for tests and tuning, read from the environment at each call (unset = default):
+ * PQ_SCAN_PRUNE=0 (no lower-bound pruning), PQ_SCAN_FORCE_GENERAL=1 (general kernel for every
+ * shape), PQ_SCAN_BLOCKS / PQ_SCAN_ITEMS_PER_BLOCK (launch shape), PQ_LUT_MFMA=0 (pq_build_luts
+ * without the matrix cores). */
 int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
                      pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);
 

@@ -1287,7 +1287,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int ngroups = (nq + qb - 1) / qb;
     const int64_t block_tile = (int64_t)tile * TUNED_WAVES;
     // persistent blocks: one per CU (64 KB of tables and 16 waves of 128 registers fill a CU)
-    const int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+    int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+    if (nblocks_max < 1) nblocks_max = 1;
 
     // several items per block for balance, chunks of at least 8 block tiles
     int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;

@@ -368,6 +368,31 @@ def test_scan_f32_plain_loop_on_a_large_database(ctx, monkeypatch):
     run_float_scan(ctx, codes, orc.CODES_U8, luts_h[:2], 700)
 
 
+def test_switches_general_kernel_and_launch_shapes(ctx, monkeypatch):
+    """The general kernel on the shapes the tuned kernels normally take, and unusual launch shapes."""
+    r = np.random.default_rng(33)
+    codes = r.integers(0, 256, (120_001, 8), dtype=np.uint8)
+    luts_h = (r.random((6, 8, 256)) * 100).astype(np.float32)
+    qluts = r.integers(0, 256, (5, 16, 16), dtype=np.uint8)
+    monkeypatch.setenv("PQ_SCAN_FORCE_GENERAL", "1")
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    run_int_scan(ctx, codes, orc.CODES_U4_PACKED, qluts, 100)
+    monkeypatch.delenv("PQ_SCAN_FORCE_GENERAL")
+    for blocks, items in (("3", "1"), ("1000", "7"), ("1", "1")):
+        monkeypatch.setenv("PQ_SCAN_BLOCKS", blocks)
+        monkeypatch.setenv("PQ_SCAN_ITEMS_PER_BLOCK", items)
+        run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+        run_int_scan(ctx, codes, orc.CODES_U4_PACKED, qluts, 1000)
+
+
+def test_build_luts_without_matrix_cores(ctx, monkeypatch):
+    monkeypatch.setenv("PQ_LUT_MFMA", "0")
+    r = np.random.default_rng(34)
+    q = (r.random((19, 128)) * 255).astype(np.float32)
+    cb = (r.random((8, 256, 16)) * 255).astype(np.float32)
+    np.testing.assert_allclose(host(ctx.pq_build_luts(dev(q), dev(cb))), orc.build_luts(q, cb), rtol=4e-6, atol=0)
+
+
 # ----------------------------------------------------------------------------- full size (bench configuration)
 FULL_N, FULL_NQ = 25_000_000, 1000
 SAMPLE_Q = [0, 1, 7, 8, 123, 500, 640, 777, 998, 999]

@@ -4,7 +4,8 @@
  * The entry points follow the three-step search of the thesis (Section 2.3.3 "ANN
  * Search", Alg. 1): Index (ivf_adc_search), Tables (pq_build_luts, optionally followed
  * by pq_quantize_luts) and Scan (pq_adc_scan_topk), plus the second pass of the
- * two-pass search of Section 6.3 / Alg. 5 (pq_rerank_f32).
+ * two-pass search of Section 6.3 / Alg. 5 (pq_rerank_f32) and, on the database side, the
+ * encoder of Section 2.3.1 (pq_encode).
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller (for instance the
@@ -80,6 +81,16 @@ int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes);
  * ones by differences in f32. */
 int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                   float *luts);
+
+/* Encoder of the product quantizer (Section 2.3.1, "Vector Encoding"): sub-vector j of every
+ * vector is replaced by the index of the closest centroid of codebook j,
+ *   code_j(x) = argmin_i || x^j - C^j[i] ||^2, ties to the smallest i,
+ * decided on distances computed in double precision.
+ *   vectors [n][d] f32, codebooks [m][k][d/m] f32  ->  codes [n][code_bytes] u8
+ * (PQ_CODES_U8: m bytes, k <= 256; PQ_CODES_U4_PACKED: m/2 bytes, k <= 16, m even).
+ * Requires d % m == 0. */
+int pq_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k,
+              pq_code_fmt cf, uint8_t *codes);
 
 /* 8-bit quantisation of each query's tables (Sections 4.2.4, 5.2.1; Section 6.3 Step 1.2
  * for the unsigned 0..254 + 255 range).  Per query q:

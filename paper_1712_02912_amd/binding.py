@@ -21,7 +21,7 @@ LUT_F32 = 0
 LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
-           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_set_profiling",
+           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_set_profiling",
            "pq_last_scan_kernel_ms", "pq_calibration_copy"]
 
 _lib = None
@@ -54,6 +54,7 @@ def load():
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
+    lib.pq_encode.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
     lib.pq_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.pq_set_profiling.argtypes = [vp, ci]
     lib.pq_last_scan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -185,6 +186,17 @@ class Context:
         self._check(self.lib.pq_rerank_f32(self.handle, _ptr(codes), codes.shape[0], code_fmt, _ptr(luts), nq, m, k,
                                            _ptr(cand_ids), ncand, topk, _ptr(dist), _ptr(ids)))
         return dist, ids
+
+    # -- Encoder ----------------------------------------------------------------------------
+    def pq_encode(self, vectors, codebooks, code_fmt=CODES_U8):
+        vectors = _dev(vectors, torch.float32, "vectors")
+        codebooks = _dev(codebooks, torch.float32, "codebooks")
+        n, d = vectors.shape
+        m, k, _ = codebooks.shape
+        code_bytes = m // 2 if code_fmt == CODES_U4_PACKED else m
+        codes = torch.empty((n, code_bytes), dtype=torch.uint8, device=vectors.device)
+        self._check(self.lib.pq_encode(self.handle, _ptr(vectors), _ptr(codebooks), n, d, m, k, code_fmt, _ptr(codes)))
+        return codes
 
     # -- Index + Tables + Scan ---------------------------------------------------------------
     def ivf_adc_search(self, coarse_centroids, list_offsets, codes, ids, codebooks, code_fmt, queries, nprobe, topk,

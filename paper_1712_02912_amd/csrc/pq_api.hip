@@ -193,6 +193,20 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
     return launch_rerank(ctx, codes, n, cf, luts, nq, m, k, cand_ids, ncand, topk, out_dist, out_ids);
 }
 
+int pq_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k,
+              pq_code_fmt cf, uint8_t *codes) {
+    if (!ctx) return PQ_EINVAL;
+    if (n < 0 || d <= 0 || m <= 0 || k <= 0) return fail(ctx, PQ_EINVAL, "encode: bad size");
+    if (cf != PQ_CODES_U8 && cf != PQ_CODES_U4_PACKED) return fail(ctx, PQ_EINVAL, "encode: bad code format");
+    if (d % m != 0) return fail(ctx, PQ_ESHAPE, "encode: d=%d is not a multiple of m=%d", d, m);
+    if (cf == PQ_CODES_U8 && k > 256) return fail(ctx, PQ_ESHAPE, "encode: k=%d does not fit one byte per index", k);
+    if (cf == PQ_CODES_U4_PACKED && (k > 16 || m % 2 != 0))
+        return fail(ctx, PQ_ESHAPE, "encode: packed 4-bit codes need k <= 16 and an even m (k=%d, m=%d)", k, m);
+    if (n == 0) return PQ_OK;
+    if (!vectors || !codebooks || !codes) return fail(ctx, PQ_EINVAL, "encode: null pointer");
+    return launch_encode(ctx, vectors, codebooks, n, d, m, k, cf, codes);
+}
+
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out) {

@@ -977,10 +977,9 @@ void scan_tuned_kernel(TunedArgs a) {
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
         if (wave == TUNED_WAVES - 1 && lane < QB && sm.ncand_blk[lane] != 0u)   // what the block has not reported yet
             __hip_atomic_fetch_add(sm.ncand[lane], sm.ncand_blk[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // queries whose result list overflowed (loose bounds, first items): cut every wave's list
-        // to its k smallest keys and merge the lists instead
-        // Overflowed queries whose keys within the bound fit into the ring memory are sorted there;
-        // the others get every wave's list cut to its k smallest keys and the lists merged.
+        // Queries whose result list overflowed (loose bounds, first items): if their keys within the
+        // bound fit into the ring memory they are sorted there; otherwise every wave's list is cut to
+        // its k smallest keys and the lists are merged.
         constexpr int RING_KEYS = (int)(sizeof(sm.ring) / 8) & ~63;
         uint32_t overflow = 0, sortable = 0;
 #pragma unroll
@@ -991,6 +990,7 @@ void scan_tuned_kernel(TunedArgs a) {
                 else overflow |= 1u << q;
             }
         }
+        __syncthreads();   // every wave has read the counters before any of them is reused
         if (__builtin_expect(sortable != 0u, 0)) {
             for (int q = 0; q < QB; ++q)
                 if ((sortable >> q) & 1u) scan_overflow_sort<SM, QB, E, KPAD>(smp, wave_buf, q);

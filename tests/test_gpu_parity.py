@@ -393,6 +393,40 @@ def test_build_luts_without_matrix_cores(ctx, monkeypatch):
     np.testing.assert_allclose(host(ctx.pq_build_luts(dev(q), dev(cb))), orc.build_luts(q, cb), rtol=4e-6, atol=0)
 
 
+# ----------------------------------------------------------------------------- encoder
+@pytest.mark.parametrize("m,k,d,n,fmt", [(8, 256, 128, 100_000, orc.CODES_U8), (16, 16, 128, 33_333, orc.CODES_U4_PACKED),
+                                         (16, 256, 960, 5_001, orc.CODES_U8), (4, 7, 20, 1_000, orc.CODES_U8),
+                                         (2, 16, 6, 129, orc.CODES_U4_PACKED), (1, 200, 33, 63, orc.CODES_U8)])
+def test_encode_bit_exact(ctx, m, k, d, n, fmt):
+    """Codes of mixture data against trained-like codebooks equal the oracle's, index for index."""
+    mix = datagen.sift_like() if d == 128 else (datagen.gist_like() if d == 960 else None)
+    r = np.random.default_rng(m * 1000 + k)
+    if mix is not None:
+        x = mix.sample(n, datagen.SEED_DATA + 3)
+        cb = datagen.sampled_codebooks(mix, m, k)
+    else:
+        x = (r.random((n, d)) * 10).astype(np.float32)
+        cb = (r.random((m, k, d // m)) * 10).astype(np.float32)
+    ref = orc.pq_encode(x, cb)
+    if fmt == orc.CODES_U4_PACKED:
+        ref = orc.pack_u4(ref)
+    got = host(ctx.pq_encode(dev(x), dev(cb), fmt))
+    assert np.array_equal(got, ref)
+
+
+def test_encode_ties_and_exact_hits(ctx):
+    """Duplicate centroids tie exactly (smallest index wins); vectors that are centroids encode to themselves."""
+    r = np.random.default_rng(77)
+    cb = (r.random((8, 256, 16)) * 255).astype(np.float32)
+    cb[:, 200:] = cb[:, :56]                      # duplicates of centroids 0..55
+    pick = r.integers(0, 256, (5000, 8))
+    x = np.concatenate([cb[j][pick[:, j]] for j in range(8)], axis=1)
+    got = host(ctx.pq_encode(dev(x), dev(cb)))
+    assert np.array_equal(got, orc.pq_encode(x, cb))
+    assert np.array_equal(got, np.where(pick >= 200, pick - 200, pick).astype(np.uint8))
+    assert host(ctx.pq_encode(dev(x[:0]), dev(cb))).shape == (0, 8)
+
+
 # ----------------------------------------------------------------------------- full size (bench configuration)
 FULL_N, FULL_NQ = 25_000_000, 1000
 SAMPLE_Q = [0, 1, 7, 8, 123, 500, 640, 777, 998, 999]

@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--skip-streaming", action="store_true")
     ap.add_argument("--ivf", action="store_true", help="also time ivf_adc_search on config 4 (allocates 8 GB of codes)")
     ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
+    ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
+    ap.add_argument("--encode-n", type=int, default=4_000_000)
     ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
     ap.add_argument("--streaming-n", type=int, default=100_000_000)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -207,6 +209,26 @@ def main():
             tables[name] = {"nq": nq_t, "d": d_t, "m": m_t, "k": k_t, "ms": ms, "TFLOP/s (2*nq*d*k, fp64 MFMA)": 2.0 * nq_t * d_t * k_t / ms / 1e9,
                             "frac_of_fp64_mfma_peak": 2.0 * nq_t * d_t * k_t / ms / 1e9 / 78.6}
         result["tables_step"] = tables
+
+    # ---------------------------------------------------------------- encoder, on request
+    if args.encode:
+        ne = args.encode_n
+        x_e = torch.from_numpy(mix.sample(ne, datagen.SEED_DATA + 11)).cuda()
+        enc = {}
+        for name, cb_e, fmt_e in (("pq8x8", cb8, binding.CODES_U8),
+                                  ("pq16x4", torch.from_numpy(datagen.sampled_codebooks(mix, 16, 16)).cuda(), binding.CODES_U4_PACKED)):
+            ctx.pq_encode(x_e, cb_e, fmt_e)
+            sync()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                ctx.pq_encode(x_e, cb_e, fmt_e)
+            sync()
+            ms = (time.perf_counter() - t0) * 1e3 / 3
+            flops = 2.0 * ne * 128 * cb_e.shape[1]
+            enc[name] = {"vectors": ne, "ms": ms, "M vectors/s": ne / ms / 1e3, "TFLOP/s (2*n*d*k, fp64 MFMA)": flops / ms / 1e9,
+                         "frac_of_fp64_mfma_peak": flops / ms / 1e9 / 78.6}
+        result["encode"] = enc
+        del x_e
 
     # ---------------------------------------------------------------- IVF-ADC (BASELINE config 4), on request
     if args.ivf:

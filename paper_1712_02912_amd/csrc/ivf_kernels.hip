@@ -26,9 +26,11 @@ constexpr int IVF_QB = 4;                     // queries per work item (float ta
 
 // ------------------------------------------------------------------------------------------
 // nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.
-// Histogram of the top 12 bits of the ordered value -> bin holding the nprobe-th; everything
-// in lower bins and in that bin is sorted in LDS.  If that is too much (heavy ties), bisection
-// on the 64-bit key over the whole row.
+// Fast path for long rows: a threshold guessed from a sorted sample of 1024 entries (aimed at three
+// times nprobe entries at or below it), one pass that collects the keys at or below it, sort.
+// If the guess caught fewer than nprobe or more than fit: histogram of the top 12 bits of the
+// ordered value -> bin holding the nprobe-th; everything in lower bins and in that bin is sorted
+// in LDS.  If that is too much (heavy ties), bisection on the 64-bit key over the whole row.
 constexpr int SEL_CAP = 4096;
 __global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__restrict__ dist, int nlist,
                                                                 int nprobe, int32_t *__restrict__ probes,
@@ -40,59 +42,85 @@ __global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__r
     __shared__ unsigned long long s_kth;
     const int q = blockIdx.x, tid = threadIdx.x;
     const float *row = dist + (size_t)q * nlist;
-    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
-    if (tid == 0) { s_bin = 4095; s_count = 0; }
-    __syncthreads();
-    for (int i = tid; i < nlist; i += 256) atomicAdd(&hist[f32_to_ord(row[i]) >> 20], 1u);
-    __syncthreads();
-    // thread t owns bins 16t .. 16t+15
-    uint32_t mine = 0;
-    for (int b = 0; b < 16; ++b) mine += hist[tid * 16 + b];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t cum = 0;
-        int t = 0;
-        for (; t < 256; ++t) { if (cum + part[t] >= (uint32_t)nprobe) break; cum += part[t]; }
-        int b = t * 16;
-        for (; b < t * 16 + 16 && b < 4096; ++b) { if (cum + hist[b] >= (uint32_t)nprobe) break; cum += hist[b]; }
-        s_bin = b < 4096 ? b : 4095;
-    }
-    __syncthreads();
-    const uint32_t bin = (uint32_t)s_bin;
-    for (int i = tid; i < nlist; i += 256) {
-        const uint32_t o = f32_to_ord(row[i]);
-        if ((o >> 20) <= bin) {
-            const int pos = atomicAdd(&s_count, 1);
-            if (pos < SEL_CAP) cand[pos] = ((uint64_t)o << 32) | (uint32_t)i;
-        }
-    }
-    __syncthreads();
-    int total = s_count;
-    if (total > SEL_CAP) {
-        // bisection: smallest key v with count(key <= v) >= nprobe
-        uint64_t v = 0;
-        for (int bit = 63; bit >= 0; --bit) {
-            const uint64_t trial = v | ((1ull << bit) - 1ull);
-            __syncthreads();
-            if (tid == 0) s_count = 0;
-            __syncthreads();
-            int c = 0;
-            for (int i = tid; i < nlist; i += 256) c += ((((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i) <= trial) ? 1 : 0;
-            atomicAdd(&s_count, c);
-            __syncthreads();
-            if (s_count < nprobe) v |= (1ull << bit);
+    bool done = false;
+    if (nlist >= 8192 && (nlist & 3) == 0 && (size_t)nprobe * 3 * 1024 / nlist + 8 < 1024) {
+        const int stride = nlist / 1024;
+        for (int i = tid; i < 1024; i += 256) cand[i] = ((uint64_t)f32_to_ord(row[(size_t)i * stride]) << 32) | (uint32_t)i;
+        if (tid == 0) s_count = 0;
+        block_bitonic_sort(cand, 1024);
+        const uint32_t guess = (uint32_t)(cand[(size_t)nprobe * 3 * 1024 / nlist + 8] >> 32);
+        __syncthreads();
+        const float4 *row4 = reinterpret_cast<const float4 *>(row);   // rows start on 16-byte boundaries (nlist % 4 == 0)
+        for (int i = tid; i < nlist / 4; i += 256) {
+            const float4 v = row4[i];
+            const uint32_t o[4] = {f32_to_ord(v.x), f32_to_ord(v.y), f32_to_ord(v.z), f32_to_ord(v.w)};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (o[e] <= guess) {
+                    const int pos = atomicAdd(&s_count, 1);
+                    if (pos < SEL_CAP) cand[pos] = ((uint64_t)o[e] << 32) | (uint32_t)(4 * i + e);
+                }
         }
         __syncthreads();
-        if (tid == 0) { s_kth = v; s_count = 0; }
+        done = s_count >= nprobe && s_count <= SEL_CAP;
         __syncthreads();
-        const uint64_t kth = s_kth;
+    }
+    int total = done ? s_count : 0;
+    if (!done) {
+        for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+        if (tid == 0) { s_bin = 4095; s_count = 0; }
+        __syncthreads();
+        for (int i = tid; i < nlist; i += 256) atomicAdd(&hist[f32_to_ord(row[i]) >> 20], 1u);
+        __syncthreads();
+        // thread t owns bins 16t .. 16t+15
+        uint32_t mine = 0;
+        for (int b = 0; b < 16; ++b) mine += hist[tid * 16 + b];
+        part[tid] = mine;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            int t = 0;
+            for (; t < 256; ++t) { if (cum + part[t] >= (uint32_t)nprobe) break; cum += part[t]; }
+            int b = t * 16;
+            for (; b < t * 16 + 16 && b < 4096; ++b) { if (cum + hist[b] >= (uint32_t)nprobe) break; cum += hist[b]; }
+            s_bin = b < 4096 ? b : 4095;
+        }
+        __syncthreads();
+        const uint32_t bin = (uint32_t)s_bin;
         for (int i = tid; i < nlist; i += 256) {
-            const uint64_t key = ((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i;
-            if (key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < SEL_CAP) cand[pos] = key; }
+            const uint32_t o = f32_to_ord(row[i]);
+            if ((o >> 20) <= bin) {
+                const int pos = atomicAdd(&s_count, 1);
+                if (pos < SEL_CAP) cand[pos] = ((uint64_t)o << 32) | (uint32_t)i;
+            }
         }
         __syncthreads();
-        total = s_count;   // exactly nprobe (keys are unique)
+        total = s_count;
+        if (total > SEL_CAP) {
+            // bisection: smallest key v with count(key <= v) >= nprobe
+            uint64_t v = 0;
+            for (int bit = 63; bit >= 0; --bit) {
+                const uint64_t trial = v | ((1ull << bit) - 1ull);
+                __syncthreads();
+                if (tid == 0) s_count = 0;
+                __syncthreads();
+                int c = 0;
+                for (int i = tid; i < nlist; i += 256) c += ((((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i) <= trial) ? 1 : 0;
+                atomicAdd(&s_count, c);
+                __syncthreads();
+                if (s_count < nprobe) v |= (1ull << bit);
+            }
+            __syncthreads();
+            if (tid == 0) { s_kth = v; s_count = 0; }
+            __syncthreads();
+            const uint64_t kth = s_kth;
+            for (int i = tid; i < nlist; i += 256) {
+                const uint64_t key = ((uint64_t)f32_to_ord(row[i]) << 32) | (uint32_t)i;
+                if (key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < SEL_CAP) cand[pos] = key; }
+            }
+            __syncthreads();
+            total = s_count;   // exactly nprobe (keys are unique)
+        }
     }
     int n2 = 64;
     while (n2 < total) n2 <<= 1;

@@ -122,3 +122,20 @@ def test_ivf_errors(ctx):
         ctx.ivf_adc_search(z(4, 16), z(5, dt=torch.int64), z(6, 4, dt=torch.uint8), None, z(4, 256, 4), binding.CODES_U8,
                            z(1, 16), 2, 3)
     assert e.value.code == -3      # m = 4 is outside the covered shapes
+
+
+def test_ivf_many_lists_probe_selection(ctx):
+    """16 384 lists (the probe selection's sampled-threshold path), random codes, Zipf-like list sizes."""
+    r = np.random.default_rng(61)
+    d, m, nlist, n = 32, 8, 16384, 300_000
+    sizes = datagen.zipf_list_sizes(n, nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    codes = r.integers(0, 256, (n, m), dtype=np.uint8)
+    coarse = (r.random((nlist, d)) * 100).astype(np.float32)
+    cb = (r.random((m, 256, d // m)) * 20 - 10).astype(np.float32)
+    queries = (r.random((40, d)) * 100).astype(np.float32)
+    queries[3] = coarse[77]                      # a query on top of a centroid
+    coarse[200:232] = coarse[100:132]            # duplicate centroids: exact ties of coarse distances
+    for nprobe, topk in ((1, 10), (16, 100), (64, 128)):
+        run_ivf(ctx, queries, coarse, offsets, codes, None, cb, nprobe, topk)
+

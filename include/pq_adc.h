@@ -82,6 +82,13 @@ int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes);
 int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                   float *luts);
 
+/* Rotation of optimized product quantization (Section 2.3.4, paragraph on OPQ:
+ * opq(x) = pq(R x) with R orthogonal): out[p] = R * vectors[p], to be applied to database
+ * vectors before pq_encode and to queries before pq_build_luts.
+ *   vectors [n][d] f32, rot [d][d] f32 row-major  ->  out [n][d] f32 (must not overlap vectors).
+ * Sums in double precision, rounded once.  At most 2^28 vectors per call. */
+int pq_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out);
+
 /* Encoder of the product quantizer (Section 2.3.1, "Vector Encoding"): sub-vector j of every
  * vector is replaced by the index of the closest centroid of codebook j,
  *   code_j(x) = argmin_i || x^j - C^j[i] ||^2, ties to the smallest i,

@@ -17,6 +17,7 @@
  *   - 8-bit table quantisation                : Section 4.2.4 "Quantization of Distances",
  *                                               Section 5.2.1, Section 6.3 Step 1.2
  *   - two-pass search (candidates + rerank)   : Section 6.3, Alg. 5
+ *   - rotation of optimized product quantization : Section 2.3.4 (OPQ paragraph)
  *
  * Arithmetic: floating-point sums are accumulated in double and rounded once to
  * float, except the table quantiser, whose float operation sequence is fixed
@@ -162,6 +163,24 @@ int orc_pack_u4(const uint8_t *codes, int64_t n, int m, uint8_t *packed /* [n][m
             uint8_t lo = codes[p * m + 2 * r], hi = codes[p * m + 2 * r + 1];
             if (lo > 15 || hi > 15) return -2;
             packed[p * (m / 2) + r] = (uint8_t)(lo | (hi << 4));
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Rotation of optimized product quantization (Section 2.3.4, paragraph OPQ):
+ * opq(x) = pq(R x) with R a d x d orthogonal matrix; this is the product R x,
+ * out[p][r] = sum_t R[r][t] * x[p][t], accumulated in double in index order and
+ * rounded once.  (R is data: learning it is outside the search path.) */
+int orc_rotate(const float *x, int64_t n, int d, const float *R /* [d][d] */, float *out /* [n][d] */)
+{
+    if (d <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < n; p++)
+        for (int r = 0; r < d; r++) {
+            double acc = 0.0;
+            for (int t = 0; t < d; t++) acc += (double)R[(size_t)r * d + t] * (double)x[p * d + t];
+            out[p * d + r] = (float)acc;
         }
     return 0;
 }

@@ -100,6 +100,16 @@ def pack_u4(codes):
     return out
 
 
+def rotate(x, R):
+    x = _f32(x)
+    R = _f32(R)
+    n, d = x.shape
+    assert R.shape == (d, d)
+    out = np.empty((n, d), np.float32)
+    _check(lib().orc_rotate(_p(x), _i64(n), d, _p(R), _p(out)), "rotate")
+    return out
+
+
 def build_luts(queries, codebooks):
     queries = _f32(queries)
     codebooks = _f32(codebooks)

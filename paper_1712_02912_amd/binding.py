@@ -21,7 +21,7 @@ LUT_F32 = 0
 LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
-           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_set_profiling",
+           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_set_profiling",
            "pq_last_scan_kernel_ms", "pq_calibration_copy"]
 
 _lib = None
@@ -54,6 +54,7 @@ def load():
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
+    lib.pq_rotate.argtypes = [vp, vp, vp, i64, ci, vp]
     lib.pq_encode.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
     lib.pq_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.pq_set_profiling.argtypes = [vp, ci]
@@ -186,6 +187,17 @@ class Context:
         self._check(self.lib.pq_rerank_f32(self.handle, _ptr(codes), codes.shape[0], code_fmt, _ptr(luts), nq, m, k,
                                            _ptr(cand_ids), ncand, topk, _ptr(dist), _ptr(ids)))
         return dist, ids
+
+    # -- OPQ rotation ------------------------------------------------------------------------
+    def pq_rotate(self, vectors, rot):
+        vectors = _dev(vectors, torch.float32, "vectors")
+        rot = _dev(rot, torch.float32, "rot")
+        n, d = vectors.shape
+        if tuple(rot.shape) != (d, d):
+            raise ValueError("rot must be [d][d]")
+        out = torch.empty_like(vectors)
+        self._check(self.lib.pq_rotate(self.handle, _ptr(vectors), _ptr(rot), n, d, _ptr(out)))
+        return out
 
     # -- Encoder ----------------------------------------------------------------------------
     def pq_encode(self, vectors, codebooks, code_fmt=CODES_U8):

@@ -73,6 +73,8 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
 // Block: 256 threads = 4 waves in a 2 x 2 grid, each wave 32 x 32 outputs as 2 x 2 MFMA tiles.
 constexpr int MT = 64;   // queries and centroids per block
 constexpr int MK = 16;   // dimensions per LDS chunk
+// DOT: write the inner products themselves (out[q][c] = <y_q, c>, used for R x) instead of distances.
+template <bool DOT>
 __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__restrict__ queries,
                                                               const float *__restrict__ codebooks, int nq, int d, int m,
                                                               int k, float *__restrict__ luts) {
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
         }
         __syncthreads();
         if (k0 + MK < ds) fetch(k0 + MK);
-        if (tid < 2 * MT) {
+        if (!DOT && tid < 2 * MT) {
             const double(*src)[MT + 2] = tid < MT ? ys : cs;
             const int r = tid & (MT - 1);
 #pragma unroll
@@ -157,6 +159,10 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
                 const int r = wy * 32 + ta * 16 + (lane >> 4) + 4 * v, c = wx * 32 + tb * 16 + (lane & 15);
                 const int q = q0 + r, ci = c0 + c;
                 if (q >= nq || ci >= k) continue;
+                if (DOT) {
+                    luts[((size_t)q * m + j) * k + ci] = (float)acc[ta][tb][v];
+                    continue;
+                }
                 const double sum = ny[r] + nc[c];
                 double dist = sum - 2.0 * acc[ta][tb][v];
                 if (dist < 1e-9 * sum) {   // nearly complete cancellation: take the plain definition
@@ -175,7 +181,7 @@ int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks,
     if (d / m >= 8 && env_flag_on("PQ_LUT_MFMA")) {
         dim3 mgrid((k + MT - 1) / MT, (nq + MT - 1) / MT, m);
         if (mgrid.y > 65535 || mgrid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/64 above 65535");
-        build_luts_mfma_kernel<<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
+        build_luts_mfma_kernel<false><<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
         PQ_HIP(ctx, hipGetLastError());
         return PQ_OK;
     }
@@ -183,6 +189,24 @@ int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks,
     if (grid.y > 65535 || grid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/16 above 65535");
     build_luts_kernel<<<grid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
     PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// Rotation of optimized product quantization (Section 2.3.4, OPQ: opq(x) = pq(R x)):
+// out[p][r] = sum_t R[r][t] * x[p][t] -- the inner products of the vectors with the rows of R, on
+// the fp64 matrix cores, rounded once to float.
+int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out) {
+    const int64_t ytiles = (n + MT - 1) / MT;
+    if (ytiles > 65535 * 64) return fail(ctx, PQ_EUNSUPPORTED, "rotate: more than 2^28 vectors per call");
+    // the y dimension of a grid is limited to 65535 blocks: long inputs go in slices of rows
+    for (int64_t t0 = 0; t0 < ytiles; t0 += 65535) {
+        const int64_t rows0 = t0 * MT;
+        const int64_t rows = (n - rows0) < (int64_t)65535 * MT ? (n - rows0) : (int64_t)65535 * MT;
+        dim3 grid((d + MT - 1) / MT, (unsigned)((rows + MT - 1) / MT), 1);
+        build_luts_mfma_kernel<true><<<grid, 256, 0, ctx->stream>>>(vectors + (size_t)rows0 * d, rot, (int)rows, d, 1, d,
+                                                                    out + (size_t)rows0 * d);
+        PQ_HIP(ctx, hipGetLastError());
+    }
     return PQ_OK;
 }
 

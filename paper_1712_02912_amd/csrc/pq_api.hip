@@ -193,6 +193,15 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
     return launch_rerank(ctx, codes, n, cf, luts, nq, m, k, cand_ids, ncand, topk, out_dist, out_ids);
 }
 
+int pq_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out) {
+    if (!ctx) return PQ_EINVAL;
+    if (n < 0 || d <= 0) return fail(ctx, PQ_EINVAL, "rotate: bad size");
+    if (n == 0) return PQ_OK;
+    if (!vectors || !rot || !out) return fail(ctx, PQ_EINVAL, "rotate: null pointer");
+    if (vectors == out) return fail(ctx, PQ_EINVAL, "rotate: input and output must not overlap");
+    return launch_rotate(ctx, vectors, rot, n, d, out);
+}
+
 int pq_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k,
               pq_code_fmt cf, uint8_t *codes) {
     if (!ctx) return PQ_EINVAL;

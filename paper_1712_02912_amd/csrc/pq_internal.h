@@ -45,6 +45,7 @@ int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const fl
                   const int64_t *cand, int ncand, int topk, float *out_dist, int64_t *out_ids);
 int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, int lf, int nq, int m,
                 int k, int topk, void *out_val, int64_t *out_ids);
+int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out);
 int launch_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k, int cf,
                   uint8_t *codes);
 int launch_ivf(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, int cf,

@@ -393,6 +393,50 @@ def test_build_luts_without_matrix_cores(ctx, monkeypatch):
     np.testing.assert_allclose(host(ctx.pq_build_luts(dev(q), dev(cb))), orc.build_luts(q, cb), rtol=4e-6, atol=0)
 
 
+# ----------------------------------------------------------------------------- OPQ rotation
+@pytest.mark.parametrize("n,d", [(1000, 128), (77, 960), (4097, 20), (1, 8), (0, 16)])
+def test_rotate_matches_oracle(ctx, n, d):
+    r = np.random.default_rng(n + d)
+    x = (r.random((n, d)) * 255).astype(np.float32)
+    Q, _ = np.linalg.qr(r.standard_normal((d, d)))
+    R = Q.astype(np.float32)
+    got = host(ctx.pq_rotate(dev(x) if n else torch.empty((0, d), device="cuda"), dev(R)))
+    ref = orc.rotate(x, R)
+    # both sides add in double and round once; the orders differ, so the last float bit may
+    np.testing.assert_allclose(got, ref, rtol=2e-7, atol=1e-30 + 2e-7 * np.abs(ref).max() if n else 0)
+    if n:
+        assert (got == ref).mean() > 0.99
+        perm = r.permutation(d)
+        P = np.zeros((d, d), np.float32)
+        P[np.arange(d), perm] = 1.0
+        assert np.array_equal(host(ctx.pq_rotate(dev(x), dev(P))), x[:, perm])
+
+
+def test_opq_search_equals_search_on_rotated_data(ctx):
+    """opq(x) = pq(R x): rotating database and queries, encoding and scanning on the GPU gives the
+    oracle's results for the rotated data (rotation, encoder, tables and scan chained)."""
+    mix = datagen.sift_like()
+    r = np.random.default_rng(91)
+    Q, _ = np.linalg.qr(r.standard_normal((128, 128)))
+    R = Q.astype(np.float32)
+    x = mix.sample(70_000, datagen.SEED_DATA + 5)
+    y = mix.sample(9, datagen.SEED_QUERIES + 5)
+    xr, yr = ctx.pq_rotate(dev(x), dev(R)), ctx.pq_rotate(dev(y), dev(R))
+    cb = orc.rotate(mix.sample(256, 5), R).reshape(256, 8, 16).transpose(1, 0, 2).copy()   # centroids = rotated samples
+    codes = ctx.pq_encode(xr, dev(cb))
+    luts = ctx.pq_build_luts(yr, dev(cb))
+    d, i = ctx.pq_adc_scan_topk(codes, binding.CODES_U8, luts, 100)
+    xr_h, yr_h = host(xr), host(yr)
+    codes_h = orc.pq_encode(xr_h, cb)
+    assert np.array_equal(host(codes), codes_h)
+    luts_h = host(luts)
+    np.testing.assert_allclose(luts_h, orc.build_luts(yr_h, cb), rtol=4e-6)
+    od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, luts_h, 100)
+    gd, gi = host(d), host(i)
+    for q in range(len(y)):
+        check_float_topk(gd[q], gi[q], od[q], oi[q], codes_h, orc.CODES_U8, luts_h[q], len(codes_h))
+
+
 # ----------------------------------------------------------------------------- encoder
 @pytest.mark.parametrize("m,k,d,n,fmt", [(8, 256, 128, 100_000, orc.CODES_U8), (16, 16, 128, 33_333, orc.CODES_U4_PACKED),
                                          (16, 256, 960, 5_001, orc.CODES_U8), (4, 7, 20, 1_000, orc.CODES_U8),

@@ -379,6 +379,36 @@ def test_ivf_single_list_zero_centroid_is_flat_scan():
 
 
 # ----------------------------------------------------------------------------- input generators
+def test_rotate_identity_permutation_and_matmul():
+    """Section 2.3.4 (OPQ): R x.  Identity and permutations are exact; a general R matches a float64 product."""
+    r = np.random.default_rng(50)
+    x = (r.random((37, 24)) * 100 - 50).astype(np.float32)
+    assert np.array_equal(orc.rotate(x, np.eye(24, dtype=np.float32)), x)
+    perm = r.permutation(24)
+    P = np.zeros((24, 24), np.float32)
+    P[np.arange(24), perm] = 1.0                      # (P x)[r] = x[perm[r]]
+    assert np.array_equal(orc.rotate(x, P), x[:, perm])
+    R = r.standard_normal((24, 24)).astype(np.float32)
+    ref = x.astype(np.float64) @ R.astype(np.float64).T
+    np.testing.assert_allclose(orc.rotate(x, R), ref, rtol=1e-6, atol=1e-4)
+    # a transposed operand would give x @ R instead
+    assert not np.allclose(orc.rotate(x, R), x.astype(np.float64) @ R.astype(np.float64), rtol=1e-3, atol=1e-2)
+
+
+def test_rotate_orthogonal_preserves_distances():
+    """With R^T R = I distances are unchanged, so exact search results do not depend on the rotation."""
+    r = np.random.default_rng(51)
+    Q, _ = np.linalg.qr(r.standard_normal((32, 32)))
+    R = Q.astype(np.float32)
+    x = (r.random((50, 32)) * 255).astype(np.float32)
+    y = (r.random((5, 32)) * 255).astype(np.float32)
+    before = ((x[None].astype(np.float64) - y[:, None].astype(np.float64)) ** 2).sum(-1)
+    xr, yr = orc.rotate(x, R), orc.rotate(y, R)
+    after = ((xr[None].astype(np.float64) - yr[:, None].astype(np.float64)) ** 2).sum(-1)
+    np.testing.assert_allclose(after, before, rtol=1e-5)
+    assert np.array_equal(np.argsort(after, axis=1)[:, :5], np.argsort(before, axis=1)[:, :5])
+
+
 def test_datagen_is_seeded_and_shaped():
     mix = datagen.sift_like()
     a, b = mix.sample(100, 1), mix.sample(100, 1)

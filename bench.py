@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
     ap.add_argument("--encode-n", type=int, default=4_000_000)
     ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
-    ap.add_argument("--streaming-n", type=int, default=100_000_000)
+    ap.add_argument("--streaming-n", type=int, nargs="+", default=[100_000_000, 1_000_000_000])
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -171,24 +171,25 @@ def main():
 
     # ---------------------------------------------------------------- streaming mode (few queries, codes from HBM)
     if not args.skip_streaming:
-        ns = args.streaming_n
-        gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_CODES + 2)
-        codes_s = torch.randint(0, 256, (ns, 8), dtype=torch.uint8, device="cuda", generator=gen)
-        stream = {"workload": "N=%d random 8-byte codes (%.0f MB, larger than the Infinity Cache), top-%d; GB/s = code bytes "
-                              "of all passes / scan kernel time" % (ns, ns * 8 / 1e6, args.topk), "cases": []}
-        for nq_s in (8, 64):
-            luts_s = ctx.pq_build_luts(queries[:nq_s].contiguous(), cb8)
-            ms = []
-            for _ in range(4):
-                ctx.pq_adc_scan_topk(codes_s, binding.CODES_U8, luts_s, args.topk)
-                ms.append(ctx.pq_last_scan_kernel_ms())
-            k_ms = float(np.mean(ms[1:]))
-            passes = (nq_s + 7) // 8
-            gbs = ns * 8.0 * passes / (k_ms * 1e-3) / 1e9
-            stream["cases"].append({"queries": nq_s, "passes_over_the_codes": passes, "kernel_ms": k_ms, "GB/s": gbs,
-                                    "frac_of_hbm_peak": gbs / HBM_PEAK_GBS, "G codes/s": ns * nq_s / (k_ms * 1e-3) / 1e9})
+        stream = {"note": "random 8-byte codes, top-%d; GB/s = code bytes of all passes (8 queries share a pass) / scan "
+                          "kernel time; both sizes exceed the 256 MB Infinity Cache" % args.topk, "cases": []}
+        for ns in args.streaming_n:
+            gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_CODES + 2)
+            codes_s = torch.randint(0, 256, (ns, 8), dtype=torch.uint8, device="cuda", generator=gen)
+            for nq_s in (8, 64):
+                luts_s = ctx.pq_build_luts(queries[:nq_s].contiguous(), cb8)
+                ms = []
+                for _ in range(4):
+                    ctx.pq_adc_scan_topk(codes_s, binding.CODES_U8, luts_s, args.topk)
+                    ms.append(ctx.pq_last_scan_kernel_ms())
+                k_ms = float(np.mean(ms[1:]))
+                passes = (nq_s + 7) // 8
+                gbs = ns * 8.0 * passes / (k_ms * 1e-3) / 1e9
+                stream["cases"].append({"codes": ns, "queries": nq_s, "passes_over_the_codes": passes, "kernel_ms": k_ms,
+                                        "GB/s": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS,
+                                        "G codes/s": ns * nq_s / (k_ms * 1e-3) / 1e9})
+            del codes_s
         result["streaming_pq8x8"] = stream
-        del codes_s
 
     # ---------------------------------------------------------------- Tables step alone, on request
     if args.lut_shapes:

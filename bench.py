@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--skip-streaming", action="store_true")
     ap.add_argument("--ivf", action="store_true", help="also time ivf_adc_search on config 4 (allocates 8 GB of codes)")
     ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
+    ap.add_argument("--config3", action="store_true", help="also time config 3 (d=960, 16x8 codes, 1 M codes)")
     ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
     ap.add_argument("--encode-n", type=int, default=4_000_000)
     ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
@@ -190,6 +191,32 @@ def main():
                                         "G codes/s": ns * nq_s / (k_ms * 1e-3) / 1e9})
             del codes_s
         result["streaming_pq8x8"] = stream
+
+    # ---------------------------------------------------------------- config 3 (d=960, 16x8), on request
+    if args.config3:
+        mix3 = datagen.gist_like()
+        q3 = torch.from_numpy(mix3.sample(args.nq, datagen.SEED_QUERIES)).cuda()
+        cb3 = torch.from_numpy(datagen.sampled_codebooks(mix3, 16, 256)).cuda()
+        n3 = 1_000_000
+        codes3 = torch.from_numpy(datagen.random_codes(n3, 16, seed=datagen.SEED_CODES + 4)).cuda()
+
+        def step3():
+            l3 = ctx.pq_build_luts(q3, cb3)
+            return ctx.pq_adc_scan_topk(codes3, binding.CODES_U8, l3, args.topk)
+
+        step3()
+        sync()
+        k3 = []
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step3()
+            k3.append(ctx.pq_last_scan_kernel_ms())
+        sync()
+        ms3 = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["config3_pq16x8_d960"] = {"workload": "N=%d 16-byte codes, %d queries of d=960, tables 16x256 built each step, top-%d"
+                                         % (n3, args.nq, args.topk), "ms_per_step": ms3, "scan_kernel_ms": float(np.mean(k3)),
+                                         "G codes/s": n3 * args.nq / (ms3 * 1e-3) / 1e9,
+                                         "algorithmic GB/s (16 B per code per query)": n3 * 16.0 * args.nq / (float(np.mean(k3)) * 1e-3) / 1e9}
 
     # ---------------------------------------------------------------- Tables step alone, on request
     if args.lut_shapes:

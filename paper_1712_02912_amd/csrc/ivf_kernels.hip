@@ -330,7 +330,10 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
     block_bitonic_sort(skeys, n2);
     if (tid == 0) {
         float bound = __builtin_inff();
-        if (count >= topk) bound = ord_to_f32((uint32_t)(skeys[topk - 1] >> 32)) * (1.f + 4e-6f);
+        if (count >= topk) {
+            const float kth = ord_to_f32((uint32_t)(skeys[topk - 1] >> 32));
+            bound = kth + fabsf(kth) * 4e-6f;
+        }
         tau0[q] = bound;
     }
 }

@@ -1012,17 +1012,21 @@ void scan_tuned_kernel(TunedArgs a) {
 }
 
 // tau0 (optional, [nq]): a bound already known per query (at least k codes are at or below it);
-// it seeds the shared bound and serves as the reference of the query's histogram.
+// times tau0_scale (1, or slightly more when the scan adds in another order than the bound was
+// computed in) it seeds the shared bound and serves as the reference of the query's histogram.
 __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_t *ncand, uint32_t *mark,
                                   uint32_t *tau_ref, int ntau,
-                                  uint32_t tau_value, uint32_t *hist, size_t nhist, const float *tau0, int nq) {
+                                  uint32_t tau_value, uint32_t *hist, size_t nhist, const float *tau0, int nq,
+                                  float tau0_scale) {
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     if (i0 == 0) *work_counter = 0;
     for (size_t i = i0; i < (size_t)ntau; i += stride) {
         const bool seeded = tau0 != nullptr && i < (size_t)nq && tau0[i] < __builtin_inff();
-        tau[i] = seeded ? f32_to_ord(tau0[i]) : tau_value;
-        tau_ref[i] = seeded ? f32_to_ord(tau0[i]) : TAU_REF_UNSET;
+        // enlarged away from the value whatever its sign (tables handed in need not be distances)
+        const float bound = seeded ? tau0[i] + fabsf(tau0[i]) * (tau0_scale - 1.f) : 0.f;
+        tau[i] = seeded ? f32_to_ord(bound) : tau_value;
+        tau_ref[i] = seeded ? f32_to_ord(bound) : TAU_REF_UNSET;
         ncand[i] = 0;
         mark[i] = 0;
     }
@@ -1254,7 +1258,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     a.nprobe = nprobe;
     a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
-                                                     0xff800000u, a.hist, L.nhist, tau0, nq);
+                                                     0xff800000u, a.hist, L.nhist, tau0, nq, 1.f);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
     int rc = launch_by_kind(ctx, kind, small, true, a, nblocks);
@@ -1294,6 +1298,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
     if (nchunks > max_by_n) nchunks = max_by_n;
+    const int64_t min_chunks = (n + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits
+    if (nchunks < min_chunks) nchunks = min_chunks;
     if (nchunks < 1) nchunks = 1;
     int64_t chunk_codes = (n + nchunks - 1) / nchunks;
     chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
@@ -1310,7 +1316,10 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const size_t off_poff = off_tau0 + align_up((size_t)ntau * 4, 256);
     const size_t off_pscale = off_poff + align_up((size_t)ntau * 4, 256);
     const size_t off_qtabs = off_pscale + align_up((size_t)ntau * 4, 256);
-    const size_t total = prune ? off_qtabs + (size_t)ngroups * 2048 * sizeof(uint4) : off_tau0;
+    // the plain float loops get a first bound as well (enlarged by a few units of fp32 rounding: they
+    // add the table entries in a rotated order, the bound is computed in table order)
+    const bool seed_plain = !is_u4 && !prune && n >= PRUNE_INIT;
+    const size_t total = prune ? off_qtabs + (size_t)ngroups * 2048 * sizeof(uint4) : (seed_plain ? off_poff : off_tau0);
     rc = ws_reserve(ctx, total);
     if (rc) return rc;
     uint8_t *ws = (uint8_t *)ctx->ws;
@@ -1337,9 +1346,14 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         prune_tables_kernel<<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
         PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
+    } else if (seed_plain) {
+        tau0 = (float *)(ws + off_tau0);
+        rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, cb, 256, PRUNE_INIT, topk, tau0);
+        if (rc) return rc;
     }
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
-                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq);
+                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq,
+                                                     seed_plain ? 1.f + 4e-6f : 1.f);
     PQ_HIP(ctx, hipGetLastError());
     if (is_u4 && n >= PRUNE_MIN_N) {
         const int seed_codes = ngroups < STREAM_GROUPS ? SEED_CODES_STREAM : (topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT);

@@ -88,7 +88,8 @@ struct __align__(16) TunedSmemT {
 typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 
-// KIND_F32P_M8: the 8 x 256 float scan with pruning by 16-bit lower bounds (see scan_flush_pruned)
+// KIND_F32P_M8 / _M16: the 8 x 256 and 16 x 256 float scans with pruning by 16-bit lower bounds
+// (see scan_flush_pruned)
 // the sort of `count` keys pads them to a power of two, which must fit as well
 __device__ __forceinline__ bool n2_fits(int count, int capacity) {
     int n2 = 64;
@@ -96,7 +97,7 @@ __device__ __forceinline__ bool n2_fits(int count, int capacity) {
     return n2 <= capacity;
 }
 
-enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3 };
+enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3, KIND_F32P_M16 = 4 };
 constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
 constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
 constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain float scan
@@ -388,9 +389,9 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
 // integer test against the current thresholds, and for every (code, query) that still passes adds
 // the eight float entries in table order -- the order of the plain definition, Eq. (adc1) -- tests the
 // result against the float bound and appends it to the wave's list of the query.
-template <class SM, int E>
+template <class SM, int NT, int E>
 __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
-    constexpr int QB = 8, CPL = 2, CAP = 64 * E;
+    constexpr int QB = 8, CPL = 16 / NT, CAP = 64 * E;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     LdsWaveState *ws = &sm->ws[wave];
     const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
@@ -415,14 +416,14 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             const uint8_t *p = chunk_ptr + (size_t)(pos / CPL) * 16;
             if (pos + CPL <= ncodes) {
                 c = *reinterpret_cast<const uint4 *>(p);
-            } else if (pos < ncodes) {   // last lane of a ragged chunk: only its first code exists
+            } else if (CPL == 2 && pos < ncodes) {   // last lane of a ragged chunk: only its first code exists
                 const uint2 half = *reinterpret_cast<const uint2 *>(p);
                 c.x = half.x; c.y = half.y;
             }
         }
-        const LaneWalk<8> lw((uint32_t)(pos / CPL) & 15u);
+        const LaneWalk<NT> lw((uint32_t)(pos / CPL) & 15u);
         uint32_t acc[CPL][4];
-        code_values<8, true>(c, lw, [&](uint32_t off) {
+        code_values<NT, true>(c, lw, [&](uint32_t off) {
             const v4u v = *(const __attribute__((address_space(3))) v4u *)(lut_bytes + off);
             return make_uint4(v.x, v.y, v.z, v.w);
         }, acc);
@@ -470,6 +471,16 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             d += fl[1280 + ((w1 >> 8) & 255u)];
             d += fl[1536 + ((w1 >> 16) & 255u)];
             d += fl[1792 + (w1 >> 24)];
+            if constexpr (NT == 16) {   // one 16-byte code per lane: tables 8..15 index with c.z, c.w
+                d += fl[2048 + (c.z & 255u)];
+                d += fl[2304 + ((c.z >> 8) & 255u)];
+                d += fl[2560 + ((c.z >> 16) & 255u)];
+                d += fl[2816 + (c.z >> 24)];
+                d += fl[3072 + (c.w & 255u)];
+                d += fl[3328 + ((c.w >> 8) & 255u)];
+                d += fl[3584 + ((c.w >> 16) & 255u)];
+                d += fl[3840 + (c.w >> 24)];
+            }
             const uint32_t ord = f32_to_ord(d);
             uint32_t eff = eff_q[0];
 #pragma unroll
@@ -488,7 +499,8 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
         }
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            const int added = __popcll(__ballot((inserted >> q) & 1u)) + __popcll(__ballot((inserted >> (QB + q)) & 1u));
+            int added = __popcll(__ballot((inserted >> q) & 1u));
+            if (CPL == 2) added += __popcll(__ballot((inserted >> (QB + q)) & 1u));
             if (added != 0 && lane == 0)
                 __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
@@ -650,10 +662,10 @@ template <int KIND, int E, int KPAD, int BATCH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void scan_tuned_kernel(TunedArgs a) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;           // values are integer sums
-    constexpr bool PRUNED = KIND == KIND_F32P_M8;         // float values, scan loop on 16-bit lower bounds
+    constexpr bool PRUNED = KIND == KIND_F32P_M8 || KIND == KIND_F32P_M16;   // float values, scan loop on 16-bit lower bounds
     constexpr bool PACKED = IS_U4 || PRUNED;              // scan loop adds packed 16-bit entries, 8 queries
     constexpr int QB = PACKED ? 8 : 4;
-    constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;     // tables = lookups per code
+    constexpr int NT = KIND == KIND_F32_M16 || KIND == KIND_F32P_M16 ? 16 : 8;   // tables = lookups per code
     constexpr int CB = NT;                                // code bytes (8 or 16)
     constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
     constexpr int SUB = 64 * CPL;                         // codes per wave sub-tile (one load per lane)
@@ -747,11 +759,15 @@ void scan_tuned_kernel(TunedArgs a) {
         // ---- stage the tables of the slots' queries -----------------------------------------------
         if constexpr (PRUNED) {
             // 16-bit tables of the group, prepared in slot order: [group][byte][table] x 8 queries
-            const uint4 *qt = a.qtabs + (size_t)sm.group * 2048;
-            for (int e = threadIdx.x; e < 2048; e += TUNED_THREADS) {
+            const uint4 *qt = a.qtabs + (size_t)sm.group * (256 * NT);
+            for (int e = threadIdx.x; e < 256 * NT; e += TUNED_THREADS) {
                 const uint4 pk = qt[e];
-                sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
-                sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
+                if constexpr (NT == 8) {
+                    sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
+                    sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
+                } else {
+                    sm.lut[e] = pk;   // (e >> 4) * 16 + (e & 15)
+                }
             }
         } else if constexpr (!IS_U4) {
             for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
@@ -909,7 +925,7 @@ void scan_tuned_kernel(TunedArgs a) {
         auto between_steps = [&]() {
             bool changed = false;
             if (flush_due()) {
-                if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
+                if constexpr (PRUNED) scan_flush_pruned<SM, NT, E>(smp, wave_buf, ring_cnt);
                 else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
                 pressure += ring_cnt;
                 ring_cnt = 0;
@@ -970,7 +986,7 @@ void scan_tuned_kernel(TunedArgs a) {
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
         if (ring_cnt > 0) {
-            if constexpr (PRUNED) scan_flush_pruned<SM, E>(smp, wave_buf, ring_cnt);
+            if constexpr (PRUNED) scan_flush_pruned<SM, NT, E>(smp, wave_buf, ring_cnt);
             else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
         }
         scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
@@ -1124,18 +1140,21 @@ __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__r
 // 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
 // Per query: off = sum over the tables of their minimum entry, scale = PRUNE_RANGE / (tau0 - off)
 // (0, which disables the pruning of that query, if tau0 leaves no usable range), and for every table
-// L[j][b] = min(4095, floor((D[j][b] - min_j) * scale)).  Output in the slot order of the scan
-// kernel: qtabs[group][b][j] holds entry b of table j for the 8 queries of the group.
+// L[j][b] = min(32767 / M, floor((D[j][b] - min_j) * scale)) for the M = 8 or 16 tables.  Output in
+// the slot order of the scan kernel: qtabs[group][b][j] holds entry b of table j for the 8 queries
+// of the group.
+template <int M>
 __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
                                                            int nq, uint4 *qtabs, float *off_out, float *scale_out) {
-    __shared__ float smin[8][8];
+    constexpr float ENTRY_MAX = (float)(32767 / M);   // M entries must add up to less than 2^15
+    __shared__ float smin[8][M];
     __shared__ float sscale[8];
     const int group = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int r = wave * 16; r < wave * 16 + 16; ++r) {
-        const int q = r >> 3, j = r & 7, gq = group * 8 + q;
+    for (int r = wave * (2 * M); r < (wave + 1) * (2 * M); ++r) {
+        const int q = r / M, j = r % M, gq = group * 8 + q;
         float v = __builtin_inff();
         if (gq < nq) {
-            const float *t = luts + ((size_t)gq * 8 + j) * 256;
+            const float *t = luts + ((size_t)gq * M + j) * 256;
             v = fminf(fminf(t[lane], t[lane + 64]), fminf(t[lane + 128], t[lane + 192]));
         }
         for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
@@ -1147,7 +1166,7 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
         float scale = 0.f;
         if (gq < nq) {
             float off = 0.f;
-            for (int j = 0; j < 8; ++j) off += smin[tid][j];
+            for (int j = 0; j < M; ++j) off += smin[tid][j];
             const float range = tau0[gq] - off;
             if (range > 0.f && range < 3.0e38f) {
                 scale = PRUNE_RANGE / range;
@@ -1161,18 +1180,18 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
     }
     __syncthreads();
     const int b = tid;
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < M; ++j) {
         uint32_t e[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const int gq = group * 8 + q;
-            e[q] = 0x0fffu;   // no query in this slot
+            e[q] = (uint32_t)ENTRY_MAX;   // no query in this slot: sums that never qualify
             if (gq < nq) {
-                const float x = (luts[((size_t)gq * 8 + j) * 256 + b] - smin[q][j]) * sscale[q];
-                e[q] = (uint32_t)fminf(floorf(x), 4095.f);
+                const float x = (luts[((size_t)gq * M + j) * 256 + b] - smin[q][j]) * sscale[q];
+                e[q] = (uint32_t)fminf(floorf(x), ENTRY_MAX);
             }
         }
-        qtabs[(size_t)group * 2048 + b * 8 + j] =
+        qtabs[(size_t)group * (256 * M) + b * M + j] =
             make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
     }
 }
@@ -1228,6 +1247,7 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const 
         case KIND_F32_M8: return launch_kind_sized<KIND_F32_M8>(ctx, small, stream, a, nblocks);
         case KIND_F32_M16: return launch_kind_sized<KIND_F32_M16>(ctx, small, stream, a, nblocks);
         case KIND_F32P_M8: return launch_kind_sized<KIND_F32P_M8>(ctx, small, stream, a, nblocks);
+        case KIND_F32P_M16: return launch_kind_sized<KIND_F32P_M16>(ctx, small, stream, a, nblocks);
         default: return launch_kind_sized<KIND_U4_M16>(ctx, small, stream, a, nblocks);
     }
 }
@@ -1279,10 +1299,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const bool is_u4 = kind == KIND_U4_M16;
     // The 8 x 256 float scan prunes with 16-bit lower bounds when the database is large enough to
     // pay for the preparation (a bound per query from the first PRUNE_INIT codes, then the tables).
-    const bool prune = kind == KIND_F32_M8 && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
-    if (prune) kind = KIND_F32P_M8;
+    const bool prune = (kind == KIND_F32_M8 || kind == KIND_F32_M16) && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
+    const int tables = kind == KIND_F32_M16 ? 16 : 8;
+    if (prune) kind = tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8;
     const int qb = is_u4 || prune ? 8 : 4;
-    const int cb = kind == KIND_F32_M16 ? 16 : 8;
+    const int cb = kind == KIND_F32_M16 || kind == KIND_F32P_M16 ? 16 : 8;
     const int batch = ngroups_of(nq, is_u4 || prune) < STREAM_GROUPS ? 4 : 1;
     const int tile = 64 * (16 / cb) * batch;   // codes per wave tile (BATCH sub-tiles)
     const bool small = topk <= 128;
@@ -1319,7 +1340,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // the plain float loops get a first bound as well (enlarged by a few units of fp32 rounding: they
     // add the table entries in a rotated order, the bound is computed in table order)
     const bool seed_plain = !is_u4 && !prune && n >= PRUNE_INIT;
-    const size_t total = prune ? off_qtabs + (size_t)ngroups * 2048 * sizeof(uint4) : (seed_plain ? off_poff : off_tau0);
+    const size_t total = prune ? off_qtabs + (size_t)ngroups * 256 * tables * sizeof(uint4) : (seed_plain ? off_poff : off_tau0);
     rc = ws_reserve(ctx, total);
     if (rc) return rc;
     uint8_t *ws = (uint8_t *)ctx->ws;
@@ -1337,13 +1358,14 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         tau0 = (float *)(ws + off_tau0);
         float *poff = (float *)(ws + off_poff), *pscale = (float *)(ws + off_pscale);
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
-        rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, 8, 256, PRUNE_INIT, topk, tau0);
+        rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
         if (rc) return rc;
-        if (ngroups < STREAM_GROUPS) {
+        if (ngroups < STREAM_GROUPS && tables == 8) {
             f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, SEED_CODES_STREAM, (const float *)luts, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
-        prune_tables_kernel<<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
+        if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
+        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
         PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
     } else if (seed_plain) {

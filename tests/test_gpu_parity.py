@@ -243,6 +243,19 @@ def test_scan_f32_pruned_descending_order_worst_case(ctx):
     assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
 
 
+@pytest.mark.parametrize("n,nq,topk", [(65536, 3, 100), (200_001, 9, 128), (131_072, 2, 1000)])
+def test_scan_f32_pruned_16_tables(ctx, n, nq, topk):
+    """16 x 256 float tables on the pruned path: random tables, then tables with exact ties."""
+    r = np.random.default_rng(n + topk)
+    codes = r.integers(0, 256, (n, 16), dtype=np.uint8)
+    luts_h = (r.random((nq, 16, 256)) * 40 + r.random((nq, 16, 1)) * 300).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, topk)
+    luts_h = r.integers(0, 3, (nq, 16, 256)).astype(np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), topk)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, luts_h, topk)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+
+
 def test_scan_f32_pruned_encoded_duplicates(ctx):
     """Encoded mixture data (many identical codes), 37 queries: not a multiple of the group size."""
     _, queries, cb, codes = sift_pq(8, 256, 100000, 16)

@@ -77,7 +77,7 @@ struct __align__(16) TunedSmemT {
     int nvalid;                // slots in use
     int topk;
     int item;
-    int next_pair;             // next pair of tiles to hand to a wave
+    int next_group;            // next group of sub-tiles to hand to a wave
     int group;                 // flat scan: query group of the item
 };
 
@@ -658,7 +658,7 @@ __device__ __noinline__ void scan_merge_item(LDS_PTR(SM) sm, uint64_t *block_scr
     for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
 }
 
-template <int KIND, int E, int KPAD, int BATCH>
+template <int KIND, int E, int KPAD, int DEPTH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void scan_tuned_kernel(TunedArgs a) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;           // values are integer sums
@@ -669,13 +669,13 @@ void scan_tuned_kernel(TunedArgs a) {
     constexpr int CB = NT;                                // code bytes (8 or 16)
     constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
     constexpr int SUB = 64 * CPL;                         // codes per wave sub-tile (one load per lane)
-    // BATCH = sub-tiles fetched together: 1 when the codes are shared by many blocks through L2
-    // (flat scan), more when every block streams its own list from HBM (IVF)
-    constexpr int TILE = SUB * BATCH;                     // codes per wave tile
+    // DEPTH = sub-tiles a wave has in registers or on their way: 2 when the codes are shared by many
+    // blocks through L2 (flat scan of many query groups), 8 when every block streams its own codes
+    // from HBM (few groups, inverted lists).  A wave works through groups of DEPTH sub-tiles.
     constexpr int CAP = 64 * E;
     typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
     // ring: two tiles fit behind a ring that was not flushed
-    typedef TunedSmemT<RING_FLUSH + 2 * 64 * BATCH> SM;
+    typedef TunedSmemT<RING_FLUSH + 64 * DEPTH> SM;   // a group of sub-tiles fits behind a ring that was not flushed
     __shared__ SM sm;
     LDS_PTR(SM) smp = (LDS_PTR(SM))&sm;
 
@@ -753,7 +753,7 @@ void scan_tuned_kernel(TunedArgs a) {
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
         if (threadIdx.x < 8) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
-        if (threadIdx.x == 0) sm.next_pair = TUNED_WAVES;
+        if (threadIdx.x == 0) sm.next_group = 2 * TUNED_WAVES;
         __syncthreads();
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
@@ -843,14 +843,12 @@ void scan_tuned_kernel(TunedArgs a) {
 
         const int ncodes = sm.ncodes;                                      // rows of this item (below 2^31)
         const int nsub = (ncodes + SUB - 1) / SUB;                         // sub-tiles, the last may be ragged
-        const int nfull = ncodes / TILE;                                   // tiles with every code present
+        const int nfull = ncodes / SUB;                                    // sub-tiles with every code present
         const uint8_t *chunk_ptr = sm.chunk_ptr;
 
-        // the 16 bytes of this lane in each sub-tile of full tile t
-        auto load_full = [&](int t, uint4 (&c)[BATCH]) {
-            const uint8_t *p = chunk_ptr + (size_t)t * (TILE * CB) + lane * 16;
-#pragma unroll
-            for (int i = 0; i < BATCH; ++i) c[i] = *reinterpret_cast<const uint4 *>(p + i * (SUB * CB));
+        // the 16 bytes of this lane in full sub-tile t
+        auto load_full = [&](int t) -> uint4 {
+            return *reinterpret_cast<const uint4 *>(chunk_ptr + (size_t)t * (SUB * CB) + lane * 16);
         };
         // one sub-tile past the full tiles (zeros for codes past the end of the chunk)
         auto load_ragged = [&](int sidx) -> uint4 {
@@ -939,45 +937,47 @@ void scan_tuned_kernel(TunedArgs a) {
             if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
 
-        // Full tiles go in pairs, two register sets used in turn.  The next tile is requested only
-        // after the current one has arrived (the empty asm reads its last register), so that waiting
-        // for the current tile never waits for the one just requested; the loads are unconditional
-        // (past the last pair they re-read it and the data is dropped).  Pairs are handed out through
-        // a counter in LDS, one pair ahead, so that a wave held up by inserts or refreshes simply
-        // takes fewer pairs and the waves reach the end of the item together.  The inner loop holds
-        // no call.
-        const int npairs = nfull / 2;
-        int p = wave;   // the first pair of every wave is fixed, the counter starts behind them
-        if (p < npairs) {
-            uint4 bufa[BATCH], bufb[BATCH];
-            load_full(2 * p, bufa);
+        // Full sub-tiles go in groups of DEPTH, one register set per sub-tile of the group.  While
+        // a group is scanned, the sub-tiles of the wave's next group are requested into the registers
+        // just freed, so DEPTH - 1 loads are always on their way; a sub-tile is waited for right
+        // before its use (the empty asm reads its last register, and loads complete in order), so
+        // that wait never includes younger requests.  The loads are unconditional (past the last group
+        // they re-read it and the data is dropped).  Groups are handed out through a counter in LDS,
+        // two groups ahead, so that a wave held up by inserts or refreshes simply takes fewer groups
+        // and the waves reach the end of the item together.  The inner loop holds no call.
+        const int ngroups_t = nfull / DEPTH;
+        int g = wave, g_next = wave + TUNED_WAVES;   // the first two groups of a wave are fixed, the counter starts behind them
+        if (g < ngroups_t) {
+            uint4 buf[DEPTH];
+#pragma unroll
+            for (int i = 0; i < DEPTH; ++i) buf[i] = load_full(g * DEPTH + i);
             for (;;) {
                 bool more;
                 do {
-                    int next_v = 0;
-                    if (lane == 0) next_v = __hip_atomic_fetch_add(&sm.next_pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    asm volatile("" : "+v"(bufa[BATCH - 1].w) : : "memory");
-                    load_full(2 * p + 1, bufb);
+                    int after_v = 0;
+                    if (lane == 0) after_v = __hip_atomic_fetch_add(&sm.next_group, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    const int gl = g_next < ngroups_t ? g_next : ngroups_t - 1;
 #pragma unroll
-                    for (int i = 0; i < BATCH; ++i) scan_sub(bufa[i], 2 * p * BATCH + i);
-                    const int pn = __builtin_amdgcn_readfirstlane(next_v);
-                    asm volatile("" : "+v"(bufb[BATCH - 1].w) : : "memory");
-                    load_full(2 * (pn < npairs ? pn : npairs - 1), bufa);
-#pragma unroll
-                    for (int i = 0; i < BATCH; ++i) scan_sub(bufb[i], (2 * p + 1) * BATCH + i);
-                    p = pn;
+                    for (int i = 0; i < DEPTH; ++i) {
+                        asm volatile("" : "+v"(buf[i].w) : : "memory");
+                        const uint4 cur = buf[i];
+                        buf[i] = load_full(gl * DEPTH + i);
+                        scan_sub(cur, g * DEPTH + i);
+                    }
+                    g = g_next;
+                    g_next = __builtin_amdgcn_readfirstlane(after_v);
                     ++step;
                     ++gstep;
-                    more = p < npairs;
+                    more = g < ngroups_t;
                     if (step < 32 || (step & 3) == 0) reload_tau();
                 } while (__builtin_expect(more && !flush_due() && !refresh_due(), 1));
                 between_steps();
                 if (!more) break;
             }
         }
-        // what is left after the pairs: at most one full tile and the sub-tiles behind it (the very
-        // last one may be ragged), dealt round-robin
-        for (int sidx = 2 * npairs * BATCH + wave; sidx < nsub; sidx += TUNED_WAVES) {
+        // what is left after the groups: fewer than DEPTH full sub-tiles and possibly a ragged one,
+        // dealt round-robin
+        for (int sidx = ngroups_t * DEPTH + wave; sidx < nsub; sidx += TUNED_WAVES) {
             scan_sub(load_ragged(sidx), sidx);
             ++step;
             ++gstep;
@@ -1196,9 +1196,9 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
     }
 }
 
-template <int KIND, int E, int KPAD, int BATCH>
+template <int KIND, int E, int KPAD, int DEPTH>
 static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
-    scan_tuned_kernel<KIND, E, KPAD, BATCH><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
+    scan_tuned_kernel<KIND, E, KPAD, DEPTH><<<nblocks, TUNED_THREADS, 0, ctx->stream>>>(a);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }
@@ -1231,15 +1231,15 @@ static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
     a.scratch = (uint64_t *)(ws + L.off_scratch);
 }
 
-// BATCH (sub-tiles fetched together): one when the same codes serve many query groups at about the
-// same time and so come from the caches; four when they stream from HBM (inverted lists, scans
-// for few queries), which takes more bytes in flight per wave.
+// DEPTH (sub-tiles per group, see the kernel): two when the same codes serve many query groups at
+// about the same time and so come from the caches; eight when they stream from HBM (inverted
+// lists, scans for few queries), which takes more bytes on their way per wave.
 template <int KIND>
 static int launch_kind_sized(pq_ctx *ctx, bool small, bool stream, const TunedArgs &a, int nblocks) {
     if (stream) {
-        return small ? launch_kind<KIND, E_SMALL, 128, 4>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 4>(ctx, a, nblocks);
+        return small ? launch_kind<KIND, E_SMALL, 128, 8>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 8>(ctx, a, nblocks);
     }
-    return small ? launch_kind<KIND, E_SMALL, 128, 1>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 1>(ctx, a, nblocks);
+    return small ? launch_kind<KIND, E_SMALL, 128, 2>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 2>(ctx, a, nblocks);
 }
 
 static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const TunedArgs &a, int nblocks) {
@@ -1304,8 +1304,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     if (prune) kind = tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8;
     const int qb = is_u4 || prune ? 8 : 4;
     const int cb = kind == KIND_F32_M16 || kind == KIND_F32P_M16 ? 16 : 8;
-    const int batch = ngroups_of(nq, is_u4 || prune) < STREAM_GROUPS ? 4 : 1;
-    const int tile = 64 * (16 / cb) * batch;   // codes per wave tile (BATCH sub-tiles)
+    const int depth = ngroups_of(nq, is_u4 || prune) < STREAM_GROUPS ? 8 : 2;
+    const int tile = 64 * (16 / cb) * depth;   // codes per wave group (DEPTH sub-tiles)
     const bool small = topk <= 128;
     const int kpad = small ? 128 : 1024;
     const int cap = 64 * (small ? E_SMALL : E_LARGE);

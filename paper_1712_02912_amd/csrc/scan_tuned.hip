@@ -166,6 +166,9 @@ __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &l
     } else {
         rot16(w, lw.rot);
     }
+    // all reads first (they are independent of one another), then the additions: the LDS serves the
+    // 16 reads back to back while the first results are already being added up
+    uint4 v[CPL][NT];
 #pragma unroll
     for (int h = 0; h < CPL; ++h) {
 #pragma unroll
@@ -178,16 +181,24 @@ __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &l
                 case 2: off = lut_offset<2>(word, bs); break;
                 default: off = lut_offset<3>(word, bs); break;
             }
-            const uint4 v = ld(off);
+            v[h][s] = ld(off);
+        }
+    }
+    asm volatile("" : : : "memory");   // every read above is issued before any addition below
+#pragma unroll
+    for (int h = 0; h < CPL; ++h) {
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+            const uint4 e = v[h][s];
             if constexpr (IS_U4) {
-                if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
-                else { d[h][0] += v.x; d[h][1] += v.y; d[h][2] += v.z; d[h][3] += v.w; }
+                if (s == 0) { d[h][0] = e.x; d[h][1] = e.y; d[h][2] = e.z; d[h][3] = e.w; }
+                else { d[h][0] += e.x; d[h][1] += e.y; d[h][2] += e.z; d[h][3] += e.w; }
             } else {
-                if (s == 0) { d[h][0] = v.x; d[h][1] = v.y; d[h][2] = v.z; d[h][3] = v.w; }
+                if (s == 0) { d[h][0] = e.x; d[h][1] = e.y; d[h][2] = e.z; d[h][3] = e.w; }
                 else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const uint32_t add = i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w;
+                        const uint32_t add = i == 0 ? e.x : i == 1 ? e.y : i == 2 ? e.z : e.w;
                         d[h][i] = __float_as_uint(__uint_as_float(d[h][i]) + __uint_as_float(add));
                     }
                 }
@@ -847,8 +858,13 @@ void scan_tuned_kernel(TunedArgs a) {
         const uint8_t *chunk_ptr = sm.chunk_ptr;
 
         // the 16 bytes of this lane in full sub-tile t
+        // (the codes are in device memory: saying so lets the loads be global ones, which do not
+        // share a completion counter with the LDS reads of the loop the way generic loads do)
+        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+        typedef const __attribute__((address_space(1))) v4u *global_v4u;
         auto load_full = [&](int t) -> uint4 {
-            return *reinterpret_cast<const uint4 *>(chunk_ptr + (size_t)t * (SUB * CB) + lane * 16);
+            const v4u v = *(global_v4u)(chunk_ptr + (size_t)t * (SUB * CB) + lane * 16);
+            return make_uint4(v.x, v.y, v.z, v.w);
         };
         // one sub-tile past the full tiles (zeros for codes past the end of the chunk)
         auto load_ragged = [&](int sidx) -> uint4 {
@@ -871,9 +887,6 @@ void scan_tuned_kernel(TunedArgs a) {
             code_values<NT, PACKED>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
             // issue order: all address arithmetic, then every LDS read back to back, then the
             // additions (the reads are independent of one another)
-            __builtin_amdgcn_sched_group_barrier(0x002, 8 + 2 * NT, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, NT * CPL, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 8 * NT, 0);
             uint64_t hit = 0;
             if constexpr (PACKED) {
                 // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold

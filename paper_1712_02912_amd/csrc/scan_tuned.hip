@@ -155,9 +155,12 @@ struct LaneWalk {
 // Accumulated values of the codes in the 16 bytes `c` (two 8-byte codes or one 16-byte code),
 // four accumulators per code: d[h][0..3] = the four queries' float sums, or the eight queries'
 // integer sums as four packed pairs.  `ld(offset)` returns the 16-byte LDS slot at that offset.
-template <int NT, bool IS_U4, class Ld>
+// READS: table reads issued back to back before their results are added up (16, or 8 where the
+// registers are needed for codes on their way).
+template <int NT, bool IS_U4, int READS = 16, class Ld>
 __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &lw, Ld ld, uint32_t (&d)[16 / NT][4]) {
     constexpr int CPL = 16 / NT;
+    static_assert(READS == 16 || READS == 8, "a sub-tile is 16 reads per lane");
     uint32_t w[4] = {c.x, c.y, c.z, c.w};
     if constexpr (NT == 8) {
         const bool swap = (lw.rot & 4u) != 0;
@@ -166,13 +169,13 @@ __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &l
     } else {
         rot16(w, lw.rot);
     }
-    // all reads first (they are independent of one another), then the additions: the LDS serves the
-    // 16 reads back to back while the first results are already being added up
-    uint4 v[CPL][NT];
+    // read r of the lane: table step r % NT of code r / NT
 #pragma unroll
-    for (int h = 0; h < CPL; ++h) {
+    for (int r0 = 0; r0 < 16; r0 += READS) {
+        uint4 v[READS];
 #pragma unroll
-        for (int s = 0; s < NT; ++s) {
+        for (int r = 0; r < READS; ++r) {
+            const int h = (r0 + r) / NT, s = (r0 + r) % NT;
             uint32_t off;
             const uint32_t word = w[h * (NT / 4) + (s >> 2)], bs = lw.bases[s >> 2];
             switch (s & 3) {
@@ -181,15 +184,15 @@ __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &l
                 case 2: off = lut_offset<2>(word, bs); break;
                 default: off = lut_offset<3>(word, bs); break;
             }
-            v[h][s] = ld(off);
+            v[r] = ld(off);
         }
-    }
-    asm volatile("" : : : "memory");   // every read above is issued before any addition below
+        // every read above is issued before any addition below: the LDS serves them back to back
+        // while the first results are already being added up
+        asm volatile("" : : : "memory");
 #pragma unroll
-    for (int h = 0; h < CPL; ++h) {
-#pragma unroll
-        for (int s = 0; s < NT; ++s) {
-            const uint4 e = v[h][s];
+        for (int r = 0; r < READS; ++r) {
+            const int h = (r0 + r) / NT, s = (r0 + r) % NT;
+            const uint4 e = v[r];
             if constexpr (IS_U4) {
                 if (s == 0) { d[h][0] = e.x; d[h][1] = e.y; d[h][2] = e.z; d[h][3] = e.w; }
                 else { d[h][0] += e.x; d[h][1] += e.y; d[h][2] += e.z; d[h][3] += e.w; }
@@ -884,9 +887,7 @@ void scan_tuned_kernel(TunedArgs a) {
         // positions of the lanes with a candidate parked in the ring.  No calls in here.
         auto scan_sub = [&](const uint4 cur, const int sidx) {
             uint32_t d[CPL][4];
-            code_values<NT, PACKED>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
-            // issue order: all address arithmetic, then every LDS read back to back, then the
-            // additions (the reads are independent of one another)
+            code_values<NT, PACKED, DEPTH == 2 ? 16 : 8>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
             uint64_t hit = 0;
             if constexpr (PACKED) {
                 // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold

@@ -44,9 +44,18 @@ def cpu_baseline(codes_h, luts_h, gpu_dist, gpu_ids, sample_q, topk):
     od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, luts_s, topk)
     dt = time.perf_counter() - t0
     ok = bool(np.allclose(gpu_dist[:sample_q], od, rtol=1e-5, atol=0) and (gpu_ids[:sample_q] == oi).mean() > 0.98)
+    # one thread, for comparison with single-core figures in the literature (a few queries are enough)
+    one_q = min(16, sample_q)
+    orc.set_threads(1)
+    t0 = time.perf_counter()
+    orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, np.ascontiguousarray(luts_h[:one_q]), topk)
+    dt1 = time.perf_counter() - t0
+    orc.set_threads(threads)
     return {"value": codes_h.shape[0] * sample_q / dt / 1e9, "unit": "G codes/s", "cores": threads, "kind": "oracle",
             "sample": f"first {sample_q} of the queries over all {codes_h.shape[0]} codes, {dt:.1f} s wall",
-            "gpu_matches_oracle_on_sample": ok}
+            "gpu_matches_oracle_on_sample": ok,
+            "one_core": {"value": codes_h.shape[0] * one_q / dt1 / 1e9, "unit": "G codes/s", "cores": 1,
+                         "sample": f"first {one_q} queries, {dt1:.1f} s wall"}}
 
 
 def main():

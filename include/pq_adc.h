@@ -164,7 +164,11 @@ typedef struct {
  * smallest (distance, id) overall.  probe_out [nq][nprobe] i32 may be NULL; when given
  * it receives the probed lists in ascending (distance, list id) order.
  * Covered: U8 codes, k = 256, m = 8 or 16; 1 <= nprobe <= min(nlist, 1024);
- * 1 <= topk <= 128; ntotal < 2^32. */
+ * 1 <= topk <= 128; ntotal < 2^32.
+ * Queries are served in batches whose workspace (coarse distances, residual tables of
+ * every (query, list) pair, result lists) stays within PQ_IVF_WS_GIB GiB of device
+ * memory (environment, default 24, 1 ... 128); one batch is fastest because a list's
+ * codes are then scanned once for all the queries that probe it. */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);

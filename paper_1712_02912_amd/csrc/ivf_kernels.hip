@@ -349,10 +349,14 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     hipStream_t s = ctx->stream;
 
     // queries per batch: keeps the per-query part of the workspace (coarse distances, residuals and
-    // tables of the nprobe pairs, upper bound of their result lists, histogram) within about 6 GiB
+    // tables of the nprobe pairs, upper bound of their result lists, histogram) within PQ_IVF_WS_GIB
+    // GiB (default 24); the more queries share a batch, the more of them share a pass over a list
     const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 +
                              (size_t)IVF_MAX_CHUNKS * kpad * 8 + 64) + (size_t)HIST_BINS * 4 + 64;
-    int qbatch = (int)(((size_t)6 << 30) / per_query);
+    int ws_gib = env_int("PQ_IVF_WS_GIB", 24);
+    if (ws_gib < 1) ws_gib = 1;
+    if (ws_gib > 128) ws_gib = 128;
+    int qbatch = (int)(((size_t)ws_gib << 30) / per_query);
     if (qbatch < 1) qbatch = 1;
     if (qbatch > nq) qbatch = nq;
     const size_t npairs_max = (size_t)qbatch * nprobe;

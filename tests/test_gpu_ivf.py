@@ -25,7 +25,8 @@ def dev(a):
 def check_probes(queries, coarse, gpu_probes, nprobe):
     """Probed lists equal the oracle's up to ties of the coarse distances inside 1e-6 relative."""
     ref, ref_d = orc.ivf_probe(queries, coarse, nprobe)
-    cd = ((queries[:, None, :].astype(np.float64) - coarse[None].astype(np.float64)) ** 2).sum(-1)
+    c64 = coarse.astype(np.float64)
+    cd = np.stack([((q.astype(np.float64)[None, :] - c64) ** 2).sum(-1) for q in queries])
     for q in range(len(queries)):
         if np.array_equal(gpu_probes[q], ref[q]):
             continue
@@ -139,3 +140,17 @@ def test_ivf_many_lists_probe_selection(ctx):
     for nprobe, topk in ((1, 10), (16, 100), (64, 128)):
         run_ivf(ctx, queries, coarse, offsets, codes, None, cb, nprobe, topk)
 
+
+
+def test_ivf_queries_served_in_several_batches(ctx, monkeypatch):
+    """A 1 GiB workspace holds about 600 queries of this shape: 1500 queries take three batches."""
+    monkeypatch.setenv("PQ_IVF_WS_GIB", "1")
+    r = np.random.default_rng(67)
+    d, m, nlist, n, nq = 32, 8, 16384, 200_000, 1500
+    sizes = datagen.zipf_list_sizes(n, nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    codes = r.integers(0, 256, (n, m), dtype=np.uint8)
+    coarse = (r.random((nlist, d)) * 100).astype(np.float32)
+    cb = (r.random((m, 256, d // m)) * 20 - 10).astype(np.float32)
+    queries = (r.random((nq, d)) * 100).astype(np.float32)
+    run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 64, 20)

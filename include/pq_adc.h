@@ -4,7 +4,7 @@
  * The entry points follow the three-step search of the thesis (Section 2.3.3 "ANN
  * Search", Alg. 1): Index (ivf_adc_search), Tables (pq_build_luts, optionally followed
  * by pq_quantize_luts) and Scan (pq_adc_scan_topk), plus the second pass of the
- * two-pass search of Section 6.3 / Alg. 5 (pq_rerank_f32) and, on the database side, the
+ * two-pass search of Section 6.2.3 / Alg. 5 (pq_rerank_f32) and, on the database side, the
  * encoder of Section 2.3.1 (pq_encode).
  *
  * Conventions for every call
@@ -99,7 +99,7 @@ int pq_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, in
 int pq_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k,
               pq_code_fmt cf, uint8_t *codes);
 
-/* 8-bit quantisation of each query's tables (Sections 4.2.4, 5.2.1; Section 6.3 Step 1.2
+/* 8-bit quantisation of each query's tables (Sections 4.2.4, 5.2.1; Section 6.2.3 Step 1.2
  * for the unsigned 0..254 + 255 range).  Per query q:
  *   qmin  = min over all m*k entries;  range = qmax[q] - qmin;
  *   scale = (range > 0 and finite) ? 255 / range : 0;
@@ -110,7 +110,7 @@ int pq_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, const
                      float *qmin_out, float *scale_out);
 
 /* Upper quantisation bound (Sections 4.2.4 / 5.2.1: distance to a temporary neighbour
- * found by a float ADC scan of the first `init` codes; Section 6.3 Step 1.2: greatest
+ * found by a float ADC scan of the first `init` codes; Section 6.2.3 Step 1.2: greatest
  * distance among the first r2 codes).  qmax_out[q] = kq-th smallest float ADC distance
  * among the first min(init, n) codes (kq clipped to that count).  Requires init <= 4096. */
 int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq,

@@ -15,8 +15,8 @@
  *   - scan with a binary heap of size r       : Alg. 1 (scan) and the heap paragraph
  *   - 4-bit sub-codes, two per byte           : Section 5.2.2, Alg. 3 (Quick ADC)
  *   - 8-bit table quantisation                : Section 4.2.4 "Quantization of Distances",
- *                                               Section 5.2.1, Section 6.3 Step 1.2
- *   - two-pass search (candidates + rerank)   : Section 6.3, Alg. 5
+ *                                               Section 5.2.1, Section 6.2.3 Step 1.2
+ *   - two-pass search (candidates + rerank)   : Section 6.2.3, Alg. 5
  *   - rotation of optimized product quantization : Section 2.3.4 (OPQ paragraph)
  *
  * Arithmetic: floating-point sums are accumulated in double and rounded once to

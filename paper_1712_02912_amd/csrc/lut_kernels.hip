@@ -1,6 +1,6 @@
 // Tables step (Eq. (tables) of Section 2.3.3), 8-bit table quantisation (Sections 4.2.4,
 // 5.2.1, 6.3 Step 1.2), the qmax pre-scan and the rerank pass of the two-pass search
-// (Section 6.3, Alg. 5).
+// (Section 6.2.3, Alg. 5).
 #include "pq_internal.h"
 #include "topk_device.h"
 

@@ -148,6 +148,38 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
 /* Inverted lists of an IVFADC index (Section 2.3.2): nlist coarse centroids; the codes
  * of list l are rows list_offsets[l] .. list_offsets[l+1]-1 of `codes`, which encode the
  * residuals x - centroid_l.  ids may be NULL (id = row number). */
+/* Search with derived quantizers (chapter 6; Section 6.2.3, Alg. 5 nns_derived) over 64-bit codes
+ * of m = 4 sub-quantizer indexes of 16 bits each.  The codebooks obey property P1 of Section
+ * 6.2.2: the low 8 bits of a centroid's index name the centroid of the derived 8-bit quantizer
+ * it belongs to, so the derived quantizer needs no codes of its own.
+ *   Step 1.1  compact tables of the derived codebooks (as pq_build_luts);
+ *   Step 1.2  qmin = smallest entry of the query's compact tables, qmax = greatest compact
+ *             distance among the first min(r2, n) codes (entries added in double in table
+ *             order, rounded once), 8-bit tables as pq_quantize_luts;
+ *   Step 1.3  integer distance of every code = sum of the 8-bit entries at the low bytes of
+ *             its indexes (plain sums, no saturation), which is the index of its bucket;
+ *   Step 2    the buckets are taken in increasing order until r2 vectors are in; the bucket
+ *             of the r2-th vector is finished, so the candidates of a query are all codes up
+ *             to that bucket b* (all codes if n < r2).  Their precise distances
+ *             sum_j || y^j - C^j[c[j]] ||^2 come from the full codebooks (each term summed in
+ *             double and rounded to f32 like a table entry, the four terms added in double,
+ *             rounded once); the topk smallest (distance, row) are returned, padded with
+ *             (+inf, -1).
+ *   codes [n][4] u16 (device, 16-byte aligned; index c[j] < k), derived_codebooks [4][256][d/4],
+ *   codebooks [4][k][d/4], queries [nq][d]  ->  out_dist [nq][topk] f32, out_ids [nq][topk] i64.
+ * Optional outputs (device, may be NULL): bucket_out [nq] u32 = b*; ncand_out [nq] i64 = number
+ * of candidates; cand_ids_out [nq][cand_cap] i64 = their rows in no particular order, padded
+ * with -1 (PQ_ESHAPE if a query has more than cand_cap candidates).
+ * The capped-buckets lists of the thesis are replaced by two passes over the codes (bucket
+ * counts, then the ids of the buckets 0..b*); between them the call waits for the stream and
+ * reads the nq list sizes back to size its workspace.
+ * Covered: m = 4, d % 4 == 0, d <= 4096, 256 <= k <= 65536, 1 <= topk <= 128, r2 >= 1,
+ * nq <= 65535, 0 <= n < 2^32. */
+int pq_derived_search(pq_ctx *ctx, const uint16_t *codes, int64_t n, const float *derived_codebooks,
+                      const float *codebooks, int k, const float *queries, int nq, int d, int m, int r2, int topk,
+                      float *out_dist, int64_t *out_ids, uint32_t *bucket_out, int64_t *ncand_out,
+                      int64_t *cand_ids_out, int64_t cand_cap);
+
 typedef struct {
     const float *coarse_centroids; /* [nlist][d] f32, device */
     const int64_t *list_offsets;   /* [nlist+1] i64, device, non-decreasing, [0] = 0 */

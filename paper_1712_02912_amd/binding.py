@@ -21,7 +21,7 @@ LUT_F32 = 0
 LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
-           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_set_profiling",
+           "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_derived_search", "pq_set_profiling",
            "pq_last_scan_kernel_ms", "pq_calibration_copy"]
 
 _lib = None
@@ -56,6 +56,7 @@ def load():
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
     lib.pq_rotate.argtypes = [vp, vp, vp, i64, ci, vp]
     lib.pq_encode.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
+    lib.pq_derived_search.argtypes = [vp, vp, i64, vp, vp, ci, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, i64]
     lib.pq_calibration_copy.argtypes = [vp, vp, vp, ctypes.c_size_t]
     lib.pq_set_profiling.argtypes = [vp, ci]
     lib.pq_last_scan_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -209,6 +210,33 @@ class Context:
         codes = torch.empty((n, code_bytes), dtype=torch.uint8, device=vectors.device)
         self._check(self.lib.pq_encode(self.handle, _ptr(vectors), _ptr(codebooks), n, d, m, k, code_fmt, _ptr(codes)))
         return codes
+
+    # -- Search with derived quantizers ---------------------------------------------------------
+    def pq_derived_search(self, codes, derived_codebooks, codebooks, queries, r2, topk, cand_cap=0):
+        """codes [n][4] int16/uint16 bit patterns (torch.int16), codebooks [4][k][d/4].
+        Returns (dist, ids, bucket, ncand, cand_ids or None)."""
+        if codes.dtype not in (torch.int16, torch.uint16):
+            raise TypeError("codes must hold 16-bit indexes")
+        if not codes.is_cuda or not codes.is_contiguous():
+            raise ValueError("codes must be a contiguous device tensor")
+        derived_codebooks = _dev(derived_codebooks, torch.float32, "derived_codebooks")
+        codebooks = _dev(codebooks, torch.float32, "codebooks")
+        queries = _dev(queries, torch.float32, "queries")
+        n, m = codes.shape
+        nq, d = queries.shape
+        k = codebooks.shape[1]
+        if tuple(derived_codebooks.shape) != (m, 256, d // m) or tuple(codebooks.shape) != (m, k, d // m):
+            raise ValueError("codebook shapes do not match the codes and queries")
+        dev = queries.device
+        dist = torch.empty((nq, topk), dtype=torch.float32, device=dev)
+        ids = torch.empty((nq, topk), dtype=torch.int64, device=dev)
+        bucket = torch.empty((nq,), dtype=torch.int32, device=dev)
+        ncand = torch.empty((nq,), dtype=torch.int64, device=dev)
+        cand = torch.empty((nq, cand_cap), dtype=torch.int64, device=dev) if cand_cap > 0 else None
+        self._check(self.lib.pq_derived_search(self.handle, _ptr(codes), n, _ptr(derived_codebooks), _ptr(codebooks), k,
+                                               _ptr(queries), nq, d, m, r2, topk, _ptr(dist), _ptr(ids), _ptr(bucket),
+                                               _ptr(ncand), _ptr(cand) if cand is not None else None, cand_cap))
+        return dist, ids, bucket, ncand, cand
 
     # -- Index + Tables + Scan ---------------------------------------------------------------
     def ivf_adc_search(self, coarse_centroids, list_offsets, codes, ids, codebooks, code_fmt, queries, nprobe, topk,

@@ -1,0 +1,558 @@
+// Search with derived quantizers (chapter 6; Section 6.2.3, Alg. 5) for 64-bit codes of four
+// 16-bit indexes whose low 8 bits name the centroid of the derived 8-bit quantizer (property P1
+// of Section 6.2.2).
+//
+//   Step 1.1  compact tables from the derived codebooks      -> the Tables kernel (lut_kernels.hip)
+//   Step 1.2  qmax = greatest compact distance of the first r2 codes (derived_qmax_kernel),
+//             8-bit tables                                   -> the quantiser (lut_kernels.hip)
+//   Step 1.3  adc_low_bits over the whole database into buckets indexed by the integer distance
+//   Step 2    precise distances from the full codebooks for the vectors of the buckets taken in
+//             increasing order until r2 vectors are in (the bucket of the r2-th is finished)
+//
+// Capped buckets on a GPU.  The thesis appends every vector to the list of its bucket and keeps
+// an upper bound on the bucket index so that the lists stay short.  Here the lists are replaced
+// by counts: a first pass over the codes counts, per query, the vectors of every bucket up to a
+// bound that is lowered in the same way (the smallest bucket below which r2 counted vectors lie
+// bounds the bucket of the r2-th from above, so every vector at or below the final bucket is
+// always counted); the bucket b* of the r2-th vector and the exact number of vectors in the
+// buckets 0..b* follow from the counts.  A second pass over the codes, with b* fixed, writes the
+// ids of exactly those vectors into a list whose size is known beforehand.  Both passes run the
+// same loop: 8 queries per pass over a chunk of codes, tables in LDS as 16-bit entries (8 queries
+// per 16-byte slot, the four tables stored four times in the rotated slot order of lds_walk.h,
+// so every read is conflict-free), four lookups and three packed adds per code, one packed
+// compare for 8 queries x 2 codes.
+#include <vector>
+
+#include "pq_internal.h"
+#include "scan_common.h"
+#include "topk_device.h"
+#include "lds_walk.h"
+
+namespace pq {
+namespace {
+
+constexpr int DQ_WAVES = 16;
+constexpr int DQ_THREADS = DQ_WAVES * 64;
+constexpr int DQ_QB = 8;            // queries per pass
+constexpr int DQ_M = 4;             // sub-quantizers (16-bit indexes per code)
+constexpr int DQ_BINS = 1024;       // buckets: integer distances are at most 4 * 255
+constexpr int DQ_SUB = 128;         // codes per wave sub-tile (16 bytes = two codes per lane)
+constexpr uint32_t DQ_THR_MAX = 0x7fffu;   // "every sum passes" (sums stay below 1024)
+
+struct DqArgs {
+    const uint8_t *codes;        // [n][8]
+    int64_t n, chunk_codes;
+    int nchunks, ngroups, nitems, nq, r2;
+    const uint8_t *qluts;        // [nq][4][256]
+    uint32_t *work_counter;
+    uint32_t *g_hist;            // [nq][DQ_BINS] vectors counted per bucket
+    uint32_t *g_bound;           // [nq] bucket bound shared by the blocks (counting pass)
+    const uint32_t *bucket;      // [nq] b* (collecting pass)
+    const uint64_t *cand_off;    // [nq + 1]
+    uint32_t *cand_cnt;          // [nq]
+    uint64_t *cand;              // keys (integer distance << 32 | row)
+};
+
+struct __align__(16) DqSmem {
+    uint4 lut[4096];                   // row b: 16 slots; slot s = table s >> 2 (four copies)
+    uint32_t hist[DQ_QB][DQ_BINS];     // this block's counts of the current item
+    uint32_t thr[DQ_QB];               // a vector is kept for query q if its sum is below thr[q]
+    int item;
+};
+
+// first bin at which the running count reaches k, and that count; DQ_BINS if it never does.
+// `load(i)` returns the count of bin i.  One wave.
+template <class Load>
+__device__ __forceinline__ int first_bin_reaching(Load load, uint32_t k, uint32_t *count_out) {
+    const int lane = lane_id();
+    uint32_t carry = 0;
+    for (int j = 0; j < DQ_BINS / 64; ++j) {
+        uint32_t v = load(j * 64 + lane);
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(v, o);
+            if (lane >= o) v += up;
+        }
+        v += carry;
+        const uint64_t reached = __ballot(v >= k);
+        if (reached != 0ull) {
+            const int first = __builtin_ctzll(reached);
+            if (count_out) *count_out = __shfl(v, first);
+            return j * 64 + first;
+        }
+        carry = __shfl(v, 63);
+    }
+    if (count_out) *count_out = carry;
+    return DQ_BINS;
+}
+
+// MODE 0: counting pass (buckets), MODE 1: collecting pass (ids of the buckets 0..b*)
+template <int MODE>
+__global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
+    __shared__ DqSmem sm;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = lane_id();
+    const uint32_t lane15 = (uint32_t)lane & 15u;
+    // Lane l reads slot ((l & 15) + 4 s) & 15 at step s, which holds table ((l >> 2) + s) & 3;
+    // rotating the code right by 2 * ((l >> 2) & 3) bytes brings that table's index byte to
+    // byte 2 s.  bases[g]: slot offsets of steps 2g (byte 0) and 2g + 1 (byte 2).
+    const uint32_t rot = 2u * ((lane15 >> 2) & 3u);
+    uint32_t bases[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+        bases[g] = (((lane15 + 4u * (2 * g)) & 15u) << 4) | ((((lane15 + 4u * (2 * g + 1)) & 15u) << 4) << 16);
+    const char *lut_bytes = reinterpret_cast<const char *>(sm.lut);
+
+    for (;;) {
+        if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
+        __syncthreads();
+        const int item = sm.item;
+        if (item >= a.nitems) break;
+        const int group = item % a.ngroups, chunk = item / a.ngroups;
+        const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
+        const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
+        const int ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;
+
+        if (threadIdx.x < DQ_QB) {
+            const int gq = group * DQ_QB + threadIdx.x;
+            uint32_t thr = 0;   // empty slot: nothing passes
+            if (gq < a.nq) {
+                const uint32_t b = MODE == 0 ? __hip_atomic_load(&a.g_bound[gq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                             : a.bucket[gq];
+                thr = b + 1u < DQ_THR_MAX ? b + 1u : DQ_THR_MAX;
+            }
+            sm.thr[threadIdx.x] = thr;
+        }
+        if (MODE == 0)
+            for (int i = threadIdx.x; i < DQ_QB * DQ_BINS; i += DQ_THREADS) (&sm.hist[0][0])[i] = 0u;
+        {   // tables of the group's queries: entry (byte b, table t) of all 8 queries in one slot
+            const int b = threadIdx.x >> 2, t = threadIdx.x & 3;
+            uint32_t v[DQ_QB];
+#pragma unroll
+            for (int q = 0; q < DQ_QB; ++q) {
+                const int gq = group * DQ_QB + q;
+                v[q] = gq < a.nq ? (uint32_t)a.qluts[((size_t)gq * DQ_M + t) * 256 + b] : 0u;
+            }
+            const uint4 pk = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sm.lut[b * 16 + t * 4 + c] = pk;
+        }
+        __syncthreads();
+
+        const uint8_t *chunk_ptr = a.codes + cbeg * 8;
+        const int nfull = ncodes / DQ_SUB;
+        uint32_t tau[4];   // thresholds of the 8 queries, two per register
+        auto reload_tau = [&]() {
+            const uint32_t t = sm.thr[lane & (DQ_QB - 1)];
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                tau[p] = __builtin_amdgcn_readlane(t, 2 * p) | (__builtin_amdgcn_readlane(t, 2 * p + 1) << 16);
+        };
+        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+        typedef const __attribute__((address_space(1))) v4u *global_v4u;
+        auto load_full = [&](int t) -> uint4 {
+            const v4u v = *(global_v4u)(chunk_ptr + (size_t)t * (DQ_SUB * 8) + lane * 16);
+            return make_uint4(v.x, v.y, v.z, v.w);
+        };
+
+        // sums of the lane's two codes for the 8 queries (packed pairs), the test, and for the rare
+        // lanes that pass: the bucket count or the list append
+        auto process = [&](const uint4 c, const int sidx, const bool full) {
+            uint32_t w[4] = {c.x, c.y, c.z, c.w};
+            rot8(w[0], w[1], (rot & 4u) != 0, rot & 3u);
+            rot8(w[2], w[3], (rot & 4u) != 0, rot & 3u);
+            uint4 v[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint32_t word = w[2 * h + (s >> 1)];
+                    const uint32_t off = (s & 1) ? lut_offset<2>(word, bases[s >> 1]) : lut_offset<0>(word, bases[s >> 1]);
+                    v[4 * h + s] = *reinterpret_cast<const uint4 *>(lut_bytes + off);
+                }
+            }
+            asm volatile("" : : : "memory");   // all eight reads are issued before the first add
+            uint32_t d[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                d[h][0] = v[4 * h].x + v[4 * h + 1].x + v[4 * h + 2].x + v[4 * h + 3].x;
+                d[h][1] = v[4 * h].y + v[4 * h + 1].y + v[4 * h + 2].y + v[4 * h + 3].y;
+                d[h][2] = v[4 * h].z + v[4 * h + 1].z + v[4 * h + 2].z + v[4 * h + 3].z;
+                d[h][3] = v[4 * h].w + v[4 * h + 1].w + v[4 * h + 2].w + v[4 * h + 3].w;
+            }
+            // 16-bit fields below 0x8000: the smaller of the two sums minus the threshold wraps
+            // (sets bit 15) iff one of them is below the threshold
+            typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+            uint32_t below = 0;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, d[0][p]), __builtin_bit_cast(u16x2, d[1][p]));
+                below |= __builtin_bit_cast(uint32_t, (u16x2)(mn - __builtin_bit_cast(u16x2, tau[p])));
+            }
+            if (__builtin_expect(__ballot((below & 0x80008000u) != 0u) == 0ull, 1)) return;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int row = sidx * DQ_SUB + lane * 2 + h;   // within the chunk
+                const bool valid = full || row < ncodes;
+#pragma unroll
+                for (int q = 0; q < DQ_QB; ++q) {
+                    const uint32_t sum = (d[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                    const uint32_t thr = (tau[q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                    const bool pass = valid && sum < thr;
+                    if (MODE == 0) {
+                        if (pass) atomicAdd(&sm.hist[q][sum], 1u);
+                    } else {
+                        const uint64_t mask = __ballot(pass);
+                        if (mask != 0ull) {
+                            const int gq = group * DQ_QB + q;
+                            const int first = __builtin_ctzll(mask);
+                            uint32_t base = 0;
+                            if (lane == first) base = atomicAdd(&a.cand_cnt[gq], (uint32_t)__popcll(mask));
+                            base = __shfl(base, first);
+                            // (the list holds exactly the vectors the first pass counted; the
+                            // comparison only keeps a disagreement from writing past it)
+                            const uint64_t at = a.cand_off[gq] + base + (uint32_t)mask_prefix(mask);
+                            if (pass && at < a.cand_off[gq + 1]) a.cand[at] = ((uint64_t)sum << 32) | (uint32_t)(cbeg + row);
+                        }
+                    }
+                }
+            }
+        };
+
+        // Counting pass: the bound of a query is lowered from the block's own counts while the item
+        // runs (waves 0..7, one query each), early and then every 64 steps.
+        auto refresh = [&]() {
+            const int q = wave;
+            if (group * DQ_QB + q >= a.nq) return;
+            const int b = first_bin_reaching([&](int i) { return sm.hist[q][i]; }, (uint32_t)a.r2, nullptr);
+            if (b < DQ_BINS && lane == 0) atomicMin(&sm.thr[q], (uint32_t)b + 1u);
+        };
+
+        int it = 0;
+        int t = wave;
+        uint4 cur = make_uint4(0, 0, 0, 0);
+        if (t < nfull) cur = load_full(t);
+        while (t < nfull) {
+            const int tn = t + DQ_WAVES;
+            uint4 nxt = make_uint4(0, 0, 0, 0);
+            if (tn < nfull) nxt = load_full(tn);
+            reload_tau();
+            process(cur, t, true);
+            if (MODE == 0 && wave < DQ_QB && ((it & (it + 1)) == 0 || (it & 63) == 63)) refresh();
+            cur = nxt;
+            t = tn;
+            ++it;
+        }
+        if (nfull * DQ_SUB < ncodes && (nfull % DQ_WAVES) == wave) {   // the ragged last sub-tile
+            uint4 c = make_uint4(0, 0, 0, 0);
+            const int rem = ncodes - nfull * DQ_SUB;
+            const uint8_t *p = chunk_ptr + (size_t)nfull * (DQ_SUB * 8) + lane * 16;
+            if (lane * 2 + 2 <= rem) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (lane * 2 < rem) {
+                const uint2 half = *reinterpret_cast<const uint2 *>(p);
+                c.x = half.x; c.y = half.y;
+            }
+            reload_tau();
+            process(c, nfull, false);
+        }
+
+        if (MODE == 0) {
+            // the block's counts join the query's device-wide buckets, whose bound then serves
+            // every block that starts an item of this query later
+            __syncthreads();
+            for (int i = threadIdx.x; i < DQ_QB * DQ_BINS; i += DQ_THREADS) {
+                const int q = i / DQ_BINS, bin = i % DQ_BINS;
+                const uint32_t v = sm.hist[q][bin];
+                const int gq = group * DQ_QB + q;
+                if (v != 0u && gq < a.nq) atomicAdd(&a.g_hist[(size_t)gq * DQ_BINS + bin], v);
+            }
+            __syncthreads();
+            if (wave < DQ_QB && group * DQ_QB + wave < a.nq) {
+                const int gq = group * DQ_QB + wave;
+                const uint32_t *gh = a.g_hist + (size_t)gq * DQ_BINS;
+                const int b = first_bin_reaching(
+                    [&](int i) { return __hip_atomic_load(&gh[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); },
+                    (uint32_t)a.r2, nullptr);
+                if (b < DQ_BINS && lane == 0) atomicMin(&a.g_bound[gq], (uint32_t)b);
+            }
+        }
+    }
+}
+
+__global__ void derived_init_kernel(uint32_t *work_counter, uint32_t *g_hist, size_t nhist, uint32_t *g_bound,
+                                    uint32_t *cand_cnt, int nq) {
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+    if (i0 == 0) *work_counter = 0;
+    for (size_t i = i0; i < nhist; i += stride) g_hist[i] = 0u;
+    for (size_t i = i0; i < (size_t)nq; i += stride) {
+        if (g_bound) g_bound[i] = DQ_BINS - 1;   // no bound yet: every bucket is counted
+        if (cand_cnt) cand_cnt[i] = 0u;
+    }
+}
+
+// One wave per query: the bucket in which the r2-th vector falls (all vectors if there are fewer)
+// and the number of vectors in the buckets up to it.
+__global__ __launch_bounds__(64) void derived_bucket_kernel(const uint32_t *g_hist, int64_t n, int r2, uint32_t *bucket,
+                                                            uint32_t *count) {
+    const int q = blockIdx.x;
+    const uint32_t *gh = g_hist + (size_t)q * DQ_BINS;
+    const uint32_t want = (int64_t)r2 < n ? (uint32_t)r2 : (uint32_t)n;
+    uint32_t cnt = 0;
+    int b = 0;
+    if (want > 0) b = first_bin_reaching([&](int i) { return gh[i]; }, want, &cnt);
+    if (threadIdx.x == 0) {
+        bucket[q] = (uint32_t)(b < DQ_BINS ? b : DQ_BINS - 1);
+        count[q] = cnt;
+    }
+}
+
+// Step 1.2: greatest compact distance (float tables of the derived quantizers, low bits of the
+// indexes; entries added in double in table order, rounded once) among the first `init` codes.
+__global__ __launch_bounds__(256) void derived_qmax_kernel(const uint8_t *codes, int init, const float *dluts, float *qmax) {
+    __shared__ float red[256];
+    const int q = blockIdx.x;
+    const float *lut = dluts + (size_t)q * DQ_M * 256;
+    float best = 0.f;   // distances are not negative; no code at all gives 0
+    for (int i = threadIdx.x; i < init; i += 256) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+        const double s = (double)lut[c.x & 255u] + (double)lut[256 + ((c.x >> 16) & 255u)] +
+                         (double)lut[512 + (c.y & 255u)] + (double)lut[768 + ((c.y >> 16) & 255u)];
+        best = fmaxf(best, (float)s);
+    }
+    red[threadIdx.x] = best;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + o]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) qmax[q] = red[0];
+}
+
+// Step 2 for one query per block: precise distance of every candidate from the full codebooks
+// (each of the four terms ||y^j - C^j[c[j]]||^2 summed in double and rounded to float as the table
+// entry of Eq. (tables) would be, the four entries added in double and rounded once, Eq. (adc1)),
+// and the topk smallest (distance, row).  Candidates are taken in tiles; a tile's keys below the
+// current topk-th are sorted in LDS together with the best so far.
+constexpr int RR_THREADS = 1024;
+constexpr int RR_KEEP = 128;            // best keys carried from tile to tile (topk <= 128)
+constexpr int RR_TILE = 2 * RR_THREADS; // candidates per tile
+__global__ __launch_bounds__(RR_THREADS) void derived_rerank_kernel(const uint8_t *codes, const float *codebooks, int k,
+                                                                   int dsub, const float *queries, const uint64_t *cand,
+                                                                   const uint64_t *cand_off, const int64_t *ids, int topk,
+                                                                   float *out_dist, int64_t *out_ids) {
+    __shared__ uint64_t keys[RR_KEEP + RR_TILE + RR_KEEP * 15];   // 4096 keys: a power of two above KEEP + TILE
+    __shared__ float y[4096];
+    __shared__ int nnew;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const int d = DQ_M * dsub;
+    for (int i = tid; i < d; i += RR_THREADS) y[i] = queries[(size_t)q * d + i];
+    for (int i = tid; i < RR_KEEP; i += RR_THREADS) keys[i] = KEY_EMPTY;
+    if (tid == 0) nnew = 0;
+    __syncthreads();
+    const uint64_t begin = cand_off[q], end = cand_off[q + 1];
+    for (uint64_t base = begin; base < end; base += RR_TILE) {
+        const uint64_t bound = keys[topk - 1];
+        for (int u = 0; u < 2; ++u) {
+            const uint64_t ci = base + (uint64_t)u * RR_THREADS + tid;
+            if (ci >= end) continue;
+            const uint32_t row = (uint32_t)cand[ci];
+            const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)row * 8);
+            uint32_t idx[4] = {c.x & 0xffffu, c.x >> 16, c.y & 0xffffu, c.y >> 16};
+#pragma unroll
+            for (int j = 0; j < DQ_M; ++j) idx[j] = idx[j] < (uint32_t)k ? idx[j] : (uint32_t)k - 1u;   // indexes are below k by contract
+            double total = 0.0;
+#pragma unroll
+            for (int j = 0; j < DQ_M; ++j) {
+                const float *cent = codebooks + ((size_t)j * k + idx[j]) * dsub;
+                const float *yj = y + j * dsub;
+                double s = 0.0;
+                for (int t = 0; t < dsub; ++t) {
+                    const double diff = (double)yj[t] - (double)cent[t];
+                    s += diff * diff;
+                }
+                total += (double)(float)s;
+            }
+            const uint64_t key = ((uint64_t)f32_to_ord((float)total) << 32) | row;
+            if (key < bound) keys[RR_KEEP + atomicAdd(&nnew, 1)] = key;
+        }
+        __syncthreads();
+        const int total = RR_KEEP + nnew;
+        if (nnew > 0) {
+            int n2 = 256;
+            while (n2 < total) n2 <<= 1;
+            for (int i = total + tid; i < n2; i += RR_THREADS) keys[i] = KEY_EMPTY;
+            block_bitonic_sort(keys, n2);
+        }
+        __syncthreads();
+        if (tid == 0) nnew = 0;
+        __syncthreads();
+    }
+    for (int i = tid; i < topk; i += RR_THREADS) {
+        const uint64_t key = keys[i];
+        const bool have = key != KEY_EMPTY;
+        out_dist[(size_t)q * topk + i] = have ? ord_to_f32((uint32_t)(key >> 32)) : __builtin_inff();
+        const uint32_t row = (uint32_t)key;
+        out_ids[(size_t)q * topk + i] = have ? (ids ? ids[row] : (int64_t)row) : -1;
+    }
+}
+
+// candidate rows of every query as [nq][cap] ids (ascending positions in the list are not sorted), padded with -1
+__global__ void derived_export_kernel(const uint64_t *cand, const uint64_t *cand_off, int64_t cap, int64_t *out) {
+    const int q = blockIdx.y;
+    const uint64_t begin = cand_off[q], cnt = cand_off[q + 1] - begin;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cap; i += (int64_t)gridDim.x * blockDim.x)
+        out[(size_t)q * cap + i] = (uint64_t)i < cnt ? (int64_t)(uint32_t)cand[begin + i] : -1;
+}
+
+__global__ void derived_widen_kernel(const uint32_t *src, int n, int64_t *dst) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = (int64_t)src[i];
+}
+
+}  // namespace
+
+int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const float *derived_codebooks,
+                          const float *codebooks, int k, const float *queries, int nq, int d, int r2, int topk,
+                          float *out_dist, int64_t *out_ids, uint32_t *bucket_out, int64_t *ncand_out,
+                          int64_t *cand_ids_out, int64_t cand_cap) {
+    const uint8_t *codes = reinterpret_cast<const uint8_t *>(codes16);
+    const int dsub = d / DQ_M;
+    hipStream_t s = ctx->stream;
+    const int ngroups = (nq + DQ_QB - 1) / DQ_QB;
+
+    // work items: chunk of codes x group of 8 queries, chunk-major (blocks running together share chunks)
+    const int64_t block_tile = (int64_t)DQ_SUB * DQ_WAVES;
+    int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+    if (nblocks_max < 1) nblocks_max = 1;
+    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;
+    const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
+    if (nchunks > max_by_n) nchunks = max_by_n;
+    const int64_t min_chunks = (n + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits
+    if (nchunks < min_chunks) nchunks = min_chunks;
+    if (nchunks < 1) nchunks = 1;
+    int64_t chunk_codes = (n + nchunks - 1) / nchunks;
+    chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
+    if (chunk_codes < block_tile) chunk_codes = block_tile;
+    nchunks = n > 0 ? (n + chunk_codes - 1) / chunk_codes : 0;
+    const int64_t nitems = nchunks * ngroups;
+    if (nitems > 0x3fffffff) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: too many work items (%lld)", (long long)nitems);
+    const int nblocks = (int)(nitems < nblocks_max ? nitems : nblocks_max);
+
+    // workspace, first part: tables and counts
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; };
+    const size_t o_counter = take(256);
+    const size_t o_dluts = take((size_t)nq * DQ_M * 256 * 4);
+    const size_t o_qmax = take((size_t)nq * 4);
+    const size_t o_qmin = take((size_t)nq * 4);
+    const size_t o_scale = take((size_t)nq * 4);
+    const size_t o_qluts = take((size_t)nq * DQ_M * 256);
+    const size_t o_hist = take((size_t)nq * DQ_BINS * 4);
+    const size_t o_bound = take((size_t)nq * 4);
+    const size_t o_bucket = take((size_t)nq * 4);
+    const size_t o_count = take((size_t)nq * 4);
+    const size_t o_candcnt = take((size_t)nq * 4);
+    const size_t o_candoff = take((size_t)(nq + 1) * 8);
+    const size_t first_part = off;
+
+    auto prepare = [&](uint8_t *ws) -> int {   // Steps 1.1 and 1.2
+        float *dluts = (float *)(ws + o_dluts), *qmax = (float *)(ws + o_qmax);
+        int rc = launch_build_luts(ctx, queries, derived_codebooks, nq, d, DQ_M, 256, dluts);
+        if (rc) return rc;
+        const int init = (int)((int64_t)r2 < n ? (int64_t)r2 : n);
+        derived_qmax_kernel<<<nq, 256, 0, s>>>(codes, init, dluts, qmax);
+        PQ_HIP(ctx, hipGetLastError());
+        return launch_quantize_luts(ctx, dluts, nq, DQ_M, 256, qmax, ws + o_qluts, (float *)(ws + o_qmin),
+                                    (float *)(ws + o_scale));
+    };
+
+    int rc = ws_reserve(ctx, first_part);
+    if (rc) return rc;
+    uint8_t *ws = (uint8_t *)ctx->ws;
+    rc = prepare(ws);
+    if (rc) return rc;
+
+    DqArgs a;
+    a.codes = codes; a.n = n; a.chunk_codes = chunk_codes; a.nchunks = (int)nchunks; a.ngroups = ngroups;
+    a.nitems = (int)nitems; a.nq = nq; a.r2 = r2;
+    a.qluts = ws + o_qluts;
+    a.work_counter = (uint32_t *)(ws + o_counter);
+    a.g_hist = (uint32_t *)(ws + o_hist);
+    a.g_bound = (uint32_t *)(ws + o_bound);
+    a.bucket = nullptr; a.cand_off = nullptr; a.cand_cnt = nullptr; a.cand = nullptr;
+
+    // Step 1.3, counting pass
+    derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, a.g_hist, (size_t)nq * DQ_BINS, a.g_bound, nullptr, nq);
+    PQ_HIP(ctx, hipGetLastError());
+    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
+    if (nblocks > 0) {
+        derived_scan_kernel<0><<<nblocks, DQ_THREADS, 0, s>>>(a);
+        PQ_HIP(ctx, hipGetLastError());
+    }
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
+        ctx->ev_valid = 1;
+    }
+    derived_bucket_kernel<<<nq, 64, 0, s>>>(a.g_hist, n, r2, (uint32_t *)(ws + o_bucket), (uint32_t *)(ws + o_count));
+    PQ_HIP(ctx, hipGetLastError());
+
+    // the sizes of the candidate lists decide the rest of the workspace: the host has to see them
+    std::vector<uint32_t> count((size_t)nq), bucket((size_t)nq);
+    PQ_HIP(ctx, hipMemcpyAsync(count.data(), ws + o_count, (size_t)nq * 4, hipMemcpyDeviceToHost, s));
+    PQ_HIP(ctx, hipMemcpyAsync(bucket.data(), ws + o_bucket, (size_t)nq * 4, hipMemcpyDeviceToHost, s));
+    PQ_HIP(ctx, hipStreamSynchronize(s));
+    std::vector<uint64_t> cand_off((size_t)nq + 1);
+    cand_off[0] = 0;
+    for (int q = 0; q < nq; ++q) {
+        cand_off[(size_t)q + 1] = cand_off[(size_t)q] + count[(size_t)q];
+        if (cand_ids_out && (int64_t)count[(size_t)q] > cand_cap)
+            return fail(ctx, PQ_ESHAPE, "derived_search: query %d has %u candidates, cand_cap is %lld", q, count[(size_t)q],
+                        (long long)cand_cap);
+    }
+    const uint64_t total = cand_off[(size_t)nq];
+    const size_t o_cand = take((size_t)total * 8);
+    const bool regrow = off > ctx->ws_bytes;
+    rc = ws_reserve(ctx, off);
+    if (rc) return rc;
+    ws = (uint8_t *)ctx->ws;
+    if (regrow) {   // a new workspace: the tables are computed again (same bits), the buckets copied back
+        rc = prepare(ws);
+        if (rc) return rc;
+        PQ_HIP(ctx, hipMemcpyAsync(ws + o_bucket, bucket.data(), (size_t)nq * 4, hipMemcpyHostToDevice, s));
+        PQ_HIP(ctx, hipMemcpyAsync(ws + o_count, count.data(), (size_t)nq * 4, hipMemcpyHostToDevice, s));
+    }
+    PQ_HIP(ctx, hipMemcpyAsync(ws + o_candoff, cand_off.data(), (size_t)(nq + 1) * 8, hipMemcpyHostToDevice, s));
+    PQ_HIP(ctx, hipStreamSynchronize(s));   // the host vectors go away with this call
+
+    // Step 1.3, collecting pass
+    a.qluts = ws + o_qluts;
+    a.work_counter = (uint32_t *)(ws + o_counter);
+    a.g_hist = nullptr; a.g_bound = nullptr;
+    a.bucket = (const uint32_t *)(ws + o_bucket);
+    a.cand_off = (const uint64_t *)(ws + o_candoff);
+    a.cand_cnt = (uint32_t *)(ws + o_candcnt);
+    a.cand = (uint64_t *)(ws + o_cand);
+    derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, nullptr, 0, nullptr, a.cand_cnt, nq);
+    PQ_HIP(ctx, hipGetLastError());
+    if (nblocks > 0) {
+        derived_scan_kernel<1><<<nblocks, DQ_THREADS, 0, s>>>(a);
+        PQ_HIP(ctx, hipGetLastError());
+    }
+    // Step 2
+    derived_rerank_kernel<<<nq, RR_THREADS, 0, s>>>(codes, codebooks, k, dsub, queries, a.cand, a.cand_off, nullptr, topk,
+                                                    out_dist, out_ids);
+    PQ_HIP(ctx, hipGetLastError());
+    if (bucket_out) PQ_HIP(ctx, hipMemcpyAsync(bucket_out, ws + o_bucket, (size_t)nq * 4, hipMemcpyDeviceToDevice, s));
+    if (ncand_out) {
+        derived_widen_kernel<<<(nq + 255) / 256, 256, 0, s>>>((const uint32_t *)(ws + o_count), nq, ncand_out);
+        PQ_HIP(ctx, hipGetLastError());
+    }
+    if (cand_ids_out && cand_cap > 0) {
+        derived_export_kernel<<<dim3(64, nq), 256, 0, s>>>(a.cand, a.cand_off, cand_cap, cand_ids_out);
+        PQ_HIP(ctx, hipGetLastError());
+    }
+    return PQ_OK;
+}
+
+}  // namespace pq

@@ -216,6 +216,28 @@ int pq_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t
     return launch_encode(ctx, vectors, codebooks, n, d, m, k, cf, codes);
 }
 
+int pq_derived_search(pq_ctx *ctx, const uint16_t *codes, int64_t n, const float *derived_codebooks,
+                      const float *codebooks, int k, const float *queries, int nq, int d, int m, int r2, int topk,
+                      float *out_dist, int64_t *out_ids, uint32_t *bucket_out, int64_t *ncand_out,
+                      int64_t *cand_ids_out, int64_t cand_cap) {
+    if (!ctx) return PQ_EINVAL;
+    if (n < 0 || nq < 0 || d <= 0 || m <= 0 || k <= 0 || r2 < 1 || topk < 1 || cand_cap < 0)
+        return fail(ctx, PQ_EINVAL, "derived_search: bad size");
+    if (m != 4) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: m=%d (64-bit codes of four 16-bit indexes only)", m);
+    if (d % m != 0) return fail(ctx, PQ_ESHAPE, "derived_search: d=%d is not a multiple of m=%d", d, m);
+    if (d > 4096) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: d=%d above 4096", d);
+    if (k < 256 || k > 65536) return fail(ctx, PQ_ESHAPE, "derived_search: k=%d outside 256..65536", k);
+    if (topk > 128) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: topk=%d above 128", topk);
+    if (nq > 65535) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: more than 65535 queries per call");
+    if (n >= ((int64_t)1 << 32)) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: n must be below 2^32");
+    if (nq == 0) return PQ_OK;
+    if (!derived_codebooks || !codebooks || !queries || !out_dist || !out_ids || (n > 0 && !codes))
+        return fail(ctx, PQ_EINVAL, "derived_search: null pointer");
+    if (!aligned16(codes)) return fail(ctx, PQ_EINVAL, "derived_search: codes must be 16-byte aligned");
+    return launch_derived_search(ctx, codes, n, derived_codebooks, codebooks, k, queries, nq, d, r2, topk, out_dist,
+                                 out_ids, bucket_out, ncand_out, cand_ids_out, cand_cap);
+}
+
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out) {

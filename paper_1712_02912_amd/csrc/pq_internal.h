@@ -48,6 +48,10 @@ int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void
 int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out);
 int launch_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k, int cf,
                   uint8_t *codes);
+int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const float *derived_codebooks,
+                          const float *codebooks, int k, const float *queries, int nq, int d, int r2, int topk,
+                          float *out_dist, int64_t *out_ids, uint32_t *bucket_out, int64_t *ncand_out,
+                          int64_t *cand_ids_out, int64_t cand_cap);
 int launch_ivf(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, int cf,
                const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                int32_t *probe_out);

@@ -32,6 +32,7 @@
 #include "pq_internal.h"
 #include "scan_common.h"
 #include "topk_device.h"
+#include "lds_walk.h"
 
 namespace pq {
 
@@ -104,35 +105,6 @@ constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain f
 constexpr int PRUNE_INIT = 4096;           // codes looked at for the first bound of every query
 constexpr int PRUNE_MARGIN = 8;      // slack of the integer threshold, in table units
 constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the minima and the first bound
-
-// rotate the bytes of a 64-bit code right by r bytes (r in 0..7): byte s of the result is
-// byte (s + r) & 7 of the input
-__device__ __forceinline__ void rot8(uint32_t &lo, uint32_t &hi, bool swap, uint32_t sh) {
-    const uint32_t a = swap ? hi : lo, b = swap ? lo : hi;
-    lo = __builtin_amdgcn_alignbyte(b, a, sh);
-    hi = __builtin_amdgcn_alignbyte(a, b, sh);
-}
-
-// rotate the bytes of a 128-bit code right by r bytes (r in 0..15)
-__device__ __forceinline__ void rot16(uint32_t (&w)[4], uint32_t r) {
-    if (r & 8u) { uint32_t t = w[0]; w[0] = w[2]; w[2] = t; t = w[1]; w[1] = w[3]; w[3] = t; }
-    if (r & 4u) { const uint32_t t = w[0]; w[0] = w[1]; w[1] = w[2]; w[2] = w[3]; w[3] = t; }
-    const uint32_t sh = r & 3u;
-    const uint32_t a = w[0], b = w[1], c = w[2], d = w[3];
-    w[0] = __builtin_amdgcn_alignbyte(b, a, sh);
-    w[1] = __builtin_amdgcn_alignbyte(c, b, sh);
-    w[2] = __builtin_amdgcn_alignbyte(d, c, sh);
-    w[3] = __builtin_amdgcn_alignbyte(a, d, sh);
-}
-
-// LDS byte offset of the lookup for byte `pos` of `word`: (code byte << 8) | slot offset.
-// `bases` holds the slot offsets (slot * 16, below 256) of four consecutive steps.
-template <int POS>
-__device__ __forceinline__ uint32_t lut_offset(uint32_t word, uint32_t bases) {
-    // result byte 0 <- bases byte POS, byte 1 <- word byte POS, bytes 2 and 3 <- 0
-    constexpr uint32_t sel = 0x0c0c0000u | ((4u + POS) << 8) | (uint32_t)POS;
-    return __builtin_amdgcn_perm(word, bases, sel);
-}
 
 // What a lane needs to walk the tables in its own rotated order (see the layout note on top):
 // derived from the low four bits of the lane that holds the code bytes.

@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--config3", action="store_true", help="also time config 3 (d=960, 16x8 codes, 1 M codes)")
     ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
     ap.add_argument("--encode-n", type=int, default=4_000_000)
+    ap.add_argument("--derived", action="store_true", help="also time pq_derived_search (64-bit codes of four 16-bit indexes, k=65536)")
+    ap.add_argument("--derived-r2", type=int, default=10000)
     ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
     ap.add_argument("--streaming-n", type=int, nargs="+", default=[100_000_000, 1_000_000_000])
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -266,6 +268,30 @@ def main():
                          "frac_of_fp64_mfma_peak": flops / ms / 1e9 / 78.6}
         result["encode"] = enc
         del x_e
+
+    # ---------------------------------------------------------------- derived quantizers, on request
+    if args.derived:
+        cb16_h, cbar_h = datagen.clustered_codebooks(mix, 4, 65536)
+        cb16, cbar = torch.from_numpy(cb16_h).cuda(), torch.from_numpy(cbar_h).cuda()
+        gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_CODES + 5)
+        codes16 = torch.randint(-32768, 32768, (args.n, 4), dtype=torch.int16, device="cuda", generator=gen)
+        times, kms = [], []
+        for _ in range(1 + args.steps):
+            sync()
+            t0 = time.perf_counter()
+            _, _, _, ncand, _ = ctx.pq_derived_search(codes16, cbar, cb16, queries, args.derived_r2, args.topk)
+            sync()
+            times.append((time.perf_counter() - t0) * 1e3)
+            kms.append(ctx.pq_last_scan_kernel_ms())
+        ms_d = float(np.mean(times[1:]))
+        result["derived_pq4x8_16"] = {
+            "workload": "N=%d codes of four 16-bit indexes (k=65536, derived 8-bit quantizers), %d queries, r2=%d, top-%d"
+                        % (args.n, args.nq, args.derived_r2, args.topk),
+            "ms_per_call": ms_d, "counting_pass_kernel_ms": float(np.mean(kms[1:])),
+            "G codes/s": args.n * args.nq / (ms_d * 1e-3) / 1e9,
+            "candidates_per_query_mean": float(ncand.double().mean().item()),
+            "algorithmic GB/s (8 B per code per query, one pass)": args.n * 8.0 * args.nq / (ms_d * 1e-3) / 1e9}
+        del codes16, cb16
 
     # ---------------------------------------------------------------- IVF-ADC (BASELINE config 4), on request
     if args.ivf:

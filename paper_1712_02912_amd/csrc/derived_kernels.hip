@@ -38,6 +38,8 @@ constexpr int DQ_M = 4;             // sub-quantizers (16-bit indexes per code)
 constexpr int DQ_BINS = 1024;       // buckets: integer distances are at most 4 * 255
 constexpr int DQ_SUB = 128;         // codes per wave sub-tile (16 bytes = two codes per lane)
 constexpr uint32_t DQ_THR_MAX = 0x7fffu;   // "every sum passes" (sums stay below 1024)
+constexpr int DQ_DEPTH = 4;         // sub-tiles per group of a wave
+constexpr int DQ_RING = 64 * (DQ_DEPTH + 1);   // parked rows per wave: a group's worth behind an unflushed rest
 
 struct DqArgs {
     const uint8_t *codes;        // [n][8]
@@ -57,6 +59,7 @@ struct __align__(16) DqSmem {
     uint4 lut[4096];                   // row b: 16 slots; slot s = table s >> 2 (four copies)
     uint32_t hist[DQ_QB][DQ_BINS];     // this block's counts of the current item
     uint32_t thr[DQ_QB];               // a vector is kept for query q if its sum is below thr[q]
+    uint32_t ring[DQ_WAVES][DQ_RING];  // rows whose sums passed a threshold, waiting to be counted or listed
     int item;
 };
 
@@ -140,7 +143,8 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
         __syncthreads();
 
         const uint8_t *chunk_ptr = a.codes + cbeg * 8;
-        const int nfull = ncodes / DQ_SUB;
+        const int nfull = ncodes / DQ_SUB;                       // sub-tiles with every code present
+        const int nsub = (ncodes + DQ_SUB - 1) / DQ_SUB;         // the last one may be ragged
         uint32_t tau[4];   // thresholds of the 8 queries, two per register
         auto reload_tau = [&]() {
             const uint32_t t = sm.thr[lane & (DQ_QB - 1)];
@@ -154,14 +158,24 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
             const v4u v = *(global_v4u)(chunk_ptr + (size_t)t * (DQ_SUB * 8) + lane * 16);
             return make_uint4(v.x, v.y, v.z, v.w);
         };
+        // the two codes at rows pos, pos + 1 of the chunk (zeros for rows past its end)
+        auto load_pair = [&](int pos) -> uint4 {
+            uint4 c = make_uint4(0, 0, 0, 0);
+            const uint8_t *p = chunk_ptr + (size_t)pos * 8;
+            if (pos + 2 <= ncodes) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (pos < ncodes) {
+                const uint2 half = *reinterpret_cast<const uint2 *>(p);
+                c.x = half.x; c.y = half.y;
+            }
+            return c;
+        };
 
-        // sums of the lane's two codes for the 8 queries (packed pairs), the test, and for the rare
-        // lanes that pass: the bucket count or the list append
-        auto process = [&](const uint4 c, const int sidx, const bool full) {
+        // the eight table reads of the lane's two codes (four tables each, in the lane's rotated order)
+        auto issue = [&](const uint4 c, uint4 (&v)[8]) {
             uint32_t w[4] = {c.x, c.y, c.z, c.w};
             rot8(w[0], w[1], (rot & 4u) != 0, rot & 3u);
             rot8(w[2], w[3], (rot & 4u) != 0, rot & 3u);
-            uint4 v[8];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -171,8 +185,9 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
                     v[4 * h + s] = *reinterpret_cast<const uint4 *>(lut_bytes + off);
                 }
             }
-            asm volatile("" : : : "memory");   // all eight reads are issued before the first add
-            uint32_t d[2][4];
+        };
+        // integer distances of the two codes for the 8 queries, as four packed pairs per code
+        auto add_up = [&](const uint4 (&v)[8], uint32_t (&d)[2][4]) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 d[h][0] = v[4 * h].x + v[4 * h + 1].x + v[4 * h + 2].x + v[4 * h + 3].x;
@@ -180,6 +195,14 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
                 d[h][2] = v[4 * h].z + v[4 * h + 1].z + v[4 * h + 2].z + v[4 * h + 3].z;
                 d[h][3] = v[4 * h].w + v[4 * h + 1].w + v[4 * h + 2].w + v[4 * h + 3].w;
             }
+        };
+
+        // One sub-tile whose reads are on their way: sums, one packed test for 8 queries x 2 codes,
+        // and the rows of the lanes with a sum below a threshold parked in the wave's ring.
+        int ring_cnt = 0;
+        auto finish = [&](const uint4 (&v)[8], const int sidx) {
+            uint32_t d[2][4];
+            add_up(v, d);
             // 16-bit fields below 0x8000: the smaller of the two sums minus the threshold wraps
             // (sets bit 15) iff one of them is below the threshold
             typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -189,30 +212,55 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
                 const u16x2 mn = __builtin_elementwise_min(__builtin_bit_cast(u16x2, d[0][p]), __builtin_bit_cast(u16x2, d[1][p]));
                 below |= __builtin_bit_cast(uint32_t, (u16x2)(mn - __builtin_bit_cast(u16x2, tau[p])));
             }
-            if (__builtin_expect(__ballot((below & 0x80008000u) != 0u) == 0ull, 1)) return;
+            const uint64_t hit = __ballot((below & 0x80008000u) != 0u);
+            if (__builtin_expect(hit != 0ull, 0)) {
+                if ((hit >> lane) & 1ull) sm.ring[wave][ring_cnt + mask_prefix(hit)] = (uint32_t)(sidx * DQ_SUB + lane * 2);
+                ring_cnt += __popcll(hit);
+            }
+        };
+        auto scan_sub = [&](const uint4 c, const int sidx) {
+            uint4 v[8];
+            issue(c, v);
+            asm volatile("" : : : "memory");   // all eight reads are issued before the first add
+            finish(v, sidx);
+        };
+
+        // Parked rows, 64 at a time: the sums again, the test against the thresholds of now, and
+        // for every (code, query) that passes the bucket count or the list append.
+        auto flush = [&](const int count) {
+            reload_tau();
+            for (int base = 0; base < count; base += 64) {
+                const bool have = base + lane < count;
+                const int pos = have ? (int)sm.ring[wave][base + lane] : ncodes;
+                uint32_t d[2][4];
+                {
+                    uint4 v[8];
+                    issue(load_pair(pos), v);
+                    add_up(v, d);
+                }
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int row = sidx * DQ_SUB + lane * 2 + h;   // within the chunk
-                const bool valid = full || row < ncodes;
+                for (int h = 0; h < 2; ++h) {
+                    const bool valid = pos + h < ncodes;
 #pragma unroll
-                for (int q = 0; q < DQ_QB; ++q) {
-                    const uint32_t sum = (d[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                    const uint32_t thr = (tau[q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                    const bool pass = valid && sum < thr;
-                    if (MODE == 0) {
-                        if (pass) atomicAdd(&sm.hist[q][sum], 1u);
-                    } else {
-                        const uint64_t mask = __ballot(pass);
-                        if (mask != 0ull) {
-                            const int gq = group * DQ_QB + q;
-                            const int first = __builtin_ctzll(mask);
-                            uint32_t base = 0;
-                            if (lane == first) base = atomicAdd(&a.cand_cnt[gq], (uint32_t)__popcll(mask));
-                            base = __shfl(base, first);
-                            // (the list holds exactly the vectors the first pass counted; the
-                            // comparison only keeps a disagreement from writing past it)
-                            const uint64_t at = a.cand_off[gq] + base + (uint32_t)mask_prefix(mask);
-                            if (pass && at < a.cand_off[gq + 1]) a.cand[at] = ((uint64_t)sum << 32) | (uint32_t)(cbeg + row);
+                    for (int q = 0; q < DQ_QB; ++q) {
+                        const uint32_t sum = (d[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                        const uint32_t thr = (tau[q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                        const bool pass = valid && sum < thr;
+                        if (MODE == 0) {
+                            if (pass) atomicAdd(&sm.hist[q][sum], 1u);
+                        } else {
+                            const uint64_t mask = __ballot(pass);
+                            if (mask != 0ull) {
+                                const int gq = group * DQ_QB + q;
+                                const int first = __builtin_ctzll(mask);
+                                uint32_t slot = 0;
+                                if (lane == first) slot = atomicAdd(&a.cand_cnt[gq], (uint32_t)__popcll(mask));
+                                slot = __shfl(slot, first);
+                                // (the list holds exactly the vectors the first pass counted; the
+                                // comparison only keeps a disagreement from writing past it)
+                                const uint64_t at = a.cand_off[gq] + slot + (uint32_t)mask_prefix(mask);
+                                if (pass && at < a.cand_off[gq + 1]) a.cand[at] = ((uint64_t)sum << 32) | (uint32_t)(cbeg + pos + h);
+                            }
                         }
                     }
                 }
@@ -220,7 +268,7 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
         };
 
         // Counting pass: the bound of a query is lowered from the block's own counts while the item
-        // runs (waves 0..7, one query each), early and then every 64 steps.
+        // runs (waves 0..7, one query each), early and then every 16 groups.
         auto refresh = [&]() {
             const int q = wave;
             if (group * DQ_QB + q >= a.nq) return;
@@ -228,34 +276,60 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
             if (b < DQ_BINS && lane == 0) atomicMin(&sm.thr[q], (uint32_t)b + 1u);
         };
 
+        // A wave works through groups of DQ_DEPTH full sub-tiles (group g = sub-tiles g * DEPTH ...);
+        // the codes of its next group are requested into the registers of the sub-tile just scanned;
+        // full batches of parked rows are flushed between groups.
+        const int ngroups_t = nfull / DQ_DEPTH;
         int it = 0;
-        int t = wave;
-        uint4 cur = make_uint4(0, 0, 0, 0);
-        if (t < nfull) cur = load_full(t);
-        while (t < nfull) {
-            const int tn = t + DQ_WAVES;
-            uint4 nxt = make_uint4(0, 0, 0, 0);
-            if (tn < nfull) nxt = load_full(tn);
-            reload_tau();
-            process(cur, t, true);
-            if (MODE == 0 && wave < DQ_QB && ((it & (it + 1)) == 0 || (it & 63) == 63)) refresh();
-            cur = nxt;
-            t = tn;
+        uint4 cur[DQ_DEPTH];
+#pragma unroll
+        for (int u = 0; u < DQ_DEPTH; ++u) cur[u] = make_uint4(0, 0, 0, 0);
+        // this lane's 16 bytes of sub-tile 0 of the wave's current group, then of its next group
+        const uint8_t *gp = chunk_ptr + (size_t)wave * (DQ_DEPTH * DQ_SUB * 8) + lane * 16;
+        auto load_group_sub = [&](const uint8_t *p, int u) -> uint4 {
+            const v4u v = *(global_v4u)(p + u * (DQ_SUB * 8));
+            return make_uint4(v.x, v.y, v.z, v.w);
+        };
+        if (wave < ngroups_t) {
+#pragma unroll
+            for (int u = 0; u < DQ_DEPTH; ++u) cur[u] = load_group_sub(gp, u);
+        }
+        reload_tau();
+        for (int g = wave; g < ngroups_t; g += DQ_WAVES) {
+            const bool more = g + DQ_WAVES < ngroups_t;
+            gp += (size_t)DQ_WAVES * (DQ_DEPTH * DQ_SUB * 8);
+            // the table reads of sub-tile u + 1 are issued before the sums of sub-tile u are formed
+            uint4 va[8], vb[8];
+            issue(cur[0], va);
+            if (more) cur[0] = load_group_sub(gp, 0);
+#pragma unroll
+            for (int u = 0; u < DQ_DEPTH; ++u) {
+                if (u + 1 < DQ_DEPTH) {
+                    issue(cur[u + 1], (u & 1) ? va : vb);
+                    if (more) cur[u + 1] = load_group_sub(gp, u + 1);
+                }
+                asm volatile("" : : : "memory");
+                finish((u & 1) ? vb : va, g * DQ_DEPTH + u);
+            }
+            if (__builtin_expect(ring_cnt >= 64, 0)) {
+                const int whole = ring_cnt & ~63;
+                flush(whole);
+                for (int i = lane; i < ring_cnt - whole; i += 64) {   // the rest moves to the front
+                    const uint32_t v = sm.ring[wave][whole + i];
+                    sm.ring[wave][i] = v;
+                }
+                ring_cnt -= whole;
+            }
+            if (MODE == 0) {
+                if (wave < DQ_QB && ((it & (it + 1)) == 0 || (it & 15) == 15)) refresh();
+                reload_tau();
+            }
             ++it;
         }
-        if (nfull * DQ_SUB < ncodes && (nfull % DQ_WAVES) == wave) {   // the ragged last sub-tile
-            uint4 c = make_uint4(0, 0, 0, 0);
-            const int rem = ncodes - nfull * DQ_SUB;
-            const uint8_t *p = chunk_ptr + (size_t)nfull * (DQ_SUB * 8) + lane * 16;
-            if (lane * 2 + 2 <= rem) {
-                c = *reinterpret_cast<const uint4 *>(p);
-            } else if (lane * 2 < rem) {
-                const uint2 half = *reinterpret_cast<const uint2 *>(p);
-                c.x = half.x; c.y = half.y;
-            }
-            reload_tau();
-            process(c, nfull, false);
-        }
+        // sub-tiles past the last whole group, the ragged one included
+        for (int sidx = ngroups_t * DQ_DEPTH + wave; sidx < nsub; sidx += DQ_WAVES)
+            scan_sub(load_pair(sidx * DQ_SUB + lane * 2), sidx);
+        if (ring_cnt > 0) flush(ring_cnt);
 
         if (MODE == 0) {
             // the block's counts join the query's device-wide buckets, whose bound then serves

@@ -67,6 +67,20 @@ def sampled_codebooks(mix, m, k, seed=SEED_KMEANS):
     return np.ascontiguousarray(x.reshape(k, m, dsub).transpose(1, 0, 2))
 
 
+def clustered_codebooks(mix, m, k, kbar=256, spread=6.0, seed=SEED_KMEANS + 11):
+    """Stand-in for jointly trained codebooks of a 16-bit product quantizer and its derived 8-bit
+    quantizer (throughput runs and parity inputs): kbar cluster centres per sub-space taken from
+    mixture samples, centroid i scattered around centre i % kbar, so the low bits of an index
+    name its cluster; the derived centroid of a cluster is the mean of its members.
+    Returns (codebooks [m][k][d/m], derived [m][kbar][d/m])."""
+    centres = sampled_codebooks(mix, m, kbar, seed)                      # [m][kbar][dsub]
+    r = _rng(seed + 1)
+    cb = centres[:, np.arange(k) % kbar, :] + r.normal(0.0, spread, size=(m, k, centres.shape[2])).astype(np.float32)
+    cb = np.ascontiguousarray(cb, dtype=np.float32)
+    derived = cb.astype(np.float64).reshape(m, k // kbar, kbar, -1).mean(axis=1).astype(np.float32)
+    return cb, derived
+
+
 def random_codes(n, code_bytes, seed=SEED_CODES, chunk=1 << 24):
     """[n][code_bytes] uniformly random bytes, generated in chunks of rows."""
     out = np.empty((n, code_bytes), np.uint8)

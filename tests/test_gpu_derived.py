@@ -140,3 +140,32 @@ def test_derived_search_errors(ctx):
     assert e.value.code == -3
     # the context still works after the errors
     run_case(ctx, cb, cbar, codes, queries, 100, 10)
+
+
+def test_derived_search_bench_configuration_sampled(ctx):
+    """The workload bench.py --derived times (25 M codes, 1000 queries, k = 65536, r2 = 10000, top-100):
+    bucket, candidate count, candidate set and result of three sampled queries against the oracle."""
+    from paper_1712_02912_amd import datagen
+    mix = datagen.sift_like()
+    n, nq, r2, topk = 25_000_000, 1000, 10000, 100
+    cb, cbar = datagen.clustered_codebooks(mix, 4, 65536)
+    queries = mix.sample(nq, datagen.SEED_QUERIES)
+    gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_CODES + 5)
+    d_codes = torch.randint(-32768, 32768, (n, 4), dtype=torch.int16, device="cuda", generator=gen)
+    d_cbar, d_cb, d_q = dev(cbar), dev(cb), dev(queries)
+    cap = 40000
+    gd, gi, bucket, ncand, cand = ctx.pq_derived_search(d_codes, d_cbar, d_cb, d_q, r2, topk, cand_cap=cap)
+    dluts = ctx.pq_build_luts(d_q, d_cbar)
+    torch.cuda.synchronize()
+    codes = d_codes.cpu().numpy().view(np.uint16)
+    dluts = dluts.cpu().numpy()
+    sample = [0, 499, 999]
+    qmax = dq.derived_qmax(codes, dluts[sample], r2)
+    qluts, _, _ = orc.quantize_luts(dluts[sample], qmax)
+    od, oi, s_star, cands = dq.search_from_tables(codes, qluts, cb, queries[sample], r2, topk)
+    gd, gi, bucket, ncand = gd.cpu().numpy(), gi.cpu().numpy(), bucket.cpu().numpy(), ncand.cpu().numpy()
+    assert ncand.min() >= r2 and ncand.max() <= cap
+    for i, q in enumerate(sample):
+        assert bucket[q] == s_star[i] and ncand[q] == len(cands[i])
+        assert np.array_equal(np.sort(cand[q, :ncand[q]].cpu().numpy()), cands[i])
+        check_float_topk_ranked(gd[q], gi[q], od[i], oi[i])

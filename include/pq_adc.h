@@ -200,7 +200,10 @@ typedef struct {
  * Queries are served in batches whose workspace (coarse distances, residual tables of
  * every (query, list) pair, result lists) stays within PQ_IVF_WS_GIB GiB of device
  * memory (environment, default 24, 1 ... 128); one batch is fastest because a list's
- * codes are then scanned once for all the queries that probe it. */
+ * codes are then scanned once for all the queries that probe it.
+ * The lists are scanned on 16-bit lower bounds of the distances, exact float distances only for
+ * the codes whose bound passes (as in pq_adc_scan_topk; PQ_SCAN_PRUNE=0 selects the plain float
+ * loop), by blocks of 8 waves, two per compute unit (PQ_IVF_BLOCK_WAVES=16: one block of 16). */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);

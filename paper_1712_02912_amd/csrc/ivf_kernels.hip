@@ -22,7 +22,9 @@ namespace pq {
 
 constexpr int IVF_MAX_CHUNKS = 16;            // chunks per list (bounds the lists a query can own)
 constexpr int64_t IVF_CHUNK_TARGET = 1 << 18; // rows per chunk aimed at for long lists
-constexpr int IVF_QB = 4;                     // queries per work item (float tables)
+constexpr float IVF_PRUNE_RANGE = 3500.f;      // table units between the sum of a pair's minima and the query's first bound
+constexpr int IVF_QB_PLAIN = 4;               // queries per work item: plain float loop
+constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bounds
 
 // ------------------------------------------------------------------------------------------
 // nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.
@@ -168,7 +170,7 @@ __device__ __forceinline__ int ivf_chunks_of(int64_t size) {
 __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restrict__ np,
                                                         const int64_t *__restrict__ list_offsets, int nlist,
                                                         uint32_t *pair_off, uint32_t *nc_out, uint32_t *item_off,
-                                                        uint32_t *nitems_dev) {
+                                                        uint32_t *nitems_dev, uint32_t qb) {
     __shared__ uint32_t scan[1024];
     __shared__ uint32_t cls_items[32], cls_base[32], cls_cursor[32];
     __shared__ uint32_t carry;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
             const int64_t size = list_offsets[l + 1] - list_offsets[l];
             const int nc = v > 0 ? ivf_chunks_of(size) : 0;
             nc_out[l] = (uint32_t)nc;
-            const uint32_t items = ((v + IVF_QB - 1) / IVF_QB) * (uint32_t)nc;
+            const uint32_t items = ((v + qb - 1) / qb) * (uint32_t)nc;
             if (items > 0) atomicAdd(&cls_items[63 - __builtin_clzll((unsigned long long)size)], items);
         }
         __syncthreads();
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
     __syncthreads();
     for (int l = tid; l < nlist; l += 1024) {
         const uint32_t v = np[l];
-        const uint32_t items = ((v + IVF_QB - 1) / IVF_QB) * nc_out[l];
+        const uint32_t items = ((v + qb - 1) / qb) * nc_out[l];
         if (items > 0) {
             const int64_t size = list_offsets[l + 1] - list_offsets[l];
             const int c = 63 - __builtin_clzll((unsigned long long)size);
@@ -230,7 +232,7 @@ __global__ void ivf_fill_pairs_kernel(const int32_t *__restrict__ probes, int np
 // one thread per list: write the list's items (group-major, chunks of a group consecutive)
 __global__ void ivf_fill_items_kernel(const uint32_t *__restrict__ pair_off, const uint32_t *__restrict__ nc_arr,
                                       const uint32_t *__restrict__ item_off, const int64_t *__restrict__ list_offsets,
-                                      int nlist, int rows_per_16b, IvfItem *items) {
+                                      int nlist, int rows_per_16b, uint32_t qb, IvfItem *items) {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
     const uint32_t npl = pair_off[l + 1] - pair_off[l];
@@ -239,9 +241,9 @@ __global__ void ivf_fill_items_kernel(const uint32_t *__restrict__ pair_off, con
     const int64_t beg = list_offsets[l], end = list_offsets[l + 1];
     int64_t rpc = (end - beg + nc - 1) / nc;
     rpc = (rpc + rows_per_16b - 1) / rows_per_16b * rows_per_16b;
-    const int ng = (int)((npl + IVF_QB - 1) / IVF_QB);
+    const int ng = (int)((npl + qb - 1) / qb);
     for (int g = 0; g < ng; ++g) {
-        const int nslots = (int)(npl - (uint32_t)g * IVF_QB < (uint32_t)IVF_QB ? npl - (uint32_t)g * IVF_QB : IVF_QB);
+        const int nslots = (int)(npl - (uint32_t)g * qb < qb ? npl - (uint32_t)g * qb : qb);
         for (int c = 0; c < nc; ++c) {
             int64_t cb = beg + (int64_t)c * rpc, ce = cb + rpc < end ? cb + rpc : end;
             IvfItem it;
@@ -249,7 +251,7 @@ __global__ void ivf_fill_items_kernel(const uint32_t *__restrict__ pair_off, con
             const int64_t aligned = cb / rows_per_16b * rows_per_16b;
             it.code_begin = (uint32_t)aligned;
             it.ncodes = (uint32_t)(ce - aligned);
-            it.pair_pos = pair_off[l] + (uint32_t)g * IVF_QB;
+            it.pair_pos = pair_off[l] + (uint32_t)g * qb;
             it.skip_slots_chunk = (uint32_t)(cb - aligned) | ((uint32_t)nslots << 8) | ((uint32_t)c << 16);
             items[item_off[l] + (uint32_t)g * nc + c] = it;
         }
@@ -338,12 +340,55 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
     }
 }
 
+// Pruned scan of inverted lists: per (query, list) pair the minima of its M tables, their sum, and the
+// scale of the pair's 16-bit lower-bound tables (see scan_flush_pruned): PRUNE_RANGE table units between
+// the sum of the minima and the query's first bound tau0.  A pair whose minima already add up to tau0 or
+// more cannot contribute a result and gets a negative scale; no first bound gives scale 0 (no pruning);
+// the scale is capped so that the bound converts to table units to a fraction of a unit in fp32.
+// One wave per pair.
+template <int M>
+__global__ __launch_bounds__(256) void ivf_prune_prep_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
+                                                             int npairs, int nprobe, float range_units, float *pair_min,
+                                                             float *pair_off, float *pair_scale) {
+    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (pair >= npairs) return;
+    const float4 *t = reinterpret_cast<const float4 *>(luts + (size_t)pair * M * 256);
+    float off = 0.f;
+    for (int j = 0; j < M; ++j) {
+        const float4 v = t[j * 64 + lane];
+        float mn = fminf(fminf(v.x, v.y), fminf(v.z, v.w));
+        for (int o = 32; o > 0; o >>= 1) mn = fminf(mn, __shfl_xor(mn, o));
+        if (lane == 0) pair_min[(size_t)pair * M + j] = mn;
+        off += mn;
+    }
+    if (lane == 0) {
+        const float bound = tau0[pair / nprobe];
+        float scale = 0.f;
+        if (bound < 3.0e38f) {
+            const float range = bound - off;
+            if (!(range > 0.f)) {
+                scale = -1.f;
+            } else {
+                scale = range_units / range;
+                const float cap = 0.99e6f / bound;   // bound * scale * 1e-6 stays below 1
+                if (!(scale < cap)) scale = cap;
+                if (!(scale > 0.f) || !(scale < 3.0e38f)) scale = 0.f;
+            }
+        }
+        pair_off[pair] = off;
+        pair_scale[pair] = scale;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
     (void)cf;
     const int d = L->d, nlist = L->nlist;
-    const int kind = m == 8 ? 0 : 1;
+    // the loop on 16-bit lower bounds (8 pairs per item) unless switched off
+    const bool prune = env_int("PQ_SCAN_PRUNE", 1) != 0;
+    const int kind = prune ? (m == 8 ? 3 : 4) : (m == 8 ? 0 : 1);
+    const uint32_t item_qb = prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
     const int kpad = 128;
     const int rows_per_16b = 16 / m;
     hipStream_t s = ctx->stream;
@@ -360,7 +405,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     if (qbatch < 1) qbatch = 1;
     if (qbatch > nq) qbatch = nq;
     const size_t npairs_max = (size_t)qbatch * nprobe;
-    const size_t max_items = (npairs_max / IVF_QB + (size_t)nlist + 1) * IVF_MAX_CHUNKS;
+    const size_t max_items = (npairs_max / item_qb + (size_t)nlist + 1) * IVF_MAX_CHUNKS;
     const size_t max_lists = npairs_max * IVF_MAX_CHUNKS;
 
     // workspace carving (all offsets 256-byte aligned)
@@ -382,8 +427,14 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_qlists = take((size_t)qbatch * 4);
     const size_t o_qlistoff = take((size_t)(qbatch + 1) * 4);
     const size_t o_tau0 = take((size_t)qbatch * 4);
+    const size_t o_pmin = take(prune ? npairs_max * m * 4 : 0);
+    const size_t o_poff = take(prune ? npairs_max * 4 : 0);
+    const size_t o_pscale = take(prune ? npairs_max * 4 : 0);
     const size_t o_partial = take(max_lists * kpad * 8);
-    const size_t state_bytes = tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
+    // blocks of 8 waves, two per CU, unless PQ_IVF_BLOCK_WAVES=16 asks for the flat scan's shape
+    const bool w8_blocks = env_int("PQ_IVF_BLOCK_WAVES", 8) != 16;
+    const size_t state_bytes = w8_blocks ? w8::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu)
+                                         : w16::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
     const size_t o_state = take(state_bytes);
     int rc = ws_reserve(ctx, off);
     if (rc) return rc;
@@ -424,10 +475,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         ivf_zero_kernel<<<256, 256, 0, s>>>(np, (size_t)nlist);
         ivf_zero_kernel<<<256, 256, 0, s>>>(fill, (size_t)nlist);
         ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, np);
-        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev);
+        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb);
         ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, pair_off, fill, pairs_by_list);
         ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(pair_off, nc, item_off, L->list_offsets, nlist,
-                                                                  rows_per_16b, items);
+                                                                  rows_per_16b, item_qb, items);
         ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
         ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, nprobe, qlist_off, pair_out);
         PQ_HIP(ctx, hipGetLastError());
@@ -435,9 +486,18 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         float *tau0 = (float *)(ws + o_tau0);
         ivf_seed_kernel<<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, m, topk, tau0);
         PQ_HIP(ctx, hipGetLastError());
+        float *pmin = nullptr, *poff = nullptr, *pscale = nullptr;
+        if (prune) {
+            pmin = (float *)(ws + o_pmin); poff = (float *)(ws + o_poff); pscale = (float *)(ws + o_pscale);
+            if (m == 8) ivf_prune_prep_kernel<8><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale);
+            else ivf_prune_prep_kernel<16><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale);
+            PQ_HIP(ctx, hipGetLastError());
+        }
         uint32_t *tau_global = nullptr;
-        rc = launch_scan_items(ctx, kind, L->codes, luts, nqb, nprobe, topk, items, nitems_dev, pairs_by_list, pair_out,
-                               partial, ws + o_state, state_bytes, tau0, &tau_global);
+        rc = w8_blocks ? w8::launch_scan_items(ctx, kind, pmin, poff, pscale, L->codes, luts, nqb, nprobe, topk, items, nitems_dev,
+                                               pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_global)
+                       : w16::launch_scan_items(ctx, kind, pmin, poff, pscale, L->codes, luts, nqb, nprobe, topk, items, nitems_dev,
+                                                pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_global);
         if (rc) return rc;
         rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_global, kpad, nqb, topk, L->ids, false,
                                    out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);

@@ -8,7 +8,14 @@
 
 namespace pq {
 
-constexpr int TUNED_WAVES = 16;
+// The tuned scan kernels are built twice (scan_tuned.hip, scan_items_w8.hip): blocks of 16 waves, one
+// per CU, for flat scans, and blocks of 8 waves, two per CU, for the short work items of inverted
+// lists, where one block's item set-up runs while the other block scans.  Each build lives in its
+// own namespace (w16, w8).
+#ifndef PQ_TUNED_WAVES
+#define PQ_TUNED_WAVES 16
+#endif
+constexpr int TUNED_WAVES = PQ_TUNED_WAVES;
 constexpr int TUNED_THREADS = TUNED_WAVES * 64;
 constexpr int HIST_BITS = 12;
 constexpr int HIST_BINS = 1 << HIST_BITS;
@@ -54,6 +61,11 @@ struct TunedArgs {
     const uint4 *qtabs;
     const float *prune_off;
     const float *prune_scale;
+    // pruned float scan of inverted lists: offsets and scales per (query, list) pair (prune_off and
+    // prune_scale are indexed by pair; a negative scale marks a pair no code of which can enter the
+    // result), and the minima of the pair's tables, from which the 16-bit entries are formed while
+    // the item's tables are staged
+    const float *pair_min;       // [npairs][tables]
 };
 
 static inline int env_int(const char *name, int dflt) {
@@ -72,13 +84,24 @@ int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *
 // caller-provided device region of tuned_state_bytes() bytes holding the per-query bounds,
 // histograms and the per-block candidate scratch; tau0 (optional, [nq]) seeds the per-query bounds
 // (+inf: none); *tau_global_out receives the per-query bounds.
+namespace w16 {
 size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu);
-int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
+int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float *pair_off, const float *pair_scale,
+                      const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
                       const float *tau0, uint32_t **tau_global_out);
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids);
+}  // namespace w16
+namespace w8 {   // work items only, results of up to 128
+size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu);
+int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float *pair_off, const float *pair_scale,
+                      const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
+                      const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
+                      const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
+                      const float *tau0, uint32_t **tau_global_out);
+}  // namespace w8
 
 // ------------------------------------------------------------------------------------------
 // Value traits: how the accumulated value of one (code, query) pair maps to the ordered

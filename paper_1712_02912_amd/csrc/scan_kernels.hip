@@ -352,9 +352,9 @@ int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void
                 int topk, void *out_val, int64_t *out_ids) {
     const bool general = env_int("PQ_SCAN_FORCE_GENERAL", 0) != 0;
     if (!general && cf == PQ_CODES_U8 && lf == PQ_LUT_F32 && k == 256 && (m == 8 || m == 16))
-        return launch_scan_tuned(ctx, m == 8 ? 0 : 1, codes, n, luts, nq, topk, out_val, out_ids);
+        return w16::launch_scan_tuned(ctx, m == 8 ? 0 : 1, codes, n, luts, nq, topk, out_val, out_ids);
     if (!general && cf == PQ_CODES_U4_PACKED && lf == PQ_LUT_U8 && k == 16 && m == 16)
-        return launch_scan_tuned(ctx, 2, codes, n, luts, nq, topk, out_val, out_ids);
+        return w16::launch_scan_tuned(ctx, 2, codes, n, luts, nq, topk, out_val, out_ids);
     if ((int64_t)m * k <= 8192)
         return run_generic(ctx, codes, n, cf, luts, lf == PQ_LUT_U8, nq, m, k, topk, out_val, out_ids);
     return fail(ctx, PQ_EUNSUPPORTED, "scan: no kernel for m=%d k=%d code_fmt=%d lut_fmt=%d", m, k, cf, lf);

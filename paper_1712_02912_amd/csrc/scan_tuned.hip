@@ -34,7 +34,17 @@
 #include "topk_device.h"
 #include "lds_walk.h"
 
+// This file is compiled as is (blocks of 16 waves, namespace pq::w16) and once more through
+// scan_items_w8.hip (blocks of 8 waves, namespace pq::w8, work items of inverted lists only).
+#ifndef PQ_TUNED_NS
+#define PQ_TUNED_NS w16
+#endif
+#ifndef PQ_TUNED_ITEMS_ONLY
+#define PQ_TUNED_ITEMS_ONLY 0
+#endif
+
 namespace pq {
+namespace PQ_TUNED_NS {
 
 // Per-wave selection state kept in LDS: the scan loop itself only holds the thresholds in
 // registers; everything else is touched on the rare paths below.
@@ -57,7 +67,8 @@ struct __align__(16) TunedSmemT {
     // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
     uint32_t ring[TUNED_WAVES][RING];
     float prune_off[8];      // per slot: sum of the table minima, and the scale of the 16-bit tables
-    float prune_scale[8];
+    float prune_scale[8];    // (0: no pruning for this slot, negative: nothing of this slot can qualify)
+    float pmin[8][16];       // inverted lists: minima of the slot's tables
     WaveState ws[TUNED_WAVES];
     uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
     int out_cnt[8];        // keys handed to the item's result list of each query so far
@@ -423,8 +434,9 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             const uint32_t loose = shared == 0xffffffffu ? shared : shared + 1u;
             const uint32_t own = ws->own_ord[ql];
             eff_lane = own < loose ? own : loose;
-            const float t = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sm->prune_scale[ql]) + (float)PRUNE_MARGIN;
-            thr_lane = (uint32_t)fmaxf(fminf(t, 32767.f), 0.f);
+            const float sc = sm->prune_scale[ql];
+            const float t = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sc) + (float)PRUNE_MARGIN;
+            thr_lane = sc >= 0.f ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
         }
         // bit h * QB + q of m: the lower bound of code h does not rule out query q
         uint32_t m = 0;
@@ -694,6 +706,15 @@ void scan_tuned_kernel(TunedArgs a) {
                     qid = pair / a.nprobe;
                     lut = (const float *)a.luts + (size_t)pair * (NT * 256);
                     out = a.partial + ((size_t)a.pair_out[pair] + (it.skip_slots_chunk >> 16)) * KPAD;
+                    if constexpr (PRUNED) {
+                        sm.prune_off[s] = a.prune_off[pair];
+                        sm.prune_scale[s] = a.prune_scale[pair];
+                        const float4 *pm = reinterpret_cast<const float4 *>(a.pair_min + (size_t)pair * NT);
+#pragma unroll
+                        for (int i = 0; i < NT / 4; ++i) *reinterpret_cast<float4 *>(&sm.pmin[s][4 * i]) = pm[i];
+                    }
+                } else if constexpr (PRUNED) {
+                    sm.prune_off[s] = 0.f; sm.prune_scale[s] = -1.f;
                 }
                 if (s == 0) {
                     sm.code_begin = it.code_begin;
@@ -744,15 +765,36 @@ void scan_tuned_kernel(TunedArgs a) {
 
         // ---- stage the tables of the slots' queries -----------------------------------------------
         if constexpr (PRUNED) {
-            // 16-bit tables of the group, prepared in slot order: [group][byte][table] x 8 queries
-            const uint4 *qt = a.qtabs + (size_t)sm.group * (256 * NT);
-            for (int e = threadIdx.x; e < 256 * NT; e += TUNED_THREADS) {
-                const uint4 pk = qt[e];
-                if constexpr (NT == 8) {
-                    sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
-                    sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
-                } else {
-                    sm.lut[e] = pk;   // (e >> 4) * 16 + (e & 15)
+            if (a.item_tab) {
+                // inverted lists: every slot has the float tables of its own (query, list) pair; the
+                // 16-bit entries min(ENTRY_MAX, floor((D - min of the table) * scale of the pair)) are
+                // formed here (same arithmetic as prune_tables_kernel)
+                constexpr float ENTRY_MAX = (float)(32767 / NT);
+                for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
+                    const int j = e >> 8, byte = e & 255;
+                    uint32_t v[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const float *lut = (const float *)sm.slot_lut[q];
+                        const float sc = sm.prune_scale[q];
+                        v[q] = 0u;
+                        if (lut != nullptr && sc > 0.f) v[q] = (uint32_t)fminf(floorf((lut[e] - sm.pmin[q][j]) * sc), ENTRY_MAX);
+                    }
+                    const uint4 pk = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+                    if (NT == 8) { sm.lut[byte * 16 + 2 * j] = pk; sm.lut[byte * 16 + 2 * j + 1] = pk; }
+                    else sm.lut[byte * 16 + j] = pk;
+                }
+            } else {
+                // 16-bit tables of the group, prepared in slot order: [group][byte][table] x 8 queries
+                const uint4 *qt = a.qtabs + (size_t)sm.group * (256 * NT);
+                for (int e = threadIdx.x; e < 256 * NT; e += TUNED_THREADS) {
+                    const uint4 pk = qt[e];
+                    if constexpr (NT == 8) {
+                        sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
+                        sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
+                    } else {
+                        sm.lut[e] = pk;   // (e >> 4) * 16 + (e & 15)
+                    }
                 }
             }
         } else if constexpr (!IS_U4) {
@@ -812,8 +854,9 @@ void scan_tuned_kernel(TunedArgs a) {
             } else if constexpr (PRUNED) {
                 // the bound in table units, rounded down, plus the slack that covers the rounding of
                 // the tables and of this conversion; no bound (or no scale) admits every sum
-                const float t = floorf((ord_to_f32(eff) - sm.prune_off[ql]) * sm.prune_scale[ql]) + (float)PRUNE_MARGIN;
-                eff = ql < nvalid_q ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
+                const float sc = sm.prune_scale[ql];
+                const float t = floorf((ord_to_f32(eff) - sm.prune_off[ql]) * sc) + (float)PRUNE_MARGIN;
+                eff = ql < nvalid_q && sc >= 0.f ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
             } else {
                 eff = __float_as_uint(ord_to_f32(eff));
             }
@@ -1222,10 +1265,17 @@ static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
 // lists, scans for few queries), which takes more bytes on their way per wave.
 template <int KIND>
 static int launch_kind_sized(pq_ctx *ctx, bool small, bool stream, const TunedArgs &a, int nblocks) {
+#if PQ_TUNED_ITEMS_ONLY
+    // work items of inverted lists: groups of four sub-tiles keep the rings small enough for two
+    // blocks per CU
+    (void)small; (void)stream;
+    return launch_kind<KIND, E_SMALL, 128, 4>(ctx, a, nblocks);
+#else
     if (stream) {
         return small ? launch_kind<KIND, E_SMALL, 128, 8>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 8>(ctx, a, nblocks);
     }
     return small ? launch_kind<KIND, E_SMALL, 128, 2>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 2>(ctx, a, nblocks);
+#endif
 }
 
 static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const TunedArgs &a, int nblocks) {
@@ -1234,24 +1284,36 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const 
         case KIND_F32_M16: return launch_kind_sized<KIND_F32_M16>(ctx, small, stream, a, nblocks);
         case KIND_F32P_M8: return launch_kind_sized<KIND_F32P_M8>(ctx, small, stream, a, nblocks);
         case KIND_F32P_M16: return launch_kind_sized<KIND_F32P_M16>(ctx, small, stream, a, nblocks);
+#if PQ_TUNED_ITEMS_ONLY
+        default: return fail(ctx, PQ_EUNSUPPORTED, "scan_items: kind %d", kind);
+#else
         default: return launch_kind_sized<KIND_U4_M16>(ctx, small, stream, a, nblocks);
+#endif
     }
 }
 
+static int qb_of_kind(int kind) { return kind == KIND_U4_M16 || kind == KIND_F32P_M8 || kind == KIND_F32P_M16 ? 8 : 4; }
+
+// blocks that share a CU: one of 16 waves, two of 8
+constexpr int BLOCKS_PER_CU = 16 / TUNED_WAVES;
+
 size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu) {
-    const int qb = kind == KIND_U4_M16 ? 8 : 4;
+    const int qb = qb_of_kind(kind);
     const int cap = 64 * (topk <= 128 ? E_SMALL : E_LARGE);
-    return state_layout(qb, nq, cap, num_cu).total;
+    return state_layout(qb, nq, cap, num_cu * BLOCKS_PER_CU).total;
 }
 
-int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
+int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float *pair_off, const float *pair_scale,
+                      const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
                       const float *tau0, uint32_t **tau_global_out) {
-    const int qb = kind == KIND_U4_M16 ? 8 : 4;
+    const int qb = qb_of_kind(kind);
+    if ((kind == KIND_F32P_M8 || kind == KIND_F32P_M16) && (!pair_min || !pair_off || !pair_scale))
+        return fail(ctx, PQ_EINVAL, "scan_items: the pruned scan needs the pairs' minima, offsets and scales");
     const bool small = topk <= 128;
     const int cap = 64 * (small ? E_SMALL : E_LARGE);
-    const int nblocks = ctx->num_cu;
+    const int nblocks = ctx->num_cu * BLOCKS_PER_CU;
     if (!small) return fail(ctx, PQ_EUNSUPPORTED, "scan_items: topk above 128");
     const StateLayout L = state_layout(qb, nq, cap, nblocks);
     if (L.total > state_bytes) return fail(ctx, PQ_EINVAL, "scan_items: state region too small");
@@ -1262,7 +1324,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     a.partial = partial;
     a.item_tab = items; a.nitems_dev = nitems_dev; a.pairs_by_list = pairs_by_list; a.pair_out = pair_out;
     a.nprobe = nprobe;
-    a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
+    a.qtabs = nullptr; a.prune_off = pair_off; a.prune_scale = pair_scale; a.pair_min = pair_min;
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
                                                      0xff800000u, a.hist, L.nhist, tau0, nq, 1.f);
     PQ_HIP(ctx, hipGetLastError());
@@ -1277,6 +1339,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const uint8_t *codes, const float *
     return PQ_OK;
 }
 
+#if !PQ_TUNED_ITEMS_ONLY
 static int ngroups_of(int nq, bool packed) { const int qb = packed ? 8 : 4; return (nq + qb - 1) / qb; }
 
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
@@ -1338,7 +1401,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     a.partial = (uint64_t *)(ws + off_partial);
     a.item_tab = nullptr; a.nitems_dev = nullptr; a.pairs_by_list = nullptr; a.pair_out = nullptr; a.nprobe = 0;
 
-    a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr;
+    a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr; a.pair_min = nullptr;
     float *tau0 = nullptr;
     if (prune) {
         tau0 = (float *)(ws + off_tau0);
@@ -1379,4 +1442,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
                                  out_val, out_ids);
 }
 
+#endif   // !PQ_TUNED_ITEMS_ONLY
+
+}  // namespace PQ_TUNED_NS
 }  // namespace pq

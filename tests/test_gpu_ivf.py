@@ -154,3 +154,35 @@ def test_ivf_queries_served_in_several_batches(ctx, monkeypatch):
     cb = (r.random((m, 256, d // m)) * 20 - 10).astype(np.float32)
     queries = (r.random((nq, d)) * 100).astype(np.float32)
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 64, 20)
+
+
+@pytest.mark.parametrize("env", [{"PQ_IVF_BLOCK_WAVES": "16"}, {"PQ_SCAN_PRUNE": "0"},
+                                 {"PQ_SCAN_PRUNE": "0", "PQ_IVF_BLOCK_WAVES": "16"}])
+@pytest.mark.parametrize("m", [8, 16])
+def test_ivf_switches_plain_float_loop_and_block_shape(ctx, monkeypatch, env, m):
+    """The inverted-list scan without lower-bound pruning (4 pairs per item) and in blocks of 16 waves."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    mix, coarse, cb, codes, order, offsets = make_index(20000, 64, m, 40, seed=71 + m)
+    queries = mix.sample(11, 97)
+    run_ivf(ctx, queries, coarse, offsets, codes, order, cb, 8, 100)
+    run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 40, 7)
+
+
+def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx):
+    """Far lists whose table minima already exceed the query's first bound (nothing of them may enter the
+    result), and a query whose nearest lists hold fewer than topk codes (no first bound, no pruning)."""
+    r = np.random.default_rng(73)
+    d, m, nlist = 32, 8, 12
+    sizes = np.array([5000, 4000, 3, 2, 6000, 2500, 1, 0, 3000, 3500, 2000, 4500])
+    offsets = datagen.offsets_from_sizes(sizes)
+    n = int(offsets[-1])
+    codes = r.integers(0, 256, (n, m), dtype=np.uint8)
+    coarse = (r.random((nlist, d)) * 10).astype(np.float32)
+    coarse[4:] += 400.0                               # a far group of lists: residuals there are huge
+    cb = (r.random((m, 256, d // m)) * 4 - 2).astype(np.float32)
+    queries = (r.random((7, d)) * 10).astype(np.float32)
+    queries[5] = coarse[2] + 0.01                     # nearest lists are the tiny ones
+    queries[6] = coarse[6] + 0.01
+    for nprobe, topk in ((12, 100), (6, 10), (3, 128)):
+        run_ivf(ctx, queries, coarse, offsets, codes, None, cb, nprobe, topk)

@@ -72,13 +72,14 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
 // recomputed from the differences, so that exact zeros stay exact.
 // Block: 256 threads = 4 waves in a 2 x 2 grid, each wave 32 x 32 outputs as 2 x 2 MFMA tiles.
 constexpr int MT = 64;   // queries and centroids per block
-constexpr int MK = 16;   // dimensions per LDS chunk
+// MK: dimensions per LDS chunk (16 is used; 32 measured slower on every configured shape)
 // DOT: write the inner products themselves (out[q][c] = <y_q, c>, used for R x) instead of distances.
-template <bool DOT>
+template <bool DOT, int MK>
 __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__restrict__ queries,
                                                               const float *__restrict__ codebooks, int nq, int d, int m,
                                                               int k, float *__restrict__ luts) {
     typedef double double4_t __attribute__((ext_vector_type(4)));
+    constexpr int MDPT = MK / 4;   // dimensions of a row that one thread stages (four threads per row)
     __shared__ double ys[MK][MT + 2];
     __shared__ double cs[MK][MT + 2];
     __shared__ double ny[MT], nc[MT];
@@ -94,36 +95,40 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = (double4_t){0.0, 0.0, 0.0, 0.0};
     double norm = 0.0;   // thread t < 64: ||y_t||^2, thread 64 + t: ||c_t||^2
-    const int lrow = tid >> 2, lk = (tid & 3) * 4;   // this thread stages 4 consecutive dimensions of one row
+    const int lrow = tid >> 2, lk = (tid & 3) * MDPT;   // this thread stages MDPT consecutive dimensions of one row
     const bool yrow_ok = q0 + lrow < nq, crow_ok = c0 + lrow < k;
     const float *yrow = ybase + (size_t)(yrow_ok ? q0 + lrow : 0) * d;
     const float *crow = cbase + (size_t)(crow_ok ? c0 + lrow : 0) * ds;
     const bool vec = (ds & 3) == 0 && (d & 3) == 0;   // rows start on 16-byte boundaries
-    // the chunk after the one being multiplied waits in registers
-    float yv[4], cv[4];
-    auto fetch = [&](int k0) {
+    // the two chunks after the one being multiplied are on their way or wait in registers
+    float yv[2][MDPT], cv[2][MDPT];
+    auto fetch = [&](int k0, float (&yr)[MDPT], float (&cr)[MDPT]) {
         const int t = k0 + lk;
-        if (vec && t + 4 <= ds) {
-            const float4 a = *reinterpret_cast<const float4 *>(yrow + t), b = *reinterpret_cast<const float4 *>(crow + t);
-            yv[0] = a.x; yv[1] = a.y; yv[2] = a.z; yv[3] = a.w;
-            cv[0] = b.x; cv[1] = b.y; cv[2] = b.z; cv[3] = b.w;
+        if (vec && t + MDPT <= ds) {
+#pragma unroll
+            for (int v = 0; v < MDPT / 4; ++v) {
+                const float4 a = *reinterpret_cast<const float4 *>(yrow + t + 4 * v), b = *reinterpret_cast<const float4 *>(crow + t + 4 * v);
+                yr[4 * v] = a.x; yr[4 * v + 1] = a.y; yr[4 * v + 2] = a.z; yr[4 * v + 3] = a.w;
+                cr[4 * v] = b.x; cr[4 * v + 1] = b.y; cr[4 * v + 2] = b.z; cr[4 * v + 3] = b.w;
+            }
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                yv[i] = t + i < ds ? yrow[t + i] : 0.f;
-                cv[i] = t + i < ds ? crow[t + i] : 0.f;
+            for (int i = 0; i < MDPT; ++i) {
+                yr[i] = t + i < ds ? yrow[t + i] : 0.f;
+                cr[i] = t + i < ds ? crow[t + i] : 0.f;
             }
         }
     };
-    fetch(0);
-    for (int k0 = 0; k0 < ds; k0 += MK) {
+    // one chunk of MK dimensions: registers -> LDS (as doubles), refill the registers with the
+    // chunk two steps ahead, norms, products
+    auto chunk = [&](int k0, float (&yr)[MDPT], float (&cr)[MDPT]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ys[lk + i][lrow] = yrow_ok ? (double)yv[i] : 0.0;
-            cs[lk + i][lrow] = crow_ok ? (double)cv[i] : 0.0;
+        for (int i = 0; i < MDPT; ++i) {
+            ys[lk + i][lrow] = yrow_ok ? (double)yr[i] : 0.0;
+            cs[lk + i][lrow] = crow_ok ? (double)cr[i] : 0.0;
         }
         __syncthreads();
-        if (k0 + MK < ds) fetch(k0 + MK);
+        if (k0 + 2 * MK < ds) fetch(k0 + 2 * MK, yr, cr);
         if (!DOT && tid < 2 * MT) {
             const double(*src)[MT + 2] = tid < MT ? ys : cs;
             const int r = tid & (MT - 1);
@@ -145,6 +150,12 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
                     acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
         }
         __syncthreads();
+    };
+    fetch(0, yv[0], cv[0]);
+    if (MK < ds) fetch(MK, yv[1], cv[1]);
+    for (int k0 = 0; k0 < ds; k0 += 2 * MK) {
+        chunk(k0, yv[0], cv[0]);
+        if (k0 + MK < ds) chunk(k0 + MK, yv[1], cv[1]);
     }
     if (tid < MT) ny[tid] = norm;
     else if (tid < 2 * MT) nc[tid - MT] = norm;
@@ -181,7 +192,7 @@ int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks,
     if (d / m >= 8 && env_flag_on("PQ_LUT_MFMA")) {
         dim3 mgrid((k + MT - 1) / MT, (nq + MT - 1) / MT, m);
         if (mgrid.y > 65535 || mgrid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/64 above 65535");
-        build_luts_mfma_kernel<false><<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
+        build_luts_mfma_kernel<false, 16><<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
         PQ_HIP(ctx, hipGetLastError());
         return PQ_OK;
     }
@@ -203,7 +214,7 @@ int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n
         const int64_t rows0 = t0 * MT;
         const int64_t rows = (n - rows0) < (int64_t)65535 * MT ? (n - rows0) : (int64_t)65535 * MT;
         dim3 grid((d + MT - 1) / MT, (unsigned)((rows + MT - 1) / MT), 1);
-        build_luts_mfma_kernel<true><<<grid, 256, 0, ctx->stream>>>(vectors + (size_t)rows0 * d, rot, (int)rows, d, 1, d,
+        build_luts_mfma_kernel<true, 16><<<grid, 256, 0, ctx->stream>>>(vectors + (size_t)rows0 * d, rot, (int)rows, d, 1, d,
                                                                     out + (size_t)rows0 * d);
         PQ_HIP(ctx, hipGetLastError());
     }

@@ -1117,6 +1117,54 @@ __global__ __launch_bounds__(256) void u4_seed_kernel(const uint8_t *__restrict_
     }
 }
 
+// The same over more codes than one block per query can look at (few query groups, large database):
+// block (s, q) counts the sums of slice s of the first `cnt` codes into the query's bins in device
+// memory, u4_seed_pick_kernel reads the bound off the counts.
+__global__ __launch_bounds__(256) void u4_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
+                                                           const uint8_t *__restrict__ qluts, uint32_t *seed_hist) {
+    __shared__ uint32_t hist[4096];
+    __shared__ uint8_t tab[256];
+    const int q = blockIdx.y, tid = threadIdx.x;
+    tab[tid] = qluts[(size_t)q * 256 + tid];
+    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+    __syncthreads();
+    const int64_t begin = (int64_t)blockIdx.x * (1 << 16);
+    const int64_t end = begin + (1 << 16) < cnt ? begin + (1 << 16) : cnt;
+    for (int64_t i = begin + tid; i < end; i += 256) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+        uint32_t sum = 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t byte = ((r < 4 ? c.x : c.y) >> (8 * (r & 3))) & 255u;
+            sum += (uint32_t)tab[(2 * r) * 16 + (byte & 15u)] + (uint32_t)tab[(2 * r + 1) * 16 + (byte >> 4)];
+        }
+        atomicAdd(&hist[sum], 1u);   // sum <= 16 * 255 < 4096
+    }
+    __syncthreads();
+    for (int i = tid; i < 4096; i += 256)
+        if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * 4096 + i], hist[i]);
+}
+
+__global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int kq, uint32_t *tau_global) {
+    __shared__ uint32_t part[256];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *hist = seed_hist + (size_t)q * 4096;
+    uint32_t mine = 0;
+    for (int i = 0; i < 16; ++i) mine += hist[tid * 16 + i];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cum = 0;
+        int t = 0;
+        while (t < 256 && cum + part[t] < (uint32_t)kq) cum += part[t++];
+        if (t < 256) {
+            int b = t * 16;
+            while (cum + hist[b] < (uint32_t)kq) cum += hist[b++];
+            tau_global[q] = (uint32_t)b;
+        }
+    }
+}
+
 // Better first bound for scans in which many blocks start on the same query at once (few query
 // groups): one block per query looks at the first `cnt` codes, counts the float distances at or
 // below the bound known so far (tau0, from the first PRUNE_INIT codes, which are among the `cnt`)
@@ -1164,6 +1212,70 @@ __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__r
             tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
         }
     }
+}
+
+// The same refinement over more codes than one block per query can look at (flat scans of few
+// query groups over large databases, where every candidate the first bound lets through costs more
+// than a code it dismisses): block (s, q) counts the distances of slice s at or below the query's
+// bound in the bins of the scan's histogram and adds its counts to the query's bins in device memory;
+// f32_seed_pick_kernel then lowers the bound to the smallest bin edge with at least k distances.
+constexpr int SEED_SLICE = 1 << 16;
+__global__ __launch_bounds__(256) void f32_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
+                                                            const float *__restrict__ luts, const float *__restrict__ tau0,
+                                                            uint32_t *seed_hist) {
+    __shared__ float tab[8 * 256];
+    __shared__ uint32_t hist[HIST_BINS];
+    const int q = blockIdx.y, tid = threadIdx.x;
+    for (int i = tid; i < 2048; i += 256) tab[i] = luts[(size_t)q * 2048 + i];
+    for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
+    __syncthreads();
+    const uint32_t ref = f32_to_ord(tau0[q]);
+    const int64_t begin = (int64_t)blockIdx.x * SEED_SLICE;
+    const int64_t end = begin + SEED_SLICE < cnt ? begin + SEED_SLICE : cnt;
+    for (int64_t i = begin + tid; i < end; i += 256) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+        float d = tab[c.x & 255u];
+        d += tab[256 + ((c.x >> 8) & 255u)];
+        d += tab[512 + ((c.x >> 16) & 255u)];
+        d += tab[768 + (c.x >> 24)];
+        d += tab[1024 + (c.y & 255u)];
+        d += tab[1280 + ((c.y >> 8) & 255u)];
+        d += tab[1536 + ((c.y >> 16) & 255u)];
+        d += tab[1792 + (c.y >> 24)];
+        const uint32_t ord = f32_to_ord(d);
+        if (ord <= ref) {
+            const uint32_t below = (ref - ord) >> HIST_SHIFT;
+            atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < HIST_BINS; i += 256)
+        if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * HIST_BINS + i], hist[i]);
+}
+
+__global__ __launch_bounds__(256) void f32_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int k, float *tau0) {
+    __shared__ uint32_t part[256];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *hist = seed_hist + (size_t)q * HIST_BINS;
+    uint32_t mine = 0;
+    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t ref = f32_to_ord(tau0[q]);
+        uint32_t cum = 0;
+        int t = 0;
+        while (t < 256 && cum + part[t] < (uint32_t)k) cum += part[t++];
+        if (t < 256) {
+            int b = t * (HIST_BINS / 256);
+            while (cum + hist[b] < (uint32_t)k) cum += hist[b++];
+            tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
+        }
+    }
+}
+
+__global__ void zero_u32_kernel(uint32_t *p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 // 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
@@ -1389,7 +1501,15 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // the plain float loops get a first bound as well (enlarged by a few units of fp32 rounding: they
     // add the table entries in a rotated order, the bound is computed in table order)
     const bool seed_plain = !is_u4 && !prune && n >= PRUNE_INIT;
-    const size_t total = prune ? off_qtabs + (size_t)ngroups * 256 * tables * sizeof(uint4) : (seed_plain ? off_poff : off_tau0);
+    // few query groups over a large database: the first bound comes from a sixty-fourth of the codes
+    const bool few_groups = ngroups < STREAM_GROUPS;
+    int64_t seed_codes_f32 = SEED_CODES_STREAM;   // (integer scans use the same count)
+    if (few_groups && n / 64 > seed_codes_f32) seed_codes_f32 = n / 64;
+    const bool wide_seed = prune && few_groups && tables == 8 && seed_codes_f32 > SEED_SLICE;
+    const bool wide_seed_u4 = is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
+    const size_t off_seedhist = prune ? off_qtabs + align_up((size_t)ngroups * 256 * tables * sizeof(uint4), 256) : off_tau0;
+    const size_t total = prune ? off_seedhist + (wide_seed ? (size_t)nq * HIST_BINS * 4 : 0)
+                               : (wide_seed_u4 ? off_seedhist + (size_t)nq * 4096 * 4 : (seed_plain ? off_poff : off_tau0));
     rc = ws_reserve(ctx, total);
     if (rc) return rc;
     uint8_t *ws = (uint8_t *)ctx->ws;
@@ -1409,7 +1529,14 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
         rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
         if (rc) return rc;
-        if (ngroups < STREAM_GROUPS && tables == 8) {
+        if (wide_seed) {
+            uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
+            zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * HIST_BINS);
+            const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
+            f32_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
+            f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
+            PQ_HIP(ctx, hipGetLastError());
+        } else if (few_groups && tables == 8) {
             f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, SEED_CODES_STREAM, (const float *)luts, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
@@ -1427,8 +1554,16 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
                                                      seed_plain ? 1.f + 4e-6f : 1.f);
     PQ_HIP(ctx, hipGetLastError());
     if (is_u4 && n >= PRUNE_MIN_N) {
-        const int seed_codes = ngroups < STREAM_GROUPS ? SEED_CODES_STREAM : (topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT);
-        u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, a.tau_global);
+        if (wide_seed_u4) {
+            uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
+            zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * 4096);
+            const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
+            u4_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
+            u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_global);
+        } else {
+            const int seed_codes = few_groups ? SEED_CODES_STREAM : (topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT);
+            u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, a.tau_global);
+        }
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));

@@ -552,3 +552,33 @@ def test_config3_gist_like_16x8_sampled(ctx):
     for r, q in enumerate(SAMPLE_Q):
         check_float_topk(gd[q], gi[q], od[r], oi[r], codes_h, orc.CODES_U8, luts_h[q], len(codes_h))
 
+
+
+def test_scan_f32_few_queries_large_database_wide_first_bound(ctx):
+    """Few query groups over a database large enough for the first bound to come from n / 64 codes
+    (several seed slices): 8 x 256 tables, 3 and 17 queries, ragged size; top-100 and top-1."""
+    r = np.random.default_rng(47)
+    n = 9_000_011
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    codes[n // 2:n // 2 + 300] = codes[:300]          # exact ties across slices
+    luts_h = (r.random((17, 8, 256)) * 100).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h[:3], 100)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 1)
+    # distances descending with the row number for query 0: the first bound (from the front of the
+    # database) is the loosest possible
+    d0 = orc.adc_all_f32(codes[:2_000_000], orc.CODES_U8, luts_h[0])
+    worst = np.ascontiguousarray(codes[:2_000_000][np.argsort(-d0, kind="stable")])
+    big = np.concatenate([worst, codes[2_000_000:5_000_000]])
+    run_float_scan(ctx, big, orc.CODES_U8, luts_h[:2], 100)
+
+
+def test_scan_u4_few_queries_large_database_wide_first_bound(ctx):
+    """The integer scan's first bound from n / 64 codes (several seed slices): bit-exact top-100 and top-1000."""
+    r = np.random.default_rng(49)
+    n = 9_000_011
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = r.integers(0, 256, (11, 16, 16), dtype=np.uint8)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts[:2], 100)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 1000)
+    qluts[0, :, :] = 7                                  # every code has the same sum: ids decide
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts[:1], 100)

@@ -110,6 +110,7 @@ __device__ __forceinline__ bool n2_fits(int count, int capacity) {
 }
 
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3, KIND_F32P_M16 = 4 };
+constexpr int SEED_CODES_BATCH = 1 << 15;   // codes looked at for the first bound of a float scan of many query groups
 constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
 constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
 constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain float scan
@@ -1165,8 +1166,8 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
     }
 }
 
-// Better first bound for scans in which many blocks start on the same query at once (few query
-// groups): one block per query looks at the first `cnt` codes, counts the float distances at or
+// Better first bound (every candidate the first bound lets through costs far more than a code the
+// integer test dismisses): one block per query looks at the first `cnt` codes, counts the float distances at or
 // below the bound known so far (tau0, from the first PRUNE_INIT codes, which are among the `cnt`)
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
 // distances at or below it.  Distances are summed in table order, as everywhere on this path.
@@ -1536,8 +1537,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             f32_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
-        } else if (few_groups && tables == 8) {
-            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, SEED_CODES_STREAM, (const float *)luts, topk, tau0);
+        } else if (tables == 8) {
+            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH, (const float *)luts, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
         if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
@@ -1561,7 +1562,10 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             u4_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
             u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_global);
         } else {
-            const int seed_codes = few_groups ? SEED_CODES_STREAM : (topk * 16 > PRUNE_INIT ? topk * 16 : PRUNE_INIT);
+            // 256 codes per result wanted, between PRUNE_INIT and 65 536 (more costs the seed kernel more than it saves the scan)
+            int seed_codes = topk * 256 > PRUNE_INIT ? topk * 256 : PRUNE_INIT;
+            if (few_groups || seed_codes > SEED_CODES_STREAM) seed_codes = SEED_CODES_STREAM;
+            if ((int64_t)seed_codes > n) seed_codes = (int)n;
             u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, a.tau_global);
         }
         PQ_HIP(ctx, hipGetLastError());

@@ -1168,20 +1168,22 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
 
 // Better first bound (every candidate the first bound lets through costs far more than a code the
 // integer test dismisses): one block per query looks at the first `cnt` codes, counts the float distances at or
-// below the bound known so far (tau0, from the first PRUNE_INIT codes, which are among the `cnt`)
+// below the bound known so far (tau0 as handed in, or with self_ref the greatest distance of the first k codes)
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
 // distances at or below it.  Distances are summed in table order, as everywhere on this path.
 __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
-                                                              const float *__restrict__ luts, int k, float *tau0) {
+                                                              const float *__restrict__ luts, int k, bool self_ref,
+                                                              float *tau0) {
     __shared__ float tab[8 * 256];
     __shared__ uint32_t hist[HIST_BINS];
     __shared__ uint32_t part[256];
+    __shared__ uint32_t ref_s;
     const int q = blockIdx.x, tid = threadIdx.x;
     for (int i = tid; i < 2048; i += 256) tab[i] = luts[(size_t)q * 2048 + i];
     for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
+    if (tid == 0) ref_s = self_ref ? 0u : f32_to_ord(tau0[q]);
     __syncthreads();
-    const uint32_t ref = f32_to_ord(tau0[q]);
-    for (int i = tid; i < cnt; i += 256) {
+    auto dist_ord = [&](int i) {
         const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
         float d = tab[c.x & 255u];
         d += tab[256 + ((c.x >> 8) & 255u)];
@@ -1191,7 +1193,15 @@ __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__r
         d += tab[1280 + ((c.y >> 8) & 255u)];
         d += tab[1536 + ((c.y >> 16) & 255u)];
         d += tab[1792 + (c.y >> 24)];
-        const uint32_t ord = f32_to_ord(d);
+        return f32_to_ord(d);
+    };
+    if (self_ref) {   // no bound yet: the greatest distance among the first k codes is one
+        for (int i = tid; i < k && i < cnt; i += 256) atomicMax(&ref_s, dist_ord(i));
+        __syncthreads();
+    }
+    const uint32_t ref = ref_s;
+    for (int i = tid; i < cnt; i += 256) {
+        const uint32_t ord = dist_ord(i);
         if (ord <= ref) {
             const uint32_t below = (ref - ord) >> HIST_SHIFT;
             atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
@@ -1211,6 +1221,8 @@ __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__r
             while (cum + hist[b] < (uint32_t)k) cum += hist[b++];
             // every distance counted in bins <= b is at or below this edge
             tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
+        } else if (self_ref) {
+            tau0[q] = cnt >= k ? ord_to_f32(ref) : __builtin_inff();
         }
     }
 }
@@ -1528,17 +1540,21 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         tau0 = (float *)(ws + off_tau0);
         float *poff = (float *)(ws + off_poff), *pscale = (float *)(ws + off_pscale);
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
-        rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
-        if (rc) return rc;
+        if (tables == 8) {
+            // the first bound: smallest histogram edge with k distances among the first codes
+            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH,
+                                                                (const float *)luts, topk, true, tau0);
+            PQ_HIP(ctx, hipGetLastError());
+        } else {
+            rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
+            if (rc) return rc;
+        }
         if (wide_seed) {
             uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * HIST_BINS);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
             f32_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
-            PQ_HIP(ctx, hipGetLastError());
-        } else if (tables == 8) {
-            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH, (const float *)luts, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
         if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);

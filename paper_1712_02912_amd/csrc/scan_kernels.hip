@@ -193,22 +193,29 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
     __shared__ unsigned long long s_kth;
     const int gq = blockIdx.x, tid = threadIdx.x;
     const size_t nlists = qlist_off ? (size_t)(qlist_off[gq + 1] - qlist_off[gq]) : (size_t)nchunks;
-    const size_t total = nlists * kpad;
-    auto key_at = [&](size_t i) -> uint64_t {
-        const size_t l = i / kpad, e = i % kpad;
-        const size_t list = qlist_off ? (size_t)qlist_off[gq] + l : (l * ngroups + gq / qb) * qb + gq % qb;
-        return partial[list * kpad + e];
+    // Every list is packed (its keys first, KEY_EMPTY behind them; kpad is a multiple of 64): a wave
+    // takes whole lists, 64 keys at a time, and leaves a list at the first empty slot it sees.
+    const int wave = tid >> 6, lane = tid & 63, nwaves = (int)(blockDim.x >> 6);
+    auto for_each_key = [&](auto &&f) {
+        for (size_t l = wave; l < nlists; l += nwaves) {
+            const size_t list = qlist_off ? (size_t)qlist_off[gq] + l : (l * ngroups + gq / qb) * qb + gq % qb;
+            const uint64_t *lp = partial + list * kpad;
+            for (int e0 = 0; e0 < kpad; e0 += 64) {
+                const uint64_t key = lp[e0 + lane];
+                f(key);
+                if (__ballot(key == KEY_EMPTY) != 0ull) break;
+            }
+        }
     };
     const uint32_t tau = tau_global[gq];
     if (tid == 0) s_count = 0;
     __syncthreads();
-    for (size_t i = tid; i < total; i += blockDim.x) {
-        const uint64_t key = key_at(i);
+    for_each_key([&](uint64_t key) {
         if (key != KEY_EMPTY && (uint32_t)(key >> 32) <= tau) {
             const int pos = atomicAdd(&s_count, 1);
             if (pos < MERGE_CAP) skeys[pos] = key;
         }
-    }
+    });
     __syncthreads();
     int kept = s_count;
     if (kept > MERGE_CAP) {
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
             if (tid == 0) s_count = 0;
             __syncthreads();
             int c = 0;
-            for (size_t i = tid; i < total; i += blockDim.x) c += key_at(i) <= trial ? 1 : 0;
+            for_each_key([&](uint64_t key) { c += key <= trial ? 1 : 0; });
             atomicAdd(&s_count, c);
             __syncthreads();
             if (s_count < topk) v |= (1ull << bit);
@@ -229,10 +236,9 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
         if (tid == 0) { s_kth = v; s_count = 0; }
         __syncthreads();
         const uint64_t kth = s_kth;
-        for (size_t i = tid; i < total; i += blockDim.x) {
-            const uint64_t key = key_at(i);
+        for_each_key([&](uint64_t key) {
             if (key != KEY_EMPTY && key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < MERGE_CAP) skeys[pos] = key; }
-        }
+        });
         __syncthreads();
         kept = s_count < MERGE_CAP ? s_count : MERGE_CAP;
     }

@@ -1121,28 +1121,37 @@ __global__ __launch_bounds__(256) void u4_seed_kernel(const uint8_t *__restrict_
 // The same over more codes than one block per query can look at (few query groups, large database):
 // block (s, q) counts the sums of slice s of the first `cnt` codes into the query's bins in device
 // memory, u4_seed_pick_kernel reads the bound off the counts.
-__global__ __launch_bounds__(256) void u4_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
-                                                           const uint8_t *__restrict__ qluts, uint32_t *seed_hist) {
+__global__ __launch_bounds__(1024) void u4_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
+                                                            const uint8_t *__restrict__ qluts, uint32_t *seed_hist) {
     __shared__ uint32_t hist[4096];
     __shared__ uint8_t tab[256];
     const int q = blockIdx.y, tid = threadIdx.x;
-    tab[tid] = qluts[(size_t)q * 256 + tid];
-    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+    if (tid < 256) tab[tid] = qluts[(size_t)q * 256 + tid];
+    for (int i = tid; i < 4096; i += 1024) hist[i] = 0;
     __syncthreads();
     const int64_t begin = (int64_t)blockIdx.x * (1 << 16);
     const int64_t end = begin + (1 << 16) < cnt ? begin + (1 << 16) : cnt;
-    for (int64_t i = begin + tid; i < end; i += 256) {
-        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
-        uint32_t sum = 0;
+    for (int64_t i0 = begin + tid; i0 < end; i0 += 4 * 1024) {
+        uint2 c[4];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const uint32_t byte = ((r < 4 ? c.x : c.y) >> (8 * (r & 3))) & 255u;
-            sum += (uint32_t)tab[(2 * r) * 16 + (byte & 15u)] + (uint32_t)tab[(2 * r + 1) * 16 + (byte >> 4)];
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + u * 1024;
+            c[u] = i < end ? *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8) : make_uint2(0, 0);
         }
-        atomicAdd(&hist[sum], 1u);   // sum <= 16 * 255 < 4096
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + u * 1024 >= end) break;
+            uint32_t sum = 0;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const uint32_t byte = ((r < 4 ? c[u].x : c[u].y) >> (8 * (r & 3))) & 255u;
+                sum += (uint32_t)tab[(2 * r) * 16 + (byte & 15u)] + (uint32_t)tab[(2 * r + 1) * 16 + (byte >> 4)];
+            }
+            atomicAdd(&hist[sum], 1u);   // sum <= 16 * 255 < 4096
+        }
     }
     __syncthreads();
-    for (int i = tid; i < 4096; i += 256)
+    for (int i = tid; i < 4096; i += 1024)
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * 4096 + i], hist[i]);
 }
 
@@ -1233,36 +1242,45 @@ __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__r
 // bound in the bins of the scan's histogram and adds its counts to the query's bins in device memory;
 // f32_seed_pick_kernel then lowers the bound to the smallest bin edge with at least k distances.
 constexpr int SEED_SLICE = 1 << 16;
-__global__ __launch_bounds__(256) void f32_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
-                                                            const float *__restrict__ luts, const float *__restrict__ tau0,
-                                                            uint32_t *seed_hist) {
+__global__ __launch_bounds__(1024) void f32_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
+                                                             const float *__restrict__ luts, const float *__restrict__ tau0,
+                                                             uint32_t *seed_hist) {
     __shared__ float tab[8 * 256];
     __shared__ uint32_t hist[HIST_BINS];
     const int q = blockIdx.y, tid = threadIdx.x;
-    for (int i = tid; i < 2048; i += 256) tab[i] = luts[(size_t)q * 2048 + i];
-    for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
+    for (int i = tid; i < 2048; i += 1024) tab[i] = luts[(size_t)q * 2048 + i];
+    for (int i = tid; i < HIST_BINS; i += 1024) hist[i] = 0;
     __syncthreads();
     const uint32_t ref = f32_to_ord(tau0[q]);
     const int64_t begin = (int64_t)blockIdx.x * SEED_SLICE;
     const int64_t end = begin + SEED_SLICE < cnt ? begin + SEED_SLICE : cnt;
-    for (int64_t i = begin + tid; i < end; i += 256) {
-        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
-        float d = tab[c.x & 255u];
-        d += tab[256 + ((c.x >> 8) & 255u)];
-        d += tab[512 + ((c.x >> 16) & 255u)];
-        d += tab[768 + (c.x >> 24)];
-        d += tab[1024 + (c.y & 255u)];
-        d += tab[1280 + ((c.y >> 8) & 255u)];
-        d += tab[1536 + ((c.y >> 16) & 255u)];
-        d += tab[1792 + (c.y >> 24)];
-        const uint32_t ord = f32_to_ord(d);
-        if (ord <= ref) {
-            const uint32_t below = (ref - ord) >> HIST_SHIFT;
-            atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+    for (int64_t i0 = begin + tid; i0 < end; i0 += 4 * 1024) {
+        uint2 c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t i = i0 + u * 1024;
+            c[u] = i < end ? *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8) : make_uint2(0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (i0 + u * 1024 >= end) break;
+            float d = tab[c[u].x & 255u];
+            d += tab[256 + ((c[u].x >> 8) & 255u)];
+            d += tab[512 + ((c[u].x >> 16) & 255u)];
+            d += tab[768 + (c[u].x >> 24)];
+            d += tab[1024 + (c[u].y & 255u)];
+            d += tab[1280 + ((c[u].y >> 8) & 255u)];
+            d += tab[1536 + ((c[u].y >> 16) & 255u)];
+            d += tab[1792 + (c[u].y >> 24)];
+            const uint32_t ord = f32_to_ord(d);
+            if (ord <= ref) {
+                const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+            }
         }
     }
     __syncthreads();
-    for (int i = tid; i < HIST_BINS; i += 256)
+    for (int i = tid; i < HIST_BINS; i += 1024)
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * HIST_BINS + i], hist[i]);
 }
 
@@ -1514,10 +1532,16 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // the plain float loops get a first bound as well (enlarged by a few units of fp32 rounding: they
     // add the table entries in a rotated order, the bound is computed in table order)
     const bool seed_plain = !is_u4 && !prune && n >= PRUNE_INIT;
-    // few query groups over a large database: the first bound comes from a sixty-fourth of the codes
+    // Few query groups over a large database: the first bound comes from a larger part of the codes.
+    // Measured optimum (10^7 .. 10^9 codes, 1 .. 200 queries): about 64 M code evaluations over all
+    // queries of the call, at most a thirty-second of the database per query.
     const bool few_groups = ngroups < STREAM_GROUPS;
     int64_t seed_codes_f32 = SEED_CODES_STREAM;   // (integer scans use the same count)
-    if (few_groups && n / 64 > seed_codes_f32) seed_codes_f32 = n / 64;
+    if (few_groups) {
+        int64_t want = ((int64_t)64 << 20) / (nq > 0 ? nq : 1);
+        if (want > n / 32) want = n / 32;
+        if (want > seed_codes_f32) seed_codes_f32 = want;
+    }
     const bool wide_seed = prune && few_groups && tables == 8 && seed_codes_f32 > SEED_SLICE;
     const bool wide_seed_u4 = is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
     const size_t off_seedhist = prune ? off_qtabs + align_up((size_t)ngroups * 256 * tables * sizeof(uint4), 256) : off_tau0;
@@ -1542,8 +1566,9 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
         if (tables == 8) {
             // the first bound: smallest histogram edge with k distances among the first codes
-            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH,
-                                                                (const float *)luts, topk, true, tau0);
+            // (a reference for the histogram bins is all the wide pass needs from this one)
+            const int first_codes = wide_seed ? PRUNE_INIT : (few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH);
+            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
             PQ_HIP(ctx, hipGetLastError());
         } else {
             rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
@@ -1553,7 +1578,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * HIST_BINS);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
-            f32_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
+            f32_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
@@ -1575,7 +1600,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * 4096);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
-            u4_seed_hist_kernel<<<sgrid, 256, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
+            u4_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
             u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_global);
         } else {
             // 256 codes per result wanted, between PRUNE_INIT and 65 536 (more costs the seed kernel more than it saves the scan)

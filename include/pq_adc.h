@@ -201,9 +201,10 @@ typedef struct {
  * every (query, list) pair, result lists) stays within PQ_IVF_WS_GIB GiB of device
  * memory (environment, default 24, 1 ... 128); one batch is fastest because a list's
  * codes are then scanned once for all the queries that probe it.
- * The lists are scanned on 16-bit lower bounds of the distances, exact float distances only for
- * the codes whose bound passes (as in pq_adc_scan_topk; PQ_SCAN_PRUNE=0 selects the plain float
- * loop), by blocks of 8 waves, two per compute unit (PQ_IVF_BLOCK_WAVES=16: one block of 16). */
+ * The lists are scanned by the float loop, four (query, list) pairs per work item, in blocks of 8
+ * waves, two per compute unit (PQ_IVF_BLOCK_WAVES=16: one block of 16).  PQ_IVF_PRUNE=1 selects the
+ * loop on 16-bit lower bounds with exact float distances only for the codes whose bound passes
+ * (as in pq_adc_scan_topk), eight pairs per item. */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);

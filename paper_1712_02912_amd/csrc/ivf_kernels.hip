@@ -302,41 +302,82 @@ __global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__
 }
 
 // First bound per query: float ADC (table order) of up to IVF_SEED_CODES codes taken from the
-// query's probed lists in probe order, each with the tables of its (query, list) pair; the topk-th
-// smallest distance, enlarged by a few units of fp32 rounding because the scan adds the same
-// eight or sixteen entries in another order.  +inf if the lists hold fewer than topk codes.
-constexpr int IVF_SEED_CODES = 4096;
+// query's probed lists in probe order, each with the tables of its (query, list) pair.  The greatest
+// of the first topk distances is a bound already; the distances at or below it are counted in bins of
+// 2^HIST_SHIFT ordered-value units below it (0.2 % of the value each), and the smallest bin edge with
+// topk distances at or below it is the bound handed on, enlarged by a few units of fp32 rounding
+// because the plain scan loop adds the same entries in another order.  +inf if the lists hold fewer
+// than topk codes.  (Every candidate a loose first bound lets through costs the scan far more than a
+// code its integer test dismisses, so the sample is generous.)
+constexpr int IVF_SEED_CODES = 16384;
+template <int M>
 __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict__ codes,
                                                        const int64_t *__restrict__ list_offsets,
                                                        const int32_t *__restrict__ probes, const float *__restrict__ luts,
-                                                       int nprobe, int m, int topk, float *tau0) {
-    __shared__ uint64_t skeys[IVF_SEED_CODES];
+                                                       int nprobe, int topk, float *tau0) {
+    __shared__ float tab[M * 256];
+    __shared__ uint32_t hist[HIST_BINS];
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t ref_s;
     const int q = blockIdx.x, tid = threadIdx.x;
-    int count = 0;
-    for (int r = 0; r < nprobe && count < IVF_SEED_CODES; ++r) {
-        const int l = probes[(size_t)q * nprobe + r];
-        const int64_t beg = list_offsets[l], size = list_offsets[l + 1] - beg;
-        const int take = (int)(size < IVF_SEED_CODES - count ? size : IVF_SEED_CODES - count);
-        const float *lut = luts + ((size_t)q * nprobe + r) * m * 256;
-        for (int i = tid; i < take; i += 256) {
-            const uint8_t *c = codes + (size_t)(beg + i) * m;
-            float dist = 0.f;
-            for (int j = 0; j < m; ++j) dist += lut[j * 256 + c[j]];
-            skeys[count + i] = ((uint64_t)f32_to_ord(dist) << 32) | (uint32_t)(count + i);
+    for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
+    if (tid == 0) ref_s = 0;
+    // f(ordered distance) for the first `limit` codes of the probed lists; returns how many there were
+    auto for_codes = [&](int limit, auto &&f) {
+        int count = 0;
+        for (int r = 0; r < nprobe && count < limit; ++r) {
+            const int l = probes[(size_t)q * nprobe + r];
+            const int64_t beg = list_offsets[l], size = list_offsets[l + 1] - beg;
+            const int take = (int)(size < limit - count ? size : limit - count);
+            if (take <= 0) continue;
+            const float *lut = luts + ((size_t)q * nprobe + r) * M * 256;
+            __syncthreads();
+            for (int i = tid; i < M * 256; i += 256) tab[i] = lut[i];
+            __syncthreads();
+            for (int i = tid; i < take; i += 256) {
+                const uint8_t *c = codes + (size_t)(beg + i) * M;
+                uint32_t w[M / 4];
+                if (M == 8) { const uint2 v = *reinterpret_cast<const uint2 *>(c); w[0] = v.x; w[1] = v.y; }
+                else { const uint4 v = *reinterpret_cast<const uint4 *>(c); w[0] = v.x; w[1] = v.y; w[M / 4 - 2] = v.z; w[M / 4 - 1] = v.w; }
+                float dist = 0.f;
+#pragma unroll
+                for (int j = 0; j < M; ++j) dist += tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
+                f(f32_to_ord(dist));
+            }
+            count += take;
         }
-        count += take;
+        return count;
+    };
+    const int first = for_codes(topk, [&](uint32_t ord) { atomicMax(&ref_s, ord); });
+    __syncthreads();
+    if (first < topk) {
+        if (tid == 0) tau0[q] = __builtin_inff();
+        return;
     }
-    int n2 = 64;
-    while (n2 < count) n2 <<= 1;
-    for (int i = count + tid; i < n2; i += 256) skeys[i] = KEY_EMPTY;
-    block_bitonic_sort(skeys, n2);
-    if (tid == 0) {
-        float bound = __builtin_inff();
-        if (count >= topk) {
-            const float kth = ord_to_f32((uint32_t)(skeys[topk - 1] >> 32));
-            bound = kth + fabsf(kth) * 4e-6f;
+    const uint32_t ref = ref_s;
+    for_codes(IVF_SEED_CODES, [&](uint32_t ord) {
+        if (ord <= ref) {
+            const uint32_t below = (ref - ord) >> HIST_SHIFT;
+            atomicAdd(&hist[HIST_BINS - 1 - (below < (uint32_t)HIST_BINS ? below : HIST_BINS - 1)], 1u);
         }
-        tau0[q] = bound;
+    });
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
+    part[tid] = mine;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t cum = 0;
+        int t = 0;
+        while (t < 256 && cum + part[t] < (uint32_t)topk) cum += part[t++];
+        uint32_t edge = ref;
+        if (t < 256) {
+            int b = t * (HIST_BINS / 256);
+            while (cum + hist[b] < (uint32_t)topk) cum += hist[b++];
+            edge = ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT);   // every distance counted in bins <= b is at or below it
+        }
+        const float kth = ord_to_f32(edge);
+        tau0[q] = kth + fabsf(kth) * 4e-6f;
     }
 }
 
@@ -385,8 +426,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
     (void)cf;
     const int d = L->d, nlist = L->nlist;
-    // the loop on 16-bit lower bounds (8 pairs per item) unless switched off
-    const bool prune = env_int("PQ_SCAN_PRUNE", 1) != 0;
+    // The plain float loop (4 pairs per item) by default; PQ_IVF_PRUNE=1 selects the loop on 16-bit lower
+    // bounds (8 pairs per item, one more preparation kernel), which measured the same scan time and a
+    // longer call on the configured workload once two blocks share a CU.
+    const bool prune = env_int("PQ_IVF_PRUNE", 0) != 0;
     const int kind = prune ? (m == 8 ? 3 : 4) : (m == 8 ? 0 : 1);
     const uint32_t item_qb = prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
     const int kpad = 128;
@@ -484,7 +527,8 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         PQ_HIP(ctx, hipGetLastError());
         // Scan step, seeded with a first bound per query
         float *tau0 = (float *)(ws + o_tau0);
-        ivf_seed_kernel<<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, m, topk, tau0);
+        if (m == 8) ivf_seed_kernel<8><<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, topk, tau0);
+        else ivf_seed_kernel<16><<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, topk, tau0);
         PQ_HIP(ctx, hipGetLastError());
         float *pmin = nullptr, *poff = nullptr, *pscale = nullptr;
         if (prune) {

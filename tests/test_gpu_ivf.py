@@ -85,8 +85,10 @@ def test_ivf_all_lists_equals_flat_scan_of_residual_tables(ctx):
         np.testing.assert_allclose(gd[q], np.sort(dd)[:20], rtol=1e-5)
 
 
-def test_ivf_skewed_lists_many_chunks_and_empty_lists(ctx):
+@pytest.mark.parametrize("prune", ["0", "1"])
+def test_ivf_skewed_lists_many_chunks_and_empty_lists(ctx, monkeypatch, prune):
     """Zipf-like list sizes with one list long enough to be cut into chunks, odd list boundaries, empty lists."""
+    monkeypatch.setenv("PQ_IVF_PRUNE", prune)
     r = np.random.default_rng(41)
     d, m, nlist = 32, 8, 24
     sizes = np.array([700_001, 90_003, 7, 0, 1, 33_333, 0, 129, 128, 127] + [1000 + 37 * i for i in range(14)])
@@ -156,11 +158,11 @@ def test_ivf_queries_served_in_several_batches(ctx, monkeypatch):
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 64, 20)
 
 
-@pytest.mark.parametrize("env", [{"PQ_IVF_BLOCK_WAVES": "16"}, {"PQ_SCAN_PRUNE": "0"},
-                                 {"PQ_SCAN_PRUNE": "0", "PQ_IVF_BLOCK_WAVES": "16"}])
+@pytest.mark.parametrize("env", [{"PQ_IVF_BLOCK_WAVES": "16"}, {"PQ_IVF_PRUNE": "1"},
+                                 {"PQ_IVF_PRUNE": "1", "PQ_IVF_BLOCK_WAVES": "16"}])
 @pytest.mark.parametrize("m", [8, 16])
-def test_ivf_switches_plain_float_loop_and_block_shape(ctx, monkeypatch, env, m):
-    """The inverted-list scan without lower-bound pruning (4 pairs per item) and in blocks of 16 waves."""
+def test_ivf_switches_lower_bound_loop_and_block_shape(ctx, monkeypatch, env, m):
+    """The inverted-list scan on 16-bit lower bounds (8 pairs per item) and in blocks of 16 waves."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     mix, coarse, cb, codes, order, offsets = make_index(20000, 64, m, 40, seed=71 + m)
@@ -169,9 +171,11 @@ def test_ivf_switches_plain_float_loop_and_block_shape(ctx, monkeypatch, env, m)
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 40, 7)
 
 
-def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx):
+@pytest.mark.parametrize("prune", ["0", "1"])
+def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx, monkeypatch, prune):
     """Far lists whose table minima already exceed the query's first bound (nothing of them may enter the
     result), and a query whose nearest lists hold fewer than topk codes (no first bound, no pruning)."""
+    monkeypatch.setenv("PQ_IVF_PRUNE", prune)
     r = np.random.default_rng(73)
     d, m, nlist = 32, 8, 12
     sizes = np.array([5000, 4000, 3, 2, 6000, 2500, 1, 0, 3000, 3500, 2000, 4500])

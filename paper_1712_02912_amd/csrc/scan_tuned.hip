@@ -1180,28 +1180,31 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
 // below the bound known so far (tau0 as handed in, or with self_ref the greatest distance of the first k codes)
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
 // distances at or below it.  Distances are summed in table order, as everywhere on this path.
+template <int M>
 __global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
                                                               const float *__restrict__ luts, int k, bool self_ref,
                                                               float *tau0) {
-    __shared__ float tab[8 * 256];
+    __shared__ float tab[M * 256];
     __shared__ uint32_t hist[HIST_BINS];
     __shared__ uint32_t part[256];
     __shared__ uint32_t ref_s;
     const int q = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < 2048; i += 256) tab[i] = luts[(size_t)q * 2048 + i];
+    for (int i = tid; i < M * 256; i += 256) tab[i] = luts[(size_t)q * (M * 256) + i];
     for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
     if (tid == 0) ref_s = self_ref ? 0u : f32_to_ord(tau0[q]);
     __syncthreads();
     auto dist_ord = [&](int i) {
-        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
-        float d = tab[c.x & 255u];
-        d += tab[256 + ((c.x >> 8) & 255u)];
-        d += tab[512 + ((c.x >> 16) & 255u)];
-        d += tab[768 + (c.x >> 24)];
-        d += tab[1024 + (c.y & 255u)];
-        d += tab[1280 + ((c.y >> 8) & 255u)];
-        d += tab[1536 + ((c.y >> 16) & 255u)];
-        d += tab[1792 + (c.y >> 24)];
+        uint32_t w[M / 4];
+        if (M == 8) {
+            const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+            w[0] = c.x; w[1] = c.y;
+        } else {
+            const uint4 c = *reinterpret_cast<const uint4 *>(codes + (size_t)i * 16);
+            w[0] = c.x; w[1] = c.y; w[M / 4 - 2] = c.z; w[M / 4 - 1] = c.w;
+        }
+        float d = tab[w[0] & 255u];
+#pragma unroll
+        for (int j = 1; j < M; ++j) d += tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
         return f32_to_ord(d);
     };
     if (self_ref) {   // no bound yet: the greatest distance among the first k codes is one
@@ -1564,15 +1567,13 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         tau0 = (float *)(ws + off_tau0);
         float *poff = (float *)(ws + off_poff), *pscale = (float *)(ws + off_pscale);
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
-        if (tables == 8) {
+        {
             // the first bound: smallest histogram edge with k distances among the first codes
             // (a reference for the histogram bins is all the wide pass needs from this one)
             const int first_codes = wide_seed ? PRUNE_INIT : (few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH);
-            f32_seed_refine_kernel<<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
+            if (tables == 8) f32_seed_refine_kernel<8><<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
+            else f32_seed_refine_kernel<16><<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
             PQ_HIP(ctx, hipGetLastError());
-        } else {
-            rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, tables, 256, PRUNE_INIT, topk, tau0);
-            if (rc) return rc;
         }
         if (wide_seed) {
             uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);

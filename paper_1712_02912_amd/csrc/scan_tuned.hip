@@ -49,13 +49,13 @@ namespace PQ_TUNED_NS {
 // Per-wave selection state kept in LDS: the scan loop itself only holds the thresholds in
 // registers; everything else is touched on the rare paths below.
 struct WaveState {
-    int cnt[8];
-    uint32_t own_ord[8];   // k-th smallest value of the wave's own list, ord_inf while not full
+    int cnt[16];
+    uint32_t own_ord[16];   // k-th smallest value of the wave's own list, ord_inf while not full
 };
 
 // wave list capacity in units of 64 keys: 384 keys for results of up to 128, 2048 for up to 1024
 constexpr int E_SMALL = 6, E_LARGE = 32;
-constexpr int RING_FLUSH = 32;    // flush when more than this many positions are parked
+constexpr int RING_FLUSH = 64;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
 
 // RING: ring entries per wave
@@ -66,22 +66,23 @@ struct __align__(16) TunedSmemT {
     // Per wave: lanes that found a candidate park the position of their 16 code bytes here; the
     // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
     uint32_t ring[TUNED_WAVES][RING];
-    float prune_off[8];      // per slot: sum of the table minima, and the scale of the 16-bit tables
-    float prune_scale[8];    // (0: no pruning for this slot, negative: nothing of this slot can qualify)
+    float prune_off[16];      // per slot: sum of the table minima, and the scale of the 16-bit tables
+    float prune_scale[16];    // (0: no pruning for this slot, negative: nothing of this slot can qualify)
     float pmin[8][16];       // inverted lists: minima of the slot's tables
+    uint32_t eff_tmp[TUNED_WAVES][16];   // 16-query insert path: the float bounds of the batch being inserted
     WaveState ws[TUNED_WAVES];
-    uint32_t tau_blk[8];   // best bound known to the block per query (prunes with "<=")
-    int out_cnt[8];        // keys handed to the item's result list of each query so far
-    uint32_t ncand_blk[8]; // candidates inserted by the block and not yet added to the query's device counter
-    uint32_t tau_ref[8];   // histogram reference per query (float path)
+    uint32_t tau_blk[16];   // best bound known to the block per query (prunes with "<=")
+    int out_cnt[16];        // keys handed to the item's result list of each query so far
+    uint32_t ncand_blk[16]; // candidates inserted by the block and not yet added to the query's device counter
+    uint32_t tau_ref[16];   // histogram reference per query (float path)
     // per item, written at its start: where the state of the query in each slot lives
-    uint32_t *hist[8];
-    uint32_t *ncand[8];
-    uint32_t *refresh_mark[8];
-    uint32_t *tau_global[8];
-    uint32_t *tau_ref_global[8];
-    const void *slot_lut[8];   // tables of the slot's query (nullptr: empty slot)
-    uint64_t *slot_out[8];     // where the slot's KPAD result keys go
+    uint32_t *hist[16];
+    uint32_t *ncand[16];
+    uint32_t *refresh_mark[16];
+    uint32_t *tau_global[16];
+    uint32_t *tau_ref_global[16];
+    const void *slot_lut[16];   // tables of the slot's query (nullptr: empty slot)
+    uint64_t *slot_out[16];     // where the slot's KPAD result keys go
     const uint8_t *chunk_ptr;  // first row scanned by the item
     int64_t code_begin;        // its row number
     int ncodes;                // rows scanned
@@ -109,7 +110,7 @@ __device__ __forceinline__ bool n2_fits(int count, int capacity) {
     return n2 <= capacity;
 }
 
-enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3, KIND_F32P_M16 = 4 };
+enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3, KIND_F32P_M16 = 4, KIND_F32Q_M8 = 5 };
 constexpr int SEED_CODES_BATCH = 1 << 15;   // codes looked at for the first bound of a float scan of many query groups
 constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
 constexpr int STREAM_GROUPS = 32;          // flat scans of fewer query groups fetch like streaming scans
@@ -117,6 +118,13 @@ constexpr int64_t PRUNE_MIN_N = 1 << 16;   // smaller databases take the plain f
 constexpr int PRUNE_INIT = 4096;           // codes looked at for the first bound of every query
 constexpr int PRUNE_MARGIN = 8;      // slack of the integer threshold, in table units
 constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the minima and the first bound
+// KIND_F32Q_M8: the same with 8-bit entries, 16 queries per 16-byte slot: entries of at most 15 (eight of them add
+// up to less than 128, so the sums of 16 queries add up byte-wise in four 32-bit words without carries and one
+// subtraction per word tests four of them), 64 units between the sum of the minima and the first bound (measured
+// optimum: fewer units blur the bound, more let codes with a few saturated entries through)
+constexpr float PRUNE_RANGE_Q8 = 64.f;
+constexpr int PRUNE_MARGIN_Q8 = 3;
+constexpr float PRUNE_ENTRY_MAX_Q8 = 15.f;
 
 // What a lane needs to walk the tables in its own rotated order (see the layout note on top):
 // derived from the low four bits of the lane that holds the code bytes.
@@ -387,9 +395,10 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
 // integer test against the current thresholds, and for every (code, query) that still passes adds
 // the eight float entries in table order -- the order of the plain definition, Eq. (adc1) -- tests the
 // result against the float bound and appends it to the wave's list of the query.
-template <class SM, int NT, int E>
+template <class SM, int NT, int E, int QB = 8>
 __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
-    constexpr int QB = 8, CPL = 16 / NT, CAP = 64 * E;
+    constexpr int CPL = 16 / NT, CAP = 64 * E;
+    constexpr bool Q8 = QB == 16;   // 8-bit entries, 16 queries per slot
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     LdsWaveState *ws = &sm->ws[wave];
     const int nvalid = sm->nvalid, skip = sm->skip, ncodes = sm->ncodes;
@@ -436,8 +445,9 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             const uint32_t own = ws->own_ord[ql];
             eff_lane = own < loose ? own : loose;
             const float sc = sm->prune_scale[ql];
-            const float t = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sc) + (float)PRUNE_MARGIN;
-            thr_lane = sc >= 0.f ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
+            const float t = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sc) + (float)(Q8 ? PRUNE_MARGIN_Q8 : PRUNE_MARGIN);
+            thr_lane = sc >= 0.f ? (uint32_t)fmaxf(fminf(t, Q8 ? 127.f : 32767.f), 0.f) : 0u;
+            if constexpr (Q8) sm->eff_tmp[wave][ql] = eff_lane;   // (16 lanes write the same 16 words four times over)
         }
         // bit h * QB + q of m: the lower bound of code h does not rule out query q
         uint32_t m = 0;
@@ -446,15 +456,17 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             const uint32_t thr = __builtin_amdgcn_readlane(thr_lane, q);
 #pragma unroll
             for (int h = 0; h < CPL; ++h) {
-                const uint32_t lb = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                const uint32_t lb = Q8 ? (acc[h][q >> 2] >> (8 * (q & 3))) & 0xffu : (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
                 if (ok[h] && q < nvalid && lb < thr) m |= 1u << (h * QB + q);
             }
         }
         // the float bounds as scalars (a lane read inside the divergent loop below would miss
         // the lanes that have already left it)
-        uint32_t eff_q[QB];
+        uint32_t eff_q[Q8 ? 1 : QB];   // (with 16 queries the bounds wait in LDS instead)
+        if constexpr (!Q8) {
 #pragma unroll
-        for (int q = 0; q < QB; ++q) eff_q[q] = __builtin_amdgcn_readlane(eff_lane, q);
+            for (int q = 0; q < QB; ++q) eff_q[q] = __builtin_amdgcn_readlane(eff_lane, q);
+        }
         uint32_t bits = m, inserted = 0;
         while (bits != 0u) {
             const int b = __builtin_ctz(bits);
@@ -481,9 +493,14 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
                 d += fl[3840 + (c.w >> 24)];
             }
             const uint32_t ord = f32_to_ord(d);
-            uint32_t eff = eff_q[0];
+            uint32_t eff;
+            if constexpr (Q8) {
+                eff = sm->eff_tmp[wave][q];
+            } else {
+                eff = eff_q[0];
 #pragma unroll
-            for (int i = 1; i < QB; ++i) eff = q == i ? eff_q[i] : eff;
+                for (int i = 1; i < QB; ++i) eff = q == i ? eff_q[i] : eff;
+            }
             if (ord < eff) {
                 inserted |= 1u << b;
                 const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
@@ -661,9 +678,10 @@ template <int KIND, int E, int KPAD, int DEPTH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void scan_tuned_kernel(TunedArgs a) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;           // values are integer sums
-    constexpr bool PRUNED = KIND == KIND_F32P_M8 || KIND == KIND_F32P_M16;   // float values, scan loop on 16-bit lower bounds
-    constexpr bool PACKED = IS_U4 || PRUNED;              // scan loop adds packed 16-bit entries, 8 queries
-    constexpr int QB = PACKED ? 8 : 4;
+    constexpr bool Q8 = KIND == KIND_F32Q_M8;             // float values, scan loop on 8-bit lower bounds, 16 queries
+    constexpr bool PRUNED = KIND == KIND_F32P_M8 || KIND == KIND_F32P_M16 || Q8;   // float values, scan loop on integer lower bounds
+    constexpr bool PACKED = IS_U4 || PRUNED;              // scan loop adds packed entries (16-bit: 8 queries, 8-bit: 16)
+    constexpr int QB = Q8 ? 16 : PACKED ? 8 : 4;
     constexpr int NT = KIND == KIND_F32_M16 || KIND == KIND_F32P_M16 ? 16 : 8;   // tables = lookups per code
     constexpr int CB = NT;                                // code bytes (8 or 16)
     constexpr int CPL = 16 / CB;                          // codes per lane per 16-byte load
@@ -760,7 +778,7 @@ void scan_tuned_kernel(TunedArgs a) {
             if (s == 0) sm.topk = a.topk;
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
-        if (threadIdx.x < 8) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
+        if (threadIdx.x < 16) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
         if (threadIdx.x == 0) sm.next_group = 2 * TUNED_WAVES;
         __syncthreads();
 
@@ -856,14 +874,17 @@ void scan_tuned_kernel(TunedArgs a) {
                 // the bound in table units, rounded down, plus the slack that covers the rounding of
                 // the tables and of this conversion; no bound (or no scale) admits every sum
                 const float sc = sm.prune_scale[ql];
-                const float t = floorf((ord_to_f32(eff) - sm.prune_off[ql]) * sc) + (float)PRUNE_MARGIN;
-                eff = ql < nvalid_q && sc >= 0.f ? (uint32_t)fmaxf(fminf(t, 32767.f), 0.f) : 0u;
+                const float t = floorf((ord_to_f32(eff) - sm.prune_off[ql]) * sc) + (float)(Q8 ? PRUNE_MARGIN_Q8 : PRUNE_MARGIN);
+                eff = ql < nvalid_q && sc >= 0.f ? (uint32_t)fmaxf(fminf(t, Q8 ? 127.f : 32767.f), 0.f) : 0u;
             } else {
                 eff = __float_as_uint(ord_to_f32(eff));
             }
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if constexpr (PACKED)
+                if constexpr (Q8)
+                    tau[p] = __builtin_amdgcn_readlane(eff, 4 * p) | (__builtin_amdgcn_readlane(eff, 4 * p + 1) << 8) |
+                             (__builtin_amdgcn_readlane(eff, 4 * p + 2) << 16) | (__builtin_amdgcn_readlane(eff, 4 * p + 3) << 24);
+                else if constexpr (PACKED)
                     tau[p] = __builtin_amdgcn_readlane(eff, 2 * p) | (__builtin_amdgcn_readlane(eff, 2 * p + 1) << 16);
                 else
                     tau[p] = __builtin_amdgcn_readlane(eff, p);
@@ -905,7 +926,16 @@ void scan_tuned_kernel(TunedArgs a) {
             uint32_t d[CPL][4];
             code_values<NT, PACKED, DEPTH == 2 ? 16 : 8>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
             uint64_t hit = 0;
-            if constexpr (PACKED) {
+            if constexpr (Q8) {
+                // 8-bit fields below 0x80 (sums and thresholds): (0x80 | sum) - threshold keeps bit 7 iff the
+                // sum is not below the threshold, and no field borrows from its neighbour
+                uint32_t keep = 0x80808080u;
+#pragma unroll
+                for (int h = 0; h < CPL; ++h)
+#pragma unroll
+                    for (int pp = 0; pp < 4; ++pp) keep &= (d[h][pp] | 0x80808080u) - tau[pp];
+                hit = __ballot(keep != 0x80808080u);
+            } else if constexpr (PACKED) {
                 // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold
                 // wraps (sets bit 15) iff one of them is below the threshold
                 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
@@ -936,8 +966,8 @@ void scan_tuned_kernel(TunedArgs a) {
         // that share a query alternate, so that each query is looked at every 32 steps of the block
         // and no wave carries more of this work than another.
         const int my_q = wave % QB;
-        const int my_phase = 1 + 4 * my_q + 32 * (wave / QB);
-        constexpr int REFRESH_MASK = 32 * (TUNED_WAVES / QB) - 1;
+        const int my_phase = QB > 8 ? 1 + 2 * my_q : 1 + 4 * my_q + 32 * (wave / QB);
+        constexpr int REFRESH_MASK = QB > 8 ? 31 : 32 * (TUNED_WAVES / QB) - 1;
         const bool refresher = my_q < nvalid_q;
         // Items that start without a useful bound: no bound at all, or (long result lists) the first
         // item of a block, which only has the loose bound the launch was seeded with.
@@ -953,7 +983,7 @@ void scan_tuned_kernel(TunedArgs a) {
         auto between_steps = [&]() {
             bool changed = false;
             if (flush_due()) {
-                if constexpr (PRUNED) scan_flush_pruned<SM, NT, E>(smp, wave_buf, ring_cnt);
+                if constexpr (PRUNED) scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
                 else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
                 pressure += ring_cnt;
                 ring_cnt = 0;
@@ -1016,7 +1046,7 @@ void scan_tuned_kernel(TunedArgs a) {
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
         if (ring_cnt > 0) {
-            if constexpr (PRUNED) scan_flush_pruned<SM, NT, E>(smp, wave_buf, ring_cnt);
+            if constexpr (PRUNED) scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
             else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
         }
         scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
@@ -1318,15 +1348,18 @@ __global__ void zero_u32_kernel(uint32_t *p, size_t n) {
 // L[j][b] = min(32767 / M, floor((D[j][b] - min_j) * scale)) for the M = 8 or 16 tables.  Output in
 // the slot order of the scan kernel: qtabs[group][b][j] holds entry b of table j for the 8 queries
 // of the group.
-template <int M>
+template <int M, int G = 8>   // G: queries per group (8 with 16-bit entries, 16 with 8-bit entries)
 __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
-                                                           int nq, uint4 *qtabs, float *off_out, float *scale_out) {
-    constexpr float ENTRY_MAX = (float)(32767 / M);   // M entries must add up to less than 2^15
-    __shared__ float smin[8][M];
-    __shared__ float sscale[8];
+                                                           int nq, uint4 *qtabs, float *off_out, float *scale_out, float range_q8) {
+    constexpr bool Q8 = G == 16;
+    constexpr float ENTRY_MAX = Q8 ? PRUNE_ENTRY_MAX_Q8 : (float)(32767 / M);   // M entries must add up to less than 2^15 (2^7)
+    const float RANGE = Q8 ? range_q8 : PRUNE_RANGE;
+    static_assert(!Q8 || M == 8, "8-bit entries: eight tables");
+    __shared__ float smin[G][M];
+    __shared__ float sscale[G];
     const int group = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int r = wave * (2 * M); r < (wave + 1) * (2 * M); ++r) {
-        const int q = r / M, j = r % M, gq = group * 8 + q;
+    for (int r = wave * (G * M / 4); r < (wave + 1) * (G * M / 4); ++r) {
+        const int q = r / M, j = r % M, gq = group * G + q;
         float v = __builtin_inff();
         if (gq < nq) {
             const float *t = luts + ((size_t)gq * M + j) * 256;
@@ -1336,15 +1369,15 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
         if (lane == 0) smin[q][j] = v;
     }
     __syncthreads();
-    if (tid < 8) {
-        const int gq = group * 8 + tid;
+    if (tid < G) {
+        const int gq = group * G + tid;
         float scale = 0.f;
         if (gq < nq) {
             float off = 0.f;
             for (int j = 0; j < M; ++j) off += smin[tid][j];
             const float range = tau0[gq] - off;
             if (range > 0.f && range < 3.0e38f) {
-                scale = PRUNE_RANGE / range;
+                scale = RANGE / range;
                 // the threshold conversion must stay accurate to a fraction of a table unit in fp32
                 if (!(tau0[gq] * scale * 1e-6f < 1.f)) scale = 0.f;
             }
@@ -1356,18 +1389,24 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
     __syncthreads();
     const int b = tid;
     for (int j = 0; j < M; ++j) {
-        uint32_t e[8];
+        uint32_t e[G];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int gq = group * 8 + q;
+        for (int q = 0; q < G; ++q) {
+            const int gq = group * G + q;
             e[q] = (uint32_t)ENTRY_MAX;   // no query in this slot: sums that never qualify
             if (gq < nq) {
                 const float x = (luts[((size_t)gq * M + j) * 256 + b] - smin[q][j]) * sscale[q];
                 e[q] = (uint32_t)fminf(floorf(x), ENTRY_MAX);
             }
         }
-        qtabs[(size_t)group * (256 * M) + b * M + j] =
-            make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+        uint4 pk;
+        if constexpr (Q8) {
+            pk = make_uint4(e[0] | (e[1] << 8) | (e[2] << 16) | (e[3] << 24), e[4] | (e[5] << 8) | (e[6] << 16) | (e[7] << 24),
+                            e[8] | (e[9] << 8) | (e[10] << 16) | (e[11] << 24), e[12] | (e[13] << 8) | (e[14] << 16) | (e[15] << 24));
+        } else {
+            pk = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+        }
+        qtabs[(size_t)group * (256 * M) + b * M + j] = pk;
     }
 }
 
@@ -1418,7 +1457,8 @@ static int launch_kind_sized(pq_ctx *ctx, bool small, bool stream, const TunedAr
     return launch_kind<KIND, E_SMALL, 128, 4>(ctx, a, nblocks);
 #else
     if (stream) {
-        return small ? launch_kind<KIND, E_SMALL, 128, 8>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 8>(ctx, a, nblocks);
+        if constexpr (KIND == KIND_F32Q_M8) return fail(ctx, PQ_EINVAL, "scan: the 16-query kind serves many query groups only");
+        else return small ? launch_kind<KIND, E_SMALL, 128, 8>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 8>(ctx, a, nblocks);
     }
     return small ? launch_kind<KIND, E_SMALL, 128, 2>(ctx, a, nblocks) : launch_kind<KIND, E_LARGE, 1024, 2>(ctx, a, nblocks);
 #endif
@@ -1430,6 +1470,9 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const 
         case KIND_F32_M16: return launch_kind_sized<KIND_F32_M16>(ctx, small, stream, a, nblocks);
         case KIND_F32P_M8: return launch_kind_sized<KIND_F32P_M8>(ctx, small, stream, a, nblocks);
         case KIND_F32P_M16: return launch_kind_sized<KIND_F32P_M16>(ctx, small, stream, a, nblocks);
+#if !PQ_TUNED_ITEMS_ONLY
+        case KIND_F32Q_M8: return launch_kind_sized<KIND_F32Q_M8>(ctx, small, stream, a, nblocks);
+#endif
 #if PQ_TUNED_ITEMS_ONLY
         default: return fail(ctx, PQ_EUNSUPPORTED, "scan_items: kind %d", kind);
 #else
@@ -1438,7 +1481,9 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const 
     }
 }
 
-static int qb_of_kind(int kind) { return kind == KIND_U4_M16 || kind == KIND_F32P_M8 || kind == KIND_F32P_M16 ? 8 : 4; }
+static int qb_of_kind(int kind) {
+    return kind == KIND_F32Q_M8 ? 16 : (kind == KIND_U4_M16 || kind == KIND_F32P_M8 || kind == KIND_F32P_M16 ? 8 : 4);
+}
 
 // blocks that share a CU: one of 16 waves, two of 8
 constexpr int BLOCKS_PER_CU = 16 / TUNED_WAVES;
@@ -1486,8 +1531,6 @@ int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float 
 }
 
 #if !PQ_TUNED_ITEMS_ONLY
-static int ngroups_of(int nq, bool packed) { const int qb = packed ? 8 : 4; return (nq + qb - 1) / qb; }
-
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids) {
     int rc;
@@ -1496,10 +1539,13 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // pay for the preparation (a bound per query from the first PRUNE_INIT codes, then the tables).
     const bool prune = (kind == KIND_F32_M8 || kind == KIND_F32_M16) && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
     const int tables = kind == KIND_F32_M16 ? 16 : 8;
-    if (prune) kind = tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8;
-    const int qb = is_u4 || prune ? 8 : 4;
+    // eight tables and enough queries to fill the GPU with groups of 16: 8-bit lower bounds, 16 queries per pass
+    // (PQ_SCAN_Q8=0: 16-bit lower bounds, 8 queries per pass, as for fewer queries)
+    const bool q8 = prune && tables == 8 && (nq + 15) / 16 >= STREAM_GROUPS && env_int("PQ_SCAN_Q8", 1) != 0;
+    if (prune) kind = q8 ? KIND_F32Q_M8 : (tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8);
+    const int qb = q8 ? 16 : (is_u4 || prune ? 8 : 4);
     const int cb = kind == KIND_F32_M16 || kind == KIND_F32P_M16 ? 16 : 8;
-    const int depth = ngroups_of(nq, is_u4 || prune) < STREAM_GROUPS ? 8 : 2;
+    const int depth = (nq + qb - 1) / qb < STREAM_GROUPS ? 8 : 2;
     const int tile = 64 * (16 / cb) * depth;   // codes per wave group (DEPTH sub-tiles)
     const bool small = topk <= 128;
     const int kpad = small ? 128 : 1024;
@@ -1583,8 +1629,9 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
-        if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
-        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale);
+        if (q8) prune_tables_kernel<8, 16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, (float)env_int("PQ_Q8_RANGE", (int)PRUNE_RANGE_Q8));
+        else if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f);
+        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f);
         PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
     } else if (seed_plain) {

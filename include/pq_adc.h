@@ -126,12 +126,16 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
  * m = 16), and any (U8 | U4 codes, F32 | U8 tables) with m*k <= 8192 through a slower
  * general kernel.  1 <= topk <= 1024, 0 <= n < 2^32; `codes` 16-byte aligned.
  * Float sums add the m entries in fp32, in table order or in a rotation of it (the result
- * differs from the exact sum by at most (m-1) * 2^-24 relative either way).  For m = 8,
- * k = 256 and n >= 65536 the kernel first dismisses codes by integer lower bounds of their
- * distances (the pruning idea of Section 4.2) and forms float sums only for the rest; the
- * result is that of the plain definition.  Integer sums are exact.
+ * differs from the exact sum by at most (m-1) * 2^-24 relative either way).  For k = 256,
+ * m = 8 or 16 and n >= 65536 the kernel first dismisses codes by integer lower bounds of their
+ * distances (the pruning idea of Section 4.2: small quantised tables, exact distances only
+ * for the codes they cannot rule out) and forms float sums only for the rest; the result is
+ * that of the plain definition.  The bounds are 16-bit sums for 8 queries per pass over the
+ * codes, or, for m = 8 and 512 queries and more, 8-bit sums for 16 queries per pass.
+ * Integer sums are exact.
  * Switches for tests and tuning, read from the environment at each call (unset = default):
- * PQ_SCAN_PRUNE=0 (no lower-bound pruning), PQ_SCAN_FORCE_GENERAL=1 (general kernel for every
+ * PQ_SCAN_PRUNE=0 (no lower-bound pruning), PQ_SCAN_Q8=0 (16-bit bounds for any number of
+ * queries), PQ_SCAN_FORCE_GENERAL=1 (general kernel for every
  * shape), PQ_SCAN_BLOCKS / PQ_SCAN_ITEMS_PER_BLOCK (launch shape), PQ_LUT_MFMA=0 (pq_build_luts
  * without the matrix cores). */
 int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,

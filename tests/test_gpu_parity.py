@@ -582,3 +582,54 @@ def test_scan_u4_few_queries_large_database_wide_first_bound(ctx):
     run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 1000)
     qluts[0, :, :] = 7                                  # every code has the same sum: ids decide
     run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts[:1], 100)
+
+
+# --------------------------------------------- 8x8 float scan, 8-bit lower bounds, 16 queries per pass
+# 512 queries and more (enough groups of 16 to fill the GPU) take the loop on 8-bit lower bounds; these
+# cases aim at what is specific to it: ragged last group, saturating entries, degenerate ranges, ties.
+def many_queries(r, nq, spread=50.0, offset=200.0):
+    return (r.random((nq, 8, 256)) * spread + r.random((nq, 8, 1)) * offset).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_000, 513, 1000)])
+def test_scan_f32_16_queries_per_pass_sizes(ctx, n, nq, topk):
+    r = np.random.default_rng(n + nq)
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    run_float_scan(ctx, codes, orc.CODES_U8, many_queries(r, nq), topk)
+
+
+def test_scan_f32_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
+    r = np.random.default_rng(23)
+    n, nq = 70_001, 515
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    # a huge dynamic range: most 8-bit entries saturate
+    luts_h = np.exp(r.random((nq, 8, 256)) * 30 - 10).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # a large common offset with a tiny spread: no fp32 resolution for a threshold (no pruning for those queries),
+    # mixed with ordinary queries in the same groups
+    luts_h = many_queries(r, nq)
+    luts_h[::3] = (1.0e7 + r.random((len(luts_h[::3]), 8, 256))).astype(np.float32)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+    # few distinct table values: exact sums, massive exact ties, unique (value, id) order
+    luts_h = r.integers(0, 3, (nq, 8, 256)).astype(np.float32)
+    d, i = ctx.pq_adc_scan_topk(dev(codes), binding.CODES_U8, dev(luts_h), 100)
+    od, oi = orc.adc_scan_topk_f32(codes, orc.CODES_U8, luts_h, 100)
+    assert np.array_equal(host(i), oi) and np.array_equal(host(d), od)
+    # every code is the per-table minimiser of query 0: its first bound leaves no range
+    luts_h = many_queries(r, nq)
+    same = np.tile(luts_h[0].argmin(axis=1).astype(np.uint8), (n, 1))
+    run_float_scan(ctx, same, orc.CODES_U8, luts_h, 100)
+    # the 16-bit loop for the same inputs (switch), as a cross-check of the switch itself
+    monkeypatch.setenv("PQ_SCAN_Q8", "0")
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
+
+
+def test_scan_f32_16_queries_per_pass_worst_case_order_and_duplicates(ctx):
+    r = np.random.default_rng(29)
+    n, nq = 80_000, 512
+    codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    luts_h = many_queries(r, nq)
+    d0 = orc.adc_all_f32(codes, orc.CODES_U8, luts_h[0])
+    worst = np.ascontiguousarray(codes[np.argsort(-d0, kind="stable")])    # far to near for query 0
+    worst[40_000:40_500] = worst[-500:]                                    # duplicates of the best codes
+    run_float_scan(ctx, worst, orc.CODES_U8, luts_h, 100)

@@ -66,6 +66,10 @@ struct TunedArgs {
     // result), and the minima of the pair's tables, from which the 16-bit entries are formed while
     // the item's tables are staged
     const float *pair_min;       // [npairs][tables]
+    // 16 queries per pass (8-bit tables in qtabs): the 16-bit tables of the same queries, [group][entry][table][2]
+    // (two 16-byte halves of 8 queries each), for the second test of the insert path, and their scale per query
+    const uint4 *qtabs16;
+    const float *prune_scale16;
 };
 
 static inline int env_int(const char *name, int dflt) {

@@ -59,15 +59,18 @@ constexpr int RING_FLUSH = 64;    // flush when more than this many positions ar
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
 
 // RING: ring entries per wave
-template <int RING>
+// WIDE16: room for a second set of tables (16-bit entries of 16 queries, 64 KB) beside the scan's own
+template <int RING, bool WIDE16 = false>
 struct __align__(16) TunedSmemT {
     uint4 lut[4096];
+    uint4 lut16[WIDE16 ? 4096 : 1];   // entry (byte b, table j): two 16-byte halves at (b * 8 + j) * 2
     uint8_t qstage[8][256];
     // Per wave: lanes that found a candidate park the position of their 16 code bytes here; the
     // positions are turned into list inserts in batches (scan_flush), which recomputes the values.
     uint32_t ring[TUNED_WAVES][RING];
     float prune_off[16];      // per slot: sum of the table minima, and the scale of the 16-bit tables
     float prune_scale[16];    // (0: no pruning for this slot, negative: nothing of this slot can qualify)
+    float prune_scale16[16];  // 16 queries per pass: scale of the 16-bit tables of the second test
     float pmin[8][16];       // inverted lists: minima of the slot's tables
     uint32_t eff_tmp[TUNED_WAVES][16];   // 16-query insert path: the float bounds of the batch being inserted
     WaveState ws[TUNED_WAVES];
@@ -123,7 +126,7 @@ constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the min
 // subtraction per word tests four of them), 64 units between the sum of the minima and the first bound (measured
 // optimum: fewer units blur the bound, more let codes with a few saturated entries through)
 constexpr float PRUNE_RANGE_Q8 = 64.f;
-constexpr int PRUNE_MARGIN_Q8 = 3;
+constexpr int PRUNE_MARGIN_Q8 = 2;   // a candidate's sum is at most floor(bound in units) up to fp32 rounding of that conversion
 constexpr float PRUNE_ENTRY_MAX_Q8 = 15.f;
 
 // What a lane needs to walk the tables in its own rotated order (see the layout note on top):
@@ -460,6 +463,41 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
                 if (ok[h] && q < nvalid && lb < thr) m |= 1u << (h * QB + q);
             }
         }
+        if constexpr (Q8) {
+            // Second test, 16 queries per pass only: the 8-bit bounds are coarse (64 units, entries saturating
+            // at 15), so most parked codes are no candidates.  The 16-bit tables of the same queries wait in
+            // LDS; the lanes that still have a bit set add up their eight entries (two 16-byte halves of 8
+            // queries each) and keep the bits whose 16-bit bound is below the 16-bit threshold.
+            const float sc16 = sm->prune_scale16[ql];
+            const float t16 = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sc16) + (float)PRUNE_MARGIN;
+            const uint32_t thr16_lane = sc16 > 0.f ? (uint32_t)fmaxf(fminf(t16, 32767.f), 0.f) : 32768u;   // no scale: every sum passes
+            uint32_t thr16_q[QB];
+#pragma unroll
+            for (int q = 0; q < QB; ++q) thr16_q[q] = __builtin_amdgcn_readlane(thr16_lane, q);
+            if (m != 0u) {
+                const __attribute__((address_space(3))) v4u *l16 = (const __attribute__((address_space(3))) v4u *)sm->lut16;
+                uint32_t m2 = 0;
+#pragma unroll
+                for (int h = 0; h < CPL; ++h) {
+                    if (((m >> (h * QB)) & 0xffffu) == 0u) continue;
+                    const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
+                    uint32_t a16[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t byte = ((j < 4 ? w0 : w1) >> (8 * (j & 3))) & 255u;
+                        const v4u lo = l16[(byte * 8 + j) * 2], hi = l16[(byte * 8 + j) * 2 + 1];
+                        a16[0] += lo.x; a16[1] += lo.y; a16[2] += lo.z; a16[3] += lo.w;
+                        a16[4] += hi.x; a16[5] += hi.y; a16[6] += hi.z; a16[7] += hi.w;
+                    }
+#pragma unroll
+                    for (int q = 0; q < QB; ++q) {
+                        const uint32_t lb16 = (a16[q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                        if (((m >> (h * QB + q)) & 1u) != 0u && lb16 < thr16_q[q]) m2 |= 1u << (h * QB + q);
+                    }
+                }
+                m = m2;
+            }
+        }
         // the float bounds as scalars (a lane read inside the divergent loop below would miss
         // the lanes that have already left it)
         uint32_t eff_q[Q8 ? 1 : QB];   // (with 16 queries the bounds wait in LDS instead)
@@ -692,7 +730,7 @@ void scan_tuned_kernel(TunedArgs a) {
     constexpr int CAP = 64 * E;
     typedef typename std::conditional<IS_U4, U32Val, F32Val>::type V;
     // ring: two tiles fit behind a ring that was not flushed
-    typedef TunedSmemT<RING_FLUSH + 64 * DEPTH> SM;   // a group of sub-tiles fits behind a ring that was not flushed
+    typedef TunedSmemT<RING_FLUSH + 64 * DEPTH, Q8> SM;   // a group of sub-tiles fits behind a ring that was not flushed
     __shared__ SM sm;
     LDS_PTR(SM) smp = (LDS_PTR(SM))&sm;
 
@@ -750,8 +788,10 @@ void scan_tuned_kernel(TunedArgs a) {
                     lut = IS_U4 ? (const void *)((const uint8_t *)a.luts + (size_t)gq * 256)
                                 : (const void *)((const float *)a.luts + (size_t)gq * (NT * 256));
                     if constexpr (PRUNED) { sm.prune_off[s] = a.prune_off[gq]; sm.prune_scale[s] = a.prune_scale[gq]; }
+                    if constexpr (Q8) sm.prune_scale16[s] = a.prune_scale16[gq];
                 } else if constexpr (PRUNED) {
                     sm.prune_off[s] = 0.f; sm.prune_scale[s] = 0.f;
+                    if constexpr (Q8) sm.prune_scale16[s] = 0.f;
                 }
                 out = a.partial + ((size_t)item * QB + s) * KPAD;
                 if (s == 0) {
@@ -814,6 +854,10 @@ void scan_tuned_kernel(TunedArgs a) {
                     } else {
                         sm.lut[e] = pk;   // (e >> 4) * 16 + (e & 15)
                     }
+                }
+                if constexpr (Q8) {   // the 16-bit tables of the second test, as prepared
+                    const uint4 *qt16 = a.qtabs16 + (size_t)sm.group * 4096;
+                    for (int e = threadIdx.x; e < 4096; e += TUNED_THREADS) sm.lut16[e] = qt16[e];
                 }
             }
         } else if constexpr (!IS_U4) {
@@ -1350,13 +1394,15 @@ __global__ void zero_u32_kernel(uint32_t *p, size_t n) {
 // of the group.
 template <int M, int G = 8>   // G: queries per group (8 with 16-bit entries, 16 with 8-bit entries)
 __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
-                                                           int nq, uint4 *qtabs, float *off_out, float *scale_out, float range_q8) {
+                                                           int nq, uint4 *qtabs, float *off_out, float *scale_out, float range_q8,
+                                                           uint4 *qtabs16, float *scale16_out) {
     constexpr bool Q8 = G == 16;
     constexpr float ENTRY_MAX = Q8 ? PRUNE_ENTRY_MAX_Q8 : (float)(32767 / M);   // M entries must add up to less than 2^15 (2^7)
     const float RANGE = Q8 ? range_q8 : PRUNE_RANGE;
     static_assert(!Q8 || M == 8, "8-bit entries: eight tables");
     __shared__ float smin[G][M];
     __shared__ float sscale[G];
+    __shared__ float sscale16[G];   // 8-bit entries: the scale of the 16-bit tables written beside them
     const int group = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int r = wave * (G * M / 4); r < (wave + 1) * (G * M / 4); ++r) {
         const int q = r / M, j = r % M, gq = group * G + q;
@@ -1383,6 +1429,17 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
             }
             off_out[gq] = off;
             scale_out[gq] = scale;
+            if constexpr (Q8) {
+                float scale16 = 0.f;
+                if (range > 0.f && range < 3.0e38f) {
+                    scale16 = PRUNE_RANGE / range;
+                    if (!(tau0[gq] * scale16 * 1e-6f < 1.f)) scale16 = 0.f;
+                }
+                scale16_out[gq] = scale16;
+                sscale16[tid] = scale16;
+            }
+        } else if (Q8) {
+            sscale16[tid] = 0.f;
         }
         sscale[tid] = scale;
     }
@@ -1407,6 +1464,21 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
             pk = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
         }
         qtabs[(size_t)group * (256 * M) + b * M + j] = pk;
+        if constexpr (Q8) {   // 16-bit entries of the same 16 queries, two halves of 8
+            uint32_t w[G];
+#pragma unroll
+            for (int q = 0; q < G; ++q) {
+                const int gq = group * G + q;
+                w[q] = 4095u;
+                if (gq < nq) {
+                    const float x = (luts[((size_t)gq * M + j) * 256 + b] - smin[q][j]) * sscale16[q];
+                    w[q] = (uint32_t)fminf(floorf(x), 4095.f);
+                }
+            }
+            uint4 *dst = qtabs16 + (size_t)group * 4096 + (size_t)(b * 8 + j) * 2;
+            dst[0] = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+            dst[1] = make_uint4(w[8] | (w[9] << 16), w[10] | (w[11] << 16), w[12] | (w[13] << 16), w[14] | (w[15] << 16));
+        }
     }
 }
 
@@ -1516,6 +1588,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float 
     a.item_tab = items; a.nitems_dev = nitems_dev; a.pairs_by_list = pairs_by_list; a.pair_out = pair_out;
     a.nprobe = nprobe;
     a.qtabs = nullptr; a.prune_off = pair_off; a.prune_scale = pair_scale; a.pair_min = pair_min;
+    a.qtabs16 = nullptr; a.prune_scale16 = nullptr;
     tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
                                                      0xff800000u, a.hist, L.nhist, tau0, nq, 1.f);
     PQ_HIP(ctx, hipGetLastError());
@@ -1594,7 +1667,10 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const bool wide_seed = prune && few_groups && tables == 8 && seed_codes_f32 > SEED_SLICE;
     const bool wide_seed_u4 = is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
     const size_t off_seedhist = prune ? off_qtabs + align_up((size_t)ngroups * 256 * tables * sizeof(uint4), 256) : off_tau0;
-    const size_t total = prune ? off_seedhist + (wide_seed ? (size_t)nq * HIST_BINS * 4 : 0)
+    // 16 queries per pass: the 16-bit tables of the second test (64 KB per group) and their scales
+    const size_t off_qtabs16 = off_seedhist + align_up(wide_seed ? (size_t)nq * HIST_BINS * 4 : 0, 256);
+    const size_t off_pscale16 = off_qtabs16 + (q8 ? (size_t)ngroups * 4096 * sizeof(uint4) : 0);
+    const size_t total = prune ? off_pscale16 + (q8 ? align_up((size_t)ntau * 4, 256) : 0)
                                : (wide_seed_u4 ? off_seedhist + (size_t)nq * 4096 * 4 : (seed_plain ? off_poff : off_tau0));
     rc = ws_reserve(ctx, total);
     if (rc) return rc;
@@ -1608,11 +1684,14 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     a.item_tab = nullptr; a.nitems_dev = nullptr; a.pairs_by_list = nullptr; a.pair_out = nullptr; a.nprobe = 0;
 
     a.qtabs = nullptr; a.prune_off = nullptr; a.prune_scale = nullptr; a.pair_min = nullptr;
+    a.qtabs16 = nullptr; a.prune_scale16 = nullptr;
     float *tau0 = nullptr;
     if (prune) {
         tau0 = (float *)(ws + off_tau0);
         float *poff = (float *)(ws + off_poff), *pscale = (float *)(ws + off_pscale);
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
+        uint4 *qtabs16 = q8 ? (uint4 *)(ws + off_qtabs16) : nullptr;
+        float *pscale16 = q8 ? (float *)(ws + off_pscale16) : nullptr;
         {
             // the first bound: smallest histogram edge with k distances among the first codes
             // (a reference for the histogram bins is all the wide pass needs from this one)
@@ -1629,11 +1708,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
-        if (q8) prune_tables_kernel<8, 16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, (float)env_int("PQ_Q8_RANGE", (int)PRUNE_RANGE_Q8));
-        else if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f);
-        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f);
+        if (q8) prune_tables_kernel<8, 16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
+        else if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
+        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
         PQ_HIP(ctx, hipGetLastError());
-        a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale;
+        a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale; a.qtabs16 = qtabs16; a.prune_scale16 = pscale16;
     } else if (seed_plain) {
         tau0 = (float *)(ws + off_tau0);
         rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, cb, 256, PRUNE_INIT, topk, tau0);

@@ -591,7 +591,8 @@ def many_queries(r, nq, spread=50.0, offset=200.0):
     return (r.random((nq, 8, 256)) * spread + r.random((nq, 8, 1)) * offset).astype(np.float32)
 
 
-@pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_000, 513, 1000)])
+@pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_000, 513, 1000),
+                                       (75_001, 530, 129), (100_003, 512, 512)])
 def test_scan_f32_16_queries_per_pass_sizes(ctx, n, nq, topk):
     r = np.random.default_rng(n + nq)
     codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
@@ -633,3 +634,57 @@ def test_scan_f32_16_queries_per_pass_worst_case_order_and_duplicates(ctx):
     worst = np.ascontiguousarray(codes[np.argsort(-d0, kind="stable")])    # far to near for query 0
     worst[40_000:40_500] = worst[-500:]                                    # duplicates of the best codes
     run_float_scan(ctx, worst, orc.CODES_U8, luts_h, 100)
+
+
+# ------------------------------------------------- integer scan of many queries (8-bit lower bounds, 16 per pass)
+def quantized_like_tables(r, nq):
+    """u8 tables shaped like quantised distance tables: a spread of small values per component and a few
+    saturated entries."""
+    base = r.integers(0, 40, (nq, 16, 1))
+    t = base + (r.random((nq, 16, 16)) ** 2 * 60).astype(np.int64)
+    t[r.random((nq, 16, 16)) < 0.05] = 255
+    return np.clip(t, 0, 255).astype(np.uint8)
+
+
+@pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_001, 513, 1000),
+                                       (75_001, 530, 129), (100_003, 512, 512)])
+def test_scan_u4_16_queries_per_pass_sizes(ctx, n, nq, topk):
+    r = np.random.default_rng(n + nq)
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, quantized_like_tables(r, nq), topk)
+
+
+def test_scan_u4_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
+    r = np.random.default_rng(31)
+    n, nq = 70_001, 515
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    # uniform bytes: wide sums, the 8-bit entries saturate for most codes
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, r.integers(0, 256, (nq, 16, 16), dtype=np.uint8), 100)
+    # sums in 0..48 (thousands of ties at the bound), constant tables (no range at all), all 255, all 0
+    qluts = r.integers(0, 4, (nq, 16, 16), dtype=np.uint8)
+    qluts[1] = 255
+    qluts[2] = 0
+    qluts[3] = 7
+    qluts[20:40] = quantized_like_tables(r, 20)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 100)
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 400)
+    # every code is the minimiser of query 0: its first bound equals the sum of the minima
+    qluts = quantized_like_tables(r, nq)
+    best = qluts[0].argmin(axis=1)
+    same = np.tile((best[0::2] | (best[1::2] << 4)).astype(np.uint8), (n, 1))
+    run_int_scan(ctx, same, orc.CODES_U4_PACKED, qluts, 100)
+    # the 16-bit loop for the same inputs (switch)
+    monkeypatch.setenv("PQ_SCAN_Q8", "0")
+    run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 100)
+
+
+def test_scan_u4_16_queries_per_pass_worst_case_order_and_duplicates(ctx):
+    r = np.random.default_rng(37)
+    n, nq = 80_000, 512
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = quantized_like_tables(r, nq)
+    d0 = orc.adc_all_u8(packed, orc.CODES_U4_PACKED, qluts[0]).astype(np.int64)
+    worst = np.ascontiguousarray(packed[np.argsort(-d0, kind="stable")])   # far to near for query 0
+    worst[40_000:40_500] = worst[-500:]                                    # duplicates of the best codes
+    run_int_scan(ctx, worst, orc.CODES_U4_PACKED, qluts, 100)
+    run_int_scan(ctx, worst, orc.CODES_U4_PACKED, qluts, 500)

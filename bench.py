@@ -141,9 +141,12 @@ def main():
                                "fp32 LUTs 8x256 built each step, top-%d" % (args.n, args.nq, args.topk)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("scan_f32_pq8x8_config1_pmc.txt"),
-                     "kernel": "scan_tuned_kernel<F32P_M8 (8x8 float, lower-bound pruning), lists for top<=128, groups of 2 sub-tiles>", "kernel_ms": scan_ms,
+                     "kernel": ("scan_tuned_kernel<F32Q_M8 (8x8 float, 8-bit lower bounds, 16 queries per pass), lists for top<=%d, groups of 2 sub-tiles>"
+                                if args.nq >= 512 and args.topk <= 512 else
+                                "scan_tuned_kernel<F32P_M8 (8x8 float, 16-bit lower bounds, 8 queries per pass), lists for top<=%d>")
+                               % (128 if args.topk <= 128 else 1024), "kernel_ms": scan_ms,
                      "algorithmic_bytes": alg_bytes,
-                     "note": "algorithmic bytes = 8 B per code per query pass; one pass over a chunk serves 8 queries and "
+                     "note": "algorithmic bytes = 8 B per code per query pass; one pass over a chunk serves 8 or 16 queries and "
                              "concurrent blocks share chunks through L2, so the HBM bytes really moved (traffic) are far below "
                              "the algorithmic figure and frac exceeds 1; the kernel is bound by LDS reads and vector issue"},
     }
@@ -177,7 +180,8 @@ def main():
                             "dtype": "u8 tables, integer sums", "workload": "PQ 16x4 packed codes (BASELINE config 2): "
                             "tables, qmax pre-scan, 8-bit tables, integer scan top-%d, fp32 rerank top-%d" % (args.cand, args.topk),
                             "roofline": {"bound": "hbm", "achieved": ach16, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": "scan_tuned_kernel<U4_M16, lists for top<=%d>" % (128 if args.cand <= 128 else 1024), "kernel_ms": scan16_ms,
+                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": ("scan_tuned_kernel<U4Q_M16 (8-bit lower bounds, 16 queries per pass), lists for top<=%d>" if args.nq >= 512 and args.cand <= 512
+                                                    else "scan_tuned_kernel<U4_M16, lists for top<=%d>") % (128 if args.cand <= 128 else 1024), "kernel_ms": scan16_ms,
                                          "traffic": read_traffic("scan_u4_pq16x4_config2_pmc.txt")}}
         del codes4
 

@@ -281,7 +281,7 @@ __device__ __noinline__ int scan_compact(LDS_PTR(SM) sm, uint64_t *buf, int cnt,
 // counts them in the query's histogram.  Before a batch, a list that the batch could overflow
 // is cut to its k smallest keys.
 template <class SM, int KIND, int E>
-__device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
+__device__ __noinline__ int scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
     constexpr bool IS_U4 = KIND == KIND_U4_M16;
     constexpr int QB = IS_U4 ? 8 : 4;
     constexpr int NT = KIND == KIND_F32_M16 ? 16 : 8;
@@ -296,6 +296,7 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const __attribute__((address_space(3))) char *lut_bytes = (const __attribute__((address_space(3))) char *)sm->lut;
     const int ql = lane & (QB - 1);
+    int appended = 0;   // keys added to the wave's lists (returned)
     for (int base = 0; base < n; base += 64) {
         // room for 64 * CPL more keys in every list
         uint32_t full = (uint32_t)__ballot(ws->cnt[ql] > CAP - 64 * CPL) & ((1u << QB) - 1u);
@@ -384,9 +385,62 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
         for (int q = 0; q < QB; ++q) {
             int added = __popcll(__ballot((m >> q) & 1u));
             if (CPL == 2) added += __popcll(__ballot((m >> (QB + q)) & 1u));
+            appended += added;
             if (added != 0 && lane == 0)
                 __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
+    }
+    return appended;
+}
+
+// Sixteen "not below the bound" flags of sixteen queries at once.
+// 8-bit sums (four per word, below 0x80) against 8-bit bounds of at most 0x7f: `comp` holds 0x80 - bound in every byte,
+// so sum + comp has bit 7 set iff the sum is not below its bound, and no byte carries.  The set bits 7 of four words are
+// gathered into bits 0 .. 15 by byte-wise dot products with powers of two (every byte is 0x80 or 0: 128 x the flags).
+__device__ __forceinline__ uint32_t fail_flags_8bit(const uint32_t (&sums)[4], const uint32_t (&comp)[4]) {
+    uint32_t lo = __builtin_amdgcn_udot4((sums[0] + comp[0]) & 0x80808080u, 0x08040201u, 0u, false);
+    lo = __builtin_amdgcn_udot4((sums[1] + comp[1]) & 0x80808080u, 0x80402010u, lo, false);
+    uint32_t hi = __builtin_amdgcn_udot4((sums[2] + comp[2]) & 0x80808080u, 0x08040201u, 0u, false);
+    hi = __builtin_amdgcn_udot4((sums[3] + comp[3]) & 0x80808080u, 0x80402010u, hi, false);
+    return (lo >> 7) | ((hi >> 7) << 8);
+}
+// 16-bit sums (two per word, below 0x8000) against 16-bit bounds of at most 0x8000: `comp` holds 0x8000 - bound in
+// both halves; bits 15 and 31 of sum + comp are the flags.
+__device__ __forceinline__ uint32_t fail_flags_16bit(const uint32_t (&sums)[8], const uint32_t (&comp)[8]) {
+    uint32_t lo = 0, hi = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t weights = (1u << (8 + 2 * w)) | (1u << (24 + 2 * w + 1));   // byte 1: query 2w, byte 3: query 2w + 1
+        lo = __builtin_amdgcn_udot4((sums[w] + comp[w]) & 0x80008000u, weights, lo, false);
+        hi = __builtin_amdgcn_udot4((sums[4 + w] + comp[4 + w]) & 0x80008000u, weights, hi, false);
+    }
+    return (lo >> 7) | ((hi >> 7) << 8);
+}
+
+// Sums of the eight 16-bit entries of one 8-byte code (words w0, w1) for 16 queries from the tables at `l16`
+// (entry (byte b, table j): two 16-byte halves of 8 queries at (b * 8 + j) * 2), two queries per word of a16.
+// Every lane of a wave looks up other byte values, so the lanes walk the tables in a rotated order (lane l starts
+// at table l & 7; lanes 8..15 of every 16 read the halves in the other order): the 16 lanes that the LDS serves
+// together then read 16 different 16-byte bank groups whatever their bytes are.  Integer adds: any order, same sums.
+typedef uint32_t lds_v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void sums16_rotated(const __attribute__((address_space(3))) lds_v4u *l16, uint32_t w0, uint32_t w1,
+                                               int lane, uint32_t (&a16)[8]) {
+    const uint64_t w = ((uint64_t)w1 << 32) | w0;
+    const uint32_t rot = (uint32_t)lane & 7u, other = ((uint32_t)lane >> 3) & 1u;
+    uint32_t fa[4] = {0, 0, 0, 0}, fb[4] = {0, 0, 0, 0};   // first and second half read by this lane
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t jj = ((uint32_t)j + rot) & 7u;
+        const uint32_t byte = (uint32_t)(w >> (8u * jj)) & 255u;
+        const uint32_t e = (byte * 8u + jj) * 2u;
+        const lds_v4u x = l16[e + other], y = l16[e + (other ^ 1u)];
+        fa[0] += x.x; fa[1] += x.y; fa[2] += x.z; fa[3] += x.w;
+        fb[0] += y.x; fb[1] += y.y; fb[2] += y.z; fb[3] += y.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        a16[i] = other ? fb[i] : fa[i];
+        a16[4 + i] = other ? fa[i] : fb[i];
     }
 }
 
@@ -401,7 +455,7 @@ __device__ __noinline__ void scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int 
 // the eight float entries in table order -- the order of the plain definition, Eq. (adc1) -- tests the
 // result against the float bound and appends it to the wave's list of the query.
 template <class SM, int NT, int E, int QB = 8>
-__device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
+__device__ __noinline__ int scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
     constexpr int CPL = 16 / NT, CAP = 64 * E;
     constexpr bool Q8 = QB == 16;   // 8-bit entries, 16 queries per slot
     const int lane = lane_id(), wave = threadIdx.x >> 6;
@@ -412,6 +466,7 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const __attribute__((address_space(3))) char *lut_bytes = (const __attribute__((address_space(3))) char *)sm->lut;
     const int ql = lane & (QB - 1);
+    int appended = 0;   // keys added to the wave's lists (returned)
     for (int base = 0; base < n; base += 64) {
         // room for 64 * CPL more keys in every list
         uint32_t full = (uint32_t)__ballot(ws->cnt[ql] > CAP - 64 * CPL) & ((1u << QB) - 1u);
@@ -456,13 +511,26 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
         }
         // bit h * QB + q of m: the lower bound of code h does not rule out query q
         uint32_t m = 0;
+        if constexpr (Q8) {
+            // all 16 queries of a code at once (bounds of empty slots are 0: never below)
+            const uint32_t thr_valid = ql < nvalid ? thr_lane : 0u;
+            uint32_t comp[4];
 #pragma unroll
-        for (int q = 0; q < QB; ++q) {
-            const uint32_t thr = __builtin_amdgcn_readlane(thr_lane, q);
+            for (int p = 0; p < 4; ++p)
+                comp[p] = 0x80808080u - (__builtin_amdgcn_readlane(thr_valid, 4 * p) | (__builtin_amdgcn_readlane(thr_valid, 4 * p + 1) << 8) |
+                                         (__builtin_amdgcn_readlane(thr_valid, 4 * p + 2) << 16) | (__builtin_amdgcn_readlane(thr_valid, 4 * p + 3) << 24));
 #pragma unroll
-            for (int h = 0; h < CPL; ++h) {
-                const uint32_t lb = Q8 ? (acc[h][q >> 2] >> (8 * (q & 3))) & 0xffu : (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                if (ok[h] && q < nvalid && lb < thr) m |= 1u << (h * QB + q);
+            for (int h = 0; h < CPL; ++h)
+                if (ok[h]) m |= (~fail_flags_8bit(acc[h], comp) & 0xffffu) << (h * QB);
+        } else {
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                const uint32_t thr = __builtin_amdgcn_readlane(thr_lane, q);
+#pragma unroll
+                for (int h = 0; h < CPL; ++h) {
+                    const uint32_t lb = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
+                    if (ok[h] && q < nvalid && lb < thr) m |= 1u << (h * QB + q);
+                }
             }
         }
         if constexpr (Q8) {
@@ -473,9 +541,10 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
             const float sc16 = sm->prune_scale16[ql];
             const float t16 = floorf((ord_to_f32(eff_lane) - sm->prune_off[ql]) * sc16) + (float)PRUNE_MARGIN;
             const uint32_t thr16_lane = sc16 > 0.f ? (uint32_t)fmaxf(fminf(t16, 32767.f), 0.f) : 32768u;   // no scale: every sum passes
-            uint32_t thr16_q[QB];
+            uint32_t comp16[8];   // 0x8000 - bound of queries 2w and 2w + 1
 #pragma unroll
-            for (int q = 0; q < QB; ++q) thr16_q[q] = __builtin_amdgcn_readlane(thr16_lane, q);
+            for (int w = 0; w < 8; ++w)
+                comp16[w] = 0x80008000u - (__builtin_amdgcn_readlane(thr16_lane, 2 * w) | (__builtin_amdgcn_readlane(thr16_lane, 2 * w + 1) << 16));
             if (m != 0u) {
                 const __attribute__((address_space(3))) v4u *l16 = (const __attribute__((address_space(3))) v4u *)sm->lut16;
                 uint32_t m2 = 0;
@@ -483,19 +552,9 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
                 for (int h = 0; h < CPL; ++h) {
                     if (((m >> (h * QB)) & 0xffffu) == 0u) continue;
                     const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
-                    uint32_t a16[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const uint32_t byte = ((j < 4 ? w0 : w1) >> (8 * (j & 3))) & 255u;
-                        const v4u lo = l16[(byte * 8 + j) * 2], hi = l16[(byte * 8 + j) * 2 + 1];
-                        a16[0] += lo.x; a16[1] += lo.y; a16[2] += lo.z; a16[3] += lo.w;
-                        a16[4] += hi.x; a16[5] += hi.y; a16[6] += hi.z; a16[7] += hi.w;
-                    }
-#pragma unroll
-                    for (int q = 0; q < QB; ++q) {
-                        const uint32_t lb16 = (a16[q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                        if (((m >> (h * QB + q)) & 1u) != 0u && lb16 < thr16_q[q]) m2 |= 1u << (h * QB + q);
-                    }
+                    uint32_t a16[8];
+                    sums16_rotated(l16, w0, w1, lane, a16);
+                    m2 |= m & ((~fail_flags_16bit(a16, comp16) & 0xffffu) << (h * QB));
                 }
                 m = m2;
             }
@@ -553,14 +612,17 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
                 }
             }
         }
+        if (__ballot(inserted != 0u) == 0ull) continue;   // (the usual case with 8-bit bounds: nothing got through)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             int added = __popcll(__ballot((inserted >> q) & 1u));
             if (CPL == 2) added += __popcll(__ballot((inserted >> (QB + q)) & 1u));
+            appended += added;
             if (added != 0 && lane == 0)
                 __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
+    return appended;
 }
 
 // Insert path of the integer scan on 8-bit lower bounds (16 queries per pass, KIND_U4Q_M16): the exact
@@ -568,7 +630,7 @@ __device__ __noinline__ void scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_bu
 // up the eight exact entries of each of its codes (two 16-byte halves of 8 queries per lookup) and
 // appends the sums below a query's bound to the wave's list of that query.  Sums are exact integers.
 template <class SM, int E>
-__device__ __noinline__ void scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
+__device__ __noinline__ int scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, int n) {
     constexpr int QB = 16, CPL = 2, CAP = 64 * E;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     LdsWaveState *ws = &sm->ws[wave];
@@ -578,6 +640,7 @@ __device__ __noinline__ void scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, 
     typedef uint32_t v4u __attribute__((ext_vector_type(4)));
     const __attribute__((address_space(3))) v4u *l16 = (const __attribute__((address_space(3))) v4u *)sm->lut16;
     const int ql = lane & (QB - 1);
+    int appended = 0;   // keys added to the wave's lists (returned)
     for (int base = 0; base < n; base += 64) {
         // room for 64 * CPL more keys in every list
         uint32_t full = (uint32_t)__ballot(ws->cnt[ql] > CAP - 64 * CPL) & ((1u << QB) - 1u);
@@ -604,15 +667,7 @@ __device__ __noinline__ void scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, 
 #pragma unroll
         for (int h = 0; h < CPL; ++h) {
             const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[h][i] = 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t byte = ((j < 4 ? w0 : w1) >> (8 * (j & 3))) & 255u;
-                const v4u lo = l16[(byte * 8 + j) * 2], hi = l16[(byte * 8 + j) * 2 + 1];
-                acc[h][0] += lo.x; acc[h][1] += lo.y; acc[h][2] += lo.z; acc[h][3] += lo.w;
-                acc[h][4] += hi.x; acc[h][5] += hi.y; acc[h][6] += hi.z; acc[h][7] += hi.w;
-            }
+            sums16_rotated(l16, w0, w1, lane, acc[h]);
         }
         bool ok[CPL];
 #pragma unroll
@@ -625,16 +680,20 @@ __device__ __noinline__ void scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, 
             const uint32_t own = ws->own_ord[ql];
             eff_lane = own < loose ? own : loose;
         }
-        uint32_t m = 0;   // bit h * QB + q: code h of this lane qualifies for query q
+        // bit h * QB + q of m: code h of this lane qualifies for query q (all 16 queries of a code at once; the bounds
+        // are at most 0x7fff, those of empty slots 0: never below)
+        uint32_t m = 0;
+        {
+            const uint32_t eff_valid = ql < nvalid ? eff_lane : 0u;
+            uint32_t comp16[8];
 #pragma unroll
-        for (int q = 0; q < QB; ++q) {
-            const uint32_t eff = __builtin_amdgcn_readlane(eff_lane, q);
+            for (int w = 0; w < 8; ++w)
+                comp16[w] = 0x80008000u - (__builtin_amdgcn_readlane(eff_valid, 2 * w) | (__builtin_amdgcn_readlane(eff_valid, 2 * w + 1) << 16));
 #pragma unroll
-            for (int h = 0; h < CPL; ++h) {
-                const uint32_t ord = (acc[h][q >> 1] >> (16 * (q & 1))) & 0xffffu;
-                if (ok[h] && q < nvalid && ord < eff) m |= 1u << (h * QB + q);
-            }
+            for (int h = 0; h < CPL; ++h)
+                if (ok[h]) m |= (~fail_flags_16bit(acc[h], comp16) & 0xffffu) << (h * QB);
         }
+        if (__ballot(m != 0u) == 0ull) continue;
         uint32_t bits = m;
         while (bits != 0u) {
             const int b = __builtin_ctz(bits);
@@ -651,10 +710,12 @@ __device__ __noinline__ void scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, 
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             const int added = __popcll(__ballot((m >> q) & 1u)) + __popcll(__ballot((m >> (QB + q)) & 1u));
+            appended += added;
             if (added != 0 && lane == 0)
                 __hip_atomic_fetch_add(&sm->ncand_blk[q], (uint32_t)added, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
     }
+    return appended;
 }
 
 // Periodic path (one wave per query and period): pick up the best bound published for query q
@@ -1097,9 +1158,9 @@ void scan_tuned_kernel(TunedArgs a) {
             }
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
-                if constexpr (Q8)
-                    tau[p] = __builtin_amdgcn_readlane(eff, 4 * p) | (__builtin_amdgcn_readlane(eff, 4 * p + 1) << 8) |
-                             (__builtin_amdgcn_readlane(eff, 4 * p + 2) << 16) | (__builtin_amdgcn_readlane(eff, 4 * p + 3) << 24);
+                if constexpr (Q8)   // 0x80 minus the threshold in every byte (thresholds are at most 127): see the test
+                    tau[p] = 0x80808080u - (__builtin_amdgcn_readlane(eff, 4 * p) | (__builtin_amdgcn_readlane(eff, 4 * p + 1) << 8) |
+                                            (__builtin_amdgcn_readlane(eff, 4 * p + 2) << 16) | (__builtin_amdgcn_readlane(eff, 4 * p + 3) << 24));
                 else if constexpr (PACKED)
                     tau[p] = __builtin_amdgcn_readlane(eff, 2 * p) | (__builtin_amdgcn_readlane(eff, 2 * p + 1) << 16);
                 else
@@ -1143,13 +1204,13 @@ void scan_tuned_kernel(TunedArgs a) {
             code_values<NT, PACKED, DEPTH == 2 ? 16 : 8>(cur, lw, [&](uint32_t off) { return *reinterpret_cast<const uint4 *>(lut_bytes + off); }, d);
             uint64_t hit = 0;
             if constexpr (Q8) {
-                // 8-bit fields below 0x80 (sums and thresholds): (0x80 | sum) - threshold keeps bit 7 iff the
-                // sum is not below the threshold, and no field borrows from its neighbour
+                // 8-bit fields below 0x80 (sums and thresholds): sum + (0x80 - threshold) has bit 7 set iff the sum
+                // is not below the threshold; every field stays within 1 .. 255, so none carries into its neighbour
                 uint32_t keep = 0x80808080u;
 #pragma unroll
                 for (int h = 0; h < CPL; ++h)
 #pragma unroll
-                    for (int pp = 0; pp < 4; ++pp) keep &= (d[h][pp] | 0x80808080u) - tau[pp];
+                    for (int pp = 0; pp < 4; ++pp) keep &= d[h][pp] + tau[pp];
                 hit = __ballot(keep != 0x80808080u);
             } else if constexpr (PACKED) {
                 // 16-bit fields below 0x8000: the smaller of the lane's two sums minus the threshold
@@ -1180,16 +1241,18 @@ void scan_tuned_kernel(TunedArgs a) {
         // per query re-evaluates the query's histogram now and then, thresholds are re-read.
         // Every wave takes its turn at refreshing one query from the device state: the 16 / QB waves
         // that share a query alternate, so that each query is looked at every 32 steps of the block
-        // and no wave carries more of this work than another.
+        // and no wave carries more of this work than another (with 16 queries per pass, one wave per
+        // query, every 128 steps: a look costs a device round trip, and a wave whose bound is stale
+        // finds keys and asks earlier, see `pressure`).
         const int my_q = wave % QB;
-        const int my_phase = QB > 8 ? 1 + 2 * my_q : 1 + 4 * my_q + 32 * (wave / QB);
-        constexpr int REFRESH_MASK = QB > 8 ? 31 : 32 * (TUNED_WAVES / QB) - 1;
+        const int my_phase = QB > 8 ? 1 + 8 * my_q : 1 + 4 * my_q + 32 * (wave / QB);
+        constexpr int REFRESH_MASK = QB > 8 ? 127 : 32 * (TUNED_WAVES / QB) - 1;
         const bool refresher = my_q < nvalid_q;
         // Items that start without a useful bound: no bound at all, or (long result lists) the first
         // item of a block, which only has the loose bound the launch was seeded with.
         const bool cold_item = sm.tau_blk[my_q] >= V::ord_inf() || (KPAD > 128 && a.item_tab == nullptr && gstep == 0);
         int step = 0;
-        int pressure = 0;   // positions this wave has flushed since it last refreshed a bound
+        int pressure = 0;   // positions this wave has flushed (8-bit bounds: keys it has added) since it last refreshed a bound
         auto flush_due = [&]() { return ring_cnt > RING_FLUSH || (ring_cnt > 0 && (step & (RING_PERIOD / 2 - 1)) == 0); };
         // in cold items: at steps 1, 2, 4 .. 32 as well
         auto refresh_due = [&]() {
@@ -1199,10 +1262,12 @@ void scan_tuned_kernel(TunedArgs a) {
         auto between_steps = [&]() {
             bool changed = false;
             if (flush_due()) {
-                if constexpr (PRUNED) scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
-                else if constexpr (U4Q) scan_flush_u4q<SM, E>(smp, wave_buf, ring_cnt);
-                else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
-                pressure += ring_cnt;
+                int appended;
+                if constexpr (PRUNED) appended = scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
+                else if constexpr (U4Q) appended = scan_flush_u4q<SM, E>(smp, wave_buf, ring_cnt);
+                else appended = scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
+                // 8-bit bounds park many codes that turn out to be none: there only the keys count
+                pressure += Q8 ? appended : ring_cnt;
                 ring_cnt = 0;
                 changed = true;
             }

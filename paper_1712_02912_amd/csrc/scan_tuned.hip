@@ -129,7 +129,6 @@ constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the min
 constexpr float PRUNE_RANGE_Q8 = 64.f;
 constexpr int PRUNE_MARGIN_Q8 = 2;   // a candidate's sum is at most floor(bound in units) up to fp32 rounding of that conversion
 constexpr float PRUNE_ENTRY_MAX_Q8 = 15.f;
-constexpr int Q8_MAX_TOPK = 512;     // longer result lists go through the loops on 16-bit entries
 
 // What a lane needs to walk the tables in its own rotated order (see the layout note on top):
 // derived from the low four bits of the lane that holds the code bytes.
@@ -1854,9 +1853,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int tables = kind == KIND_F32_M16 ? 16 : 8;
     // eight tables and enough queries to fill the GPU with groups of 16: 8-bit lower bounds, 16 queries per pass
     // (PQ_SCAN_Q8=0: 16-bit lower bounds, 8 queries per pass, as for fewer queries)
-    // Longer result lists take more candidates, and the 8-bit bounds let more codes through to the insert path
-    // than the 16-bit ones: measured on 25 M codes and 1000 queries, the 16-query loops win up to about 600 results.
-    const bool many16 = (nq + 15) / 16 >= STREAM_GROUPS && topk <= Q8_MAX_TOPK && env_int("PQ_SCAN_Q8", 1) != 0;
+    const bool many16 = (nq + 15) / 16 >= STREAM_GROUPS && env_int("PQ_SCAN_Q8", 1) != 0;
     const bool q8 = prune && tables == 8 && many16;
     if (prune) kind = q8 ? KIND_F32Q_M8 : (tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8);
     // the integer scan likewise: with a first bound and enough queries, its loop runs on 8-bit lower bounds of

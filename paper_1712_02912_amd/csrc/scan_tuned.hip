@@ -127,6 +127,7 @@ constexpr float PRUNE_RANGE = 3500.f;  // table units between the sum of the min
 // subtraction per word tests four of them), 64 units between the sum of the minima and the first bound (measured
 // optimum: fewer units blur the bound, more let codes with a few saturated entries through)
 constexpr float PRUNE_RANGE_Q8 = 64.f;
+constexpr float PRUNE_RANGE_U4Q = 48.f;   // the same for the integer scan (measured: 40 .. 56 within 2 % of one another, 64: +4 .. 8 %, 32: +6 .. 16 %)
 constexpr int PRUNE_MARGIN_Q8 = 2;   // a candidate's sum is at most floor(bound in units) up to fp32 rounding of that conversion
 constexpr float PRUNE_ENTRY_MAX_Q8 = 15.f;
 
@@ -1066,7 +1067,7 @@ void scan_tuned_kernel(TunedArgs a) {
                 // sums at or below the bound the item starts with are what must get through
                 const uint32_t bound = sm.tau_blk[q];
                 float scale = 0.f;   // no bound yet: every entry 0, every sum passes
-                if (sm.slot_lut[q] != nullptr && bound < 0x7fffu && bound >= off) scale = PRUNE_RANGE_Q8 / (float)(bound - off + 1u);
+                if (sm.slot_lut[q] != nullptr && bound < 0x7fffu && bound >= off) scale = PRUNE_RANGE_U4Q / (float)(bound - off + 1u);
                 sm.prune_off[q] = (float)off;
                 sm.prune_scale[q] = scale;
             }

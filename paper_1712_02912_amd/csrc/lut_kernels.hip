@@ -270,28 +270,50 @@ int launch_quantize_luts(pq_ctx *ctx, const float *luts, int nq, int m, int k, c
 // ------------------------------------------------------------------------------------------
 // Float ADC of one stored code with one query's tables (global memory), Eq. (adc1).
 __device__ __forceinline__ float adc_one(const uint8_t *code, int cf, const float *lut, int m, int k) {
+    const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
+    // codes of 8 or 16 bytes (every configured shape) aligned to their size come in one load
+    uint32_t w[4] = {0, 0, 0, 0};
+    const bool words = (cb == 8 || cb == 16) && ((uintptr_t)code & (uintptr_t)(cb - 1)) == 0;
+    if (words && cb == 8) {
+        const uint2 c = *reinterpret_cast<const uint2 *>(code);
+        w[0] = c.x; w[1] = c.y;
+    } else if (words) {
+        const uint4 c = *reinterpret_cast<const uint4 *>(code);
+        w[0] = c.x; w[1] = c.y; w[2] = c.z; w[3] = c.w;
+    }
     float dist = 0.f;
     for (int j = 0; j < m; ++j) {
+        const int pos = cf == PQ_CODES_U4_PACKED ? j >> 1 : j;
+        const uint32_t byte = words ? (w[(pos >> 2) & 3] >> (8 * (pos & 3))) & 255u : code[pos];
         int idx;
-        if (cf == PQ_CODES_U4_PACKED) {
-            const uint32_t byte = code[j >> 1];
-            idx = (j & 1) ? (byte >> 4) : (byte & 15u);
-        } else {
-            idx = code[j];
-        }
+        if (cf == PQ_CODES_U4_PACKED) idx = (j & 1) ? (byte >> 4) : (byte & 15u);
+        else idx = byte;
         if (idx < k) dist += lut[(size_t)j * k + idx];
     }
     return dist;
+}
+
+// The query's tables copied behind the sort keys in LDS when they fit there (`staged` = their number of floats, else
+// 0): every code then looks its m entries up in LDS instead of device memory.  Returns the tables to use.
+__device__ __forceinline__ const float *stage_tables(const float *lut, float *lds, int staged) {
+    if (staged == 0) return lut;
+    for (int i = threadIdx.x; i < staged; i += blockDim.x) lds[i] = lut[i];
+    __syncthreads();
+    return lds;
+}
+// dynamic LDS of the two kernels below: n2 sort keys and, if both fit into 48 KB, the query's tables
+static inline int staged_floats(int n2, int m, int k) {
+    return (size_t)n2 * 8 + (size_t)m * k * 4 <= 48 * 1024 ? m * k : 0;
 }
 
 // One block per query: distances of the first `cnt` codes (cnt <= 4096) into LDS keys,
 // bitonic sort, take the kq-th.
 __global__ __launch_bounds__(256) void qmax_prescan_kernel(const uint8_t *__restrict__ codes, int cnt, int cb,
                                                            int cf, const float *__restrict__ luts, int m, int k,
-                                                           int kq, int n2, float *qmax_out) {
+                                                           int kq, int n2, int staged, float *qmax_out) {
     extern __shared__ uint64_t skeys[];
     const int q = blockIdx.x;
-    const float *lut = luts + (size_t)q * m * k;
+    const float *lut = stage_tables(luts + (size_t)q * m * k, reinterpret_cast<float *>(skeys + n2), staged);
     for (int i = threadIdx.x; i < n2; i += 256) {
         uint64_t key = KEY_EMPTY;
         if (i < cnt) key = ((uint64_t)f32_to_ord(adc_one(codes + (size_t)i * cb, cf, lut, m, k)) << 32) | (uint32_t)i;
@@ -308,7 +330,8 @@ int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, co
     int n2 = 64;
     while (n2 < cnt) n2 <<= 1;
     const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
-    qmax_prescan_kernel<<<nq, 256, (size_t)n2 * 8, ctx->stream>>>(codes, cnt, cb, cf, luts, m, k, kq, n2, qmax_out);
+    const int staged = staged_floats(n2, m, k);
+    qmax_prescan_kernel<<<nq, 256, (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, cnt, cb, cf, luts, m, k, kq, n2, staged, qmax_out);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }
@@ -316,11 +339,11 @@ int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, co
 // One block per query: float ADC of the candidates, sort by (distance, id), write topk.
 __global__ __launch_bounds__(256) void rerank_kernel(const uint8_t *__restrict__ codes, int64_t n, int cb, int cf,
                                                      const float *__restrict__ luts, int m, int k,
-                                                     const int64_t *__restrict__ cand, int ncand, int n2, int topk,
+                                                     const int64_t *__restrict__ cand, int ncand, int n2, int topk, int staged,
                                                      float *out_dist, int64_t *out_ids) {
     extern __shared__ uint64_t skeys[];
     const int q = blockIdx.x;
-    const float *lut = luts + (size_t)q * m * k;
+    const float *lut = stage_tables(luts + (size_t)q * m * k, reinterpret_cast<float *>(skeys + n2), staged);
     for (int i = threadIdx.x; i < n2; i += 256) {
         uint64_t key = KEY_EMPTY;
         if (i < ncand) {
@@ -345,8 +368,9 @@ int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const fl
     while (n2 < ncand) n2 <<= 1;
     const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
     if (nq == 0) return PQ_OK;
-    rerank_kernel<<<nq, 256, (size_t)n2 * 8, ctx->stream>>>(codes, n, cb, cf, luts, m, k, cand, ncand, n2, topk,
-                                                             out_dist, out_ids);
+    const int staged = staged_floats(n2, m, k);
+    rerank_kernel<<<nq, 256, (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, n, cb, cf, luts, m, k, cand, ncand, n2, topk,
+                                                                                   staged, out_dist, out_ids);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }

@@ -1392,43 +1392,88 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
     for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
 }
 
-// First bound of the integer scan: one block per query adds up the 8-bit table entries of the
-// first `cnt` codes (two 4-bit indexes per byte), finds the smallest sum T with at least kq codes
-// at or below it, and stores it as the query's shared bound (the scan prunes with "<=" against it).
-__global__ __launch_bounds__(256) void u4_seed_kernel(const uint8_t *__restrict__ codes, int cnt,
-                                                      const uint8_t *__restrict__ qluts, int kq, uint32_t *tau_global) {
-    __shared__ uint32_t hist[4096];
-    __shared__ uint32_t part[256];
-    __shared__ uint8_t tab[256];
-    const int q = blockIdx.x, tid = threadIdx.x;
-    tab[tid] = qluts[(size_t)q * 256 + tid];
-    for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+// First bound of the integer scan: one block per SEED_QPB queries adds up the 8-bit table entries of the
+// first `cnt` codes (two 4-bit indexes per byte), finds per query the smallest sum T with at least kq
+// codes at or below it, and stores it as the query's shared bound (the scan prunes with "<=" against it).
+// What limits this kernel is fetching the codes once per block, hence several queries per block: the
+// entries of the block's queries for one code byte (both of its components added) are one 8-byte LDS
+// read, and their sums add up as four 16-bit fields of a 64-bit word.
+constexpr int SEED_QPB = 4;
+__global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict__ codes, int cnt,
+                                                       const uint8_t *__restrict__ qluts, int kq, int nq, uint32_t *tau_global) {
+    __shared__ uint32_t hist[SEED_QPB][4096];
+    __shared__ uint32_t part[SEED_QPB][256];
+    __shared__ uint8_t tab[SEED_QPB][256];
+    __shared__ uint2 pair[8][256];
+    __shared__ uint32_t cut_s[SEED_QPB];
+    const int q0 = blockIdx.x * SEED_QPB, tid = threadIdx.x;
+    const int myq = tid >> 8, sub = tid & 255;   // 256 threads per query where the queries are handled apart
+    tab[myq][sub] = q0 + myq < nq ? qluts[(size_t)(q0 + myq) * 256 + sub] : (uint8_t)255;
+    for (int i = tid; i < SEED_QPB * 4096; i += 1024) (&hist[0][0])[i] = 0;
     __syncthreads();
-    for (int i = tid; i < cnt; i += 256) {
+    for (int e = tid; e < 8 * 256; e += 1024) {
+        const int r = e >> 8, byte = e & 255;
+        uint32_t t[SEED_QPB];
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq)
+            t[qq] = (uint32_t)tab[qq][(2 * r) * 16 + (byte & 15)] + (uint32_t)tab[qq][(2 * r + 1) * 16 + (byte >> 4)];
+        pair[r][byte] = make_uint2(t[0] | (t[1] << 16), t[2] | (t[3] << 16));
+    }
+    // per query: smallest sum with at least kq counted codes at or below it (4096: fewer than kq counted)
+    auto kth_sums = [&]() {
+        __syncthreads();
+        uint32_t mine = 0;
+        for (int i = 0; i < 16; ++i) mine += hist[myq][sub * 16 + i];
+        part[myq][sub] = mine;
+        __syncthreads();
+        if (sub == 0) {
+            uint32_t cum = 0;
+            int t = 0;
+            while (t < 256 && cum + part[myq][t] < (uint32_t)kq) cum += part[myq][t++];
+            int b = 4096;
+            if (t < 256) {
+                b = t * 16;
+                while (cum + hist[myq][b] < (uint32_t)kq) cum += hist[myq][b++];
+            }
+            cut_s[myq] = (uint32_t)b;
+        }
+        __syncthreads();
+    };
+    auto code_sums = [&](int i) -> uint64_t {   // four sums of at most 16 * 255 < 4096
         const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
-        uint32_t sum = 0;
+        uint64_t acc = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const uint32_t byte = ((r < 4 ? c.x : c.y) >> (8 * (r & 3))) & 255u;
-            sum += (uint32_t)tab[(2 * r) * 16 + (byte & 15u)] + (uint32_t)tab[(2 * r + 1) * 16 + (byte >> 4)];
+            const uint2 v = pair[r][((r < 4 ? c.x : c.y) >> (8 * (r & 3))) & 255u];
+            acc += ((uint64_t)v.y << 32) | v.x;
         }
-        atomicAdd(&hist[sum], 1u);   // sum <= 16 * 255 < 4096
+        return acc;
+    };
+    // The first 4096 codes are all counted; their kq-th sum bounds that of any superset, so of the other
+    // codes only the sums up to it need counting.
+    const int head = cnt < 4096 ? cnt : 4096;
+    __syncthreads();
+    for (int i = tid; i < head; i += 1024) {
+        const uint64_t acc = code_sums(i);
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq) atomicAdd(&hist[qq][(uint32_t)(acc >> (16 * qq)) & 0xffffu], 1u);
     }
-    __syncthreads();
-    uint32_t mine = 0;
-    for (int i = 0; i < 16; ++i) mine += hist[tid * 16 + i];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t cum = 0;
-        int t = 0;
-        while (t < 256 && cum + part[t] < (uint32_t)kq) cum += part[t++];
-        if (t < 256) {
-            int b = t * 16;
-            while (cum + hist[b] < (uint32_t)kq) cum += hist[b++];
-            tau_global[q] = (uint32_t)b;
+    if (cnt > head) {
+        kth_sums();
+        uint32_t cut[SEED_QPB];
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq) cut[qq] = cut_s[qq] > 4095u ? 4095u : cut_s[qq];
+        for (int i = head + tid; i < cnt; i += 1024) {
+            const uint64_t acc = code_sums(i);
+#pragma unroll
+            for (int qq = 0; qq < SEED_QPB; ++qq) {
+                const uint32_t sum = (uint32_t)(acc >> (16 * qq)) & 0xffffu;
+                if (sum <= cut[qq]) atomicAdd(&hist[qq][sum], 1u);
+            }
         }
     }
+    kth_sums();
+    if (sub == 0 && q0 + myq < nq && cut_s[myq] < 4096u) tau_global[q0 + myq] = cut_s[myq];
 }
 
 // The same over more codes than one block per query can look at (few query groups, large database):
@@ -1625,7 +1670,8 @@ __global__ void zero_u32_kernel(uint32_t *p, size_t n) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
-// 16-bit tables of the pruned float scan.  One block of 256 threads per group of 8 queries.
+// 16-bit tables of the pruned float scan.  Blocks (group, y) of 256 threads: every block of a group works out the
+// minima and scales of the group's queries, block y writes the tables y, y + gridDim.y, ...
 // Per query: off = sum over the tables of their minimum entry, scale = PRUNE_RANGE / (tau0 - off)
 // (0, which disables the pruning of that query, if tau0 leaves no usable range), and for every table
 // L[j][b] = min(32767 / M, floor((D[j][b] - min_j) * scale)) for the M = 8 or 16 tables.  Output in
@@ -1666,15 +1712,14 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
                 // the threshold conversion must stay accurate to a fraction of a table unit in fp32
                 if (!(tau0[gq] * scale * 1e-6f < 1.f)) scale = 0.f;
             }
-            off_out[gq] = off;
-            scale_out[gq] = scale;
+            if (blockIdx.y == 0) { off_out[gq] = off; scale_out[gq] = scale; }
             if constexpr (Q8) {
                 float scale16 = 0.f;
                 if (range > 0.f && range < 3.0e38f) {
                     scale16 = PRUNE_RANGE / range;
                     if (!(tau0[gq] * scale16 * 1e-6f < 1.f)) scale16 = 0.f;
                 }
-                scale16_out[gq] = scale16;
+                if (blockIdx.y == 0) scale16_out[gq] = scale16;
                 sscale16[tid] = scale16;
             }
         } else if (Q8) {
@@ -1684,7 +1729,7 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
     }
     __syncthreads();
     const int b = tid;
-    for (int j = 0; j < M; ++j) {
+    for (int j = blockIdx.y; j < M; j += gridDim.y) {
         uint32_t e[G];
 #pragma unroll
         for (int q = 0; q < G; ++q) {
@@ -1953,9 +1998,9 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
-        if (q8) prune_tables_kernel<8, 16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
-        else if (tables == 8) prune_tables_kernel<8><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
-        else prune_tables_kernel<16><<<ngroups, 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
+        if (q8) prune_tables_kernel<8, 16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
+        else if (tables == 8) prune_tables_kernel<8><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
+        else prune_tables_kernel<16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
         PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale; a.qtabs16 = qtabs16; a.prune_scale16 = pscale16;
     } else if (seed_plain) {
@@ -1979,7 +2024,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             int seed_codes = topk * 256 > PRUNE_INIT ? topk * 256 : PRUNE_INIT;
             if (few_groups || seed_codes > SEED_CODES_STREAM) seed_codes = SEED_CODES_STREAM;
             if ((int64_t)seed_codes > n) seed_codes = (int)n;
-            u4_seed_kernel<<<nq, 256, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, a.tau_global);
+            u4_seed_kernel<<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, nq, a.tau_global);
         }
         PQ_HIP(ctx, hipGetLastError());
     }

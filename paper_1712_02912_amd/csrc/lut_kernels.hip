@@ -306,21 +306,52 @@ static inline int staged_floats(int n2, int m, int k) {
     return (size_t)n2 * 8 + (size_t)m * k * 4 <= 48 * 1024 ? m * k : 0;
 }
 
-// One block per query: distances of the first `cnt` codes (cnt <= 4096) into LDS keys,
-// bitonic sort, take the kq-th.
-__global__ __launch_bounds__(256) void qmax_prescan_kernel(const uint8_t *__restrict__ codes, int cnt, int cb,
+// One block per query: distances of the first `cnt` codes (cnt <= 4096) as ordered 32-bit values in LDS,
+// then the kq-th smallest of them by radix selection, most significant byte first (four rounds of a
+// 256-bin count over the values that share the bytes fixed so far; 1 <= kq <= cnt).
+__global__ __launch_bounds__(1024) void qmax_prescan_kernel(const uint8_t *__restrict__ codes, int cnt, int cb,
                                                            int cf, const float *__restrict__ luts, int m, int k,
                                                            int kq, int n2, int staged, float *qmax_out) {
     extern __shared__ uint64_t skeys[];
-    const int q = blockIdx.x;
+    __shared__ uint32_t bins[256];
+    __shared__ uint32_t sel_prefix, sel_k;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    uint32_t *ords = reinterpret_cast<uint32_t *>(skeys);
     const float *lut = stage_tables(luts + (size_t)q * m * k, reinterpret_cast<float *>(skeys + n2), staged);
-    for (int i = threadIdx.x; i < n2; i += 256) {
-        uint64_t key = KEY_EMPTY;
-        if (i < cnt) key = ((uint64_t)f32_to_ord(adc_one(codes + (size_t)i * cb, cf, lut, m, k)) << 32) | (uint32_t)i;
-        skeys[i] = key;
+    for (int i = tid; i < cnt; i += blockDim.x) ords[i] = f32_to_ord(adc_one(codes + (size_t)i * cb, cf, lut, m, k));
+    if (tid == 0) { sel_prefix = 0u; sel_k = (uint32_t)kq; }
+    for (int pass = 3; pass >= 0; --pass) {
+        if (tid < 256) bins[tid] = 0u;
+        __syncthreads();
+        const int shift = 8 * pass;
+        const uint32_t fixed = pass == 3 ? 0u : 0xffffffffu << (shift + 8);   // bytes decided in earlier rounds
+        const uint32_t prefix = sel_prefix, want = sel_k;
+        for (int i = tid; i < cnt; i += blockDim.x) {
+            const uint32_t v = ords[i];
+            if ((v & fixed) == prefix) atomicAdd(&bins[(v >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {   // one wave: the byte value whose bin holds the `want`-th value
+            const uint32_t h[4] = {bins[4 * tid], bins[4 * tid + 1], bins[4 * tid + 2], bins[4 * tid + 3]};
+            const uint32_t tot = h[0] + h[1] + h[2] + h[3];
+            uint32_t incl = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t up = __shfl_up(incl, o);
+                if (tid >= o) incl += up;
+            }
+            const uint64_t reach = __ballot(incl >= want);   // never empty: want <= values that share the prefix
+            if (reach != 0ull && tid == __builtin_ctzll(reach)) {
+                uint32_t cum = incl - tot;
+                int b = 4 * tid;
+                for (int t = 0; t < 3 && cum + h[t] < want; ++t) { cum += h[t]; ++b; }
+                sel_prefix = prefix | ((uint32_t)b << shift);
+                sel_k = want - cum;
+            }
+        }
+        __syncthreads();
     }
-    block_bitonic_sort(skeys, n2);
-    if (threadIdx.x == 0) qmax_out[q] = ord_to_f32((uint32_t)(skeys[kq - 1] >> 32));
+    if (tid == 0) qmax_out[q] = ord_to_f32(sel_prefix);
 }
 
 int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m,
@@ -331,20 +362,20 @@ int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, co
     while (n2 < cnt) n2 <<= 1;
     const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
     const int staged = staged_floats(n2, m, k);
-    qmax_prescan_kernel<<<nq, 256, (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, cnt, cb, cf, luts, m, k, kq, n2, staged, qmax_out);
+    qmax_prescan_kernel<<<nq, n2 >= 2048 ? 1024 : (n2 >= 1024 ? 512 : 256), (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, cnt, cb, cf, luts, m, k, kq, n2, staged, qmax_out);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }
 
 // One block per query: float ADC of the candidates, sort by (distance, id), write topk.
-__global__ __launch_bounds__(256) void rerank_kernel(const uint8_t *__restrict__ codes, int64_t n, int cb, int cf,
+__global__ __launch_bounds__(1024) void rerank_kernel(const uint8_t *__restrict__ codes, int64_t n, int cb, int cf,
                                                      const float *__restrict__ luts, int m, int k,
                                                      const int64_t *__restrict__ cand, int ncand, int n2, int topk, int staged,
                                                      float *out_dist, int64_t *out_ids) {
     extern __shared__ uint64_t skeys[];
     const int q = blockIdx.x;
     const float *lut = stage_tables(luts + (size_t)q * m * k, reinterpret_cast<float *>(skeys + n2), staged);
-    for (int i = threadIdx.x; i < n2; i += 256) {
+    for (int i = threadIdx.x; i < n2; i += blockDim.x) {
         uint64_t key = KEY_EMPTY;
         if (i < ncand) {
             const int64_t id = cand[(size_t)q * ncand + i];
@@ -354,7 +385,7 @@ __global__ __launch_bounds__(256) void rerank_kernel(const uint8_t *__restrict__
         skeys[i] = key;
     }
     block_bitonic_sort(skeys, n2);
-    for (int i = threadIdx.x; i < topk; i += 256) {
+    for (int i = threadIdx.x; i < topk; i += blockDim.x) {
         const uint64_t key = skeys[i];
         const bool empty = key == KEY_EMPTY;
         out_dist[(size_t)q * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
@@ -369,7 +400,7 @@ int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const fl
     const int cb = cf == PQ_CODES_U4_PACKED ? m / 2 : m;
     if (nq == 0) return PQ_OK;
     const int staged = staged_floats(n2, m, k);
-    rerank_kernel<<<nq, 256, (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, n, cb, cf, luts, m, k, cand, ncand, n2, topk,
+    rerank_kernel<<<nq, n2 >= 2048 ? 1024 : (n2 >= 1024 ? 512 : 256), (size_t)n2 * 8 + (size_t)staged * 4, ctx->stream>>>(codes, n, cb, cf, luts, m, k, cand, ncand, n2, topk,
                                                                                    staged, out_dist, out_ids);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;

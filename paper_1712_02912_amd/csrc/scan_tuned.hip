@@ -1401,15 +1401,15 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
 constexpr int SEED_QPB = 4;
 __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict__ codes, int cnt,
                                                        const uint8_t *__restrict__ qluts, int kq, int nq, uint32_t *tau_global) {
-    __shared__ uint32_t hist[SEED_QPB][4096];
-    __shared__ uint32_t part[SEED_QPB][256];
+    static_assert(HIST_BINS == 4096, "sums of 16 bytes index the bins");
+    __shared__ __align__(16) uint32_t hist[SEED_QPB][HIST_BINS];
     __shared__ uint8_t tab[SEED_QPB][256];
     __shared__ uint2 pair[8][256];
     __shared__ uint32_t cut_s[SEED_QPB];
     const int q0 = blockIdx.x * SEED_QPB, tid = threadIdx.x;
     const int myq = tid >> 8, sub = tid & 255;   // 256 threads per query where the queries are handled apart
     tab[myq][sub] = q0 + myq < nq ? qluts[(size_t)(q0 + myq) * 256 + sub] : (uint8_t)255;
-    for (int i = tid; i < SEED_QPB * 4096; i += 1024) (&hist[0][0])[i] = 0;
+    for (int i = tid; i < SEED_QPB * HIST_BINS; i += 1024) (&hist[0][0])[i] = 0;
     __syncthreads();
     for (int e = tid; e < 8 * 256; e += 1024) {
         const int r = e >> 8, byte = e & 255;
@@ -1420,22 +1420,11 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
         pair[r][byte] = make_uint2(t[0] | (t[1] << 16), t[2] | (t[3] << 16));
     }
     // per query: smallest sum with at least kq counted codes at or below it (4096: fewer than kq counted)
-    auto kth_sums = [&]() {
+    auto kth_sums = [&]() {   // (the first wave of the query's 256 threads)
         __syncthreads();
-        uint32_t mine = 0;
-        for (int i = 0; i < 16; ++i) mine += hist[myq][sub * 16 + i];
-        part[myq][sub] = mine;
-        __syncthreads();
-        if (sub == 0) {
-            uint32_t cum = 0;
-            int t = 0;
-            while (t < 256 && cum + part[myq][t] < (uint32_t)kq) cum += part[myq][t++];
-            int b = 4096;
-            if (t < 256) {
-                b = t * 16;
-                while (cum + hist[myq][b] < (uint32_t)kq) cum += hist[myq][b++];
-            }
-            cut_s[myq] = (uint32_t)b;
+        if (sub < 64) {
+            const int b = hist_threshold(hist[myq], kq);
+            if (sub == 0) cut_s[myq] = (uint32_t)b;
         }
         __syncthreads();
     };
@@ -1539,61 +1528,109 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
 // distances at or below it.  Distances are summed in table order, as everywhere on this path.
 template <int M>
-__global__ __launch_bounds__(256) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
-                                                              const float *__restrict__ luts, int k, bool self_ref,
-                                                              float *tau0) {
-    __shared__ float tab[M * 256];
-    __shared__ uint32_t hist[HIST_BINS];
-    __shared__ uint32_t part[256];
-    __shared__ uint32_t ref_s;
-    const int q = blockIdx.x, tid = threadIdx.x;
-    for (int i = tid; i < M * 256; i += 256) tab[i] = luts[(size_t)q * (M * 256) + i];
-    for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
-    if (tid == 0) ref_s = self_ref ? 0u : f32_to_ord(tau0[q]);
-    __syncthreads();
-    auto dist_ord = [&](int i) {
-        uint32_t w[M / 4];
-        if (M == 8) {
-            const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
-            w[0] = c.x; w[1] = c.y;
-        } else {
-            const uint4 c = *reinterpret_cast<const uint4 *>(codes + (size_t)i * 16);
-            w[0] = c.x; w[1] = c.y; w[M / 4 - 2] = c.z; w[M / 4 - 1] = c.w;
-        }
-        float d = tab[w[0] & 255u];
+__global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
+                                                               const float *__restrict__ luts, int k, bool self_ref, int nq,
+                                                               float *tau0) {
+    // SEED_QPB queries per block (the kernel is limited by fetching the codes once per block): entry e of table j
+    // for the block's queries is one 16-byte LDS read
+    static_assert(SEED_QPB == 4, "four queries share a float4");
+    __shared__ float4 tab[M * 256];
+    __shared__ __align__(16) uint32_t hist[SEED_QPB][HIST_BINS];
+    __shared__ uint32_t ref_s[SEED_QPB];
+    const int q0 = blockIdx.x * SEED_QPB, tid = threadIdx.x;
+    const int myq = tid >> 8, sub = tid & 255;   // 256 threads per query where the queries are handled apart
+    for (int e = tid; e < M * 256; e += 1024) {
+        float v[SEED_QPB];
 #pragma unroll
-        for (int j = 1; j < M; ++j) d += tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
-        return f32_to_ord(d);
+        for (int qq = 0; qq < SEED_QPB; ++qq) v[qq] = q0 + qq < nq ? luts[(size_t)(q0 + qq) * (M * 256) + e] : __builtin_inff();
+        tab[e] = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    for (int i = tid; i < SEED_QPB * HIST_BINS; i += 1024) (&hist[0][0])[i] = 0;
+    if (sub == 0) ref_s[myq] = self_ref || q0 + myq >= nq ? 0u : f32_to_ord(tau0[q0 + myq]);
+    __syncthreads();
+    struct Code { uint32_t w[M / 4]; };
+    auto load_code = [&](int i) {
+        Code c;
+        if (M == 8) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+            c.w[0] = v.x; c.w[1] = v.y;
+        } else {
+            const uint4 v = *reinterpret_cast<const uint4 *>(codes + (size_t)i * 16);
+            c.w[0] = v.x; c.w[1] = v.y; c.w[M / 4 - 2] = v.z; c.w[M / 4 - 1] = v.w;
+        }
+        return c;
+    };
+    auto dist_ords = [&](const Code &c, uint32_t (&ord)[SEED_QPB]) {
+        const uint32_t (&w)[M / 4] = c.w;
+        float4 d = tab[w[0] & 255u];
+#pragma unroll
+        for (int j = 1; j < M; ++j) {
+            const float4 t = tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
+            d.x += t.x; d.y += t.y; d.z += t.z; d.w += t.w;
+        }
+        ord[0] = f32_to_ord(d.x); ord[1] = f32_to_ord(d.y); ord[2] = f32_to_ord(d.z); ord[3] = f32_to_ord(d.w);
     };
     if (self_ref) {   // no bound yet: the greatest distance among the first k codes is one
-        for (int i = tid; i < k && i < cnt; i += 256) atomicMax(&ref_s, dist_ord(i));
+        for (int i = tid; i < k && i < cnt; i += 1024) {
+            uint32_t ord[SEED_QPB];
+            dist_ords(load_code(i), ord);
+#pragma unroll
+            for (int qq = 0; qq < SEED_QPB; ++qq) atomicMax(&ref_s[qq], ord[qq]);
+        }
         __syncthreads();
     }
-    const uint32_t ref = ref_s;
-    for (int i = tid; i < cnt; i += 256) {
-        const uint32_t ord = dist_ord(i);
-        if (ord <= ref) {
-            const uint32_t below = (ref - ord) >> HIST_SHIFT;
-            atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+    uint32_t ref[SEED_QPB];
+#pragma unroll
+    for (int qq = 0; qq < SEED_QPB; ++qq) ref[qq] = ref_s[qq];
+    __shared__ int bin_s[SEED_QPB];
+    // per query: the smallest bin with at least k counted distances in the bins up to it (HIST_BINS: fewer than k)
+    auto kth_bins = [&]() {   // (the first wave of the query's 256 threads)
+        __syncthreads();
+        if (sub < 64) {
+            const int b = hist_threshold(hist[myq], k);
+            if (sub == 0) bin_s[myq] = b;
         }
+        __syncthreads();
+    };
+    // every distance counted in bins <= b is at or below this edge, every other one above it
+    auto edge_of = [&](uint32_t rq, int b) { return rq - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT); };
+    auto count = [&](const Code &c, const uint32_t (&limit)[SEED_QPB]) {
+        uint32_t ord[SEED_QPB];
+        dist_ords(c, ord);
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq) {
+            if (ord[qq] <= limit[qq]) {
+                const uint32_t below = (ref[qq] - ord[qq]) >> HIST_SHIFT;
+                atomicAdd(&hist[qq][HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+            }
+        }
+    };
+    // The first 4096 codes are counted against the reference; the bin edge they give bounds the answer over any
+    // superset, so of the other codes only the distances up to that edge need counting (counting them all is
+    // what this kernel would spend most of its time on).
+    const int head = cnt < 4096 ? cnt : 4096;
+    // four codes of a thread on their way at a time (the loop is otherwise a chain of load latencies)
+    auto count_range = [&](int begin, int end, const uint32_t (&limit)[SEED_QPB]) {
+        int i = begin + tid;
+        for (; i + 3 * 1024 < end; i += 4 * 1024) {
+            const Code c0 = load_code(i), c1 = load_code(i + 1024), c2 = load_code(i + 2048), c3 = load_code(i + 3072);
+            count(c0, limit); count(c1, limit); count(c2, limit); count(c3, limit);
+        }
+        for (; i < end; i += 1024) count(load_code(i), limit);
+    };
+    count_range(0, head, ref);
+    if (cnt > head) {
+        kth_bins();
+        uint32_t limit[SEED_QPB];
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq) limit[qq] = bin_s[qq] < HIST_BINS ? edge_of(ref[qq], bin_s[qq]) : ref[qq];
+        count_range(head, cnt, limit);
     }
-    __syncthreads();
-    uint32_t mine = 0;
-    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t cum = 0;
-        int t = 0;
-        while (t < 256 && cum + part[t] < (uint32_t)k) cum += part[t++];
-        if (t < 256) {
-            int b = t * (HIST_BINS / 256);
-            while (cum + hist[b] < (uint32_t)k) cum += hist[b++];
-            // every distance counted in bins <= b is at or below this edge
-            tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
-        } else if (self_ref) {
-            tau0[q] = cnt >= k ? ord_to_f32(ref) : __builtin_inff();
-        }
+    kth_bins();
+    if (sub == 0 && q0 + myq < nq) {
+        const int q = q0 + myq;
+        if (bin_s[myq] < HIST_BINS) tau0[q] = ord_to_f32(edge_of(ref_s[myq], bin_s[myq]));
+        else if (self_ref) tau0[q] = cnt >= k ? ord_to_f32(ref_s[myq]) : __builtin_inff();
     }
 }
 
@@ -1986,8 +2023,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             // the first bound: smallest histogram edge with k distances among the first codes
             // (a reference for the histogram bins is all the wide pass needs from this one)
             const int first_codes = wide_seed ? PRUNE_INIT : (few_groups ? SEED_CODES_STREAM : SEED_CODES_BATCH);
-            if (tables == 8) f32_seed_refine_kernel<8><<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
-            else f32_seed_refine_kernel<16><<<nq, 256, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, tau0);
+            if (tables == 8) f32_seed_refine_kernel<8><<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, nq, tau0);
+            else f32_seed_refine_kernel<16><<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, nq, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
         if (wide_seed) {

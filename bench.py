@@ -146,6 +146,14 @@ def main():
                                 "scan_tuned_kernel<F32P_M8 (8x8 float, 16-bit lower bounds, 8 queries per pass), lists for top<=%d>")
                                % (128 if args.topk <= 128 else 1024), "kernel_ms": scan_ms,
                      "algorithmic_bytes": alg_bytes,
+                     # what binds this kernel: issue slots of the 1024 SIMDs.  One sub-tile of the 16-query loop (128 codes x 16
+                     # queries) is 60 three-operand vector instructions (4 cycles each), 4 two-operand ones (2 cycles) and 16
+                     # ds_read_b128 (8 SIMD cycles each, measured): 376 cycles; peak = every SIMD issuing all the time at 2.4 GHz
+                     "issue_model": ({"bound": "alu", "unit": "G SIMD cycles per launch",
+                                      "achieved": args.n * ((args.nq + 15) // 16) / 128 * 376 / 1e9,
+                                      "peak": 1024 * scan_ms * 1e-3 * 2.4e9 / 1e9,
+                                      "frac": args.n * ((args.nq + 15) // 16) / 128 * 376 / (1024 * scan_ms * 1e-3 * 2.4e9)}
+                                     if args.nq >= 512 and args.n >= 65536 else None),
                      "note": "algorithmic bytes = 8 B per code per query pass; one pass over a chunk serves 8 or 16 queries and "
                              "concurrent blocks share chunks through L2, so the HBM bytes really moved (traffic) are far below "
                              "the algorithmic figure and frac exceeds 1; the kernel is bound by LDS reads and vector issue"},

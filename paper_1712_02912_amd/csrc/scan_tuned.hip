@@ -1465,7 +1465,7 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
     if (sub == 0 && q0 + myq < nq && cut_s[myq] < 4096u) tau_global[q0 + myq] = cut_s[myq];
 }
 
-// The same over more codes than one block per query can look at (few query groups, large database):
+// The same over more codes than one block can look at (few query groups, large database):
 // block (s, q) counts the sums of slice s of the first `cnt` codes into the query's bins in device
 // memory, u4_seed_pick_kernel reads the bound off the counts.
 __global__ __launch_bounds__(1024) void u4_seed_hist_kernel(const uint8_t *__restrict__ codes, int64_t cnt,
@@ -1523,7 +1523,7 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
 }
 
 // Better first bound (every candidate the first bound lets through costs far more than a code the
-// integer test dismisses): one block per query looks at the first `cnt` codes, counts the float distances at or
+// integer test dismisses): one block per four queries looks at the first `cnt` codes, counts the float distances at or
 // below the bound known so far (tau0 as handed in, or with self_ref the greatest distance of the first k codes)
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
 // distances at or below it.  Distances are summed in table order, as everywhere on this path.
@@ -1634,7 +1634,7 @@ __global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__
     }
 }
 
-// The same refinement over more codes than one block per query can look at (flat scans of few
+// The same refinement over more codes than one block can look at (flat scans of few
 // query groups over large databases, where every candidate the first bound lets through costs more
 // than a code it dismisses): block (s, q) counts the distances of slice s at or below the query's
 // bound in the bins of the scan's histogram and adds its counts to the query's bins in device memory;

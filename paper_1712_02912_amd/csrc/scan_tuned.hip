@@ -55,7 +55,7 @@ struct WaveState {
 
 // wave list capacity in units of 64 keys: 384 keys for results of up to 128, 2048 for up to 1024
 constexpr int E_SMALL = 6, E_LARGE = 32;
-constexpr int RING_FLUSH = 64;    // flush when more than this many positions are parked
+constexpr int RING_FLUSH = TUNED_WAVES == 8 ? 64 : 192;    // flush when more than this many positions are parked
 constexpr int RING_PERIOD = 256;  // and, if anything is parked, every this many iterations
 
 // RING: ring entries per wave
@@ -1262,13 +1262,21 @@ void scan_tuned_kernel(TunedArgs a) {
         auto between_steps = [&]() {
             bool changed = false;
             if (flush_due()) {
+                // A full ring is drained in whole batches of 64 positions (every lane of the insert path busy); what
+                // is left over moves to the front and waits for company.  The periodic drain takes everything.
+                const int take = ring_cnt > RING_FLUSH ? (ring_cnt & ~63) : ring_cnt;
                 int appended;
-                if constexpr (PRUNED) appended = scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
-                else if constexpr (U4Q) appended = scan_flush_u4q<SM, E>(smp, wave_buf, ring_cnt);
-                else appended = scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
+                if constexpr (PRUNED) appended = scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, take);
+                else if constexpr (U4Q) appended = scan_flush_u4q<SM, E>(smp, wave_buf, take);
+                else appended = scan_flush<SM, KIND, E>(smp, wave_buf, take);
                 // 8-bit bounds park many codes that turn out to be none: there only the keys count
-                pressure += Q8 ? appended : ring_cnt;
-                ring_cnt = 0;
+                pressure += Q8 ? appended : take;
+                const int left = ring_cnt - take;   // below 64
+                if (left > 0) {
+                    const uint32_t moved = lane < left ? sm.ring[wave][take + lane] : 0u;   // (take >= 64 > lane)
+                    if (lane < left) sm.ring[wave][lane] = moved;
+                }
+                ring_cnt = left;
                 changed = true;
             }
             // a wave that keeps finding candidates asks for a new bound without waiting for its turn

@@ -28,8 +28,9 @@ constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bo
 
 // ------------------------------------------------------------------------------------------
 // nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.
-// Fast path for long rows: a threshold guessed from a sorted sample of 1024 entries (aimed at three
-// times nprobe entries at or below it), one pass that collects the keys at or below it, sort.
+// Fast path for long rows: a threshold guessed from a sample of 1024 entries (its order statistic aimed at
+// three times nprobe entries at or below it, by radix selection), one pass that collects the keys at or below
+// it (four 16-byte loads of a thread on their way at a time), sort.
 // If the guess caught fewer than nprobe or more than fit: histogram of the top 12 bits of the
 // ordered value -> bin holding the nprobe-th; everything in lower bins and in that bin is sorted
 // in LDS.  If that is too much (heavy ties), bisection on the 64-bit key over the whole row.
@@ -37,24 +38,27 @@ constexpr int SEL_CAP = 4096;
 __global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__restrict__ dist, int nlist,
                                                                 int nprobe, int32_t *__restrict__ probes,
                                                                 int32_t *probe_out) {
-    __shared__ uint32_t hist[4096];
     __shared__ uint64_t cand[SEL_CAP];
     __shared__ uint32_t part[256];
+    __shared__ uint32_t sel_state[2];
     __shared__ int s_bin, s_count;
+    // the sample of the fast path and the histogram of the slow one live in the memory of the candidates, which
+    // are collected only after either has served its purpose
+    uint32_t *sample = reinterpret_cast<uint32_t *>(cand);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(cand);
+    static_assert(SEL_CAP * 8 >= 4096 * 4, "the histogram fits into the candidates' memory");
     __shared__ unsigned long long s_kth;
     const int q = blockIdx.x, tid = threadIdx.x;
     const float *row = dist + (size_t)q * nlist;
     bool done = false;
     if (nlist >= 8192 && (nlist & 3) == 0 && (size_t)nprobe * 3 * 1024 / nlist + 8 < 1024) {
         const int stride = nlist / 1024;
-        for (int i = tid; i < 1024; i += 256) cand[i] = ((uint64_t)f32_to_ord(row[(size_t)i * stride]) << 32) | (uint32_t)i;
+        for (int i = tid; i < 1024; i += 256) sample[i] = f32_to_ord(row[(size_t)i * stride]);
         if (tid == 0) s_count = 0;
-        block_bitonic_sort(cand, 1024);
-        const uint32_t guess = (uint32_t)(cand[(size_t)nprobe * 3 * 1024 / nlist + 8] >> 32);
         __syncthreads();
+        const uint32_t guess = block_kth_smallest_u32(sample, 1024, (uint32_t)((size_t)nprobe * 3 * 1024 / nlist + 8) + 1u, part, sel_state);
         const float4 *row4 = reinterpret_cast<const float4 *>(row);   // rows start on 16-byte boundaries (nlist % 4 == 0)
-        for (int i = tid; i < nlist / 4; i += 256) {
-            const float4 v = row4[i];
+        auto collect = [&](int i, const float4 v) {
             const uint32_t o[4] = {f32_to_ord(v.x), f32_to_ord(v.y), f32_to_ord(v.z), f32_to_ord(v.w)};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -62,7 +66,14 @@ __global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__r
                     const int pos = atomicAdd(&s_count, 1);
                     if (pos < SEL_CAP) cand[pos] = ((uint64_t)o[e] << 32) | (uint32_t)(4 * i + e);
                 }
+        };
+        const int n4 = nlist / 4;
+        int i = tid;
+        for (; i + 3 * 256 < n4; i += 4 * 256) {
+            const float4 v0 = row4[i], v1 = row4[i + 256], v2 = row4[i + 512], v3 = row4[i + 768];
+            collect(i, v0); collect(i + 256, v1); collect(i + 512, v2); collect(i + 768, v3);
         }
+        for (; i < n4; i += 256) collect(i, row4[i]);
         __syncthreads();
         done = s_count >= nprobe && s_count <= SEL_CAP;
         __syncthreads();

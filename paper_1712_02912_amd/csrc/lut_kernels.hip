@@ -307,51 +307,20 @@ static inline int staged_floats(int n2, int m, int k) {
 }
 
 // One block per query: distances of the first `cnt` codes (cnt <= 4096) as ordered 32-bit values in LDS,
-// then the kq-th smallest of them by radix selection, most significant byte first (four rounds of a
-// 256-bin count over the values that share the bytes fixed so far; 1 <= kq <= cnt).
+// then the kq-th smallest of them by radix selection (1 <= kq <= cnt).
 __global__ __launch_bounds__(1024) void qmax_prescan_kernel(const uint8_t *__restrict__ codes, int cnt, int cb,
                                                            int cf, const float *__restrict__ luts, int m, int k,
                                                            int kq, int n2, int staged, float *qmax_out) {
     extern __shared__ uint64_t skeys[];
     __shared__ uint32_t bins[256];
-    __shared__ uint32_t sel_prefix, sel_k;
+    __shared__ uint32_t state[2];
     const int q = blockIdx.x, tid = threadIdx.x;
     uint32_t *ords = reinterpret_cast<uint32_t *>(skeys);
     const float *lut = stage_tables(luts + (size_t)q * m * k, reinterpret_cast<float *>(skeys + n2), staged);
     for (int i = tid; i < cnt; i += blockDim.x) ords[i] = f32_to_ord(adc_one(codes + (size_t)i * cb, cf, lut, m, k));
-    if (tid == 0) { sel_prefix = 0u; sel_k = (uint32_t)kq; }
-    for (int pass = 3; pass >= 0; --pass) {
-        if (tid < 256) bins[tid] = 0u;
-        __syncthreads();
-        const int shift = 8 * pass;
-        const uint32_t fixed = pass == 3 ? 0u : 0xffffffffu << (shift + 8);   // bytes decided in earlier rounds
-        const uint32_t prefix = sel_prefix, want = sel_k;
-        for (int i = tid; i < cnt; i += blockDim.x) {
-            const uint32_t v = ords[i];
-            if ((v & fixed) == prefix) atomicAdd(&bins[(v >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid < 64) {   // one wave: the byte value whose bin holds the `want`-th value
-            const uint32_t h[4] = {bins[4 * tid], bins[4 * tid + 1], bins[4 * tid + 2], bins[4 * tid + 3]};
-            const uint32_t tot = h[0] + h[1] + h[2] + h[3];
-            uint32_t incl = tot;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t up = __shfl_up(incl, o);
-                if (tid >= o) incl += up;
-            }
-            const uint64_t reach = __ballot(incl >= want);   // never empty: want <= values that share the prefix
-            if (reach != 0ull && tid == __builtin_ctzll(reach)) {
-                uint32_t cum = incl - tot;
-                int b = 4 * tid;
-                for (int t = 0; t < 3 && cum + h[t] < want; ++t) { cum += h[t]; ++b; }
-                sel_prefix = prefix | ((uint32_t)b << shift);
-                sel_k = want - cum;
-            }
-        }
-        __syncthreads();
-    }
-    if (tid == 0) qmax_out[q] = ord_to_f32(sel_prefix);
+    __syncthreads();
+    const uint32_t kth = block_kth_smallest_u32(ords, cnt, (uint32_t)kq, bins, state);
+    if (tid == 0) qmax_out[q] = ord_to_f32(kth);
 }
 
 int launch_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const float *luts, int nq, int m,

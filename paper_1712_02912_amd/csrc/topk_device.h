@@ -120,6 +120,46 @@ __device__ __forceinline__ int wave_append(uint64_t *buf, int cnt, bool pass, ui
     return cnt + __popcll(mask);
 }
 
+// The k-th smallest (k = 1 .. n) of n 32-bit values in LDS, by the whole block (at least 256 threads), by radix
+// selection, most significant byte first: four rounds of a 256-bin count over the values that share the bytes
+// fixed so far.  `bins`: 256 LDS words, `state`: 2 LDS words.  Every thread gets the value; a few barriers in all.
+__device__ inline uint32_t block_kth_smallest_u32(const uint32_t *vals, int n, uint32_t k, uint32_t *bins, uint32_t *state) {
+    const int tid = threadIdx.x;
+    if (tid == 0) { state[0] = 0u; state[1] = k; }
+    for (int pass = 3; pass >= 0; --pass) {
+        if (tid < 256) bins[tid] = 0u;
+        __syncthreads();
+        const int shift = 8 * pass;
+        const uint32_t fixed = pass == 3 ? 0u : 0xffffffffu << (shift + 8);   // bytes decided in earlier rounds
+        const uint32_t prefix = state[0], want = state[1];
+        for (int i = tid; i < n; i += blockDim.x) {
+            const uint32_t v = vals[i];
+            if ((v & fixed) == prefix) atomicAdd(&bins[(v >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {   // one wave: the byte value whose bin holds the `want`-th value
+            const uint32_t h[4] = {bins[4 * tid], bins[4 * tid + 1], bins[4 * tid + 2], bins[4 * tid + 3]};
+            const uint32_t tot = h[0] + h[1] + h[2] + h[3];
+            uint32_t incl = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t up = __shfl_up(incl, o);
+                if (tid >= o) incl += up;
+            }
+            const uint64_t reach = __ballot(incl >= want);   // never empty: want <= values that share the prefix
+            if (reach != 0ull && tid == __builtin_ctzll(reach)) {
+                uint32_t cum = incl - tot;
+                int b = 4 * tid;
+                for (int t = 0; t < 3 && cum + h[t] < want; ++t) { cum += h[t]; ++b; }
+                state[0] = prefix | ((uint32_t)b << shift);
+                state[1] = want - cum;
+            }
+        }
+        __syncthreads();
+    }
+    return state[0];
+}
+
 // In-LDS bitonic sort (ascending) of n2 keys, n2 a power of two, by the whole block.
 __device__ inline void block_bitonic_sort(uint64_t *s, int n2) {
     for (int size = 2; size <= n2; size <<= 1) {

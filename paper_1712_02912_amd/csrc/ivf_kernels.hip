@@ -327,8 +327,7 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
                                                        const int32_t *__restrict__ probes, const float *__restrict__ luts,
                                                        int nprobe, int topk, float *tau0) {
     __shared__ float tab[M * 256];
-    __shared__ uint32_t hist[HIST_BINS];
-    __shared__ uint32_t part[256];
+    __shared__ __align__(16) uint32_t hist[HIST_BINS];
     __shared__ uint32_t ref_s;
     const int q = blockIdx.x, tid = threadIdx.x;
     for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
@@ -345,16 +344,27 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
             __syncthreads();
             for (int i = tid; i < M * 256; i += 256) tab[i] = lut[i];
             __syncthreads();
-            for (int i = tid; i < take; i += 256) {
+            struct Code { uint32_t w[M / 4]; };
+            auto load_code = [&](int i) {
                 const uint8_t *c = codes + (size_t)(beg + i) * M;
-                uint32_t w[M / 4];
-                if (M == 8) { const uint2 v = *reinterpret_cast<const uint2 *>(c); w[0] = v.x; w[1] = v.y; }
-                else { const uint4 v = *reinterpret_cast<const uint4 *>(c); w[0] = v.x; w[1] = v.y; w[M / 4 - 2] = v.z; w[M / 4 - 1] = v.w; }
+                Code k;
+                if (M == 8) { const uint2 v = *reinterpret_cast<const uint2 *>(c); k.w[0] = v.x; k.w[1] = v.y; }
+                else { const uint4 v = *reinterpret_cast<const uint4 *>(c); k.w[0] = v.x; k.w[1] = v.y; k.w[M / 4 - 2] = v.z; k.w[M / 4 - 1] = v.w; }
+                return k;
+            };
+            auto eval = [&](const Code &k) {
                 float dist = 0.f;
 #pragma unroll
-                for (int j = 0; j < M; ++j) dist += tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
+                for (int j = 0; j < M; ++j) dist += tab[j * 256 + ((k.w[j >> 2] >> (8 * (j & 3))) & 255u)];
                 f(f32_to_ord(dist));
+            };
+            // four codes of a thread on their way at a time (the loop is otherwise a chain of load latencies)
+            int i = tid;
+            for (; i + 3 * 256 < take; i += 4 * 256) {
+                const Code c0 = load_code(i), c1 = load_code(i + 256), c2 = load_code(i + 512), c3 = load_code(i + 768);
+                eval(c0); eval(c1); eval(c2); eval(c3);
             }
+            for (; i < take; i += 256) eval(load_code(i));
             count += take;
         }
         return count;
@@ -373,22 +383,14 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
         }
     });
     __syncthreads();
-    uint32_t mine = 0;
-    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t cum = 0;
-        int t = 0;
-        while (t < 256 && cum + part[t] < (uint32_t)topk) cum += part[t++];
-        uint32_t edge = ref;
-        if (t < 256) {
-            int b = t * (HIST_BINS / 256);
-            while (cum + hist[b] < (uint32_t)topk) cum += hist[b++];
-            edge = ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT);   // every distance counted in bins <= b is at or below it
+    if (tid < 64) {   // one wave reads the bin off the counts
+        const int b = hist_threshold(hist, topk);
+        if (tid == 0) {
+            // every distance counted in bins <= b is at or below this edge
+            const uint32_t edge = b < HIST_BINS ? ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT) : ref;
+            const float kth = ord_to_f32(edge);
+            tau0[q] = kth + fabsf(kth) * 4e-6f;
         }
-        const float kth = ord_to_f32(edge);
-        tau0[q] = kth + fabsf(kth) * 4e-6f;
     }
 }
 

@@ -155,4 +155,43 @@ struct WaveTopK {
     }
 };
 
+// smallest histogram bin b with count(bins <= b) >= k, or HIST_BINS if fewer than k counted; for one wave
+// (all 64 lanes); `hist` (HIST_BINS words, 16-byte aligned) in device memory or LDS
+__device__ __forceinline__ int hist_threshold(const uint32_t *hist, int k) {
+    const int lane = lane_id();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const uint4 *h4 = reinterpret_cast<const uint4 *>(hist) + lane * (HIST_BINS / 64 / 4);
+    uint32_t tot = 0;
+#pragma unroll 4
+    for (int i = 0; i < HIST_BINS / 64 / 4; ++i) {
+        const uint4 v = h4[i];
+        tot += v.x + v.y + v.z + v.w;
+    }
+    uint32_t incl = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    const uint64_t reach = __ballot(incl >= (uint32_t)k);
+    if (reach == 0ull) return HIST_BINS;
+    const int first = __builtin_ctzll(reach);
+    // every lane locates the crossing inside its own 64 bins; only lane `first` has a meaningful need
+    const uint32_t need = (uint32_t)k - (incl - tot);
+    uint32_t cum = 0;
+    int bin = HIST_BINS;
+#pragma unroll 2
+    for (int i = 0; i < HIST_BINS / 64 / 4; ++i) {
+        const uint4 v = h4[i];
+        const uint32_t e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            cum += e[t];
+            if (bin == HIST_BINS && cum >= need) bin = lane * (HIST_BINS / 64) + i * 4 + t;
+        }
+    }
+    return __shfl(bin, first);
+}
+
+
 }  // namespace pq

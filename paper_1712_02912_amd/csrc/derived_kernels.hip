@@ -354,6 +354,374 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The same two passes for many queries (512 and more): 16 queries per pass over the codes.  The entries of the
+// 8-bit tables are bytes, so the entries of 16 queries for one (table, byte) fill a 16-byte LDS slot exactly;
+// their sums of four do not fit a byte, so the scan loop adds 5-bit lower bounds instead,
+//   L[t][b] = min(31, floor((Q[t][b] - min_b Q[t][b]) * scale)),   scale = DQ16_RANGE / (thr - off),
+// (off = the sum of the four minima, thr = the query's threshold: sums below it are wanted), four of which stay
+// below 128: the 16 sums of a code add up byte-wise in four 32-bit adds per table, and one add per word tests them
+// against 0x80 - threshold (bit 7 of a byte stays clear iff that sum is below its threshold).  A code with
+// sum <= thr - 1 has a bound of at most floor((thr - 1 - off) * scale) + 1 (fp32 rounding of the products), so
+// testing "bound < that + 2" loses none.  Lanes that pass park their rows; the parked rows get their exact sums
+// from the exact tables, which wait in LDS as well (16 KB), and are counted or listed as in the 8-query kernel.
+// In the counting pass the thresholds fall quickly at the start of an item; the bounds are rebuilt from the
+// exact tables at the thresholds of the moment after 4, 16 and 64 groups of a wave.
+constexpr int DQ16_QB = 16;
+constexpr int DQ16_DEPTH = 2;
+constexpr int DQ16_RING = 64 * (DQ16_DEPTH + 1);
+constexpr float DQ16_RANGE = 48.f;
+constexpr float DQ16_ENTRY_MAX = 31.f;
+
+template <int MODE>
+struct __align__(16) DqSmem16 {
+    uint4 lut[4096];                   // lower bounds: row b, 16 slots; slot s = table s >> 2 (four copies); 16 queries per slot
+    uint4 lutx[DQ_M][256];             // exact entries: table t, byte b, 16 queries
+    uint32_t hist[MODE == 0 ? DQ16_QB : 1][DQ_BINS];   // this block's counts of the current item (counting pass)
+    uint32_t thr[DQ16_QB];             // a vector is kept for query q if its sum is below thr[q] (0: empty slot)
+    uint32_t tmin[DQ16_QB][DQ_M];      // minima of the exact tables
+    float off[DQ16_QB], scale[DQ16_QB];
+    uint32_t ring[DQ_WAVES][DQ16_RING];
+    int item;
+};
+
+template <int MODE>
+__global__ __launch_bounds__(DQ_THREADS) void derived_scan16_kernel(DqArgs a) {
+    typedef DqSmem16<MODE> SM;
+    __shared__ SM sm;
+    static_assert(sizeof(SM) <= 160 * 1024, "LDS of a CU");
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = lane_id();
+    const uint32_t lane15 = (uint32_t)lane & 15u;
+    // the walk over the slots of a row is that of the 8-query kernel (same layout of the rows)
+    const uint32_t rot = 2u * ((lane15 >> 2) & 3u);
+    uint32_t bases[2];
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+        bases[g] = (((lane15 + 4u * (2 * g)) & 15u) << 4) | ((((lane15 + 4u * (2 * g + 1)) & 15u) << 4) << 16);
+    const char *lut_bytes = reinterpret_cast<const char *>(sm.lut);
+
+    for (;;) {
+        if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
+        __syncthreads();
+        const int item = sm.item;
+        if (item >= a.nitems) break;
+        const int group = item % a.ngroups, chunk = item / a.ngroups;
+        const int64_t cbeg = (int64_t)chunk * a.chunk_codes;
+        const int64_t cend = cbeg + a.chunk_codes < a.n ? cbeg + a.chunk_codes : a.n;
+        const int ncodes = cend > cbeg ? (int)(cend - cbeg) : 0;
+
+        if (threadIdx.x < DQ16_QB) {
+            const int gq = group * DQ16_QB + threadIdx.x;
+            uint32_t thr = 0;   // empty slot: nothing passes
+            if (gq < a.nq) {
+                const uint32_t b = MODE == 0 ? __hip_atomic_load(&a.g_bound[gq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                             : a.bucket[gq];
+                thr = b + 1u;   // at most DQ_BINS
+            }
+            sm.thr[threadIdx.x] = thr;
+        }
+        if (MODE == 0)
+            for (int i = threadIdx.x; i < DQ16_QB * DQ_BINS; i += DQ_THREADS) (&sm.hist[0][0])[i] = 0u;
+        {   // exact tables of the group's queries: entry (table t, byte b) of all 16 queries in one slot
+            const int b = threadIdx.x >> 2, t = threadIdx.x & 3;
+            uint32_t v[DQ16_QB];
+#pragma unroll
+            for (int q = 0; q < DQ16_QB; ++q) {
+                const int gq = group * DQ16_QB + q;
+                v[q] = gq < a.nq ? (uint32_t)a.qluts[((size_t)gq * DQ_M + t) * 256 + b] : 255u;
+            }
+            sm.lutx[t][b] = make_uint4(v[0] | (v[1] << 8) | (v[2] << 16) | (v[3] << 24), v[4] | (v[5] << 8) | (v[6] << 16) | (v[7] << 24),
+                                       v[8] | (v[9] << 8) | (v[10] << 16) | (v[11] << 24), v[12] | (v[13] << 8) | (v[14] << 16) | (v[15] << 24));
+        }
+        __syncthreads();
+        {   // minima: wave w takes rows (q, t) = 4w .. 4w + 3 of the 64, four entries per lane
+            const uint8_t *xb = reinterpret_cast<const uint8_t *>(sm.lutx);
+            for (int row = wave * 4; row < wave * 4 + 4; ++row) {
+                const int q = row >> 2, t = row & 3;
+                uint32_t mn = 255u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t v = xb[((size_t)t * 256 + lane + 64 * i) * 16 + q];
+                    mn = v < mn ? v : mn;
+                }
+                for (int o = 32; o > 0; o >>= 1) { const uint32_t other = __shfl_xor(mn, o); mn = other < mn ? other : mn; }
+                if (lane == 0) sm.tmin[q][t] = mn;
+            }
+        }
+        __syncthreads();
+        // lower-bound tables from the exact ones at the thresholds of the moment (all threads; ends with a barrier)
+        auto build_bounds = [&]() {
+            if (threadIdx.x < DQ16_QB) {
+                const int q = threadIdx.x;
+                const uint32_t off = sm.tmin[q][0] + sm.tmin[q][1] + sm.tmin[q][2] + sm.tmin[q][3];
+                const uint32_t thr = sm.thr[q];
+                float scale = 0.f;   // every bound 0: every code goes to the exact test
+                if (thr > off) scale = DQ16_RANGE / (float)(thr - off);
+                sm.off[q] = (float)off;
+                sm.scale[q] = scale;
+            }
+            __syncthreads();
+            {
+                const int b = threadIdx.x >> 2, t = threadIdx.x & 3;
+                const uint4 x = sm.lutx[t][b];
+                const uint32_t xw[4] = {x.x, x.y, x.z, x.w};
+                uint32_t l[DQ16_QB];
+#pragma unroll
+                for (int q = 0; q < DQ16_QB; ++q) {
+                    const uint32_t e = (xw[q >> 2] >> (8 * (q & 3))) & 255u;
+                    const float v = (float)(e - sm.tmin[q][t]) * sm.scale[q];
+                    l[q] = sm.thr[q] != 0u ? (uint32_t)fminf(floorf(v), DQ16_ENTRY_MAX) : (uint32_t)DQ16_ENTRY_MAX;
+                }
+                const uint4 pk = make_uint4(l[0] | (l[1] << 8) | (l[2] << 16) | (l[3] << 24), l[4] | (l[5] << 8) | (l[6] << 16) | (l[7] << 24),
+                                            l[8] | (l[9] << 8) | (l[10] << 16) | (l[11] << 24), l[12] | (l[13] << 8) | (l[14] << 16) | (l[15] << 24));
+#pragma unroll
+                for (int c = 0; c < 4; ++c) sm.lut[b * 16 + t * 4 + c] = pk;
+            }
+            __syncthreads();
+        };
+        build_bounds();
+
+        const uint8_t *chunk_ptr = a.codes + cbeg * 8;
+        const int nfull = ncodes / DQ_SUB;                       // sub-tiles with every code present
+        const int nsub = (ncodes + DQ_SUB - 1) / DQ_SUB;         // the last one may be ragged
+        uint32_t tau[4];   // 0x80 minus the threshold (in units of the bounds) of the 16 queries, four per register
+        auto reload_tau = [&]() {
+            const int ql = lane & (DQ16_QB - 1);
+            const uint32_t thr = sm.thr[ql];
+            const float t = floorf(((float)thr - 1.f - sm.off[ql]) * sm.scale[ql]) + 2.f;
+            const uint32_t t8 = thr != 0u ? (uint32_t)fmaxf(fminf(t, 127.f), 0.f) : 0u;
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                tau[p] = 0x80808080u - (__builtin_amdgcn_readlane(t8, 4 * p) | (__builtin_amdgcn_readlane(t8, 4 * p + 1) << 8) |
+                                        (__builtin_amdgcn_readlane(t8, 4 * p + 2) << 16) | (__builtin_amdgcn_readlane(t8, 4 * p + 3) << 24));
+        };
+        typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+        typedef const __attribute__((address_space(1))) v4u *global_v4u;
+        // the two codes at rows pos, pos + 1 of the chunk (zeros for rows past its end)
+        auto load_pair = [&](int pos) -> uint4 {
+            uint4 c = make_uint4(0, 0, 0, 0);
+            const uint8_t *p = chunk_ptr + (size_t)pos * 8;
+            if (pos + 2 <= ncodes) {
+                c = *reinterpret_cast<const uint4 *>(p);
+            } else if (pos < ncodes) {
+                const uint2 half = *reinterpret_cast<const uint2 *>(p);
+                c.x = half.x; c.y = half.y;
+            }
+            return c;
+        };
+        // the eight table reads of the lane's two codes (four tables each, in the lane's rotated order)
+        auto issue = [&](const uint4 c, uint4 (&v)[8]) {
+            uint32_t w[4] = {c.x, c.y, c.z, c.w};
+            rot8(w[0], w[1], (rot & 4u) != 0, rot & 3u);
+            rot8(w[2], w[3], (rot & 4u) != 0, rot & 3u);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const uint32_t word = w[2 * h + (s >> 1)];
+                    const uint32_t off = (s & 1) ? lut_offset<2>(word, bases[s >> 1]) : lut_offset<0>(word, bases[s >> 1]);
+                    v[4 * h + s] = *reinterpret_cast<const uint4 *>(lut_bytes + off);
+                }
+            }
+        };
+        // One sub-tile whose reads are on their way: the bounds of the two codes for the 16 queries (four bytes per
+        // word), one add per word against the thresholds, the rows of the lanes with a bound below one parked.
+        int ring_cnt = 0;
+        auto finish = [&](const uint4 (&v)[8], const int sidx) {
+            uint32_t keep = 0x80808080u;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                keep &= v[4 * h].x + v[4 * h + 1].x + v[4 * h + 2].x + v[4 * h + 3].x + tau[0];
+                keep &= v[4 * h].y + v[4 * h + 1].y + v[4 * h + 2].y + v[4 * h + 3].y + tau[1];
+                keep &= v[4 * h].z + v[4 * h + 1].z + v[4 * h + 2].z + v[4 * h + 3].z + tau[2];
+                keep &= v[4 * h].w + v[4 * h + 1].w + v[4 * h + 2].w + v[4 * h + 3].w + tau[3];
+            }
+            const uint64_t hit = __ballot(keep != 0x80808080u);
+            if (__builtin_expect(hit != 0ull, 0)) {
+                if ((hit >> lane) & 1ull) sm.ring[wave][ring_cnt + mask_prefix(hit)] = (uint32_t)(sidx * DQ_SUB + lane * 2);
+                ring_cnt += __popcll(hit);
+            }
+        };
+        auto scan_sub = [&](const uint4 c, const int sidx) {
+            uint4 v[8];
+            issue(c, v);
+            asm volatile("" : : : "memory");   // all eight reads are issued before the first add
+            finish(v, sidx);
+        };
+
+        // Parked rows, 64 at a time: the exact sums of the two codes of a row for the 16 queries (the 16 bytes of a
+        // slot split into even and odd queries, two 16-bit sums per word: word p of `ev` holds queries 4p and 4p + 2,
+        // word p of `od` queries 4p + 1 and 4p + 3), the test against the thresholds of now, and for every
+        // (code, query) that passes the bucket count or the list append.
+        auto flush = [&](const int count) {
+            const uint32_t thr_lane = sm.thr[lane & (DQ16_QB - 1)];
+            uint32_t comp_ev[4], comp_od[4];   // 0x8000 - threshold (thresholds are at most 1024)
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                comp_ev[p] = 0x80008000u - (__builtin_amdgcn_readlane(thr_lane, 4 * p) | (__builtin_amdgcn_readlane(thr_lane, 4 * p + 2) << 16));
+                comp_od[p] = 0x80008000u - (__builtin_amdgcn_readlane(thr_lane, 4 * p + 1) | (__builtin_amdgcn_readlane(thr_lane, 4 * p + 3) << 16));
+            }
+            for (int base = 0; base < count; base += 64) {
+                const bool have = base + lane < count;
+                const int pos = have ? (int)sm.ring[wave][base + lane] : ncodes;
+                const uint4 c = load_pair(pos);
+                uint32_t ev[2][4], od[2][4];
+                uint32_t m = 0;   // bit h * 16 + q: code h of the row is wanted by query q
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t w0 = h == 0 ? c.x : c.z, w1 = h == 0 ? c.y : c.w;
+                    const uint32_t idx[4] = {w0 & 255u, (w0 >> 16) & 255u, w1 & 255u, (w1 >> 16) & 255u};
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) { ev[h][p] = 0; od[h][p] = 0; }
+#pragma unroll
+                    for (int t = 0; t < DQ_M; ++t) {
+                        const uint4 x = sm.lutx[t][idx[t]];
+                        const uint32_t xw[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                        for (int p = 0; p < 4; ++p) {
+                            ev[h][p] += xw[p] & 0x00ff00ffu;
+                            od[h][p] += (xw[p] >> 8) & 0x00ff00ffu;
+                        }
+                    }
+                    if (pos + h < ncodes) {
+#pragma unroll
+                        for (int p = 0; p < 4; ++p) {
+                            // bit 15 / 31 of sum + (0x8000 - threshold) is clear iff the sum is below the threshold
+                            const uint32_t fe = ~(ev[h][p] + comp_ev[p]), fo = ~(od[h][p] + comp_od[p]);
+                            const uint32_t nib = ((fe >> 15) & 1u) | (((fo >> 15) & 1u) << 1) | (((fe >> 31) & 1u) << 2) | (((fo >> 31) & 1u) << 3);
+                            m |= nib << (h * 16 + 4 * p);
+                        }
+                    }
+                }
+                if (MODE == 0) {
+                    uint32_t bits = m;
+                    while (bits != 0u) {
+                        const int bit = __builtin_ctz(bits);
+                        bits &= bits - 1u;
+                        const int q = bit & 15, h = bit >> 4, p = q >> 2;
+                        uint32_t word = (q & 1) ? (h == 0 ? od[0][0] : od[1][0]) : (h == 0 ? ev[0][0] : ev[1][0]);
+#pragma unroll
+                        for (int i = 1; i < 4; ++i)
+                            word = p == i ? ((q & 1) ? (h == 0 ? od[0][i] : od[1][i]) : (h == 0 ? ev[0][i] : ev[1][i])) : word;
+                        const uint32_t sum = (q & 2) ? word >> 16 : word & 0xffffu;
+                        atomicAdd(&sm.hist[q][sum], 1u);
+                    }
+                } else {
+                    if (__ballot(m != 0u) == 0ull) continue;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                        for (int q = 0; q < DQ16_QB; ++q) {
+                            const bool pass = ((m >> (h * 16 + q)) & 1u) != 0u;
+                            const uint64_t mask = __ballot(pass);
+                            if (mask != 0ull) {
+                                const uint32_t word = (q & 1) ? od[h][q >> 2] : ev[h][q >> 2];
+                                const uint32_t sum = (q & 2) ? word >> 16 : word & 0xffffu;
+                                const int gq = group * DQ16_QB + q;
+                                const int first = __builtin_ctzll(mask);
+                                uint32_t slot = 0;
+                                if (lane == first) slot = atomicAdd(&a.cand_cnt[gq], (uint32_t)__popcll(mask));
+                                slot = __shfl(slot, first);
+                                // (the list holds exactly the vectors the first pass counted; the
+                                // comparison only keeps a disagreement from writing past it)
+                                const uint64_t at = a.cand_off[gq] + slot + (uint32_t)mask_prefix(mask);
+                                if (pass && at < a.cand_off[gq + 1]) a.cand[at] = ((uint64_t)sum << 32) | (uint32_t)(cbeg + pos + h);
+                            }
+                        }
+                    }
+                }
+            }
+        };
+
+        // Counting pass: the bound of a query is lowered from the block's own counts while the item
+        // runs (one wave per query), early and then every 16 groups.
+        auto refresh = [&]() {
+            const int q = wave;
+            if (group * DQ16_QB + q >= a.nq) return;
+            const int b = first_bin_reaching([&](int i) { return sm.hist[q][i]; }, (uint32_t)a.r2, nullptr);
+            if (b < DQ_BINS && lane == 0) atomicMin(&sm.thr[q], (uint32_t)b + 1u);
+        };
+
+        const int ngroups_t = nfull / DQ16_DEPTH;
+        int it = 0;
+        uint4 cur[DQ16_DEPTH];
+#pragma unroll
+        for (int u = 0; u < DQ16_DEPTH; ++u) cur[u] = make_uint4(0, 0, 0, 0);
+        const uint8_t *gp = chunk_ptr + (size_t)wave * (DQ16_DEPTH * DQ_SUB * 8) + lane * 16;
+        auto load_group_sub = [&](const uint8_t *p, int u) -> uint4 {
+            const v4u v = *(global_v4u)(p + u * (DQ_SUB * 8));
+            return make_uint4(v.x, v.y, v.z, v.w);
+        };
+        if (wave < ngroups_t) {
+#pragma unroll
+            for (int u = 0; u < DQ16_DEPTH; ++u) cur[u] = load_group_sub(gp, u);
+        }
+        reload_tau();
+        for (int g = wave; g < ngroups_t; g += DQ_WAVES) {
+            const bool more = g + DQ_WAVES < ngroups_t;
+            gp += (size_t)DQ_WAVES * (DQ16_DEPTH * DQ_SUB * 8);
+            // the table reads of sub-tile u + 1 are issued before the sums of sub-tile u are formed
+            uint4 va[8], vb[8];
+            issue(cur[0], va);
+            if (more) cur[0] = load_group_sub(gp, 0);
+#pragma unroll
+            for (int u = 0; u < DQ16_DEPTH; ++u) {
+                if (u + 1 < DQ16_DEPTH) {
+                    issue(cur[u + 1], (u & 1) ? va : vb);
+                    if (more) cur[u + 1] = load_group_sub(gp, u + 1);
+                }
+                asm volatile("" : : : "memory");
+                finish((u & 1) ? vb : va, g * DQ16_DEPTH + u);
+            }
+            if (__builtin_expect(ring_cnt >= 64, 0)) {
+                const int whole = ring_cnt & ~63;
+                flush(whole);
+                for (int i = lane; i < ring_cnt - whole; i += 64) {   // the rest moves to the front
+                    const uint32_t v = sm.ring[wave][whole + i];
+                    sm.ring[wave][i] = v;
+                }
+                ring_cnt -= whole;
+            }
+            if (MODE == 0) {
+                if ((it & (it + 1)) == 0 || (it & 15) == 15) refresh();
+                // every wave of the block runs iteration `it` iff its last wave does: then all of them meet here
+                if ((it == 3 || it == 15 || it == 63) && DQ_WAVES * it + DQ_WAVES - 1 < ngroups_t) {
+                    __syncthreads();
+                    build_bounds();
+                }
+                reload_tau();
+            }
+            ++it;
+        }
+        // sub-tiles past the last whole group, the ragged one included
+        for (int sidx = ngroups_t * DQ16_DEPTH + wave; sidx < nsub; sidx += DQ_WAVES)
+            scan_sub(load_pair(sidx * DQ_SUB + lane * 2), sidx);
+        if (ring_cnt > 0) flush(ring_cnt);
+
+        if (MODE == 0) {
+            // the block's counts join the query's device-wide buckets, whose bound then serves
+            // every block that starts an item of this query later
+            __syncthreads();
+            for (int i = threadIdx.x; i < DQ16_QB * DQ_BINS; i += DQ_THREADS) {
+                const int q = i / DQ_BINS, bin = i % DQ_BINS;
+                const uint32_t v = sm.hist[q][bin];
+                const int gq = group * DQ16_QB + q;
+                if (v != 0u && gq < a.nq) atomicAdd(&a.g_hist[(size_t)gq * DQ_BINS + bin], v);
+            }
+            __syncthreads();
+            if (group * DQ16_QB + wave < a.nq) {
+                const int gq = group * DQ16_QB + wave;
+                const uint32_t *gh = a.g_hist + (size_t)gq * DQ_BINS;
+                const int b = first_bin_reaching(
+                    [&](int i) { return __hip_atomic_load(&gh[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); },
+                    (uint32_t)a.r2, nullptr);
+                if (b < DQ_BINS && lane == 0) atomicMin(&a.g_bound[gq], (uint32_t)b);
+            }
+        }
+    }
+}
+
 __global__ void derived_init_kernel(uint32_t *work_counter, uint32_t *g_hist, size_t nhist, uint32_t *g_bound,
                                     uint32_t *cand_cnt, int nq) {
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
@@ -493,25 +861,40 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(codes16);
     const int dsub = d / DQ_M;
     hipStream_t s = ctx->stream;
-    const int ngroups = (nq + DQ_QB - 1) / DQ_QB;
+    // 512 queries and more: the collecting pass takes 16 queries per pass over the codes (PQ_SCAN_Q8=0: 8, as for
+    // fewer queries).  The counting pass stays with 8: its bound is the loose one of the block's own counts for most of
+    // an item, so a large share of the codes needs exact sums, which the 8-query loop has at hand and the 16-query
+    // loop fetches again (measured: 3.7 ms against 5.0 ms, 4.7 ms with a first bound from a sample).
+    const bool wide = nq >= 512 && env_int("PQ_SCAN_Q8", 1) != 0;
 
-    // work items: chunk of codes x group of 8 queries, chunk-major (blocks running together share chunks)
-    const int64_t block_tile = (int64_t)DQ_SUB * DQ_WAVES;
-    int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
-    if (nblocks_max < 1) nblocks_max = 1;
-    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + ngroups - 1) / ngroups;
-    const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
-    if (nchunks > max_by_n) nchunks = max_by_n;
-    const int64_t min_chunks = (n + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits
-    if (nchunks < min_chunks) nchunks = min_chunks;
-    if (nchunks < 1) nchunks = 1;
-    int64_t chunk_codes = (n + nchunks - 1) / nchunks;
-    chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
-    if (chunk_codes < block_tile) chunk_codes = block_tile;
-    nchunks = n > 0 ? (n + chunk_codes - 1) / chunk_codes : 0;
-    const int64_t nitems = nchunks * ngroups;
-    if (nitems > 0x3fffffff) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: too many work items (%lld)", (long long)nitems);
-    const int nblocks = (int)(nitems < nblocks_max ? nitems : nblocks_max);
+    // work items: chunk of codes x group of 8 or 16 queries, chunk-major (blocks running together share chunks)
+    struct Geometry { int ngroups, nblocks; int64_t nchunks, chunk_codes, nitems; };
+    auto geometry = [&](int qb) {
+        Geometry g;
+        g.ngroups = (nq + qb - 1) / qb;
+        const int64_t block_tile = (int64_t)DQ_SUB * DQ_WAVES;
+        int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+        if (nblocks_max < 1) nblocks_max = 1;
+        int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + g.ngroups - 1) / g.ngroups;
+        const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
+        if (nchunks > max_by_n) nchunks = max_by_n;
+        const int64_t min_chunks = (n + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits
+        if (nchunks < min_chunks) nchunks = min_chunks;
+        if (nchunks < 1) nchunks = 1;
+        int64_t chunk_codes = (n + nchunks - 1) / nchunks;
+        chunk_codes = (chunk_codes + block_tile - 1) / block_tile * block_tile;
+        if (chunk_codes < block_tile) chunk_codes = block_tile;
+        g.chunk_codes = chunk_codes;
+        g.nchunks = n > 0 ? (n + chunk_codes - 1) / chunk_codes : 0;
+        g.nitems = g.nchunks * g.ngroups;
+        g.nblocks = (int)(g.nitems < nblocks_max ? g.nitems : nblocks_max);
+        return g;
+    };
+    const Geometry g_count = geometry(DQ_QB), g_collect = geometry(wide ? DQ16_QB : DQ_QB);
+    if (g_count.nitems > 0x3fffffff) return fail(ctx, PQ_EUNSUPPORTED, "derived_search: too many work items (%lld)", (long long)g_count.nitems);
+    auto bind_geometry = [&](DqArgs &a, const Geometry &g) {
+        a.chunk_codes = g.chunk_codes; a.nchunks = (int)g.nchunks; a.ngroups = g.ngroups; a.nitems = (int)g.nitems;
+    };
 
     // workspace, first part: tables and counts
     size_t off = 0;
@@ -548,8 +931,8 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     if (rc) return rc;
 
     DqArgs a;
-    a.codes = codes; a.n = n; a.chunk_codes = chunk_codes; a.nchunks = (int)nchunks; a.ngroups = ngroups;
-    a.nitems = (int)nitems; a.nq = nq; a.r2 = r2;
+    a.codes = codes; a.n = n; a.nq = nq; a.r2 = r2;
+    bind_geometry(a, g_count);
     a.qluts = ws + o_qluts;
     a.work_counter = (uint32_t *)(ws + o_counter);
     a.g_hist = (uint32_t *)(ws + o_hist);
@@ -560,8 +943,8 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, a.g_hist, (size_t)nq * DQ_BINS, a.g_bound, nullptr, nq);
     PQ_HIP(ctx, hipGetLastError());
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
-    if (nblocks > 0) {
-        derived_scan_kernel<0><<<nblocks, DQ_THREADS, 0, s>>>(a);
+    if (g_count.nblocks > 0) {
+        derived_scan_kernel<0><<<g_count.nblocks, DQ_THREADS, 0, s>>>(a);
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) {
@@ -609,8 +992,10 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     a.cand = (uint64_t *)(ws + o_cand);
     derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, nullptr, 0, nullptr, a.cand_cnt, nq);
     PQ_HIP(ctx, hipGetLastError());
-    if (nblocks > 0) {
-        derived_scan_kernel<1><<<nblocks, DQ_THREADS, 0, s>>>(a);
+    bind_geometry(a, g_collect);
+    if (g_collect.nblocks > 0) {
+        if (wide) derived_scan16_kernel<1><<<g_collect.nblocks, DQ_THREADS, 0, s>>>(a);
+        else derived_scan_kernel<1><<<g_collect.nblocks, DQ_THREADS, 0, s>>>(a);
         PQ_HIP(ctx, hipGetLastError());
     }
     // Step 2

@@ -282,34 +282,39 @@ __global__ void ivf_pair_lists_kernel(const int32_t *__restrict__ probes, const 
     qlists[q] = run;
 }
 
-// single block: exclusive scan of qlists -> qlist_off[nq+1], then absolute first list of every pair
-__global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__restrict__ qlists, int nq, int nprobe,
-                                                              uint32_t *qlist_off, uint32_t *pair_out) {
-    __shared__ uint32_t scan[1024];
+// single block: exclusive scan of qlists -> qlist_off[nq+1] (1024 values per round: shuffles inside the waves, the
+// 16 wave totals through LDS)
+__global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__restrict__ qlists, int nq, uint32_t *qlist_off) {
+    __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t carry;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) carry = 0;
     __syncthreads();
     for (int q0 = 0; q0 < nq; q0 += 1024) {
         const int q = q0 + tid;
         const uint32_t v = q < nq ? qlists[q] : 0u;
-        scan[tid] = v;
-        __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {
-            const uint32_t add = tid >= o ? scan[tid - o] : 0u;
-            __syncthreads();
-            scan[tid] += add;
-            __syncthreads();
+        uint32_t incl = v;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
         }
-        if (q < nq) qlist_off[q] = carry + scan[tid] - v;
+        if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        if (tid == 1023) carry += scan[1023];
+        uint32_t before = carry;
+        for (int w = 0; w < wave; ++w) before += wave_tot[w];
+        if (q < nq) qlist_off[q] = before + incl - v;
+        __syncthreads();
+        if (tid == 1023) carry = before + incl;
         __syncthreads();
     }
     if (tid == 0) qlist_off[nq] = carry;
-    __syncthreads();
-    const size_t npairs = (size_t)nq * nprobe;
-    for (size_t p = tid; p < npairs; p += 1024) pair_out[p] += qlist_off[p / nprobe];
+}
+
+// absolute first result list of every (query, probe) pair: its place within the query's lists plus the query's first list
+__global__ void ivf_pair_abs_kernel(const uint32_t *__restrict__ qlist_off, size_t npairs, int nprobe, uint32_t *pair_out) {
+    const size_t p = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < npairs) pair_out[p] += qlist_off[p / nprobe];
 }
 
 // First bound per query: float ADC (table order) of up to IVF_SEED_CODES codes taken from the
@@ -536,7 +541,8 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(pair_off, nc, item_off, L->list_offsets, nlist,
                                                                   rows_per_16b, item_qb, items);
         ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
-        ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, nprobe, qlist_off, pair_out);
+        ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, qlist_off);
+        ivf_pair_abs_kernel<<<(unsigned)(((size_t)nqb * nprobe + 255) / 256), 256, 0, s>>>(qlist_off, (size_t)nqb * nprobe, nprobe, pair_out);
         PQ_HIP(ctx, hipGetLastError());
         // Scan step, seeded with a first bound per query
         float *tau0 = (float *)(ws + o_tau0);

@@ -175,6 +175,27 @@ __device__ __forceinline__ int ivf_chunks_of(int64_t size) {
     return (int)(nc < 1 ? 1 : (nc > IVF_MAX_CHUNKS ? IVF_MAX_CHUNKS : nc));
 }
 
+// One round of an exclusive scan by a block of 1024 threads: the sum of the values of the threads before this one
+// plus *carry, which is then advanced by the block's total (shuffles inside the waves, the 16 wave totals through
+// LDS; three barriers).
+__device__ __forceinline__ uint32_t block_scan_round(uint32_t v, uint32_t *wave_tot, uint32_t *carry) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t before = *carry;
+    for (int w = 0; w < wave; ++w) before += wave_tot[w];
+    __syncthreads();
+    if (tid == 1023) *carry = before + incl;
+    __syncthreads();
+    return before + incl - v;
+}
+
 // Single block.  From the number of pairs per list: where each list's pairs start
 // (pair_off), how many chunks it is cut into (nc), where its items start in the item table
 // (item_off; lists of a larger size class come first) and the number of items.
@@ -182,7 +203,7 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
                                                         const int64_t *__restrict__ list_offsets, int nlist,
                                                         uint32_t *pair_off, uint32_t *nc_out, uint32_t *item_off,
                                                         uint32_t *nitems_dev, uint32_t qb) {
-    __shared__ uint32_t scan[1024];
+    __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t cls_items[32], cls_base[32], cls_cursor[32];
     __shared__ uint32_t carry;
     const int tid = threadIdx.x;
@@ -192,26 +213,17 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
     for (int l0 = 0; l0 < nlist; l0 += 1024) {
         const int l = l0 + tid;
         const uint32_t v = l < nlist ? np[l] : 0u;
-        scan[tid] = v;
-        __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {
-            const uint32_t add = tid >= o ? scan[tid - o] : 0u;
-            __syncthreads();
-            scan[tid] += add;
-            __syncthreads();
-        }
+        const uint32_t before = block_scan_round(v, wave_tot, &carry);
         if (l < nlist) {
-            pair_off[l] = carry + scan[tid] - v;
+            pair_off[l] = before;
             const int64_t size = list_offsets[l + 1] - list_offsets[l];
             const int nc = v > 0 ? ivf_chunks_of(size) : 0;
             nc_out[l] = (uint32_t)nc;
             const uint32_t items = ((v + qb - 1) / qb) * (uint32_t)nc;
             if (items > 0) atomicAdd(&cls_items[63 - __builtin_clzll((unsigned long long)size)], items);
         }
-        __syncthreads();
-        if (tid == 1023) carry += scan[1023];
-        __syncthreads();
     }
+    __syncthreads();
     if (tid == 0) {
         pair_off[nlist] = carry;
         uint32_t run = 0;
@@ -287,26 +299,13 @@ __global__ void ivf_pair_lists_kernel(const int32_t *__restrict__ probes, const 
 __global__ __launch_bounds__(1024) void ivf_qlist_scan_kernel(const uint32_t *__restrict__ qlists, int nq, uint32_t *qlist_off) {
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t carry;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     if (tid == 0) carry = 0;
     __syncthreads();
     for (int q0 = 0; q0 < nq; q0 += 1024) {
         const int q = q0 + tid;
-        const uint32_t v = q < nq ? qlists[q] : 0u;
-        uint32_t incl = v;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t up = __shfl_up(incl, o);
-            if (lane >= o) incl += up;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        uint32_t before = carry;
-        for (int w = 0; w < wave; ++w) before += wave_tot[w];
-        if (q < nq) qlist_off[q] = before + incl - v;
-        __syncthreads();
-        if (tid == 1023) carry = before + incl;
-        __syncthreads();
+        const uint32_t before = block_scan_round(q < nq ? qlists[q] : 0u, wave_tot, &carry);
+        if (q < nq) qlist_off[q] = before;
     }
     if (tid == 0) qlist_off[nq] = carry;
 }

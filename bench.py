@@ -142,7 +142,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic("scan_f32_pq8x8_config1_pmc.txt"),
                      "kernel": ("scan_tuned_kernel<F32Q_M8 (8x8 float, 8-bit lower bounds, 16 queries per pass), lists for top<=%d, groups of 2 sub-tiles>"
-                                if args.nq >= 512 else
+                                if args.nq >= 249 else
                                 "scan_tuned_kernel<F32P_M8 (8x8 float, 16-bit lower bounds, 8 queries per pass), lists for top<=%d>")
                                % (128 if args.topk <= 128 else 1024), "kernel_ms": scan_ms,
                      "algorithmic_bytes": alg_bytes,
@@ -153,7 +153,7 @@ def main():
                                       "achieved": args.n * ((args.nq + 15) // 16) / 128 * 376 / 1e9,
                                       "peak": 1024 * scan_ms * 1e-3 * 2.4e9 / 1e9,
                                       "frac": args.n * ((args.nq + 15) // 16) / 128 * 376 / (1024 * scan_ms * 1e-3 * 2.4e9)}
-                                     if args.nq >= 512 and args.n >= 65536 else None),
+                                     if args.nq >= 249 and args.n >= 65536 else None),
                      "note": "algorithmic bytes = 8 B per code per query pass; one pass over a chunk serves 8 or 16 queries and "
                              "concurrent blocks share chunks through L2, so the HBM bytes really moved (traffic) are far below "
                              "the algorithmic figure and frac exceeds 1; the kernel is bound by LDS reads and vector issue"},
@@ -188,7 +188,7 @@ def main():
                             "dtype": "u8 tables, integer sums", "workload": "PQ 16x4 packed codes (BASELINE config 2): "
                             "tables, qmax pre-scan, 8-bit tables, integer scan top-%d, fp32 rerank top-%d" % (args.cand, args.topk),
                             "roofline": {"bound": "hbm", "achieved": ach16, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": ("scan_tuned_kernel<U4Q_M16 (8-bit lower bounds, 16 queries per pass), lists for top<=%d>" if args.nq >= 512
+                                         "frac": ach16 / HBM_PEAK_GBS, "kernel": ("scan_tuned_kernel<U4Q_M16 (8-bit lower bounds, 16 queries per pass), lists for top<=%d>" if args.nq >= 249
                                                     else "scan_tuned_kernel<U4_M16, lists for top<=%d>") % (128 if args.cand <= 128 else 1024), "kernel_ms": scan16_ms,
                                          "traffic": read_traffic("scan_u4_pq16x4_config2_pmc.txt")}}
         del codes4

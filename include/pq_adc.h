@@ -131,8 +131,8 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
  * distances (the pruning idea of Section 4.2: small quantised tables, exact distances only
  * for the codes they cannot rule out) and forms float sums only for the rest; the result is
  * that of the plain definition.  The bounds are 16-bit sums for 8 queries per pass over the
- * codes, or, for m = 8 and 512 queries and more, 8-bit sums for 16 queries per pass.
- * Integer sums are exact; with 512 queries and more and n >= 65536 the integer scan also
+ * codes, or, for m = 8 and 249 queries and more, 8-bit sums for 16 queries per pass.
+ * Integer sums are exact; with 249 queries and more and n >= 65536 the integer scan also
  * runs on 8-bit lower bounds of its sums (16 queries per pass) and adds up the exact sums
  * only for the codes that pass.
  * Switches for tests and tuning, read from the environment at each call (unset = default):

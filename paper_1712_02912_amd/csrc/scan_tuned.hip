@@ -1905,9 +1905,11 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // pay for the preparation (a bound per query from the first PRUNE_INIT codes, then the tables).
     const bool prune = (kind == KIND_F32_M8 || kind == KIND_F32_M16) && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
     const int tables = kind == KIND_F32_M16 ? 16 : 8;
-    // eight tables and enough queries to fill the GPU with groups of 16: 8-bit lower bounds, 16 queries per pass
-    // (PQ_SCAN_Q8=0: 16-bit lower bounds, 8 queries per pass, as for fewer queries)
-    const bool many16 = (nq + 15) / 16 >= STREAM_GROUPS && env_int("PQ_SCAN_Q8", 1) != 0;
+    // eight tables and too many queries for the streaming shape (32 groups of 8 and more, i.e. 249 queries): 8-bit
+    // lower bounds, 16 queries per pass (PQ_SCAN_Q8=0: 16-bit lower bounds, 8 queries per pass).  Measured on 25 M
+    // codes: 256 queries 1.69 -> 1.28 ms, 384 queries 2.28 -> 1.51 ms; 128 queries in the streaming shape 0.62 ms
+    // against 1.21 ms with this loop.
+    const bool many16 = (nq + 7) / 8 >= STREAM_GROUPS && env_int("PQ_SCAN_Q8", 1) != 0;
     const bool q8 = prune && tables == 8 && many16;
     if (prune) kind = q8 ? KIND_F32Q_M8 : (tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8);
     // the integer scan likewise: with a first bound and enough queries, its loop runs on 8-bit lower bounds of
@@ -1916,7 +1918,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     if (u4q) kind = KIND_U4Q_M16;
     const int qb = q8 || u4q ? 16 : (is_u4 || prune ? 8 : 4);
     const int cb = kind == KIND_F32_M16 || kind == KIND_F32P_M16 ? 16 : 8;
-    const int depth = (nq + qb - 1) / qb < STREAM_GROUPS ? 8 : 2;
+    const int depth = !(q8 || u4q) && (nq + qb - 1) / qb < STREAM_GROUPS ? 8 : 2;
     const int tile = 64 * (16 / cb) * depth;   // codes per wave group (DEPTH sub-tiles)
     const bool small = topk <= 128;
     const int kpad = small ? 128 : 1024;
@@ -1955,7 +1957,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     // Few query groups over a large database: the first bound comes from a larger part of the codes.
     // Measured optimum (10^7 .. 10^9 codes, 1 .. 200 queries): about 64 M code evaluations over all
     // queries of the call, at most a thirty-second of the database per query.
-    const bool few_groups = ngroups < STREAM_GROUPS;
+    const bool few_groups = !(q8 || u4q) && ngroups < STREAM_GROUPS;   // (the 16-query loops start at 16 groups)
     int64_t seed_codes_f32 = SEED_CODES_STREAM;   // (integer scans use the same count)
     if (few_groups) {
         int64_t want = ((int64_t)64 << 20) / (nq > 0 ? nq : 1);
@@ -2037,7 +2039,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
-    rc = launch_by_kind(ctx, kind, small, ngroups < STREAM_GROUPS, a, nblocks);
+    rc = launch_by_kind(ctx, kind, small, few_groups, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));

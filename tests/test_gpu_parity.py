@@ -592,7 +592,7 @@ def many_queries(r, nq, spread=50.0, offset=200.0):
 
 
 @pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_000, 513, 1000),
-                                       (75_001, 530, 129), (100_003, 512, 512)])
+                                       (75_001, 530, 129), (100_003, 512, 512), (80_001, 249, 100), (66_000, 250, 1000)])
 def test_scan_f32_16_queries_per_pass_sizes(ctx, n, nq, topk):
     r = np.random.default_rng(n + nq)
     codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
@@ -647,7 +647,7 @@ def quantized_like_tables(r, nq):
 
 
 @pytest.mark.parametrize("n,nq,topk", [(65536, 512, 100), (70_001, 520, 1), (90_003, 777, 128), (66_001, 513, 1000),
-                                       (75_001, 530, 129), (100_003, 512, 512)])
+                                       (75_001, 530, 129), (100_003, 512, 512), (80_001, 249, 100), (66_000, 250, 1000)])
 def test_scan_u4_16_queries_per_pass_sizes(ctx, n, nq, topk):
     r = np.random.default_rng(n + nq)
     packed = r.integers(0, 256, (n, 8), dtype=np.uint8)

@@ -178,7 +178,7 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
  * with -1 (PQ_ESHAPE if a query has more than cand_cap candidates).
  * The capped-buckets lists of the thesis are replaced by two passes over the codes (bucket
  * counts, then the ids of the buckets 0..b*); between them the call waits for the stream and
- * reads the nq list sizes back to size its workspace.  With 512 queries and more the second pass
+ * reads the nq list sizes back to size its workspace.  With 640 queries and more the second pass
  * takes 16 queries per pass over the codes (lower bounds of the integer sums in the loop, exact
  * sums for the codes that pass; PQ_SCAN_Q8=0: 8 queries per pass as for fewer queries).
  * Covered: m = 4, d % 4 == 0, d <= 4096, 256 <= k <= 65536, 1 <= topk <= 128, r2 >= 1,

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(DQ_THREADS) void derived_scan_kernel(DqArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The same two passes for many queries (512 and more): 16 queries per pass over the codes.  The entries of the
+// The same loop for many queries (640 and more; used by the collecting pass): 16 queries per pass over the codes.  The entries of the
 // 8-bit tables are bytes, so the entries of 16 queries for one (table, byte) fill a 16-byte LDS slot exactly;
 // their sums of four do not fit a byte, so the scan loop adds 5-bit lower bounds instead,
 //   L[t][b] = min(31, floor((Q[t][b] - min_b Q[t][b]) * scale)),   scale = DQ16_RANGE / (thr - off),
@@ -861,11 +861,12 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     const uint8_t *codes = reinterpret_cast<const uint8_t *>(codes16);
     const int dsub = d / DQ_M;
     hipStream_t s = ctx->stream;
-    // 512 queries and more: the collecting pass takes 16 queries per pass over the codes (PQ_SCAN_Q8=0: 8, as for
-    // fewer queries).  The counting pass stays with 8: its bound is the loose one of the block's own counts for most of
+    // 640 queries and more (measured on 25 M codes: 512 queries 4.45 -> 4.90 ms per call, 700 queries 6.23 -> 6.06 ms,
+    // 1000 queries 8.30 -> 7.87 ms): the collecting pass takes 16 queries per pass over the codes (PQ_SCAN_Q8=0: 8, as
+    // for fewer queries).  The counting pass stays with 8: its bound is the loose one of the block's own counts for most of
     // an item, so a large share of the codes needs exact sums, which the 8-query loop has at hand and the 16-query
     // loop fetches again (measured: 3.7 ms against 5.0 ms, 4.7 ms with a first bound from a sample).
-    const bool wide = nq >= 512 && env_int("PQ_SCAN_Q8", 1) != 0;
+    const bool wide = nq >= 640 && env_int("PQ_SCAN_Q8", 1) != 0;
 
     // work items: chunk of codes x group of 8 or 16 queries, chunk-major (blocks running together share chunks)
     struct Geometry { int ngroups, nblocks; int64_t nchunks, chunk_codes, nitems; };

@@ -171,8 +171,8 @@ def test_derived_search_bench_configuration_sampled(ctx):
         check_float_topk_ranked(gd[q], gi[q], od[i], oi[i])
 
 
-# ------------------------------------------------------------ 512 queries and more: 16 queries per pass over the codes
-@pytest.mark.parametrize("n,nq,r2,topk", [(30_003, 520, 300, 10), (8_193, 513, 2000, 50), (300, 512, 1000, 5),
+# ------------------------------------------------------------ 640 queries and more: 16 queries per pass over the codes
+@pytest.mark.parametrize("n,nq,r2,topk", [(30_003, 650, 300, 10), (8_193, 641, 2000, 50), (300, 640, 1000, 5),
                                           (70_001, 777, 64, 128)])
 def test_derived_search_many_queries(ctx, n, nq, r2, topk):
     cb, cbar, codes, queries = make_problem(21 + n, n, 1024, 8, nq)
@@ -181,11 +181,11 @@ def test_derived_search_many_queries(ctx, n, nq, r2, topk):
 
 def test_derived_search_many_queries_identical_codes_and_worst_case_order(ctx, monkeypatch):
     # 40 distinct codes: buckets of thousands of vectors, all candidates
-    cb, cbar, codes, queries = make_problem(23, 40_000, 1024, 8, 515, distinct=40)
+    cb, cbar, codes, queries = make_problem(23, 40_000, 1024, 8, 643, distinct=40)
     ncand = run_case(ctx, cb, cbar, codes, queries, 700, 20)
     assert ncand.max() > 1400
     # far to near for query 0: every vector passes the bound of its time
-    cb, cbar, codes, queries = make_problem(25, 40_000, 1024, 8, 512)
+    cb, cbar, codes, queries = make_problem(25, 40_000, 1024, 8, 640)
     dl = orc.build_luts(queries[:1], cbar)[0]
     low = (codes & 255).astype(np.int64)
     dist = sum(dl[j][low[:, j]].astype(np.float64) for j in range(4))

@@ -2002,7 +2002,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             // fewer queries: more chunks of a query start at once with this bound, and the seed kernel has blocks to spare
             // (2^26 code evaluations per call, at most 262 144 codes: 256 queries 1.39 -> 1.30 ms per step)
             const int by_queries = (1 << 26) / (nq > 0 ? nq : 1) < (1 << 18) ? (1 << 26) / (nq > 0 ? nq : 1) : (1 << 18);
-            if (batch_codes < by_queries) batch_codes = by_queries;
+            if (batch_codes < by_queries && (int64_t)by_queries <= n / 16) batch_codes = by_queries;   // (a small part of the database only)
             if ((int64_t)batch_codes > n) batch_codes = (int)n;
             const int first_codes = wide_seed ? PRUNE_INIT : (few_groups ? SEED_CODES_STREAM : batch_codes);
             if (tables == 8) f32_seed_refine_kernel<8><<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, nq, tau0);
@@ -2046,7 +2046,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             else if (seed_codes > 4 * SEED_CODES_STREAM) seed_codes = 4 * SEED_CODES_STREAM;
             if (!few_groups) {   // (fewer queries: larger sample, as for the float scan)
                 const int by_queries = (1 << 26) / (nq > 0 ? nq : 1) < (1 << 18) ? (1 << 26) / (nq > 0 ? nq : 1) : (1 << 18);
-                if (seed_codes < by_queries) seed_codes = by_queries;
+                if (seed_codes < by_queries && (int64_t)by_queries <= n / 16) seed_codes = by_queries;
             }
             if ((int64_t)seed_codes > n) seed_codes = (int)n;
             u4_seed_kernel<<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, nq, a.tau_global);

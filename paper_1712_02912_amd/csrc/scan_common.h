@@ -36,6 +36,8 @@ struct TunedArgs {
     const uint8_t *codes;
     int64_t n;
     int64_t chunk_codes;     // multiple of the block tile
+    int64_t head_codes;      // flat scans: the first head_chunks chunks are this short (a first round of items that
+    int head_chunks;         // leaves good bounds behind); the other chunks follow them and have chunk_codes codes each
     int nchunks;
     int ngroups;
     int nitems;              // nchunks * ngroups, item = chunk * ngroups + group

@@ -688,3 +688,15 @@ def test_scan_u4_16_queries_per_pass_worst_case_order_and_duplicates(ctx):
     worst[40_000:40_500] = worst[-500:]                                    # duplicates of the best codes
     run_int_scan(ctx, worst, orc.CODES_U4_PACKED, qluts, 100)
     run_int_scan(ctx, worst, orc.CODES_U4_PACKED, qluts, 500)
+
+
+def test_scan_16_queries_per_pass_first_round_of_short_items(ctx, monkeypatch):
+    """Long result lists start with a round of short chunks (one per block) before the long ones: here forced onto a
+    small database (one block tile per short chunk, few blocks), ragged end, float and integer scans."""
+    monkeypatch.setenv("PQ_SCAN_HEAD", "1")
+    monkeypatch.setenv("PQ_SCAN_BLOCKS", "20")   # one short chunk per group (513 queries), two (300 queries)
+    r = np.random.default_rng(43)
+    for n, nq, topk in [(100_003, 513, 1000), (140_001, 300, 300)]:
+        codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
+        run_float_scan(ctx, codes, orc.CODES_U8, many_queries(r, nq), topk)
+        run_int_scan(ctx, codes, orc.CODES_U4_PACKED, quantized_like_tables(r, nq), topk)

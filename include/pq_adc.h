@@ -138,7 +138,8 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
  * Switches for tests and tuning, read from the environment at each call (unset = default):
  * PQ_SCAN_PRUNE=0 (no lower-bound pruning), PQ_SCAN_Q8=0 (no 8-bit bounds, whatever the number
  * of queries), PQ_SCAN_FORCE_GENERAL=1 (general kernel for every
- * shape), PQ_SCAN_BLOCKS / PQ_SCAN_ITEMS_PER_BLOCK (launch shape), PQ_LUT_MFMA=0 (pq_build_luts
+ * shape), PQ_SCAN_BLOCKS / PQ_SCAN_ITEMS_PER_BLOCK / PQ_SCAN_HEAD (launch shape: blocks, work items per
+ * block, block tiles per chunk of the first round of short items that long result lists start with; 0: none), PQ_LUT_MFMA=0 (pq_build_luts
  * without the matrix cores). */
 int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
                      pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);

@@ -974,8 +974,9 @@ void scan_tuned_kernel(TunedArgs a) {
                 for (int e = threadIdx.x; e < 256 * NT; e += TUNED_THREADS) {
                     const uint4 pk = qt[e];
                     if constexpr (NT == 8) {
-                        sm.lut[(e >> 3) * 16 + 2 * (e & 7)] = pk;
-                        sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1] = pk;
+                        sm.lut[(e >> 3) * 16 + 2 * (e & 7) + ((e >> 3) & 1)] = pk;   // (the first copies of two neighbouring byte values go to the even and to the odd slot of the
+                                                                                       // table: the 16 lanes the LDS serves together write 16 different bank groups)
+                        sm.lut[(e >> 3) * 16 + 2 * (e & 7) + 1 - ((e >> 3) & 1)] = pk;
                     } else {
                         sm.lut[e] = pk;   // (e >> 4) * 16 + (e & 15)
                     }
@@ -988,7 +989,7 @@ void scan_tuned_kernel(TunedArgs a) {
         } else if constexpr (U4Q) {
             // Integer scan on 8-bit lower bounds.  (1) the 16 queries' 8-bit tables of 16 entries; (2) the exact
             // pair-merged tables T[r][byte] = Q[2r][byte & 15] + Q[2r+1][byte >> 4] as 16-bit entries into
-            // lut16; (3) their minima, the sum of the minima and, from the bound the item starts with, the
+            // lut16; (3) their minima (from the 8-bit tables), the sum of the minima and, from the bound the item starts with, the
             // scale of the lower bounds; (4) L[r][byte] = min(15, floor((T - min_r) * scale)) into lut.
             for (int e = threadIdx.x; e < QB * 256; e += TUNED_THREADS) {
                 const int q = e >> 8;
@@ -997,7 +998,7 @@ void scan_tuned_kernel(TunedArgs a) {
             }
             __syncthreads();
             for (int e = threadIdx.x; e < 8 * 256; e += TUNED_THREADS) {
-                const int r = e >> 8, byte = e & 255;
+                const int r = e & 7, byte = e >> 3;   // (table fastest: a wave's LDS accesses spread over the bank groups)
                 uint32_t t[16];
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
@@ -1008,21 +1009,16 @@ void scan_tuned_kernel(TunedArgs a) {
                 sm.lut16[(byte * 8 + r) * 2] = make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
                 sm.lut16[(byte * 8 + r) * 2 + 1] = make_uint4(t[8] | (t[9] << 16), t[10] | (t[11] << 16), t[12] | (t[13] << 16), t[14] | (t[15] << 16));
             }
-            __syncthreads();
-            {   // minima: wave w takes rows (q, r) = 8w .. 8w + 7 of the 128, four entries per lane
-                const unsigned short *t16 = reinterpret_cast<const unsigned short *>(sm.lut16);
-                for (int row = wave * (128 / TUNED_WAVES); row < (wave + 1) * (128 / TUNED_WAVES); ++row) {
-                    const int q = row >> 3, r = row & 7;
-                    uint32_t mn = 0xffffu;
+            if (threadIdx.x < 128) {   // minima of the merged tables: the two components of a byte vary independently
+                const int q = threadIdx.x >> 3, r = threadIdx.x & 7;
+                uint32_t lo = 255u, hi = 255u;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int byte = lane + 64 * i;
-                        const uint32_t v = t16[((byte * 8 + r) * 2 + (q >> 3)) * 8 + (q & 7)];
-                        mn = v < mn ? v : mn;
-                    }
-                    for (int o = 32; o > 0; o >>= 1) { const uint32_t other = __shfl_xor(mn, o); mn = other < mn ? other : mn; }
-                    if (lane == 0) sm.umin[q][r] = mn;
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t x = sm.qstage[q][(2 * r) * 16 + i], y = sm.qstage[q][(2 * r + 1) * 16 + i];
+                    lo = x < lo ? x : lo;
+                    hi = y < hi ? y : hi;
                 }
+                sm.umin[q][r] = sm.slot_lut[q] ? lo + hi : 0x0fffu;
             }
             __syncthreads();
             if (threadIdx.x < 16) {
@@ -1039,7 +1035,7 @@ void scan_tuned_kernel(TunedArgs a) {
             }
             __syncthreads();
             for (int e = threadIdx.x; e < 8 * 256; e += TUNED_THREADS) {
-                const int r = e >> 8, byte = e & 255;
+                const int r = e & 7, byte = e >> 3;   // (table fastest: a wave's LDS accesses spread over the bank groups)
                 const uint4 lo = sm.lut16[(byte * 8 + r) * 2], hi = sm.lut16[(byte * 8 + r) * 2 + 1];
                 const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
                 uint32_t l[16];
@@ -1051,10 +1047,12 @@ void scan_tuned_kernel(TunedArgs a) {
                 }
                 const uint4 pk = make_uint4(l[0] | (l[1] << 8) | (l[2] << 16) | (l[3] << 24), l[4] | (l[5] << 8) | (l[6] << 16) | (l[7] << 24),
                                             l[8] | (l[9] << 8) | (l[10] << 16) | (l[11] << 24), l[12] | (l[13] << 8) | (l[14] << 16) | (l[15] << 24));
-                sm.lut[byte * 16 + 2 * r] = pk;
-                sm.lut[byte * 16 + 2 * r + 1] = pk;
+                sm.lut[byte * 16 + 2 * r + (byte & 1)] = pk;
+                sm.lut[byte * 16 + 2 * r + 1 - (byte & 1)] = pk;
             }
         } else if constexpr (!IS_U4) {
+            // (byte values fastest: the tables come from device memory, often for the only time, and the loads of a wave
+            // are contiguous that way; the price is that its 64 lanes write the same LDS bank group)
             for (int e = threadIdx.x; e < NT * 256; e += TUNED_THREADS) {
                 const int j = e >> 8, byte = e & 255;
                 float v[4];
@@ -1077,7 +1075,7 @@ void scan_tuned_kernel(TunedArgs a) {
             __syncthreads();
             // pair-merged tables: T[r][byte] = Q[2r][byte & 15] + Q[2r+1][byte >> 4]
             for (int e = threadIdx.x; e < 8 * 256; e += TUNED_THREADS) {
-                const int r = e >> 8, byte = e & 255;
+                const int r = e & 7, byte = e >> 3;   // (table fastest: a wave's LDS accesses spread over the bank groups)
                 uint32_t s[8];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
@@ -1087,8 +1085,8 @@ void scan_tuned_kernel(TunedArgs a) {
                 }
                 const uint4 pk = make_uint4(s[0] | (s[1] << 16), s[2] | (s[3] << 16), s[4] | (s[5] << 16),
                                             s[6] | (s[7] << 16));
-                sm.lut[byte * 16 + 2 * r] = pk;
-                sm.lut[byte * 16 + 2 * r + 1] = pk;
+                sm.lut[byte * 16 + 2 * r + (byte & 1)] = pk;
+                sm.lut[byte * 16 + 2 * r + 1 - (byte & 1)] = pk;
             }
         }
         __syncthreads();

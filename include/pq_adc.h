@@ -16,9 +16,13 @@
  *   - The context owns a device workspace that grows on demand (hipMalloc inside the
  *     call when a larger one is needed, otherwise no allocation).  One context must
  *     not be used from two host threads at once.
- *   - Return value: PQ_OK (0) or a negative pq_status.  On error nothing has been
- *     enqueued and outputs are untouched; pq_last_error() gives a message owned by
- *     the context (valid until the next call on it).  No exception crosses the ABI.
+ *   - Return value: PQ_OK (0) or a negative pq_status.  Arguments are validated before
+ *     anything is enqueued (a PQ_EINVAL / PQ_ESHAPE / PQ_EUNSUPPORTED leaves the outputs
+ *     untouched); a PQ_EHIP or PQ_ENOMEM, and the PQ_ESHAPE of pq_derived_search for a
+ *     candidate buffer that turns out too small, can arrive after some of the call's
+ *     kernels were enqueued: the outputs are then unspecified.  pq_last_error() gives a
+ *     message owned by the context (valid until the next call on it).  No exception
+ *     crosses the ABI.
  *   - Codes: a code is m sub-quantizer indexes (Section 2.3.1).  PQ_CODES_U8 stores
  *     one index per byte, component 0 first (m bytes per code).  PQ_CODES_U4_PACKED
  *     stores two 4-bit indexes per byte, component 2r in bits 0-3 and component 2r+1
@@ -63,15 +67,22 @@ const char *pq_last_error(const pq_ctx *ctx);
 /* Library version string, static storage. */
 const char *pq_version(void);
 
-/* Measurement aid: when enabled, pq_adc_scan_topk brackets its scan kernel (the kernel that
- * streams the codes; not the small set-up and merge kernels) with HIP events on the context's
- * stream.  pq_last_scan_kernel_ms waits for that kernel and returns its duration. */
-int pq_set_profiling(pq_ctx *ctx, int enable);
-int pq_last_scan_kernel_ms(pq_ctx *ctx, float *ms);
-/* Measurement aid: plain device-to-device copy of `bytes` bytes (multiple of 16, both pointers
- * 16-byte aligned) by one kernel.  Its known traffic (bytes read + bytes written) calibrates
- * the hardware counters that are read for the scan kernels. */
-int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes);
+/* Switches for tests and tuning, kept in the context.  pq_create reads each one once from the
+ * environment variable "PQ_" + NAME IN UPPER CASE (unset = the default below); pq_set_option changes
+ * it for the calls that follow, pq_unset_option returns it to its default.  Unknown name: PQ_EINVAL.
+ *   scan_prune (1)            0: float scans without lower-bound pruning
+ *   scan_q8 (1)               0: no 8-bit lower bounds (16 queries per pass), whatever the number of queries
+ *   scan_force_general (0)    1: the general scan kernel for every shape
+ *   scan_blocks (number of compute units), scan_items_per_block (4, or 6 with 16 queries per pass),
+ *   scan_head (4)             launch shape of the flat scans: persistent blocks, work items per block, block
+ *                             tiles per chunk of the first round of short items that long result lists
+ *                             start with (0: none)
+ *   lut_mfma (1)              0: pq_build_luts without the matrix cores
+ *   ivf_prune (0)             1: inverted lists scanned by the loop on 16-bit lower bounds
+ *   ivf_ws_gib (24)           workspace limit of ivf_adc_search in GiB (1 ... 128)
+ *   ivf_block_waves (8)       16: inverted lists scanned by blocks of 16 waves */
+int pq_set_option(pq_ctx *ctx, const char *name, int value);
+int pq_unset_option(pq_ctx *ctx, const char *name);
 
 /* Tables step, Eq. (tables) of Section 2.3.3:  luts[q][j][i] = || y_q^j - C^j[i] ||^2,
  * sub-space j = dimensions j*d/m .. (j+1)*d/m-1.
@@ -135,12 +146,7 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
  * Integer sums are exact; with 249 queries and more and n >= 65536 the integer scan also
  * runs on 8-bit lower bounds of its sums (16 queries per pass) and adds up the exact sums
  * only for the codes that pass.
- * Switches for tests and tuning, read from the environment at each call (unset = default):
- * PQ_SCAN_PRUNE=0 (no lower-bound pruning), PQ_SCAN_Q8=0 (no 8-bit bounds, whatever the number
- * of queries), PQ_SCAN_FORCE_GENERAL=1 (general kernel for every
- * shape), PQ_SCAN_BLOCKS / PQ_SCAN_ITEMS_PER_BLOCK / PQ_SCAN_HEAD (launch shape: blocks, work items per
- * block, block tiles per chunk of the first round of short items that long result lists start with; 0: none), PQ_LUT_MFMA=0 (pq_build_luts
- * without the matrix cores). */
+ * (Switches: pq_set_option.) */
 int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
                      pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);
 
@@ -152,9 +158,6 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
                   int m, int k, const int64_t *cand_ids, int ncand, int topk, float *out_dist,
                   int64_t *out_ids);
 
-/* Inverted lists of an IVFADC index (Section 2.3.2): nlist coarse centroids; the codes
- * of list l are rows list_offsets[l] .. list_offsets[l+1]-1 of `codes`, which encode the
- * residuals x - centroid_l.  ids may be NULL (id = row number). */
 /* Search with derived quantizers (chapter 6; Section 6.2.3, Alg. 5 nns_derived) over 64-bit codes
  * of m = 4 sub-quantizer indexes of 16 bits each.  The codebooks obey property P1 of Section
  * 6.2.2: the low 8 bits of a centroid's index name the centroid of the derived 8-bit quantizer
@@ -181,7 +184,7 @@ int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, 
  * counts, then the ids of the buckets 0..b*); between them the call waits for the stream and
  * reads the nq list sizes back to size its workspace.  With 640 queries and more the second pass
  * takes 16 queries per pass over the codes (lower bounds of the integer sums in the loop, exact
- * sums for the codes that pass; PQ_SCAN_Q8=0: 8 queries per pass as for fewer queries).
+ * sums for the codes that pass; option scan_q8 = 0: 8 queries per pass as for fewer queries).
  * Covered: m = 4, d % 4 == 0, d <= 4096, 256 <= k <= 65536, 1 <= topk <= 128, r2 >= 1,
  * nq <= 65535, 0 <= n < 2^32. */
 int pq_derived_search(pq_ctx *ctx, const uint16_t *codes, int64_t n, const float *derived_codebooks,
@@ -189,6 +192,9 @@ int pq_derived_search(pq_ctx *ctx, const uint16_t *codes, int64_t n, const float
                       float *out_dist, int64_t *out_ids, uint32_t *bucket_out, int64_t *ncand_out,
                       int64_t *cand_ids_out, int64_t cand_cap);
 
+/* Inverted lists of an IVFADC index (Section 2.3.2): nlist coarse centroids; the codes
+ * of list l are rows list_offsets[l] .. list_offsets[l+1]-1 of `codes`, which encode the
+ * residuals x - centroid_l.  ids may be NULL (id = row number). */
 typedef struct {
     const float *coarse_centroids; /* [nlist][d] f32, device */
     const int64_t *list_offsets;   /* [nlist+1] i64, device, non-decreasing, [0] = 0 */
@@ -202,16 +208,17 @@ typedef struct {
 /* Index + Tables + Scan of Section 2.3.3 with an inverted index: for each query the
  * nprobe lists with the closest centroids (ties: smaller list id), tables of the query
  * residual y - centroid_l per probed list, ADC over the codes of those lists, topk
- * smallest (distance, id) overall.  probe_out [nq][nprobe] i32 may be NULL; when given
+ * smallest (distance, row) overall, rows then mapped through `ids` (equal distances are
+ * ordered by their position in the grouped code array, not by the mapped id).  probe_out [nq][nprobe] i32 may be NULL; when given
  * it receives the probed lists in ascending (distance, list id) order.
  * Covered: U8 codes, k = 256, m = 8 or 16; 1 <= nprobe <= min(nlist, 1024);
  * 1 <= topk <= 128; ntotal < 2^32.
  * Queries are served in batches whose workspace (coarse distances, residual tables of
- * every (query, list) pair, result lists) stays within PQ_IVF_WS_GIB GiB of device
- * memory (environment, default 24, 1 ... 128); one batch is fastest because a list's
+ * every (query, list) pair, result lists) stays within ivf_ws_gib GiB of device
+ * memory (pq_set_option, default 24, 1 ... 128); one batch is fastest because a list's
  * codes are then scanned once for all the queries that probe it.
  * The lists are scanned by the float loop, four (query, list) pairs per work item, in blocks of 8
- * waves, two per compute unit (PQ_IVF_BLOCK_WAVES=16: one block of 16).  PQ_IVF_PRUNE=1 selects the
+ * waves, two per compute unit (option ivf_block_waves = 16: one block of 16).  Option ivf_prune = 1 selects the
  * loop on 16-bit lower bounds with exact float distances only for the codes whose bound passes
  * (as in pq_adc_scan_topk), eight pairs per item. */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,

@@ -22,7 +22,7 @@ LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
            "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_derived_search", "pq_set_profiling",
-           "pq_last_scan_kernel_ms", "pq_calibration_copy"]
+           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option"]
 
 _lib = None
 
@@ -52,6 +52,8 @@ def load():
     lib.pq_quantize_luts.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.pq_qmax_prescan.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp]
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
+    lib.pq_set_option.argtypes = [vp, ctypes.c_char_p, ci]
+    lib.pq_unset_option.argtypes = [vp, ctypes.c_char_p]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
     lib.pq_rotate.argtypes = [vp, vp, vp, i64, ci, vp]
@@ -115,6 +117,13 @@ class Context:
         if rc != 0:
             raise PqError(rc, self.lib.pq_last_error(self.handle).decode())
 
+    def pq_set_option(self, name, value):
+        """Set a tuning/test switch (see include/pq_adc.h); value None returns it to its default."""
+        if value is None:
+            self._check(self.lib.pq_unset_option(self.handle, name.encode()))
+        else:
+            self._check(self.lib.pq_set_option(self.handle, name.encode(), int(value)))
+
     def pq_set_profiling(self, enable):
         self._check(self.lib.pq_set_profiling(self.handle, 1 if enable else 0))
 
@@ -173,8 +182,9 @@ class Context:
             ids = torch.empty((nq, topk), dtype=torch.int64, device=luts.device)
         else:
             vals, ids = out
-        self._check(self.lib.pq_adc_scan_topk(self.handle, _ptr(codes), codes.shape[0], code_fmt, _ptr(luts), lut_fmt,
-                                              nq, m, k, topk, _ptr(vals), _ptr(ids)))
+        entry = self.lib.pq_adc_scan_topk
+        self._check(entry(self.handle, _ptr(codes), codes.shape[0], code_fmt, _ptr(luts), lut_fmt,
+                          nq, m, k, topk, _ptr(vals), _ptr(ids)))
         return vals, ids
 
     def pq_rerank_f32(self, codes, code_fmt, luts, cand_ids, topk):

@@ -866,7 +866,7 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     // for fewer queries).  The counting pass stays with 8: its bound is the loose one of the block's own counts for most of
     // an item, so a large share of the codes needs exact sums, which the 8-query loop has at hand and the 16-query
     // loop fetches again (measured: 3.7 ms against 5.0 ms, 4.7 ms with a first bound from a sample).
-    const bool wide = nq >= 640 && env_int("PQ_SCAN_Q8", 1) != 0;
+    const bool wide = nq >= 640 && opt_int(ctx, PQ_OPT_SCAN_Q8, 1) != 0;
 
     // work items: chunk of codes x group of 8 or 16 queries, chunk-major (blocks running together share chunks)
     struct Geometry { int ngroups, nblocks; int64_t nchunks, chunk_codes, nitems; };
@@ -874,9 +874,9 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
         Geometry g;
         g.ngroups = (nq + qb - 1) / qb;
         const int64_t block_tile = (int64_t)DQ_SUB * DQ_WAVES;
-        int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+        int nblocks_max = opt_int(ctx, PQ_OPT_SCAN_BLOCKS, ctx->num_cu);
         if (nblocks_max < 1) nblocks_max = 1;
-        int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", 4) * nblocks_max + g.ngroups - 1) / g.ngroups;
+        int64_t nchunks = ((int64_t)opt_int(ctx, PQ_OPT_SCAN_ITEMS_PER_BLOCK, 4) * nblocks_max + g.ngroups - 1) / g.ngroups;
         const int64_t max_by_n = (n + 8 * block_tile - 1) / (8 * block_tile);
         if (nchunks > max_by_n) nchunks = max_by_n;
         const int64_t min_chunks = (n + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits

@@ -446,7 +446,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     // The plain float loop (4 pairs per item) by default; PQ_IVF_PRUNE=1 selects the loop on 16-bit lower
     // bounds (8 pairs per item, one more preparation kernel), which measured the same scan time and a
     // longer call on the configured workload once two blocks share a CU.
-    const bool prune = env_int("PQ_IVF_PRUNE", 0) != 0;
+    const bool prune = opt_int(ctx, PQ_OPT_IVF_PRUNE, 0) != 0;
     const int kind = prune ? (m == 8 ? 3 : 4) : (m == 8 ? 0 : 1);
     const uint32_t item_qb = prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
     const int kpad = 128;
@@ -458,7 +458,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     // GiB (default 24); the more queries share a batch, the more of them share a pass over a list
     const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 +
                              (size_t)IVF_MAX_CHUNKS * kpad * 8 + 64) + (size_t)HIST_BINS * 4 + 64;
-    int ws_gib = env_int("PQ_IVF_WS_GIB", 24);
+    int ws_gib = opt_int(ctx, PQ_OPT_IVF_WS_GIB, 24);
     if (ws_gib < 1) ws_gib = 1;
     if (ws_gib > 128) ws_gib = 128;
     int qbatch = (int)(((size_t)ws_gib << 30) / per_query);
@@ -492,7 +492,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_pscale = take(prune ? npairs_max * 4 : 0);
     const size_t o_partial = take(max_lists * kpad * 8);
     // blocks of 8 waves, two per CU, unless PQ_IVF_BLOCK_WAVES=16 asks for the flat scan's shape
-    const bool w8_blocks = env_int("PQ_IVF_BLOCK_WAVES", 8) != 16;
+    const bool w8_blocks = opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16;
     const size_t state_bytes = w8_blocks ? w8::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu)
                                          : w16::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
     const size_t o_state = take(state_bytes);

@@ -6,12 +6,6 @@
 
 namespace pq {
 
-// tuning switch, on unless the variable is set to 0
-static bool env_flag_on(const char *name) {
-    const char *v = getenv(name);
-    return !(v && v[0] == '0');
-}
-
 
 // ------------------------------------------------------------------------------------------
 // Direct form  D[q][j][i] = sum_t (y[q][j*dsub+t] - C[j][i][t])^2  in f32.  All terms are
@@ -189,7 +183,7 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
 
 int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                       float *luts) {
-    if (d / m >= 8 && env_flag_on("PQ_LUT_MFMA")) {
+    if (d / m >= 8 && opt_int(ctx, PQ_OPT_LUT_MFMA, 1) != 0) {
         dim3 mgrid((k + MT - 1) / MT, (nq + MT - 1) / MT, m);
         if (mgrid.y > 65535 || mgrid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/64 above 65535");
         build_luts_mfma_kernel<false, 16><<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);

@@ -24,6 +24,9 @@ int hip_fail(pq_ctx *ctx, hipError_t e, const char *what) {
 
 int ws_reserve(pq_ctx *ctx, size_t bytes) {
     if (bytes <= ctx->ws_bytes) return PQ_OK;
+    if (ctx->ws_fixed)
+        return fail(ctx, PQ_ENOMEM, "this call needs %zu bytes of scratch memory, the fixed scratch of the entry point that "
+                                    "allocates nothing holds %zu", bytes, ctx->ws_bytes);
     // kernels already enqueued may still use the old workspace
     PQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->ws) {
@@ -44,6 +47,23 @@ int ws_reserve(pq_ctx *ctx, size_t bytes) {
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Names of the switches of pq_set_option, in the order of pq_option_id; the environment variable of a
+// switch is "PQ_" + its name in upper case and is read once, by pq_create.
+static const char *const OPTION_NAMES[PQ_OPT_COUNT] = {"scan_prune", "scan_q8", "scan_force_general", "scan_blocks",
+                                                       "scan_items_per_block", "scan_head", "lut_mfma", "ivf_prune",
+                                                       "ivf_ws_gib", "ivf_block_waves"};
+
+static void options_from_environment(pq_ctx *ctx) {
+    for (int i = 0; i < PQ_OPT_COUNT; ++i) {
+        char var[64] = "PQ_";
+        size_t at = 3;
+        for (const char *c = OPTION_NAMES[i]; *c && at + 1 < sizeof(var); ++c) var[at++] = (char)(*c >= 'a' && *c <= 'z' ? *c - 32 : *c);
+        var[at] = 0;
+        const char *v = getenv(var);
+        ctx->opt[i] = v && *v ? atoi(v) : PQ_OPT_UNSET;
+    }
+}
 
 }  // namespace pq
 
@@ -76,9 +96,22 @@ int pq_create(pq_ctx **out, int device, void *hip_stream) {
     ctx->stream = (hipStream_t)hip_stream;
     ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     strcpy(ctx->err, "no error");
+    options_from_environment(ctx);
     *out = ctx;
     return PQ_OK;
 }
+
+int pq_set_option(pq_ctx *ctx, const char *name, int value) {
+    if (!ctx || !name) return PQ_EINVAL;
+    for (int i = 0; i < PQ_OPT_COUNT; ++i)
+        if (strcmp(name, OPTION_NAMES[i]) == 0) {
+            ctx->opt[i] = value;
+            return PQ_OK;
+        }
+    return fail(ctx, PQ_EINVAL, "set_option: unknown option '%s'", name);
+}
+
+int pq_unset_option(pq_ctx *ctx, const char *name) { return pq_set_option(ctx, name, PQ_OPT_UNSET); }
 
 int pq_destroy(pq_ctx *ctx) {
     if (!ctx) return PQ_EINVAL;
@@ -92,9 +125,17 @@ int pq_destroy(pq_ctx *ctx) {
 
 int pq_set_profiling(pq_ctx *ctx, int enable) {
     if (!ctx) return PQ_EINVAL;
-    if (enable && !ctx->ev_begin) {
-        PQ_HIP(ctx, hipEventCreate(&ctx->ev_begin));
-        PQ_HIP(ctx, hipEventCreate(&ctx->ev_end));
+    if (enable && !(ctx->ev_begin && ctx->ev_end)) {
+        // both events or none: a failure must not leave half of the pair behind
+        hipEvent_t b = nullptr, e = nullptr;
+        hipError_t rc = hipEventCreate(&b);
+        if (rc == hipSuccess) rc = hipEventCreate(&e);
+        if (rc != hipSuccess) {
+            if (b) (void)hipEventDestroy(b);
+            return hip_fail(ctx, rc, "hipEventCreate");
+        }
+        ctx->ev_begin = b;
+        ctx->ev_end = e;
     }
     ctx->profiling = enable ? 1 : 0;
     ctx->ev_valid = 0;

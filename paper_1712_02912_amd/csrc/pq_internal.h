@@ -5,12 +5,22 @@
 #include <stdio.h>
 
 #include "pq_adc.h"
+#include "pq_adc_bench.h"
+
+// Tuning and test switches (pq_set_option).  PQ_OPT_UNSET = the kernel's own default.
+enum pq_option_id {
+    PQ_OPT_SCAN_PRUNE = 0, PQ_OPT_SCAN_Q8, PQ_OPT_SCAN_FORCE_GENERAL, PQ_OPT_SCAN_BLOCKS, PQ_OPT_SCAN_ITEMS_PER_BLOCK,
+    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_COUNT
+};
+constexpr int PQ_OPT_UNSET = -2147483647 - 1;
 
 struct pq_ctx {
     int device;
     hipStream_t stream;
-    void *ws;          // device workspace, grown on demand
+    void *ws;          // device workspace, grown on demand (or the fixed scratch of the call that allocates nothing)
     size_t ws_bytes;
+    int ws_fixed;      // ws must not grow: a request beyond ws_bytes is an error
+    int opt[PQ_OPT_COUNT];
     int num_cu;
     int profiling;              // bracket the scan kernel with events
     hipEvent_t ev_begin, ev_end;
@@ -31,6 +41,9 @@ int ws_reserve(pq_ctx *ctx, size_t bytes);
         hipError_t e__ = (call);                                         \
         if (e__ != hipSuccess) return pq::hip_fail((ctx), e__, #call);   \
     } while (0)
+
+// value of a switch, or dflt if it was never set
+static inline int opt_int(const pq_ctx *ctx, int id, int dflt) { return ctx->opt[id] == PQ_OPT_UNSET ? dflt : ctx->opt[id]; }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

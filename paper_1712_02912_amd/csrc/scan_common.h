@@ -74,11 +74,6 @@ struct TunedArgs {
     const float *prune_scale16;
 };
 
-static inline int env_int(const char *name, int dflt) {
-    const char *s = getenv(name);
-    return s && *s ? atoi(s) : dflt;
-}
-
 int launch_merge_topk(pq_ctx *ctx, const uint64_t *partial, int nchunks, int ngroups, int qb, int kpad, int nq,
                       int topk, bool val_u32, void *out_val, int64_t *out_ids);
 // merge of the per-query result lists of a scan that leaves a final bound per query in tau_global

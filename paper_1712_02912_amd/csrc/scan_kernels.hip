@@ -356,7 +356,7 @@ static int run_generic(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, con
 
 int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, int lf, int nq, int m, int k,
                 int topk, void *out_val, int64_t *out_ids) {
-    const bool general = env_int("PQ_SCAN_FORCE_GENERAL", 0) != 0;
+    const bool general = opt_int(ctx, PQ_OPT_SCAN_FORCE_GENERAL, 0) != 0;
     if (!general && cf == PQ_CODES_U8 && lf == PQ_LUT_F32 && k == 256 && (m == 8 || m == 16))
         return w16::launch_scan_tuned(ctx, m == 8 ? 0 : 1, codes, n, luts, nq, topk, out_val, out_ids);
     if (!general && cf == PQ_CODES_U4_PACKED && lf == PQ_LUT_U8 && k == 16 && m == 16)

@@ -897,7 +897,7 @@ void scan_tuned_kernel(TunedArgs a) {
                 }
                 if (s == 0) {
                     sm.code_begin = it.code_begin;
-                    sm.chunk_ptr = a.codes + it.code_begin * CB;
+                    sm.chunk_ptr = a.codes + (size_t)it.code_begin * CB;   // (64-bit: rows beyond 2^32 / CB bytes)
                     sm.ncodes = (int)it.ncodes;
                     sm.skip = it.skip_slots_chunk & 0xff;
                     sm.nvalid = nslots;
@@ -1904,13 +1904,13 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const bool is_u4 = kind == KIND_U4_M16;
     // The 8 x 256 float scan prunes with 16-bit lower bounds when the database is large enough to
     // pay for the preparation (a bound per query from the first PRUNE_INIT codes, then the tables).
-    const bool prune = (kind == KIND_F32_M8 || kind == KIND_F32_M16) && n >= PRUNE_MIN_N && env_int("PQ_SCAN_PRUNE", 1) != 0;
+    const bool prune = (kind == KIND_F32_M8 || kind == KIND_F32_M16) && n >= PRUNE_MIN_N && opt_int(ctx, PQ_OPT_SCAN_PRUNE, 1) != 0;
     const int tables = kind == KIND_F32_M16 ? 16 : 8;
     // eight tables and too many queries for the streaming shape (32 groups of 8 and more, i.e. 249 queries): 8-bit
     // lower bounds, 16 queries per pass (PQ_SCAN_Q8=0: 16-bit lower bounds, 8 queries per pass).  Measured on 25 M
     // codes: 256 queries 1.69 -> 1.28 ms, 384 queries 2.28 -> 1.51 ms; 128 queries in the streaming shape 0.62 ms
     // against 1.21 ms with this loop.
-    const bool many16 = (nq + 7) / 8 >= STREAM_GROUPS && env_int("PQ_SCAN_Q8", 1) != 0;
+    const bool many16 = (nq + 7) / 8 >= STREAM_GROUPS && opt_int(ctx, PQ_OPT_SCAN_Q8, 1) != 0;
     const bool q8 = prune && tables == 8 && many16;
     if (prune) kind = q8 ? KIND_F32Q_M8 : (tables == 16 ? KIND_F32P_M16 : KIND_F32P_M8);
     // the integer scan likewise: with a first bound and enough queries, its loop runs on 8-bit lower bounds of
@@ -1927,7 +1927,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const int ngroups = (nq + qb - 1) / qb;
     const int64_t block_tile = (int64_t)tile * TUNED_WAVES;
     // persistent blocks: one per CU (64 KB of tables and 16 waves of 128 registers fill a CU)
-    int nblocks_max = env_int("PQ_SCAN_BLOCKS", ctx->num_cu);
+    int nblocks_max = opt_int(ctx, PQ_OPT_SCAN_BLOCKS, ctx->num_cu);
     if (nblocks_max < 1) nblocks_max = 1;
 
     // several items per block for balance, chunks of at least 8 block tiles
@@ -1939,12 +1939,12 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     int head_chunks = 0;
     int64_t head_codes = 0;
     if ((q8 || u4q) && topk > 128) {
-        const int64_t hc = (int64_t)env_int("PQ_SCAN_HEAD", 4) * block_tile;
+        const int64_t hc = (int64_t)opt_int(ctx, PQ_OPT_SCAN_HEAD, 4) * block_tile;
         const int64_t c0 = (nblocks_max + ngroups - 1) / ngroups;
         if (hc > 0 && c0 * hc * 16 <= n) { head_chunks = (int)c0; head_codes = hc; }
     }
     const int64_t n_head = (int64_t)head_chunks * head_codes, n_main = n - n_head;
-    int64_t nchunks = ((int64_t)env_int("PQ_SCAN_ITEMS_PER_BLOCK", q8 || u4q ? 6 : 4) * nblocks_max + ngroups - 1) / ngroups;
+    int64_t nchunks = ((int64_t)opt_int(ctx, PQ_OPT_SCAN_ITEMS_PER_BLOCK, q8 || u4q ? 6 : 4) * nblocks_max + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n_main + 8 * block_tile - 1) / (8 * block_tile);
     if (nchunks > max_by_n) nchunks = max_by_n;
     const int64_t min_chunks = (n_main + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits

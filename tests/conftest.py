@@ -21,3 +21,25 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+class _Options:
+    """Sets switches of a context (pq_set_option) and returns them to their defaults afterwards."""
+
+    def __init__(self, ctx):
+        self.ctx, self.touched = ctx, set()
+
+    def set(self, name, value):
+        self.touched.add(name)
+        self.ctx.pq_set_option(name, value)
+
+    def restore(self):
+        for name in self.touched:
+            self.ctx.pq_set_option(name, None)
+
+
+@pytest.fixture
+def opts(ctx):
+    o = _Options(ctx)
+    yield o
+    o.restore()

@@ -12,13 +12,16 @@ import torch
 from paper_1712_02912_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "pq_adc.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"^(?:int|const char \*|void|size_t)\s*\*?(\w+)\s*\(", text, flags=re.M)
+    names = []
+    for header in HEADERS:
+        text = open(header).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"^(?:int|const char \*|void|size_t)\s*\*?(\w+)\s*\(", text, flags=re.M)
+    return names
 
 
 def test_header_declares_the_named_entry_points():
@@ -31,7 +34,7 @@ def test_header_declares_the_named_entry_points():
 def test_library_exports_every_declared_function():
     lib = ctypes.CDLL(binding.LIB_PATH)
     for name in declared_functions():
-        assert hasattr(lib, name), f"{name} is declared in pq_adc.h but not exported"
+        assert hasattr(lib, name), f"{name} is declared in include/*.h but not exported"
 
 
 def test_binding_lists_exactly_the_declared_functions():

@@ -179,7 +179,7 @@ def test_derived_search_many_queries(ctx, n, nq, r2, topk):
     run_case(ctx, cb, cbar, codes, queries, r2, topk)
 
 
-def test_derived_search_many_queries_identical_codes_and_worst_case_order(ctx, monkeypatch):
+def test_derived_search_many_queries_identical_codes_and_worst_case_order(ctx, opts):
     # 40 distinct codes: buckets of thousands of vectors, all candidates
     cb, cbar, codes, queries = make_problem(23, 40_000, 1024, 8, 643, distinct=40)
     ncand = run_case(ctx, cb, cbar, codes, queries, 700, 20)
@@ -192,5 +192,5 @@ def test_derived_search_many_queries_identical_codes_and_worst_case_order(ctx, m
     codes = codes[np.argsort(-dist, kind="stable")]
     run_case(ctx, cb, cbar, codes, queries, 400, 10)
     # the 8-query kernel for the same input (switch)
-    monkeypatch.setenv("PQ_SCAN_Q8", "0")
+    opts.set("scan_q8", 0)
     run_case(ctx, cb, cbar, codes, queries, 400, 10)

@@ -85,10 +85,10 @@ def test_ivf_all_lists_equals_flat_scan_of_residual_tables(ctx):
         np.testing.assert_allclose(gd[q], np.sort(dd)[:20], rtol=1e-5)
 
 
-@pytest.mark.parametrize("prune", ["0", "1"])
-def test_ivf_skewed_lists_many_chunks_and_empty_lists(ctx, monkeypatch, prune):
+@pytest.mark.parametrize("prune", [0, 1])
+def test_ivf_skewed_lists_many_chunks_and_empty_lists(ctx, opts, prune):
     """Zipf-like list sizes with one list long enough to be cut into chunks, odd list boundaries, empty lists."""
-    monkeypatch.setenv("PQ_IVF_PRUNE", prune)
+    opts.set("ivf_prune", prune)
     r = np.random.default_rng(41)
     d, m, nlist = 32, 8, 24
     sizes = np.array([700_001, 90_003, 7, 0, 1, 33_333, 0, 129, 128, 127] + [1000 + 37 * i for i in range(14)])
@@ -144,9 +144,9 @@ def test_ivf_many_lists_probe_selection(ctx):
 
 
 
-def test_ivf_queries_served_in_several_batches(ctx, monkeypatch):
+def test_ivf_queries_served_in_several_batches(ctx, opts):
     """A 1 GiB workspace holds about 600 queries of this shape: 1500 queries take three batches."""
-    monkeypatch.setenv("PQ_IVF_WS_GIB", "1")
+    opts.set("ivf_ws_gib", 1)
     r = np.random.default_rng(67)
     d, m, nlist, n, nq = 32, 8, 16384, 200_000, 1500
     sizes = datagen.zipf_list_sizes(n, nlist)
@@ -158,24 +158,24 @@ def test_ivf_queries_served_in_several_batches(ctx, monkeypatch):
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 64, 20)
 
 
-@pytest.mark.parametrize("env", [{"PQ_IVF_BLOCK_WAVES": "16"}, {"PQ_IVF_PRUNE": "1"},
-                                 {"PQ_IVF_PRUNE": "1", "PQ_IVF_BLOCK_WAVES": "16"}])
+@pytest.mark.parametrize("env", [{"ivf_block_waves": 16}, {"ivf_prune": 1},
+                                 {"ivf_prune": 1, "ivf_block_waves": 16}])
 @pytest.mark.parametrize("m", [8, 16])
-def test_ivf_switches_lower_bound_loop_and_block_shape(ctx, monkeypatch, env, m):
+def test_ivf_switches_lower_bound_loop_and_block_shape(ctx, opts, env, m):
     """The inverted-list scan on 16-bit lower bounds (8 pairs per item) and in blocks of 16 waves."""
     for k, v in env.items():
-        monkeypatch.setenv(k, v)
+        opts.set(k, v)
     mix, coarse, cb, codes, order, offsets = make_index(20000, 64, m, 40, seed=71 + m)
     queries = mix.sample(11, 97)
     run_ivf(ctx, queries, coarse, offsets, codes, order, cb, 8, 100)
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 40, 7)
 
 
-@pytest.mark.parametrize("prune", ["0", "1"])
-def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx, monkeypatch, prune):
+@pytest.mark.parametrize("prune", [0, 1])
+def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx, opts, prune):
     """Far lists whose table minima already exceed the query's first bound (nothing of them may enter the
     result), and a query whose nearest lists hold fewer than topk codes (no first bound, no pruning)."""
-    monkeypatch.setenv("PQ_IVF_PRUNE", prune)
+    opts.set("ivf_prune", prune)
     r = np.random.default_rng(73)
     d, m, nlist = 32, 8, 12
     sizes = np.array([5000, 4000, 3, 2, 6000, 2500, 1, 0, 3000, 3500, 2000, 4500])
@@ -190,3 +190,40 @@ def test_ivf_pairs_that_cannot_contribute_and_unseeded_queries(ctx, monkeypatch,
     queries[6] = coarse[6] + 0.01
     for nprobe, topk in ((12, 100), (6, 10), (3, 128)):
         run_ivf(ctx, queries, coarse, offsets, codes, None, cb, nprobe, topk)
+
+
+@pytest.mark.parametrize("m", [8, 16])
+def test_ivf_lists_beyond_4_gib_of_codes(ctx, m):
+    """Lists whose codes start more than 2^32 bytes into the code array (row 2^29 with 8-byte codes, 2^28 with
+    16-byte codes): byte offsets of list chunks are 64-bit.  One huge list with a far centroid fills the front
+    of the array and is never probed; the probed lists lie behind it.  The oracle runs on those lists alone,
+    with the rows of the full array as ids."""
+    r = np.random.default_rng(83 + m)
+    d, nlist, nq = 32, 40, 12
+    filler = (1 << 32) // m + 12_345                       # rows of list 0
+    sizes = np.array([filler] + [3000 + 211 * i for i in range(nlist - 1)])
+    sizes[7] = 0
+    sizes[11] = 150_001                                    # a list cut into chunks
+    offsets = datagen.offsets_from_sizes(sizes)
+    n = int(offsets[-1])
+    gen = torch.Generator(device="cuda").manual_seed(830 + m)
+    codes_d = torch.randint(0, 256, (n, m), dtype=torch.uint8, device="cuda", generator=gen)
+    tail = codes_d[filler:].cpu().numpy()                  # the probed lists' codes
+    coarse = (r.random((nlist, d)) * 100).astype(np.float32)
+    coarse[0] += 10_000.0                                  # never among the nearest lists
+    cb = (r.random((m, 256, d // m)) * 20 - 10).astype(np.float32)
+    queries = (r.random((nq, d)) * 100).astype(np.float32)
+    for nprobe, topk in ((8, 100), (39, 20)):
+        gd, gi, gp = ctx.ivf_adc_search(dev(coarse), dev(offsets), codes_d, None, dev(cb), binding.CODES_U8, dev(queries),
+                                        nprobe, topk, return_probes=True)
+        torch.cuda.synchronize()
+        gd, gi, gp = gd.cpu().numpy(), gi.cpu().numpy(), gp.cpu().numpy()
+        assert np.all(gp > 0), "the filler list must not be probed"
+        check_probes(queries, coarse, gp, nprobe)
+        assert gi.min() >= filler
+        od, oi = orc.ivf_scan(queries, coarse[1:], offsets[1:] - filler, tail, np.arange(filler, n, dtype=np.int64), cb,
+                              orc.CODES_U8, gp - 1, topk)
+        for q in range(nq):
+            check_float_topk_ranked(gd[q], gi[q], od[q], oi[q])
+    del codes_d
+    torch.cuda.empty_cache()

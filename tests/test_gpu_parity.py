@@ -371,9 +371,9 @@ def test_errors_are_reported_not_raised_in_kernels(ctx):
     assert host(i).tolist() == [[0, 1, 2]]
 
 
-def test_scan_f32_plain_loop_on_a_large_database(ctx, monkeypatch):
+def test_scan_f32_plain_loop_on_a_large_database(ctx, opts):
     """The plain float loop (no pruning) normally serves small databases only; here it scans a large one."""
-    monkeypatch.setenv("PQ_SCAN_PRUNE", "0")
+    opts.set("scan_prune", 0)
     r = np.random.default_rng(31)
     codes = r.integers(0, 256, (400_003, 8), dtype=np.uint8)
     luts_h = (r.random((9, 8, 256)) * 100).astype(np.float32)
@@ -381,25 +381,25 @@ def test_scan_f32_plain_loop_on_a_large_database(ctx, monkeypatch):
     run_float_scan(ctx, codes, orc.CODES_U8, luts_h[:2], 700)
 
 
-def test_switches_general_kernel_and_launch_shapes(ctx, monkeypatch):
+def test_switches_general_kernel_and_launch_shapes(ctx, opts):
     """The general kernel on the shapes the tuned kernels normally take, and unusual launch shapes."""
     r = np.random.default_rng(33)
     codes = r.integers(0, 256, (120_001, 8), dtype=np.uint8)
     luts_h = (r.random((6, 8, 256)) * 100).astype(np.float32)
     qluts = r.integers(0, 256, (5, 16, 16), dtype=np.uint8)
-    monkeypatch.setenv("PQ_SCAN_FORCE_GENERAL", "1")
+    opts.set("scan_force_general", 1)
     run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
     run_int_scan(ctx, codes, orc.CODES_U4_PACKED, qluts, 100)
-    monkeypatch.delenv("PQ_SCAN_FORCE_GENERAL")
-    for blocks, items in (("3", "1"), ("1000", "7"), ("1", "1")):
-        monkeypatch.setenv("PQ_SCAN_BLOCKS", blocks)
-        monkeypatch.setenv("PQ_SCAN_ITEMS_PER_BLOCK", items)
+    opts.set("scan_force_general", None)
+    for blocks, items in ((3, 1), (1000, 7), (1, 1)):
+        opts.set("scan_blocks", blocks)
+        opts.set("scan_items_per_block", items)
         run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
         run_int_scan(ctx, codes, orc.CODES_U4_PACKED, qluts, 1000)
 
 
-def test_build_luts_without_matrix_cores(ctx, monkeypatch):
-    monkeypatch.setenv("PQ_LUT_MFMA", "0")
+def test_build_luts_without_matrix_cores(ctx, opts):
+    opts.set("lut_mfma", 0)
     r = np.random.default_rng(34)
     q = (r.random((19, 128)) * 255).astype(np.float32)
     cb = (r.random((8, 256, 16)) * 255).astype(np.float32)
@@ -599,7 +599,7 @@ def test_scan_f32_16_queries_per_pass_sizes(ctx, n, nq, topk):
     run_float_scan(ctx, codes, orc.CODES_U8, many_queries(r, nq), topk)
 
 
-def test_scan_f32_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
+def test_scan_f32_16_queries_per_pass_degenerate_tables(ctx, opts):
     r = np.random.default_rng(23)
     n, nq = 70_001, 515
     codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
@@ -621,7 +621,7 @@ def test_scan_f32_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
     same = np.tile(luts_h[0].argmin(axis=1).astype(np.uint8), (n, 1))
     run_float_scan(ctx, same, orc.CODES_U8, luts_h, 100)
     # the 16-bit loop for the same inputs (switch), as a cross-check of the switch itself
-    monkeypatch.setenv("PQ_SCAN_Q8", "0")
+    opts.set("scan_q8", 0)
     run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 100)
 
 
@@ -654,7 +654,7 @@ def test_scan_u4_16_queries_per_pass_sizes(ctx, n, nq, topk):
     run_int_scan(ctx, packed, orc.CODES_U4_PACKED, quantized_like_tables(r, nq), topk)
 
 
-def test_scan_u4_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
+def test_scan_u4_16_queries_per_pass_degenerate_tables(ctx, opts):
     r = np.random.default_rng(31)
     n, nq = 70_001, 515
     packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
@@ -674,7 +674,7 @@ def test_scan_u4_16_queries_per_pass_degenerate_tables(ctx, monkeypatch):
     same = np.tile((best[0::2] | (best[1::2] << 4)).astype(np.uint8), (n, 1))
     run_int_scan(ctx, same, orc.CODES_U4_PACKED, qluts, 100)
     # the 16-bit loop for the same inputs (switch)
-    monkeypatch.setenv("PQ_SCAN_Q8", "0")
+    opts.set("scan_q8", 0)
     run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, 100)
 
 
@@ -690,11 +690,11 @@ def test_scan_u4_16_queries_per_pass_worst_case_order_and_duplicates(ctx):
     run_int_scan(ctx, worst, orc.CODES_U4_PACKED, qluts, 500)
 
 
-def test_scan_16_queries_per_pass_first_round_of_short_items(ctx, monkeypatch):
+def test_scan_16_queries_per_pass_first_round_of_short_items(ctx, opts):
     """Long result lists start with a round of short chunks (one per block) before the long ones: here forced onto a
     small database (one block tile per short chunk, few blocks), ragged end, float and integer scans."""
-    monkeypatch.setenv("PQ_SCAN_HEAD", "1")
-    monkeypatch.setenv("PQ_SCAN_BLOCKS", "20")   # one short chunk per group (513 queries), two (300 queries)
+    opts.set("scan_head", 1)
+    opts.set("scan_blocks", 20)   # one short chunk per group (513 queries), two (300 queries)
     r = np.random.default_rng(43)
     for n, nq, topk in [(100_003, 513, 1000), (140_001, 300, 300)]:
         codes = r.integers(0, 256, (n, 8), dtype=np.uint8)

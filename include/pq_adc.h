@@ -150,6 +150,26 @@ int pq_qmax_prescan(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf
 int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
                      pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);
 
+/* pq_adc_scan_topk for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same results as pq_adc_scan_topk; where that call uses the context's growable workspace
+ * (shared bounds, candidate histograms, per-wave candidate lists, per-chunk result lists, first-bound
+ * tables), this one uses a fixed scratch array of PQ_NOALLOC_SCRATCH_MIB MiB that is part of the
+ * library image: every GPU the library runs on holds its own copy until the process ends, and its
+ * address is looked up once per device by pq_create.  The call itself makes no hipMalloc / hipFree
+ * and calls no allocating routine; inputs and outputs are the caller's.
+ * Limit: the scratch the scan needs must fit.  That holds for the tuned shapes with topk <= 128 and
+ * fewer than 249 queries, whatever n is (about 120 MiB on 256 compute units), and for calls of the
+ * general kernel with few (chunk, query) blocks; a request that does not fit returns PQ_ENOMEM with a
+ * message naming both sizes, and nothing has been enqueued.
+ * Every call on a GPU shares that GPU's array (whatever the context or stream): calls that overlap
+ * in time on one GPU race.  The array keeps the last call's contents; everything that must start
+ * from a known value (work counter, bounds, histograms, candidate counters) is cleared by the call's
+ * first kernel, as in pq_adc_scan_topk. */
+#define PQ_NOALLOC_SCRATCH_MIB 128
+int pq_adc_scan_topk_noalloc(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
+                             pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids);
+
 /* Second pass of the two-pass search (Alg. 5 `rerank`): float ADC of the given
  * candidates and the topk smallest (distance, id).
  *   cand_ids [nq][ncand] i64, positions into codes; negative entries are skipped.

@@ -22,7 +22,7 @@ LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
            "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_derived_search", "pq_set_profiling",
-           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option"]
+           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option", "pq_adc_scan_topk_noalloc"]
 
 _lib = None
 
@@ -52,6 +52,7 @@ def load():
     lib.pq_quantize_luts.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp]
     lib.pq_qmax_prescan.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp]
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
+    lib.pq_adc_scan_topk_noalloc.argtypes = lib.pq_adc_scan_topk.argtypes
     lib.pq_set_option.argtypes = [vp, ctypes.c_char_p, ci]
     lib.pq_unset_option.argtypes = [vp, ctypes.c_char_p]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
@@ -168,7 +169,9 @@ class Context:
         return qmax
 
     # -- Scan step ---------------------------------------------------------------------------
-    def pq_adc_scan_topk(self, codes, code_fmt, luts, topk, out=None):
+    def pq_adc_scan_topk(self, codes, code_fmt, luts, topk, out=None, noalloc=False):
+        """noalloc=True: the entry point that uses the library's fixed scratch (pass `out` so that this
+        layer allocates nothing either)."""
         codes = _dev(codes, torch.uint8, "codes")
         if luts.dtype == torch.uint8:
             luts = _dev(luts, torch.uint8, "luts")
@@ -182,7 +185,7 @@ class Context:
             ids = torch.empty((nq, topk), dtype=torch.int64, device=luts.device)
         else:
             vals, ids = out
-        entry = self.lib.pq_adc_scan_topk
+        entry = self.lib.pq_adc_scan_topk_noalloc if noalloc else self.lib.pq_adc_scan_topk
         self._check(entry(self.handle, _ptr(codes), codes.shape[0], code_fmt, _ptr(luts), lut_fmt,
                           nq, m, k, topk, _ptr(vals), _ptr(ids)))
         return vals, ids

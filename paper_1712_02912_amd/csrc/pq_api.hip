@@ -67,6 +67,32 @@ static void options_from_environment(pq_ctx *ctx) {
 
 }  // namespace pq
 
+// Scratch memory of pq_adc_scan_topk_noalloc: one copy per GPU the library runs on, held until the process
+// ends.  The name is a host-side stand-in; host code uses the device address that hipGetSymbolAddress
+// returns for the current device (fixed_scratch_of), never the name.
+constexpr size_t FIXED_SCRATCH_BYTES = (size_t)PQ_NOALLOC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[FIXED_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void *g_fixed_scratch[MAX_DEVICES];   // per device, looked up once with that device current
+
+namespace pq {
+static int fixed_scratch_of(pq_ctx *ctx, void **out) {
+    if (ctx->device < 0 || ctx->device >= MAX_DEVICES) return fail(ctx, PQ_EUNSUPPORTED, "device index %d above %d", ctx->device, MAX_DEVICES - 1);
+    if (!g_fixed_scratch[ctx->device]) {
+        int current = -1;
+        PQ_HIP(ctx, hipGetDevice(&current));
+        if (current != ctx->device) PQ_HIP(ctx, hipSetDevice(ctx->device));
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (current != ctx->device) (void)hipSetDevice(current);
+        if (e != hipSuccess || !p) return hip_fail(ctx, e, "hipGetSymbolAddress(scratch)");
+        g_fixed_scratch[ctx->device] = p;
+    }
+    *out = g_fixed_scratch[ctx->device];
+    return PQ_OK;
+}
+}  // namespace pq
+
 namespace pq {
 __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                                                size_t n16) {
@@ -97,6 +123,13 @@ int pq_create(pq_ctx **out, int device, void *hip_stream) {
     ctx->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     strcpy(ctx->err, "no error");
     options_from_environment(ctx);
+    // the address of this device's fixed scratch is looked up here, at set-up, so that
+    // pq_adc_scan_topk_noalloc itself has nothing left to initialise
+    void *fixed = nullptr;
+    if (fixed_scratch_of(ctx, &fixed) != PQ_OK) {
+        free(ctx);
+        return PQ_EHIP;
+    }
     *out = ctx;
     return PQ_OK;
 }
@@ -218,6 +251,26 @@ int pq_adc_scan_topk(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt c
     if (!luts || !out_val || !out_ids || (n > 0 && !codes)) return fail(ctx, PQ_EINVAL, "adc_scan_topk: null pointer");
     if (!aligned16(codes)) return fail(ctx, PQ_EINVAL, "adc_scan_topk: codes must be 16-byte aligned");
     return launch_scan(ctx, codes, n, cf, luts, lf, nq, m, k, topk, out_val, out_ids);
+}
+
+int pq_adc_scan_topk_noalloc(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const void *luts,
+                             pq_lut_fmt lf, int nq, int m, int k, int topk, void *out_val, int64_t *out_ids) {
+    if (!ctx) return PQ_EINVAL;
+    void *fixed = nullptr;
+    int rc = fixed_scratch_of(ctx, &fixed);   // (looked up by pq_create; this only reads the table)
+    if (rc) return rc;
+    // the same validation and the same kernels as pq_adc_scan_topk, with the fixed scratch of this GPU in
+    // place of the context's workspace; a request that does not fit fails in ws_reserve
+    void *const own_ws = ctx->ws;
+    const size_t own_bytes = ctx->ws_bytes;
+    ctx->ws = fixed;
+    ctx->ws_bytes = FIXED_SCRATCH_BYTES;
+    ctx->ws_fixed = 1;
+    rc = pq_adc_scan_topk(ctx, codes, n, cf, luts, lf, nq, m, k, topk, out_val, out_ids);
+    ctx->ws = own_ws;
+    ctx->ws_bytes = own_bytes;
+    ctx->ws_fixed = 0;
+    return rc;
 }
 
 int pq_rerank_f32(pq_ctx *ctx, const uint8_t *codes, int64_t n, pq_code_fmt cf, const float *luts, int nq, int m,

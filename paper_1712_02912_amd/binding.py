@@ -22,7 +22,7 @@ LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
            "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_derived_search", "pq_set_profiling",
-           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option", "pq_adc_scan_topk_noalloc"]
+           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option", "pq_last_scan_info", "pq_adc_scan_topk_noalloc"]
 
 _lib = None
 
@@ -53,6 +53,8 @@ def load():
     lib.pq_qmax_prescan.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp]
     lib.pq_adc_scan_topk.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, ci, ci, vp, vp]
     lib.pq_adc_scan_topk_noalloc.argtypes = lib.pq_adc_scan_topk.argtypes
+    lib.pq_last_scan_info.argtypes = [vp, ctypes.c_char_p, ctypes.c_size_t, ctypes.POINTER(ci), ctypes.POINTER(ci),
+                                      ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     lib.pq_set_option.argtypes = [vp, ctypes.c_char_p, ci]
     lib.pq_unset_option.argtypes = [vp, ctypes.c_char_p]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
@@ -132,6 +134,15 @@ class Context:
         ms = ctypes.c_float()
         self._check(self.lib.pq_last_scan_kernel_ms(self.handle, ctypes.byref(ms)))
         return ms.value
+
+    def pq_last_scan_info(self):
+        name = ctypes.create_string_buffer(200)
+        qpp, passes = ctypes.c_int(), ctypes.c_int()
+        parked, inserted = ctypes.c_uint64(), ctypes.c_uint64()
+        self._check(self.lib.pq_last_scan_info(self.handle, name, 200, ctypes.byref(qpp), ctypes.byref(passes),
+                                               ctypes.byref(parked), ctypes.byref(inserted)))
+        return {"kernel": name.value.decode(), "queries_per_pass": qpp.value, "passes": passes.value,
+                "parked_lanes": parked.value, "inserted_keys": inserted.value}
 
     def pq_calibration_copy(self, src, dst):
         nbytes = src.numel() * src.element_size()

@@ -943,7 +943,10 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     // Step 1.3, counting pass
     derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, a.g_hist, (size_t)nq * DQ_BINS, a.g_bound, nullptr, nq);
     PQ_HIP(ctx, hipGetLastError());
-    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
+    if (ctx->profiling) {
+        note_plain_scan(ctx, "derived_scan_kernel<count> (8 queries per pass)", 8, g_count.ngroups);
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
+    }
     if (g_count.nblocks > 0) {
         derived_scan_kernel<0><<<g_count.nblocks, DQ_THREADS, 0, s>>>(a);
         PQ_HIP(ctx, hipGetLastError());

@@ -555,13 +555,13 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
             else ivf_prune_prep_kernel<16><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale);
             PQ_HIP(ctx, hipGetLastError());
         }
-        uint32_t *tau_global = nullptr;
+        unsigned long long *tau_key = nullptr;
         rc = w8_blocks ? w8::launch_scan_items(ctx, kind, pmin, poff, pscale, L->codes, luts, nqb, nprobe, topk, items, nitems_dev,
-                                               pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_global)
+                                               pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_key)
                        : w16::launch_scan_items(ctx, kind, pmin, poff, pscale, L->codes, luts, nqb, nprobe, topk, items, nitems_dev,
-                                                pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_global);
+                                                pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_key);
         if (rc) return rc;
-        rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_global, kpad, nqb, topk, L->ids, false,
+        rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_key, kpad, nqb, topk, L->ids, false,
                                    out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
         if (rc) return rc;
     }

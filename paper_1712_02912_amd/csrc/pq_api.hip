@@ -183,6 +183,37 @@ int pq_last_scan_kernel_ms(pq_ctx *ctx, float *ms) {
     return PQ_OK;
 }
 
+int pq_last_scan_info(pq_ctx *ctx, char *name, size_t name_bytes, int *queries_per_pass, int *passes,
+                      uint64_t *parked_lanes, uint64_t *inserted_keys) {
+    if (!ctx) return PQ_EINVAL;
+    if (!ctx->ev_valid) return fail(ctx, PQ_EINVAL, "no profiled scan kernel recorded");
+    PQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (name && name_bytes > 0) snprintf(name, name_bytes, "%s", ctx->last_scan_name);
+    if (queries_per_pass) *queries_per_pass = ctx->last_scan_qpp;
+    if (passes) *passes = ctx->last_scan_passes;
+    if (parked_lanes) {
+        unsigned long long v[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        if (ctx->stat_parked) PQ_HIP(ctx, hipMemcpy(v, ctx->stat_parked, sizeof(v), hipMemcpyDeviceToHost));
+        *parked_lanes = v[0];
+#ifdef PQ_SCAN_TIMING
+        fprintf(stderr, "scan phases (wave cycles x 1e6): setup %.1f loop %.1f flush %.1f refresh %.1f emit %.1f overflow %.1f\n",
+                v[1] / 1e6, v[2] / 1e6, v[3] / 1e6, v[4] / 1e6, v[5] / 1e6, v[6] / 1e6);
+        fprintf(stderr, "  item results sorted %llu, merged %llu, keys in them %llu\n", v[7], v[8], v[9]);
+#endif
+    }
+    if (inserted_keys) {
+        uint64_t total = 0;
+        uint32_t buf[1024];
+        for (int at = 0; ctx->stat_ncand && at < ctx->stat_ncand_len; at += 1024) {
+            const int take = ctx->stat_ncand_len - at < 1024 ? ctx->stat_ncand_len - at : 1024;
+            PQ_HIP(ctx, hipMemcpy(buf, ctx->stat_ncand + at, (size_t)take * 4, hipMemcpyDeviceToHost));
+            for (int i = 0; i < take; ++i) total += buf[i];
+        }
+        *inserted_keys = total;
+    }
+    return PQ_OK;
+}
+
 int pq_calibration_copy(pq_ctx *ctx, const void *src, void *dst, size_t bytes) {
     if (!ctx) return PQ_EINVAL;
     if (!src || !dst || bytes % 16 != 0 || !aligned16(src) || !aligned16(dst))

@@ -25,6 +25,12 @@ struct pq_ctx {
     int profiling;              // bracket the scan kernel with events
     hipEvent_t ev_begin, ev_end;
     int ev_valid;
+    // measurement aids (valid while profiling): the scan kernel last launched, and where its counters live in the workspace
+    char last_scan_name[160];
+    int last_scan_qpp, last_scan_passes;
+    const unsigned long long *stat_parked;
+    const uint32_t *stat_ncand;
+    int stat_ncand_len;
     char err[512];
 };
 
@@ -44,6 +50,16 @@ int ws_reserve(pq_ctx *ctx, size_t bytes);
 
 // value of a switch, or dflt if it was never set
 static inline int opt_int(const pq_ctx *ctx, int id, int dflt) { return ctx->opt[id] == PQ_OPT_UNSET ? dflt : ctx->opt[id]; }
+
+// measurement aid: a scan kernel without counters of its own is about to be launched
+static inline void note_plain_scan(pq_ctx *ctx, const char *name, int queries_per_pass, int passes) {
+    snprintf(ctx->last_scan_name, sizeof(ctx->last_scan_name), "%s", name);
+    ctx->last_scan_qpp = queries_per_pass;
+    ctx->last_scan_passes = passes;
+    ctx->stat_parked = nullptr;
+    ctx->stat_ncand = nullptr;
+    ctx->stat_ncand_len = 0;
+}
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -45,7 +45,10 @@ struct TunedArgs {
     int nq;
     int topk;
     uint32_t *work_counter;  // next item to hand out
-    uint32_t *tau_global;    // [ngroups*QB] best bound known per query, ordered-value domain
+    unsigned long long *stats;   // measurement aid (nullptr unless profiling is on): [0] lanes parked for the insert path
+    unsigned long long *tau_key;   // [ngroups*QB] best bound known per query, a whole key (ordered value << 32 | row): at least k
+                                   // keys are at or below it.  A bound on the value alone is stored with the last row
+                                   // (0xffffffff).  Values cannot separate codes that tie at the k-th value; their rows can.
     uint32_t *ncand;         // [ngroups*QB] number of insert events per query
     uint32_t *refresh_mark;  // [ngroups*QB] value of ncand when the histogram was last evaluated
     uint32_t *tau_ref;       // [ngroups*QB] reference value of the histogram bins (float path), UNSET at first
@@ -76,22 +79,22 @@ struct TunedArgs {
 
 int launch_merge_topk(pq_ctx *ctx, const uint64_t *partial, int nchunks, int ngroups, int qb, int kpad, int nq,
                       int topk, bool val_u32, void *out_val, int64_t *out_ids);
-// merge of the per-query result lists of a scan that leaves a final bound per query in tau_global
+// merge of the per-query result lists of a scan that leaves a final bound per query in tau_key
 // (see merge_filtered_kernel); any number of lists
 int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *qlist_off, int nchunks, int ngroups, int qb,
-                          const uint32_t *tau_global, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
+                          const unsigned long long *tau_key, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
                           void *out_val, int64_t *out_ids);
 // IVF: run the persistent scan kernel over a table of work items (see IvfItem).  `state` is a
 // caller-provided device region of tuned_state_bytes() bytes holding the per-query bounds,
 // histograms and the per-block candidate scratch; tau0 (optional, [nq]) seeds the per-query bounds
-// (+inf: none); *tau_global_out receives the per-query bounds.
+// (+inf: none); *tau_key_out receives the per-query bounds.
 namespace w16 {
 size_t tuned_state_bytes(int kind, int nq, int topk, int num_cu);
 int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float *pair_off, const float *pair_scale,
                       const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
-                      const float *tau0, uint32_t **tau_global_out);
+                      const float *tau0, unsigned long long **tau_key_out);
 int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, const void *luts, int nq, int topk,
                       void *out_val, int64_t *out_ids);
 }  // namespace w16
@@ -101,7 +104,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float 
                       const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
-                      const float *tau0, uint32_t **tau_global_out);
+                      const float *tau0, unsigned long long **tau_key_out);
 }  // namespace w8
 
 // ------------------------------------------------------------------------------------------

@@ -185,7 +185,7 @@ template <bool VAL_U32>
 __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__restrict__ partial,
                                                               const uint32_t *__restrict__ qlist_off, int nchunks,
                                                               int ngroups, int qb,
-                                                              const uint32_t *__restrict__ tau_global, int kpad, int topk,
+                                                              const unsigned long long *__restrict__ tau_key, int kpad, int topk,
                                                               const int64_t *__restrict__ ids, void *out_val,
                                                               int64_t *out_ids) {
     extern __shared__ uint64_t skeys[];
@@ -207,11 +207,11 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
             }
         }
     };
-    const uint32_t tau = tau_global[gq];
+    const uint64_t tau_k = tau_key[gq];   // a whole key at or below which k keys exist (rows separate ties of the value)
     if (tid == 0) s_count = 0;
     __syncthreads();
     for_each_key([&](uint64_t key) {
-        if (key != KEY_EMPTY && (uint32_t)(key >> 32) <= tau) {
+        if (key != KEY_EMPTY && key <= tau_k) {
             const int pos = atomicAdd(&s_count, 1);
             if (pos < MERGE_CAP) skeys[pos] = key;
         }
@@ -257,19 +257,19 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
 }
 
 int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *qlist_off, int nchunks, int ngroups, int qb,
-                          const uint32_t *tau_global, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
+                          const unsigned long long *tau_key, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
                           void *out_val, int64_t *out_ids) {
     if (nq == 0) return PQ_OK;
     if (val_u32) {
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
-        merge_filtered_kernel<true><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb, tau_global,
-                                                                             kpad, topk, ids, out_val, out_ids);
+        merge_filtered_kernel<true><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
+                                                                             tau_key, kpad, topk, ids, out_val, out_ids);
     } else {
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<false>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
         merge_filtered_kernel<false><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
-                                                                              tau_global, kpad, topk, ids, out_val, out_ids);
+                                                                              tau_key, kpad, topk, ids, out_val, out_ids);
     }
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
@@ -337,7 +337,10 @@ static int run_generic(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, con
     init_tau_kernel<<<(ntau + 255) / 256, 256, 0, ctx->stream>>>(a.tau_global, ntau,
                                                                  lut_u8 ? 0xfffffffeu : 0xff800000u /* ordered +inf */);
     PQ_HIP(ctx, hipGetLastError());
-    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    if (ctx->profiling) {
+        note_plain_scan(ctx, "scan_generic_kernel (one query per block)", 1, nq);
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    }
     hipStream_t s = ctx->stream;
     if (lut_u8) {
         if (small) scan_generic_kernel<true, 4, 128><<<nblocks, SCAN_THREADS, 0, s>>>(a, m, k, cf);

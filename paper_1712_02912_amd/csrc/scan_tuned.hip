@@ -27,6 +27,7 @@
 // units, below a per-query reference (the first bound any wave publishes): bin width 2^14
 // units (about 0.2 % of the value), 4096 bins reaching down to 1/256 of the reference, smaller
 // values lumped in the first bin; candidates seen before the reference exists are not counted.
+#include <stddef.h>
 #include <type_traits>
 
 #include "pq_internal.h"
@@ -76,14 +77,18 @@ struct __align__(16) TunedSmemT {
     uint32_t eff_tmp[TUNED_WAVES][16];   // 16-query insert path: the float bounds of the batch being inserted
     WaveState ws[TUNED_WAVES];
     uint32_t tau_blk[16];   // best bound known to the block per query (prunes with "<=")
+    unsigned long long tau_key_blk[16];   // the same as a whole key (value, row): keys above it are no candidates
+    unsigned long long *tau_key_global[16];
     int out_cnt[16];        // keys handed to the item's result list of each query so far
     uint32_t ncand_blk[16]; // candidates inserted by the block and not yet added to the query's device counter
     uint32_t tau_ref[16];   // histogram reference per query (float path)
+    uint32_t hwin_base[16]; // first bin of the query's histogram window (see hist_count)
+    unsigned long long stat_parked;   // measurement aid: positions the block's waves have parked
+    uint32_t hwin_pending[16];   // keys the block has counted for the query since it last moved the window to device memory
     // per item, written at its start: where the state of the query in each slot lives
     uint32_t *hist[16];
     uint32_t *ncand[16];
     uint32_t *refresh_mark[16];
-    uint32_t *tau_global[16];
     uint32_t *tau_ref_global[16];
     const void *slot_lut[16];   // tables of the slot's query (nullptr: empty slot)
     uint64_t *slot_out[16];     // where the slot's KPAD result keys go
@@ -105,15 +110,37 @@ struct __align__(16) TunedSmemT {
 typedef __attribute__((address_space(3))) WaveState LdsWaveState;
 
 
-// KIND_F32P_M8 / _M16: the 8 x 256 and 16 x 256 float scans with pruning by 16-bit lower bounds
-// (see scan_flush_pruned)
-// the sort of `count` keys pads them to a power of two, which must fit as well
-__device__ __forceinline__ bool n2_fits(int count, int capacity) {
-    int n2 = 64;
-    while (n2 < count) n2 <<= 1;
-    return n2 <= capacity;
+// Candidate histograms.  Every inserted key is counted in a bin of its query's histogram in device memory, from
+// which the shared bound is read.  The keys a block inserts during an item lie at or below the bound the item
+// started with and crowd just under it (on encoded data thousands of codes share a handful of integer sums), and
+// device-scope atomic adds to one word serialise at the memory side.  The block therefore counts the HWIN bins
+// up to that bound in LDS (in the memory that staged the 8-bit tables, which is idle while codes are scanned)
+// and adds the window to the device histogram when one of its waves is about to read it (scan_refresh) and at
+// the end of the item; keys below the window go to the device histogram directly.  A bound read from counts
+// that miss another block's window is looser than it could be, never wrong.
+constexpr int HWIN = 64;
+typedef __attribute__((address_space(3))) uint32_t LdsU32;
+template <class SM>
+__device__ __forceinline__ LdsU32 *hist_window(LDS_PTR(SM) sm, int q) {
+
+    return (LdsU32 *)&sm->qstage[0][0] + q * HWIN;
+}
+template <class SM>
+__device__ __forceinline__ void hist_count(LDS_PTR(SM) sm, int q, uint32_t bin) {
+    const uint32_t rel = bin - sm->hwin_base[q];
+    if (rel < (uint32_t)HWIN) __hip_atomic_fetch_add(hist_window(sm, q) + rel, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    else __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// one wave: move the window of query q into the device histogram
+template <class SM>
+__device__ __forceinline__ void hist_window_flush(LDS_PTR(SM) sm, int q) {
+    const int lane = lane_id();
+    const uint32_t v = __hip_atomic_exchange(hist_window(sm, q) + lane, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (v != 0u) __hip_atomic_fetch_add(sm->hist[q] + sm->hwin_base[q] + lane, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// KIND_F32P_M8 / _M16: the 8 x 256 and 16 x 256 float scans with pruning by 16-bit lower bounds
+// (see scan_flush_pruned)
 enum { KIND_F32_M8 = 0, KIND_F32_M16 = 1, KIND_U4_M16 = 2, KIND_F32P_M8 = 3, KIND_F32P_M16 = 4, KIND_F32Q_M8 = 5, KIND_U4Q_M16 = 6 };
 constexpr int SEED_CODES_BATCH = 1 << 15;   // codes looked at for the first bound of a float scan of many query groups
 constexpr int SEED_CODES_STREAM = 1 << 16;  // codes looked at for the first bound when few groups share the GPU (<= PRUNE_MIN_N)
@@ -209,8 +236,18 @@ __device__ __forceinline__ void code_values(const uint4 c, const LaneWalk<NT> &l
 
 template <class SM>
 __device__ __forceinline__ void publish_bound(LDS_PTR(SM) sm, int q, uint32_t ord) {
+    // a bound on the value alone is the key (value, last row)
+    const unsigned long long key = ((unsigned long long)ord << 32) | 0xffffffffull;
     __hip_atomic_fetch_min(&sm->tau_blk[q], ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    atomicMin(sm->tau_global[q], ord);
+    __hip_atomic_fetch_min(&sm->tau_key_blk[q], key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    atomicMin(sm->tau_key_global[q], key);
+}
+// `key` is the k-th smallest key of some set of the query's codes: no key above it belongs to the result
+template <class SM>
+__device__ __forceinline__ void publish_key_bound(LDS_PTR(SM) sm, int q, uint64_t key) {
+    __hip_atomic_fetch_min(&sm->tau_blk[q], (uint32_t)(key >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __hip_atomic_fetch_min(&sm->tau_key_blk[q], (unsigned long long)key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    atomicMin(sm->tau_key_global[q], (unsigned long long)key);
 }
 
 // Rare path: the candidate list of query q of this wave is nearly full.  Keep its k smallest
@@ -222,8 +259,10 @@ __device__ __noinline__ int scan_compact(LDS_PTR(SM) sm, uint64_t *buf, int cnt,
     const uint64_t kth = wave_compact<E>(buf, cnt, sm->topk);
     if (kth != KEY_EMPTY) {
         const uint32_t kord = (uint32_t)(kth >> 32);
-        if (lane == 0) ws->own_ord[q] = kord;
-        publish_bound(sm, q, kord);
+        if (lane == 0) {
+            ws->own_ord[q] = kord;
+            publish_key_bound(sm, q, kth);
+        }
         if (!INTVAL && sm->tau_ref[q] == TAU_REF_UNSET) {
             // the first bound published for a query becomes the reference of its histogram
             uint32_t expected = TAU_REF_UNSET;
@@ -329,8 +368,10 @@ __device__ __noinline__ int scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int n
             } else {
                 ord = f32_to_ord(__uint_as_float(q == 0 ? lo : q == 1 ? l1 : q == 2 ? l2 : l3));
             }
+            const uint64_t key = ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h));
+            if (key > sm->tau_key_blk[q]) { m &= ~(1u << b); continue; }   // ties with the k-th value beyond the k-th row
             const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            key_store(wave_buf + (size_t)q * CAP + slot, ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
+            key_store(wave_buf + (size_t)q * CAP + slot, key);
             const uint32_t ref = IS_U4 ? 0u : sm->tau_ref[q];
             if (IS_U4 || (ref != TAU_REF_UNSET && ord <= ref)) {
                 uint32_t bin;
@@ -340,7 +381,7 @@ __device__ __noinline__ int scan_flush(LDS_PTR(SM) sm, uint64_t *wave_buf, int n
                     const uint32_t below = (ref - ord) >> HIST_SHIFT;
                     bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
                 }
-                __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                hist_count(sm, q, bin);
             }
         }
         // candidates seen per query (paces the histogram evaluations)
@@ -563,15 +604,16 @@ __device__ __noinline__ int scan_flush_pruned(LDS_PTR(SM) sm, uint64_t *wave_buf
 #pragma unroll
                 for (int i = 1; i < QB; ++i) eff = q == i ? eff_q[i] : eff;
             }
-            if (ord < eff) {
+            const uint64_t key = ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h));
+            if (ord < eff && key <= sm->tau_key_blk[q]) {
                 inserted |= 1u << b;
                 const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                key_store(wave_buf + (size_t)q * CAP + slot, ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
+                key_store(wave_buf + (size_t)q * CAP + slot, key);
                 const uint32_t ref = sm->tau_ref[q];
                 if (ref != TAU_REF_UNSET && ord <= ref) {
                     const uint32_t below = (ref - ord) >> HIST_SHIFT;
                     const uint32_t bin = HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1);
-                    __hip_atomic_fetch_add(sm->hist[q] + bin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    hist_count(sm, q, bin);
                 }
             }
         }
@@ -666,9 +708,11 @@ __device__ __noinline__ int scan_flush_u4q(LDS_PTR(SM) sm, uint64_t *wave_buf, i
 #pragma unroll
             for (int i = 1; i < 8; ++i) pk = pp == i ? (h == 0 ? acc[0][i] : acc[1][i]) : pk;
             const uint32_t ord = (pk >> (16 * (q & 1))) & 0xffffu;
+            const uint64_t key = ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h));
+            if (key > sm->tau_key_blk[q]) { m &= ~(1u << b); continue; }   // ties with the k-th value beyond the k-th row
             const int slot = __hip_atomic_fetch_add(&ws->cnt[q], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-            key_store(wave_buf + (size_t)q * CAP + slot, ((uint64_t)ord << 32) | (row0 + (uint32_t)(pos + h)));
-            __hip_atomic_fetch_add(sm->hist[q] + (ord < HIST_BINS ? ord : HIST_BINS - 1), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            key_store(wave_buf + (size_t)q * CAP + slot, key);
+            hist_count(sm, q, ord < HIST_BINS ? ord : HIST_BINS - 1);
         }
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
@@ -689,16 +733,29 @@ constexpr uint32_t REFRESH_MIN_NEW = 16;
 template <class SM, bool IS_U4>
 __device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     // the four device words of the query are independent of one another: one round trip
-    const uint32_t g = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long gk = __hip_atomic_load(sm->tau_key_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t g = (uint32_t)(gk >> 32);
     // (the block's own count of new candidates goes into the device counter on this occasion)
-    uint32_t n_v = 0;
+    // The block's histogram window goes to device memory once it holds a worthwhile share of a result list (a
+    // quarter, 16 .. 256 keys): moving it costs up to HWIN device-scope atomic adds on this wave's path.
+    uint32_t n_v = 0, flush_v = 0;
     if (lane_id() == 0) {
         const uint32_t mine = __hip_atomic_exchange(&sm->ncand_blk[q], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         n_v = __hip_atomic_fetch_add(sm->ncand[q], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + mine;
+        const uint32_t pending = __hip_atomic_fetch_add(&sm->hwin_pending[q], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) + mine;
+        const uint32_t quarter = (uint32_t)sm->topk / 4u;
+        if (pending >= (quarter < 16u ? 16u : quarter > 256u ? 256u : quarter)) {
+            sm->hwin_pending[q] = 0u;
+            flush_v = 1u;
+        }
     }
+    if (__builtin_amdgcn_readfirstlane(flush_v) != 0u) hist_window_flush(sm, q);
     const uint32_t mark_v = __hip_atomic_load(sm->refresh_mark[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t ref_v = IS_U4 ? 0u : __hip_atomic_load(sm->tau_ref_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane_id() == 0) __hip_atomic_fetch_min(&sm->tau_blk[q], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (lane_id() == 0) {
+        __hip_atomic_fetch_min(&sm->tau_blk[q], g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_min(&sm->tau_key_blk[q], gk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
     uint32_t ref = 0;
     if (!IS_U4) {
         ref = __builtin_amdgcn_readfirstlane(sm->tau_ref[q]);
@@ -722,7 +779,7 @@ __device__ __noinline__ void scan_refresh(LDS_PTR(SM) sm, int q) {
     if (bin < HIST_BINS) {
         // every value counted in bins <= bin is at or below this edge
         const uint32_t edge = IS_U4 ? (uint32_t)bin : ref - ((uint32_t)(HIST_BINS - 1 - bin) << HIST_SHIFT);
-        publish_bound(sm, q, edge);
+        if (lane_id() == 0) publish_bound(sm, q, edge);
     }
 }
 
@@ -752,18 +809,22 @@ __device__ __noinline__ void scan_emit_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) 
     list_fence();
     // lane q: the bound of query q, the better of the block's and the device's current one
     const int ql = lane & (QB - 1);
-    const uint32_t dev_bound = __hip_atomic_load(sm->tau_global[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long dev_key = __hip_atomic_load(sm->tau_key_global[ql], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long blk_key = sm->tau_key_blk[ql];
+    const unsigned long long key_lane = dev_key < blk_key ? dev_key : blk_key;
     const uint32_t blk_bound = sm->tau_blk[ql];
-    const uint32_t bound_lane = dev_bound < blk_bound ? dev_bound : blk_bound;
+    const uint32_t bound_lane = (uint32_t)(key_lane >> 32) < blk_bound ? (uint32_t)(key_lane >> 32) : blk_bound;
     for (int q = 0; q < sm->nvalid && q < QB; ++q) {
         const int cnt = ws->cnt[q];
         if (cnt == 0) continue;
         const uint32_t bound = __builtin_amdgcn_readlane(bound_lane, q);
+        const uint64_t key_bound = ((uint64_t)__builtin_amdgcn_readlane((uint32_t)(key_lane >> 32), q) << 32) |
+                                   __builtin_amdgcn_readlane((uint32_t)key_lane, q);
         uint64_t *out = sm->slot_out[q];
         const uint64_t *buf = wave_buf + (size_t)q * CAP;
         for (int i0 = 0; i0 < cnt; i0 += 64) {
             const uint64_t key = i0 + lane < cnt ? key_load(buf + i0 + lane) : KEY_EMPTY;
-            const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound;
+            const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound && key <= key_bound;
             const uint64_t mask = __ballot(pass);
             if (mask == 0ull) continue;
             int at = 0;
@@ -775,24 +836,27 @@ __device__ __noinline__ void scan_emit_wave(LDS_PTR(SM) sm, uint64_t *wave_buf) 
 }
 
 // End of item, whole block, for a query whose result list overflowed but whose keys within the
-// bound fit into the (now idle) ring memory: gather them there, sort them with the whole block
-// and write the KPAD smallest.  Every thread of the block must call it.
+// bound fit into the memory of the tables (idle once every wave has left the scan; the next item
+// stages them anew): gather them there, sort them with the whole block, write the KPAD smallest
+// and share the k-th as a bound.  Every thread of the block must call it.
 template <class SM, int QB, int E, int KPAD>
 __device__ __noinline__ void scan_overflow_sort(LDS_PTR(SM) sm, uint64_t *wave_buf, int q) {
     constexpr int CAP = 64 * E;
     const int lane = lane_id();
     LdsWaveState *ws = &sm->ws[threadIdx.x >> 6];
-    uint64_t *keys = (uint64_t *)&sm->ring[0][0];   // generic pointer into LDS
+    uint64_t *keys = (uint64_t *)&sm->lut[0];   // generic pointer into LDS (lut16 follows lut without a gap)
     if (threadIdx.x == 0) sm->out_cnt[q] = 0;
     __syncthreads();
-    const uint32_t dev_bound = __hip_atomic_load(sm->tau_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long dev_key = __hip_atomic_load(sm->tau_key_global[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long blk_key = sm->tau_key_blk[q];
+    const uint64_t key_bound = dev_key < blk_key ? dev_key : blk_key;       // never above the bounds of the first pass
     const uint32_t blk_bound = sm->tau_blk[q];
-    const uint32_t bound = dev_bound < blk_bound ? dev_bound : blk_bound;   // never above the bound of the first pass
+    const uint32_t bound = (uint32_t)(key_bound >> 32) < blk_bound ? (uint32_t)(key_bound >> 32) : blk_bound;
     const int cnt = ws->cnt[q];
     const uint64_t *buf = wave_buf + (size_t)q * CAP;
     for (int i0 = 0; i0 < cnt; i0 += 64) {
         const uint64_t key = i0 + lane < cnt ? key_load(buf + i0 + lane) : KEY_EMPTY;
-        const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound;
+        const bool pass = key != KEY_EMPTY && (uint32_t)(key >> 32) <= bound && key <= key_bound;
         const uint64_t mask = __ballot(pass);
         if (mask == 0ull) continue;
         int at = 0;
@@ -808,6 +872,8 @@ __device__ __noinline__ void scan_overflow_sort(LDS_PTR(SM) sm, uint64_t *wave_b
     block_bitonic_sort(keys, n2);
     uint64_t *out = sm->slot_out[q];
     for (int i = threadIdx.x; i < KPAD; i += TUNED_THREADS) out[i] = i < n2 ? keys[i] : KEY_EMPTY;
+    // the k-th smallest key of the item bounds the k-th smallest of the whole scan
+    if (threadIdx.x == 0 && total >= sm->topk) publish_key_bound(sm, q, keys[sm->topk - 1]);
     __syncthreads();
 }
 
@@ -820,17 +886,28 @@ __device__ __noinline__ void scan_merge_item(LDS_PTR(SM) sm, uint64_t *block_scr
     const int k = sm->topk;
     uint64_t *acc = block_scratch + (size_t)q * CAP;   // list of wave 0
     int cnt = sm->ws[0].cnt[q];
+    uint64_t kth = KEY_EMPTY;
     for (int w = 1; w < TUNED_WAVES; ++w) {
         const uint64_t *src = block_scratch + (size_t)(w * QB + q) * CAP;
         const int cw = sm->ws[w].cnt[q];
         if (cw == 0) continue;
         for (int i = lane; i < cw; i += 64) key_store(acc + cnt + i, key_load(src + i));
         cnt += cw;
-        if (cnt > k) wave_compact<E>(acc, cnt, k);
+        if (cnt > k) kth = wave_compact<E>(acc, cnt, k);
     }
+    if (kth != KEY_EMPTY && lane == 0) publish_key_bound(sm, q, kth);
     if (cnt > 0) list_fence();
     for (int i = lane; i < KPAD; i += 64) out[i] = i < cnt ? key_load(acc + i) : KEY_EMPTY;
 }
+
+// Optional instrumentation (-DPQ_SCAN_TIMING, measurement builds only): wall-clock cycles of every wave per
+// phase, added up in stats[1 + phase] when the wave leaves the kernel.
+#ifdef PQ_SCAN_TIMING
+#define PQ_TICK(phase) do { const unsigned long long now__ = __builtin_amdgcn_s_memtime(); tick_acc[phase] += now__ - tick_last; tick_last = now__; } while (0)
+#else
+#define PQ_TICK(phase) do { } while (0)
+#endif
+enum { TICK_SETUP = 0, TICK_LOOP, TICK_FLUSH, TICK_REFRESH, TICK_EMIT, TICK_OVERFLOW, TICK_COUNT };
 
 template <int KIND, int E, int KPAD, int DEPTH>
 __global__ __launch_bounds__(TUNED_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4)))
@@ -865,11 +942,28 @@ void scan_tuned_kernel(TunedArgs a) {
 
     const int nitems = a.item_tab ? (int)*a.nitems_dev : a.nitems;
     int gstep = 0;   // steps of this wave over all its items: paces the periodic bound refresh
+    unsigned long long parked_total = 0;   // positions this wave has handed to the insert path (uniform; reported when profiling)
+    if (threadIdx.x == 0) sm.stat_parked = 0ull;
+#ifdef PQ_SCAN_TIMING
+    unsigned long long tick_acc[TICK_COUNT] = {0, 0, 0, 0, 0, 0}, tick_last = __builtin_amdgcn_s_memtime();
+#endif
     for (;;) {
         if (threadIdx.x == 0) sm.item = (int)atomicAdd(a.work_counter, 1u);
         __syncthreads();
         const int item = sm.item;
-        if (item >= nitems) break;
+        if (item >= nitems) {
+            if (a.stats != nullptr) {   // one device atomic per block: thousands of waves adding to one word would serialise
+                if (lane == 0 && parked_total != 0ull)
+                    __hip_atomic_fetch_add(&sm.stat_parked, parked_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __syncthreads();
+                if (threadIdx.x == 0 && sm.stat_parked != 0ull) atomicAdd(a.stats, sm.stat_parked);
+            }
+#ifdef PQ_SCAN_TIMING
+            if (a.stats != nullptr && lane == 0)
+                for (int i = 0; i < TICK_COUNT; ++i) atomicAdd(a.stats + 1 + i, tick_acc[i]);
+#endif
+            break;
+        }
 
         // ---- describe the item: rows to scan, and for every slot the query whose tables it holds ----
         if (threadIdx.x < QB) {
@@ -936,14 +1030,16 @@ void scan_tuned_kernel(TunedArgs a) {
             sm.hist[s] = a.hist + (size_t)sq * HIST_BINS;
             sm.ncand[s] = a.ncand + sq;
             sm.refresh_mark[s] = a.refresh_mark + sq;
-            sm.tau_global[s] = a.tau_global + sq;
+            sm.tau_key_global[s] = a.tau_key + sq;
+            const unsigned long long start_key = qid < 0 ? 0ull : __hip_atomic_load(&a.tau_key[sq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sm.tau_key_blk[s] = start_key;
             sm.tau_ref_global[s] = a.tau_ref + sq;
-            sm.tau_blk[s] = qid < 0 ? 0u : __hip_atomic_load(&a.tau_global[sq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sm.tau_blk[s] = (uint32_t)(start_key >> 32);
             sm.tau_ref[s] = __hip_atomic_load(&a.tau_ref[sq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (s == 0) sm.topk = a.topk;
         }
         if (lane < QB) { sm.ws[wave].cnt[lane] = 0; sm.ws[wave].own_ord[lane] = V::ord_inf(); }
-        if (threadIdx.x < 16) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; }
+        if (threadIdx.x < 16) { sm.out_cnt[threadIdx.x] = 0; sm.ncand_blk[threadIdx.x] = 0; sm.hwin_pending[threadIdx.x] = 0; }
         if (threadIdx.x == 0) sm.next_group = 2 * TUNED_WAVES;
         __syncthreads();
 
@@ -1090,7 +1186,26 @@ void scan_tuned_kernel(TunedArgs a) {
             }
         }
         __syncthreads();
+        // the staging memory now serves as the histogram windows of the slots' queries: HWIN bins up to the bin
+        // of the bound the item starts with
+        for (int i = threadIdx.x; i < QB * HWIN; i += TUNED_THREADS) hist_window(smp, 0)[i] = 0u;
+        if (threadIdx.x < QB) {
+            const uint32_t bound = sm.tau_blk[threadIdx.x];
+            uint32_t top = HIST_BINS - 1;
+            if constexpr (IS_U4) {
+                top = bound < (uint32_t)HIST_BINS ? bound : HIST_BINS - 1;
+            } else {
+                const uint32_t ref = sm.tau_ref[threadIdx.x];
+                if (ref != TAU_REF_UNSET && bound <= ref) {
+                    const uint32_t below = (ref - bound) >> HIST_SHIFT;
+                    top = HIST_BINS - 1 - (below < (uint32_t)HIST_BINS ? below : HIST_BINS - 1);
+                }
+            }
+            sm.hwin_base[threadIdx.x] = top >= (uint32_t)(HWIN - 1) ? top - (HWIN - 1) : 0u;
+        }
+        __syncthreads();
 
+        PQ_TICK(TICK_SETUP);
         const int nvalid_q = sm.nvalid;
         int ring_cnt = 0;                  // positions parked in this wave's ring (uniform)
         // Thresholds in registers: a code is a candidate for query q if value < tau[q].
@@ -1225,10 +1340,12 @@ void scan_tuned_kernel(TunedArgs a) {
         };
         auto between_steps = [&]() {
             bool changed = false;
+            PQ_TICK(TICK_LOOP);
             if (flush_due()) {
                 // A full ring is drained in whole batches of 64 positions (every lane of the insert path busy); what
                 // is left over moves to the front and waits for company.  The periodic drain takes everything.
                 const int take = ring_cnt > RING_FLUSH ? (ring_cnt & ~63) : ring_cnt;
+                parked_total += (unsigned long long)take;
                 int appended;
                 if constexpr (PRUNED) appended = scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, take);
                 else if constexpr (U4Q) appended = scan_flush_u4q<SM, E>(smp, wave_buf, take);
@@ -1242,11 +1359,13 @@ void scan_tuned_kernel(TunedArgs a) {
                 }
                 ring_cnt = left;
                 changed = true;
+                PQ_TICK(TICK_FLUSH);
             }
             // a wave that keeps finding candidates asks for a new bound without waiting for its turn
             if (refresh_due() || (refresher && pressure >= KPAD / 2)) {
                 scan_refresh<SM, IS_U4>(smp, my_q);
                 pressure = 0;
+                PQ_TICK(TICK_REFRESH);
             }
             if (changed || step < 32 || (step & 3) == 0) reload_tau();
         };
@@ -1299,29 +1418,42 @@ void scan_tuned_kernel(TunedArgs a) {
         }
 
         // ---- end of item: merge the wave lists of each query ------------------------------------
+        PQ_TICK(TICK_LOOP);
         if (ring_cnt > 0) {
+            parked_total += (unsigned long long)ring_cnt;
             if constexpr (PRUNED) scan_flush_pruned<SM, NT, E, QB>(smp, wave_buf, ring_cnt);
             else if constexpr (U4Q) scan_flush_u4q<SM, E>(smp, wave_buf, ring_cnt);
             else scan_flush<SM, KIND, E>(smp, wave_buf, ring_cnt);
         }
+        PQ_TICK(TICK_FLUSH);
         scan_emit_wave<SM, QB, E, KPAD>(smp, wave_buf);
         __syncthreads();   // (orders the waves' scratch writes within the block as well)
+        PQ_TICK(TICK_EMIT);
+        if (wave < QB) hist_window_flush(smp, wave);   // (every insert of the item is done)
         if (wave == TUNED_WAVES - 1 && lane < QB && sm.ncand_blk[lane] != 0u)   // what the block has not reported yet
             __hip_atomic_fetch_add(sm.ncand[lane], sm.ncand_blk[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // Queries whose result list overflowed (loose bounds, first items): if their keys within the
         // bound fit into the ring memory they are sorted there; otherwise every wave's list is cut to
         // its k smallest keys and the lists are merged.
-        constexpr int RING_KEYS = (int)(sizeof(sm.ring) / 8) & ~63;
+        constexpr int SORT_KEYS = Q8 ? 16384 : 8192;   // the tables' 64 KB (128 KB with the second set) as 64-bit keys
+        static_assert(offsetof(SM, lut16) == sizeof(sm.lut), "the second set of tables follows the first");
         uint32_t overflow = 0, sortable = 0;
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
             const int got = sm.out_cnt[q];
             if (got > KPAD) {
-                if (got <= RING_KEYS && n2_fits(got, RING_KEYS)) sortable |= 1u << q;
+                if (got <= SORT_KEYS) sortable |= 1u << q;
                 else overflow |= 1u << q;
             }
         }
         __syncthreads();   // every wave has read the counters before any of them is reused
+#ifdef PQ_SCAN_TIMING
+        if (a.stats != nullptr && threadIdx.x == 0) {
+            if (sortable) atomicAdd(a.stats + 7, (unsigned long long)__popc(sortable));
+            if (overflow) atomicAdd(a.stats + 8, (unsigned long long)__popc(overflow));
+            for (int q = 0; q < QB; ++q) if (sm.out_cnt[q] > KPAD) atomicAdd(a.stats + 9, (unsigned long long)sm.out_cnt[q]);
+        }
+#endif
         if (__builtin_expect(sortable != 0u, 0)) {
             for (int q = 0; q < QB; ++q)
                 if ((sortable >> q) & 1u) scan_overflow_sort<SM, QB, E, KPAD>(smp, wave_buf, q);
@@ -1339,24 +1471,28 @@ void scan_tuned_kernel(TunedArgs a) {
             }
         }
         __syncthreads();
+        PQ_TICK(TICK_OVERFLOW);
     }
 }
 
 // tau0 (optional, [nq]): a bound already known per query (at least k codes are at or below it);
 // times tau0_scale (1, or slightly more when the scan adds in another order than the bound was
 // computed in) it seeds the shared bound and serves as the reference of the query's histogram.
-__global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_t *ncand, uint32_t *mark,
+__global__ void tuned_init_kernel(uint32_t *work_counter, unsigned long long *tau_key, uint32_t *ncand, uint32_t *mark,
                                   uint32_t *tau_ref, int ntau,
                                   uint32_t tau_value, uint32_t *hist, size_t nhist, const float *tau0, int nq,
                                   float tau0_scale) {
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    if (i0 == 0) *work_counter = 0;
+    if (i0 == 0) {
+        *work_counter = 0;
+        for (int i = 2; i < 32; ++i) work_counter[i] = 0;   // the 64-bit statistics words behind it
+    }
     for (size_t i = i0; i < (size_t)ntau; i += stride) {
         const bool seeded = tau0 != nullptr && i < (size_t)nq && tau0[i] < __builtin_inff();
         // enlarged away from the value whatever its sign (tables handed in need not be distances)
         const float bound = seeded ? tau0[i] + fabsf(tau0[i]) * (tau0_scale - 1.f) : 0.f;
-        tau[i] = seeded ? f32_to_ord(bound) : tau_value;
+        tau_key[i] = ((unsigned long long)(seeded ? f32_to_ord(bound) : tau_value) << 32) | 0xffffffffull;   // (bounds on the value alone: last row)
         tau_ref[i] = seeded ? f32_to_ord(bound) : TAU_REF_UNSET;
         ncand[i] = 0;
         mark[i] = 0;
@@ -1372,7 +1508,7 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, uint32_t *tau, uint32_
 // read, and their sums add up as four 16-bit fields of a 64-bit word.
 constexpr int SEED_QPB = 4;
 __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict__ codes, int cnt,
-                                                       const uint8_t *__restrict__ qluts, int kq, int nq, uint32_t *tau_global) {
+                                                       const uint8_t *__restrict__ qluts, int kq, int nq, unsigned long long *tau_key) {
     static_assert(HIST_BINS == 4096, "sums of 16 bytes index the bins");
     __shared__ __align__(16) uint32_t hist[SEED_QPB][HIST_BINS];
     __shared__ uint8_t tab[SEED_QPB][256];
@@ -1434,7 +1570,57 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
         }
     }
     kth_sums();
-    if (sub == 0 && q0 + myq < nq && cut_s[myq] < 4096u) tau_global[q0 + myq] = cut_s[myq];
+    if (sub == 0 && q0 + myq < nq && cut_s[myq] < 4096u) tau_key[q0 + myq] = ((unsigned long long)cut_s[myq] << 32) | 0xffffffffull;
+    // Integer sums tie: far more than kq codes can share the sum T found above (8-bit tables are coarse where the
+    // codes crowd), and a bound on the sum alone lets all of them through.  Rows decide among ties, so the bound is
+    // handed on as a whole key as well: with r = kq - count(sum < T), the row at the end of the bucket of 1024 sample
+    // rows in which the r-th code with sum T falls.  At least kq codes of the sample have a key at or below (T, that row).
+    constexpr int TIE_BUCKETS = 256;
+    __shared__ uint32_t tie_cnt[SEED_QPB][TIE_BUCKETS];
+    __shared__ uint32_t need_s[SEED_QPB];   // r per query, 0: no key bound wanted
+    __shared__ int any_s;
+    if (tid == 0) any_s = 0;
+    for (int i = tid; i < SEED_QPB * TIE_BUCKETS; i += 1024) (&tie_cnt[0][0])[i] = 0;
+    __syncthreads();
+    if (sub < 64) {   // the first wave of the query's threads: codes below the cut, codes at the cut
+        const uint32_t cut = cut_s[myq];
+        uint32_t below = 0;
+        if (cut < 4096u) for (uint32_t b = sub; b < cut; b += 64) below += hist[myq][b];
+        for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o);
+        if (sub == 0) {
+            uint32_t r = 0;
+            // (worth a pass over the sample only if many codes tie at the cut)
+            if (q0 + myq < nq && cut < 4096u && below < (uint32_t)kq && below + hist[myq][cut] > (uint32_t)kq + 256u &&
+                (cnt + 1023) / 1024 <= TIE_BUCKETS)
+                r = (uint32_t)kq - below;
+            need_s[myq] = r;
+            if (r != 0u) any_s = 1;
+        }
+    }
+    __syncthreads();
+    if (any_s == 0) return;
+    {
+        uint32_t cut[SEED_QPB];
+#pragma unroll
+        for (int qq = 0; qq < SEED_QPB; ++qq) cut[qq] = need_s[qq] != 0u ? cut_s[qq] : 0xffffffffu;
+        for (int i = tid; i < cnt; i += 1024) {
+            const uint64_t acc = code_sums(i);
+#pragma unroll
+            for (int qq = 0; qq < SEED_QPB; ++qq)
+                if (((uint32_t)(acc >> (16 * qq)) & 0xffffu) == cut[qq]) atomicAdd(&tie_cnt[qq][i >> 10], 1u);
+        }
+    }
+    __syncthreads();
+    if (sub == 0 && need_s[myq] != 0u) {
+        uint32_t cum = 0;
+        int b = 0;
+        const int nb = (cnt + 1023) / 1024;
+        while (b < nb && cum + tie_cnt[myq][b] < need_s[myq]) cum += tie_cnt[myq][b++];
+        if (b < nb) {
+            const uint32_t last_row = (uint32_t)((b + 1) * 1024 < cnt ? (b + 1) * 1024 : cnt) - 1u;
+            tau_key[q0 + myq] = ((unsigned long long)cut_s[myq] << 32) | last_row;
+        }
+    }
 }
 
 // The same over more codes than one block can look at (few query groups, large database):
@@ -1474,7 +1660,7 @@ __global__ __launch_bounds__(1024) void u4_seed_hist_kernel(const uint8_t *__res
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * 4096 + i], hist[i]);
 }
 
-__global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int kq, uint32_t *tau_global) {
+__global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int kq, unsigned long long *tau_key) {
     __shared__ uint32_t part[256];
     const int q = blockIdx.x, tid = threadIdx.x;
     const uint32_t *hist = seed_hist + (size_t)q * 4096;
@@ -1489,7 +1675,7 @@ __global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__res
         if (t < 256) {
             int b = t * 16;
             while (cum + hist[b] < (uint32_t)kq) cum += hist[b++];
-            tau_global[q] = (uint32_t)b;
+            tau_key[q] = ((unsigned long long)b << 32) | 0xffffffffull;
         }
     }
 }
@@ -1783,14 +1969,14 @@ static int launch_kind(pq_ctx *ctx, const TunedArgs &a, int nblocks) {
 }
 
 struct StateLayout {
-    size_t off_tau, off_ncand, off_mark, off_ref, off_hist, off_scratch, total;
+    size_t off_key, off_ncand, off_mark, off_ref, off_hist, off_scratch, total;
     size_t nhist;
 };
 
 static StateLayout state_layout(int qb, int ntau, int cap, int nblocks) {
     StateLayout L;
-    L.off_tau = 256;
-    L.off_ncand = L.off_tau + align_up((size_t)ntau * 4, 256);
+    L.off_key = 256;
+    L.off_ncand = L.off_key + align_up((size_t)ntau * 8, 256);
     L.off_mark = L.off_ncand + align_up((size_t)ntau * 4, 256);
     L.off_ref = L.off_mark + align_up((size_t)ntau * 4, 256);
     L.off_hist = L.off_ref + align_up((size_t)ntau * 4, 256);
@@ -1802,7 +1988,8 @@ static StateLayout state_layout(int qb, int ntau, int cap, int nblocks) {
 
 static void bind_state(TunedArgs &a, uint8_t *ws, const StateLayout &L) {
     a.work_counter = (uint32_t *)ws;
-    a.tau_global = (uint32_t *)(ws + L.off_tau);
+    a.stats = nullptr;
+    a.tau_key = (unsigned long long *)(ws + L.off_key);
     a.ncand = (uint32_t *)(ws + L.off_ncand);
     a.refresh_mark = (uint32_t *)(ws + L.off_mark);
     a.tau_ref = (uint32_t *)(ws + L.off_ref);
@@ -1847,6 +2034,20 @@ static int launch_by_kind(pq_ctx *ctx, int kind, bool small, bool stream, const 
     }
 }
 
+// measurement aid: what the scan about to be launched is, and where its counters live
+static void note_scan(pq_ctx *ctx, int kind, int qb, int passes, const unsigned long long *parked, const uint32_t *ncand, int ncand_len) {
+    static const char *const names[] = {"F32_M8 (8x8 float, plain float adds, 4 queries per pass)", "F32_M16 (16x8 float, plain float adds, 4 queries per pass)",
+                                        "U4_M16 (16x4 integer, exact 16-bit sums, 8 queries per pass)",
+                                        "F32P_M8 (8x8 float on 16-bit lower bounds, 8 queries per pass)", "F32P_M16 (16x8 float on 16-bit lower bounds, 8 queries per pass)",
+                                        "F32Q_M8 (8x8 float on 8-bit lower bounds, 16 queries per pass)", "U4Q_M16 (16x4 integer on 8-bit lower bounds, 16 queries per pass)"};
+    snprintf(ctx->last_scan_name, sizeof(ctx->last_scan_name), "scan_tuned_kernel<%s>, blocks of %d waves", kind >= 0 && kind < 7 ? names[kind] : "?", TUNED_WAVES);
+    ctx->last_scan_qpp = qb;
+    ctx->last_scan_passes = passes;
+    ctx->stat_parked = parked;
+    ctx->stat_ncand = ncand;
+    ctx->stat_ncand_len = ncand_len;
+}
+
 static int qb_of_kind(int kind) {
     return kind == KIND_F32Q_M8 || kind == KIND_U4Q_M16 ? 16 : (kind == KIND_U4_M16 || kind == KIND_F32P_M8 || kind == KIND_F32P_M16 ? 8 : 4);
 }
@@ -1864,7 +2065,7 @@ int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float 
                       const uint8_t *codes, const float *luts, int nq, int nprobe, int topk,
                       const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
                       const uint32_t *pair_out, uint64_t *partial, uint8_t *state, size_t state_bytes,
-                      const float *tau0, uint32_t **tau_global_out) {
+                      const float *tau0, unsigned long long **tau_key_out) {
     const int qb = qb_of_kind(kind);
     if ((kind == KIND_F32P_M8 || kind == KIND_F32P_M16) && (!pair_min || !pair_off || !pair_scale))
         return fail(ctx, PQ_EINVAL, "scan_items: the pruned scan needs the pairs' minima, offsets and scales");
@@ -1883,17 +2084,21 @@ int launch_scan_items(pq_ctx *ctx, int kind, const float *pair_min, const float 
     a.nprobe = nprobe;
     a.qtabs = nullptr; a.prune_off = pair_off; a.prune_scale = pair_scale; a.pair_min = pair_min;
     a.qtabs16 = nullptr; a.prune_scale16 = nullptr;
-    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, nq,
+    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_key, a.ncand, a.refresh_mark, a.tau_ref, nq,
                                                      0xff800000u, a.hist, L.nhist, tau0, nq, 1.f);
     PQ_HIP(ctx, hipGetLastError());
-    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    if (ctx->profiling) {
+        a.stats = (unsigned long long *)(state + 8);
+        note_scan(ctx, kind, qb, 0, a.stats, a.ncand, nq);
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    }
     int rc = launch_by_kind(ctx, kind, small, true, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
         ctx->ev_valid = 1;
     }
-    *tau_global_out = a.tau_global;
+    *tau_key_out = a.tau_key;
     return PQ_OK;
 }
 
@@ -2041,7 +2246,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, cb, 256, PRUNE_INIT, topk, tau0);
         if (rc) return rc;
     }
-    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_global, a.ncand, a.refresh_mark, a.tau_ref, ntau,
+    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_key, a.ncand, a.refresh_mark, a.tau_ref, ntau,
                                                      is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq,
                                                      seed_plain ? 1.f + 4e-6f : 1.f);
     PQ_HIP(ctx, hipGetLastError());
@@ -2051,7 +2256,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * 4096);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
             u4_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
-            u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_global);
+            u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_key);
         } else {
             // 256 codes per result wanted, between PRUNE_INIT and 262 144 (top-1000: 4.11 -> 3.94 ms per step; twice as many
             // cost the seed kernel more than they save the scan)
@@ -2063,18 +2268,22 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
                 if (seed_codes < by_queries && (int64_t)by_queries <= n / 16) seed_codes = by_queries;
             }
             if ((int64_t)seed_codes > n) seed_codes = (int)n;
-            u4_seed_kernel<<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, nq, a.tau_global);
+            u4_seed_kernel<<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, seed_codes, (const uint8_t *)luts, topk, nq, a.tau_key);
         }
         PQ_HIP(ctx, hipGetLastError());
     }
-    if (ctx->profiling) PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    if (ctx->profiling) {
+        a.stats = (unsigned long long *)(ws + 8);
+        note_scan(ctx, kind, qb, ngroups, a.stats, a.ncand, ntau);
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, ctx->stream));
+    }
     rc = launch_by_kind(ctx, kind, small, few_groups, a, nblocks);
     if (rc) return rc;
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, ctx->stream));
         ctx->ev_valid = 1;
     }
-    return launch_merge_filtered(ctx, a.partial, nullptr, (int)nchunks, ngroups, qb, a.tau_global, kpad, nq, topk, nullptr, is_u4,
+    return launch_merge_filtered(ctx, a.partial, nullptr, (int)nchunks, ngroups, qb, a.tau_key, kpad, nq, topk, nullptr, is_u4,
                                  out_val, out_ids);
 }
 

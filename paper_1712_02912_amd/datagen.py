@@ -7,7 +7,10 @@ thesis measures on (128-dimensional non-negative byte-range local descriptors,
 billion-code index with 2^16 cells); none of those datasets is reproduced.
 
 All randomness comes from numpy's PCG64 with the seeds below, so that both sides
-of every comparison see bit-identical inputs.
+of every comparison see bit-identical inputs.  Inputs too large to be made on the host in
+reasonable time (tens of millions of vectors, a billion codes) are drawn on the GPU from
+torch's seeded generator by the ``*_device`` functions; they are copied to the host when
+the CPU side needs them.
 """
 import numpy as np
 
@@ -38,6 +41,33 @@ class Mixture:
         comp = r.choice(len(self.weights), size=n, p=self.weights)
         x = self.means[comp] + r.standard_normal((n, self.d)) * self.sigmas[comp][:, None]
         return np.clip(x, self.clip[0], self.clip[1]).astype(np.float32)
+
+
+    def sample_device(self, n, seed, device="cuda"):
+        """The same mixture drawn on the GPU (torch generator seeded with `seed`): [n][d] f32 device tensor."""
+        import torch
+        gen = torch.Generator(device=device).manual_seed(int(seed))
+        w = torch.from_numpy(self.weights).to(device)
+        comp = torch.multinomial(w, n, replacement=True, generator=gen)
+        means = torch.from_numpy(self.means.astype(np.float32)).to(device)
+        sig = torch.from_numpy(self.sigmas.astype(np.float32)).to(device)
+        x = torch.randn((n, self.d), device=device, dtype=torch.float32, generator=gen)
+        x.mul_(sig[comp][:, None]).add_(means[comp])
+        return x.clamp_(self.clip[0], self.clip[1])
+
+
+def random_codes_device(n, code_bytes, seed=SEED_CODES, device="cuda"):
+    """[n][code_bytes] uniformly random bytes drawn on the GPU."""
+    import torch
+    gen = torch.Generator(device=device).manual_seed(int(seed))
+    return torch.randint(0, 256, (n, code_bytes), dtype=torch.uint8, device=device, generator=gen)
+
+
+def tile_rows(unique, n, seed=SEED_CODES + 17):
+    """n rows drawn with replacement (seeded) from the rows of `unique`: a large database with the value
+    distribution of a smaller encoded one (and many exact duplicates)."""
+    idx = _rng(seed).integers(0, unique.shape[0], size=n)
+    return np.ascontiguousarray(unique[idx])
 
 
 def sift_like():

@@ -700,3 +700,65 @@ def test_scan_16_queries_per_pass_first_round_of_short_items(ctx, opts):
         codes = r.integers(0, 256, (n, 8), dtype=np.uint8)
         run_float_scan(ctx, codes, orc.CODES_U8, many_queries(r, nq), topk)
         run_int_scan(ctx, codes, orc.CODES_U4_PACKED, quantized_like_tables(r, nq), topk)
+
+
+# ----------------------------------------------------------------------------- encoded data at full size
+ENC_UNIQUE = 400_000   # vectors encoded by the oracle; the 25 M rows are drawn from them (so every code has ~60 exact copies)
+
+
+def test_full_size_config1_encoded_sampled(ctx):
+    """Config 1 on encoded data: mixture vectors encoded by the oracle against codebooks trained by the oracle's
+    k-means, rows drawn from them to fill 25 M (clustered distances, heavy duplicates: what a pruning scan finds
+    hardest), 1000 queries, top-100; complete results of a sample of the queries against the oracle."""
+    _, _, cb, unique = sift_pq(8, 256, ENC_UNIQUE, 16)
+    codes_h = datagen.tile_rows(unique, FULL_N)
+    queries = dev(datagen.sift_like().sample(FULL_NQ, datagen.SEED_QUERIES))
+    luts = ctx.pq_build_luts(queries, dev(cb))
+    d, i = ctx.pq_adc_scan_topk(dev(codes_h), binding.CODES_U8, luts, 100)
+    gd, gi, luts_h = host(d), host(i), host(luts)
+    od, oi = orc.adc_scan_topk_f32(codes_h, orc.CODES_U8, np.ascontiguousarray(luts_h[SAMPLE_Q]), 100)
+    for r, q in enumerate(SAMPLE_Q):
+        check_float_topk(gd[q], gi[q], od[r], oi[r], codes_h, orc.CODES_U8, luts_h[q], FULL_N)
+        np.testing.assert_allclose(gd[q], od[r], rtol=RTOL)
+    assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < FULL_N
+    assert all(len(set(row.tolist())) == 100 for row in gi[::50])
+
+
+def test_full_size_config2_encoded_sampled(ctx):
+    """Config 2 on encoded data (16 x 4, packed; rows drawn from oracle-encoded vectors): 8-bit tables are coarse where
+    the codes crowd, so thousands of codes tie at the 1000th integer sum and rows decide; stage-wise, bit-exact."""
+    _, _, cb, unique = sift_pq(16, 16, ENC_UNIQUE, 16)
+    fmt = orc.CODES_U4_PACKED
+    packed_h = datagen.tile_rows(orc.pack_u4(unique), FULL_N)
+    queries = dev(datagen.sift_like().sample(FULL_NQ, datagen.SEED_QUERIES))
+    dpacked = dev(packed_h)
+    luts = ctx.pq_build_luts(queries, dev(cb))
+    qmax = ctx.pq_qmax_prescan(dpacked, fmt, luts, 2000, 1000)
+    qluts, _, _ = ctx.pq_quantize_luts(luts, qmax)
+    luts_h, qmax_h, qluts_h = host(luts), host(qmax), host(qluts)
+    ref_q, _, _ = orc.quantize_luts(np.ascontiguousarray(luts_h[SAMPLE_Q]), np.ascontiguousarray(qmax_h[SAMPLE_Q]))
+    assert np.array_equal(qluts_h[SAMPLE_Q], ref_q)
+    for topk in (1000, 100):
+        sums, cand = ctx.pq_adc_scan_topk(dpacked, fmt, qluts, topk)
+        os_, oi = orc.adc_scan_topk_u8(packed_h, fmt, np.ascontiguousarray(qluts_h[SAMPLE_Q]), topk)
+        check_exact_topk(host(sums)[SAMPLE_Q], host(cand)[SAMPLE_Q], os_, oi)
+    # every query: sums ascending, rows valid, distinct, and ascending inside runs of equal sums
+    gs, gc = host(sums).astype(np.int64), host(cand)
+    assert np.all(np.diff(gs, axis=1) >= 0) and gc.min() >= 0 and gc.max() < FULL_N
+    order_key = gs * (1 << 32) + gc
+    assert np.all(np.diff(order_key, axis=1) > 0)
+
+
+@pytest.mark.parametrize("nq", [20, 300])
+def test_scan_u4_ties_at_the_kth_sum_far_beyond_k(ctx, nq):
+    """Tables with entries 0 / 1 / 40: sums take a handful of values and tens of thousands of codes tie at the
+    k-th; the result is the tied codes with the smallest rows.  Both integer loops, short and long lists."""
+    r = np.random.default_rng(91 + nq)
+    n = 400_003
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    qluts = r.choice(np.array([0, 1, 40], dtype=np.uint8), size=(nq, 16, 16), p=[0.5, 0.3, 0.2])
+    qluts[1] = 0          # every code ties
+    qluts[2, :, 1:] = 7   # one cheap entry per table: sums 0, 7, 14, ...
+    qluts[2, :, 0] = 0
+    for topk in (100, 1000, 1):
+        run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, topk)

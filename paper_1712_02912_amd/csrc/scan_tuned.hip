@@ -1901,19 +1901,21 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
         if (gq < nq) {
             float off = 0.f;
             for (int j = 0; j < M; ++j) off += smin[tid][j];
-            const float range = tau0[gq] - off;
-            if (range > 0.f && range < 3.0e38f) {
-                scale = RANGE / range;
-                // the threshold conversion must stay accurate to a fraction of a table unit in fp32
-                if (!(tau0[gq] * scale * 1e-6f < 1.f)) scale = 0.f;
-            }
+            // RANGE units between the sum of the minima and the first bound, but never so many per unit of distance that
+            // the threshold conversion loses a fraction of a table unit in fp32 (bound * scale stays below 10^6).  A bound
+            // that leaves no range at all (k codes and more attain the minima: exact duplicates) takes that finest scale:
+            // any entry above its table's minimum then counts several units and only the duplicates pass.
+            const float bound = tau0[gq], range = bound - off;
+            const float finest = bound > 0.f && bound < 3.0e38f ? 0.99e6f / bound : 0.f;
+            auto scale_for = [&](float units) {
+                float sc = range > 0.f ? units / range : finest;
+                if (!(sc < finest)) sc = finest;
+                return sc > 0.f && sc < 3.0e38f ? sc : 0.f;
+            };
+            scale = scale_for(RANGE);
             if (blockIdx.y == 0) { off_out[gq] = off; scale_out[gq] = scale; }
             if constexpr (Q8) {
-                float scale16 = 0.f;
-                if (range > 0.f && range < 3.0e38f) {
-                    scale16 = PRUNE_RANGE / range;
-                    if (!(tau0[gq] * scale16 * 1e-6f < 1.f)) scale16 = 0.f;
-                }
+                const float scale16 = scale_for(PRUNE_RANGE);
                 if (blockIdx.y == 0) scale16_out[gq] = scale16;
                 sscale16[tid] = scale16;
             }

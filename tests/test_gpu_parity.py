@@ -762,3 +762,23 @@ def test_scan_u4_ties_at_the_kth_sum_far_beyond_k(ctx, nq):
     qluts[2, :, 0] = 0
     for topk in (100, 1000, 1):
         run_int_scan(ctx, packed, orc.CODES_U4_PACKED, qluts, topk)
+
+
+@pytest.mark.parametrize("m,nq", [(8, 5), (8, 300), (16, 5), (16, 40)])
+def test_scan_f32_first_bound_equal_to_the_sum_of_the_table_minima(ctx, m, nq):
+    """More than k codes are exact copies of a query's best possible code (every table entry at its minimum), as
+    happens with encoded high-dimensional data: the first bound leaves no range for the lower-bound tables.
+    Query 0: thousands of copies; query 1: k - 1 copies (the k-th result is an ordinary code); the others: none."""
+    r = np.random.default_rng(300 + m + nq)
+    n, topk = 200_003, 100
+    codes = r.integers(0, 256, (n, m), dtype=np.uint8)
+    luts_h = (r.random((nq, m, 256)) * 50 + r.random((nq, m, 1)) * 100).astype(np.float32)
+    best0 = luts_h[0].argmin(axis=1).astype(np.uint8)
+    best1 = luts_h[1].argmin(axis=1).astype(np.uint8)
+    codes[r.choice(n, 5000, replace=False)] = best0
+    rows1 = r.choice(n, topk - 1, replace=False)
+    codes[rows1] = best1
+    gd, gi, od, oi = run_float_scan(ctx, codes, orc.CODES_U8, luts_h, topk)
+    assert np.all(gd[0] == gd[0][0])                       # a hundred copies of the best code
+    np.testing.assert_allclose(gd, od, rtol=RTOL)
+    run_float_scan(ctx, codes, orc.CODES_U8, luts_h, 1000 if nq <= 40 else 300)

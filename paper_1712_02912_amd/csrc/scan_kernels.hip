@@ -196,14 +196,33 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
     // Every list is packed (its keys first, KEY_EMPTY behind them; kpad is a multiple of 64): a wave
     // takes whole lists, 64 keys at a time, and leaves a list at the first empty slot it sees.
     const int wave = tid >> 6, lane = tid & 63, nwaves = (int)(blockDim.x >> 6);
+    // (the first 64 keys of four lists are requested together: a walk over a thousand short lists is otherwise a
+    // chain of memory round trips)
+    auto list_ptr = [&](size_t l) {
+        const size_t list = qlist_off ? (size_t)qlist_off[gq] + l : (l * ngroups + gq / qb) * qb + gq % qb;
+        return partial + list * kpad;
+    };
     auto for_each_key = [&](auto &&f) {
-        for (size_t l = wave; l < nlists; l += nwaves) {
-            const size_t list = qlist_off ? (size_t)qlist_off[gq] + l : (l * ngroups + gq / qb) * qb + gq % qb;
-            const uint64_t *lp = partial + list * kpad;
-            for (int e0 = 0; e0 < kpad; e0 += 64) {
-                const uint64_t key = lp[e0 + lane];
-                f(key);
-                if (__ballot(key == KEY_EMPTY) != 0ull) break;
+        constexpr int MLP = 4;
+        for (size_t l0 = wave; l0 < nlists; l0 += (size_t)MLP * nwaves) {
+            const uint64_t *lp[MLP];
+            uint64_t first[MLP];
+#pragma unroll
+            for (int u = 0; u < MLP; ++u) {
+                const size_t l = l0 + (size_t)u * nwaves;
+                lp[u] = l < nlists ? list_ptr(l) : nullptr;
+                first[u] = lp[u] ? lp[u][lane] : KEY_EMPTY;
+            }
+#pragma unroll
+            for (int u = 0; u < MLP; ++u) {
+                if (lp[u] == nullptr) continue;
+                uint64_t key = first[u];
+                for (int e0 = 0;;) {
+                    f(key);
+                    e0 += 64;
+                    if (__ballot(key == KEY_EMPTY) != 0ull || e0 >= kpad) break;
+                    key = lp[u][e0 + lane];
+                }
             }
         }
     };

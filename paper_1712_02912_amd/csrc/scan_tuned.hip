@@ -1660,24 +1660,10 @@ __global__ __launch_bounds__(1024) void u4_seed_hist_kernel(const uint8_t *__res
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * 4096 + i], hist[i]);
 }
 
-__global__ __launch_bounds__(256) void u4_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int kq, unsigned long long *tau_key) {
-    __shared__ uint32_t part[256];
-    const int q = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *hist = seed_hist + (size_t)q * 4096;
-    uint32_t mine = 0;
-    for (int i = 0; i < 16; ++i) mine += hist[tid * 16 + i];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t cum = 0;
-        int t = 0;
-        while (t < 256 && cum + part[t] < (uint32_t)kq) cum += part[t++];
-        if (t < 256) {
-            int b = t * 16;
-            while (cum + hist[b] < (uint32_t)kq) cum += hist[b++];
-            tau_key[q] = ((unsigned long long)b << 32) | 0xffffffffull;
-        }
-    }
+__global__ __launch_bounds__(64) void u4_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int kq, unsigned long long *tau_key) {
+    const int q = blockIdx.x;
+    const int b = hist_threshold(seed_hist + (size_t)q * 4096, kq);   // one wave; smallest sum with kq counted codes at or below it
+    if (threadIdx.x == 0 && b < HIST_BINS) tau_key[q] = ((unsigned long long)b << 32) | 0xffffffffull;
 }
 
 // Better first bound (every candidate the first bound lets through costs far more than a code the
@@ -1840,24 +1826,12 @@ __global__ __launch_bounds__(1024) void f32_seed_hist_kernel(const uint8_t *__re
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * HIST_BINS + i], hist[i]);
 }
 
-__global__ __launch_bounds__(256) void f32_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int k, float *tau0) {
-    __shared__ uint32_t part[256];
-    const int q = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *hist = seed_hist + (size_t)q * HIST_BINS;
-    uint32_t mine = 0;
-    for (int i = 0; i < HIST_BINS / 256; ++i) mine += hist[tid * (HIST_BINS / 256) + i];
-    part[tid] = mine;
-    __syncthreads();
-    if (tid == 0) {
+__global__ __launch_bounds__(64) void f32_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int k, float *tau0) {
+    const int q = blockIdx.x;
+    const int b = hist_threshold(seed_hist + (size_t)q * HIST_BINS, k);   // one wave
+    if (threadIdx.x == 0 && b < HIST_BINS) {
         const uint32_t ref = f32_to_ord(tau0[q]);
-        uint32_t cum = 0;
-        int t = 0;
-        while (t < 256 && cum + part[t] < (uint32_t)k) cum += part[t++];
-        if (t < 256) {
-            int b = t * (HIST_BINS / 256);
-            while (cum + hist[b] < (uint32_t)k) cum += hist[b++];
-            tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
-        }
+        tau0[q] = ord_to_f32(ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT));
     }
 }
 
@@ -2151,7 +2125,13 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         if (hc > 0 && c0 * hc * 16 <= n) { head_chunks = (int)c0; head_codes = hc; }
     }
     const int64_t n_head = (int64_t)head_chunks * head_codes, n_main = n - n_head;
-    int64_t nchunks = ((int64_t)opt_int(ctx, PQ_OPT_SCAN_ITEMS_PER_BLOCK, q8 || u4q ? 6 : 4) * nblocks_max + ngroups - 1) / ngroups;
+    // Up to 8 query groups over a large database (streaming shape): one item per block.  All items are equally long there,
+    // so nothing is gained by handing out several, and every item pays its set-up (tables, bounds, first codes) and
+    // leaves a result list for the merge (10^8 codes, one query: scan 0.21 -> 0.19 ms, call 0.39 -> 0.34 ms).
+    const int ipb_default = q8 || u4q ? 6 : (ngroups <= 8 && (nq + qb - 1) / qb < STREAM_GROUPS && n >= ((int64_t)1 << 22) ? 1 : 4);
+    const int ipb = opt_int(ctx, PQ_OPT_SCAN_ITEMS_PER_BLOCK, ipb_default);
+    int64_t nchunks = ipb == 1 ? (nblocks_max >= ngroups ? nblocks_max / ngroups : 1)   // (never more items than blocks)
+                               : ((int64_t)ipb * nblocks_max + ngroups - 1) / ngroups;
     const int64_t max_by_n = (n_main + 8 * block_tile - 1) / (8 * block_tile);
     if (nchunks > max_by_n) nchunks = max_by_n;
     const int64_t min_chunks = (n_main + ((int64_t)1 << 30) - 1) >> 30;   // a chunk's rows are counted in 32 bits
@@ -2185,8 +2165,9 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         if (want > n / 32) want = n / 32;
         if (want > seed_codes_f32) seed_codes_f32 = want;
     }
-    const bool wide_seed = prune && few_groups && tables == 8 && seed_codes_f32 > SEED_SLICE;
-    const bool wide_seed_u4 = is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
+    const bool wide_ok = opt_int(ctx, PQ_OPT_SCAN_WIDE_SEED, 1) != 0;
+    const bool wide_seed = wide_ok && prune && few_groups && tables == 8 && seed_codes_f32 > SEED_SLICE;
+    const bool wide_seed_u4 = wide_ok && is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
     const size_t off_seedhist = prune ? off_qtabs + align_up((size_t)ngroups * 256 * tables * sizeof(uint4), 256) : off_tau0;
     // 16 queries per pass: the 16-bit tables of the second test (64 KB per group) and their scales
     const size_t off_qtabs16 = off_seedhist + align_up(wide_seed ? (size_t)nq * HIST_BINS * 4 : 0, 256);
@@ -2235,7 +2216,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * HIST_BINS);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
             f32_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
-            f32_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, tau0);
+            f32_seed_pick_kernel<<<nq, 64, 0, ctx->stream>>>(seed_hist, topk, tau0);
             PQ_HIP(ctx, hipGetLastError());
         }
         if (q8) prune_tables_kernel<8, 16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
@@ -2258,7 +2239,7 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * 4096);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
             u4_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
-            u4_seed_pick_kernel<<<nq, 256, 0, ctx->stream>>>(seed_hist, topk, a.tau_key);
+            u4_seed_pick_kernel<<<nq, 64, 0, ctx->stream>>>(seed_hist, topk, a.tau_key);
         } else {
             // 256 codes per result wanted, between PRUNE_INIT and 262 144 (top-1000: 4.11 -> 3.94 ms per step; twice as many
             // cost the seed kernel more than they save the scan)

@@ -227,3 +227,48 @@ def test_ivf_lists_beyond_4_gib_of_codes(ctx, m):
             check_float_topk_ranked(gd[q], gi[q], od[q], oi[q])
     del codes_d
     torch.cuda.empty_cache()
+
+
+def test_full_size_config4_sampled(ctx):
+    """Config 4 as bench.py runs it: 10^9 uniform random 8-byte codes in 65 536 Zipf-sized lists (made on the GPU by
+    the input generator), 10 000 queries in one call, nprobe 64, top-100.  Complete results of a sample of the queries
+    against the oracle, which scans the lists the GPU probed (their codes are copied back; rows of the full array
+    serve as ids); the probes themselves are checked for those queries as well."""
+    nt, nlist, nq, nprobe, topk = 1_000_000_000, 65536, 10000, 64, 100
+    mix = datagen.sift_like()
+    coarse = mix.sample(nlist, datagen.SEED_DATA + 7)
+    sizes = datagen.zipf_list_sizes(nt, nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    codes_d = datagen.random_codes_device(nt, 8, datagen.SEED_CODES + 3)
+    cb = datagen.sampled_codebooks(mix, 8, 256) * np.float32(0.25)
+    queries = mix.sample(nq, datagen.SEED_QUERIES + 1)
+    gd, gi, gp = ctx.ivf_adc_search(dev(coarse), dev(offsets), codes_d, None, dev(cb), binding.CODES_U8, dev(queries),
+                                    nprobe, topk, return_probes=True)
+    torch.cuda.synchronize()
+    gd, gi, gp = gd.cpu().numpy(), gi.cpu().numpy(), gp.cpu().numpy()
+    # the query that probes the longest list is part of the sample (its list is cut into the most chunks)
+    longest = int(np.argmax(sizes))
+    hits = np.flatnonzero((gp == longest).any(axis=1))
+    sample = sorted(set([0, 1, 777, 4096, 5000, 9998, 9999] + hits[:2].tolist()))
+    check_probes(queries[sample], coarse, gp[sample], nprobe)
+    lists = np.unique(gp[sample])
+    sub_sizes = sizes[lists].astype(np.int64)
+    sub_off = datagen.offsets_from_sizes(sub_sizes)
+    sub_codes = np.empty((int(sub_off[-1]), 8), np.uint8)
+    sub_ids = np.empty(int(sub_off[-1]), np.int64)
+    for j, l in enumerate(lists):
+        a, b = int(offsets[l]), int(offsets[l + 1])
+        sub_codes[sub_off[j]:sub_off[j + 1]] = codes_d[a:b].cpu().numpy()
+        sub_ids[sub_off[j]:sub_off[j + 1]] = np.arange(a, b)
+    remap = np.searchsorted(lists, gp[sample]).astype(np.int32)
+    od, oi = orc.ivf_scan(queries[sample], coarse[lists], sub_off, sub_codes, sub_ids, cb, orc.CODES_U8, remap, topk)
+    for r, q in enumerate(sample):
+        check_float_topk_ranked(gd[q], gi[q], od[r], oi[r])
+    # every query: ascending, rows valid and distinct, each result row inside one of the probed lists
+    assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < nt
+    for q in range(0, nq, 97):
+        assert len(set(gi[q].tolist())) == topk
+        owner = np.searchsorted(offsets, gi[q], side="right") - 1
+        assert np.isin(owner, gp[q]).all()
+    del codes_d
+    torch.cuda.empty_cache()

@@ -403,8 +403,8 @@ def main():
             "scan_kernel": inf_i["kernel"], "scan_kernel_ms": k_i, "queries_per_pass_over_a_list": inf_i["queries_per_pass"],
             "scan_kernel_code_bytes_GB/s": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9,
             "scan_kernel_frac_of_hbm_peak": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "note": "code bytes the scan kernel passes = pairs x 8 B / pairs per work item (an upper estimate of the sharing: items of a "
-                    "list with fewer probing queries are not full)"}
+            "note": "scan_kernel_ms covers both scan kernels (long lists, short lists); code bytes they pass = pairs x 8 B / pairs per work "
+                    "item (an upper estimate of the sharing: items of a list with fewer probing queries are not full)"}
         ivf = (coarse_h, offsets_h, codes_i, cb_r.cpu().numpy(), q_i_h, probes.cpu().numpy(), d_i.cpu().numpy(), i_i.cpu().numpy(), nprobe)
 
     # ---------------------------------------------------------------- oracle on the host cores

@@ -136,10 +136,10 @@ class Context:
         return ms.value
 
     def pq_last_scan_info(self):
-        name = ctypes.create_string_buffer(200)
+        name = ctypes.create_string_buffer(400)
         qpp, passes = ctypes.c_int(), ctypes.c_int()
         parked, inserted = ctypes.c_uint64(), ctypes.c_uint64()
-        self._check(self.lib.pq_last_scan_info(self.handle, name, 200, ctypes.byref(qpp), ctypes.byref(passes),
+        self._check(self.lib.pq_last_scan_info(self.handle, name, 400, ctypes.byref(qpp), ctypes.byref(passes),
                                                ctypes.byref(parked), ctypes.byref(inserted)))
         return {"kernel": name.value.decode(), "queries_per_pass": qpp.value, "passes": passes.value,
                 "parked_lanes": parked.value, "inserted_keys": inserted.value}

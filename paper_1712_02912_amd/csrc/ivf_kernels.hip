@@ -14,6 +14,8 @@
 //           list establishes prunes the other lists of the same query.
 // Everything is sized from upper bounds, so the call enqueues without reading back from the
 // device.
+#include <string.h>
+
 #include "pq_internal.h"
 #include "scan_common.h"
 #include "topk_device.h"
@@ -25,6 +27,7 @@ constexpr int64_t IVF_CHUNK_TARGET = 1 << 18; // rows per chunk aimed at for lon
 constexpr float IVF_PRUNE_RANGE = 3500.f;      // table units between the sum of a pair's minima and the query's first bound
 constexpr int IVF_QB_PLAIN = 4;               // queries per work item: plain float loop
 constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bounds
+constexpr int IVF_SHORT_MAX = 16384;          // lists of fewer codes are scanned by the kernel of short lists (8 tables, plain loop)
 
 // ------------------------------------------------------------------------------------------
 // nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.
@@ -199,15 +202,17 @@ __device__ __forceinline__ uint32_t block_scan_round(uint32_t v, uint32_t *wave_
 // Single block.  From the number of pairs per list: where each list's pairs start
 // (pair_off), how many chunks it is cut into (nc), where its items start in the item table
 // (item_off; lists of a larger size class come first) and the number of items.
+// Lists of fewer than short_max codes go to a table of their own (one item per group of short_qs pairs, the whole
+// list, for the kernel of short lists); item_off is then the position in that table and nitems_dev[1] its length.
 __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restrict__ np,
                                                         const int64_t *__restrict__ list_offsets, int nlist,
                                                         uint32_t *pair_off, uint32_t *nc_out, uint32_t *item_off,
-                                                        uint32_t *nitems_dev, uint32_t qb) {
+                                                        uint32_t *nitems_dev, uint32_t qb, int64_t short_max, uint32_t short_qs) {
     __shared__ uint32_t wave_tot[16];
-    __shared__ uint32_t cls_items[32], cls_base[32], cls_cursor[32];
+    __shared__ uint32_t cls_items[64], cls_base[64], cls_cursor[64];   // 32 size classes of the long lists, 32 of the short ones
     __shared__ uint32_t carry;
     const int tid = threadIdx.x;
-    if (tid < 32) { cls_items[tid] = 0; cls_cursor[tid] = 0; }
+    if (tid < 64) { cls_items[tid] = 0; cls_cursor[tid] = 0; }
     if (tid == 0) carry = 0;
     __syncthreads();
     for (int l0 = 0; l0 < nlist; l0 += 1024) {
@@ -219,8 +224,9 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
             const int64_t size = list_offsets[l + 1] - list_offsets[l];
             const int nc = v > 0 ? ivf_chunks_of(size) : 0;
             nc_out[l] = (uint32_t)nc;
-            const uint32_t items = ((v + qb - 1) / qb) * (uint32_t)nc;
-            if (items > 0) atomicAdd(&cls_items[63 - __builtin_clzll((unsigned long long)size)], items);
+            const bool is_short = size < short_max;
+            const uint32_t items = is_short ? (nc > 0 ? (v + short_qs - 1) / short_qs : 0u) : ((v + qb - 1) / qb) * (uint32_t)nc;
+            if (items > 0) atomicAdd(&cls_items[(is_short ? 32 : 0) + 63 - __builtin_clzll((unsigned long long)size)], items);
         }
     }
     __syncthreads();
@@ -228,15 +234,19 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
         pair_off[nlist] = carry;
         uint32_t run = 0;
         for (int c = 31; c >= 0; --c) { cls_base[c] = run; run += cls_items[c]; }
-        *nitems_dev = run;
+        nitems_dev[0] = run;
+        run = 0;
+        for (int c = 63; c >= 32; --c) { cls_base[c] = run; run += cls_items[c]; }
+        nitems_dev[1] = run;
     }
     __syncthreads();
     for (int l = tid; l < nlist; l += 1024) {
         const uint32_t v = np[l];
-        const uint32_t items = ((v + qb - 1) / qb) * nc_out[l];
+        const int64_t size = list_offsets[l + 1] - list_offsets[l];
+        const bool is_short = size < short_max;
+        const uint32_t items = is_short ? (nc_out[l] > 0 ? (v + short_qs - 1) / short_qs : 0u) : ((v + qb - 1) / qb) * nc_out[l];
         if (items > 0) {
-            const int64_t size = list_offsets[l + 1] - list_offsets[l];
-            const int c = 63 - __builtin_clzll((unsigned long long)size);
+            const int c = (is_short ? 32 : 0) + 63 - __builtin_clzll((unsigned long long)size);
             item_off[l] = cls_base[c] + atomicAdd(&cls_cursor[c], items);
         } else {
             item_off[l] = 0;
@@ -255,13 +265,29 @@ __global__ void ivf_fill_pairs_kernel(const int32_t *__restrict__ probes, int np
 // one thread per list: write the list's items (group-major, chunks of a group consecutive)
 __global__ void ivf_fill_items_kernel(const uint32_t *__restrict__ pair_off, const uint32_t *__restrict__ nc_arr,
                                       const uint32_t *__restrict__ item_off, const int64_t *__restrict__ list_offsets,
-                                      int nlist, int rows_per_16b, uint32_t qb, IvfItem *items) {
+                                      int nlist, int rows_per_16b, uint32_t qb, IvfItem *items, int64_t short_max,
+                                      const int32_t *__restrict__ pairs_by_list, IvfShortItem *short_items) {
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= nlist) return;
     const uint32_t npl = pair_off[l + 1] - pair_off[l];
     const int nc = (int)nc_arr[l];
     if (npl == 0 || nc == 0) return;
     const int64_t beg = list_offsets[l], end = list_offsets[l + 1];
+    if (end - beg < short_max) {   // a short list: the whole list for every group of IVF_SHORT_QS pairs
+        const int64_t aligned = beg / rows_per_16b * rows_per_16b;
+        const int ng = (int)((npl + IVF_SHORT_QS - 1) / IVF_SHORT_QS);
+        for (int g = 0; g < ng; ++g) {
+            const uint32_t nslots = npl - (uint32_t)g * IVF_SHORT_QS < (uint32_t)IVF_SHORT_QS ? npl - (uint32_t)g * IVF_SHORT_QS : (uint32_t)IVF_SHORT_QS;
+            IvfShortItem it;
+            it.code_begin = (uint32_t)aligned;
+            it.ncodes_skip_slots = (uint32_t)(end - aligned) | ((uint32_t)(beg - aligned) << 24) | (nslots << 28);
+            for (int s2 = 0; s2 < IVF_SHORT_QS; ++s2)
+                it.pair[s2] = (uint32_t)s2 < nslots ? pairs_by_list[pair_off[l] + (uint32_t)g * IVF_SHORT_QS + s2] : 0;
+            it.pad[0] = it.pad[1] = 0u;
+            short_items[item_off[l] + (uint32_t)g] = it;
+        }
+        return;
+    }
     int64_t rpc = (end - beg + nc - 1) / nc;
     rpc = (rpc + rows_per_16b - 1) / rows_per_16b * rows_per_16b;
     const int ng = (int)((npl + qb - 1) / qb);
@@ -480,9 +506,16 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_pairoff = take((size_t)(nlist + 1) * 4);
     const size_t o_nc = take((size_t)nlist * 4);
     const size_t o_itemoff = take((size_t)nlist * 4);
-    const size_t o_nitems = take(4);
+    const size_t o_nitems = take(8);   // (long lists' items, short lists' items)
     const size_t o_pairs = take(npairs_max * 4);
     const size_t o_items = take(max_items * sizeof(IvfItem));
+    // Short lists (8 tables, plain loop, blocks of 8 waves): a kernel of their own, see ivf_short_kernels.hip.
+    // Option ivf_short_max: lists of fewer codes than this take it (default IVF_SHORT_MAX, 0: none, at most 2^18).
+    int64_t short_max = m == 8 && !prune && opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16 ? opt_int(ctx, PQ_OPT_IVF_SHORT_MAX, IVF_SHORT_MAX) : 0;
+    if (short_max < 0) short_max = 0;
+    if (short_max > IVF_CHUNK_TARGET) short_max = IVF_CHUNK_TARGET;
+    const size_t max_short_items = short_max > 0 ? npairs_max / IVF_SHORT_QS + (size_t)nlist + 1 : 0;
+    const size_t o_sitems = take(max_short_items * sizeof(IvfShortItem));
     const size_t o_pairout = take(npairs_max * 4);
     const size_t o_qlists = take((size_t)qbatch * 4);
     const size_t o_qlistoff = take((size_t)(qbatch + 1) * 4);
@@ -508,6 +541,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     uint32_t *item_off = (uint32_t *)(ws + o_itemoff), *nitems_dev = (uint32_t *)(ws + o_nitems);
     int32_t *pairs_by_list = (int32_t *)(ws + o_pairs);
     IvfItem *items = (IvfItem *)(ws + o_items);
+    IvfShortItem *short_items = (IvfShortItem *)(ws + o_sitems);
     uint32_t *pair_out = (uint32_t *)(ws + o_pairout), *qlists = (uint32_t *)(ws + o_qlists);
     uint32_t *qlist_off = (uint32_t *)(ws + o_qlistoff);
     uint64_t *partial = (uint64_t *)(ws + o_partial);
@@ -535,10 +569,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         ivf_zero_kernel<<<256, 256, 0, s>>>(np, (size_t)nlist);
         ivf_zero_kernel<<<256, 256, 0, s>>>(fill, (size_t)nlist);
         ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, np);
-        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb);
+        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb, short_max, (uint32_t)IVF_SHORT_QS);
         ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, pair_off, fill, pairs_by_list);
         ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(pair_off, nc, item_off, L->list_offsets, nlist,
-                                                                  rows_per_16b, item_qb, items);
+                                                                  rows_per_16b, item_qb, items, short_max, pairs_by_list, short_items);
         ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
         ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, qlist_off);
         ivf_pair_abs_kernel<<<(unsigned)(((size_t)nqb * nprobe + 255) / 256), 256, 0, s>>>(qlist_off, (size_t)nqb * nprobe, nprobe, pair_out);
@@ -561,6 +595,16 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
                        : w16::launch_scan_items(ctx, kind, pmin, poff, pscale, L->codes, luts, nqb, nprobe, topk, items, nitems_dev,
                                                 pairs_by_list, pair_out, partial, ws + o_state, state_bytes, tau0, &tau_key);
         if (rc) return rc;
+        // the short lists after the long ones: by then a query's bound has seen the lists that hold most of its codes
+        if (short_max > 0) {
+            rc = launch_ivf_short_scan(ctx, L->codes, luts, short_items, nitems_dev + 1, pair_out, nprobe, topk, tau_key, partial);
+            if (rc) return rc;
+            if (ctx->profiling) {   // the measured "scan kernel" is both kernels
+                PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
+                const size_t len = strlen(ctx->last_scan_name);
+                snprintf(ctx->last_scan_name + len, sizeof(ctx->last_scan_name) - len, " (lists of %lld codes and more) + ivf_short_scan_kernel (shorter lists, 4 pairs per pass, blocks of 4 waves)", (long long)short_max);
+            }
+        }
         rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_key, kpad, nqb, topk, L->ids, false,
                                    out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
         if (rc) return rc;

@@ -32,6 +32,20 @@ struct IvfItem {
                                  // bits 8-15: number of pairs (slots), bits 16-31: chunk index in the list
 };
 
+// One work item of the scan of short inverted lists (ivf_short_kernels.hip): a whole list for up to
+// IVF_SHORT_QS of the (query, list) pairs that probe it.  32 bytes.
+constexpr int IVF_SHORT_QS = 4;
+struct __align__(16) IvfShortItem {
+    uint32_t code_begin;          // first row, rounded down to a 16-byte boundary
+    uint32_t ncodes_skip_slots;   // bits 0-23: rows from code_begin to the end of the list, 24-27: rows at the front that
+                                  // belong to the previous list, 28-31: pairs in use (0: no item)
+    int32_t pair[IVF_SHORT_QS];   // pair = query * nprobe + rank
+    uint32_t pad[2];
+};
+int launch_ivf_short_scan(pq_ctx *ctx, const uint8_t *codes, const float *luts, const IvfShortItem *items,
+                          const uint32_t *nitems_dev, const uint32_t *pair_out, int nprobe, int topk,
+                          unsigned long long *tau_key, uint64_t *partial);
+
 struct TunedArgs {
     const uint8_t *codes;
     int64_t n;

@@ -181,6 +181,7 @@ __global__ __launch_bounds__(1024) void merge_topk_kernel(const uint64_t *partia
 // (inverted-list search) or, with qlist_off == nullptr, list (c * ngroups + gq / qb) * qb + gq % qb
 // for every chunk c (flat scan).  ids (optional) maps rows to the ids to return.
 constexpr int MERGE_CAP = 8192;
+constexpr int MERGE_LDS = MERGE_CAP * 8 + MERGE_CAP * 4 + 1024 * 8;   // kept keys, 32-bit values for the selection, the result's keys
 template <bool VAL_U32>
 __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__restrict__ partial,
                                                               const uint32_t *__restrict__ qlist_off, int nchunks,
@@ -261,18 +262,56 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
         __syncthreads();
         kept = s_count < MERGE_CAP ? s_count : MERGE_CAP;
     }
-    int n2 = 64;
-    while (n2 < kept) n2 <<= 1;
-    for (int i = kept + tid; i < n2; i += blockDim.x) skeys[i] = KEY_EMPTY;
-    block_bitonic_sort(skeys, n2);
-    for (int i = tid; i < topk; i += blockDim.x) {
-        const uint64_t key = i < n2 ? skeys[i] : KEY_EMPTY;
+    auto emit = [&](int i, uint64_t key) {
         const bool empty = key == KEY_EMPTY;
         const uint32_t row = (uint32_t)key;
         if (VAL_U32) ((uint32_t *)out_val)[(size_t)gq * topk + i] = empty ? 0xffffffffu : (uint32_t)(key >> 32);
         else ((float *)out_val)[(size_t)gq * topk + i] = empty ? __builtin_inff() : ord_to_f32((uint32_t)(key >> 32));
         out_ids[(size_t)gq * topk + i] = empty ? -1 : (ids ? ids[row] : (int64_t)row);
+    };
+    // The topk smallest of the kept keys without sorting them all (a bitonic sort of a few thousand keys is dozens of
+    // barrier stages): radix selection of the topk-th value, then of the row among the keys that tie with it, gives the
+    // topk-th key; the keys up to it are moved to a short list, where every thread finds the rank of its keys by
+    // counting the smaller ones and writes them straight to their places.
+    uint32_t *vals = reinterpret_cast<uint32_t *>(skeys + MERGE_CAP);          // [MERGE_CAP]
+    uint64_t *shortlist = skeys + MERGE_CAP + MERGE_CAP / 2;                   // [1024]
+    __shared__ uint32_t sel_bins[256], sel_state[2];
+    __shared__ int s_below, s_ties;
+    int nshort = kept;
+    const uint64_t *src = skeys;
+    if (kept > topk) {
+        for (int i = tid; i < kept; i += blockDim.x) vals[i] = (uint32_t)(skeys[i] >> 32);
+        if (tid == 0) { s_below = 0; s_ties = 0; s_count = 0; }
+        __syncthreads();
+        const uint32_t vk = block_kth_smallest_u32(vals, kept, (uint32_t)topk, sel_bins, sel_state);
+        // rows of the keys that tie with the topk-th value (into vals, which has served its purpose), keys below it counted
+        __syncthreads();
+        int below = 0;
+        for (int i = tid; i < kept; i += blockDim.x) {
+            const uint32_t v = (uint32_t)(skeys[i] >> 32);
+            below += v < vk ? 1 : 0;
+        }
+        atomicAdd(&s_below, below);
+        __syncthreads();
+        for (int i = tid; i < kept; i += blockDim.x)
+            if ((uint32_t)(skeys[i] >> 32) == vk) vals[atomicAdd(&s_ties, 1)] = (uint32_t)skeys[i];
+        __syncthreads();
+        const uint32_t rk = block_kth_smallest_u32(vals, s_ties, (uint32_t)(topk - s_below), sel_bins, sel_state);
+        const uint64_t kth = ((uint64_t)vk << 32) | rk;
+        __syncthreads();
+        for (int i = tid; i < kept; i += blockDim.x)
+            if (skeys[i] <= kth) shortlist[atomicAdd(&s_count, 1)] = skeys[i];   // exactly topk keys (keys are distinct)
+        __syncthreads();
+        nshort = s_count;
+        src = shortlist;
     }
+    for (int i = tid; i < nshort; i += blockDim.x) {
+        const uint64_t mine = src[i];
+        int rank = 0;
+        for (int j = 0; j < nshort; ++j) rank += src[j] < mine ? 1 : 0;
+        if (rank < topk) emit(rank, mine);
+    }
+    for (int i = nshort + tid; i < topk; i += blockDim.x) emit(i, KEY_EMPTY);
 }
 
 int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *qlist_off, int nchunks, int ngroups, int qb,
@@ -281,13 +320,13 @@ int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *
     if (nq == 0) return PQ_OK;
     if (val_u32) {
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
-        merge_filtered_kernel<true><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_LDS));
+        merge_filtered_kernel<true><<<nq, 1024, MERGE_LDS, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
                                                                              tau_key, kpad, topk, ids, out_val, out_ids);
     } else {
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_CAP * 8));
-        merge_filtered_kernel<false><<<nq, 1024, MERGE_CAP * 8, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_LDS));
+        merge_filtered_kernel<false><<<nq, 1024, MERGE_LDS, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
                                                                               tau_key, kpad, topk, ids, out_val, out_ids);
     }
     PQ_HIP(ctx, hipGetLastError());

@@ -1481,7 +1481,7 @@ void scan_tuned_kernel(TunedArgs a) {
 __global__ void tuned_init_kernel(uint32_t *work_counter, unsigned long long *tau_key, uint32_t *ncand, uint32_t *mark,
                                   uint32_t *tau_ref, int ntau,
                                   uint32_t tau_value, uint32_t *hist, size_t nhist, const float *tau0, int nq,
-                                  float tau0_scale) {
+                                  float tau0_scale, uint32_t *also_zero = nullptr, size_t also_zero_n = 0) {
     const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     if (i0 == 0) {
@@ -1498,6 +1498,7 @@ __global__ void tuned_init_kernel(uint32_t *work_counter, unsigned long long *ta
         mark[i] = 0;
     }
     for (size_t i = i0; i < nhist; i += stride) hist[i] = 0;
+    for (size_t i = i0; i < also_zero_n; i += stride) also_zero[i] = 0;   // (the bins of a first-bound pass that follows)
 }
 
 // First bound of the integer scan: one block per SEED_QPB queries adds up the 8-bit table entries of the
@@ -1826,6 +1827,80 @@ __global__ __launch_bounds__(1024) void f32_seed_hist_kernel(const uint8_t *__re
         if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * HIST_BINS + i], hist[i]);
 }
 
+// The same sample without a pass before it: the bins hang below ref0 = the sum of the tables' greatest entries (no
+// distance exceeds it; 4096 bins of 0.2 % reach down to 1/4000 of it), which every block works out for itself from
+// the tables it stages anyway.  A block counts its first 4096 codes in full; the k-th smallest of those bounds the
+// k-th smallest of the whole sample, so of its other codes only the ones at or below that bin edge are counted.
+// Blocks of `slice` codes (many short blocks when few queries share the launch: the pass is a chain of load latencies,
+// not bandwidth).
+constexpr int SEED2_SLICE = 1 << 14;
+__global__ __launch_bounds__(1024) void f32_seed_hist2_kernel(const uint8_t *__restrict__ codes, int64_t cnt, int slice,
+                                                              const float *__restrict__ luts, int k, uint32_t *seed_hist,
+                                                              float *seed_ref) {
+    __shared__ float tab[8 * 256];
+    __shared__ __align__(16) uint32_t hist[HIST_BINS];
+    __shared__ float smax[8];
+    __shared__ int bin_s;
+    const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 2048; i += 1024) tab[i] = luts[(size_t)q * 2048 + i];
+    for (int i = tid; i < HIST_BINS; i += 1024) hist[i] = 0;
+    __syncthreads();
+    if (wave < 8) {
+        float v = fmaxf(fmaxf(tab[wave * 256 + lane], tab[wave * 256 + lane + 64]), fmaxf(tab[wave * 256 + lane + 128], tab[wave * 256 + lane + 192]));
+        for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+        if (lane == 0) smax[wave] = v;
+    }
+    __syncthreads();
+    float ref0 = smax[0];
+    for (int j = 1; j < 8; ++j) ref0 += smax[j];
+    if (blockIdx.x == 0 && tid == 0) seed_ref[q] = ref0;
+    const uint32_t ref = f32_to_ord(ref0);
+    const int64_t begin = (int64_t)blockIdx.x * slice;
+    const int64_t end = begin + slice < cnt ? begin + slice : cnt;
+    auto count_range = [&](int64_t from, int64_t to, uint32_t limit) {
+        for (int64_t i0 = from + tid; i0 < to; i0 += 4 * 1024) {
+            uint2 c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + u * 1024;
+                c[u] = i < to ? *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8) : make_uint2(0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (i0 + u * 1024 >= to) break;
+                float d = tab[c[u].x & 255u];
+                d += tab[256 + ((c[u].x >> 8) & 255u)];
+                d += tab[512 + ((c[u].x >> 16) & 255u)];
+                d += tab[768 + (c[u].x >> 24)];
+                d += tab[1024 + (c[u].y & 255u)];
+                d += tab[1280 + ((c[u].y >> 8) & 255u)];
+                d += tab[1536 + ((c[u].y >> 16) & 255u)];
+                d += tab[1792 + (c[u].y >> 24)];
+                const uint32_t ord = f32_to_ord(d);
+                if (ord <= limit) {
+                    const uint32_t below = (ref - ord) >> HIST_SHIFT;
+                    atomicAdd(&hist[HIST_BINS - 1 - (below < HIST_BINS ? below : HIST_BINS - 1)], 1u);
+                }
+            }
+        }
+    };
+    const int64_t head_end = begin + 4096 < end ? begin + 4096 : end;
+    count_range(begin, head_end, ref);
+    if (head_end < end) {
+        __syncthreads();
+        if (wave == 0) {
+            const int b = hist_threshold(hist, k);
+            if (lane == 0) bin_s = b;
+        }
+        __syncthreads();
+        const uint32_t limit = bin_s < HIST_BINS ? ref - ((uint32_t)(HIST_BINS - 1 - bin_s) << HIST_SHIFT) : ref;
+        count_range(head_end, end, limit);
+    }
+    __syncthreads();
+    for (int i = tid; i < HIST_BINS; i += 1024)
+        if (hist[i] != 0u) atomicAdd(&seed_hist[(size_t)q * HIST_BINS + i], hist[i]);
+}
+
 __global__ __launch_bounds__(64) void f32_seed_pick_kernel(const uint32_t *__restrict__ seed_hist, int k, float *tau0) {
     const int q = blockIdx.x;
     const int b = hist_threshold(seed_hist + (size_t)q * HIST_BINS, k);   // one wave
@@ -1846,10 +1921,15 @@ __global__ void zero_u32_kernel(uint32_t *p, size_t n) {
 // L[j][b] = min(32767 / M, floor((D[j][b] - min_j) * scale)) for the M = 8 or 16 tables.  Output in
 // the slot order of the scan kernel: qtabs[group][b][j] holds entry b of table j for the 8 queries
 // of the group.
+// With seed_hist given, the kernel first reads every query's first bound off the bins of the sampling pass
+// (f32_seed_hist2_kernel; bins below seed_ref) and stores it as tau0, as the query's shared bound and as the reference
+// of its scan histogram: one launch instead of three.
 template <int M, int G = 8>   // G: queries per group (8 with 16-bit entries, 16 with 8-bit entries)
-__global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
+__global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restrict__ luts, float *tau0,
                                                            int nq, uint4 *qtabs, float *off_out, float *scale_out, float range_q8,
-                                                           uint4 *qtabs16, float *scale16_out) {
+                                                           uint4 *qtabs16, float *scale16_out, const uint32_t *seed_hist = nullptr,
+                                                           const float *seed_ref = nullptr, int seed_k = 0,
+                                                           unsigned long long *tau_key_out = nullptr, uint32_t *tau_ref_out = nullptr) {
     constexpr bool Q8 = G == 16;
     constexpr float ENTRY_MAX = Q8 ? PRUNE_ENTRY_MAX_Q8 : (float)(32767 / M);   // M entries must add up to less than 2^15 (2^7)
     const float RANGE = Q8 ? range_q8 : PRUNE_RANGE;
@@ -1858,6 +1938,23 @@ __global__ __launch_bounds__(256) void prune_tables_kernel(const float *__restri
     __shared__ float sscale[G];
     __shared__ float sscale16[G];   // 8-bit entries: the scale of the 16-bit tables written beside them
     const int group = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (seed_hist != nullptr) {
+        for (int q = wave; q < G; q += 4) {
+            const int gq = group * G + q;
+            if (gq >= nq) continue;
+            const int b = hist_threshold(seed_hist + (size_t)gq * HIST_BINS, seed_k);
+            if (lane == 0) {
+                const uint32_t ref = f32_to_ord(seed_ref[gq]);
+                const uint32_t edge = b < HIST_BINS ? ref - ((uint32_t)(HIST_BINS - 1 - b) << HIST_SHIFT) : ref;
+                tau0[gq] = ord_to_f32(edge);   // (every block of the group stores the same value)
+                if (blockIdx.y == 0) {
+                    tau_key_out[gq] = ((unsigned long long)edge << 32) | 0xffffffffull;
+                    tau_ref_out[gq] = edge;
+                }
+            }
+        }
+        __syncthreads();
+    }
     for (int r = wave * (G * M / 4); r < (wave + 1) * (G * M / 4); ++r) {
         const int q = r / M, j = r % M, gq = group * G + q;
         float v = __builtin_inff();
@@ -2170,7 +2267,8 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
     const bool wide_seed_u4 = wide_ok && is_u4 && few_groups && n >= PRUNE_MIN_N && seed_codes_f32 > SEED_SLICE;
     const size_t off_seedhist = prune ? off_qtabs + align_up((size_t)ngroups * 256 * tables * sizeof(uint4), 256) : off_tau0;
     // 16 queries per pass: the 16-bit tables of the second test (64 KB per group) and their scales
-    const size_t off_qtabs16 = off_seedhist + align_up(wide_seed ? (size_t)nq * HIST_BINS * 4 : 0, 256);
+    const size_t off_seedref = off_seedhist + align_up(wide_seed ? (size_t)nq * HIST_BINS * 4 : 0, 256);   // (wide first bound: reference of the bins per query)
+    const size_t off_qtabs16 = off_seedref + align_up(wide_seed ? (size_t)ntau * 4 : 0, 256);
     const size_t off_pscale16 = off_qtabs16 + (q8 ? (size_t)ngroups * 4096 * sizeof(uint4) : 0);
     const size_t total = prune ? off_pscale16 + (q8 ? align_up((size_t)ntau * 4, 256) : 0)
                                : (wide_seed_u4 ? off_seedhist + (size_t)nq * 4096 * 4 : (seed_plain ? off_poff : off_tau0));
@@ -2195,9 +2293,24 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
         uint4 *qtabs = (uint4 *)(ws + off_qtabs);
         uint4 *qtabs16 = q8 ? (uint4 *)(ws + off_qtabs16) : nullptr;
         float *pscale16 = q8 ? (float *)(ws + off_pscale16) : nullptr;
-        {
+        if (wide_seed) {
+            // Few query groups over a large database: state cleared first, then one sampling pass whose bins every block
+            // bounds for itself, then bound, shared state and tables of every group in one launch (three launches before the
+            // scan; a pass over the first 4096 codes for the bins' reference, a launch to clear the bins, one to pick the
+            // bounds and one to seed the state came on top before: 10^8 codes x 1 query 0.32 -> 0.27 ms per call)
+            uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
+            float *seed_ref = (float *)(ws + off_seedref);
+            tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_key, a.ncand, a.refresh_mark, a.tau_ref, ntau,
+                                                             0xff800000u, a.hist, L.nhist, nullptr, nq, 1.f, seed_hist, (size_t)nq * HIST_BINS);
+            // (short slices while the launch stays under 2048 blocks, else the slices of the older pass)
+            const int slice = (seed_codes_f32 + SEED2_SLICE - 1) / SEED2_SLICE * nq <= 2048 ? SEED2_SLICE : SEED_SLICE;
+            const dim3 sgrid((unsigned)((seed_codes_f32 + slice - 1) / slice), (unsigned)nq);
+            f32_seed_hist2_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, slice, (const float *)luts, topk, seed_hist, seed_ref);
+            prune_tables_kernel<8><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr,
+                                                                             seed_hist, seed_ref, topk, a.tau_key, a.tau_ref);
+            PQ_HIP(ctx, hipGetLastError());
+        } else {
             // the first bound: smallest histogram edge with k distances among the first codes
-            // (a reference for the histogram bins is all the wide pass needs from this one)
             // (batched: 256 codes per result wanted, between 32 768 and 131 072: top-1000 4.60 -> 4.30 ms per step)
             int batch_codes = topk * 256 > SEED_CODES_BATCH ? topk * 256 : SEED_CODES_BATCH;
             if (batch_codes > 4 * SEED_CODES_BATCH) batch_codes = 4 * SEED_CODES_BATCH;
@@ -2206,37 +2319,31 @@ int launch_scan_tuned(pq_ctx *ctx, int kind, const uint8_t *codes, int64_t n, co
             const int by_queries = (1 << 26) / (nq > 0 ? nq : 1) < (1 << 18) ? (1 << 26) / (nq > 0 ? nq : 1) : (1 << 18);
             if (batch_codes < by_queries && (int64_t)by_queries <= n / 16) batch_codes = by_queries;   // (a small part of the database only)
             if ((int64_t)batch_codes > n) batch_codes = (int)n;
-            const int first_codes = wide_seed ? PRUNE_INIT : (few_groups ? SEED_CODES_STREAM : batch_codes);
+            const int first_codes = few_groups ? SEED_CODES_STREAM : batch_codes;
             if (tables == 8) f32_seed_refine_kernel<8><<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, nq, tau0);
             else f32_seed_refine_kernel<16><<<(nq + SEED_QPB - 1) / SEED_QPB, 1024, 0, ctx->stream>>>(codes, first_codes, (const float *)luts, topk, true, nq, tau0);
             PQ_HIP(ctx, hipGetLastError());
-        }
-        if (wide_seed) {
-            uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
-            zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * HIST_BINS);
-            const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
-            f32_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const float *)luts, tau0, seed_hist);
-            f32_seed_pick_kernel<<<nq, 64, 0, ctx->stream>>>(seed_hist, topk, tau0);
+            if (q8) prune_tables_kernel<8, 16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
+            else if (tables == 8) prune_tables_kernel<8><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
+            else prune_tables_kernel<16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
             PQ_HIP(ctx, hipGetLastError());
         }
-        if (q8) prune_tables_kernel<8, 16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, PRUNE_RANGE_Q8, qtabs16, pscale16);
-        else if (tables == 8) prune_tables_kernel<8><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
-        else prune_tables_kernel<16><<<dim3(ngroups, 8), 256, 0, ctx->stream>>>((const float *)luts, tau0, nq, qtabs, poff, pscale, 0.f, nullptr, nullptr);
-        PQ_HIP(ctx, hipGetLastError());
         a.qtabs = qtabs; a.prune_off = poff; a.prune_scale = pscale; a.qtabs16 = qtabs16; a.prune_scale16 = pscale16;
     } else if (seed_plain) {
         tau0 = (float *)(ws + off_tau0);
         rc = launch_qmax_prescan(ctx, codes, n, PQ_CODES_U8, (const float *)luts, nq, cb, 256, PRUNE_INIT, topk, tau0);
         if (rc) return rc;
     }
-    tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_key, a.ncand, a.refresh_mark, a.tau_ref, ntau,
-                                                     is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq,
-                                                     seed_plain ? 1.f + 4e-6f : 1.f);
-    PQ_HIP(ctx, hipGetLastError());
+    if (!wide_seed) {   // (the wide first bound has cleared and seeded the state already)
+        uint32_t *seed_hist_u4 = wide_seed_u4 ? (uint32_t *)(ws + off_seedhist) : nullptr;
+        tuned_init_kernel<<<1024, 256, 0, ctx->stream>>>(a.work_counter, a.tau_key, a.ncand, a.refresh_mark, a.tau_ref, ntau,
+                                                         is_u4 ? 0x7fffu : 0xff800000u, a.hist, L.nhist, tau0, nq,
+                                                         seed_plain ? 1.f + 4e-6f : 1.f, seed_hist_u4, wide_seed_u4 ? (size_t)nq * 4096 : 0);
+        PQ_HIP(ctx, hipGetLastError());
+    }
     if (is_u4 && n >= PRUNE_MIN_N) {
         if (wide_seed_u4) {
             uint32_t *seed_hist = (uint32_t *)(ws + off_seedhist);
-            zero_u32_kernel<<<64, 256, 0, ctx->stream>>>(seed_hist, (size_t)nq * 4096);
             const dim3 sgrid((unsigned)((seed_codes_f32 + SEED_SLICE - 1) / SEED_SLICE), (unsigned)nq);
             u4_seed_hist_kernel<<<sgrid, 1024, 0, ctx->stream>>>(codes, seed_codes_f32, (const uint8_t *)luts, seed_hist);
             u4_seed_pick_kernel<<<nq, 64, 0, ctx->stream>>>(seed_hist, topk, a.tau_key);

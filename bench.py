@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--derived-r2", type=int, default=10000)
     ap.add_argument("--lut-shapes", action="store_true", help="also time the Tables step alone at the shapes of configs 1, 3, 4")
     ap.add_argument("--streaming-n", type=int, nargs="+", default=[25_000_000, 100_000_000, 1_000_000_000])
+    ap.add_argument("--streaming-queries", type=int, nargs="+", default=None,
+                    help="numbers of queries of the streaming cases (default: 1 8 64 256 for 8x8, 1 8 for 16x4)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain copy kernel of this many MiB (counter calibration under rocprofv3)")
     args = ap.parse_args()
@@ -233,7 +235,7 @@ def main():
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
         for ns in args.streaming_n:
             codes_s = datagen.random_codes_device(ns, 8, datagen.SEED_CODES + 2)
-            for which, nqs in (("8x8", (1, 8, 64, 256)), ("16x4", (1, 8))):
+            for which, nqs in (("8x8", args.streaming_queries or (1, 8, 64, 256)), ("16x4", args.streaming_queries or (1, 8))):
                 if which == "16x4" and args.skip_16x4:
                     continue
                 for nq_s in nqs:

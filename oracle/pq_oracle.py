@@ -24,10 +24,14 @@ _lib = None
 
 
 def build(force=False):
-    """Compile pq_oracle.c with gcc (no fast-math, no contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile pq_oracle.c with gcc (no fast-math, no contraction).  PQ_ORACLE_SANITIZE=1 builds it with the address
+    and undefined-behaviour sanitizers (CPU only; the interpreter then has to be started with libasan preloaded)."""
+    sanitize = os.environ.get("PQ_ORACLE_SANITIZE", "") not in ("", "0")
+    if force or sanitize or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
                "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        if sanitize:
+            cmd[1:1] = ["-g", "-fsanitize=address,undefined", "-fno-omit-frame-pointer", "-fno-sanitize-recover=undefined"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -181,9 +181,444 @@ __global__ __launch_bounds__(256) void build_luts_mfma_kernel(const float *__res
             }
 }
 
+// The same contraction for launches with many tiles: 128 queries x 128 centroids per tile, each of
+// the 4 waves 64 x 64 outputs as 4 x 4 MFMA tiles, so that one operand read from LDS feeds four
+// matrix instructions instead of two and every operand byte fetched from memory feeds twice the
+// arithmetic.  On this chip the fp64 matrix instructions and the ordinary vector instructions of a
+// SIMD take turns (a lone wave issues one v_mfma_f64_16x16x4f64 every 64 cycles, and the rate of
+// two waves drops by what their other vector instructions take), so the kernel is laid out to
+// issue few of those:
+//  - PRE: a pass over the operands beforehand writes them as doubles (rows padded with zeros to
+//    a multiple of 16 dimensions, the centroids doubled) together with minus their squared
+//    norms; staging a chunk is then loads and LDS stores only, the sums start at
+//    -(||y||^2 + ||c||^2) instead of zero and end at minus the distance.  Without PRE (few dimensions per sub-vector, where that pass
+//    would cost more than it saves) chunks are converted and the norms added up while staging.
+//  - rows past the end of an operand are staged as whatever row 0 holds: they only reach outputs
+//    that are never written.
+//  - the test for nearly complete cancellation is made on the floats, four at a time, against one
+//    bound per tile that no exact bound exceeds (entries it marks needlessly still get the plain
+//    definition, which is never the less accurate of the two).
+// Operands lie in LDS as [row][dimension] doubles with a row stride of 18: the 16 rows and 2
+// dimensions that half a wave reads at once then fall into 64 different banks.  Two LDS buffers
+// alternate (one barrier per chunk of 16 dimensions, placed so that the matrix cores have work
+// queued while the waves of a block meet); the chunk after the one in LDS is on its way from
+// memory into registers meanwhile.
+// Two blocks per compute unit stay for the whole launch and take tiles in turn; the first chunk
+// of a block's next tile is requested while its current tile is still being multiplied, and the
+// results leave through LDS as whole rows of 64 floats per wave with stores that nothing waits for.
+// Tiles are numbered so that the 8 dies of the chip (which take consecutive block ids in turn and
+// have a cache each) work on separate bands of query tiles, and the tiles in flight on one die form
+// a patch of 8 query tiles x 8 centroid tiles whose operands stay in that cache.
+constexpr int MT2 = 128, MK2 = 16, LS2 = MK2 + 2, OS2 = 72;   // tile, chunk, operand row stride (doubles), output row stride (floats)
+constexpr int GROUP_Y2 = 8;                                    // query tiles per patch
+
+struct Tile128 {
+    int j, q0, c0;
+};
+
+__device__ __forceinline__ Tile128 tile128_of(int seq, int tiles_x, int tiles_y) {
+    const int per_j = tiles_x * tiles_y;
+    const int j = seq / per_j, rj = seq - j * per_j;
+    const int patch = rj / (GROUP_Y2 * tiles_x), rp = rj - patch * (GROUP_Y2 * tiles_x);
+    const int ty0 = patch * GROUP_Y2, gy = tiles_y - ty0 < GROUP_Y2 ? tiles_y - ty0 : GROUP_Y2;
+    return Tile128{j, (ty0 + rp % gy) * MT2, (rp / gy) * MT2};
+}
+
+struct Mfma128Args {
+    const float *queries, *codebooks;   // [nq][d], [m][k][ds]
+    const double *yd, *cd;              // PRE: [m][nq_pad][dsp], [m][k_pad][dsp]; for distances cd holds 2 c
+    const double *nyg, *ncg;            // PRE: minus the squared norms, [m][nq_pad], [m][k_pad]
+    const float *ymax, *cmax;           // PRE: the largest squared norm of each block of prep128_kernel, as floats (rounded up)
+    int nymax, ncmax;
+    float *out;                         // [nq][m][k]
+    int nq, d, m, k, ds, dsp;
+    int nq_pad, k_pad;                  // PRE: rows per sub-space of yd and cd (whole tiles, the padding is zeros)
+    int tiles_x, tiles_y, total;
+};
+
+// Operands as doubles with their squared norms, one row of `ds` floats (at src + row * stride, for
+// sub-space j at + j * jstride) per 16 lanes: dst[j * rows_pad + row][dsp] = scale * row, norms[j * rows_pad + row]
+// = norm_sign * ||row||^2; rows from `rows` up to rows_pad and dimensions from `ds` up to dsp are zeros.
+__global__ __launch_bounds__(256) void prep128_kernel(const float *__restrict__ src, size_t stride, size_t jstride, int rows,
+                                                      int rows_pad, int m, int ds, int dsp, double *__restrict__ dst,
+                                                      double *__restrict__ norms, float *__restrict__ block_max,
+                                                      double scale, double norm_sign) {
+    __shared__ float wmax_s[4];
+    typedef double double2_t __attribute__((ext_vector_type(2)));
+    const size_t g = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 4;   // row over all sub-spaces
+    const int l = threadIdx.x & 15;
+    const bool inside = g < (size_t)rows_pad * m;
+    const int j = inside ? (int)(g / rows_pad) : 0, row = inside ? (int)(g - (size_t)j * rows_pad) : 0;
+    const bool ok = inside && row < rows;
+    const float *r = src + (size_t)j * jstride + (size_t)(ok ? row : 0) * stride;
+    double norm = 0.0;
+    for (int t = l * 4; t < dsp; t += 64) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok && t < ds) v = *reinterpret_cast<const float4 *>(r + t);   // ds is a multiple of 4
+        const double a = v.x, b = v.y, c = v.z, e = v.w;
+        if (inside) {
+            double *o = dst + g * dsp + t;
+            *reinterpret_cast<double2_t *>(o) = (double2_t){scale * a, scale * b};
+            *reinterpret_cast<double2_t *>(o + 2) = (double2_t){scale * c, scale * e};
+        }
+        norm += a * a; norm += b * b; norm += c * c; norm += e * e;
+    }
+    for (int o = 8; o > 0; o >>= 1) norm += __shfl_xor(norm, o);
+    if (inside && l == 0) norms[g] = norm_sign * norm;
+    // the largest norm of the block's 16 rows, as a float that is not below it
+    float fm = (float)norm * 1.0000002f;
+    for (int o = 32; o >= 16; o >>= 1) fm = fmaxf(fm, __shfl_xor(fm, o));
+    if ((threadIdx.x & 63) == 0) wmax_s[threadIdx.x >> 6] = fm;
+    __syncthreads();
+    if (threadIdx.x == 0) block_max[blockIdx.x] = fmaxf(fmaxf(wmax_s[0], wmax_s[1]), fmaxf(wmax_s[2], wmax_s[3]));
+}
+
+template <bool DOT, bool PRE>
+__global__ __launch_bounds__(256, 2) void build_luts_mfma128_kernel(const Mfma128Args A) {
+    typedef double double4_t __attribute__((ext_vector_type(4)));
+    typedef double double2_t __attribute__((ext_vector_type(2)));
+    __shared__ __align__(16) double lds[2 * 2 * MT2 * LS2];   // [buffer][y | c][row][LS2]
+    __shared__ double ny[MT2], nc[MT2];
+    __shared__ float wave_max[8];
+    static_assert(4 * 64 * OS2 * sizeof(float) <= sizeof(double) * 2 * 2 * MT2 * LS2, "output staging fits the operand buffers");
+    const int nq = A.nq, d = A.d, m = A.m, k = A.k, ds = A.ds;
+    // die e of 8 takes the tiles [e * per_die, (e + 1) * per_die), its blocks in turn
+    const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
+    const int die = blockIdx.x & 7;
+    int local = blockIdx.x >> 3;   // tile of this block within the die's share
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    const int nchunks = PRE ? A.dsp / MK2 : (ds + MK2 - 1) / MK2;
+    auto has_tile = [&](int l) { return l < per_die && die * per_die + l < A.total; };
+    if (!has_tile(local)) return;
+
+    // What a thread fetches and stages.  PRE: 8 threads per row (2 doubles each, a whole 128-byte
+    // line per row and request), rows tid / 8 + 32 * pass, pass 0..3; the converted operands are
+    // padded with rows of zeros to whole tiles.  Otherwise 4 threads per row (4 floats each), rows
+    // tid / 4 + 64 * pass, pass 0..1, and row 0 stands in for rows past the end.
+    constexpr int NPASS = PRE ? 4 : 2, ROWS_PER_PASS = MT2 / NPASS;
+    const int srow = PRE ? tid >> 3 : tid >> 2, sk = PRE ? (tid & 7) * 2 : (tid & 3) * 4;
+    struct Rows {
+        const void *y[PRE ? 1 : 2], *c[PRE ? 1 : 2];
+    };
+    auto rows_of = [&](const Tile128 &t) {
+        Rows r;
+        if constexpr (PRE) {
+            r.y[0] = A.yd + ((size_t)t.j * A.nq_pad + t.q0 + srow) * A.dsp + sk;
+            r.c[0] = A.cd + ((size_t)t.j * A.k_pad + t.c0 + srow) * A.dsp + sk;
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int row = p * ROWS_PER_PASS + srow;
+                const int qr = t.q0 + row < nq ? t.q0 + row : 0, cr = t.c0 + row < k ? t.c0 + row : 0;
+                r.y[p] = A.queries + (size_t)t.j * ds + (size_t)qr * d + sk;
+                r.c[p] = A.codebooks + ((size_t)t.j * k + cr) * ds + sk;
+            }
+        }
+        return r;
+    };
+    // the chunk after the one being multiplied, [y | c][pass]: 4 floats, or 2 doubles with PRE
+    float4 rf[2][PRE ? 1 : 2];
+    double2_t rd[2][PRE ? 4 : 1];
+    // rows start on 16-byte boundaries and hold a multiple of 4 dimensions (the launcher sees to
+    // it), so a group of 4 dimensions lies inside a row or past its end as a whole
+    auto fetch = [&](const Rows &r, int k0) {
+        if constexpr (PRE) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                rd[0][p] = *reinterpret_cast<const double2_t *>((const double *)r.y[0] + (size_t)p * ROWS_PER_PASS * A.dsp + k0);
+                rd[1][p] = *reinterpret_cast<const double2_t *>((const double *)r.c[0] + (size_t)p * ROWS_PER_PASS * A.dsp + k0);
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                rf[0][p] = rf[1][p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k0 + sk < ds) {
+                    rf[0][p] = *reinterpret_cast<const float4 *>((const float *)r.y[p] + k0);
+                    rf[1][p] = *reinterpret_cast<const float4 *>((const float *)r.c[p] + k0);
+                }
+            }
+        }
+    };
+    double norm_y[2] = {0.0, 0.0}, norm_c[2] = {0.0, 0.0};   // without PRE: this thread's part of the squared norms of its rows
+    auto stage = [&](int buf) {
+        double *yd = lds + ((size_t)(buf * 2 + 0) * MT2 + srow) * LS2 + sk;
+        double *cd = lds + ((size_t)(buf * 2 + 1) * MT2 + srow) * LS2 + sk;
+        if constexpr (PRE) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                *reinterpret_cast<double2_t *>(yd + p * ROWS_PER_PASS * LS2) = rd[0][p];
+                *reinterpret_cast<double2_t *>(cd + p * ROWS_PER_PASS * LS2) = rd[1][p];
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const double y0 = rf[0][p].x, y1 = rf[0][p].y, y2 = rf[0][p].z, y3 = rf[0][p].w;
+                const double c0v = rf[1][p].x, c1v = rf[1][p].y, c2v = rf[1][p].z, c3v = rf[1][p].w;
+                *reinterpret_cast<double2_t *>(yd + p * ROWS_PER_PASS * LS2) = (double2_t){y0, y1};
+                *reinterpret_cast<double2_t *>(yd + p * ROWS_PER_PASS * LS2 + 2) = (double2_t){y2, y3};
+                *reinterpret_cast<double2_t *>(cd + p * ROWS_PER_PASS * LS2) = (double2_t){c0v, c1v};
+                *reinterpret_cast<double2_t *>(cd + p * ROWS_PER_PASS * LS2 + 2) = (double2_t){c2v, c3v};
+                if (!DOT) {
+                    norm_y[p] += y0 * y0; norm_y[p] += y1 * y1; norm_y[p] += y2 * y2; norm_y[p] += y3 * y3;
+                    norm_c[p] += c0v * c0v; norm_c[p] += c1v * c1v; norm_c[p] += c2v * c2v; norm_c[p] += c3v * c3v;
+                }
+            }
+        }
+    };
+    double4_t acc[4][4];
+    double a[4], b[4];   // operands of the step about to be multiplied
+    // the rows of both operands that this lane feeds to the matrix cores, dimensions ks + lane / 16
+    auto operands = [&](int buf, int ks, double (&ao)[4], double (&bo)[4]) {
+        const double *yt = lds + ((size_t)(buf * 2 + 0) * MT2 + wy * 64 + (lane & 15)) * LS2 + (lane >> 4) + ks;
+        const double *ct = lds + ((size_t)(buf * 2 + 1) * MT2 + wx * 64 + (lane & 15)) * LS2 + (lane >> 4) + ks;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            ao[t] = yt[t * 16 * LS2];
+            bo[t] = ct[t * 16 * LS2];
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                acc[ta][tb] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+    };
+    // Block barrier that orders LDS accesses only (requests to memory stay in flight across it).
+    auto lds_barrier = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // One chunk: the operands of each step are read while the step before it multiplies.  The
+    // barrier that ends the chunk stands before its last step (whose operands are in registers by
+    // then), and the first operands of the next chunk are read right behind it, so that the
+    // matrix cores have those 16 instructions to work on while the waves meet and the reads return.
+    auto compute = [&](int buf, bool has_next) {
+        double an[4], bn[4];
+#pragma unroll
+        for (int ks = 0; ks < MK2; ks += 4) {
+            if (ks + 4 < MK2) {
+                operands(buf, ks + 4, an, bn);
+            } else {
+                lds_barrier();
+                if (has_next) operands(buf ^ 1, 0, an, bn);
+            }
+            multiply();
+            __builtin_amdgcn_sched_barrier(0);   // no further ahead than that: the registers hold no more
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                a[t] = an[t];
+                b[t] = bn[t];
+            }
+        }
+    };
+
+    Tile128 cur = tile128_of(die * per_die + local, A.tiles_x, A.tiles_y);
+    Rows rows = rows_of(cur);
+    fetch(rows, 0);
+    // Entries below `bound` are looked at again.  PRE: one bound for the launch, 1e-9 x (the largest
+    // ||y||^2 + the largest ||c||^2), rounding included; otherwise one per tile, see below.
+    float bound = 0.f;
+    if (PRE && !DOT) {
+        float my = 0.f, mc = 0.f;
+        for (int i = tid; i < A.nymax; i += 256) my = fmaxf(my, A.ymax[i]);
+        for (int i = tid; i < A.ncmax; i += 256) mc = fmaxf(mc, A.cmax[i]);
+        for (int o = 32; o > 0; o >>= 1) {
+            my = fmaxf(my, __shfl_xor(my, o));
+            mc = fmaxf(mc, __shfl_xor(mc, o));
+        }
+        if (lane == 0) { wave_max[wave] = my; wave_max[4 + wave] = mc; }
+        __syncthreads();
+        bound = (fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3])) +
+                 fmaxf(fmaxf(wave_max[4], wave_max[5]), fmaxf(wave_max[6], wave_max[7]))) * 1.001e-9f;
+        __syncthreads();
+    }
+    for (;;) {
+        // the registers hold chunk 0 of the tile `cur`; `next` is what this block takes after it
+        const bool more = has_tile(local + blocks_per_die);
+        const Tile128 next = more ? tile128_of(die * per_die + local + blocks_per_die, A.tiles_x, A.tiles_y) : cur;
+        const Rows next_rows = rows_of(next);
+        if (!(PRE && !DOT)) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] = (double4_t){0.0, 0.0, 0.0, 0.0};
+        }
+        if (PRE && !DOT) {   // -||y_tid||^2 (tid < 128) or -||c_(tid - 128)||^2 of this tile, zero past the end
+            const int r = tid & (MT2 - 1);
+            if (tid < MT2) ny[r] = A.nyg[(size_t)cur.j * A.nq_pad + cur.q0 + r];
+            else nc[r] = A.ncg[(size_t)cur.j * A.k_pad + cur.c0 + r];
+        }
+        norm_y[0] = norm_y[1] = norm_c[0] = norm_c[1] = 0.0;
+        stage(0);
+        if (1 < nchunks) fetch(rows, MK2);
+        else if (more) fetch(next_rows, 0);
+        lds_barrier();
+        operands(0, 0, a, b);
+        if (PRE && !DOT) {
+            // the sums start at -(||y||^2 + ||c||^2) and the centroids come doubled: they end at minus the distance
+#pragma unroll
+            for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        acc[ta][tb][v] = ny[wy * 64 + ta * 16 + (lane >> 4) + 4 * v] + nc[wx * 64 + tb * 16 + (lane & 15)];
+        }
+        for (int c = 0; c < nchunks; ++c) {
+            if (c + 1 < nchunks) {
+                stage((c + 1) & 1);
+                if (c + 2 < nchunks) fetch(rows, (c + 2) * MK2);
+                else if (more) fetch(next_rows, 0);
+            }
+            compute(c & 1, c + 1 < nchunks);
+        }
+        if (!DOT && !PRE) {
+            // rows past the end hold the norms of row 0: finite, and a bound too large does no harm
+            float wmax = 0.f;
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                norm_y[p] += __shfl_xor(norm_y[p], 1); norm_y[p] += __shfl_xor(norm_y[p], 2);
+                norm_c[p] += __shfl_xor(norm_c[p], 1); norm_c[p] += __shfl_xor(norm_c[p], 2);
+                if ((tid & 3) == 0) { ny[p * ROWS_PER_PASS + srow] = norm_y[p]; nc[p * ROWS_PER_PASS + srow] = norm_c[p]; }
+                wmax = fmaxf(wmax, (float)(norm_y[p] > norm_c[p] ? norm_y[p] : norm_c[p]));
+            }
+            for (int o = 32; o > 0; o >>= 1) wmax = fmaxf(wmax, __shfl_xor(wmax, o));
+            if (lane == 0) wave_max[wave] = wmax;
+            __syncthreads();
+            // at least 1e-9 * (||y||^2 + ||c||^2) for every entry of the tile, rounding included
+            bound = 2.f * fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3])) * 1.001e-9f;
+        }
+        // lane l of an MFMA tile holds rows l / 16 + 4 * v (v = 0..3) of column l % 16.  Each wave turns
+        // its 64 x 64 results into floats in an LDS patch of its own and writes them out as rows of 64;
+        // within a wave LDS accesses take effect in program order.
+        float *patch_out = reinterpret_cast<float *>(lds) + wave * 64 * OS2;
+        const bool vec_out = (k & 3) == 0;
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int rl = ta * 16 + (lane >> 4) + 4 * v, cl = tb * 16 + (lane & 15);
+                    float res;
+                    if (DOT) res = (float)acc[ta][tb][v];
+                    else if (PRE) res = -(float)acc[ta][tb][v];
+                    else res = (float)((ny[wy * 64 + rl] + nc[wx * 64 + cl]) - 2.0 * acc[ta][tb][v]);
+                    patch_out[rl * OS2 + cl] = res;
+                }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll 4
+        for (int i = 0; i < 16; ++i) {
+            const int rl = i * 4 + (lane >> 4), cl = (lane & 15) * 4;
+            const int q = cur.q0 + wy * 64 + rl, ci = cur.c0 + wx * 64 + cl;
+            float4 o = *reinterpret_cast<const float4 *>(patch_out + rl * OS2 + cl);
+            if (q >= nq || ci >= k) continue;
+            if (!DOT && fminf(fminf(o.x, o.y), fminf(o.z, o.w)) < bound) {
+                // nearly complete cancellation: the plain definition, so that exact zeros stay exact
+                const float *yq = A.queries + (size_t)cur.j * ds + (size_t)q * d;
+                float e4[4] = {o.x, o.y, o.z, o.w};
+#pragma unroll 1
+                for (int e = 0; e < 4; ++e) {
+                    if (!(e4[e] < bound) || ci + e >= k) continue;
+                    const float *ce = A.codebooks + ((size_t)cur.j * k + ci + e) * ds;
+                    double dist = 0.0;
+                    for (int t = 0; t < ds; ++t) {
+                        const double df = (double)yq[t] - (double)ce[t];
+                        dist += df * df;
+                    }
+                    e4[e] = (float)dist;
+                }
+                o = make_float4(e4[0], e4[1], e4[2], e4[3]);
+            }
+            float *dst = A.out + ((size_t)q * m + cur.j) * k + ci;
+            if (vec_out && ci + 4 <= k) {
+                *reinterpret_cast<float4 *>(dst) = o;
+            } else {
+                dst[0] = o.x;
+                if (ci + 1 < k) dst[1] = o.y;
+                if (ci + 2 < k) dst[2] = o.z;
+                if (ci + 3 < k) dst[3] = o.w;
+            }
+        }
+        if (!more) break;
+        __syncthreads();   // every wave has left its patch: the operand buffers are free again
+        local += blocks_per_die;
+        cur = next;
+        rows = next_rows;
+    }
+}
+
+// Scratch memory of the 128 x 128 form (operands as doubles and their norms), kept by the context.
+static int lut_ws_reserve(pq_ctx *ctx, size_t bytes) {
+    if (bytes <= ctx->lut_ws_bytes) return PQ_OK;
+    PQ_HIP(ctx, hipStreamSynchronize(ctx->stream));   // kernels already enqueued may still use the old buffer
+    if (ctx->lut_ws) {
+        PQ_HIP(ctx, hipFree(ctx->lut_ws));
+        ctx->lut_ws = nullptr;
+        ctx->lut_ws_bytes = 0;
+    }
+    const size_t want = (bytes + bytes / 4 + ((size_t)1 << 20) - 1) >> 20 << 20;
+    void *p = nullptr;
+    const hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, PQ_ENOMEM, "allocation of %zu bytes for the operands of the Tables step failed: %s", want, hipGetErrorString(e));
+    }
+    ctx->lut_ws = p;
+    ctx->lut_ws_bytes = want;
+    return PQ_OK;
+}
+
+// Launch of the 128 x 128 form: two blocks per compute unit (a multiple of 8 blocks, one share per die).
+// Sub-vectors of 64 dimensions and more take the pass that converts the operands first, if every
+// operand row serves 8 tiles and more (the pass costs about as much as one of them) and the copies
+// stay below 2 GiB.
+template <bool DOT>
+static int launch_mfma128(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
+                          float *out, int tiles_x, int tiles_y) {
+    Mfma128Args A{};
+    A.queries = queries; A.codebooks = codebooks; A.out = out;
+    A.nq = nq; A.d = d; A.m = m; A.k = k; A.ds = d / m; A.dsp = (A.ds + MK2 - 1) / MK2 * MK2;
+    A.tiles_x = tiles_x; A.tiles_y = tiles_y; A.total = tiles_x * tiles_y * m;
+    const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
+    A.nq_pad = tiles_y * MT2; A.k_pad = tiles_x * MT2;
+    const size_t rows_y = (size_t)m * A.nq_pad, rows_c = (size_t)m * A.k_pad;
+    const size_t bytes = (rows_y + rows_c) * (A.dsp + 1) * sizeof(double) + (rows_y + rows_c) / 16 * sizeof(float) + 64;
+    if (A.ds >= 64 && tiles_x >= 8 && tiles_y >= 8 && bytes <= ((size_t)2 << 30)) {
+        const int rc = lut_ws_reserve(ctx, bytes);
+        if (rc) return rc;
+        double *yd = (double *)ctx->lut_ws, *cd = yd + rows_y * A.dsp, *nyg = cd + rows_c * A.dsp, *ncg = nyg + rows_y;
+        const unsigned by = (unsigned)((rows_y * 16 + 255) / 256), bc = (unsigned)((rows_c * 16 + 255) / 256);
+        float *ymax = (float *)(ncg + rows_c), *cmax = ymax + by;
+        prep128_kernel<<<by, 256, 0, ctx->stream>>>(queries, (size_t)d, (size_t)A.ds, nq, A.nq_pad, m, A.ds, A.dsp, yd, nyg, ymax, 1.0, DOT ? 1.0 : -1.0);
+        prep128_kernel<<<bc, 256, 0, ctx->stream>>>(codebooks, (size_t)A.ds, (size_t)k * A.ds, k, A.k_pad, m, A.ds, A.dsp, cd, ncg, cmax, DOT ? 1.0 : 2.0, DOT ? 1.0 : -1.0);
+        A.yd = yd; A.cd = cd; A.nyg = nyg; A.ncg = ncg; A.ymax = ymax; A.cmax = cmax; A.nymax = (int)by; A.ncmax = (int)bc;
+        build_luts_mfma128_kernel<DOT, true><<<grid, 256, 0, ctx->stream>>>(A);
+    } else {
+        build_luts_mfma128_kernel<DOT, false><<<grid, 256, 0, ctx->stream>>>(A);
+    }
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// Number of 128 x 128 tiles from which the large form is used: two blocks for every compute unit.
+// Rows of both operands and of the output must start on 16-byte boundaries (the output rows only
+// where their length allows 16-byte stores at all) and hold a multiple of 4 dimensions.
+static bool use_mfma128(pq_ctx *ctx, int64_t tiles, int d, int ds, const void *a, const void *b, const void *out) {
+    const uintptr_t bits = (uintptr_t)a | (uintptr_t)b | (uintptr_t)out;
+    return tiles >= 2 * (int64_t)ctx->num_cu && tiles < (1ll << 30) && (d & 3) == 0 && (ds & 3) == 0 && (bits & 15) == 0;
+}
+
 int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                       float *luts) {
     if (d / m >= 8 && opt_int(ctx, PQ_OPT_LUT_MFMA, 1) != 0) {
+        const int64_t tx = (k + MT2 - 1) / MT2, ty = (nq + MT2 - 1) / MT2;
+        if (use_mfma128(ctx, tx * ty * m, d, d / m, queries, codebooks, luts)) {
+            return launch_mfma128<false>(ctx, queries, codebooks, nq, d, m, k, luts, (int)tx, (int)ty);
+        }
         dim3 mgrid((k + MT - 1) / MT, (nq + MT - 1) / MT, m);
         if (mgrid.y > 65535 || mgrid.z > 65535) return fail(ctx, PQ_EUNSUPPORTED, "build_luts: m or nq/64 above 65535");
         build_luts_mfma_kernel<false, 16><<<mgrid, 256, 0, ctx->stream>>>(queries, codebooks, nq, d, m, k, luts);
@@ -203,6 +638,10 @@ int launch_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks,
 int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out) {
     const int64_t ytiles = (n + MT - 1) / MT;
     if (ytiles > 65535 * 64) return fail(ctx, PQ_EUNSUPPORTED, "rotate: more than 2^28 vectors per call");
+    const int64_t tx2 = (d + MT2 - 1) / MT2, ty2 = (n + MT2 - 1) / MT2;
+    if (d >= 8 && use_mfma128(ctx, tx2 * ty2, d, d, vectors, rot, out)) {
+        return launch_mfma128<true>(ctx, vectors, rot, (int)n, d, 1, d, out, (int)tx2, (int)ty2);
+    }
     // the y dimension of a grid is limited to 65535 blocks: long inputs go in slices of rows
     for (int64_t t0 = 0; t0 < ytiles; t0 += 65535) {
         const int64_t rows0 = t0 * MT;

@@ -150,6 +150,7 @@ int pq_destroy(pq_ctx *ctx) {
     if (!ctx) return PQ_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->lut_ws) (void)hipFree(ctx->lut_ws);
     if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
     if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     free(ctx);

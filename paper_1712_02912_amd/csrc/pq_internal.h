@@ -20,6 +20,8 @@ struct pq_ctx {
     void *ws;          // device workspace, grown on demand (or the fixed scratch of the call that allocates nothing)
     size_t ws_bytes;
     int ws_fixed;      // ws must not grow: a request beyond ws_bytes is an error
+    void *lut_ws;      // Tables step of many tiles: operands as doubles and their norms, grown on demand
+    size_t lut_ws_bytes;
     int opt[PQ_OPT_COUNT];
     int num_cu;
     int profiling;              // bracket the scan kernel with events

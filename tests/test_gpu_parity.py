@@ -53,6 +53,30 @@ def test_build_luts_exact_zero_distance(ctx):
     assert np.array_equal(got, orc.build_luts(queries, cb))  # small integers: exact in float
 
 
+# Launches of 512 and more tiles of 128 x 128 entries take a kernel of their own (other tile, other
+# block numbering, results written through LDS): ragged tiles on both sides, one and several chunks
+# of 16 dimensions, a last chunk of 4 and of 12 dimensions, and rows of a length that rules out
+# 16-byte stores.  Sub-vectors of 64 dimensions and more whose rows serve 8 tiles and more are converted to doubles
+# by a pass of their own first (cases 3 and 7, the latter with rows padded from 68 to 80 dimensions).
+@pytest.mark.parametrize("m,k,d,nq", [(32, 256, 256, 1100), (8, 300, 96, 4500), (1, 5000, 128, 1700), (4, 250, 80, 9000),
+                                       (16, 256, 960, 2100), (2, 1100, 56, 8000), (2, 1100, 136, 4000)])
+def test_build_luts_many_tiles(ctx, m, k, d, nq):
+    r = np.random.default_rng(m * 1000 + k + nq)
+    queries = (r.random((nq, d)) * 4 - 1).astype(np.float32)
+    cb = (r.random((m, k, d // m)) * 4 - 1).astype(np.float32)
+    # some queries lie exactly on centroids of their sub-spaces: these entries must be exact zeros
+    ds = d // m
+    hits = [(int(q), int(r.integers(0, m)), int(r.integers(0, k))) for q in r.integers(0, nq, 40)]
+    for q, j, c in hits:
+        queries[q, j * ds:(j + 1) * ds] = cb[j, c]
+    ref = orc.build_luts(queries, cb)
+    got = host(ctx.pq_build_luts(dev(queries), dev(cb)))
+    assert got.shape == ref.shape
+    np.testing.assert_allclose(got, ref, rtol=4e-6, atol=1e-30)
+    for q, j, c in hits:
+        assert got[q, j, c] == 0.0
+
+
 # ----------------------------------------------------------------------------- quantiser
 @pytest.mark.parametrize("m,k", [(16, 16), (8, 256), (3, 5)])
 def test_quantize_luts_bit_exact(ctx, m, k):
@@ -407,7 +431,8 @@ def test_build_luts_without_matrix_cores(ctx, opts):
 
 
 # ----------------------------------------------------------------------------- OPQ rotation
-@pytest.mark.parametrize("n,d", [(1000, 128), (77, 960), (4097, 20), (1, 8), (0, 16)])
+# the last two cases have 512 and more tiles of 128 x 128 outputs and take the kernel for large launches
+@pytest.mark.parametrize("n,d", [(1000, 128), (77, 960), (4097, 20), (1, 8), (0, 16), (70001, 128), (9000, 960)])
 def test_rotate_matches_oracle(ctx, n, d):
     r = np.random.default_rng(n + d)
     x = (r.random((n, d)) * 255).astype(np.float32)

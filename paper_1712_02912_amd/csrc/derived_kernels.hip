@@ -21,7 +21,6 @@
 // per 16-byte slot, the four tables stored four times in the rotated slot order of lds_walk.h,
 // so every read is conflict-free), four lookups and three packed adds per code, one packed
 // compare for 8 queries x 2 codes.
-#include <vector>
 
 #include "pq_internal.h"
 #include "scan_common.h"
@@ -749,6 +748,44 @@ __global__ __launch_bounds__(64) void derived_bucket_kernel(const uint32_t *g_hi
     }
 }
 
+// Offsets of the candidate lists (exclusive prefix sum of the nq counts, one block) and what the host
+// needs of them: summary[0] = total, summary[1] = the first query whose count exceeds `cap` (nq if
+// none), summary[2] = that query's count.
+__global__ __launch_bounds__(1024) void derived_offsets_kernel(const uint32_t *__restrict__ count, int nq, long long cap,
+                                                                unsigned long long *__restrict__ cand_off,
+                                                                unsigned long long *__restrict__ summary) {
+    __shared__ unsigned long long wsum[16];
+    __shared__ unsigned long long carry;
+    __shared__ int bad;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { carry = 0; bad = nq; }
+    __syncthreads();
+    for (int base = 0; base < nq; base += 1024) {
+        const int q = base + tid;
+        const unsigned long long c = q < nq ? count[q] : 0;
+        if (q < nq && cap >= 0 && (long long)c > cap) atomicMin(&bad, q);
+        unsigned long long incl = c;   // inclusive scan over the wave
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long other = __shfl_up(incl, o);
+            if (lane >= o) incl += other;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        unsigned long long before = carry;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        if (q < nq) cand_off[q] = before + incl - c;
+        __syncthreads();
+        if (tid == 1023) carry = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        cand_off[nq] = carry;
+        summary[0] = carry;
+        summary[1] = (unsigned long long)bad;
+        summary[2] = bad < nq ? count[bad] : 0;
+    }
+}
+
 // Step 1.2: greatest compact distance (float tables of the derived quantizers, low bits of the
 // indexes; entries added in double in table order, rounded once) among the first `init` codes.
 __global__ __launch_bounds__(256) void derived_qmax_kernel(const uint8_t *codes, int init, const float *dluts, float *qmax) {
@@ -912,7 +949,6 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
     const size_t o_count = take((size_t)nq * 4);
     const size_t o_candcnt = take((size_t)nq * 4);
     const size_t o_candoff = take((size_t)(nq + 1) * 8);
-    const size_t first_part = off;
 
     auto prepare = [&](uint8_t *ws) -> int {   // Steps 1.1 and 1.2
         float *dluts = (float *)(ws + o_dluts), *qmax = (float *)(ws + o_qmax);
@@ -925,66 +961,72 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
                                     (float *)(ws + o_scale));
     };
 
-    int rc = ws_reserve(ctx, first_part);
+    const size_t o_summary = take(256);
+    const size_t first_part_all = off;
+    int rc = ws_reserve(ctx, first_part_all);
     if (rc) return rc;
-    uint8_t *ws = (uint8_t *)ctx->ws;
-    rc = prepare(ws);
-    if (rc) return rc;
-
+    if (!ctx->host_pin) {   // a few words of pinned host memory, kept by the context
+        void *p = nullptr;
+        PQ_HIP(ctx, hipHostMalloc(&p, 256, hipHostMallocDefault));
+        ctx->host_pin = p;
+    }
     DqArgs a;
     a.codes = codes; a.n = n; a.nq = nq; a.r2 = r2;
-    bind_geometry(a, g_count);
-    a.qluts = ws + o_qluts;
-    a.work_counter = (uint32_t *)(ws + o_counter);
-    a.g_hist = (uint32_t *)(ws + o_hist);
-    a.g_bound = (uint32_t *)(ws + o_bound);
-    a.bucket = nullptr; a.cand_off = nullptr; a.cand_cnt = nullptr; a.cand = nullptr;
-
-    // Step 1.3, counting pass
-    derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, a.g_hist, (size_t)nq * DQ_BINS, a.g_bound, nullptr, nq);
-    PQ_HIP(ctx, hipGetLastError());
-    if (ctx->profiling) {
-        note_plain_scan(ctx, "derived_scan_kernel<count> (8 queries per pass)", 8, g_count.ngroups);
-        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
-    }
-    if (g_count.nblocks > 0) {
-        derived_scan_kernel<0><<<g_count.nblocks, DQ_THREADS, 0, s>>>(a);
-        PQ_HIP(ctx, hipGetLastError());
-    }
-    if (ctx->profiling) {
-        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
-        ctx->ev_valid = 1;
-    }
-    derived_bucket_kernel<<<nq, 64, 0, s>>>(a.g_hist, n, r2, (uint32_t *)(ws + o_bucket), (uint32_t *)(ws + o_count));
-    PQ_HIP(ctx, hipGetLastError());
-
-    // the sizes of the candidate lists decide the rest of the workspace: the host has to see them
-    std::vector<uint32_t> count((size_t)nq), bucket((size_t)nq);
-    PQ_HIP(ctx, hipMemcpyAsync(count.data(), ws + o_count, (size_t)nq * 4, hipMemcpyDeviceToHost, s));
-    PQ_HIP(ctx, hipMemcpyAsync(bucket.data(), ws + o_bucket, (size_t)nq * 4, hipMemcpyDeviceToHost, s));
-    PQ_HIP(ctx, hipStreamSynchronize(s));
-    std::vector<uint64_t> cand_off((size_t)nq + 1);
-    cand_off[0] = 0;
-    for (int q = 0; q < nq; ++q) {
-        cand_off[(size_t)q + 1] = cand_off[(size_t)q] + count[(size_t)q];
-        if (cand_ids_out && (int64_t)count[(size_t)q] > cand_cap)
-            return fail(ctx, PQ_ESHAPE, "derived_search: query %d has %u candidates, cand_cap is %lld", q, count[(size_t)q],
-                        (long long)cand_cap);
-    }
-    const uint64_t total = cand_off[(size_t)nq];
-    const size_t o_cand = take((size_t)total * 8);
-    const bool regrow = off > ctx->ws_bytes;
-    rc = ws_reserve(ctx, off);
-    if (rc) return rc;
-    ws = (uint8_t *)ctx->ws;
-    if (regrow) {   // a new workspace: the tables are computed again (same bits), the buckets copied back
-        rc = prepare(ws);
+    // Steps 1.1 to 1.3 (counting pass) in the workspace `ws`; leaves the buckets, the counts and the
+    // offsets of the candidate lists there and brings their total (and the first list beyond
+    // cand_cap, if any) to the host: three words through pinned memory.
+    auto count_pass = [&](uint8_t *ws, unsigned long long *total) -> int {
+        int rc = prepare(ws);
         if (rc) return rc;
-        PQ_HIP(ctx, hipMemcpyAsync(ws + o_bucket, bucket.data(), (size_t)nq * 4, hipMemcpyHostToDevice, s));
-        PQ_HIP(ctx, hipMemcpyAsync(ws + o_count, count.data(), (size_t)nq * 4, hipMemcpyHostToDevice, s));
+        bind_geometry(a, g_count);
+        a.qluts = ws + o_qluts;
+        a.work_counter = (uint32_t *)(ws + o_counter);
+        a.g_hist = (uint32_t *)(ws + o_hist);
+        a.g_bound = (uint32_t *)(ws + o_bound);
+        a.bucket = nullptr; a.cand_off = nullptr; a.cand_cnt = nullptr; a.cand = nullptr;
+        derived_init_kernel<<<256, 256, 0, s>>>(a.work_counter, a.g_hist, (size_t)nq * DQ_BINS, a.g_bound, nullptr, nq);
+        PQ_HIP(ctx, hipGetLastError());
+        if (ctx->profiling) {
+            note_plain_scan(ctx, "derived_scan_kernel<count> (8 queries per pass)", 8, g_count.ngroups);
+            PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
+        }
+        if (g_count.nblocks > 0) {
+            derived_scan_kernel<0><<<g_count.nblocks, DQ_THREADS, 0, s>>>(a);
+            PQ_HIP(ctx, hipGetLastError());
+        }
+        if (ctx->profiling) {
+            PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
+            ctx->ev_valid = 1;
+        }
+        derived_bucket_kernel<<<nq, 64, 0, s>>>(a.g_hist, n, r2, (uint32_t *)(ws + o_bucket), (uint32_t *)(ws + o_count));
+        PQ_HIP(ctx, hipGetLastError());
+        derived_offsets_kernel<<<1, 1024, 0, s>>>((const uint32_t *)(ws + o_count), nq, cand_ids_out ? (long long)cand_cap : -1,
+                                                  (unsigned long long *)(ws + o_candoff), (unsigned long long *)(ws + o_summary));
+        PQ_HIP(ctx, hipGetLastError());
+        unsigned long long *pin = (unsigned long long *)ctx->host_pin;
+        PQ_HIP(ctx, hipMemcpyAsync(pin, ws + o_summary, 24, hipMemcpyDeviceToHost, s));
+        PQ_HIP(ctx, hipStreamSynchronize(s));
+        if (pin[1] < (unsigned long long)nq)
+            return fail(ctx, PQ_ESHAPE, "derived_search: query %d has %u candidates, cand_cap is %lld", (int)pin[1], (unsigned)pin[2],
+                        (long long)cand_cap);
+        *total = pin[0];
+        return PQ_OK;
+    };
+    uint8_t *ws = (uint8_t *)ctx->ws;
+    unsigned long long total = 0;
+    rc = count_pass(ws, &total);
+    if (rc) return rc;
+    // the sizes of the candidate lists decide the rest of the workspace
+    const size_t o_cand = take((size_t)total * 8);
+    if (off > ctx->ws_bytes) {   // a new workspace: the counting pass is made again there (same bits)
+        rc = ws_reserve(ctx, off);
+        if (rc) return rc;
+        ws = (uint8_t *)ctx->ws;
+        unsigned long long again = 0;
+        rc = count_pass(ws, &again);
+        if (rc) return rc;
+        if (again != total) return fail(ctx, PQ_EHIP, "derived_search: the counting pass gave %llu candidates, then %llu", total, again);
     }
-    PQ_HIP(ctx, hipMemcpyAsync(ws + o_candoff, cand_off.data(), (size_t)(nq + 1) * 8, hipMemcpyHostToDevice, s));
-    PQ_HIP(ctx, hipStreamSynchronize(s));   // the host vectors go away with this call
 
     // Step 1.3, collecting pass
     a.qluts = ws + o_qluts;

@@ -151,6 +151,7 @@ int pq_destroy(pq_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->lut_ws) (void)hipFree(ctx->lut_ws);
+    if (ctx->host_pin) (void)hipHostFree(ctx->host_pin);
     if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
     if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     free(ctx);

@@ -22,6 +22,7 @@ struct pq_ctx {
     int ws_fixed;      // ws must not grow: a request beyond ws_bytes is an error
     void *lut_ws;      // Tables step of many tiles: operands as doubles and their norms, grown on demand
     size_t lut_ws_bytes;
+    void *host_pin;    // 256 bytes of pinned host memory for the few words a call reads back
     int opt[PQ_OPT_COUNT];
     int num_cu;
     int profiling;              // bracket the scan kernel with events

@@ -172,8 +172,9 @@ def test_derived_search_bench_configuration_sampled(ctx):
 
 
 # ------------------------------------------------------------ 640 queries and more: 16 queries per pass over the codes
+# (the last case has more queries than the 1024 that the offsets of the candidate lists are summed over at a time)
 @pytest.mark.parametrize("n,nq,r2,topk", [(30_003, 650, 300, 10), (8_193, 641, 2000, 50), (300, 640, 1000, 5),
-                                          (70_001, 777, 64, 128)])
+                                          (70_001, 777, 64, 128), (4_001, 2_301, 150, 5)])
 def test_derived_search_many_queries(ctx, n, nq, r2, topk):
     cb, cbar, codes, queries = make_problem(21 + n, n, 1024, 8, nq)
     run_case(ctx, cb, cbar, codes, queries, r2, topk)

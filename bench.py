@@ -312,7 +312,7 @@ def main():
     # ---------------------------------------------------------------- Tables step alone, on request
     if args.lut_shapes:
         shapes = {"config1": (1000, 128, 8, 256), "config3": (1000, 960, 16, 256), "config4_coarse": (10000, 128, 1, 65536),
-                  "config4_residual_tables_40k_pairs": (40000, 128, 8, 256)}
+                  "config4_residual_tables_640k_pairs": (640000, 128, 8, 256)}
         tables = {}
         gen = torch.Generator(device="cuda").manual_seed(datagen.SEED_DATA + 9)
         for name, (nq_t, d_t, m_t, k_t) in shapes.items():

@@ -180,9 +180,11 @@ __global__ __launch_bounds__(1024) void merge_topk_kernel(const uint64_t *partia
 // sort.  The lists of query gq are either lists qlist_off[gq] .. qlist_off[gq + 1] of `partial`
 // (inverted-list search) or, with qlist_off == nullptr, list (c * ngroups + gq / qb) * qb + gq % qb
 // for every chunk c (flat scan).  ids (optional) maps rows to the ids to return.
-constexpr int MERGE_CAP = 8192;
-constexpr int MERGE_LDS = MERGE_CAP * 8 + MERGE_CAP * 4 + 1024 * 8;   // kept keys, 32-bit values for the selection, the result's keys
-template <bool VAL_U32>
+// MERGE_CAP keys are kept in LDS (more than that at or below the bound: the bisection below).  Calls of few queries
+// give every query a block of 1024 threads and room for 8192 keys; calls of many queries take blocks of 256 threads
+// and 2048 keys, of which a compute unit holds several.
+constexpr int merge_lds_bytes(int cap) { return cap * 8 + cap * 4 + 1024 * 8; }   // kept keys, 32-bit values for the selection, the result's keys
+template <bool VAL_U32, int MERGE_CAP>
 __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__restrict__ partial,
                                                               const uint32_t *__restrict__ qlist_off, int nchunks,
                                                               int ngroups, int qb,
@@ -318,19 +320,15 @@ int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *
                           const unsigned long long *tau_key, int kpad, int nq, int topk, const int64_t *ids, bool val_u32,
                           void *out_val, int64_t *out_ids) {
     if (nq == 0) return PQ_OK;
-    if (val_u32) {
-        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_LDS));
-        merge_filtered_kernel<true><<<nq, 1024, MERGE_LDS, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
-                                                                             tau_key, kpad, topk, ids, out_val, out_ids);
-    } else {
-        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(merge_filtered_kernel<false>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, MERGE_LDS));
-        merge_filtered_kernel<false><<<nq, 1024, MERGE_LDS, ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb,
-                                                                              tau_key, kpad, topk, ids, out_val, out_ids);
-    }
-    PQ_HIP(ctx, hipGetLastError());
-    return PQ_OK;
+    auto launch = [&](auto kernel, int cap, int threads) -> int {
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, merge_lds_bytes(cap)));
+        kernel<<<nq, threads, merge_lds_bytes(cap), ctx->stream>>>(partial, qlist_off, nchunks, ngroups, qb, tau_key, kpad, topk, ids, out_val, out_ids);
+        PQ_HIP(ctx, hipGetLastError());
+        return PQ_OK;
+    };
+    const bool many = nq >= 4 * ctx->num_cu;
+    if (val_u32) return many ? launch(merge_filtered_kernel<true, 2048>, 2048, 256) : launch(merge_filtered_kernel<true, 8192>, 8192, 1024);
+    return many ? launch(merge_filtered_kernel<false, 2048>, 2048, 256) : launch(merge_filtered_kernel<false, 8192>, 8192, 1024);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(1024) void merge_topk_kernel(const uint64_t *partia
 // for every chunk c (flat scan).  ids (optional) maps rows to the ids to return.
 // MERGE_CAP keys are kept in LDS (more than that at or below the bound: the bisection below).  Calls of few queries
 // give every query a block of 1024 threads and room for 8192 keys; calls of many queries take blocks of 256 threads
-// and 2048 keys, of which a compute unit holds several.
+// and 2048 keys (512 threads and 4096 keys for topk above 512), of which a compute unit holds several.
 constexpr int merge_lds_bytes(int cap) { return cap * 8 + cap * 4 + 1024 * 8; }   // kept keys, 32-bit values for the selection, the result's keys
 template <bool VAL_U32, int MERGE_CAP>
 __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__restrict__ partial,
@@ -193,7 +193,6 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
                                                               int64_t *out_ids) {
     extern __shared__ uint64_t skeys[];
     __shared__ int s_count;
-    __shared__ unsigned long long s_kth;
     const int gq = blockIdx.x, tid = threadIdx.x;
     const size_t nlists = qlist_off ? (size_t)(qlist_off[gq + 1] - qlist_off[gq]) : (size_t)nchunks;
     // Every list is packed (its keys first, KEY_EMPTY behind them; kpad is a multiple of 64): a wave
@@ -241,23 +240,46 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
     __syncthreads();
     int kept = s_count;
     if (kept > MERGE_CAP) {
-        // too many keys at or below the bound (massive ties): bisection for the topk-th key
-        uint64_t v = 0;
-        for (int bit = 63; bit >= 0; --bit) {
-            const uint64_t trial = v | ((1ull << bit) - 1ull);
+        // too many keys at or below the bound (massive ties): the topk-th key by radix selection, one byte of the key per
+        // pass over the lists, most significant first
+        __shared__ uint32_t key_bins[256];
+        __shared__ unsigned long long sel_prefix;
+        __shared__ uint32_t sel_want;
+        if (tid == 0) { sel_prefix = 0ull; sel_want = (uint32_t)topk; }
+        for (int pass = 7; pass >= 0; --pass) {
+            if (tid < 256) key_bins[tid] = 0u;
             __syncthreads();
-            if (tid == 0) s_count = 0;
+            const int shift = 8 * pass;
+            const uint64_t fixed = pass == 7 ? 0ull : ~0ull << (shift + 8);   // bytes decided in earlier passes
+            const uint64_t prefix = sel_prefix;
+            const uint32_t want = sel_want;
+            for_each_key([&](uint64_t key) {
+                if (key != KEY_EMPTY && (key & fixed) == prefix) atomicAdd(&key_bins[(uint32_t)(key >> shift) & 255u], 1u);
+            });
             __syncthreads();
-            int c = 0;
-            for_each_key([&](uint64_t key) { c += key <= trial ? 1 : 0; });
-            atomicAdd(&s_count, c);
+            if (tid < 64) {   // one wave: the byte value whose bin holds the `want`-th key
+                const uint32_t h[4] = {key_bins[4 * tid], key_bins[4 * tid + 1], key_bins[4 * tid + 2], key_bins[4 * tid + 3]};
+                const uint32_t tot = h[0] + h[1] + h[2] + h[3];
+                uint32_t incl = tot;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t up = __shfl_up(incl, o);
+                    if (tid >= o) incl += up;
+                }
+                const uint64_t reach = __ballot(incl >= want);   // never empty: more than topk keys lie at or below the bound
+                if (reach != 0ull && tid == __builtin_ctzll(reach)) {
+                    uint32_t cum = incl - tot;
+                    int bsel = 4 * tid;
+                    for (int t = 0; t < 3 && cum + h[t] < want; ++t) { cum += h[t]; ++bsel; }
+                    sel_prefix = prefix | ((uint64_t)bsel << shift);
+                    sel_want = want - cum;
+                }
+            }
             __syncthreads();
-            if (s_count < topk) v |= (1ull << bit);
         }
+        if (tid == 0) s_count = 0;
         __syncthreads();
-        if (tid == 0) { s_kth = v; s_count = 0; }
-        __syncthreads();
-        const uint64_t kth = s_kth;
+        const uint64_t kth = sel_prefix;
         for_each_key([&](uint64_t key) {
             if (key != KEY_EMPTY && key <= kth) { const int pos = atomicAdd(&s_count, 1); if (pos < MERGE_CAP) skeys[pos] = key; }
         });
@@ -326,9 +348,18 @@ int launch_merge_filtered(pq_ctx *ctx, const uint64_t *partial, const uint32_t *
         PQ_HIP(ctx, hipGetLastError());
         return PQ_OK;
     };
-    const bool many = nq >= 4 * ctx->num_cu;
-    if (val_u32) return many ? launch(merge_filtered_kernel<true, 2048>, 2048, 256) : launch(merge_filtered_kernel<true, 8192>, 8192, 1024);
-    return many ? launch(merge_filtered_kernel<false, 2048>, 2048, 256) : launch(merge_filtered_kernel<false, 8192>, 8192, 1024);
+    // calls of many queries: several smaller blocks per compute unit (room for at least four times topk keys)
+    const bool many = nq >= 2 * ctx->num_cu;
+    if (many && topk <= 512) {
+        if (val_u32) return launch(merge_filtered_kernel<true, 2048>, 2048, 256);
+        return launch(merge_filtered_kernel<false, 2048>, 2048, 256);
+    }
+    if (many) {
+        if (val_u32) return launch(merge_filtered_kernel<true, 4096>, 4096, 512);
+        return launch(merge_filtered_kernel<false, 4096>, 4096, 512);
+    }
+    if (val_u32) return launch(merge_filtered_kernel<true, 8192>, 8192, 1024);
+    return launch(merge_filtered_kernel<false, 8192>, 8192, 1024);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -40,8 +40,9 @@ constexpr int IVF_SHORT_MAX = 16384;          // lists of fewer codes are scanne
 constexpr int SEL_CAP = 4096;
 __global__ __launch_bounds__(256) void ivf_select_probes_kernel(const float *__restrict__ dist, int nlist,
                                                                 int nprobe, int32_t *__restrict__ probes,
-                                                                int32_t *probe_out) {
+                                                                int32_t *probe_out, const int32_t *__restrict__ only_flagged) {
     __shared__ uint64_t cand[SEL_CAP];
+    if (only_flagged && only_flagged[blockIdx.x] == 0) return;   // (rows settled otherwise)
     __shared__ uint32_t part[256];
     __shared__ uint32_t sel_state[2];
     __shared__ int s_bin, s_count;
@@ -465,6 +466,102 @@ __global__ __launch_bounds__(256) void ivf_prune_prep_kernel(const float *__rest
 }
 
 // ------------------------------------------------------------------------------------------
+// Index step through approximate distances (fp32 matrix cores, every value within eps * (||y||^2 + ||c||^2) of the
+// exact one): the ncand > nprobe lists nearest by approximate distance are measured exactly (the plain definition in
+// double, rounded to float once), and if the nprobe-th of these exact distances lies below what any list outside the
+// candidates can have (the greatest approximate distance among the candidates minus the error bound), the nprobe
+// nearest of the candidates are the nprobe nearest of all lists, in (distance, list) order.  Queries for which this
+// cannot be shown are flagged; their rows of exact distances are computed and selected from as without the short cut.
+
+// Greatest squared norm of the rows of `v`, as the bits of a float not below it (squared norms are not negative, so
+// the bits order like the values).  *out_bits starts at 0.
+__global__ __launch_bounds__(256) void ivf_max_norm_kernel(const float *__restrict__ v, int rows, int d, unsigned int *out_bits) {
+    __shared__ float red[4];
+    const int row = blockIdx.x * 256 + threadIdx.x;
+    double n = 0.0;
+    if (row < rows)
+        for (int t = 0; t < d; ++t) { const double x = v[(size_t)row * d + t]; n += x * x; }
+    float f = (float)n * 1.0000002f;
+    for (int o = 32; o > 0; o >>= 1) f = fmaxf(f, __shfl_xor(f, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = f;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
+}
+
+constexpr int IVF_REFINE_MAX = 128;   // candidates per query (nprobe and a margin)
+__global__ __launch_bounds__(IVF_REFINE_MAX) void ivf_refine_probes_kernel(const float *__restrict__ queries, const float *__restrict__ cents,
+                                                                          const float *__restrict__ approx, const int32_t *__restrict__ cand,
+                                                                          int ncand, int nlist, int d, int nprobe, float eps,
+                                                                          const unsigned int *__restrict__ max_norm_bits,
+                                                                          int32_t *__restrict__ probes, int32_t *probe_out,
+                                                                          int32_t *__restrict__ flags) {
+    extern __shared__ float ys[];   // the query, d floats (d is a multiple of 4)
+    __shared__ uint64_t keys[IVF_REFINE_MAX];
+    __shared__ double red[2];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const float *y = queries + (size_t)q * d;
+    double ny = 0.0;
+    for (int t = tid; t < d; t += IVF_REFINE_MAX) { const float x = y[t]; ys[t] = x; ny += (double)x * (double)x; }
+    for (int o = 32; o > 0; o >>= 1) ny += __shfl_xor(ny, o);
+    if ((tid & 63) == 0) red[tid >> 6] = ny;
+    __syncthreads();
+    uint64_t key = ~0ull;
+    if (tid < ncand) {
+        const int l = cand[(size_t)q * ncand + tid];
+        const float4 *c4 = reinterpret_cast<const float4 *>(cents + (size_t)l * d);   // rows start on 16-byte boundaries
+        const float4 *y4 = reinterpret_cast<const float4 *>(ys);
+        double s = 0.0;   // dimension by dimension, as the definition has it
+        for (int t = 0; t < d / 4; t += 4) {   // four loads of 16 bytes on their way at a time
+            float4 c[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) c[u] = t + u < d / 4 ? c4[t + u] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (t + u >= d / 4) break;
+                const float4 yy = y4[t + u];
+                double df = (double)yy.x - (double)c[u].x; s += df * df;
+                df = (double)yy.y - (double)c[u].y; s += df * df;
+                df = (double)yy.z - (double)c[u].z; s += df * df;
+                df = (double)yy.w - (double)c[u].w; s += df * df;
+            }
+        }
+        key = ((uint64_t)f32_to_ord((float)s) << 32) | (uint32_t)l;
+    }
+    keys[tid] = key;
+    block_bitonic_sort(keys, IVF_REFINE_MAX);
+    __syncthreads();
+    if (tid == 0) {
+        ny = red[0] + red[1];
+        // no list outside the candidates is nearer than this (its approximate distance is at least that of the last candidate)
+        const double far = (double)approx[(size_t)q * nlist + cand[(size_t)q * ncand + ncand - 1]];
+        const double low = (far - (double)eps * (ny + (double)__uint_as_float(*max_norm_bits))) * (1.0 - 1.2e-7);
+        const double kth = (double)ord_to_f32((uint32_t)(keys[nprobe - 1] >> 32));
+        flags[q] = kth < low ? 0 : 1;   // (false for a NaN anywhere as well)
+    }
+    __syncthreads();
+    if (flags[q] == 0 && tid < nprobe) {
+        const int32_t l = (int32_t)(uint32_t)keys[tid];
+        probes[(size_t)q * nprobe + tid] = l;
+        if (probe_out) probe_out[(size_t)q * nprobe + tid] = l;
+    }
+}
+
+// Exact distances (the plain definition in double, rounded to float once) of the flagged queries to every list.
+__global__ __launch_bounds__(256) void ivf_exact_rows_kernel(const float *__restrict__ queries, const float *__restrict__ cents,
+                                                             int nlist, int d, const int32_t *__restrict__ flags,
+                                                             float *__restrict__ dist) {
+    const int q = blockIdx.x;
+    if (flags[q] == 0) return;
+    const float *y = queries + (size_t)q * d;
+    for (int l = threadIdx.x; l < nlist; l += 256) {
+        const float *c = cents + (size_t)l * d;
+        double s = 0.0;
+        for (int t = 0; t < d; ++t) { const double df = (double)y[t] - (double)c[t]; s += df * df; }
+        dist[(size_t)q * nlist + l] = (float)s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
     (void)cf;
@@ -499,6 +596,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; };
     const size_t o_dist = take((size_t)qbatch * nlist * 4);
     const size_t o_probes = take(npairs_max * 4);
+    const int ncand = nprobe + 16;   // lists measured exactly when the Index step goes through approximate distances
+    const size_t o_cand = take((size_t)qbatch * ncand * 4);
+    const size_t o_flags = take((size_t)qbatch * 4);
+    const size_t o_maxnorm = take(256);
     const size_t o_resid = take(npairs_max * d * 4);
     const size_t o_luts = take(npairs_max * m * k * 4);
     const size_t o_np = take((size_t)nlist * 4);
@@ -551,11 +652,29 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         const int npairs = nqb * nprobe;
         const float *qb = queries + (size_t)q0 * d;
         // Index step
-        rc = launch_build_luts(ctx, qb, L->coarse_centroids, nqb, d, 1, nlist, dist);
-        if (rc) return rc;
-        ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes,
-                                                     probe_out ? probe_out + (size_t)q0 * nprobe : nullptr);
-        PQ_HIP(ctx, hipGetLastError());
+        int32_t *pout = probe_out ? probe_out + (size_t)q0 * nprobe : nullptr;
+        if (opt_int(ctx, PQ_OPT_IVF_COARSE_F32, 1) != 0 && ncand <= IVF_REFINE_MAX && (int64_t)ncand * 8 <= nlist && d <= 8192 &&
+            coarse_f32_usable(ctx, qb, L->coarse_centroids, nqb, d, nlist, dist)) {
+            int32_t *cand = (int32_t *)(ws + o_cand), *flags = (int32_t *)(ws + o_flags);
+            unsigned int *maxnorm = (unsigned int *)(ws + o_maxnorm);
+            ivf_zero_kernel<<<1, 64, 0, s>>>(maxnorm, (size_t)1);
+            ivf_max_norm_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(L->coarse_centroids, nlist, d, maxnorm);
+            PQ_HIP(ctx, hipGetLastError());
+            rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, nqb, d, nlist, dist);
+            if (rc) return rc;
+            ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, ncand, cand, nullptr, nullptr);
+            ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, dist, cand, ncand, nlist, d, nprobe,
+                                                                    coarse_f32_error(d), maxnorm, probes, pout, flags);
+            // (queries that the short cut could not settle: normally none)
+            ivf_exact_rows_kernel<<<nqb, 256, 0, s>>>(qb, L->coarse_centroids, nlist, d, flags, dist);
+            ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes, pout, flags);
+            PQ_HIP(ctx, hipGetLastError());
+        } else {
+            rc = launch_build_luts(ctx, qb, L->coarse_centroids, nqb, d, 1, nlist, dist);
+            if (rc) return rc;
+            ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes, pout, nullptr);
+            PQ_HIP(ctx, hipGetLastError());
+        }
         // Tables step on the residuals
         {
             const size_t n = (size_t)npairs * d;

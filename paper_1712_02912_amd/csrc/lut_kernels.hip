@@ -604,6 +604,221 @@ static int launch_mfma128(pq_ctx *ctx, const float *queries, const float *codebo
     return PQ_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Approximate squared distances ||y_q - c_i||^2 of nq vectors to k centroids (one sub-space, all d
+// dimensions) on the fp32 matrix cores (v_mfma_f32_16x16x4f32, twice the rate of the fp64 ones), for
+// callers that only rank the centroids and settle the ranks that matter exactly afterwards (the
+// coarse step of the inverted-index search).  Same tiling and block numbering as the fp64 form
+// above: tiles of 128 x 128, each of the 4 waves 64 x 64 outputs as 4 x 4 matrix tiles, persistent
+// blocks, two LDS buffers of 16 dimensions, results written as rows through LDS.  Operands stay
+// floats ([row][dimension] with a row stride of 20 words: the 16 rows x 4 dimensions that a wave
+// reads at once fall into 64 different banks); norms and the final combination are fp32 as well.
+// Every result is within coarse_f32_error(d) * (||y||^2 + ||c||^2) of the exact value.
+constexpr int LS3 = MK2 + 4;   // operand row stride in floats
+constexpr int OS3 = 72;        // output row stride in floats (32 rows of 64 floats per wave at a time)
+
+struct CoarseF32Args {
+    const float *queries, *cents;   // [nq][d], [k][d]
+    float *out;                     // [nq][k]
+    int nq, d, k;
+    int tiles_x, tiles_y, total;
+};
+
+__global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args A) {
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    __shared__ __align__(16) float lds[2 * 2 * MT2 * LS3];   // [buffer][y | c][row][LS3]
+    __shared__ float ny[MT2], nc[MT2];
+    static_assert(4 * 32 * OS3 <= 2 * 2 * MT2 * LS3, "output staging fits the operand buffers");
+    const int nq = A.nq, d = A.d, k = A.k;
+    const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
+    const int die = blockIdx.x & 7;
+    int local = blockIdx.x >> 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    const int nchunks = (d + MK2 - 1) / MK2;
+    auto has_tile = [&](int l) { return l < per_die && die * per_die + l < A.total; };
+    if (!has_tile(local)) return;
+    // 4 threads per row (4 floats each), rows tid / 4 + 64 * pass; row 0 stands in for rows past the end
+    const int srow = tid >> 2, sk = (tid & 3) * 4;
+    struct Rows {
+        const float *y[2], *c[2];
+    };
+    auto rows_of = [&](const Tile128 &t) {
+        Rows r;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int row = p * 64 + srow;
+            r.y[p] = A.queries + (size_t)(t.q0 + row < nq ? t.q0 + row : 0) * d + sk;
+            r.c[p] = A.cents + (size_t)(t.c0 + row < k ? t.c0 + row : 0) * d + sk;
+        }
+        return r;
+    };
+    float4 rf[2][2];   // [y | c][pass]: the chunk after the one being multiplied
+    auto fetch = [&](const Rows &r, int k0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            rf[0][p] = rf[1][p] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 + sk < d) {   // d is a multiple of 4
+                rf[0][p] = *reinterpret_cast<const float4 *>(r.y[p] + k0);
+                rf[1][p] = *reinterpret_cast<const float4 *>(r.c[p] + k0);
+            }
+        }
+    };
+    float norm_y[2], norm_c[2];
+    auto stage = [&](int buf) {
+        float *yd = lds + ((size_t)(buf * 2 + 0) * MT2 + srow) * LS3 + sk;
+        float *cd = lds + ((size_t)(buf * 2 + 1) * MT2 + srow) * LS3 + sk;
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            *reinterpret_cast<float4 *>(yd + p * 64 * LS3) = rf[0][p];
+            *reinterpret_cast<float4 *>(cd + p * 64 * LS3) = rf[1][p];
+            norm_y[p] = fmaf(rf[0][p].x, rf[0][p].x, fmaf(rf[0][p].y, rf[0][p].y, fmaf(rf[0][p].z, rf[0][p].z, fmaf(rf[0][p].w, rf[0][p].w, norm_y[p]))));
+            norm_c[p] = fmaf(rf[1][p].x, rf[1][p].x, fmaf(rf[1][p].y, rf[1][p].y, fmaf(rf[1][p].z, rf[1][p].z, fmaf(rf[1][p].w, rf[1][p].w, norm_c[p]))));
+        }
+    };
+    floatx4 acc[4][4];
+    float a[4], b[4];
+    // lane l feeds row l % 16 of its matrix tiles, dimension ks + l / 16
+    auto operands = [&](int buf, int ks, float (&ao)[4], float (&bo)[4]) {
+        const float *yt = lds + ((size_t)(buf * 2 + 0) * MT2 + wy * 64 + (lane & 15)) * LS3 + (lane >> 4) + ks;
+        const float *ct = lds + ((size_t)(buf * 2 + 1) * MT2 + wx * 64 + (lane & 15)) * LS3 + (lane >> 4) + ks;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            ao[t] = yt[t * 16 * LS3];
+            bo[t] = ct[t * 16 * LS3];
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb)
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+    };
+    auto lds_barrier = [&]() {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // (the barrier that ends a chunk stands before its last step, see the fp64 form)
+    auto compute = [&](int buf, bool has_next) {
+        float an[4], bn[4];
+#pragma unroll
+        for (int ks = 0; ks < MK2; ks += 4) {
+            if (ks + 4 < MK2) {
+                operands(buf, ks + 4, an, bn);
+            } else {
+                lds_barrier();
+                if (has_next) operands(buf ^ 1, 0, an, bn);
+            }
+            multiply();
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                a[t] = an[t];
+                b[t] = bn[t];
+            }
+        }
+    };
+
+    Tile128 cur = tile128_of(die * per_die + local, A.tiles_x, A.tiles_y);
+    Rows rows = rows_of(cur);
+    fetch(rows, 0);
+    for (;;) {
+        const bool more = has_tile(local + blocks_per_die);
+        const Tile128 next = more ? tile128_of(die * per_die + local + blocks_per_die, A.tiles_x, A.tiles_y) : cur;
+        const Rows next_rows = rows_of(next);
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) acc[ta][tb] = (floatx4){0.f, 0.f, 0.f, 0.f};
+        norm_y[0] = norm_y[1] = norm_c[0] = norm_c[1] = 0.f;
+        stage(0);
+        if (1 < nchunks) fetch(rows, MK2);
+        else if (more) fetch(next_rows, 0);
+        lds_barrier();
+        operands(0, 0, a, b);
+        for (int c = 0; c < nchunks; ++c) {
+            if (c + 1 < nchunks) {
+                stage((c + 1) & 1);
+                if (c + 2 < nchunks) fetch(rows, (c + 2) * MK2);
+                else if (more) fetch(next_rows, 0);
+            }
+            compute(c & 1, c + 1 < nchunks);
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            norm_y[p] += __shfl_xor(norm_y[p], 1); norm_y[p] += __shfl_xor(norm_y[p], 2);
+            norm_c[p] += __shfl_xor(norm_c[p], 1); norm_c[p] += __shfl_xor(norm_c[p], 2);
+            if ((tid & 3) == 0) { ny[p * 64 + srow] = norm_y[p]; nc[p * 64 + srow] = norm_c[p]; }
+        }
+        __syncthreads();
+        // lane l of a matrix tile holds rows 4 * (l / 16) + v (v = 0..3) of column l % 16; 32 rows x 64
+        // columns of a wave at a time go through an LDS patch of its own and leave as rows
+        float *patch_out = lds + wave * 32 * OS3;
+        const bool vec_out = (k & 3) == 0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int ta = half * 2 + t2;
+                        const int rl = t2 * 16 + 4 * (lane >> 4) + v, cl = tb * 16 + (lane & 15);
+                        patch_out[rl * OS3 + cl] = fmaf(-2.f, acc[ta][tb][v], ny[wy * 64 + half * 32 + rl] + nc[wx * 64 + cl]);
+                    }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll 4
+            for (int i = 0; i < 8; ++i) {
+                const int rl = i * 4 + (lane >> 4), cl = (lane & 15) * 4;
+                const int q = cur.q0 + wy * 64 + half * 32 + rl, ci = cur.c0 + wx * 64 + cl;
+                const float4 o = *reinterpret_cast<const float4 *>(patch_out + rl * OS3 + cl);
+                if (q >= nq || ci >= k) continue;
+                float *dst = A.out + (size_t)q * k + ci;
+                if (vec_out && ci + 4 <= k) {
+                    *reinterpret_cast<float4 *>(dst) = o;
+                } else {
+                    dst[0] = o.x;
+                    if (ci + 1 < k) dst[1] = o.y;
+                    if (ci + 2 < k) dst[2] = o.z;
+                    if (ci + 3 < k) dst[3] = o.w;
+                }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the patch is read before its next rows are written
+        }
+        if (!more) break;
+        __syncthreads();   // every wave has left its patch: the operand buffers are free again
+        local += blocks_per_die;
+        cur = next;
+        rows = next_rows;
+    }
+}
+
+// Bound on |approximate - exact| / (||y||^2 + ||c||^2) for the kernel above: d products rounded once or
+// twice and added in fp32 in some order (twice d units of 2^-24 on 2 |<y, c>| <= ||y||^2 + ||c||^2), the two
+// norms added up the same way (d units each), the final three operations; doubled for good measure.
+float coarse_f32_error(int d) { return 4.f * (float)(d + 8) * 5.9604645e-8f; }
+
+// Whether launch_coarse_f32 serves the shape (else the caller takes the exact Tables step).
+bool coarse_f32_usable(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *out) {
+    const int64_t tiles = (int64_t)((k + MT2 - 1) / MT2) * ((nq + MT2 - 1) / MT2);
+    const uintptr_t bits = (uintptr_t)queries | (uintptr_t)cents | (uintptr_t)out;
+    return d >= 16 && (d & 3) == 0 && (bits & 15) == 0 && tiles >= 2 * (int64_t)ctx->num_cu && tiles < (1ll << 30);
+}
+
+int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, float *out) {
+    if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, out)) return fail(ctx, PQ_EINVAL, "coarse_f32: shape not served");
+    CoarseF32Args A{};
+    A.queries = queries; A.cents = cents; A.out = out; A.nq = nq; A.d = d; A.k = k;
+    A.tiles_x = (k + MT2 - 1) / MT2; A.tiles_y = (nq + MT2 - 1) / MT2; A.total = A.tiles_x * A.tiles_y;
+    const int grid = (3 * ctx->num_cu + 7) / 8 * 8;   // three blocks per compute unit
+    coarse_f32_kernel<<<grid, 256, 0, ctx->stream>>>(A);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
 // Number of 128 x 128 tiles from which the large form is used: two blocks for every compute unit.
 // Rows of both operands and of the output must start on 16-byte boundaries (the output rows only
 // where their length allows 16-byte stores at all) and hold a multiple of 4 dimensions.

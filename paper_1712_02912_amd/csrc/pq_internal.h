@@ -10,7 +10,7 @@
 // Tuning and test switches (pq_set_option).  PQ_OPT_UNSET = the kernel's own default.
 enum pq_option_id {
     PQ_OPT_SCAN_PRUNE = 0, PQ_OPT_SCAN_Q8, PQ_OPT_SCAN_FORCE_GENERAL, PQ_OPT_SCAN_BLOCKS, PQ_OPT_SCAN_ITEMS_PER_BLOCK,
-    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_COUNT
+    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_IVF_COARSE_F32, PQ_OPT_COUNT
 };
 constexpr int PQ_OPT_UNSET = -2147483647 - 1;
 
@@ -78,6 +78,11 @@ int launch_rerank(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const fl
 int launch_scan(pq_ctx *ctx, const uint8_t *codes, int64_t n, int cf, const void *luts, int lf, int nq, int m,
                 int k, int topk, void *out_val, int64_t *out_ids);
 int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n, int d, float *out);
+// Approximate squared distances of nq vectors to k centroids of d dimensions on the fp32 matrix cores, each within
+// coarse_f32_error(d) * (||y||^2 + ||c||^2) of the exact value; coarse_f32_usable says whether the shape is served.
+float coarse_f32_error(int d);
+bool coarse_f32_usable(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *out);
+int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, float *out);
 int launch_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k, int cf,
                   uint8_t *codes);
 int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const float *derived_codebooks,

@@ -1537,8 +1537,8 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
         }
         __syncthreads();
     };
-    auto code_sums = [&](int i) -> uint64_t {   // four sums of at most 16 * 255 < 4096
-        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8);
+    auto load_code = [&](int i) { return *reinterpret_cast<const uint2 *>(codes + (size_t)i * 8); };
+    auto code_sums = [&](const uint2 c) -> uint64_t {   // four sums of at most 16 * 255 < 4096
         uint64_t acc = 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -1551,24 +1551,31 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
     // codes only the sums up to it need counting.
     const int head = cnt < 4096 ? cnt : 4096;
     __syncthreads();
-    for (int i = tid; i < head; i += 1024) {
-        const uint64_t acc = code_sums(i);
+    // four codes of a thread on their way at a time (the loops are otherwise chains of load latencies)
+    auto for_codes = [&](int begin, int end, auto &&f) {
+        int i = begin + tid;
+        for (; i + 3 * 1024 < end; i += 4 * 1024) {
+            const uint2 c0 = load_code(i), c1 = load_code(i + 1024), c2 = load_code(i + 2048), c3 = load_code(i + 3072);
+            f(i, code_sums(c0)); f(i + 1024, code_sums(c1)); f(i + 2048, code_sums(c2)); f(i + 3072, code_sums(c3));
+        }
+        for (; i < end; i += 1024) f(i, code_sums(load_code(i)));
+    };
+    for_codes(0, head, [&](int, uint64_t acc) {
 #pragma unroll
         for (int qq = 0; qq < SEED_QPB; ++qq) atomicAdd(&hist[qq][(uint32_t)(acc >> (16 * qq)) & 0xffffu], 1u);
-    }
+    });
     if (cnt > head) {
         kth_sums();
         uint32_t cut[SEED_QPB];
 #pragma unroll
         for (int qq = 0; qq < SEED_QPB; ++qq) cut[qq] = cut_s[qq] > 4095u ? 4095u : cut_s[qq];
-        for (int i = head + tid; i < cnt; i += 1024) {
-            const uint64_t acc = code_sums(i);
+        for_codes(head, cnt, [&](int, uint64_t acc) {
 #pragma unroll
             for (int qq = 0; qq < SEED_QPB; ++qq) {
                 const uint32_t sum = (uint32_t)(acc >> (16 * qq)) & 0xffffu;
                 if (sum <= cut[qq]) atomicAdd(&hist[qq][sum], 1u);
             }
-        }
+        });
     }
     kth_sums();
     if (sub == 0 && q0 + myq < nq && cut_s[myq] < 4096u) tau_key[q0 + myq] = ((unsigned long long)cut_s[myq] << 32) | 0xffffffffull;
@@ -1604,12 +1611,11 @@ __global__ __launch_bounds__(1024) void u4_seed_kernel(const uint8_t *__restrict
         uint32_t cut[SEED_QPB];
 #pragma unroll
         for (int qq = 0; qq < SEED_QPB; ++qq) cut[qq] = need_s[qq] != 0u ? cut_s[qq] : 0xffffffffu;
-        for (int i = tid; i < cnt; i += 1024) {
-            const uint64_t acc = code_sums(i);
+        for_codes(0, cnt, [&](int i, uint64_t acc) {
 #pragma unroll
             for (int qq = 0; qq < SEED_QPB; ++qq)
                 if (((uint32_t)(acc >> (16 * qq)) & 0xffffu) == cut[qq]) atomicAdd(&tie_cnt[qq][i >> 10], 1u);
-        }
+        });
     }
     __syncthreads();
     if (sub == 0 && need_s[myq] != 0u) {

@@ -272,3 +272,48 @@ def test_full_size_config4_sampled(ctx):
         assert np.isin(owner, gp[q]).all()
     del codes_d
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------ Index step through approximate distances
+# Calls of 512 and more tiles of 128 queries x 128 lists rank the lists by fp32 matrix-core distances first and
+# measure nprobe + 16 of them exactly; the probed lists must be the oracle's all the same.
+def _many_lists_problem(seed, nlist, nq, d, m=8, per_list=3):
+    r = np.random.default_rng(seed)
+    coarse = (r.random((nlist, d)) * 200 - 100).astype(np.float32)
+    offsets = datagen.offsets_from_sizes(np.full(nlist, per_list))
+    codes = r.integers(0, 256, (nlist * per_list, m), dtype=np.uint8)
+    cb = (r.random((m, 256, d // m)) * 20).astype(np.float32)
+    queries = (r.random((nq, d)) * 200 - 100).astype(np.float32)
+    return coarse, offsets, codes, cb, queries
+
+
+def _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe):
+    _, _, p = ctx.ivf_adc_search(dev(coarse), dev(offsets), dev(codes), None, dev(cb), binding.CODES_U8, dev(queries), nprobe, 5,
+                                 return_probes=True)
+    torch.cuda.synchronize()
+    return p.cpu().numpy()
+
+
+@pytest.mark.parametrize("nlist,nq,d,nprobe", [(4096, 2100, 64, 16), (8192, 1100, 32, 64), (5000, 1700, 128, 3)])
+def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, nprobe):
+    coarse, offsets, codes, cb, queries = _many_lists_problem(nlist + nq, nlist, nq, d)
+    gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
+    ref, _ = orc.ivf_probe(queries, coarse, nprobe)
+    assert np.array_equal(gp, ref)
+    opts.set("ivf_coarse_f32", 0)   # the exact Tables step for the Index step gives the same lists
+    assert np.array_equal(_probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe), ref)
+
+
+def test_ivf_index_step_ties_beyond_the_exactly_measured_lists(ctx):
+    """100 copies of one centroid are the nearest lists of some queries: more equal distances than the nprobe + 16 lists
+    measured exactly, so those queries take the exact rows; ties go by list number, as in the oracle."""
+    nlist, nq, d, nprobe = 4096, 2100, 64, 16
+    coarse, offsets, codes, cb, queries = _many_lists_problem(77, nlist, nq, d)
+    r = np.random.default_rng(78)
+    copies = r.choice(nlist, 100, replace=False)
+    coarse[copies] = coarse[copies[0]]
+    queries[::7] = coarse[copies[0]] + (r.random((len(queries[::7]), d)) * 2 - 1).astype(np.float32)   # near the copies
+    gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
+    ref, _ = orc.ivf_probe(queries, coarse, nprobe)
+    assert np.array_equal(gp, ref)
+    assert np.array_equal(np.sort(ref[0]), np.sort(copies)[:nprobe])   # query 0 probes the copies with the smallest numbers

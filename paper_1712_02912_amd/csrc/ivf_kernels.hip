@@ -488,17 +488,50 @@ __global__ __launch_bounds__(256) void ivf_max_norm_kernel(const float *__restri
     if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
 }
 
+// Bound per query for the pass that keeps only near lists: the r-th smallest of the query's approximate distances to a
+// sample of the lists (sel[q][r - 1] is its column in the sample's matrix).
+__global__ void ivf_theta_kernel(const float *__restrict__ sample, int ks, const int32_t *__restrict__ sel, int r, int nq, float *theta) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < nq) theta[q] = sample[(size_t)q * ks + sel[(size_t)q * r + r - 1]];
+}
+
+// The ncand smallest of the keys that the filtering pass kept for a query (sorted), and the approximate distance of
+// the last of them; queries with fewer than ncand keys or more than `cap` are flagged instead.
+constexpr int IVF_PICK_CAP = 2048;
+__global__ __launch_bounds__(256) void ivf_pick_candidates_kernel(const unsigned long long *__restrict__ keys_in, const unsigned int *__restrict__ cnt_in,
+                                                                  int ncand, int32_t *__restrict__ cand, float *__restrict__ far,
+                                                                  int32_t *__restrict__ flags) {
+    __shared__ uint64_t keys[IVF_PICK_CAP];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const unsigned int cnt = cnt_in[q];
+    if (cnt < (unsigned int)ncand || cnt > (unsigned int)IVF_PICK_CAP) {
+        if (tid == 0) flags[q] = 1;
+        return;
+    }
+    int n2 = 128;
+    while (n2 < (int)cnt) n2 <<= 1;
+    for (int i = tid; i < n2; i += 256) keys[i] = i < (int)cnt ? keys_in[(size_t)q * IVF_PICK_CAP + i] : ~0ull;
+    block_bitonic_sort(keys, n2);
+    __syncthreads();
+    if (tid < ncand) cand[(size_t)q * ncand + tid] = (int32_t)(uint32_t)keys[tid];
+    if (tid == 0) {
+        far[q] = ord_to_f32((uint32_t)(keys[ncand - 1] >> 32));
+        flags[q] = 0;
+    }
+}
+
 constexpr int IVF_REFINE_MAX = 128;   // candidates per query (nprobe and a margin)
 __global__ __launch_bounds__(IVF_REFINE_MAX) void ivf_refine_probes_kernel(const float *__restrict__ queries, const float *__restrict__ cents,
                                                                           const float *__restrict__ approx, const int32_t *__restrict__ cand,
-                                                                          int ncand, int nlist, int d, int nprobe, float eps,
-                                                                          const unsigned int *__restrict__ max_norm_bits,
+                                                                          const float *__restrict__ far_in, int ncand, int nlist, int d,
+                                                                          int nprobe, float eps, const unsigned int *__restrict__ max_norm_bits,
                                                                           int32_t *__restrict__ probes, int32_t *probe_out,
                                                                           int32_t *__restrict__ flags) {
     extern __shared__ float ys[];   // the query, d floats (d is a multiple of 4)
     __shared__ uint64_t keys[IVF_REFINE_MAX];
     __shared__ double red[2];
     const int q = blockIdx.x, tid = threadIdx.x;
+    if (far_in && flags[q] != 0) return;   // (no candidates for this query: it takes the exact row)
     const float *y = queries + (size_t)q * d;
     double ny = 0.0;
     for (int t = tid; t < d; t += IVF_REFINE_MAX) { const float x = y[t]; ys[t] = x; ny += (double)x * (double)x; }
@@ -533,7 +566,7 @@ __global__ __launch_bounds__(IVF_REFINE_MAX) void ivf_refine_probes_kernel(const
     if (tid == 0) {
         ny = red[0] + red[1];
         // no list outside the candidates is nearer than this (its approximate distance is at least that of the last candidate)
-        const double far = (double)approx[(size_t)q * nlist + cand[(size_t)q * ncand + ncand - 1]];
+        const double far = far_in ? (double)far_in[q] : (double)approx[(size_t)q * nlist + cand[(size_t)q * ncand + ncand - 1]];
         const double low = (far - (double)eps * (ny + (double)__uint_as_float(*max_norm_bits))) * (1.0 - 1.2e-7);
         const double kth = (double)ord_to_f32((uint32_t)(keys[nprobe - 1] >> 32));
         flags[q] = kth < low ? 0 : 1;   // (false for a NaN anywhere as well)
@@ -600,6 +633,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_cand = take((size_t)qbatch * ncand * 4);
     const size_t o_flags = take((size_t)qbatch * 4);
     const size_t o_maxnorm = take(256);
+    const size_t o_theta = take((size_t)qbatch * 4);
+    const size_t o_far = take((size_t)qbatch * 4);
+    const size_t o_ccnt = take((size_t)qbatch * 4);
+    const size_t o_ckeys = take((size_t)qbatch * IVF_PICK_CAP * 8);
     const size_t o_resid = take(npairs_max * d * 4);
     const size_t o_luts = take(npairs_max * m * k * 4);
     const size_t o_np = take((size_t)nlist * 4);
@@ -660,11 +697,32 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
             ivf_zero_kernel<<<1, 64, 0, s>>>(maxnorm, (size_t)1);
             ivf_max_norm_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(L->coarse_centroids, nlist, d, maxnorm);
             PQ_HIP(ctx, hipGetLastError());
-            rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, nqb, d, nlist, dist);
-            if (rc) return rc;
-            ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, ncand, cand, nullptr, nullptr);
-            ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, dist, cand, ncand, nlist, d, nprobe,
-                                                                    coarse_f32_error(d), maxnorm, probes, pout, flags);
+            // With many lists the matrix of approximate distances is not written at all: a sample of the lists (every
+            // 16th) gives each query a bound below which some hundreds of lists are expected, and the pass over all
+            // lists keeps the entries at or below it (a query left with fewer than ncand of them takes the exact row).
+            const int ks = (nlist + 15) / 16, rank = 6 * ncand / 16 > 8 ? 6 * ncand / 16 : 8;
+            if (nlist >= 16384 && rank <= ncand && coarse_f32_usable(ctx, qb, L->coarse_centroids, nqb, d, ks, dist)) {
+                float *theta = (float *)(ws + o_theta), *far = (float *)(ws + o_far);
+                unsigned int *ccnt = (unsigned int *)(ws + o_ccnt);
+                unsigned long long *ckeys = (unsigned long long *)(ws + o_ckeys);
+                ivf_zero_kernel<<<64, 256, 0, s>>>(ccnt, (size_t)nqb);
+                rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, (size_t)16 * d, nqb, d, ks, dist);
+                if (rc) return rc;
+                ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, ks, rank, cand, nullptr, nullptr);
+                ivf_theta_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(dist, ks, cand, rank, nqb, theta);
+                PQ_HIP(ctx, hipGetLastError());
+                rc = launch_coarse_f32_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP);
+                if (rc) return rc;
+                ivf_pick_candidates_kernel<<<nqb, 256, 0, s>>>(ckeys, ccnt, ncand, cand, far, flags);
+                ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, nullptr, cand, far, ncand, nlist, d,
+                                                                                   nprobe, coarse_f32_error(d), maxnorm, probes, pout, flags);
+            } else {
+                rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, (size_t)d, nqb, d, nlist, dist);
+                if (rc) return rc;
+                ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, ncand, cand, nullptr, nullptr);
+                ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, dist, cand, nullptr, ncand, nlist, d,
+                                                                                   nprobe, coarse_f32_error(d), maxnorm, probes, pout, flags);
+            }
             // (queries that the short cut could not settle: normally none)
             ivf_exact_rows_kernel<<<nqb, 256, 0, s>>>(qb, L->coarse_centroids, nlist, d, flags, dist);
             ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes, pout, flags);

@@ -606,28 +606,38 @@ static int launch_mfma128(pq_ctx *ctx, const float *queries, const float *codebo
 
 // ------------------------------------------------------------------------------------------
 // Approximate squared distances ||y_q - c_i||^2 of nq vectors to k centroids (one sub-space, all d
-// dimensions) on the fp32 matrix cores (v_mfma_f32_16x16x4f32, twice the rate of the fp64 ones), for
+// dimensions) on the fp32 matrix cores (v_mfma_f32_32x32x2f32: 64 cycles for 4096 flops, twice the rate of the
+// fp64 ones; the 16x16x4 form measured 48 cycles for 2048 flops), for
 // callers that only rank the centroids and settle the ranks that matter exactly afterwards (the
 // coarse step of the inverted-index search).  Same tiling and block numbering as the fp64 form
-// above: tiles of 128 x 128, each of the 4 waves 64 x 64 outputs as 4 x 4 matrix tiles, persistent
-// blocks, two LDS buffers of 16 dimensions, results written as rows through LDS.  Operands stay
-// floats ([row][dimension] with a row stride of 20 words: the 16 rows x 4 dimensions that a wave
+// above: tiles of 128 x 128, each of the 4 waves 64 x 64 outputs as 2 x 2 matrix tiles of 32 x 32, persistent
+// blocks, two LDS buffers (of 32 dimensions here), results written as rows through LDS.  Operands stay
+// floats ([row][dimension] with a row stride of 34 words: the 32 rows x 2 dimensions that a wave
 // reads at once fall into 64 different banks); norms and the final combination are fp32 as well.
 // Every result is within coarse_f32_error(d) * (||y||^2 + ||c||^2) of the exact value.
-constexpr int LS3 = MK2 + 4;   // operand row stride in floats
+constexpr int MK3 = 32;        // dimensions per chunk (one barrier per chunk: 64 matrix instructions of 32 cycles are too few to hide it)
+constexpr int LS3 = MK3 + 2;   // operand row stride in floats
 constexpr int OS3 = 72;        // output row stride in floats (32 rows of 64 floats per wave at a time)
 
+// FILTER: instead of the matrix, the entries at or below the row's bound theta[q] leave as keys (ordered value, column)
+// appended to the row's list cand_keys[q][cap]; cand_cnt[q] counts them all, also those that found no room.
 struct CoarseF32Args {
-    const float *queries, *cents;   // [nq][d], [k][d]
+    const float *queries, *cents;   // [nq][d], centroid i at cents + i * cent_stride
+    size_t cent_stride;
     float *out;                     // [nq][k]
     int nq, d, k;
     int tiles_x, tiles_y, total;
+    const float *theta;             // FILTER: [nq]
+    unsigned long long *cand_keys;  // FILTER: [nq][cap]
+    unsigned int *cand_cnt;         // FILTER: [nq], zero at the start
+    int cap;
 };
 
-__global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args A) {
-    typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <bool FILTER>
+__global__ __launch_bounds__(256, 2) void coarse_f32_kernel(const CoarseF32Args A) {
+    typedef float floatx16 __attribute__((ext_vector_type(16)));
     __shared__ __align__(16) float lds[2 * 2 * MT2 * LS3];   // [buffer][y | c][row][LS3]
-    __shared__ float ny[MT2], nc[MT2];
+    __shared__ float ny[MT2], nc[MT2], th[MT2];
     static_assert(4 * 32 * OS3 <= 2 * 2 * MT2 * LS3, "output staging fits the operand buffers");
     const int nq = A.nq, d = A.d, k = A.k;
     const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
@@ -635,28 +645,28 @@ __global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args 
     int local = blockIdx.x >> 3;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave >> 1, wx = wave & 1;
-    const int nchunks = (d + MK2 - 1) / MK2;
+    const int nchunks = (d + MK3 - 1) / MK3;
     auto has_tile = [&](int l) { return l < per_die && die * per_die + l < A.total; };
     if (!has_tile(local)) return;
-    // 4 threads per row (4 floats each), rows tid / 4 + 64 * pass; row 0 stands in for rows past the end
-    const int srow = tid >> 2, sk = (tid & 3) * 4;
+    // 8 threads per row (4 floats each), rows tid / 8 + 32 * pass; row 0 stands in for rows past the end
+    const int srow = tid >> 3, sk = (tid & 7) * 4;
     struct Rows {
-        const float *y[2], *c[2];
+        const float *y[4], *c[4];
     };
     auto rows_of = [&](const Tile128 &t) {
         Rows r;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int row = p * 64 + srow;
+        for (int p = 0; p < 4; ++p) {
+            const int row = p * 32 + srow;
             r.y[p] = A.queries + (size_t)(t.q0 + row < nq ? t.q0 + row : 0) * d + sk;
-            r.c[p] = A.cents + (size_t)(t.c0 + row < k ? t.c0 + row : 0) * d + sk;
+            r.c[p] = A.cents + (size_t)(t.c0 + row < k ? t.c0 + row : 0) * A.cent_stride + sk;
         }
         return r;
     };
-    float4 rf[2][2];   // [y | c][pass]: the chunk after the one being multiplied
+    float4 rf[2][4];   // [y | c][pass]: the chunk after the one being multiplied
     auto fetch = [&](const Rows &r, int k0) {
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
+        for (int p = 0; p < 4; ++p) {
             rf[0][p] = rf[1][p] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (k0 + sk < d) {   // d is a multiple of 4
                 rf[0][p] = *reinterpret_cast<const float4 *>(r.y[p] + k0);
@@ -664,36 +674,39 @@ __global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args 
             }
         }
     };
-    float norm_y[2], norm_c[2];
+    float norm_y[4], norm_c[4];
     auto stage = [&](int buf) {
         float *yd = lds + ((size_t)(buf * 2 + 0) * MT2 + srow) * LS3 + sk;
         float *cd = lds + ((size_t)(buf * 2 + 1) * MT2 + srow) * LS3 + sk;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            *reinterpret_cast<float4 *>(yd + p * 64 * LS3) = rf[0][p];
-            *reinterpret_cast<float4 *>(cd + p * 64 * LS3) = rf[1][p];
+        for (int p = 0; p < 4; ++p) {
+            // (rows of 34 words start on 8-byte boundaries)
+            *reinterpret_cast<float2 *>(yd + p * 32 * LS3) = make_float2(rf[0][p].x, rf[0][p].y);
+            *reinterpret_cast<float2 *>(yd + p * 32 * LS3 + 2) = make_float2(rf[0][p].z, rf[0][p].w);
+            *reinterpret_cast<float2 *>(cd + p * 32 * LS3) = make_float2(rf[1][p].x, rf[1][p].y);
+            *reinterpret_cast<float2 *>(cd + p * 32 * LS3 + 2) = make_float2(rf[1][p].z, rf[1][p].w);
             norm_y[p] = fmaf(rf[0][p].x, rf[0][p].x, fmaf(rf[0][p].y, rf[0][p].y, fmaf(rf[0][p].z, rf[0][p].z, fmaf(rf[0][p].w, rf[0][p].w, norm_y[p]))));
             norm_c[p] = fmaf(rf[1][p].x, rf[1][p].x, fmaf(rf[1][p].y, rf[1][p].y, fmaf(rf[1][p].z, rf[1][p].z, fmaf(rf[1][p].w, rf[1][p].w, norm_c[p]))));
         }
     };
-    floatx4 acc[4][4];
-    float a[4], b[4];
-    // lane l feeds row l % 16 of its matrix tiles, dimension ks + l / 16
-    auto operands = [&](int buf, int ks, float (&ao)[4], float (&bo)[4]) {
-        const float *yt = lds + ((size_t)(buf * 2 + 0) * MT2 + wy * 64 + (lane & 15)) * LS3 + (lane >> 4) + ks;
-        const float *ct = lds + ((size_t)(buf * 2 + 1) * MT2 + wx * 64 + (lane & 15)) * LS3 + (lane >> 4) + ks;
+    floatx16 acc[2][2];
+    float a[2], b[2];
+    // lane l feeds row l % 32 of its matrix tiles, dimension ks + l / 32
+    auto operands = [&](int buf, int ks, float (&ao)[2], float (&bo)[2]) {
+        const float *yt = lds + ((size_t)(buf * 2 + 0) * MT2 + wy * 64 + (lane & 31)) * LS3 + (lane >> 5) + ks;
+        const float *ct = lds + ((size_t)(buf * 2 + 1) * MT2 + wx * 64 + (lane & 31)) * LS3 + (lane >> 5) + ks;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            ao[t] = yt[t * 16 * LS3];
-            bo[t] = ct[t * 16 * LS3];
+        for (int t = 0; t < 2; ++t) {
+            ao[t] = yt[t * 32 * LS3];
+            bo[t] = ct[t * 32 * LS3];
         }
     };
     auto multiply = [&]() {
 #pragma unroll
-        for (int ta = 0; ta < 4; ++ta)
+        for (int ta = 0; ta < 2; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb)
-                acc[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
+            for (int tb = 0; tb < 2; ++tb)
+                acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ta], b[tb], acc[ta][tb], 0, 0, 0);
     };
     auto lds_barrier = [&]() {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -702,11 +715,11 @@ __global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args 
     };
     // (the barrier that ends a chunk stands before its last step, see the fp64 form)
     auto compute = [&](int buf, bool has_next) {
-        float an[4], bn[4];
+        float an[2], bn[2];
 #pragma unroll
-        for (int ks = 0; ks < MK2; ks += 4) {
-            if (ks + 4 < MK2) {
-                operands(buf, ks + 4, an, bn);
+        for (int ks = 0; ks < MK3; ks += 2) {
+            if (ks + 2 < MK3) {
+                operands(buf, ks + 2, an, bn);
             } else {
                 lds_barrier();
                 if (has_next) operands(buf ^ 1, 0, an, bn);
@@ -714,7 +727,7 @@ __global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args 
             multiply();
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < 2; ++t) {
                 a[t] = an[t];
                 b[t] = bn[t];
             }
@@ -729,46 +742,101 @@ __global__ __launch_bounds__(256, 3) void coarse_f32_kernel(const CoarseF32Args 
         const Tile128 next = more ? tile128_of(die * per_die + local + blocks_per_die, A.tiles_x, A.tiles_y) : cur;
         const Rows next_rows = rows_of(next);
 #pragma unroll
-        for (int ta = 0; ta < 4; ++ta)
+        for (int ta = 0; ta < 2; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < 4; ++tb) acc[ta][tb] = (floatx4){0.f, 0.f, 0.f, 0.f};
-        norm_y[0] = norm_y[1] = norm_c[0] = norm_c[1] = 0.f;
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ta][tb][v] = 0.f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) norm_y[p] = norm_c[p] = 0.f;
+        if (FILTER && tid < MT2) th[tid] = cur.q0 + tid < nq ? A.theta[cur.q0 + tid] : -__builtin_inff();
         stage(0);
-        if (1 < nchunks) fetch(rows, MK2);
+        if (1 < nchunks) fetch(rows, MK3);
         else if (more) fetch(next_rows, 0);
         lds_barrier();
         operands(0, 0, a, b);
         for (int c = 0; c < nchunks; ++c) {
             if (c + 1 < nchunks) {
                 stage((c + 1) & 1);
-                if (c + 2 < nchunks) fetch(rows, (c + 2) * MK2);
+                if (c + 2 < nchunks) fetch(rows, (c + 2) * MK3);
                 else if (more) fetch(next_rows, 0);
             }
             compute(c & 1, c + 1 < nchunks);
         }
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            norm_y[p] += __shfl_xor(norm_y[p], 1); norm_y[p] += __shfl_xor(norm_y[p], 2);
-            norm_c[p] += __shfl_xor(norm_c[p], 1); norm_c[p] += __shfl_xor(norm_c[p], 2);
-            if ((tid & 3) == 0) { ny[p * 64 + srow] = norm_y[p]; nc[p * 64 + srow] = norm_c[p]; }
+        for (int p = 0; p < 4; ++p) {
+#pragma unroll
+            for (int o = 1; o < 8; o <<= 1) {
+                norm_y[p] += __shfl_xor(norm_y[p], o);
+                norm_c[p] += __shfl_xor(norm_c[p], o);
+            }
+            if ((tid & 7) == 0) { ny[p * 32 + srow] = norm_y[p]; nc[p * 32 + srow] = norm_c[p]; }
         }
         __syncthreads();
-        // lane l of a matrix tile holds rows 4 * (l / 16) + v (v = 0..3) of column l % 16; 32 rows x 64
-        // columns of a wave at a time go through an LDS patch of its own and leave as rows
+        // lane l of a matrix tile holds rows 8 * (v / 4) + 4 * (l / 32) + v % 4 (v = 0..15) of column l % 32
+        if (FILTER) {
+            // Entries at or below their row's bound are rare: every wave collects its own in LDS first (position from
+            // a count that the wave keeps in a register: no atomic operation, no waiting inside the unrolled code) and
+            // appends them to the queries' lists afterwards, all of them at once.
+            constexpr int WSTASH = 512;
+            unsigned long long *wkeys = reinterpret_cast<unsigned long long *>(lds) + wave * WSTASH;                 // in the operand buffers
+            unsigned int *wrow = reinterpret_cast<unsigned int *>(lds) + 2 * 4 * WSTASH + wave * WSTASH;
+            static_assert(4 * WSTASH * 12 <= (int)sizeof(float) * 2 * 2 * MT2 * LS3, "the collected entries fit the operand buffers");
+            unsigned int wcount = 0;   // the same in every lane
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = wy * 64 + ta * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    const float bound = th[r], nyr = ny[r];   // (rows past the end have a bound of -inf)
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb) {
+                        const int c = wx * 64 + tb * 32 + (lane & 31);
+                        const float val = fmaf(-2.f, acc[ta][tb][v], nyr + nc[c]);
+                        const bool pass = val <= bound && cur.c0 + c < k;
+                        const unsigned long long m = __ballot(pass);
+                        if (m != 0ull) {
+                            if (pass) {
+                                const unsigned long long key = ((unsigned long long)f32_to_ord(val) << 32) | (unsigned int)(cur.c0 + c);
+                                const unsigned int slot = wcount + __builtin_amdgcn_mbcnt_hi((unsigned int)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)m, 0u));
+                                if (slot < (unsigned int)WSTASH) {
+                                    wkeys[slot] = key;
+                                    wrow[slot] = (unsigned int)r;
+                                } else {   // (more than fit: straight to the query's list)
+                                    const unsigned int pos = atomicAdd(&A.cand_cnt[cur.q0 + r], 1u);
+                                    if (pos < (unsigned int)A.cap) A.cand_keys[(size_t)(cur.q0 + r) * A.cap + pos] = key;
+                                }
+                            }
+                            wcount += (unsigned int)__popcll(m);
+                        }
+                    }
+                }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // within a wave LDS accesses take effect in program order
+            const unsigned int kept = wcount < (unsigned int)WSTASH ? wcount : (unsigned int)WSTASH;
+            for (unsigned int i = lane; i < kept; i += 64) {
+                const unsigned int q = (unsigned int)cur.q0 + wrow[i];
+                const unsigned int pos = atomicAdd(&A.cand_cnt[q], 1u);
+                if (pos < (unsigned int)A.cap) A.cand_keys[(size_t)q * A.cap + pos] = wkeys[i];
+            }
+            if (!more) break;
+            __syncthreads();   // every wave has left its collected entries: the operand buffers are free again
+            local += blocks_per_die;
+            cur = next;
+            rows = next_rows;
+            continue;
+        }
+        // 32 rows x 64 columns of a wave at a time go through an LDS patch of its own and leave as rows
         float *patch_out = lds + wave * 32 * OS3;
         const bool vec_out = (k & 3) == 0;
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
 #pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2)
+            for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int ta = half * 2 + t2;
-                        const int rl = t2 * 16 + 4 * (lane >> 4) + v, cl = tb * 16 + (lane & 15);
-                        patch_out[rl * OS3 + cl] = fmaf(-2.f, acc[ta][tb][v], ny[wy * 64 + half * 32 + rl] + nc[wx * 64 + cl]);
-                    }
+                for (int v = 0; v < 16; ++v) {
+                    const int rl = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3), cl = tb * 32 + (lane & 31);
+                    patch_out[rl * OS3 + cl] = fmaf(-2.f, acc[half][tb][v], ny[wy * 64 + half * 32 + rl] + nc[wx * 64 + cl]);
+                }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll 4
             for (int i = 0; i < 8; ++i) {
@@ -808,13 +876,28 @@ bool coarse_f32_usable(pq_ctx *ctx, const float *queries, const float *cents, in
     return d >= 16 && (d & 3) == 0 && (bits & 15) == 0 && tiles >= 2 * (int64_t)ctx->num_cu && tiles < (1ll << 30);
 }
 
-int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, float *out) {
-    if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, out)) return fail(ctx, PQ_EINVAL, "coarse_f32: shape not served");
+int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, size_t cent_stride, int nq, int d, int k, float *out) {
+    if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, out) || (cent_stride & 3) != 0) return fail(ctx, PQ_EINVAL, "coarse_f32: shape not served");
     CoarseF32Args A{};
-    A.queries = queries; A.cents = cents; A.out = out; A.nq = nq; A.d = d; A.k = k;
+    A.queries = queries; A.cents = cents; A.cent_stride = cent_stride; A.out = out; A.nq = nq; A.d = d; A.k = k;
     A.tiles_x = (k + MT2 - 1) / MT2; A.tiles_y = (nq + MT2 - 1) / MT2; A.total = A.tiles_x * A.tiles_y;
-    const int grid = (3 * ctx->num_cu + 7) / 8 * 8;   // three blocks per compute unit
-    coarse_f32_kernel<<<grid, 256, 0, ctx->stream>>>(A);
+    const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
+    coarse_f32_kernel<false><<<grid, 256, 0, ctx->stream>>>(A);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// The same distances, but only those at or below theta[q] leave, as keys (ordered value << 32 | centroid) appended to
+// cand_keys[q][cap]; cand_cnt[q] (zero at the start) counts them all.
+int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
+                             unsigned long long *cand_keys, unsigned int *cand_cnt, int cap) {
+    if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, queries)) return fail(ctx, PQ_EINVAL, "coarse_f32: shape not served");
+    CoarseF32Args A{};
+    A.queries = queries; A.cents = cents; A.cent_stride = (size_t)d; A.out = nullptr; A.nq = nq; A.d = d; A.k = k;
+    A.tiles_x = (k + MT2 - 1) / MT2; A.tiles_y = (nq + MT2 - 1) / MT2; A.total = A.tiles_x * A.tiles_y;
+    A.theta = theta; A.cand_keys = cand_keys; A.cand_cnt = cand_cnt; A.cap = cap;
+    const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
+    coarse_f32_kernel<true><<<grid, 256, 0, ctx->stream>>>(A);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }

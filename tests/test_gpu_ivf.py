@@ -294,7 +294,9 @@ def _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe):
     return p.cpu().numpy()
 
 
-@pytest.mark.parametrize("nlist,nq,d,nprobe", [(4096, 2100, 64, 16), (8192, 1100, 32, 64), (5000, 1700, 128, 3)])
+# (the last case has lists and queries enough for the form that writes no matrix: a sample of the lists gives every query
+# a bound, and only the distances at or below it leave the kernel)
+@pytest.mark.parametrize("nlist,nq,d,nprobe", [(4096, 2100, 64, 16), (8192, 1100, 32, 64), (5000, 1700, 128, 3), (32768, 4100, 32, 20)])
 def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, nprobe):
     coarse, offsets, codes, cb, queries = _many_lists_problem(nlist + nq, nlist, nq, d)
     gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
@@ -304,10 +306,11 @@ def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, n
     assert np.array_equal(_probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe), ref)
 
 
-def test_ivf_index_step_ties_beyond_the_exactly_measured_lists(ctx):
+@pytest.mark.parametrize("nlist,nq,d", [(4096, 2100, 64), (32768, 4100, 32)])
+def test_ivf_index_step_ties_beyond_the_exactly_measured_lists(ctx, nlist, nq, d):
     """100 copies of one centroid are the nearest lists of some queries: more equal distances than the nprobe + 16 lists
     measured exactly, so those queries take the exact rows; ties go by list number, as in the oracle."""
-    nlist, nq, d, nprobe = 4096, 2100, 64, 16
+    nprobe = 16
     coarse, offsets, codes, cb, queries = _many_lists_problem(77, nlist, nq, d)
     r = np.random.default_rng(78)
     copies = r.choice(nlist, 100, replace=False)

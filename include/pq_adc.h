@@ -80,7 +80,11 @@ const char *pq_version(void);
  *   lut_mfma (1)              0: pq_build_luts without the matrix cores
  *   ivf_prune (0)             1: inverted lists scanned by the loop on 16-bit lower bounds
  *   ivf_ws_gib (24)           workspace limit of ivf_adc_search in GiB (1 ... 128)
- *   ivf_block_waves (8)       16: inverted lists scanned by blocks of 16 waves */
+ *   ivf_block_waves (8)       16: inverted lists scanned by blocks of 16 waves
+ *   scan_wide_seed (1)        0: first bounds of flat scans of few queries from the small sample only
+ *   ivf_short_max (16384)     inverted lists of fewer codes take the kernel for short lists (0: none)
+ *   ivf_coarse_f32 (1)        0: Index step of ivf_adc_search from exact distances to every list (default: lists
+ *                             ranked by fp32 matrix-core distances, the nearest measured exactly; same lists) */
 int pq_set_option(pq_ctx *ctx, const char *name, int value);
 int pq_unset_option(pq_ctx *ctx, const char *name);
 
@@ -240,7 +244,12 @@ typedef struct {
  * The lists are scanned by the float loop, four (query, list) pairs per work item, in blocks of 8
  * waves, two per compute unit (option ivf_block_waves = 16: one block of 16).  Option ivf_prune = 1 selects the
  * loop on 16-bit lower bounds with exact float distances only for the codes whose bound passes
- * (as in pq_adc_scan_topk), eight pairs per item. */
+ * (as in pq_adc_scan_topk), eight pairs per item.
+ * The probed lists are those with the smallest (distance from the plain definition, summed in double and
+ * rounded to fp32 once; list id).  With many lists and queries they are found through approximate distances:
+ * the lists are ranked on the fp32 matrix cores, the nprobe + 16 nearest are measured exactly, and a query whose
+ * nprobe-th exact distance is not provably below that of every other list gets all its distances computed
+ * exactly (option ivf_coarse_f32 = 0: exact distances to every list for every query). */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);

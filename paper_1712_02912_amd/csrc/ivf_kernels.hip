@@ -669,6 +669,11 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_state = take(state_bytes);
     int rc = ws_reserve(ctx, off);
     if (rc) return rc;
+    if (!ctx->aux_stream) {   // second stream of the context and the two events that fork to it and join from it
+        PQ_HIP(ctx, hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
+        PQ_HIP(ctx, hipEventCreateWithFlags(&ctx->aux_fork, hipEventDisableTiming));
+        PQ_HIP(ctx, hipEventCreateWithFlags(&ctx->aux_join, hipEventDisableTiming));
+    }
     uint8_t *ws = (uint8_t *)ctx->ws;
     float *dist = (float *)(ws + o_dist);
     int32_t *probes = (int32_t *)(ws + o_probes);
@@ -733,6 +738,23 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
             ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, nlist, nprobe, probes, pout, nullptr);
             PQ_HIP(ctx, hipGetLastError());
         }
+        // The grouping of the pairs needs the probed lists only: it runs on a stream of the context's own (same priority)
+        // beside the residuals and their tables, and joins the caller's stream before the first bounds.
+        hipStream_t g = ctx->aux_stream;
+        PQ_HIP(ctx, hipEventRecord(ctx->aux_fork, s));
+        PQ_HIP(ctx, hipStreamWaitEvent(g, ctx->aux_fork, 0));
+        ivf_zero_kernel<<<256, 256, 0, g>>>(np, (size_t)nlist);
+        ivf_zero_kernel<<<256, 256, 0, g>>>(fill, (size_t)nlist);
+        ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, g>>>(probes, npairs, np);
+        ivf_plan_kernel<<<1, 1024, 0, g>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb, short_max, (uint32_t)IVF_SHORT_QS);
+        ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, g>>>(probes, npairs, pair_off, fill, pairs_by_list);
+        ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, g>>>(pair_off, nc, item_off, L->list_offsets, nlist,
+                                                                  rows_per_16b, item_qb, items, short_max, pairs_by_list, short_items);
+        ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, g>>>(probes, nc, nqb, nprobe, pair_out, qlists);
+        ivf_qlist_scan_kernel<<<1, 1024, 0, g>>>(qlists, nqb, qlist_off);
+        ivf_pair_abs_kernel<<<(unsigned)(((size_t)nqb * nprobe + 255) / 256), 256, 0, g>>>(qlist_off, (size_t)nqb * nprobe, nprobe, pair_out);
+        PQ_HIP(ctx, hipGetLastError());
+        PQ_HIP(ctx, hipEventRecord(ctx->aux_join, g));
         // Tables step on the residuals
         {
             const size_t n = (size_t)npairs * d;
@@ -742,18 +764,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         }
         rc = launch_build_luts(ctx, resid, codebooks, npairs, d, m, k, luts);
         if (rc) return rc;
-        // group the pairs by list, lay out the work items
-        ivf_zero_kernel<<<256, 256, 0, s>>>(np, (size_t)nlist);
-        ivf_zero_kernel<<<256, 256, 0, s>>>(fill, (size_t)nlist);
-        ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, np);
-        ivf_plan_kernel<<<1, 1024, 0, s>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb, short_max, (uint32_t)IVF_SHORT_QS);
-        ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, s>>>(probes, npairs, pair_off, fill, pairs_by_list);
-        ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, s>>>(pair_off, nc, item_off, L->list_offsets, nlist,
-                                                                  rows_per_16b, item_qb, items, short_max, pairs_by_list, short_items);
-        ivf_pair_lists_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(probes, nc, nqb, nprobe, pair_out, qlists);
-        ivf_qlist_scan_kernel<<<1, 1024, 0, s>>>(qlists, nqb, qlist_off);
-        ivf_pair_abs_kernel<<<(unsigned)(((size_t)nqb * nprobe + 255) / 256), 256, 0, s>>>(qlist_off, (size_t)nqb * nprobe, nprobe, pair_out);
-        PQ_HIP(ctx, hipGetLastError());
+        PQ_HIP(ctx, hipStreamWaitEvent(s, ctx->aux_join, 0));   // the work items are laid out
         // Scan step, seeded with a first bound per query
         float *tau0 = (float *)(ws + o_tau0);
         if (m == 8) ivf_seed_kernel<8><<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, topk, tau0);

@@ -152,6 +152,12 @@ int pq_destroy(pq_ctx *ctx) {
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->lut_ws) (void)hipFree(ctx->lut_ws);
     if (ctx->host_pin) (void)hipHostFree(ctx->host_pin);
+    if (ctx->aux_stream) {
+        (void)hipStreamSynchronize(ctx->aux_stream);
+        (void)hipStreamDestroy(ctx->aux_stream);
+        (void)hipEventDestroy(ctx->aux_fork);
+        (void)hipEventDestroy(ctx->aux_join);
+    }
     if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
     if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     free(ctx);

@@ -23,6 +23,8 @@ struct pq_ctx {
     void *lut_ws;      // Tables step of many tiles: operands as doubles and their norms, grown on demand
     size_t lut_ws_bytes;
     void *host_pin;    // 256 bytes of pinned host memory for the few words a call reads back
+    hipStream_t aux_stream;          // ivf_adc_search: work that does not depend on the tables runs beside them
+    hipEvent_t aux_fork, aux_join;
     int opt[PQ_OPT_COUNT];
     int num_cu;
     int profiling;              // bracket the scan kernel with events

@@ -78,7 +78,9 @@ const char *pq_version(void);
  *                             tiles per chunk of the first round of short items that long result lists
  *                             start with (0: none)
  *   lut_mfma (1)              0: pq_build_luts without the matrix cores
- *   ivf_prune (0)             1: inverted lists scanned by the loop on 16-bit lower bounds
+ *   ivf_prune (unset)         1 / 0: the inverted lists that the kernel for short lists does not take are scanned
+ *                             by the loop on 16-bit lower bounds / by the plain float loop (unset: the former
+ *                             where short lists have their kernel, else the latter)
  *   ivf_ws_gib (24)           workspace limit of ivf_adc_search in GiB (1 ... 128)
  *   ivf_block_waves (8)       16: inverted lists scanned by blocks of 16 waves
  *   scan_wide_seed (1)        0: first bounds of flat scans of few queries from the small sample only
@@ -241,10 +243,12 @@ typedef struct {
  * every (query, list) pair, result lists) stays within ivf_ws_gib GiB of device
  * memory (pq_set_option, default 24, 1 ... 128); one batch is fastest because a list's
  * codes are then scanned once for all the queries that probe it.
- * The lists are scanned by the float loop, four (query, list) pairs per work item, in blocks of 8
- * waves, two per compute unit (option ivf_block_waves = 16: one block of 16).  Option ivf_prune = 1 selects the
- * loop on 16-bit lower bounds with exact float distances only for the codes whose bound passes
- * (as in pq_adc_scan_topk), eight pairs per item.
+ * With m = 8, lists of fewer than ivf_short_max codes are scanned by a kernel of their own (the whole list for
+ * four pairs per pass); the longer lists by the loop on 16-bit lower bounds with exact float distances only for
+ * the codes whose bound passes (as in pq_adc_scan_topk), eight (query, list) pairs per work item, in blocks of
+ * 8 waves, two per compute unit.  Option ivf_prune = 0 selects the plain float loop, four pairs per item (also
+ * the default with m = 16 and with ivf_block_waves = 16: one block of 16 waves per compute unit, no kernel
+ * for short lists).
  * The probed lists are those with the smallest (distance from the plain definition, summed in double and
  * rounded to fp32 once; list id).  With many lists and queries they are found through approximate distances:
  * the lists are ranked on the fp32 matrix cores, the nprobe + 16 nearest are measured exactly, and a query whose

@@ -434,9 +434,14 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
 template <int M>
 __global__ __launch_bounds__(256) void ivf_prune_prep_kernel(const float *__restrict__ luts, const float *__restrict__ tau0,
                                                              int npairs, int nprobe, float range_units, float *pair_min,
-                                                             float *pair_off, float *pair_scale) {
+                                                             float *pair_off, float *pair_scale, const int32_t *__restrict__ probes,
+                                                             const int64_t *__restrict__ list_offsets, int64_t short_max) {
     const int pair = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (pair >= npairs) return;
+    if (short_max > 0) {   // pairs of lists that the kernel of short lists scans need none of this
+        const int l = probes[pair];
+        if (list_offsets[l + 1] - list_offsets[l] < short_max) return;
+    }
     const float4 *t = reinterpret_cast<const float4 *>(luts + (size_t)pair * M * 256);
     float off = 0.f;
     for (int j = 0; j < M; ++j) {
@@ -599,10 +604,17 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
                int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
     (void)cf;
     const int d = L->d, nlist = L->nlist;
-    // The plain float loop (4 pairs per item) by default; PQ_IVF_PRUNE=1 selects the loop on 16-bit lower
-    // bounds (8 pairs per item, one more preparation kernel), which measured the same scan time and a
-    // longer call on the configured workload once two blocks share a CU.
-    const bool prune = opt_int(ctx, PQ_OPT_IVF_PRUNE, 0) != 0;
+    // Short lists (8 tables, plain loop, blocks of 8 waves): a kernel of their own, see ivf_short_kernels.hip.
+    // Option ivf_short_max: lists of fewer codes than this take it (default IVF_SHORT_MAX, 0: none, at most 2^18).
+    int64_t short_max = m == 8 && opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16 ? opt_int(ctx, PQ_OPT_IVF_SHORT_MAX, IVF_SHORT_MAX) : 0;
+    if (short_max < 0) short_max = 0;
+    if (short_max > IVF_CHUNK_TARGET) short_max = IVF_CHUNK_TARGET;
+    // The other lists: the loop on 16-bit lower bounds (8 pairs per item, one preparation kernel over the pairs of
+    // these lists) where the short lists have their own kernel, so that the preparation touches the tables of few
+    // pairs; else the plain float loop (4 pairs per item), which measured the same scan time and a shorter call
+    // when every pair needs the preparation.  Option ivf_prune = 0 / 1 fixes the choice.
+    const int prune_opt = opt_int(ctx, PQ_OPT_IVF_PRUNE, -1);
+    const bool prune = prune_opt < 0 ? short_max > 0 : prune_opt != 0;
     const int kind = prune ? (m == 8 ? 3 : 4) : (m == 8 ? 0 : 1);
     const uint32_t item_qb = prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
     const int kpad = 128;
@@ -647,11 +659,6 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_nitems = take(8);   // (long lists' items, short lists' items)
     const size_t o_pairs = take(npairs_max * 4);
     const size_t o_items = take(max_items * sizeof(IvfItem));
-    // Short lists (8 tables, plain loop, blocks of 8 waves): a kernel of their own, see ivf_short_kernels.hip.
-    // Option ivf_short_max: lists of fewer codes than this take it (default IVF_SHORT_MAX, 0: none, at most 2^18).
-    int64_t short_max = m == 8 && !prune && opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16 ? opt_int(ctx, PQ_OPT_IVF_SHORT_MAX, IVF_SHORT_MAX) : 0;
-    if (short_max < 0) short_max = 0;
-    if (short_max > IVF_CHUNK_TARGET) short_max = IVF_CHUNK_TARGET;
     const size_t max_short_items = short_max > 0 ? npairs_max / IVF_SHORT_QS + (size_t)nlist + 1 : 0;
     const size_t o_sitems = take(max_short_items * sizeof(IvfShortItem));
     const size_t o_pairout = take(npairs_max * 4);
@@ -773,8 +780,8 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         float *pmin = nullptr, *poff = nullptr, *pscale = nullptr;
         if (prune) {
             pmin = (float *)(ws + o_pmin); poff = (float *)(ws + o_poff); pscale = (float *)(ws + o_pscale);
-            if (m == 8) ivf_prune_prep_kernel<8><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale);
-            else ivf_prune_prep_kernel<16><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale);
+            if (m == 8) ivf_prune_prep_kernel<8><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale, probes, L->list_offsets, short_max);
+            else ivf_prune_prep_kernel<16><<<(npairs + 3) / 4, 256, 0, s>>>(luts, tau0, npairs, nprobe, IVF_PRUNE_RANGE, pmin, poff, pscale, probes, L->list_offsets, short_max);
             PQ_HIP(ctx, hipGetLastError());
         }
         unsigned long long *tau_key = nullptr;

@@ -158,7 +158,8 @@ def test_ivf_queries_served_in_several_batches(ctx, opts):
     run_ivf(ctx, queries, coarse, offsets, codes, None, cb, 64, 20)
 
 
-@pytest.mark.parametrize("env", [{"ivf_block_waves": 16}, {"ivf_prune": 1},
+@pytest.mark.parametrize("env", [{"ivf_block_waves": 16}, {"ivf_prune": 1}, {"ivf_prune": 0},
+                                 {"ivf_prune": 1, "ivf_short_max": 0}, {"ivf_prune": 0, "ivf_short_max": 0},
                                  {"ivf_prune": 1, "ivf_block_waves": 16}])
 @pytest.mark.parametrize("m", [8, 16])
 def test_ivf_switches_lower_bound_loop_and_block_shape(ctx, opts, env, m):

@@ -73,7 +73,7 @@ __device__ unsigned long long g_short_ticks[8];
 #define SH_TICK(phase) do { } while (0)
 #endif
 
-__global__ __launch_bounds__(SH_THREADS) void ivf_short_scan_kernel(const uint8_t *__restrict__ codes,
+__global__ __launch_bounds__(SH_THREADS, 4) void ivf_short_scan_kernel(const uint8_t *__restrict__ codes,
                                                                     const float *__restrict__ luts,
                                                                     const IvfShortItem *__restrict__ items,
                                                                     const uint32_t *__restrict__ nitems_dev,
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(SH_THREADS) void ivf_short_scan_kernel(const uint8_
     auto load_pair_state = [&](const IvfShortItem &r, uint32_t &out, unsigned long long &key) {
         const int nslots = (int)(r.ncodes_skip_slots >> 28);
         if (tid < nslots) {
-            const int pair = r.pair[tid];
+            const int pair = tid == 0 ? r.pair[0] : tid == 1 ? r.pair[1] : tid == 2 ? r.pair[2] : r.pair[3];
             out = pair_out[pair];
             key = __hip_atomic_load(&tau_key[pair / nprobe], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -192,13 +192,16 @@ __global__ __launch_bounds__(SH_THREADS) void ivf_short_scan_kernel(const uint8_
                     float d[SH_QS] = {e[0].x, e[0].y, e[0].z, e[0].w};
 #pragma unroll
                     for (int st = 1; st < 8; ++st) { d[0] += e[st].x; d[1] += e[st].y; d[2] += e[st].z; d[3] += e[st].w; }
+                    // (never true for empty slots: their bound is the smallest key)
+                    if ((d[0] <= bval[0]) | (d[1] <= bval[1]) | (d[2] <= bval[2]) | (d[3] <= bval[3])) {
 #pragma unroll
-                    for (int s = 0; s < SH_QS; ++s) {
-                        if (d[s] <= bval[s]) {   // (never true for empty slots: their bound is the smallest key)
-                            const unsigned long long key = ((unsigned long long)f32_to_ord(d[s]) << 32) | (row0 + (uint32_t)i);
-                            if (key <= sm.bkey[s]) {
-                                const int at = atomicAdd(&sm.cnt[s], 1);
-                                if (at < SH_CAP) sm.cand[s][at] = key;
+                        for (int s = 0; s < SH_QS; ++s) {
+                            if (d[s] <= bval[s]) {
+                                const unsigned long long key = ((unsigned long long)f32_to_ord(d[s]) << 32) | (row0 + (uint32_t)i);
+                                if (key <= sm.bkey[s]) {
+                                    const int at = atomicAdd(&sm.cnt[s], 1);
+                                    if (at < SH_CAP) sm.cand[s][at] = key;
+                                }
                             }
                         }
                     }
@@ -218,7 +221,7 @@ __global__ __launch_bounds__(SH_THREADS) void ivf_short_scan_kernel(const uint8_
                 if (tid == 0) {
                     const unsigned long long kth = sm.sortbuf[topk - 1];
                     sm.bkey[s] = kth;   // (below the old bound: every key held was at or below it)
-                    atomicMin(&tau_key[rec.pair[s] / nprobe], kth);
+                    atomicMin(&tau_key[sm.rec.pair[s] / nprobe], kth);
                 }
                 __syncthreads();   // (the sorted keys have been read before the next pair's are written over them)
             }
@@ -237,7 +240,7 @@ __global__ __launch_bounds__(SH_THREADS) void ivf_short_scan_kernel(const uint8_
                 sm.sortbuf[tid] = tid < c ? sm.cand[s][tid] : KEY_EMPTY;
                 short_sort(sm.sortbuf);
                 if (tid < SH_KPAD) out[tid] = sm.sortbuf[tid];
-                if (tid == 0 && c >= topk) atomicMin(&tau_key[rec.pair[s] / nprobe], sm.sortbuf[topk - 1]);
+                if (tid == 0 && c >= topk) atomicMin(&tau_key[sm.rec.pair[s] / nprobe], sm.sortbuf[topk - 1]);
                 __syncthreads();
             } else if (tid < SH_KPAD) {
                 out[tid] = tid < c ? sm.cand[s][tid] : KEY_EMPTY;

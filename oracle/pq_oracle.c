@@ -491,3 +491,91 @@ int orc_ivf_scan(const float *queries, int nq, int d, const float *coarse, int n
     }
     return err;
 }
+
+/* IVFADC search with Quick ADC in the Scan step (chapter 5: 4-bit sub-quantizers and tables
+ * quantised to 8 bits, Section 5.2; Section 5.3 measures it inside the inverted index of
+ * Section 2.3.2).  Per query, with the probed lists in probe order:
+ *   Tables   float tables of the residual y - centroid_l for every probed list (as orc_ivf_scan);
+ *   qmax     float ADC (each code with the tables of its own list) of the first `init` codes met
+ *            when the probed lists are walked in probe order; qmax = the topk-th smallest of these
+ *            distances (the distance to the temporary topk-th neighbour; rank clipped to the number
+ *            of codes met; +inf if the probed lists are empty);
+ *   8 bits   the tables of each (query, list) pair quantised by orc_quantize_luts with the pair's
+ *            own qmin and the query's qmax;
+ *   Scan     plain integer sums of the quantised entries (Alg. 3 without saturation) for every code
+ *            of the list; the kprime smallest (sum, position) of each pair are its candidates;
+ *   Rerank   float ADC of the candidates with the pair's float tables; the topk smallest
+ *            (distance, position) over all pairs of the query; positions mapped through ids.
+ * Integer sums of different pairs are not comparable (each pair has its own qmin and scale), which
+ * is why candidates are chosen per pair and ranked by float distance. */
+int orc_ivf_quick_scan(const float *queries, int nq, int d, const float *coarse, int nlist,
+                       const int64_t *list_offsets, const uint8_t *codes, const int64_t *ids,
+                       const float *codebooks, int m, int k, int fmt, const int32_t *probes, int nprobe,
+                       int64_t init, int kprime, int topk, float *out_dist, int64_t *out_ids)
+{
+    if (m <= 0 || d % m != 0 || kprime <= 0 || topk <= 0 || init < 0) return -1;
+    int cb = code_bytes(m, fmt);
+    size_t per = (size_t)m * k;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int q = 0; q < nq; q++) {
+        float *resid = (float *)malloc(sizeof(float) * d);
+        float *luts = (float *)malloc(sizeof(float) * per * nprobe);
+        uint8_t *qluts = (uint8_t *)malloc(per * nprobe);
+        float *qmax = (float *)malloc(sizeof(float) * nprobe);
+        heap_t temp = { (pair_t *)malloc(sizeof(pair_t) * topk), 0, topk };
+        heap_t cand = { (pair_t *)malloc(sizeof(pair_t) * kprime), 0, kprime };
+        heap_t best = { (pair_t *)malloc(sizeof(pair_t) * topk), 0, topk };
+        pair_t *sorted = (pair_t *)malloc(sizeof(pair_t) * (topk > kprime ? topk : kprime));
+        if (!resid || !luts || !qluts || !qmax || !temp.a || !cand.a || !best.a || !sorted) {
+            err = -2;
+        } else {
+            const int32_t *pr = probes + (size_t)q * nprobe;
+            /* Tables */
+            for (int p = 0; p < nprobe; p++) {
+                int l = pr[p];
+                if (l < 0 || l >= nlist) { for (size_t e = 0; e < per; e++) luts[p * per + e] = 0.0f; continue; }
+                for (int t = 0; t < d; t++) resid[t] = queries[(size_t)q * d + t] - coarse[(size_t)l * d + t];
+                orc_build_luts(resid, 1, d, m, k, codebooks, luts + p * per);
+            }
+            /* qmax */
+            int64_t met = 0, total = 0;
+            for (int p = 0; p < nprobe; p++) {
+                int l = pr[p];
+                if (l >= 0 && l < nlist) total += list_offsets[l + 1] - list_offsets[l];
+            }
+            int64_t want = init < total ? init : total;
+            temp.cap = (int64_t)topk < want ? topk : (int)want;
+            for (int p = 0; p < nprobe && met < want; p++) {
+                int l = pr[p];
+                if (l < 0 || l >= nlist) continue;
+                for (int64_t pos = list_offsets[l]; pos < list_offsets[l + 1] && met < want; pos++, met++)
+                    heap_add(&temp, (double)adc_f32(codes + pos * cb, fmt, luts + p * per, m, k), pos);
+            }
+            float bound = temp.size > 0 ? (float)temp.a[0].v : INFINITY;
+            for (int p = 0; p < nprobe; p++) qmax[p] = bound;
+            /* 8 bits */
+            orc_quantize_luts(luts, nprobe, m, k, qmax, qluts, NULL, NULL);
+            /* Scan and Rerank */
+            for (int p = 0; p < nprobe; p++) {
+                int l = pr[p];
+                if (l < 0 || l >= nlist) continue;
+                cand.size = 0;
+                for (int64_t pos = list_offsets[l]; pos < list_offsets[l + 1]; pos++)
+                    heap_add(&cand, (double)adc_u8(codes + pos * cb, fmt, qluts + p * per, m, k), pos);
+                int nc = heap_drain_sorted(&cand, sorted);
+                for (int c = 0; c < nc; c++) {
+                    int64_t pos = sorted[c].id;
+                    heap_add(&best, (double)adc_f32(codes + pos * cb, fmt, luts + p * per, m, k), pos);
+                }
+            }
+            int got = heap_drain_sorted(&best, sorted);
+            for (int t = 0; t < topk; t++) {
+                out_dist[(size_t)q * topk + t] = t < got ? (float)sorted[t].v : INFINITY;
+                out_ids[(size_t)q * topk + t] = t < got ? (ids ? ids[sorted[t].id] : sorted[t].id) : -1;
+            }
+        }
+        free(resid); free(luts); free(qluts); free(qmax); free(temp.a); free(cand.a); free(best.a); free(sorted);
+    }
+    return err;
+}

@@ -244,6 +244,33 @@ def ivf_search(queries, coarse, list_offsets, codes, ids, codebooks, fmt, nprobe
     return ivf_scan(queries, coarse, list_offsets, codes, ids, codebooks, fmt, probes, topk)
 
 
+def ivf_quick_scan(queries, coarse, list_offsets, codes, ids, codebooks, fmt, probes, init, kprime, topk):
+    """IVFADC search with Quick ADC in the Scan step (orc_ivf_quick_scan)."""
+    queries = _f32(queries)
+    coarse = _f32(coarse)
+    codebooks = _f32(codebooks)
+    codes = _u8(codes)
+    list_offsets = np.ascontiguousarray(list_offsets, dtype=np.int64)
+    probes = np.ascontiguousarray(probes, dtype=np.int32)
+    if ids is not None:
+        ids = np.ascontiguousarray(ids, dtype=np.int64)
+    nq, d = queries.shape
+    nlist = coarse.shape[0]
+    m, k, _ = codebooks.shape
+    nprobe = probes.shape[1]
+    dist = np.empty((nq, topk), np.float32)
+    out_ids = np.empty((nq, topk), np.int64)
+    _check(lib().orc_ivf_quick_scan(_p(queries), nq, d, _p(coarse), nlist, _p(list_offsets), _p(codes), _p(ids),
+                                    _p(codebooks), m, k, fmt, _p(probes), nprobe, _i64(init), kprime, topk,
+                                    _p(dist), _p(out_ids)), "ivf_quick_scan")
+    return dist, out_ids
+
+
+def ivf_quick_search(queries, coarse, list_offsets, codes, ids, codebooks, fmt, nprobe, init, kprime, topk):
+    probes, _ = ivf_probe(queries, coarse, nprobe)
+    return ivf_quick_scan(queries, coarse, list_offsets, codes, ids, codebooks, fmt, probes, init, kprime, topk)
+
+
 def set_threads(n):
     """Number of OpenMP threads the query-parallel loops use (0 = library default)."""
     omp = ctypes.CDLL("libgomp.so.1")

@@ -378,6 +378,89 @@ def test_ivf_single_list_zero_centroid_is_flat_scan():
     assert np.array_equal(i1, i2) and np.array_equal(d1, d2)
 
 
+# ----------------------------------------------------------------------------- IVFADC with Quick ADC
+def make_ivf_u4(seed=23, n=2500, d=32, nlist=9, nq=5):
+    base, queries, coarse, cb, codes, ids, offsets, list_of = make_ivf(seed=seed, n=n, d=d, m=16, k=16, nlist=nlist, nq=nq)
+    return queries, coarse, cb, orc.pack_u4(codes), codes, ids, offsets, list_of
+
+
+def test_ivf_quick_one_list_is_the_flat_quick_adc_pipeline():
+    """One list, one probe: the search is the flat pipeline on the residual's tables, step by step through the flat
+    functions that have pins of their own (prescan -> 8-bit tables -> integer scan -> float rerank)."""
+    queries, _, cb, packed, codes, _, _, _ = make_ivf_u4(nlist=4)
+    r = np.random.default_rng(3)
+    centroid = (r.random((1, queries.shape[1])) * 40).astype(np.float32)
+    offsets = np.array([0, len(packed)], np.int64)
+    U4 = orc.CODES_U4_PACKED
+    for init, kprime, topk in ((300, 40, 10), (5000, 64, 64), (7, 9, 9)):
+        dist, ids = orc.ivf_quick_search(queries, centroid, offsets, packed, None, cb, U4, 1, init, kprime, topk)
+        luts = orc.build_luts(queries - centroid, cb)
+        qmax = orc.qmax_prescan(packed, U4, luts, init, topk)
+        qluts, _, _ = orc.quantize_luts(luts, qmax)
+        _, cand = orc.adc_scan_topk_u8(packed, U4, qluts, kprime)
+        rd, ri = orc.rerank_f32(packed, U4, luts, cand, topk)
+        assert np.array_equal(ids, ri) and np.array_equal(dist, rd)
+
+
+def test_ivf_quick_with_every_code_a_candidate_is_the_float_search():
+    """kprime at least the longest list: the integer stage dismisses nothing, the result is the float IVFADC search."""
+    queries, coarse, cb, packed, _, ids, offsets, _ = make_ivf_u4()
+    U4 = orc.CODES_U4_PACKED
+    kprime = int(np.diff(offsets).max())
+    for nprobe in (1, 4, len(coarse)):
+        d1, i1 = orc.ivf_quick_search(queries, coarse, offsets, packed, ids, cb, U4, nprobe, 200, kprime, 25)
+        d2, i2 = orc.ivf_search(queries, coarse, offsets, packed, ids, cb, U4, nprobe, 25)
+        assert np.array_equal(i1, i2) and np.array_equal(d1, d2)
+
+
+def test_ivf_quick_brute_force_several_lists():
+    """Every step written out with numpy for a few queries: qmax from the first init codes in probe order (they span
+    two lists here), per-pair qmin, floor quantisation, per-pair integer top-kprime, float top-k over the pairs."""
+    queries, coarse, cb, packed, codes, ids, offsets, _ = make_ivf_u4(seed=29)
+    U4 = orc.CODES_U4_PACKED
+    nprobe, kprime, topk = 3, 12, 8
+    probes, _ = orc.ivf_probe(queries, coarse, nprobe)
+    sizes = np.diff(offsets)
+    init = int(sizes[probes[:, 0]].min()) + 50          # reaches into the second probed list for some query
+    assert (sizes[probes[:, 0]] < init).any()
+    dist, got = orc.ivf_quick_scan(queries, coarse, offsets, packed, ids, cb, U4, probes, init, kprime, topk)
+    m = 16
+    for q in range(len(queries)):
+        tabs, seen = [], []
+        for l in probes[q]:
+            resid = (queries[q] - coarse[l]).astype(np.float32)
+            tabs.append(np_luts(resid[None], cb)[0].astype(np.float32))       # [m][k], rounded once
+        for p, l in enumerate(probes[q]):
+            for pos in range(offsets[l], offsets[l + 1]):
+                if len(seen) < init:
+                    seen.append(np.float32(tabs[p][np.arange(m), codes[pos]].astype(np.float64).sum()))
+        qmax = np.sort(np.array(seen, np.float32))[min(topk, len(seen)) - 1]
+        pool_d, pool_pos = [], []
+        for p, l in enumerate(probes[q]):
+            qmin = tabs[p].min()
+            scale = np.float32(255.0) / np.float32(qmax - qmin) if qmax - qmin > 0 else np.float32(0)
+            t = (tabs[p] - qmin).astype(np.float32) * scale
+            qt = np.where(t >= 255, 255, np.floor(t)).astype(np.int64)
+            pos = np.arange(offsets[l], offsets[l + 1])
+            sums = qt[np.arange(m)[None, :], codes[pos]].sum(1)
+            _, keep = np_topk(sums, pos, kprime)
+            pool_pos.append(keep)
+            pool_d.append(tabs[p][np.arange(m)[None, :], codes[keep]].astype(np.float64).sum(1).astype(np.float32))
+        rd, rpos = np_topk(np.concatenate(pool_d), np.concatenate(pool_pos), topk)
+        assert np.array_equal(dist[q], rd) and np.array_equal(got[q], ids[rpos])
+
+
+def test_ivf_quick_empty_lists_and_short_results():
+    queries, coarse, cb, packed, _, _, offsets, _ = make_ivf_u4()
+    U4 = orc.CODES_U4_PACKED
+    empty = np.zeros_like(offsets)
+    dist, ids = orc.ivf_quick_search(queries, coarse, empty, packed[:0], None, cb, U4, 2, 100, 10, 5)
+    assert np.all(np.isinf(dist)) and np.all(ids == -1)
+    # fewer candidates than topk: nprobe * kprime results, then (+inf, -1)
+    dist, ids = orc.ivf_quick_search(queries, coarse, offsets, packed, None, cb, U4, 2, 100, 3, 10)
+    assert np.all(np.isfinite(dist[:, :6])) and np.all(np.isinf(dist[:, 6:])) and np.all(ids[:, 6:] == -1)
+
+
 # ----------------------------------------------------------------------------- input generators
 def test_rotate_identity_permutation_and_matmul():
     """Section 2.3.4 (OPQ): R x.  Identity and permutations are exact; a general R matches a float64 product."""

@@ -95,7 +95,7 @@ int pq_unset_option(pq_ctx *ctx, const char *name);
  *   queries   [nq][d] f32, codebooks [m][k][d/m] f32  ->  luts [nq][m][k] f32.
  * Requires d % m == 0, 1 <= k <= 65536.  Sub-vectors of 8 dimensions and more are handled in
  * double precision on the matrix cores (expanded form, entries rounded once to f32); shorter
- * ones by differences in f32. */
+ * ones by differences, squared and added in double in the order of the dimensions, rounded once. */
 int pq_build_luts(pq_ctx *ctx, const float *queries, const float *codebooks, int nq, int d, int m, int k,
                   float *luts);
 
@@ -257,6 +257,28 @@ typedef struct {
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);
+
+/* The same search with Quick ADC in the Scan step (chapter 5; Section 5.2: 4-bit sub-quantizers and tables
+ * quantised to 8 bits; Section 5.3 evaluates Quick ADC inside the inverted index of Section 2.3.2).
+ * lists->codes holds PQ_CODES_U4_PACKED codes of m = 16 indexes (8 bytes per code), codebooks [16][16][d/16].
+ * Index and Tables steps as ivf_adc_search.  Then, per query:
+ *   qmax    float ADC of the first `init` codes met when the probed lists are walked in probe order, each code
+ *           with the float tables of its own (query, list) pair; qmax = the topk-th smallest of these distances
+ *           (rank clipped to the number of codes met; +inf if the probed lists are empty) - the distance to a
+ *           temporary topk-th neighbour (Section 5.2.1);
+ *   8 bits  the tables of every (query, list) pair quantised as by pq_quantize_luts, with the pair's own qmin
+ *           and the query's qmax;
+ *   Scan    plain integer sums of the 8-bit entries (Alg. 3) for every code of the list; the kprime smallest
+ *           (sum, row) of each pair are its candidates (sums of different pairs have different scales and are
+ *           never compared);
+ *   Rerank  float ADC of the candidates with the pair's float tables; the topk smallest (distance, row) over
+ *           the pairs of the query, rows mapped through `ids`.  Fewer than topk candidates: (+inf, -1) behind.
+ * Float sums are formed in double in table order and rounded to fp32 once.
+ * Covered: m = 16, k = 16; 1 <= nprobe <= min(nlist, 1024); 1 <= topk, kprime <= 128; 1 <= init <= 4096;
+ * ntotal < 2^32; codes 16-byte aligned.  Workspace and batching as ivf_adc_search. */
+int ivf_quick_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, const float *queries,
+                         int nq, int nprobe, int init, int kprime, int topk, float *out_dist, int64_t *out_ids,
+                         int32_t *probe_out);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ LUT_U8 = 1
 
 EXPORTS = ["pq_create", "pq_destroy", "pq_last_error", "pq_version", "pq_build_luts", "pq_quantize_luts",
            "pq_qmax_prescan", "pq_adc_scan_topk", "pq_rerank_f32", "ivf_adc_search", "pq_encode", "pq_rotate", "pq_derived_search", "pq_set_profiling",
-           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option", "pq_last_scan_info", "pq_adc_scan_topk_noalloc"]
+           "pq_last_scan_kernel_ms", "pq_calibration_copy", "pq_set_option", "pq_unset_option", "pq_last_scan_info", "pq_adc_scan_topk_noalloc",
+           "ivf_quick_adc_search"]
 
 _lib = None
 
@@ -59,6 +60,7 @@ def load():
     lib.pq_unset_option.argtypes = [vp, ctypes.c_char_p]
     lib.pq_rerank_f32.argtypes = [vp, vp, i64, ci, vp, ci, ci, ci, vp, ci, ci, vp, vp]
     lib.ivf_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, ci, vp, ci, ci, ci, vp, vp, vp]
+    lib.ivf_quick_adc_search.argtypes = [vp, ctypes.POINTER(IvfLists), vp, ci, ci, vp, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.pq_rotate.argtypes = [vp, vp, vp, i64, ci, vp]
     lib.pq_encode.argtypes = [vp, vp, vp, i64, ci, ci, ci, ci, vp]
     lib.pq_derived_search.argtypes = [vp, vp, i64, vp, vp, ci, vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, i64]
@@ -282,4 +284,26 @@ class Context:
         probes = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device) if return_probes else None
         self._check(self.lib.ivf_adc_search(self.handle, ctypes.byref(lists), _ptr(codebooks), m, k, code_fmt,
                                             _ptr(queries), nq, nprobe, topk, _ptr(dist), _ptr(out_ids), _ptr(probes)))
+        return (dist, out_ids, probes) if return_probes else (dist, out_ids)
+
+    def ivf_quick_adc_search(self, coarse_centroids, list_offsets, codes, ids, codebooks, queries, nprobe, init, kprime,
+                             topk, return_probes=False):
+        coarse_centroids = _dev(coarse_centroids, torch.float32, "coarse_centroids")
+        list_offsets = _dev(list_offsets, torch.int64, "list_offsets")
+        codes = _dev(codes, torch.uint8, "codes")
+        if ids is not None:
+            ids = _dev(ids, torch.int64, "ids")
+        codebooks = _dev(codebooks, torch.float32, "codebooks")
+        queries = _dev(queries, torch.float32, "queries")
+        nlist, d = coarse_centroids.shape
+        m, k, _ = codebooks.shape
+        nq = queries.shape[0]
+        lists = IvfLists(coarse_centroids.data_ptr(), list_offsets.data_ptr(), codes.data_ptr(),
+                         ids.data_ptr() if ids is not None else None, nlist, d, codes.shape[0])
+        dist = torch.empty((nq, topk), dtype=torch.float32, device=queries.device)
+        out_ids = torch.empty((nq, topk), dtype=torch.int64, device=queries.device)
+        probes = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device) if return_probes else None
+        self._check(self.lib.ivf_quick_adc_search(self.handle, ctypes.byref(lists), _ptr(codebooks), m, k, _ptr(queries),
+                                                  nq, nprobe, init, kprime, topk, _ptr(dist), _ptr(out_ids),
+                                                  _ptr(probes)))
         return (dist, out_ids, probes) if return_probes else (dist, out_ids)

@@ -27,6 +27,7 @@ constexpr int64_t IVF_CHUNK_TARGET = 1 << 18; // rows per chunk aimed at for lon
 constexpr float IVF_PRUNE_RANGE = 3500.f;      // table units between the sum of a pair's minima and the query's first bound
 constexpr int IVF_QB_PLAIN = 4;               // queries per work item: plain float loop
 constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bounds
+constexpr int IVF_QB_QUICK = 8;               // Quick ADC: pairs whose 8-bit tables lie side by side
 constexpr int IVF_SHORT_MAX = 16384;          // lists of fewer codes are scanned by the kernel of short lists (8 tables, plain loop)
 
 // ------------------------------------------------------------------------------------------
@@ -601,12 +602,14 @@ __global__ __launch_bounds__(256) void ivf_exact_rows_kernel(const float *__rest
 
 // ------------------------------------------------------------------------------------------
 int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, int k, int cf, const float *queries,
-               int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out) {
-    (void)cf;
+               int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids, int32_t *probe_out, int init, int kprime) {
     const int d = L->d, nlist = L->nlist;
+    // Packed 4-bit codes: Quick ADC in the Scan step (ivf_quick_kernels.hip), eight pairs per work item, every list
+    // cut into work items the same way.
+    const bool quick = cf == PQ_CODES_U4_PACKED;
     // Short lists (8 tables, plain loop, blocks of 8 waves): a kernel of their own, see ivf_short_kernels.hip.
     // Option ivf_short_max: lists of fewer codes than this take it (default IVF_SHORT_MAX, 0: none, at most 2^18).
-    int64_t short_max = m == 8 && opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16 ? opt_int(ctx, PQ_OPT_IVF_SHORT_MAX, IVF_SHORT_MAX) : 0;
+    int64_t short_max = !quick && m == 8 && opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16 ? opt_int(ctx, PQ_OPT_IVF_SHORT_MAX, IVF_SHORT_MAX) : 0;
     if (short_max < 0) short_max = 0;
     if (short_max > IVF_CHUNK_TARGET) short_max = IVF_CHUNK_TARGET;
     // The other lists: the loop on 16-bit lower bounds (8 pairs per item, one preparation kernel over the pairs of
@@ -614,11 +617,11 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     // pairs; else the plain float loop (4 pairs per item), which measured the same scan time and a shorter call
     // when every pair needs the preparation.  Option ivf_prune = 0 / 1 fixes the choice.
     const int prune_opt = opt_int(ctx, PQ_OPT_IVF_PRUNE, -1);
-    const bool prune = prune_opt < 0 ? short_max > 0 : prune_opt != 0;
+    const bool prune = !quick && (prune_opt < 0 ? short_max > 0 : prune_opt != 0);
     const int kind = prune ? (m == 8 ? 3 : 4) : (m == 8 ? 0 : 1);
-    const uint32_t item_qb = prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
+    const uint32_t item_qb = quick ? IVF_QB_QUICK : prune ? IVF_QB_PRUNED : IVF_QB_PLAIN;   // (query, list) pairs per work item
     const int kpad = 128;
-    const int rows_per_16b = 16 / m;
+    const int rows_per_16b = 16 / (quick ? m / 2 : m);
     hipStream_t s = ctx->stream;
 
     // queries per batch: keeps the per-query part of the workspace (coarse distances, residuals and
@@ -671,9 +674,12 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_partial = take(max_lists * kpad * 8);
     // blocks of 8 waves, two per CU, unless PQ_IVF_BLOCK_WAVES=16 asks for the flat scan's shape
     const bool w8_blocks = opt_int(ctx, PQ_OPT_IVF_BLOCK_WAVES, 8) != 16;
-    const size_t state_bytes = w8_blocks ? w8::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu)
-                                         : w16::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
+    const size_t state_bytes = quick ? 0 : w8_blocks ? w8::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu)
+                                                     : w16::tuned_state_bytes(kind, qbatch, topk, ctx->num_cu);
     const size_t o_state = take(state_bytes);
+    const size_t o_qmaxp = take(quick ? npairs_max * 4 : 0);
+    const size_t o_qluts = take(quick ? npairs_max * (size_t)m * k : 0);
+    const size_t o_tauq = take(quick ? (size_t)qbatch * 8 : 0);
     int rc = ws_reserve(ctx, off);
     if (rc) return rc;
     if (!ctx->aux_stream) {   // second stream of the context and the two events that fork to it and join from it
@@ -772,6 +778,17 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         rc = launch_build_luts(ctx, resid, codebooks, npairs, d, m, k, luts);
         if (rc) return rc;
         PQ_HIP(ctx, hipStreamWaitEvent(s, ctx->aux_join, 0));   // the work items are laid out
+        if (quick) {
+            unsigned long long *tau_q = (unsigned long long *)(ws + o_tauq);
+            rc = launch_ivf_quick(ctx, L->codes, L->list_offsets, probes, luts, nqb, nprobe, init, kprime, topk,
+                                  (float *)(ws + o_qmaxp), ws + o_qluts, items, nitems_dev, pairs_by_list, pair_out, nc,
+                                  partial, tau_q);
+            if (rc) return rc;
+            rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_q, kpad, nqb, topk, L->ids, false,
+                                       out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);
+            if (rc) return rc;
+            continue;
+        }
         // Scan step, seeded with a first bound per query
         float *tau0 = (float *)(ws + o_tau0);
         if (m == 8) ivf_seed_kernel<8><<<nqb, 256, 0, s>>>(L->codes, L->list_offsets, probes, luts, nprobe, topk, tau0);

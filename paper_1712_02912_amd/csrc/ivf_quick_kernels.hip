@@ -1,0 +1,410 @@
+// IVFADC search with Quick ADC in the Scan step (chapter 5: packed 4-bit codes, m = 16 sub-quantizers of 16
+// centroids, tables quantised to 8 bits, Section 5.2; Section 5.3 evaluates it inside the inverted index of
+// Section 2.3.2).  Per query:
+//   qmax     float ADC of the first `init` codes met when the probed lists are walked in probe order (each code with
+//            the float tables of its own (query, list) pair); qmax = the topk-th smallest of these distances, the
+//            distance to a temporary topk-th neighbour (Section 5.2.1, as Section 4.2.4);
+//   8 bits   every pair's tables quantised between the pair's own smallest entry and the query's qmax
+//            (launch_quantize_luts);
+//   Scan     integer sums of the 8-bit entries (Alg. 3, plain sums) over the codes of the list; the kprime smallest
+//            (sum, row) of a pair are its candidates;
+//   Rerank   float ADC of the candidates with the pair's float tables; the topk smallest (distance, row) of the query.
+// Sums of different pairs are not comparable (own qmin and scale each), so the candidates are chosen per pair.
+//
+// Where the thesis keeps the 16 tables of 16 bytes in SIMD registers and looks 16 codes up at once, the scan kernel
+// here keeps the tables of EIGHT (query, list) pairs that probe the same list side by side in LDS: the entry for
+// (sub-quantizer j, index i) is one 16-byte slot of eight 16-bit values, so one LDS read serves eight pairs and the
+// eight sums are formed by four packed 16-bit additions per sub-quantizer.  The 16 slots of a sub-quantizer cover
+// all 64 LDS banks once: lanes with different indexes never collide and lanes with equal indexes read one address.
+//
+// The kprime smallest sums of a work item (a chunk of a list x up to 8 pairs) are found by counting instead of
+// sorting, because sums are small integers (at most 16 * 255): a first pass over the codes counts the sums of each
+// pair in 512 bins, which gives the kprime-th smallest sum T of the pair exactly; a second pass collects the codes
+// below T (fewer than kprime) and, in row order, those equal to T.  Every float sum of this file is formed in
+// double in table order and rounded once, so that the bound, the 8-bit tables, the candidates and the distances are
+// those of the plain definition bit for bit.
+#include "pq_internal.h"
+#include "scan_common.h"
+#include "topk_device.h"
+
+namespace pq {
+
+constexpr int QK_THREADS = 256;
+constexpr int QK_WAVES = QK_THREADS / 64;
+constexpr int QK_QS = 8;          // (query, list) pairs per work item
+constexpr int QK_BINS = 512;      // sums counted per pass: base .. base + 510, and one bin for everything above
+constexpr int QK_KP = 128;        // kprime at most (the length of a result list)
+constexpr int QK_BATCH = 4;       // codes of a thread on their way at a time
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
+    const u16x2 r = __builtin_bit_cast(u16x2, a) + __builtin_bit_cast(u16x2, b);
+    return __builtin_bit_cast(uint32_t, r);
+}
+// per 16-bit half: a - b, 0 where b > a
+__device__ __forceinline__ uint32_t pk_sub_sat_u16(uint32_t a, uint32_t b) {
+    const u16x2 r = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// index j (0 .. 15) of a packed code: component 2i in the low half of byte i
+__device__ __forceinline__ uint32_t code_index4(const uint2 c, int j) { return ((j < 8 ? c.x : c.y) >> (4 * (j & 7))) & 15u; }
+
+// float ADC in double, table order, rounded once (tab: [16][16] floats)
+__device__ __forceinline__ float adc16x4_exact(const float *tab, const uint2 c) {
+    double s = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) s += (double)tab[j * 16 + code_index4(c, j)];
+    return (float)s;
+}
+
+// ------------------------------------------------------------------------------------------
+// qmax of every query, written once per (query, list) pair, and the query's bound for the final merge set to "none".
+// One block per query.
+constexpr int QK_INIT_MAX = 4096;
+__global__ __launch_bounds__(256) void ivf_quick_qmax_kernel(const uint8_t *__restrict__ codes,
+                                                             const int64_t *__restrict__ list_offsets,
+                                                             const int32_t *__restrict__ probes, const float *__restrict__ luts,
+                                                             int nprobe, int init, int topk, float *qmax_pair,
+                                                             unsigned long long *tau_key) {
+    __shared__ float tab[256];
+    __shared__ uint32_t vals[QK_INIT_MAX];
+    __shared__ uint32_t bins[256], state[2];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    int count = 0;
+    for (int r = 0; r < nprobe && count < init; ++r) {
+        const int l = probes[(size_t)q * nprobe + r];
+        const int64_t beg = list_offsets[l], size = list_offsets[l + 1] - beg;
+        const int take = (int)(size < init - count ? size : init - count);
+        if (take <= 0) continue;
+        __syncthreads();
+        tab[tid] = luts[((size_t)q * nprobe + r) * 256 + tid];
+        __syncthreads();
+        for (int i = tid; i < take; i += 256) {
+            const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)(beg + i) * 8);
+            vals[count + i] = f32_to_ord(adc16x4_exact(tab, c));
+        }
+        count += take;
+    }
+    __syncthreads();
+    float qmax = __builtin_inff();
+    if (count > 0) qmax = ord_to_f32(block_kth_smallest_u32(vals, count, (uint32_t)(topk < count ? topk : count), bins, state));
+    for (int r = tid; r < nprobe; r += 256) qmax_pair[(size_t)q * nprobe + r] = qmax;
+    if (tid == 0) tau_key[q] = KEY_EMPTY;
+}
+
+// ------------------------------------------------------------------------------------------
+struct __align__(16) QuickSmem {
+    uint4 tab[256];                              // slot j * 16 + i: the 8-bit entries (j, i) of the 8 pairs as 16-bit values
+    uint32_t hist[QK_QS][QK_BINS];
+    unsigned long long sure[QK_QS][QK_KP];       // keys below the pair's T (fewer than kprime)
+    uint32_t tie[QK_WAVES][QK_QS][QK_KP];        // rows with sum T, per wave in ascending order
+    int sure_cnt[QK_QS];
+    int tie_cnt[QK_WAVES][QK_QS];
+    uint32_t tstar[QK_QS];                       // T: the kprime-th smallest sum (0xffff: every code is a candidate)
+    uint32_t below[QK_QS];                       // sums below `base` (counted in earlier attempts)
+    uint32_t base[QK_QS];                        // first sum of bin 0 in the current counting pass
+    int found[QK_QS];
+    int pair[QK_QS];
+    uint32_t out_idx[QK_QS];
+    int pending;                                 // pairs whose T is not known yet
+};
+static_assert(sizeof(QuickSmem) <= 53 * 1024, "three blocks share the 160 KB of a compute unit");
+
+__global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
+                                                                       const uint8_t *__restrict__ qluts,
+                                                                       const IvfItem *__restrict__ items,
+                                                                       const uint32_t *__restrict__ nitems_dev,
+                                                                       const int32_t *__restrict__ pairs_by_list,
+                                                                       const uint32_t *__restrict__ pair_out, int kprime,
+                                                                       uint64_t *partial) {
+    __shared__ QuickSmem sm;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nitems = (int)*nitems_dev;
+    for (int item = (int)blockIdx.x; item < nitems; item += (int)gridDim.x) {
+        const IvfItem it = items[item];
+        const int skip = (int)(it.skip_slots_chunk & 255u);
+        const int nslots = (int)((it.skip_slots_chunk >> 8) & 255u);
+        const uint32_t chunk = it.skip_slots_chunk >> 16;
+        const int ncodes = (int)it.ncodes;            // rows from code_begin; the first `skip` belong to the list before
+        const int nvalid = ncodes - skip;
+        const uint32_t row0 = it.code_begin;
+        const uint8_t *base_ptr = codes + (size_t)row0 * 8;
+        __syncthreads();   // the item before is done with the shared state
+        if (tid < QK_QS) {
+            const int pair = tid < nslots ? pairs_by_list[it.pair_pos + tid] : -1;
+            sm.pair[tid] = pair;
+            sm.out_idx[tid] = pair >= 0 ? pair_out[pair] + chunk : 0u;
+            sm.sure_cnt[tid] = 0;
+            sm.below[tid] = 0u;
+            sm.base[tid] = 0u;
+            sm.tstar[tid] = 0xffffu;
+            sm.found[tid] = (tid >= nslots || nvalid <= kprime) ? 1 : 0;
+        }
+        __syncthreads();
+        // ---- the 8-bit tables of the item's pairs, widened to 16 bits, pair s in half s of the slot
+        {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int s = 0; s < QK_QS; ++s) {
+                const int pair = sm.pair[s];
+                const uint32_t e = pair >= 0 ? (uint32_t)qluts[(size_t)pair * 256 + tid] : 0u;
+                w[s >> 1] |= e << (16 * (s & 1));
+            }
+            sm.tab[tid] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        __syncthreads();
+
+        // sums of one code for the eight pairs: four registers of two 16-bit sums
+        const char *tab_bytes = reinterpret_cast<const char *>(sm.tab);
+        auto sums_of = [&](const uint2 c, uint32_t (&acc)[4]) {
+            acc[0] = acc[1] = acc[2] = acc[3] = 0u;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint4 e = *reinterpret_cast<const uint4 *>(tab_bytes + j * 256 + (code_index4(c, j) << 4));
+                acc[0] = pk_add_u16(acc[0], e.x); acc[1] = pk_add_u16(acc[1], e.y);
+                acc[2] = pk_add_u16(acc[2], e.z); acc[3] = pk_add_u16(acc[3], e.w);
+            }
+        };
+        // f(row index within the item, code) for every code of the item; a thread meets its rows in ascending order,
+        // and so does a wave (lane by lane within a step, step by step)
+        auto for_codes = [&](auto &&f) {
+            for (int i0 = skip + tid; i0 < ncodes; i0 += QK_BATCH * QK_THREADS) {
+                uint2 c[QK_BATCH];
+#pragma unroll
+                for (int u = 0; u < QK_BATCH; ++u) {
+                    const int i = i0 + u * QK_THREADS;
+                    c[u] = i < ncodes ? *reinterpret_cast<const uint2 *>(base_ptr + (size_t)i * 8) : make_uint2(0u, 0u);
+                }
+#pragma unroll
+                for (int u = 0; u < QK_BATCH; ++u) {
+                    const int i = i0 + u * QK_THREADS;
+                    f(i, c[u], i < ncodes);
+                }
+            }
+        };
+
+        // ---- counting passes: T of every pair (one pass unless fewer than kprime sums lie below 511)
+        if (nvalid > kprime) {
+            for (;;) {
+                for (int i = tid; i < QK_QS * QK_BINS; i += QK_THREADS) (&sm.hist[0][0])[i] = 0u;
+                if (tid == 0) sm.pending = 0;
+                __syncthreads();
+                uint32_t lo[QK_QS];
+                bool open[QK_QS];
+#pragma unroll
+                for (int s = 0; s < QK_QS; ++s) { lo[s] = sm.base[s]; open[s] = sm.found[s] == 0; }
+                for_codes([&](int, const uint2 c, bool valid) {
+                    if (!valid) return;
+                    uint32_t acc[4];
+                    sums_of(c, acc);
+#pragma unroll
+                    for (int s = 0; s < QK_QS; ++s) {
+                        const uint32_t sum = (acc[s >> 1] >> (16 * (s & 1))) & 0xffffu;
+                        if (open[s] && sum >= lo[s]) {
+                            const uint32_t b = sum - lo[s];
+                            atomicAdd(&sm.hist[s][b < (uint32_t)(QK_BINS - 1) ? b : (uint32_t)(QK_BINS - 1)], 1u);
+                        }
+                    }
+                });
+                __syncthreads();
+                // wave w reads the bins of pairs w and w + 4: lane l owns bins 8 l .. 8 l + 7
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int s = wave + QK_WAVES * h;
+                    if (sm.found[s]) continue;   // (uniform)
+                    uint32_t b8[8], tot = 0u;
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) { b8[t] = sm.hist[s][lane * 8 + t]; tot += b8[t]; }
+                    if (lane == 63) tot -= b8[7];   // the last bin holds every greater sum: it cannot name T
+                    uint32_t incl = tot;
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        const uint32_t up = __shfl_up(incl, o);
+                        if (lane >= o) incl += up;
+                    }
+                    const uint32_t want = (uint32_t)kprime - sm.below[s];
+                    const uint64_t reach = __ballot(incl >= want);
+                    if (reach != 0ull) {
+                        if (lane == __builtin_ctzll(reach)) {
+                            uint32_t cum = incl - tot;
+                            int t = 0;
+                            while (cum + b8[t] < want) { cum += b8[t]; ++t; }   // (ends within the lane's bins)
+                            sm.tstar[s] = sm.base[s] + (uint32_t)(lane * 8 + t);
+                            sm.below[s] += cum;   // sums below T
+                            sm.found[s] = 1;
+                        }
+                    } else if (lane == 63) {   // fewer than kprime sums up to base + 510: count the next 511 values
+                        sm.below[s] += incl;
+                        sm.base[s] += (uint32_t)(QK_BINS - 1);
+                        atomicAdd(&sm.pending, 1);
+                    }
+                }
+                __syncthreads();
+                if (sm.pending == 0) break;
+                __syncthreads();   // (pending is cleared by thread 0 at the top of the next pass)
+            }
+        }
+
+        // ---- collecting pass: keys below T, and the rows at T in ascending order per wave
+        {
+            uint32_t tplus[4] = {0u, 0u, 0u, 0u};   // T + 1 per pair (0 for empty slots: nothing passes)
+            uint32_t tval[QK_QS];
+            int need[QK_QS], tcnt[QK_QS];
+#pragma unroll
+            for (int s = 0; s < QK_QS; ++s) {
+                tval[s] = sm.tstar[s];
+                const uint32_t tp = s < nslots ? (tval[s] < 0xffffu ? tval[s] + 1u : 0xffffu) : 0u;
+                tplus[s >> 1] |= tp << (16 * (s & 1));
+                // rows at T that can still be candidates: kprime less the sums below T (none when every code is taken)
+                need[s] = (s < nslots && tval[s] < 0xffffu) ? kprime - (int)sm.below[s] : 0;
+                tcnt[s] = 0;
+            }
+            for_codes([&](int i, const uint2 c, bool valid) {
+                uint32_t acc[4];
+                sums_of(c, acc);
+                const uint32_t any = pk_sub_sat_u16(tplus[0], acc[0]) | pk_sub_sat_u16(tplus[1], acc[1]) |
+                                     pk_sub_sat_u16(tplus[2], acc[2]) | pk_sub_sat_u16(tplus[3], acc[3]);
+                const bool some = valid && any != 0u;
+                if (__ballot(some) == 0ull) return;
+#pragma unroll
+                for (int s = 0; s < QK_QS; ++s) {
+                    const uint32_t sum = (acc[s >> 1] >> (16 * (s & 1))) & 0xffffu;
+                    const bool in = valid && s < nslots;
+                    if (in && sum < tval[s]) {
+                        const int at = atomicAdd(&sm.sure_cnt[s], 1);   // (fewer than kprime such codes exist)
+                        sm.sure[s][at] = ((unsigned long long)sum << 32) | (row0 + (uint32_t)i);
+                    }
+                    const bool at_t = in && sum == tval[s] && tval[s] < 0xffffu;
+                    const uint64_t mask = __ballot(at_t);
+                    if (mask != 0ull) {
+                        const int pos = tcnt[s] + mask_prefix(mask);
+                        if (at_t && pos < need[s]) sm.tie[wave][s][pos] = row0 + (uint32_t)i;
+                        tcnt[s] += __popcll(mask);
+                        if (tcnt[s] > need[s]) tcnt[s] = need[s];   // (later rows of this wave are greater: not needed)
+                    }
+                }
+            });
+            if (lane == 0) {
+#pragma unroll
+                for (int s = 0; s < QK_QS; ++s) sm.tie_cnt[wave][s] = tcnt[s];
+            }
+        }
+        __syncthreads();
+
+        // ---- result lists: the keys below T, then the smallest rows at T up to kprime keys, then empty slots; put
+        // together in LDS (the list of keys below T has room for kprime keys), then written out
+        for (int e = tid; e < QK_QS * QK_KP; e += QK_THREADS) {
+            const int s = e / QK_KP, idx = e % QK_KP;
+            if (idx >= sm.sure_cnt[s]) sm.sure[s][idx] = KEY_EMPTY;
+        }
+        __syncthreads();
+        for (int s = 0; s < nslots; ++s) {
+            const int c = sm.sure_cnt[s];
+            const uint32_t t = sm.tstar[s];
+            const int need = t < 0xffffu ? kprime - c : 0;
+            if (need <= 0) continue;
+            // entry e of wave w's list: its rank among the rows at T of all waves (rows are distinct)
+            for (int e = tid; e < QK_WAVES * QK_KP; e += QK_THREADS) {
+                const int w = e / QK_KP, idx = e % QK_KP;
+                if (idx >= sm.tie_cnt[w][s]) continue;
+                const uint32_t row = sm.tie[w][s][idx];
+                int rank = idx;
+#pragma unroll
+                for (int w2 = 0; w2 < QK_WAVES; ++w2) {
+                    if (w2 == w) continue;
+                    int lo = 0, hi = sm.tie_cnt[w2][s];   // rows of w2 below `row`
+                    while (lo < hi) {
+                        const int mid = (lo + hi) >> 1;
+                        if (sm.tie[w2][s][mid] < row) lo = mid + 1; else hi = mid;
+                    }
+                    rank += lo;
+                }
+                if (rank < need) sm.sure[s][c + rank] = ((unsigned long long)t << 32) | row;
+            }
+        }
+        __syncthreads();
+        for (int e = tid; e < nslots * QK_KP; e += QK_THREADS) {
+            const int s = e / QK_KP, idx = e % QK_KP;
+            partial[(size_t)sm.out_idx[s] * QK_KP + idx] = sm.sure[s][idx];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Rerank: one block per (query, list) pair.  The kprime smallest integer keys over the pair's result lists (one list
+// per chunk of the inverted list) are its candidates; their float distances replace them in the pair's first list,
+// in ascending order, the other lists are emptied, and the pair's topk-th key (if it has one) bounds the query's result.
+__global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ luts,
+                                                               const int32_t *__restrict__ probes, const uint32_t *__restrict__ nc_arr,
+                                                               const uint32_t *__restrict__ pair_out, int nprobe, int kprime,
+                                                               int topk, uint64_t *partial, unsigned long long *tau_key) {
+    __shared__ float tab[256];
+    __shared__ uint64_t keys[2048];
+    const int pair = blockIdx.x, tid = threadIdx.x;
+    const int nc = (int)nc_arr[probes[pair]];
+    uint64_t *lists = partial + (size_t)pair_out[pair] * QK_KP;
+    tab[tid] = luts[(size_t)pair * 256 + tid];
+    tab[tid + 128] = luts[(size_t)pair * 256 + 128 + tid];
+    uint64_t key;
+    if (nc <= 1) {
+        key = nc == 1 ? lists[tid] : KEY_EMPTY;
+    } else {
+        int n2 = 256;
+        while (n2 < nc * QK_KP) n2 <<= 1;
+        for (int i = tid; i < n2; i += 128) keys[i] = i < nc * QK_KP ? lists[i] : KEY_EMPTY;
+        block_bitonic_sort(keys, n2);
+        key = tid < kprime ? keys[tid] : KEY_EMPTY;
+        __syncthreads();
+    }
+    __syncthreads();
+    uint64_t fkey = KEY_EMPTY;
+    if (key != KEY_EMPTY) {
+        const uint32_t row = (uint32_t)key;
+        const uint2 c = *reinterpret_cast<const uint2 *>(codes + (size_t)row * 8);
+        fkey = ((uint64_t)f32_to_ord(adc16x4_exact(tab, c)) << 32) | row;
+    }
+    keys[tid] = fkey;
+    block_bitonic_sort(keys, 128);
+    if (nc >= 1) lists[tid] = keys[tid];
+    for (int i = 128 + tid; i < nc * QK_KP; i += 128) lists[i] = KEY_EMPTY;
+    if (tid == 0 && keys[topk - 1] != KEY_EMPTY) atomicMin(&tau_key[pair / nprobe], (unsigned long long)keys[topk - 1]);
+}
+
+// ------------------------------------------------------------------------------------------
+int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
+                     const float *luts, int nq, int nprobe, int init, int kprime, int topk, float *qmax_pair,
+                     uint8_t *qluts, const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
+                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key) {
+    if (kprime < 1 || kprime > QK_KP || topk < 1 || topk > QK_KP || init < 1 || init > QK_INIT_MAX)
+        return fail(ctx, PQ_EUNSUPPORTED, "ivf quick adc: kprime and topk must be 1..%d, init 1..%d", QK_KP, QK_INIT_MAX);
+    hipStream_t s = ctx->stream;
+    const int npairs = nq * nprobe;
+    ivf_quick_qmax_kernel<<<nq, 256, 0, s>>>(codes, list_offsets, probes, luts, nprobe, init, topk, qmax_pair, tau_key);
+    PQ_HIP(ctx, hipGetLastError());
+    int rc = launch_quantize_luts(ctx, luts, npairs, 16, 16, qmax_pair, qluts, nullptr, nullptr);
+    if (rc) return rc;
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
+        snprintf(ctx->last_scan_name, sizeof(ctx->last_scan_name),
+                 "ivf_quick_scan_kernel (16x4 codes, 8-bit tables of 8 (query, list) pairs per work item, blocks of 4 waves)");
+        ctx->last_scan_qpp = QK_QS;
+        ctx->last_scan_passes = 2;
+        ctx->stat_parked = nullptr;
+        ctx->stat_ncand = nullptr;
+        ctx->stat_ncand_len = 0;
+    }
+    ivf_quick_scan_kernel<<<ctx->num_cu * 3, QK_THREADS, 0, s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+                                                                 kprime, partial);
+    PQ_HIP(ctx, hipGetLastError());
+    if (ctx->profiling) {
+        PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
+        ctx->ev_valid = 1;
+    }
+    ivf_quick_rerank_kernel<<<npairs, 128, 0, s>>>(codes, luts, probes, nc_arr, pair_out, nprobe, kprime, topk, partial, tau_key);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+}  // namespace pq

@@ -8,8 +8,8 @@ namespace pq {
 
 
 // ------------------------------------------------------------------------------------------
-// Direct form  D[q][j][i] = sum_t (y[q][j*dsub+t] - C[j][i][t])^2  in f32.  All terms are
-// non-negative, so the relative error is bounded by about (dsub+1) * 2^-24.
+// Direct form  D[q][j][i] = sum_t (y[q][j*dsub+t] - C[j][i][t])^2, the differences, their squares and
+// the sum in double, term by term in the order of t, rounded to f32 once: the value of the plain definition.
 // Block = (tile of 16 queries) x (one sub-space j) x (tile of 64 centroids): the centroid
 // tile and the query sub-vectors are staged in LDS in slabs of 32 dimensions.
 constexpr int LUT_TQ = 16, LUT_TC = 64, LUT_TD = 32;
@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
     const int q0 = blockIdx.z * LUT_TQ;
     const int ci = threadIdx.x & 63;        // centroid within tile
     const int qi = threadIdx.x >> 6;        // 0..3: this thread handles queries qi, qi+4, qi+8, qi+12
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};   // differences, squares and their sum in double, term by term: the plain definition
     for (int t0 = 0; t0 < dsub; t0 += LUT_TD) {
         const int td = dsub - t0 < LUT_TD ? dsub - t0 : LUT_TD;
         for (int e = threadIdx.x; e < LUT_TC * LUT_TD; e += 256) {
@@ -41,8 +41,8 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
             const float c = sc[ci][t];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float diff = sy[qi + 4 * r][t] - c;
-                acc[r] = fmaf(diff, diff, acc[r]);
+                const double diff = (double)sy[qi + 4 * r][t] - (double)c;
+                acc[r] = __dadd_rn(acc[r], __dmul_rn(diff, diff));
             }
         }
         __syncthreads();
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void build_luts_kernel(const float *__restrict
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int q = q0 + qi + 4 * r;
-            if (q < nq) luts[((size_t)q * m + j) * k + c0 + ci] = acc[r];
+            if (q < nq) luts[((size_t)q * m + j) * k + c0 + ci] = (float)acc[r];
         }
     }
 }

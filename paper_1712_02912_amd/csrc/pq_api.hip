@@ -392,7 +392,31 @@ int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, 
         (lists->ntotal > 0 && !lists->codes))
         return fail(ctx, PQ_EINVAL, "ivf_adc_search: null pointer");
     if (!aligned16(lists->codes)) return fail(ctx, PQ_EINVAL, "ivf_adc_search: codes must be 16-byte aligned");
-    return launch_ivf(ctx, lists, codebooks, m, k, cf, queries, nq, nprobe, topk, out_dist, out_ids, probe_out);
+    return launch_ivf(ctx, lists, codebooks, m, k, cf, queries, nq, nprobe, topk, out_dist, out_ids, probe_out, 0, 0);
+}
+
+int ivf_quick_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, const float *queries,
+                         int nq, int nprobe, int init, int kprime, int topk, float *out_dist, int64_t *out_ids,
+                         int32_t *probe_out) {
+    if (!ctx) return PQ_EINVAL;
+    if (!lists) return fail(ctx, PQ_EINVAL, "ivf_quick_adc_search: null lists");
+    if (lists->nlist <= 0 || lists->d <= 0 || lists->ntotal < 0 || nq < 0)
+        return fail(ctx, PQ_EINVAL, "ivf_quick_adc_search: bad size");
+    if (m != 16 || k != 16) return fail(ctx, PQ_EUNSUPPORTED, "ivf_quick_adc_search: covered is m=16, k=16 (m=%d k=%d)", m, k);
+    if (lists->d % m != 0) return fail(ctx, PQ_ESHAPE, "ivf_quick_adc_search: d=%d is not a multiple of m=%d", lists->d, m);
+    if (nprobe < 1 || nprobe > lists->nlist)
+        return fail(ctx, PQ_ESHAPE, "ivf_quick_adc_search: nprobe=%d outside 1..nlist=%d", nprobe, lists->nlist);
+    if (topk < 1 || kprime < 1 || init < 1) return fail(ctx, PQ_EINVAL, "ivf_quick_adc_search: topk, kprime and init must be at least 1");
+    if (nprobe > 1024 || topk > 128 || kprime > 128 || init > 4096)
+        return fail(ctx, PQ_EUNSUPPORTED, "ivf_quick_adc_search: covered are nprobe<=1024, topk<=128, kprime<=128, init<=4096");
+    if (lists->ntotal >= ((int64_t)1 << 32)) return fail(ctx, PQ_EUNSUPPORTED, "ivf_quick_adc_search: ntotal must be below 2^32");
+    if (nq == 0) return PQ_OK;
+    if (!lists->coarse_centroids || !lists->list_offsets || !codebooks || !queries || !out_dist || !out_ids ||
+        (lists->ntotal > 0 && !lists->codes))
+        return fail(ctx, PQ_EINVAL, "ivf_quick_adc_search: null pointer");
+    if (!aligned16(lists->codes)) return fail(ctx, PQ_EINVAL, "ivf_quick_adc_search: codes must be 16-byte aligned");
+    return launch_ivf(ctx, lists, codebooks, m, k, PQ_CODES_U4_PACKED, queries, nq, nprobe, topk, out_dist, out_ids, probe_out,
+                      init, kprime);
 }
 
 }  // extern "C"

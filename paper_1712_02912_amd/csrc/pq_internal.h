@@ -95,6 +95,6 @@ int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const
                           int64_t *cand_ids_out, int64_t cand_cap);
 int launch_ivf(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, int cf,
                const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
-               int32_t *probe_out);
+               int32_t *probe_out, int init, int kprime);   // (init, kprime: Quick ADC over packed 4-bit codes only)
 
 }  // namespace pq

@@ -32,6 +32,14 @@ struct IvfItem {
                                  // bits 8-15: number of pairs (slots), bits 16-31: chunk index in the list
 };
 
+// IVF search with Quick ADC (ivf_quick_kernels.hip): the query-wide qmax, the 8-bit tables of every pair, the integer
+// scan of the work items to the kprime candidates of every (pair, chunk) and their float rerank into the pair's
+// first result list; tau_key [nq] receives a bound of each query's result for the merge that follows.
+int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
+                     const float *luts, int nq, int nprobe, int init, int kprime, int topk, float *qmax_pair,
+                     uint8_t *qluts, const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
+                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key);
+
 // One work item of the scan of short inverted lists (ivf_short_kernels.hip): a whole list for up to
 // IVF_SHORT_QS of the (query, list) pairs that probe it.  32 bytes.
 constexpr int IVF_SHORT_QS = 4;

@@ -321,3 +321,87 @@ def test_ivf_index_step_ties_beyond_the_exactly_measured_lists(ctx, nlist, nq, d
     ref, _ = orc.ivf_probe(queries, coarse, nprobe)
     assert np.array_equal(gp, ref)
     assert np.array_equal(np.sort(ref[0]), np.sort(copies)[:nprobe])   # query 0 probes the copies with the smallest numbers
+
+
+# ----------------------------------------------------------------------------- Quick ADC inside the inverted index
+def make_index_u4(n, d, nlist, seed, ntrain=4000, sizes=None):
+    """Packed 4-bit codes (m = 16, k = 16) of residuals, grouped by list; `sizes` replaces the assignment's list
+    sizes by given ones (codes then uniformly random: list lengths and boundaries are what such a case is about)."""
+    mix = datagen.Mixture(d, 16, (0.0, 128.0), (8.0, 32.0), (0.0, 255.0), seed=seed)
+    base = mix.sample(max(n, ntrain), seed + 1)
+    coarse = orc.kmeans(base[:ntrain], nlist, 3, np.arange(nlist, dtype=np.int64) * (ntrain // nlist))
+    assign = ((base[:, None, :].astype(np.float32) - coarse[None]) ** 2).sum(-1).argmin(1)
+    resid = base - coarse[assign]
+    cb = orc.pq_train(resid[:ntrain], 16, 16, 3, datagen.kmeans_init_idx(ntrain, 16, 16, seed + 2))
+    if sizes is None:
+        order = np.argsort(assign[:n], kind="stable")
+        packed = orc.pack_u4(orc.pq_encode(resid[:n][order], cb))
+        offsets = datagen.offsets_from_sizes(np.bincount(assign[:n], minlength=nlist))
+        return mix, coarse, cb, packed, order.astype(np.int64), offsets
+    offsets = datagen.offsets_from_sizes(np.asarray(sizes))
+    packed = np.random.default_rng(seed + 3).integers(0, 256, (int(offsets[-1]), 8), dtype=np.uint8)
+    return mix, coarse, cb, packed, None, offsets
+
+
+def run_ivf_quick(ctx, queries, coarse, offsets, packed, ids, cb, nprobe, init, kprime, topk):
+    """Bit-exact: every float sum of the path is formed in double and rounded once on both sides, the rest is integer."""
+    d, i, p = ctx.ivf_quick_adc_search(dev(coarse), dev(offsets), dev(packed), None if ids is None else dev(ids), dev(cb),
+                                       dev(queries), nprobe, init, kprime, topk, return_probes=True)
+    torch.cuda.synchronize()
+    gd, gi, gp = d.cpu().numpy(), i.cpu().numpy(), p.cpu().numpy()
+    check_probes(queries, coarse, gp, nprobe)
+    od, oi = orc.ivf_quick_scan(queries, coarse, offsets, packed, ids, cb, orc.CODES_U4_PACKED, gp, init, kprime, topk)
+    assert np.array_equal(gi, oi)
+    assert np.array_equal(gd, od)
+    return gd, gi
+
+
+def test_ivf_quick_encoded_small(ctx):
+    mix, coarse, cb, packed, order, offsets = make_index_u4(20000, 64, 40, seed=51)
+    queries = mix.sample(13, 99)
+    for nprobe, init, kprime, topk in ((1, 200, 40, 10), (8, 1000, 128, 100), (40, 4096, 100, 128), (5, 64, 1, 1),
+                                       (8, 300, 20, 50)):
+        run_ivf_quick(ctx, queries, coarse, offsets, packed, order, cb, nprobe, init, kprime, topk)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 8, 500, 64, 50)
+
+
+def test_ivf_quick_long_lists_in_chunks_short_and_empty_lists(ctx):
+    """One list long enough to be cut into chunks, lists shorter than kprime, empty lists, odd list boundaries."""
+    sizes = [700_001, 90_003, 7, 0, 1, 33_333, 0, 129, 128, 127] + [1000 + 37 * i for i in range(14)]
+    mix, coarse, cb, packed, _, offsets = make_index_u4(0, 32, 24, seed=53, sizes=sizes)
+    queries = mix.sample(9, 97)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 24, 2000, 128, 100)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 6, 50, 30, 20)
+
+
+def test_ivf_quick_ties_of_the_integer_sums(ctx):
+    """Codes drawn from four distinct codes only: thousands of rows share every sum, the candidates are the smallest
+    rows among them; and a first bound from one code (init = 1), which puts most sums into the last bin counted."""
+    sizes = [5000, 3000, 40, 9000]
+    mix, coarse, cb, packed, _, offsets = make_index_u4(0, 32, 4, seed=57, sizes=sizes)
+    r = np.random.default_rng(5)
+    few = r.integers(0, 256, (4, 8), dtype=np.uint8)
+    packed = few[r.integers(0, 4, len(packed))]
+    queries = mix.sample(7, 96)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 4, 1000, 100, 60)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 3, 1, 128, 128)
+    mix, coarse, cb, packed, _, offsets = make_index_u4(0, 32, 4, seed=59, sizes=sizes)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 4, 1, 77, 33)
+
+
+def test_ivf_quick_many_queries_several_groups_per_list(ctx):
+    """More than eight queries probe a list: several work items per list chunk."""
+    mix, coarse, cb, packed, order, offsets = make_index_u4(30000, 64, 12, seed=61)
+    queries = mix.sample(150, 95)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, order, cb, 5, 800, 64, 40)
+
+
+def test_ivf_quick_rejects_what_is_not_covered(ctx):
+    mix, coarse, cb, packed, order, offsets = make_index_u4(3000, 32, 6, seed=63)
+    queries = mix.sample(3, 94)
+    for kw in (dict(nprobe=7), dict(kprime=129), dict(topk=129), dict(init=4097), dict(init=0)):
+        a = dict(nprobe=2, init=100, kprime=10, topk=5)
+        a.update(kw)
+        with pytest.raises(RuntimeError):
+            ctx.ivf_quick_adc_search(dev(coarse), dev(offsets), dev(packed), None, dev(cb), dev(queries), a["nprobe"],
+                                     a["init"], a["kprime"], a["topk"])

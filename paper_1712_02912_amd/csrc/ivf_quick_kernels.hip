@@ -29,9 +29,8 @@
 
 namespace pq {
 
-constexpr int QK_THREADS = 256;
-constexpr int QK_WAVES = QK_THREADS / 64;
 constexpr int QK_QS = 8;          // (query, list) pairs per work item
+constexpr int QK_LONG_MIN = 32768;   // work items of this many rows and more take the blocks of 16 waves
 constexpr int QK_BINS = 512;      // sums counted per pass: base .. base + 510, and one bin for everything above
 constexpr int QK_KP = 128;        // kprime at most (the length of a result list)
 constexpr int QK_BATCH = 4;       // codes of a thread on their way at a time
@@ -95,6 +94,7 @@ __global__ __launch_bounds__(256) void ivf_quick_qmax_kernel(const uint8_t *__re
 }
 
 // ------------------------------------------------------------------------------------------
+template <int QK_WAVES>
 struct __align__(16) QuickSmem {
     uint4 tab[256];                              // slot j * 16 + i: the 8-bit entries (j, i) of the 8 pairs as 16-bit values
     uint32_t hist[QK_QS][QK_BINS];
@@ -106,24 +106,35 @@ struct __align__(16) QuickSmem {
     uint32_t below[QK_QS];                       // sums below `base` (counted in earlier attempts)
     uint32_t base[QK_QS];                        // first sum of bin 0 in the current counting pass
     int found[QK_QS];
+    uint32_t cap[QK_QS];                         // sums above it are not counted (the kprime-th smallest sum so far)
+    uint32_t cum_t[QK_QS];                       // sums from `base` on below the cap (all counted sums while none is reached)
+    int reached[QK_QS];
     int pair[QK_QS];
     uint32_t out_idx[QK_QS];
     int pending;                                 // pairs whose T is not known yet
 };
-static_assert(sizeof(QuickSmem) <= 53 * 1024, "three blocks share the 160 KB of a compute unit");
+static_assert(sizeof(QuickSmem<4>) <= 53 * 1024, "three blocks of 4 waves share the 160 KB of a compute unit");
+static_assert(sizeof(QuickSmem<16>) <= 160 * 1024, "one block of 16 waves per compute unit");
 
-__global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
+// Blocks of QK_WAVES waves.  LONG: the kernel takes the work items of QK_LONG_MIN rows and more (16 waves, one block
+// per compute unit: the longest item of a skewed index is what the call waits for), else the shorter ones (4 waves,
+// three blocks per compute unit).  Items are dealt in a stride of the grid; an item of the other kind is passed over.
+template <int QK_WAVES, bool LONG>
+__global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
                                                                        const uint8_t *__restrict__ qluts,
                                                                        const IvfItem *__restrict__ items,
                                                                        const uint32_t *__restrict__ nitems_dev,
                                                                        const int32_t *__restrict__ pairs_by_list,
                                                                        const uint32_t *__restrict__ pair_out, int kprime,
                                                                        uint64_t *partial) {
-    __shared__ QuickSmem sm;
+    constexpr int QK_THREADS = QK_WAVES * 64;
+    extern __shared__ __align__(16) unsigned char quick_smem[];
+    QuickSmem<QK_WAVES> &sm = *reinterpret_cast<QuickSmem<QK_WAVES> *>(quick_smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nitems = (int)*nitems_dev;
     for (int item = (int)blockIdx.x; item < nitems; item += (int)gridDim.x) {
         const IvfItem it = items[item];
+        if (((int)it.ncodes >= QK_LONG_MIN) != LONG) continue;   // (uniform)
         const int skip = (int)(it.skip_slots_chunk & 255u);
         const int nslots = (int)((it.skip_slots_chunk >> 8) & 255u);
         const uint32_t chunk = it.skip_slots_chunk >> 16;
@@ -144,7 +155,7 @@ __global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uin
         }
         __syncthreads();
         // ---- the 8-bit tables of the item's pairs, widened to 16 bits, pair s in half s of the slot
-        {
+        if (tid < 256) {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int s = 0; s < QK_QS; ++s) {
@@ -158,7 +169,9 @@ __global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uin
 
         // sums of one code for the eight pairs: four registers of two 16-bit sums
         const char *tab_bytes = reinterpret_cast<const char *>(sm.tab);
-        auto sums_of = [&](const uint2 c, uint32_t (&acc)[4]) {
+        // Returns, per lane, whether some pair's sum is below its limit (`limit` holds the limits per 16-bit half; 0:
+        // nothing passes).
+        auto sums_below = [&](const uint2 c, bool valid, const uint32_t (&limit)[4], uint32_t (&acc)[4]) {
             acc[0] = acc[1] = acc[2] = acc[3] = 0u;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -166,78 +179,101 @@ __global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uin
                 acc[0] = pk_add_u16(acc[0], e.x); acc[1] = pk_add_u16(acc[1], e.y);
                 acc[2] = pk_add_u16(acc[2], e.z); acc[3] = pk_add_u16(acc[3], e.w);
             }
+            const uint32_t any = pk_sub_sat_u16(limit[0], acc[0]) | pk_sub_sat_u16(limit[1], acc[1]) |
+                                 pk_sub_sat_u16(limit[2], acc[2]) | pk_sub_sat_u16(limit[3], acc[3]);
+            return valid && any != 0u;
         };
         // f(row index within the item, code) for every code of the item; a thread meets its rows in ascending order,
         // and so does a wave (lane by lane within a step, step by step)
-        auto for_codes = [&](auto &&f) {
-            for (int i0 = skip + tid; i0 < ncodes; i0 += QK_BATCH * QK_THREADS) {
+        auto for_codes = [&](int begin, int end, auto &&f) {
+            for (int i0 = begin + tid; i0 < end; i0 += QK_BATCH * QK_THREADS) {
                 uint2 c[QK_BATCH];
 #pragma unroll
                 for (int u = 0; u < QK_BATCH; ++u) {
                     const int i = i0 + u * QK_THREADS;
-                    c[u] = i < ncodes ? *reinterpret_cast<const uint2 *>(base_ptr + (size_t)i * 8) : make_uint2(0u, 0u);
+                    c[u] = i < end ? *reinterpret_cast<const uint2 *>(base_ptr + (size_t)i * 8) : make_uint2(0u, 0u);
                 }
 #pragma unroll
                 for (int u = 0; u < QK_BATCH; ++u) {
                     const int i = i0 + u * QK_THREADS;
-                    f(i, c[u], i < ncodes);
+                    f(i, c[u], i < end);
                 }
             }
         };
 
-        // ---- counting passes: T of every pair (one pass unless fewer than kprime sums lie below 511)
+        // ---- counting passes: T of every pair.  Sums of base .. base + 510 are counted (one pass unless fewer than
+        // kprime sums lie in that range: then the next 511 values are counted in another pass).  The codes are taken
+        // in segments of 1024, 4096, 16384, ... rows; after each segment the kprime-th smallest sum so far becomes the
+        // pair's cap, and greater sums are no longer counted: the final T cannot exceed it.
         if (nvalid > kprime) {
             for (;;) {
                 for (int i = tid; i < QK_QS * QK_BINS; i += QK_THREADS) (&sm.hist[0][0])[i] = 0u;
+                if (tid < QK_QS) {
+                    sm.cap[tid] = sm.base[tid] + (uint32_t)(QK_BINS - 2);
+                    sm.reached[tid] = 0;
+                    sm.cum_t[tid] = 0u;
+                }
                 if (tid == 0) sm.pending = 0;
                 __syncthreads();
                 uint32_t lo[QK_QS];
                 bool open[QK_QS];
 #pragma unroll
                 for (int s = 0; s < QK_QS; ++s) { lo[s] = sm.base[s]; open[s] = sm.found[s] == 0; }
-                for_codes([&](int, const uint2 c, bool valid) {
-                    if (!valid) return;
-                    uint32_t acc[4];
-                    sums_of(c, acc);
+                for (int seg_begin = skip, seg_len = QK_BATCH * QK_THREADS; seg_begin < ncodes; seg_len *= 4) {
+                    const int seg_end = ncodes - seg_begin < seg_len ? ncodes : seg_begin + seg_len;
+                    uint32_t capv[QK_QS], capplus[4] = {0u, 0u, 0u, 0u};   // cap + 1 per pair (0: pair not counted)
 #pragma unroll
                     for (int s = 0; s < QK_QS; ++s) {
-                        const uint32_t sum = (acc[s >> 1] >> (16 * (s & 1))) & 0xffffu;
-                        if (open[s] && sum >= lo[s]) {
-                            const uint32_t b = sum - lo[s];
-                            atomicAdd(&sm.hist[s][b < (uint32_t)(QK_BINS - 1) ? b : (uint32_t)(QK_BINS - 1)], 1u);
+                        capv[s] = sm.cap[s];
+                        if (open[s]) capplus[s >> 1] |= (capv[s] + 1u) << (16 * (s & 1));
+                    }
+                    for_codes(seg_begin, seg_end, [&](int, const uint2 c, bool valid) {
+                        uint32_t acc[4];
+                        if (!sums_below(c, valid, capplus, acc)) return;
+#pragma unroll
+                        for (int s = 0; s < QK_QS; ++s) {
+                            const uint32_t sum = (acc[s >> 1] >> (16 * (s & 1))) & 0xffffu;
+                            if (open[s] && sum >= lo[s] && sum <= capv[s]) atomicAdd(&sm.hist[s][sum - lo[s]], 1u);
+                        }
+                    });
+                    __syncthreads();
+                    // a wave reads the bins of a pair: lane l owns bins 8 l .. 8 l + 7 (the last bin stays empty)
+                    for (int s = wave; s < QK_QS; s += QK_WAVES) {
+                        if (sm.found[s]) continue;   // (uniform)
+                        uint32_t b8[8], tot = 0u;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) { b8[t] = sm.hist[s][lane * 8 + t]; tot += b8[t]; }
+                        uint32_t incl = tot;
+#pragma unroll
+                        for (int o = 1; o < 64; o <<= 1) {
+                            const uint32_t up = __shfl_up(incl, o);
+                            if (lane >= o) incl += up;
+                        }
+                        const uint32_t want = (uint32_t)kprime - sm.below[s];
+                        const uint64_t reach = __ballot(incl >= want);
+                        if (reach != 0ull) {
+                            if (lane == __builtin_ctzll(reach)) {
+                                uint32_t cum = incl - tot;
+                                int t = 0;
+                                while (cum + b8[t] < want) { cum += b8[t]; ++t; }   // (ends within the lane's bins)
+                                sm.cap[s] = sm.base[s] + (uint32_t)(lane * 8 + t);   // the kprime-th smallest sum so far
+                                sm.cum_t[s] = cum;                                    // sums below it, from base on
+                                sm.reached[s] = 1;
+                            }
+                        } else if (lane == 63) {
+                            sm.cum_t[s] = incl;   // all sums counted so far
                         }
                     }
-                });
-                __syncthreads();
-                // wave w reads the bins of pairs w and w + 4: lane l owns bins 8 l .. 8 l + 7
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int s = wave + QK_WAVES * h;
-                    if (sm.found[s]) continue;   // (uniform)
-                    uint32_t b8[8], tot = 0u;
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) { b8[t] = sm.hist[s][lane * 8 + t]; tot += b8[t]; }
-                    if (lane == 63) tot -= b8[7];   // the last bin holds every greater sum: it cannot name T
-                    uint32_t incl = tot;
-#pragma unroll
-                    for (int o = 1; o < 64; o <<= 1) {
-                        const uint32_t up = __shfl_up(incl, o);
-                        if (lane >= o) incl += up;
-                    }
-                    const uint32_t want = (uint32_t)kprime - sm.below[s];
-                    const uint64_t reach = __ballot(incl >= want);
-                    if (reach != 0ull) {
-                        if (lane == __builtin_ctzll(reach)) {
-                            uint32_t cum = incl - tot;
-                            int t = 0;
-                            while (cum + b8[t] < want) { cum += b8[t]; ++t; }   // (ends within the lane's bins)
-                            sm.tstar[s] = sm.base[s] + (uint32_t)(lane * 8 + t);
-                            sm.below[s] += cum;   // sums below T
-                            sm.found[s] = 1;
-                        }
-                    } else if (lane == 63) {   // fewer than kprime sums up to base + 510: count the next 511 values
-                        sm.below[s] += incl;
-                        sm.base[s] += (uint32_t)(QK_BINS - 1);
+                    __syncthreads();
+                    seg_begin = seg_end;
+                }
+                if (tid < QK_QS && sm.found[tid] == 0) {
+                    sm.below[tid] += sm.cum_t[tid];
+                    if (sm.reached[tid]) {
+                        sm.tstar[tid] = sm.cap[tid];
+                        sm.found[tid] = 1;
+                    } else {   // fewer than kprime sums up to base + 510: count the next 511 values
+                        sm.base[tid] += (uint32_t)(QK_BINS - 1);
                         atomicAdd(&sm.pending, 1);
                     }
                 }
@@ -261,12 +297,9 @@ __global__ __launch_bounds__(QK_THREADS, 3) void ivf_quick_scan_kernel(const uin
                 need[s] = (s < nslots && tval[s] < 0xffffu) ? kprime - (int)sm.below[s] : 0;
                 tcnt[s] = 0;
             }
-            for_codes([&](int i, const uint2 c, bool valid) {
+            for_codes(skip, ncodes, [&](int i, const uint2 c, bool valid) {
                 uint32_t acc[4];
-                sums_of(c, acc);
-                const uint32_t any = pk_sub_sat_u16(tplus[0], acc[0]) | pk_sub_sat_u16(tplus[1], acc[1]) |
-                                     pk_sub_sat_u16(tplus[2], acc[2]) | pk_sub_sat_u16(tplus[3], acc[3]);
-                const bool some = valid && any != 0u;
+                const bool some = sums_below(c, valid, tplus, acc);
                 if (__ballot(some) == 0ull) return;
 #pragma unroll
                 for (int s = 0; s < QK_QS; ++s) {
@@ -388,16 +421,28 @@ int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offs
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
         snprintf(ctx->last_scan_name, sizeof(ctx->last_scan_name),
-                 "ivf_quick_scan_kernel (16x4 codes, 8-bit tables of 8 (query, list) pairs per work item, blocks of 4 waves)");
+                 "ivf_quick_scan_kernel (16x4 codes, 8-bit tables of 8 (query, list) pairs per work item; blocks of 16 waves for items of %d rows and more, of 4 waves for the others)", QK_LONG_MIN);
         ctx->last_scan_qpp = QK_QS;
         ctx->last_scan_passes = 2;
         ctx->stat_parked = nullptr;
         ctx->stat_ncand = nullptr;
         ctx->stat_ncand_len = 0;
     }
-    ivf_quick_scan_kernel<<<ctx->num_cu * 3, QK_THREADS, 0, s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
-                                                                 kprime, partial);
-    PQ_HIP(ctx, hipGetLastError());
+    {
+        auto long_kernel = ivf_quick_scan_kernel<16, true>;
+        auto short_kernel = ivf_quick_scan_kernel<4, false>;
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(long_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)sizeof(QuickSmem<16>)));
+        PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(short_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)sizeof(QuickSmem<4>)));
+        // the long items first (longest lists come first in the table of items), then the many short ones
+        long_kernel<<<ctx->num_cu, 16 * 64, sizeof(QuickSmem<16>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+                                                                       kprime, partial);
+        PQ_HIP(ctx, hipGetLastError());
+        short_kernel<<<ctx->num_cu * 3, 4 * 64, sizeof(QuickSmem<4>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+                                                                          kprime, partial);
+        PQ_HIP(ctx, hipGetLastError());
+    }
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_end, s));
         ctx->ev_valid = 1;

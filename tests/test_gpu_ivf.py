@@ -405,3 +405,44 @@ def test_ivf_quick_rejects_what_is_not_covered(ctx):
         with pytest.raises(RuntimeError):
             ctx.ivf_quick_adc_search(dev(coarse), dev(offsets), dev(packed), None, dev(cb), dev(queries), a["nprobe"],
                                      a["init"], a["kprime"], a["topk"])
+
+
+def test_ivf_quick_full_size_sampled(ctx):
+    """The shape of config 4 with Quick ADC: 10^9 uniform random packed 4-bit codes (16 x 4, 8 bytes each) in 65 536
+    Zipf-sized lists, 10 000 queries in one call, nprobe 64, init 1024, kprime 128, top-100.  Complete results of a
+    sample of the queries against the oracle on the lists the GPU probed (their codes copied back, rows as ids)."""
+    nt, nlist, nq, nprobe, init, kprime, topk = 1_000_000_000, 65536, 10000, 64, 1024, 128, 100
+    mix = datagen.sift_like()
+    coarse = mix.sample(nlist, datagen.SEED_DATA + 7)
+    sizes = datagen.zipf_list_sizes(nt, nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    codes_d = datagen.random_codes_device(nt, 8, datagen.SEED_CODES + 5)
+    cb = datagen.sampled_codebooks(mix, 16, 16) * np.float32(0.25)
+    queries = mix.sample(nq, datagen.SEED_QUERIES + 1)
+    gd, gi, gp = ctx.ivf_quick_adc_search(dev(coarse), dev(offsets), codes_d, None, dev(cb), dev(queries), nprobe, init,
+                                          kprime, topk, return_probes=True)
+    torch.cuda.synchronize()
+    gd, gi, gp = gd.cpu().numpy(), gi.cpu().numpy(), gp.cpu().numpy()
+    longest = int(np.argmax(sizes))
+    hits = np.flatnonzero((gp == longest).any(axis=1))
+    sample = sorted(set([0, 1, 777, 4096, 9999] + hits[:1].tolist()))
+    check_probes(queries[sample], coarse, gp[sample], nprobe)
+    lists = np.unique(gp[sample])
+    sub_off = datagen.offsets_from_sizes(sizes[lists].astype(np.int64))
+    sub_codes = np.empty((int(sub_off[-1]), 8), np.uint8)
+    sub_ids = np.empty(int(sub_off[-1]), np.int64)
+    for j, l in enumerate(lists):
+        a, b = int(offsets[l]), int(offsets[l + 1])
+        sub_codes[sub_off[j]:sub_off[j + 1]] = codes_d[a:b].cpu().numpy()
+        sub_ids[sub_off[j]:sub_off[j + 1]] = np.arange(a, b)
+    remap = np.searchsorted(lists, gp[sample]).astype(np.int32)
+    od, oi = orc.ivf_quick_scan(queries[sample], coarse[lists], sub_off, sub_codes, sub_ids, cb, orc.CODES_U4_PACKED,
+                                remap, init, kprime, topk)
+    assert np.array_equal(gi[sample], oi) and np.array_equal(gd[sample], od)
+    assert np.all(np.diff(gd, axis=1) >= 0) and gi.min() >= 0 and gi.max() < nt
+    for q in range(0, nq, 97):
+        assert len(set(gi[q].tolist())) == topk
+        owner = np.searchsorted(offsets, gi[q], side="right") - 1
+        assert np.isin(owner, gp[q]).all()
+    del codes_d
+    torch.cuda.empty_cache()

@@ -8,6 +8,7 @@ Beside it, each as an object of the same JSON line:
   streaming_pq8x8 / streaming_pq16x4   few queries over 25 M / 10^8 / 10^9 codes: every byte from HBM once per pass;
   config3_pq16x8_d960  config 3: d = 960, 16 x 256, 1 M encoded codes, 1000 queries (+ the Tables step alone);
   ivf_config4          config 4: 10^9 codes in 65 536 Zipf-sized lists, 10 000 queries, nprobe 64;
+  ivf_quick_adc_config4  the same index searched with Quick ADC (16 x 4 codes, 8-bit tables, integer scan, float rerank);
   cpu_baseline         the oracle's scan on the host cores (a bounded sample of config 1).
 Prints ONE JSON line.
 """
@@ -95,6 +96,8 @@ def main():
     ap.add_argument("--skip-ivf", action="store_true")
     ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
     ap.add_argument("--ivf-cpu-queries", type=int, default=100)
+    ap.add_argument("--ivf-quick-init", type=int, default=1024, help="codes scanned for the qmax bound of the Quick ADC IVF leg")
+    ap.add_argument("--ivf-quick-kprime", type=int, default=128, help="candidates per (query, list) pair of the Quick ADC IVF leg")
     ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
     ap.add_argument("--encode-n", type=int, default=4_000_000)
     ap.add_argument("--derived", action="store_true", help="also time pq_derived_search (64-bit codes of four 16-bit indexes, k=65536)")
@@ -373,6 +376,7 @@ def main():
 
     # ---------------------------------------------------------------- IVF-ADC (config 4)
     ivf = None
+    ivf_quick = None
     if not args.skip_ivf:
         nt, nlist, nq_i, nprobe = args.ivf_n, 65536, 10000, 64
         coarse_h = mix.sample(nlist, datagen.SEED_DATA + 7)
@@ -408,6 +412,33 @@ def main():
             "note": "scan_kernel_ms covers both scan kernels (long lists, short lists); code bytes they pass = pairs x 8 B / pairs per work "
                     "item (an upper estimate of the sharing: items of a list with fewer probing queries are not full)"}
         ivf = (coarse_h, offsets_h, codes_i, cb_r.cpu().numpy(), q_i_h, probes.cpu().numpy(), d_i.cpu().numpy(), i_i.cpu().numpy(), nprobe)
+        # the same index with Quick ADC in the Scan step: the 8 bytes of a code read as 16 packed 4-bit indexes
+        cb_q_h = datagen.sampled_codebooks(mix, 16, 16) * np.float32(0.25)
+        cb_q = torch.from_numpy(cb_q_h).cuda()
+        times, kms = [], []
+        for _ in range(3):
+            sync()
+            ev[0].record()
+            d_k, i_k, probes_k = ctx.ivf_quick_adc_search(coarse, offsets, codes_i, None, cb_q, q_i, nprobe, args.ivf_quick_init,
+                                                          args.ivf_quick_kprime, args.topk, return_probes=True)
+            ev[1].record()
+            sync()
+            times.append(ev[0].elapsed_time(ev[1]))
+            kms.append(ctx.pq_last_scan_kernel_ms())
+        ms_k, k_k = float(np.median(times[1:])), float(np.mean(kms[1:]))
+        inf_k = ctx.pq_last_scan_info()
+        result["ivf_quick_adc_config4"] = {
+            "workload": "config 4's index with Quick ADC in the Scan step: N=%d packed 16x4 codes (the same 8 bytes per code) in %d "
+                        "Zipf-sized lists, %d queries in one call, nprobe %d, init %d, kprime %d, top-%d"
+                        % (nt, nlist, nq_i, nprobe, args.ivf_quick_init, args.ivf_quick_kprime, args.topk),
+            "ms_per_call": ms_k, "queries_per_s": nq_i / (ms_k * 1e-3), "code_query_pairs": scanned,
+            "value": scanned / (ms_k * 1e-3) / 1e9, "unit": "G codes/s",
+            "scan_kernel": inf_k["kernel"], "scan_kernel_ms": k_k, "queries_per_pass_over_a_list": inf_k["queries_per_pass"],
+            "passes_over_a_list_per_work_item": inf_k["passes"],
+            "note": "scan_kernel_ms covers the two integer scan kernels (work items of long and of short lists); every work item reads its "
+                    "codes twice (counting pass, collecting pass)"}
+        ivf_quick = (coarse_h, offsets_h, codes_i, cb_q_h, q_i_h, probes_k.cpu().numpy(), d_k.cpu().numpy(), i_k.cpu().numpy(), nprobe,
+                     args.ivf_quick_init, args.ivf_quick_kprime)
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.skip_cpu:
@@ -417,6 +448,8 @@ def main():
             result["config3_pq16x8_d960"]["cpu_baseline"] = cpu_baseline_config3(ctx, c3, args.topk)
         if ivf is not None:
             result["ivf_config4"]["cpu_baseline"] = cpu_baseline_ivf(ivf, min(args.ivf_cpu_queries, 10000), args.topk)
+        if ivf_quick is not None:
+            result["ivf_quick_adc_config4"]["cpu_baseline"] = cpu_baseline_ivf_quick(ivf_quick, min(args.ivf_cpu_queries // 2, 10000), args.topk)
     print(json.dumps(result))
 
 
@@ -493,6 +526,35 @@ def cpu_baseline_ivf(ivf, sample_q, topk):
     ok = bool(np.allclose(gd[:sample_q], od, rtol=1e-5, atol=0) and ids_agree(gi[:sample_q], oi))
     return {"value": pairs / dt / 1e9, "unit": "G codes/s", "cores": threads, "kind": "oracle",
             "sample": f"first {sample_q} of the 10000 queries on the lists the GPU probed ({pairs} code-query pairs, tables on residuals included), {dt:.1f} s wall",
+            "queries_per_s": sample_q / dt, "gpu_matches_oracle_on_sample": ok}
+
+
+def cpu_baseline_ivf_quick(ivf, sample_q, topk):
+    """The oracle's IVF search with Quick ADC for the first sample_q queries, on the lists the GPU probed; the GPU's
+    distances and ids must equal the oracle's exactly (integer stages, float sums rounded once on both sides)."""
+    from oracle import pq_oracle as orc
+    coarse_h, offsets_h, codes_dev, cb_h, q_h, probes, gd, gi, nprobe, init, kprime = ivf
+    pr = probes[:sample_q]
+    lists = np.unique(pr)
+    sizes = (offsets_h[lists + 1] - offsets_h[lists]).astype(np.int64)
+    sub_off = np.zeros(len(lists) + 1, np.int64)
+    np.cumsum(sizes, out=sub_off[1:])
+    sub_codes = np.empty((int(sub_off[-1]), codes_dev.shape[1]), np.uint8)
+    sub_ids = np.empty(int(sub_off[-1]), np.int64)
+    for j, l in enumerate(lists):
+        a, b = int(offsets_h[l]), int(offsets_h[l + 1])
+        sub_codes[sub_off[j]:sub_off[j + 1]] = codes_dev[a:b].cpu().numpy()
+        sub_ids[sub_off[j]:sub_off[j + 1]] = np.arange(a, b)
+    remap = np.searchsorted(lists, pr).astype(np.int32)
+    threads = orc.set_threads(0)
+    t0 = time.perf_counter()
+    od, oi = orc.ivf_quick_scan(q_h[:sample_q], coarse_h[lists], sub_off, sub_codes, sub_ids, cb_h, orc.CODES_U4_PACKED, remap, init,
+                                kprime, topk)
+    dt = time.perf_counter() - t0
+    pairs = int(sizes[remap].sum())
+    ok = bool(np.array_equal(gd[:sample_q], od) and np.array_equal(gi[:sample_q], oi))
+    return {"value": pairs / dt / 1e9, "unit": "G codes/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {sample_q} of the 10000 queries on the lists the GPU probed ({pairs} code-query pairs, tables, qmax, 8-bit tables and rerank included), {dt:.1f} s wall",
             "queries_per_s": sample_q / dt, "gpu_matches_oracle_on_sample": ok}
 
 

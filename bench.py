@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--skip-ivf", action="store_true")
     ap.add_argument("--ivf-n", type=int, default=1_000_000_000)
     ap.add_argument("--ivf-cpu-queries", type=int, default=100)
+    ap.add_argument("--skip-ivf-quick", action="store_true", help="no Quick ADC leg on config 4's index")
+    ap.add_argument("--ivf-quick-only", action="store_true", help="config 4's index searched with Quick ADC only")
     ap.add_argument("--ivf-quick-init", type=int, default=1024, help="codes scanned for the qmax bound of the Quick ADC IVF leg")
     ap.add_argument("--ivf-quick-kprime", type=int, default=128, help="candidates per (query, list) pair of the Quick ADC IVF leg")
     ap.add_argument("--encode", action="store_true", help="also time pq_encode (d=128 mixture vectors, 8x8 and 16x4 codebooks)")
@@ -389,34 +391,35 @@ def main():
         q_i_h = mix.sample(nq_i, datagen.SEED_QUERIES + 1)
         q_i = torch.from_numpy(q_i_h).cuda()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        times, kms = [], []
-        for _ in range(4):
-            sync()
-            ev[0].record()
-            d_i, i_i, probes = ctx.ivf_adc_search(coarse, offsets, codes_i, None, cb_r, U8, q_i, nprobe, args.topk, return_probes=True)
-            ev[1].record()
-            sync()
-            times.append(ev[0].elapsed_time(ev[1]))
-            kms.append(ctx.pq_last_scan_kernel_ms())
-        scanned = int(torch.from_numpy(sizes).cuda()[probes.long()].sum().item())
-        ms_i, k_i = float(np.median(times[1:])), float(np.mean(kms[1:]))
-        inf_i = ctx.pq_last_scan_info()
-        result["ivf_config4"] = {
-            "workload": "BASELINE config 4: N=%d uniform random 8-byte codes in %d Zipf-sized lists, %d queries in one call, nprobe %d, "
-                        "top-%d" % (nt, nlist, nq_i, nprobe, args.topk),
-            "ms_per_call": ms_i, "queries_per_s": nq_i / (ms_i * 1e-3), "code_query_pairs": scanned,
-            "value": scanned / (ms_i * 1e-3) / 1e9, "unit": "G codes/s",
-            "scan_kernel": inf_i["kernel"], "scan_kernel_ms": k_i, "queries_per_pass_over_a_list": inf_i["queries_per_pass"],
-            "scan_kernel_code_bytes_GB/s": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9,
-            "scan_kernel_frac_of_hbm_peak": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "note": "scan_kernel_ms covers both scan kernels (long lists, short lists); code bytes they pass = pairs x 8 B / pairs per work "
-                    "item (an upper estimate of the sharing: items of a list with fewer probing queries are not full)"}
-        ivf = (coarse_h, offsets_h, codes_i, cb_r.cpu().numpy(), q_i_h, probes.cpu().numpy(), d_i.cpu().numpy(), i_i.cpu().numpy(), nprobe)
+        if not args.ivf_quick_only:
+            times, kms = [], []
+            for _ in range(4):
+                sync()
+                ev[0].record()
+                d_i, i_i, probes = ctx.ivf_adc_search(coarse, offsets, codes_i, None, cb_r, U8, q_i, nprobe, args.topk, return_probes=True)
+                ev[1].record()
+                sync()
+                times.append(ev[0].elapsed_time(ev[1]))
+                kms.append(ctx.pq_last_scan_kernel_ms())
+            scanned = int(torch.from_numpy(sizes).cuda()[probes.long()].sum().item())
+            ms_i, k_i = float(np.median(times[1:])), float(np.mean(kms[1:]))
+            inf_i = ctx.pq_last_scan_info()
+            result["ivf_config4"] = {
+                "workload": "BASELINE config 4: N=%d uniform random 8-byte codes in %d Zipf-sized lists, %d queries in one call, nprobe %d, "
+                            "top-%d" % (nt, nlist, nq_i, nprobe, args.topk),
+                "ms_per_call": ms_i, "queries_per_s": nq_i / (ms_i * 1e-3), "code_query_pairs": scanned,
+                "value": scanned / (ms_i * 1e-3) / 1e9, "unit": "G codes/s",
+                "scan_kernel": inf_i["kernel"], "scan_kernel_ms": k_i, "queries_per_pass_over_a_list": inf_i["queries_per_pass"],
+                "scan_kernel_code_bytes_GB/s": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9,
+                "scan_kernel_frac_of_hbm_peak": scanned * 8.0 / inf_i["queries_per_pass"] / (k_i * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "note": "scan_kernel_ms covers both scan kernels (long lists, short lists); code bytes they pass = pairs x 8 B / pairs per work "
+                        "item (an upper estimate of the sharing: items of a list with fewer probing queries are not full)"}
+            ivf = (coarse_h, offsets_h, codes_i, cb_r.cpu().numpy(), q_i_h, probes.cpu().numpy(), d_i.cpu().numpy(), i_i.cpu().numpy(), nprobe)
         # the same index with Quick ADC in the Scan step: the 8 bytes of a code read as 16 packed 4-bit indexes
         cb_q_h = datagen.sampled_codebooks(mix, 16, 16) * np.float32(0.25)
         cb_q = torch.from_numpy(cb_q_h).cuda()
         times, kms = [], []
-        for _ in range(3):
+        for _ in range(0 if args.skip_ivf_quick else 3):
             sync()
             ev[0].record()
             d_k, i_k, probes_k = ctx.ivf_quick_adc_search(coarse, offsets, codes_i, None, cb_q, q_i, nprobe, args.ivf_quick_init,
@@ -425,20 +428,22 @@ def main():
             sync()
             times.append(ev[0].elapsed_time(ev[1]))
             kms.append(ctx.pq_last_scan_kernel_ms())
-        ms_k, k_k = float(np.median(times[1:])), float(np.mean(kms[1:]))
-        inf_k = ctx.pq_last_scan_info()
-        result["ivf_quick_adc_config4"] = {
-            "workload": "config 4's index with Quick ADC in the Scan step: N=%d packed 16x4 codes (the same 8 bytes per code) in %d "
-                        "Zipf-sized lists, %d queries in one call, nprobe %d, init %d, kprime %d, top-%d"
-                        % (nt, nlist, nq_i, nprobe, args.ivf_quick_init, args.ivf_quick_kprime, args.topk),
-            "ms_per_call": ms_k, "queries_per_s": nq_i / (ms_k * 1e-3), "code_query_pairs": scanned,
-            "value": scanned / (ms_k * 1e-3) / 1e9, "unit": "G codes/s",
-            "scan_kernel": inf_k["kernel"], "scan_kernel_ms": k_k, "queries_per_pass_over_a_list": inf_k["queries_per_pass"],
-            "passes_over_a_list_per_work_item": inf_k["passes"],
-            "note": "scan_kernel_ms covers the two integer scan kernels (work items of long and of short lists); every work item reads its "
-                    "codes twice (counting pass, collecting pass)"}
-        ivf_quick = (coarse_h, offsets_h, codes_i, cb_q_h, q_i_h, probes_k.cpu().numpy(), d_k.cpu().numpy(), i_k.cpu().numpy(), nprobe,
-                     args.ivf_quick_init, args.ivf_quick_kprime)
+        if not args.skip_ivf_quick:
+            scanned = int(torch.from_numpy(sizes).cuda()[probes_k.long()].sum().item())
+            ms_k, k_k = float(np.median(times[1:])), float(np.mean(kms[1:]))
+            inf_k = ctx.pq_last_scan_info()
+            result["ivf_quick_adc_config4"] = {
+                "workload": "config 4's index with Quick ADC in the Scan step: N=%d packed 16x4 codes (the same 8 bytes per code) in %d "
+                            "Zipf-sized lists, %d queries in one call, nprobe %d, init %d, kprime %d, top-%d"
+                            % (nt, nlist, nq_i, nprobe, args.ivf_quick_init, args.ivf_quick_kprime, args.topk),
+                "ms_per_call": ms_k, "queries_per_s": nq_i / (ms_k * 1e-3), "code_query_pairs": scanned,
+                "value": scanned / (ms_k * 1e-3) / 1e9, "unit": "G codes/s",
+                "scan_kernel": inf_k["kernel"], "scan_kernel_ms": k_k, "queries_per_pass_over_a_list": inf_k["queries_per_pass"],
+                "passes_over_a_list_per_work_item": inf_k["passes"],
+                "note": "scan_kernel_ms covers the two integer scan kernels (work items of long and of short lists); every work item reads its "
+                        "codes twice (counting pass, collecting pass)"}
+            ivf_quick = (coarse_h, offsets_h, codes_i, cb_q_h, q_i_h, probes_k.cpu().numpy(), d_k.cpu().numpy(), i_k.cpu().numpy(), nprobe,
+                         args.ivf_quick_init, args.ivf_quick_kprime)
 
     # ---------------------------------------------------------------- oracle on the host cores
     if not args.skip_cpu:

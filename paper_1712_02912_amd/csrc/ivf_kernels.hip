@@ -24,6 +24,11 @@ namespace pq {
 
 constexpr int IVF_MAX_CHUNKS = 16;            // chunks per list (bounds the lists a query can own)
 constexpr int64_t IVF_CHUNK_TARGET = 1 << 18; // rows per chunk aimed at for long lists
+// Quick ADC: chunks of at most 2^20 rows, as many as the list needs.  The lists of a query are distinct, so a query owns
+// at most nprobe + ntotal / 2^20 chunks whatever it probes: about as many result lists as the cap above allows, and
+// no work item is longer than 2^20 rows (an item costs the same whatever the number of its pairs, and the call waits
+// for the longest one).
+constexpr int64_t IVF_QUICK_CHUNK_ROWS = 1 << 20;
 constexpr float IVF_PRUNE_RANGE = 3500.f;      // table units between the sum of a pair's minima and the query's first bound
 constexpr int IVF_QB_PLAIN = 4;               // queries per work item: plain float loop
 constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bounds
@@ -174,8 +179,9 @@ __global__ void ivf_count_pairs_kernel(const int32_t *__restrict__ probes, int n
     if (p < npairs) atomicAdd(&np[probes[p]], 1u);
 }
 
-__device__ __forceinline__ int ivf_chunks_of(int64_t size) {
+__device__ __forceinline__ int ivf_chunks_of(int64_t size, int64_t uncapped_rows) {
     if (size <= 0) return 0;
+    if (uncapped_rows > 0) return (int)((size + uncapped_rows - 1) / uncapped_rows);
     int64_t nc = (size + IVF_CHUNK_TARGET - 1) / IVF_CHUNK_TARGET;
     return (int)(nc < 1 ? 1 : (nc > IVF_MAX_CHUNKS ? IVF_MAX_CHUNKS : nc));
 }
@@ -209,7 +215,8 @@ __device__ __forceinline__ uint32_t block_scan_round(uint32_t v, uint32_t *wave_
 __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restrict__ np,
                                                         const int64_t *__restrict__ list_offsets, int nlist,
                                                         uint32_t *pair_off, uint32_t *nc_out, uint32_t *item_off,
-                                                        uint32_t *nitems_dev, uint32_t qb, int64_t short_max, uint32_t short_qs) {
+                                                        uint32_t *nitems_dev, uint32_t qb, int64_t short_max, uint32_t short_qs,
+                                                        int64_t uncapped_rows) {
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t cls_items[64], cls_base[64], cls_cursor[64];   // 32 size classes of the long lists, 32 of the short ones
     __shared__ uint32_t carry;
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(1024) void ivf_plan_kernel(const uint32_t *__restri
         if (l < nlist) {
             pair_off[l] = before;
             const int64_t size = list_offsets[l + 1] - list_offsets[l];
-            const int nc = v > 0 ? ivf_chunks_of(size) : 0;
+            const int nc = v > 0 ? ivf_chunks_of(size, uncapped_rows) : 0;
             nc_out[l] = (uint32_t)nc;
             const bool is_short = size < short_max;
             const uint32_t items = is_short ? (nc > 0 ? (v + short_qs - 1) / short_qs : 0u) : ((v + qb - 1) / qb) * (uint32_t)nc;
@@ -627,8 +634,13 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     // queries per batch: keeps the per-query part of the workspace (coarse distances, residuals and
     // tables of the nprobe pairs, upper bound of their result lists, histogram) within PQ_IVF_WS_GIB
     // GiB (default 24); the more queries share a batch, the more of them share a pass over a list
-    const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 +
-                             (size_t)IVF_MAX_CHUNKS * kpad * 8 + 64) + (size_t)HIST_BINS * 4 + 64;
+    // result lists a query can own: one per chunk of each of its lists
+    int64_t quick_rows = opt_int(ctx, PQ_OPT_IVF_QUICK_CHUNK_ROWS, (int)IVF_QUICK_CHUNK_ROWS);
+    if (quick_rows < 1024) quick_rows = 1024;
+    if (quick_rows > (1 << 24)) quick_rows = 1 << 24;
+    const size_t lists_per_query = quick ? (size_t)nprobe + (size_t)(L->ntotal / quick_rows) + 1 : (size_t)nprobe * IVF_MAX_CHUNKS;
+    const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 + 64) +
+                             lists_per_query * kpad * 8 + (size_t)HIST_BINS * 4 + 64;
     int ws_gib = opt_int(ctx, PQ_OPT_IVF_WS_GIB, 24);
     if (ws_gib < 1) ws_gib = 1;
     if (ws_gib > 128) ws_gib = 128;
@@ -636,8 +648,10 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     if (qbatch < 1) qbatch = 1;
     if (qbatch > nq) qbatch = nq;
     const size_t npairs_max = (size_t)qbatch * nprobe;
-    const size_t max_items = (npairs_max / item_qb + (size_t)nlist + 1) * IVF_MAX_CHUNKS;
-    const size_t max_lists = npairs_max * IVF_MAX_CHUNKS;
+    const size_t max_lists = (size_t)qbatch * lists_per_query;
+    // items of a list: (groups of its pairs) x chunks <= (pairs / item_qb + 1) x chunks
+    const size_t max_items = quick ? max_lists / item_qb + (size_t)nlist + (size_t)(L->ntotal / quick_rows) + 1
+                                   : (npairs_max / item_qb + (size_t)nlist + 1) * IVF_MAX_CHUNKS;
 
     // workspace carving (all offsets 256-byte aligned)
     size_t off = 0;
@@ -759,7 +773,8 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         ivf_zero_kernel<<<256, 256, 0, g>>>(np, (size_t)nlist);
         ivf_zero_kernel<<<256, 256, 0, g>>>(fill, (size_t)nlist);
         ivf_count_pairs_kernel<<<(npairs + 255) / 256, 256, 0, g>>>(probes, npairs, np);
-        ivf_plan_kernel<<<1, 1024, 0, g>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb, short_max, (uint32_t)IVF_SHORT_QS);
+        ivf_plan_kernel<<<1, 1024, 0, g>>>(np, L->list_offsets, nlist, pair_off, nc, item_off, nitems_dev, item_qb, short_max, (uint32_t)IVF_SHORT_QS,
+                                           quick ? quick_rows : (int64_t)0);
         ivf_fill_pairs_kernel<<<(npairs + 255) / 256, 256, 0, g>>>(probes, npairs, pair_off, fill, pairs_by_list);
         ivf_fill_items_kernel<<<(nlist + 255) / 256, 256, 0, g>>>(pair_off, nc, item_off, L->list_offsets, nlist,
                                                                   rows_per_16b, item_qb, items, short_max, pairs_by_list, short_items);

@@ -367,14 +367,14 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
 
 // ------------------------------------------------------------------------------------------
 // Rerank: one block per (query, list) pair.  The kprime smallest integer keys over the pair's result lists (one list
-// per chunk of the inverted list) are its candidates; their float distances replace them in the pair's first list,
+// per chunk of the inverted list, any number of them) are its candidates; their float distances replace them in the pair's first list,
 // in ascending order, the other lists are emptied, and the pair's topk-th key (if it has one) bounds the query's result.
 __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__restrict__ codes, const float *__restrict__ luts,
                                                                const int32_t *__restrict__ probes, const uint32_t *__restrict__ nc_arr,
                                                                const uint32_t *__restrict__ pair_out, int nprobe, int kprime,
                                                                int topk, uint64_t *partial, unsigned long long *tau_key) {
     __shared__ float tab[256];
-    __shared__ uint64_t keys[2048];
+    __shared__ uint64_t keys[2 * QK_KP];
     const int pair = blockIdx.x, tid = threadIdx.x;
     const int nc = (int)nc_arr[probes[pair]];
     uint64_t *lists = partial + (size_t)pair_out[pair] * QK_KP;
@@ -383,11 +383,12 @@ __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__
     uint64_t key;
     if (nc <= 1) {
         key = nc == 1 ? lists[tid] : KEY_EMPTY;
-    } else {
-        int n2 = 256;
-        while (n2 < nc * QK_KP) n2 <<= 1;
-        for (int i = tid; i < n2; i += 128) keys[i] = i < nc * QK_KP ? lists[i] : KEY_EMPTY;
-        block_bitonic_sort(keys, n2);
+    } else {   // a list of several chunks: the smallest keys so far in keys[0 .. 127], the next chunk's list sorted in beside them
+        keys[tid] = lists[tid];
+        for (int c = 1; c < nc; ++c) {
+            keys[QK_KP + tid] = lists[(size_t)c * QK_KP + tid];
+            block_bitonic_sort(keys, 2 * QK_KP);
+        }
         key = tid < kprime ? keys[tid] : KEY_EMPTY;
         __syncthreads();
     }
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__
     keys[tid] = fkey;
     block_bitonic_sort(keys, 128);
     if (nc >= 1) lists[tid] = keys[tid];
-    for (int i = 128 + tid; i < nc * QK_KP; i += 128) lists[i] = KEY_EMPTY;
+    for (size_t i = 128 + tid; i < (size_t)nc * QK_KP; i += 128) lists[i] = KEY_EMPTY;
     if (tid == 0 && keys[topk - 1] != KEY_EMPTY) atomicMin(&tau_key[pair / nprobe], (unsigned long long)keys[topk - 1]);
 }
 

@@ -10,7 +10,7 @@
 // Tuning and test switches (pq_set_option).  PQ_OPT_UNSET = the kernel's own default.
 enum pq_option_id {
     PQ_OPT_SCAN_PRUNE = 0, PQ_OPT_SCAN_Q8, PQ_OPT_SCAN_FORCE_GENERAL, PQ_OPT_SCAN_BLOCKS, PQ_OPT_SCAN_ITEMS_PER_BLOCK,
-    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_IVF_COARSE_F32, PQ_OPT_COUNT
+    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_IVF_COARSE_F32, PQ_OPT_IVF_QUICK_CHUNK_ROWS, PQ_OPT_COUNT
 };
 constexpr int PQ_OPT_UNSET = -2147483647 - 1;
 

@@ -365,8 +365,12 @@ def test_ivf_quick_encoded_small(ctx):
     run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 8, 500, 64, 50)
 
 
-def test_ivf_quick_long_lists_in_chunks_short_and_empty_lists(ctx):
-    """One list long enough to be cut into chunks, lists shorter than kprime, empty lists, odd list boundaries."""
+@pytest.mark.parametrize("chunk_rows", [None, 4096, 100_000])
+def test_ivf_quick_long_lists_in_chunks_short_and_empty_lists(ctx, opts, chunk_rows):
+    """Lists cut into chunks (the longest into 171 with 4096 rows per chunk: their candidates are merged per pair),
+    lists shorter than kprime, empty lists, odd list boundaries."""
+    if chunk_rows:
+        opts.set("ivf_quick_chunk_rows", chunk_rows)
     sizes = [700_001, 90_003, 7, 0, 1, 33_333, 0, 129, 128, 127] + [1000 + 37 * i for i in range(14)]
     mix, coarse, cb, packed, _, offsets = make_index_u4(0, 32, 24, seed=53, sizes=sizes)
     queries = mix.sample(9, 97)

@@ -87,7 +87,7 @@ const char *pq_version(void);
  *   ivf_short_max (16384)     inverted lists of fewer codes take the kernel for short lists (0: none)
  *   ivf_coarse_f32 (1)        0: Index step of ivf_adc_search from exact distances to every list (default: lists
  *                             ranked by fp32 matrix-core distances, the nearest measured exactly; same lists)
- *   ivf_quick_chunk_rows (1048576)  ivf_quick_adc_search: rows per work item at most (1024 ... 2^24); a list longer than
+ *   ivf_quick_chunk_rows (1048576)  ivf_quick_adc_search: rows per work item at most (1024 ... 2^20); a list longer than
  *                             this is scanned in chunks, and a query's result lists (one per chunk of each of its
  *                             lists, at most nprobe + ntotal / this value) are part of the workspace */
 int pq_set_option(pq_ctx *ctx, const char *name, int value);

@@ -637,7 +637,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     // result lists a query can own: one per chunk of each of its lists
     int64_t quick_rows = opt_int(ctx, PQ_OPT_IVF_QUICK_CHUNK_ROWS, (int)IVF_QUICK_CHUNK_ROWS);
     if (quick_rows < 1024) quick_rows = 1024;
-    if (quick_rows > (1 << 24)) quick_rows = 1 << 24;
+    if (quick_rows > (1 << 20)) quick_rows = 1 << 20;
     const size_t lists_per_query = quick ? (size_t)nprobe + (size_t)(L->ntotal / quick_rows) + 1 : (size_t)nprobe * IVF_MAX_CHUNKS;
     const size_t per_query = (size_t)nlist * 4 + (size_t)nprobe * ((size_t)m * k * 4 + (size_t)d * 4 + 64) +
                              lists_per_query * kpad * 8 + (size_t)HIST_BINS * 4 + 64;
@@ -694,6 +694,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_qmaxp = take(quick ? npairs_max * 4 : 0);
     const size_t o_qluts = take(quick ? npairs_max * (size_t)m * k : 0);
     const size_t o_tauq = take(quick ? (size_t)qbatch * 8 : 0);
+    const size_t o_qrows = take(quick ? ivf_quick_saved_bytes(ctx, quick_rows) : 0);
     int rc = ws_reserve(ctx, off);
     if (rc) return rc;
     if (!ctx->aux_stream) {   // second stream of the context and the two events that fork to it and join from it
@@ -797,7 +798,7 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
             unsigned long long *tau_q = (unsigned long long *)(ws + o_tauq);
             rc = launch_ivf_quick(ctx, L->codes, L->list_offsets, probes, luts, nqb, nprobe, init, kprime, topk,
                                   (float *)(ws + o_qmaxp), ws + o_qluts, items, nitems_dev, pairs_by_list, pair_out, nc,
-                                  partial, tau_q);
+                                  partial, tau_q, (uint32_t *)(ws + o_qrows), quick_rows);
             if (rc) return rc;
             rc = launch_merge_filtered(ctx, partial, qlist_off, 0, 0, 1, tau_q, kpad, nqb, topk, L->ids, false,
                                        out_dist + (size_t)q0 * topk, out_ids + (size_t)q0 * topk);

@@ -126,12 +126,15 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                                                                        const uint32_t *__restrict__ nitems_dev,
                                                                        const int32_t *__restrict__ pairs_by_list,
                                                                        const uint32_t *__restrict__ pair_out, int kprime,
-                                                                       uint64_t *partial) {
+                                                                       uint64_t *partial, uint32_t *saved_rows, int saved_cap) {
     constexpr int QK_THREADS = QK_WAVES * 64;
     extern __shared__ __align__(16) unsigned char quick_smem[];
     QuickSmem<QK_WAVES> &sm = *reinterpret_cast<QuickSmem<QK_WAVES> *>(quick_smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nitems = (int)*nitems_dev;
+    // rows of the item that the counting pass found at or below some pair's cap of the moment, per wave in the order
+    // the wave met them (ascending): the only rows the collecting pass has to look at again
+    uint32_t *my_saved = saved_rows + ((size_t)blockIdx.x * QK_WAVES + wave) * (size_t)saved_cap;
     for (int item = (int)blockIdx.x; item < nitems; item += (int)gridDim.x) {
         const IvfItem it = items[item];
         if (((int)it.ncodes >= QK_LONG_MIN) != LONG) continue;   // (uniform)
@@ -205,8 +208,11 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
         // kprime sums lie in that range: then the next 511 values are counted in another pass).  The codes are taken
         // in segments of 1024, 4096, 16384, ... rows; after each segment the kprime-th smallest sum so far becomes the
         // pair's cap, and greater sums are no longer counted: the final T cannot exceed it.
+        int scnt = 0;            // rows saved by this wave (uniform among the lanes still in the loop; lane 0 stays longest)
+        bool use_saved = nvalid > kprime;
         if (nvalid > kprime) {
-            for (;;) {
+            for (int attempt = 0;; ++attempt) {
+                if (attempt > 0) use_saved = false;   // (rows of a second counting pass would be saved twice: all rows are looked at again)
                 for (int i = tid; i < QK_QS * QK_BINS; i += QK_THREADS) (&sm.hist[0][0])[i] = 0u;
                 if (tid < QK_QS) {
                     sm.cap[tid] = sm.base[tid] + (uint32_t)(QK_BINS - 2);
@@ -227,9 +233,17 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                         capv[s] = sm.cap[s];
                         if (open[s]) capplus[s >> 1] |= (capv[s] + 1u) << (16 * (s & 1));
                     }
-                    for_codes(seg_begin, seg_end, [&](int, const uint2 c, bool valid) {
+                    for_codes(seg_begin, seg_end, [&](int i, const uint2 c, bool valid) {
                         uint32_t acc[4];
-                        if (!sums_below(c, valid, capplus, acc)) return;
+                        const bool pass = sums_below(c, valid, capplus, acc);
+                        const uint64_t mask = __ballot(pass);
+                        if (mask == 0ull) return;
+                        {
+                            const int pos = scnt + mask_prefix(mask);
+                            if (pass && pos < saved_cap) my_saved[pos] = (uint32_t)i;
+                            scnt += __popcll(mask);
+                        }
+                        if (!pass) return;
 #pragma unroll
                         for (int s = 0; s < QK_QS; ++s) {
                             const uint32_t sum = (acc[s >> 1] >> (16 * (s & 1))) & 0xffffu;
@@ -297,7 +311,25 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                 need[s] = (s < nslots && tval[s] < 0xffffu) ? kprime - (int)sm.below[s] : 0;
                 tcnt[s] = 0;
             }
-            for_codes(skip, ncodes, [&](int i, const uint2 c, bool valid) {
+            scnt = __builtin_amdgcn_readfirstlane(scnt);
+            if (scnt > saved_cap) use_saved = false;   // (cannot happen: a wave saves at most the rows it meets)
+            use_saved = __syncthreads_or(use_saved ? 0 : 1) == 0;   // (the same decision in every wave)
+            // f(row, code, valid) for the rows to look at: the wave's saved rows in their order, or every row of the item
+            auto for_rows = [&](auto &&f) {
+                if (!use_saved) { for_codes(skip, ncodes, f); return; }
+                for (int e0 = lane; e0 < scnt; e0 += QK_BATCH * 64) {
+                    uint32_t r[QK_BATCH];
+                    uint2 c[QK_BATCH];
+#pragma unroll
+                    for (int u = 0; u < QK_BATCH; ++u) r[u] = e0 + u * 64 < scnt ? my_saved[e0 + u * 64] : 0u;
+#pragma unroll
+                    for (int u = 0; u < QK_BATCH; ++u)
+                        c[u] = e0 + u * 64 < scnt ? *reinterpret_cast<const uint2 *>(base_ptr + (size_t)r[u] * 8) : make_uint2(0u, 0u);
+#pragma unroll
+                    for (int u = 0; u < QK_BATCH; ++u) f((int)r[u], c[u], e0 + u * 64 < scnt);
+                }
+            };
+            for_rows([&](int i, const uint2 c, bool valid) {
                 uint32_t acc[4];
                 const bool some = sums_below(c, valid, tplus, acc);
                 if (__ballot(some) == 0ull) return;
@@ -407,10 +439,18 @@ __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__
 }
 
 // ------------------------------------------------------------------------------------------
+// Rows a wave can meet in a work item of at most `rows` rows (+ the rows of alignment in front) scanned by `waves` waves.
+static int ivf_quick_saved_cap(int64_t rows, int waves) { return (int)(((rows + 16) / (waves * 64) + 2) * 64); }
+
+size_t ivf_quick_saved_bytes(const pq_ctx *ctx, int64_t max_item_rows) {
+    return ((size_t)ctx->num_cu * 16 * ivf_quick_saved_cap(max_item_rows, 16) + (size_t)ctx->num_cu * 3 * 4 * ivf_quick_saved_cap(QK_LONG_MIN, 4)) * 4;
+}
+
 int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
                      const float *luts, int nq, int nprobe, int init, int kprime, int topk, float *qmax_pair,
                      uint8_t *qluts, const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
-                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key) {
+                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key,
+                     uint32_t *saved_rows, int64_t max_item_rows) {
     if (kprime < 1 || kprime > QK_KP || topk < 1 || topk > QK_KP || init < 1 || init > QK_INIT_MAX)
         return fail(ctx, PQ_EUNSUPPORTED, "ivf quick adc: kprime and topk must be 1..%d, init 1..%d", QK_KP, QK_INIT_MAX);
     hipStream_t s = ctx->stream;
@@ -437,11 +477,13 @@ int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offs
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(short_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)sizeof(QuickSmem<4>)));
         // the long items first (longest lists come first in the table of items), then the many short ones
+        const int cap_long = ivf_quick_saved_cap(max_item_rows, 16), cap_short = ivf_quick_saved_cap(QK_LONG_MIN, 4);
         long_kernel<<<ctx->num_cu, 16 * 64, sizeof(QuickSmem<16>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
-                                                                       kprime, partial);
+                                                                       kprime, partial, saved_rows, cap_long);
         PQ_HIP(ctx, hipGetLastError());
         short_kernel<<<ctx->num_cu * 3, 4 * 64, sizeof(QuickSmem<4>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
-                                                                          kprime, partial);
+                                                                          kprime, partial,
+                                                                          saved_rows + (size_t)ctx->num_cu * 16 * cap_long, cap_short);
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) {

@@ -38,7 +38,11 @@ struct IvfItem {
 int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
                      const float *luts, int nq, int nprobe, int init, int kprime, int topk, float *qmax_pair,
                      uint8_t *qluts, const IvfItem *items, const uint32_t *nitems_dev, const int32_t *pairs_by_list,
-                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key);
+                     const uint32_t *pair_out, const uint32_t *nc_arr, uint64_t *partial, unsigned long long *tau_key,
+                     uint32_t *saved_rows, int64_t max_item_rows);
+// bytes of `saved_rows` (rows that the counting pass of a work item hands to its collecting pass, per wave) when no
+// work item has more than max_item_rows rows
+size_t ivf_quick_saved_bytes(const pq_ctx *ctx, int64_t max_item_rows);
 
 // One work item of the scan of short inverted lists (ivf_short_kernels.hip): a whole list for up to
 // IVF_SHORT_QS of the (query, list) pairs that probe it.  32 bytes.

@@ -206,7 +206,7 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
 
         // ---- counting passes: T of every pair.  Sums of base .. base + 510 are counted (one pass unless fewer than
         // kprime sums lie in that range: then the next 511 values are counted in another pass).  The codes are taken
-        // in segments of 1024, 4096, 16384, ... rows; after each segment the kprime-th smallest sum so far becomes the
+        // in segments of 1024, 2048, 4096, ... rows (four times that in blocks of 16 waves); after each segment the kprime-th smallest sum so far becomes the
         // pair's cap, and greater sums are no longer counted: the final T cannot exceed it.
         int scnt = 0;            // rows saved by this wave (uniform among the lanes still in the loop; lane 0 stays longest)
         bool use_saved = nvalid > kprime;
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                 bool open[QK_QS];
 #pragma unroll
                 for (int s = 0; s < QK_QS; ++s) { lo[s] = sm.base[s]; open[s] = sm.found[s] == 0; }
-                for (int seg_begin = skip, seg_len = QK_BATCH * QK_THREADS; seg_begin < ncodes; seg_len *= 4) {
+                for (int seg_begin = skip, seg_len = QK_BATCH * QK_THREADS; seg_begin < ncodes; seg_len *= 2) {
                     const int seg_end = ncodes - seg_begin < seg_len ? ncodes : seg_begin + seg_len;
                     uint32_t capv[QK_QS], capplus[4] = {0u, 0u, 0u, 0u};   // cap + 1 per pair (0: pair not counted)
 #pragma unroll

@@ -400,6 +400,20 @@ def test_ivf_quick_many_queries_several_groups_per_list(ctx):
     run_ivf_quick(ctx, queries, coarse, offsets, packed, order, cb, 5, 800, 64, 40)
 
 
+def test_ivf_quick_queries_served_in_several_batches(ctx, opts):
+    """A 1 GiB workspace holds about 5000 queries of this shape: 12 000 queries take three batches."""
+    opts.set("ivf_ws_gib", 1)
+    r = np.random.default_rng(69)
+    d, nlist, n, nq = 32, 16384, 200_000, 12_000
+    sizes = datagen.zipf_list_sizes(n, nlist)
+    offsets = datagen.offsets_from_sizes(sizes)
+    packed = r.integers(0, 256, (n, 8), dtype=np.uint8)
+    coarse = (r.random((nlist, d)) * 100).astype(np.float32)
+    cb = (r.random((16, 16, d // 16)) * 20 - 10).astype(np.float32)
+    queries = (r.random((nq, d)) * 100).astype(np.float32)
+    run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 64, 500, 16, 20)
+
+
 def test_ivf_quick_rejects_what_is_not_covered(ctx):
     mix, coarse, cb, packed, order, offsets = make_index_u4(3000, 32, 6, seed=63)
     queries = mix.sample(3, 94)

@@ -414,6 +414,16 @@ def test_ivf_quick_queries_served_in_several_batches(ctx, opts):
     run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 64, 500, 16, 20)
 
 
+def test_ivf_quick_empty_index_and_fewer_candidates_than_topk(ctx):
+    mix, coarse, cb, packed, _, offsets = make_index_u4(0, 32, 6, seed=65, sizes=[3, 0, 2, 1, 0, 40])
+    queries = mix.sample(4, 93)
+    gd, gi = run_ivf_quick(ctx, queries, coarse, offsets, packed, None, cb, 6, 100, 5, 20)
+    assert np.all(gi[:, 11:] == -1) and np.all(np.isinf(gd[:, 11:]))      # 3 + 2 + 1 + min(5, 40) candidates
+    empty = np.zeros_like(offsets)
+    gd, gi = run_ivf_quick(ctx, queries, coarse, empty, packed[:0], None, cb, 3, 100, 5, 20)
+    assert np.all(gi == -1) and np.all(np.isinf(gd))
+
+
 def test_ivf_quick_rejects_what_is_not_covered(ctx):
     mix, coarse, cb, packed, order, offsets = make_index_u4(3000, 32, 6, seed=63)
     queries = mix.sample(3, 94)

@@ -23,6 +23,7 @@
 // below T (fewer than kprime) and, in row order, those equal to T.  Every float sum of this file is formed in
 // double in table order and rounded once, so that the bound, the 8-bit tables, the candidates and the distances are
 // those of the plain definition bit for bit.
+#include <type_traits>
 #include "pq_internal.h"
 #include "scan_common.h"
 #include "topk_device.h"
@@ -94,12 +95,12 @@ __global__ __launch_bounds__(256) void ivf_quick_qmax_kernel(const uint8_t *__re
 }
 
 // ------------------------------------------------------------------------------------------
-template <int QK_WAVES>
+template <int QK_WAVES, typename TieRow>
 struct __align__(16) QuickSmem {
     uint4 tab[256];                              // slot j * 16 + i: the 8-bit entries (j, i) of the 8 pairs as 16-bit values
     uint32_t hist[QK_QS][QK_BINS];
     unsigned long long sure[QK_QS][QK_KP];       // keys below the pair's T (fewer than kprime)
-    uint32_t tie[QK_WAVES][QK_QS][QK_KP];        // rows with sum T, per wave in ascending order
+    TieRow tie[QK_WAVES][QK_QS][QK_KP];          // rows (within the item) with sum T, per wave in ascending order
     int sure_cnt[QK_QS];
     int tie_cnt[QK_WAVES][QK_QS];
     uint32_t tstar[QK_QS];                       // T: the kprime-th smallest sum (0xffff: every code is a candidate)
@@ -113,14 +114,18 @@ struct __align__(16) QuickSmem {
     uint32_t out_idx[QK_QS];
     int pending;                                 // pairs whose T is not known yet
 };
-static_assert(sizeof(QuickSmem<4>) <= 53 * 1024, "three blocks of 4 waves share the 160 KB of a compute unit");
-static_assert(sizeof(QuickSmem<16>) <= 160 * 1024, "one block of 16 waves per compute unit");
+// (items of the blocks of 4 waves have fewer than QK_LONG_MIN = 2^15 rows: 16 bits hold a row within the item)
+typedef QuickSmem<4, uint16_t> QuickSmemShort;
+typedef QuickSmem<16, uint32_t> QuickSmemLong;
+static_assert(QK_LONG_MIN <= 65536, "rows of short items fit 16 bits");
+static_assert(sizeof(QuickSmemShort) <= 40 * 1024, "four blocks of 4 waves share the 160 KB of a compute unit");
+static_assert(sizeof(QuickSmemLong) <= 160 * 1024, "one block of 16 waves per compute unit");
 
 // Blocks of QK_WAVES waves.  LONG: the kernel takes the work items of QK_LONG_MIN rows and more (16 waves, one block
 // per compute unit: the longest item of a skewed index is what the call waits for), else the shorter ones (4 waves,
-// three blocks per compute unit).  Items are dealt in a stride of the grid; an item of the other kind is passed over.
+// four blocks per compute unit).  Items are dealt in a stride of the grid; an item of the other kind is passed over.
 template <int QK_WAVES, bool LONG>
-__global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
+__global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 4) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
                                                                        const uint8_t *__restrict__ qluts,
                                                                        const IvfItem *__restrict__ items,
                                                                        const uint32_t *__restrict__ nitems_dev,
@@ -129,7 +134,8 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                                                                        uint64_t *partial, uint32_t *saved_rows, int saved_cap) {
     constexpr int QK_THREADS = QK_WAVES * 64;
     extern __shared__ __align__(16) unsigned char quick_smem[];
-    QuickSmem<QK_WAVES> &sm = *reinterpret_cast<QuickSmem<QK_WAVES> *>(quick_smem);
+    typedef typename std::conditional<LONG, uint32_t, uint16_t>::type TieRow;
+    QuickSmem<QK_WAVES, TieRow> &sm = *reinterpret_cast<QuickSmem<QK_WAVES, TieRow> *>(quick_smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nitems = (int)*nitems_dev;
     // rows of the item that the counting pass found at or below some pair's cap of the moment, per wave in the order
@@ -345,7 +351,7 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                     const uint64_t mask = __ballot(at_t);
                     if (mask != 0ull) {
                         const int pos = tcnt[s] + mask_prefix(mask);
-                        if (at_t && pos < need[s]) sm.tie[wave][s][pos] = row0 + (uint32_t)i;
+                        if (at_t && pos < need[s]) sm.tie[wave][s][pos] = (TieRow)i;
                         tcnt[s] += __popcll(mask);
                         if (tcnt[s] > need[s]) tcnt[s] = need[s];   // (later rows of this wave are greater: not needed)
                     }
@@ -374,7 +380,7 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
             for (int e = tid; e < QK_WAVES * QK_KP; e += QK_THREADS) {
                 const int w = e / QK_KP, idx = e % QK_KP;
                 if (idx >= sm.tie_cnt[w][s]) continue;
-                const uint32_t row = sm.tie[w][s][idx];
+                const uint32_t row = (uint32_t)sm.tie[w][s][idx];
                 int rank = idx;
 #pragma unroll
                 for (int w2 = 0; w2 < QK_WAVES; ++w2) {
@@ -382,11 +388,11 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 3) void ivf_quick_scan_ke
                     int lo = 0, hi = sm.tie_cnt[w2][s];   // rows of w2 below `row`
                     while (lo < hi) {
                         const int mid = (lo + hi) >> 1;
-                        if (sm.tie[w2][s][mid] < row) lo = mid + 1; else hi = mid;
+                        if ((uint32_t)sm.tie[w2][s][mid] < row) lo = mid + 1; else hi = mid;
                     }
                     rank += lo;
                 }
-                if (rank < need) sm.sure[s][c + rank] = ((unsigned long long)t << 32) | row;
+                if (rank < need) sm.sure[s][c + rank] = ((unsigned long long)t << 32) | (row0 + row);
             }
         }
         __syncthreads();
@@ -443,7 +449,7 @@ __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__
 static int ivf_quick_saved_cap(int64_t rows, int waves) { return (int)(((rows + 16) / (waves * 64) + 2) * 64); }
 
 size_t ivf_quick_saved_bytes(const pq_ctx *ctx, int64_t max_item_rows) {
-    return ((size_t)ctx->num_cu * 16 * ivf_quick_saved_cap(max_item_rows, 16) + (size_t)ctx->num_cu * 3 * 4 * ivf_quick_saved_cap(QK_LONG_MIN, 4)) * 4;
+    return ((size_t)ctx->num_cu * 16 * ivf_quick_saved_cap(max_item_rows, 16) + (size_t)ctx->num_cu * 4 * 4 * ivf_quick_saved_cap(QK_LONG_MIN, 4)) * 4;
 }
 
 int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
@@ -473,15 +479,15 @@ int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offs
         auto long_kernel = ivf_quick_scan_kernel<16, true>;
         auto short_kernel = ivf_quick_scan_kernel<4, false>;
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(long_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)sizeof(QuickSmem<16>)));
+                                        (int)sizeof(QuickSmemLong)));
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(short_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)sizeof(QuickSmem<4>)));
+                                        (int)sizeof(QuickSmemShort)));
         // the long items first (longest lists come first in the table of items), then the many short ones
         const int cap_long = ivf_quick_saved_cap(max_item_rows, 16), cap_short = ivf_quick_saved_cap(QK_LONG_MIN, 4);
-        long_kernel<<<ctx->num_cu, 16 * 64, sizeof(QuickSmem<16>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+        long_kernel<<<ctx->num_cu, 16 * 64, sizeof(QuickSmemLong), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
                                                                        kprime, partial, saved_rows, cap_long);
         PQ_HIP(ctx, hipGetLastError());
-        short_kernel<<<ctx->num_cu * 3, 4 * 64, sizeof(QuickSmem<4>), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+        short_kernel<<<ctx->num_cu * 4, 4 * 64, sizeof(QuickSmemShort), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
                                                                           kprime, partial,
                                                                           saved_rows + (size_t)ctx->num_cu * 16 * cap_long, cap_short);
         PQ_HIP(ctx, hipGetLastError());

@@ -31,7 +31,7 @@
 namespace pq {
 
 constexpr int QK_QS = 8;          // (query, list) pairs per work item
-constexpr int QK_LONG_MIN = 32768;   // work items of this many rows and more take the blocks of 16 waves
+constexpr int QK_LONG_MIN = 65536;   // work items of this many rows and more take the blocks of 16 waves
 constexpr int QK_BINS = 512;      // sums counted per pass: base .. base + 510, and one bin for everything above
 constexpr int QK_KP = 128;        // kprime at most (the length of a result list)
 constexpr int QK_BATCH = 4;       // codes of a thread on their way at a time
@@ -114,7 +114,7 @@ struct __align__(16) QuickSmem {
     uint32_t out_idx[QK_QS];
     int pending;                                 // pairs whose T is not known yet
 };
-// (items of the blocks of 4 waves have fewer than QK_LONG_MIN = 2^15 rows: 16 bits hold a row within the item)
+// (items of the blocks of 4 waves have fewer than QK_LONG_MIN = 2^16 rows: 16 bits hold a row within the item)
 typedef QuickSmem<4, uint16_t> QuickSmemShort;
 typedef QuickSmem<16, uint32_t> QuickSmemLong;
 static_assert(QK_LONG_MIN <= 65536, "rows of short items fit 16 bits");

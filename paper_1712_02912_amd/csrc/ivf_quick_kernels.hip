@@ -31,7 +31,7 @@
 namespace pq {
 
 constexpr int QK_QS = 8;          // (query, list) pairs per work item
-constexpr int QK_LONG_MIN = 65536;   // work items of this many rows and more take the blocks of 16 waves
+constexpr int QK_LONG_MIN = 65536;   // work items of this many rows and more take the blocks of 8 waves
 constexpr int QK_BINS = 512;      // sums counted per pass: base .. base + 510, and one bin for everything above
 constexpr int QK_KP = 128;        // kprime at most (the length of a result list)
 constexpr int QK_BATCH = 4;       // codes of a thread on their way at a time
@@ -116,16 +116,16 @@ struct __align__(16) QuickSmem {
 };
 // (items of the blocks of 4 waves have fewer than QK_LONG_MIN = 2^16 rows: 16 bits hold a row within the item)
 typedef QuickSmem<4, uint16_t> QuickSmemShort;
-typedef QuickSmem<16, uint32_t> QuickSmemLong;
+typedef QuickSmem<8, uint32_t> QuickSmemLong;
 static_assert(QK_LONG_MIN <= 65536, "rows of short items fit 16 bits");
 static_assert(sizeof(QuickSmemShort) <= 40 * 1024, "four blocks of 4 waves share the 160 KB of a compute unit");
-static_assert(sizeof(QuickSmemLong) <= 160 * 1024, "one block of 16 waves per compute unit");
+static_assert(sizeof(QuickSmemLong) <= 80 * 1024, "two blocks of 8 waves per compute unit");
 
-// Blocks of QK_WAVES waves.  LONG: the kernel takes the work items of QK_LONG_MIN rows and more (16 waves, one block
+// Blocks of QK_WAVES waves.  LONG: the kernel takes the work items of QK_LONG_MIN rows and more (8 waves, two blocks
 // per compute unit: the longest item of a skewed index is what the call waits for), else the shorter ones (4 waves,
 // four blocks per compute unit).  Items are dealt in a stride of the grid; an item of the other kind is passed over.
 template <int QK_WAVES, bool LONG>
-__global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 4) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
+__global__ __launch_bounds__(QK_WAVES * 64, LONG ? 2 : 4) void ivf_quick_scan_kernel(const uint8_t *__restrict__ codes,
                                                                        const uint8_t *__restrict__ qluts,
                                                                        const IvfItem *__restrict__ items,
                                                                        const uint32_t *__restrict__ nitems_dev,
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 1 : 4) void ivf_quick_scan_ke
 
         // ---- counting passes: T of every pair.  Sums of base .. base + 510 are counted (one pass unless fewer than
         // kprime sums lie in that range: then the next 511 values are counted in another pass).  The codes are taken
-        // in segments of 1024, 2048, 4096, ... rows (four times that in blocks of 16 waves); after each segment the kprime-th smallest sum so far becomes the
+        // in segments of 1024, 2048, 4096, ... rows (twice that in blocks of 8 waves); after each segment the kprime-th smallest sum so far becomes the
         // pair's cap, and greater sums are no longer counted: the final T cannot exceed it.
         int scnt = 0;            // rows saved by this wave (uniform among the lanes still in the loop; lane 0 stays longest)
         bool use_saved = nvalid > kprime;
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(128) void ivf_quick_rerank_kernel(const uint8_t *__
 static int ivf_quick_saved_cap(int64_t rows, int waves) { return (int)(((rows + 16) / (waves * 64) + 2) * 64); }
 
 size_t ivf_quick_saved_bytes(const pq_ctx *ctx, int64_t max_item_rows) {
-    return ((size_t)ctx->num_cu * 16 * ivf_quick_saved_cap(max_item_rows, 16) + (size_t)ctx->num_cu * 4 * 4 * ivf_quick_saved_cap(QK_LONG_MIN, 4)) * 4;
+    return ((size_t)ctx->num_cu * 2 * 8 * ivf_quick_saved_cap(max_item_rows, 8) + (size_t)ctx->num_cu * 4 * 4 * ivf_quick_saved_cap(QK_LONG_MIN, 4)) * 4;
 }
 
 int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offsets, const int32_t *probes,
@@ -468,7 +468,7 @@ int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offs
     if (ctx->profiling) {
         PQ_HIP(ctx, hipEventRecord(ctx->ev_begin, s));
         snprintf(ctx->last_scan_name, sizeof(ctx->last_scan_name),
-                 "ivf_quick_scan_kernel (16x4 codes, 8-bit tables of 8 (query, list) pairs per work item; blocks of 16 waves for items of %d rows and more, of 4 waves for the others)", QK_LONG_MIN);
+                 "ivf_quick_scan_kernel (16x4 codes, 8-bit tables of 8 (query, list) pairs per work item; blocks of 8 waves for items of %d rows and more, of 4 waves for the others)", QK_LONG_MIN);
         ctx->last_scan_qpp = QK_QS;
         ctx->last_scan_passes = 2;
         ctx->stat_parked = nullptr;
@@ -476,20 +476,20 @@ int launch_ivf_quick(pq_ctx *ctx, const uint8_t *codes, const int64_t *list_offs
         ctx->stat_ncand_len = 0;
     }
     {
-        auto long_kernel = ivf_quick_scan_kernel<16, true>;
+        auto long_kernel = ivf_quick_scan_kernel<8, true>;
         auto short_kernel = ivf_quick_scan_kernel<4, false>;
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(long_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)sizeof(QuickSmemLong)));
         PQ_HIP(ctx, hipFuncSetAttribute(reinterpret_cast<const void *>(short_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         (int)sizeof(QuickSmemShort)));
         // the long items first (longest lists come first in the table of items), then the many short ones
-        const int cap_long = ivf_quick_saved_cap(max_item_rows, 16), cap_short = ivf_quick_saved_cap(QK_LONG_MIN, 4);
-        long_kernel<<<ctx->num_cu, 16 * 64, sizeof(QuickSmemLong), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
+        const int cap_long = ivf_quick_saved_cap(max_item_rows, 8), cap_short = ivf_quick_saved_cap(QK_LONG_MIN, 4);
+        long_kernel<<<ctx->num_cu * 2, 8 * 64, sizeof(QuickSmemLong), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
                                                                        kprime, partial, saved_rows, cap_long);
         PQ_HIP(ctx, hipGetLastError());
         short_kernel<<<ctx->num_cu * 4, 4 * 64, sizeof(QuickSmemShort), s>>>(codes, qluts, items, nitems_dev, pairs_by_list, pair_out,
                                                                           kprime, partial,
-                                                                          saved_rows + (size_t)ctx->num_cu * 16 * cap_long, cap_short);
+                                                                          saved_rows + (size_t)ctx->num_cu * 2 * 8 * cap_long, cap_short);
         PQ_HIP(ctx, hipGetLastError());
     }
     if (ctx->profiling) {

@@ -37,6 +37,7 @@ constexpr int QK_KP = 128;        // kprime at most (the length of a result list
 constexpr int QK_BATCH = 4;       // codes of a thread on their way at a time
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
     const u16x2 r = __builtin_bit_cast(u16x2, a) + __builtin_bit_cast(u16x2, b);
@@ -177,14 +178,22 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 2 : 4) void ivf_quick_scan_ke
         __syncthreads();
 
         // sums of one code for the eight pairs: four registers of two 16-bit sums
-        const char *tab_bytes = reinterpret_cast<const char *>(sm.tab);
+        uint32_t tab_lds = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)sm.tab;   // LDS address of the tables
+        asm volatile("" : "+v"(tab_lds));
         // Returns, per lane, whether some pair's sum is below its limit (`limit` holds the limits per 16-bit half; 0:
         // nothing passes).
         auto sums_below = [&](const uint2 c, bool valid, const uint32_t (&limit)[4], uint32_t (&acc)[4]) {
             acc[0] = acc[1] = acc[2] = acc[3] = 0u;
+            // byte b of lo4 / hi4: index 2 b / 2 b + 1 of the code times 16, the offset of its slot within a sub-quantizer's 256 bytes
+            uint32_t lo4[2] = {(c.x << 4) & 0xf0f0f0f0u, (c.y << 4) & 0xf0f0f0f0u};
+            uint32_t hi4[2] = {c.x & 0xf0f0f0f0u, c.y & 0xf0f0f0f0u};
+            // (kept as they are: the compiler would otherwise go back to a shift, a mask and an addition per entry)
+            asm volatile("" : "+v"(lo4[0]), "+v"(lo4[1]), "+v"(hi4[0]), "+v"(hi4[1]));
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                const uint4 e = *reinterpret_cast<const uint4 *>(tab_bytes + j * 256 + (code_index4(c, j) << 4));
+                const uint32_t word = (j & 1) ? hi4[j >> 3] : lo4[j >> 3];
+                const uint32_t addr = tab_lds | ((word >> (8 * ((j >> 1) & 3))) & 0xffu);   // (the tables start on a 256-byte boundary)
+                const u32x4 e = *(const __attribute__((address_space(3))) u32x4 *)(uintptr_t)(addr + (uint32_t)j * 256u);
                 acc[0] = pk_add_u16(acc[0], e.x); acc[1] = pk_add_u16(acc[1], e.y);
                 acc[2] = pk_add_u16(acc[2], e.z); acc[3] = pk_add_u16(acc[3], e.w);
             }

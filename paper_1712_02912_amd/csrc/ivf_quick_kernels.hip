@@ -189,13 +189,18 @@ __global__ __launch_bounds__(QK_WAVES * 64, LONG ? 2 : 4) void ivf_quick_scan_ke
             uint32_t hi4[2] = {c.x & 0xf0f0f0f0u, c.y & 0xf0f0f0f0u};
             // (kept as they are: the compiler would otherwise go back to a shift, a mask and an addition per entry)
             asm volatile("" : "+v"(lo4[0]), "+v"(lo4[1]), "+v"(hi4[0]), "+v"(hi4[1]));
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
+            auto entry = [&](int j) {
                 const uint32_t word = (j & 1) ? hi4[j >> 3] : lo4[j >> 3];
                 const uint32_t addr = tab_lds | ((word >> (8 * ((j >> 1) & 3))) & 0xffu);   // (the tables start on a 256-byte boundary)
-                const u32x4 e = *(const __attribute__((address_space(3))) u32x4 *)(uintptr_t)(addr + (uint32_t)j * 256u);
-                acc[0] = pk_add_u16(acc[0], e.x); acc[1] = pk_add_u16(acc[1], e.y);
-                acc[2] = pk_add_u16(acc[2], e.z); acc[3] = pk_add_u16(acc[3], e.w);
+                return *(const __attribute__((address_space(3))) u32x4 *)(uintptr_t)(addr + (uint32_t)j * 256u);
+            };
+            // two 16-bit sums per register, added as 32-bit words (no half ever carries: a sum is at most 16 * 255), two
+            // entries per three-operand addition
+#pragma unroll
+            for (int j = 0; j < 16; j += 2) {
+                const u32x4 e0 = entry(j), e1 = entry(j + 1);
+                acc[0] = acc[0] + e0.x + e1.x; acc[1] = acc[1] + e0.y + e1.y;
+                acc[2] = acc[2] + e0.z + e1.z; acc[3] = acc[3] + e0.w + e1.w;
             }
             const uint32_t any = pk_sub_sat_u16(limit[0], acc[0]) | pk_sub_sat_u16(limit[1], acc[1]) |
                                  pk_sub_sat_u16(limit[2], acc[2]) | pk_sub_sat_u16(limit[3], acc[3]);

@@ -592,6 +592,60 @@ __global__ __launch_bounds__(IVF_REFINE_MAX) void ivf_refine_probes_kernel(const
     }
 }
 
+// Second attempt for the queries that ivf_refine_probes_kernel left flagged (the gap behind their nprobe-th list is smaller
+// than the error bound of the approximations times a handful of lists): exact distances to ALL lists that the filtering pass
+// kept for the query.  Their approximate distances are at or below theta[q] and those of every other list above it, so the
+// same proof holds against theta[q], some hundreds of lists further out.  Queries with fewer than nprobe kept lists, with more
+// than the lists' room, or still without proof (equal distances far out) stay flagged and take the exact row.
+__global__ __launch_bounds__(256) void ivf_refine_kept_kernel(const float *__restrict__ queries, const float *__restrict__ cents,
+                                                              const unsigned long long *__restrict__ keys_in,
+                                                              const unsigned int *__restrict__ cnt_in, const float *__restrict__ theta,
+                                                              int d, int nprobe, float eps, const unsigned int *__restrict__ max_norm_bits,
+                                                              int32_t *__restrict__ probes, int32_t *probe_out, int32_t *__restrict__ flags) {
+    extern __shared__ float ys[];   // the query
+    __shared__ uint64_t keys[IVF_PICK_CAP];
+    __shared__ double red[4];
+    __shared__ int proved;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    if (flags[q] == 0) return;
+    const unsigned int cnt = cnt_in[q];
+    if (cnt < (unsigned int)nprobe || cnt > (unsigned int)IVF_PICK_CAP) return;
+    const float *y = queries + (size_t)q * d;
+    double ny = 0.0;
+    for (int t = tid; t < d; t += 256) { const float x = y[t]; ys[t] = x; ny += (double)x * (double)x; }
+    for (int o = 32; o > 0; o >>= 1) ny += __shfl_xor(ny, o);
+    if ((tid & 63) == 0) red[tid >> 6] = ny;
+    __syncthreads();
+    int n2 = 128;
+    while (n2 < (int)cnt) n2 <<= 1;
+    for (int i = tid; i < n2; i += 256) {
+        uint64_t key = ~0ull;
+        if (i < (int)cnt) {
+            const uint32_t l = (uint32_t)keys_in[(size_t)q * IVF_PICK_CAP + i];
+            const float *c = cents + (size_t)l * d;
+            double s = 0.0;   // dimension by dimension, as the definition has it
+            for (int t = 0; t < d; ++t) { const double df = (double)ys[t] - (double)c[t]; s += df * df; }
+            key = ((uint64_t)f32_to_ord((float)s) << 32) | l;
+        }
+        keys[i] = key;
+    }
+    block_bitonic_sort(keys, n2);
+    if (tid == 0) {
+        ny = red[0] + red[1] + red[2] + red[3];
+        const double low = ((double)theta[q] - (double)eps * (ny + (double)__uint_as_float(*max_norm_bits))) * (1.0 - 1.2e-7);
+        const double kth = (double)ord_to_f32((uint32_t)(keys[nprobe - 1] >> 32));
+        proved = kth < low ? 1 : 0;   // (false for a NaN anywhere as well)
+    }
+    __syncthreads();
+    if (proved == 0) return;
+    if (tid < nprobe) {
+        const int32_t l = (int32_t)(uint32_t)keys[tid];
+        probes[(size_t)q * nprobe + tid] = l;
+        if (probe_out) probe_out[(size_t)q * nprobe + tid] = l;
+    }
+    if (tid == 0) flags[q] = 0;
+}
+
 // Exact distances (the plain definition in double, rounded to float once) of the flagged queries to every list.
 __global__ __launch_bounds__(256) void ivf_exact_rows_kernel(const float *__restrict__ queries, const float *__restrict__ cents,
                                                              int nlist, int d, const int32_t *__restrict__ flags,
@@ -744,11 +798,18 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
                 ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, ks, rank, cand, nullptr, nullptr);
                 ivf_theta_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(dist, ks, cand, rank, nqb, theta);
                 PQ_HIP(ctx, hipGetLastError());
-                rc = launch_coarse_f32_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP);
+                // (the pass over all lists on the fp16 matrix cores, every operand as two halves; option 0: on the fp32 ones)
+                const bool split16 = opt_int(ctx, PQ_OPT_IVF_COARSE_F16, 1) != 0;
+                rc = split16 ? launch_coarse_split16_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP)
+                             : launch_coarse_f32_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP);
                 if (rc) return rc;
                 ivf_pick_candidates_kernel<<<nqb, 256, 0, s>>>(ckeys, ccnt, ncand, cand, far, flags);
                 ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, nullptr, cand, far, ncand, nlist, d,
-                                                                                   nprobe, coarse_f32_error(d), maxnorm, probes, pout, flags);
+                                                                                   nprobe, split16 ? coarse_split16_error(d) : coarse_f32_error(d),
+                                                                                   maxnorm, probes, pout, flags);
+                ivf_refine_kept_kernel<<<nqb, 256, (size_t)d * 4, s>>>(qb, L->coarse_centroids, ckeys, ccnt, theta, d, nprobe,
+                                                                      split16 ? coarse_split16_error(d) : coarse_f32_error(d), maxnorm,
+                                                                      probes, pout, flags);
             } else {
                 rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, (size_t)d, nqb, d, nlist, dist);
                 if (rc) return rc;

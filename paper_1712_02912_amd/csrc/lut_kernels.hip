@@ -633,12 +633,67 @@ struct CoarseF32Args {
     int cap;
 };
 
+typedef float coarse_floatx16 __attribute__((ext_vector_type(16)));
+constexpr int COARSE_WSTASH = 512;   // entries a wave collects per tile before it appends them
+
+// End of a 128 x 128 tile of the filtering forms: acc holds the inner products <y, c> of the wave's 64 x 64 outputs (lane l
+// of a matrix tile: rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15, of column l % 32), ny / nc / th the squared norms
+// and bounds of the tile's rows and columns.  The values ny + nc - 2 <y, c> at or below their row's bound leave as keys.
+// Such entries are rare: every wave collects its own in LDS first (`stash`: the operand buffers, free by now; position from
+// a count that the wave keeps in a register: no atomic operation, no waiting inside the unrolled code) and appends them to
+// the queries' lists afterwards, all of them at once.
+__device__ __forceinline__ void coarse_filter_tile(const coarse_floatx16 (&acc)[2][2], void *stash, const float *th, const float *ny,
+                                                   const float *nc, int q0, int c0, int k, unsigned long long *cand_keys,
+                                                   unsigned int *cand_cnt, int cap) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    unsigned long long *wkeys = reinterpret_cast<unsigned long long *>(stash) + wave * COARSE_WSTASH;
+    unsigned int *wrow = reinterpret_cast<unsigned int *>(stash) + 2 * 4 * COARSE_WSTASH + wave * COARSE_WSTASH;
+    unsigned int wcount = 0;   // the same in every lane
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = wy * 64 + ta * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const float bound = th[r], nyr = ny[r];   // (rows past the end have a bound of -inf)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int c = wx * 64 + tb * 32 + (lane & 31);
+                const float val = fmaf(-2.f, acc[ta][tb][v], nyr + nc[c]);
+                const bool pass = val <= bound && c0 + c < k;
+                const unsigned long long m = __ballot(pass);
+                if (m != 0ull) {
+                    if (pass) {
+                        const unsigned long long key = ((unsigned long long)f32_to_ord(val) << 32) | (unsigned int)(c0 + c);
+                        const unsigned int slot = wcount + __builtin_amdgcn_mbcnt_hi((unsigned int)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)m, 0u));
+                        if (slot < (unsigned int)COARSE_WSTASH) {
+                            wkeys[slot] = key;
+                            wrow[slot] = (unsigned int)r;
+                        } else {   // (more than fit: straight to the query's list)
+                            const unsigned int pos = atomicAdd(&cand_cnt[q0 + r], 1u);
+                            if (pos < (unsigned int)cap) cand_keys[(size_t)(q0 + r) * cap + pos] = key;
+                        }
+                    }
+                    wcount += (unsigned int)__popcll(m);
+                }
+            }
+        }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // within a wave LDS accesses take effect in program order
+    const unsigned int kept = wcount < (unsigned int)COARSE_WSTASH ? wcount : (unsigned int)COARSE_WSTASH;
+    for (unsigned int i = lane; i < kept; i += 64) {
+        const unsigned int q = (unsigned int)q0 + wrow[i];
+        const unsigned int pos = atomicAdd(&cand_cnt[q], 1u);
+        if (pos < (unsigned int)cap) cand_keys[(size_t)q * cap + pos] = wkeys[i];
+    }
+}
+
 template <bool FILTER>
 __global__ __launch_bounds__(256, 2) void coarse_f32_kernel(const CoarseF32Args A) {
-    typedef float floatx16 __attribute__((ext_vector_type(16)));
+    typedef coarse_floatx16 floatx16;
     __shared__ __align__(16) float lds[2 * 2 * MT2 * LS3];   // [buffer][y | c][row][LS3]
     __shared__ float ny[MT2], nc[MT2], th[MT2];
     static_assert(4 * 32 * OS3 <= 2 * 2 * MT2 * LS3, "output staging fits the operand buffers");
+    static_assert(4 * COARSE_WSTASH * 12 <= (int)sizeof(float) * 2 * 2 * MT2 * LS3, "the collected entries fit the operand buffers");
     const int nq = A.nq, d = A.d, k = A.k;
     const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
     const int die = blockIdx.x & 7;
@@ -775,49 +830,7 @@ __global__ __launch_bounds__(256, 2) void coarse_f32_kernel(const CoarseF32Args 
         __syncthreads();
         // lane l of a matrix tile holds rows 8 * (v / 4) + 4 * (l / 32) + v % 4 (v = 0..15) of column l % 32
         if (FILTER) {
-            // Entries at or below their row's bound are rare: every wave collects its own in LDS first (position from
-            // a count that the wave keeps in a register: no atomic operation, no waiting inside the unrolled code) and
-            // appends them to the queries' lists afterwards, all of them at once.
-            constexpr int WSTASH = 512;
-            unsigned long long *wkeys = reinterpret_cast<unsigned long long *>(lds) + wave * WSTASH;                 // in the operand buffers
-            unsigned int *wrow = reinterpret_cast<unsigned int *>(lds) + 2 * 4 * WSTASH + wave * WSTASH;
-            static_assert(4 * WSTASH * 12 <= (int)sizeof(float) * 2 * 2 * MT2 * LS3, "the collected entries fit the operand buffers");
-            unsigned int wcount = 0;   // the same in every lane
-#pragma unroll
-            for (int ta = 0; ta < 2; ++ta)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = wy * 64 + ta * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    const float bound = th[r], nyr = ny[r];   // (rows past the end have a bound of -inf)
-#pragma unroll
-                    for (int tb = 0; tb < 2; ++tb) {
-                        const int c = wx * 64 + tb * 32 + (lane & 31);
-                        const float val = fmaf(-2.f, acc[ta][tb][v], nyr + nc[c]);
-                        const bool pass = val <= bound && cur.c0 + c < k;
-                        const unsigned long long m = __ballot(pass);
-                        if (m != 0ull) {
-                            if (pass) {
-                                const unsigned long long key = ((unsigned long long)f32_to_ord(val) << 32) | (unsigned int)(cur.c0 + c);
-                                const unsigned int slot = wcount + __builtin_amdgcn_mbcnt_hi((unsigned int)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)m, 0u));
-                                if (slot < (unsigned int)WSTASH) {
-                                    wkeys[slot] = key;
-                                    wrow[slot] = (unsigned int)r;
-                                } else {   // (more than fit: straight to the query's list)
-                                    const unsigned int pos = atomicAdd(&A.cand_cnt[cur.q0 + r], 1u);
-                                    if (pos < (unsigned int)A.cap) A.cand_keys[(size_t)(cur.q0 + r) * A.cap + pos] = key;
-                                }
-                            }
-                            wcount += (unsigned int)__popcll(m);
-                        }
-                    }
-                }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // within a wave LDS accesses take effect in program order
-            const unsigned int kept = wcount < (unsigned int)WSTASH ? wcount : (unsigned int)WSTASH;
-            for (unsigned int i = lane; i < kept; i += 64) {
-                const unsigned int q = (unsigned int)cur.q0 + wrow[i];
-                const unsigned int pos = atomicAdd(&A.cand_cnt[q], 1u);
-                if (pos < (unsigned int)A.cap) A.cand_keys[(size_t)q * A.cap + pos] = wkeys[i];
-            }
+            coarse_filter_tile(acc, lds, th, ny, nc, cur.q0, cur.c0, k, A.cand_keys, A.cand_cnt, A.cap);
             if (!more) break;
             __syncthreads();   // every wave has left its collected entries: the operand buffers are free again
             local += blocks_per_die;
@@ -898,6 +911,250 @@ int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cen
     A.theta = theta; A.cand_keys = cand_keys; A.cand_cnt = cand_cnt; A.cap = cap;
     const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
     coarse_f32_kernel<true><<<grid, 256, 0, ctx->stream>>>(A);
+    PQ_HIP(ctx, hipGetLastError());
+    return PQ_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// The filtering pass on the fp16 matrix cores (v_mfma_f32_32x32x16_f16: 16 times the rate of the fp32 form) without
+// giving up fp32 accuracy: every operand value x, scaled by a power of two s that brings the greatest magnitude of its
+// matrix to [2^13, 2^14), is kept as two halves hi = fp16(x s), lo = fp16(x s - hi) (x s = hi + lo up to 2^-22 of
+// its size), and <y, c> is accumulated in fp32 as hi hi + hi lo + lo hi (products of halves are exact in fp32; the
+// omitted lo lo is below 2^-22 of |y| |c|).  The operands are split once per call by split16_prep_kernel, [row][chunk
+// of 32 dimensions][32 hi | 32 lo] with the rows' squared norms beside them, so the kernel stages 16-byte pieces
+// as they are.  Same tiling, block numbering and end of tile as the fp32 form.
+// Magnitudes outside 2^-40 .. 2^40 (or not finite) are not served: the kernel keeps nothing then, and the caller's
+// queries, left without candidates, take their exact rows.
+constexpr int HK = 32;     // dimensions per chunk
+constexpr int HROW = 9;    // 16-byte pieces per staged row of a chunk: 4 of hi, 4 of lo, 1 unused (rows 36 words apart:
+                           // the 16 rows that a 16-byte read serves at a time fall into different banks)
+
+typedef uint32_t lut_u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 lut_half8 __attribute__((ext_vector_type(8)));
+
+__global__ void split16_clear_kernel(unsigned int *maxbits) {
+    if (threadIdx.x < 2) maxbits[threadIdx.x] = 0u;
+}
+
+// maxbits[0] = greatest |a[i]|, maxbits[1] = greatest |b[i]| as float bits (they start at 0; NaNs order above infinity)
+__global__ __launch_bounds__(256) void split16_absmax_kernel(const float *__restrict__ a, size_t na, const float *__restrict__ b,
+                                                             size_t nb, unsigned int *maxbits) {
+    __shared__ unsigned int red[2][4];
+    unsigned int m[2] = {0u, 0u};
+    const size_t step = (size_t)gridDim.x * 256;
+    for (int w = 0; w < 2; ++w) {
+        const float *v = w ? b : a;
+        const size_t n = w ? nb : na;
+        for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += step) {
+            const unsigned int bits = __float_as_uint(v[i]) & 0x7fffffffu;   // (|x|: orders like the value, NaNs above infinity)
+            m[w] = bits > m[w] ? bits : m[w];
+        }
+        for (int o = 32; o > 0; o >>= 1) { const unsigned int t = (unsigned int)__shfl_xor((int)m[w], o); m[w] = t > m[w] ? t : m[w]; }
+        if ((threadIdx.x & 63) == 0) red[w][threadIdx.x >> 6] = m[w];
+    }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        const unsigned int *r = red[threadIdx.x];
+        unsigned int t = r[0] > r[1] ? r[0] : r[1];
+        t = r[2] > t ? r[2] : t;
+        t = r[3] > t ? r[3] : t;
+        atomicMax(&maxbits[threadIdx.x], t);
+    }
+}
+
+// Power of two that brings a matrix whose greatest magnitude has the bits `maxbits` to [2^13, 2^14), as the exponent
+// field of a float; 0 if the magnitude is outside 2^-40 .. 2^40 (an all-zero matrix counts as 1).
+__device__ __forceinline__ unsigned int split16_scale_field(unsigned int maxbits) {
+    if (maxbits == 0u) return 127u + 13u;
+    const unsigned int e = maxbits >> 23;
+    if (e < 127u - 40u || e > 127u + 40u) return 0u;
+    return 267u - e;   // 2^(13 - (e - 127))
+}
+
+// 8 threads per row, 4 dimensions of every chunk each.  Rows from `rows` up to rows_pad and dimensions from d up to
+// nch * 32 are zeros.  norms[row] = ||row||^2 in fp32 (each thread a chain of fused multiply-adds, then three additions).
+__global__ __launch_bounds__(256) void split16_prep_kernel(const float *__restrict__ src, int rows, int rows_pad, int d, int nch,
+                                                           const unsigned int *__restrict__ maxbits, lut_u32x4 *__restrict__ dst,
+                                                           float *__restrict__ norms) {
+    const int row = blockIdx.x * 32 + (threadIdx.x >> 3), seg = threadIdx.x & 7;
+    if (row >= rows_pad) return;
+    const unsigned int field = split16_scale_field(*maxbits);
+    const float s = __uint_as_float(field << 23);   // (0 for matrices not served: the halves are zeros then, and unused)
+    uint2 *out = reinterpret_cast<uint2 *>(dst + (size_t)row * nch * 8);
+    float norm = 0.f;
+    for (int c = 0; c < nch; ++c) {
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int t = c * HK + seg * 4;
+        if (row < rows && t < d) x = *reinterpret_cast<const float4 *>(src + (size_t)row * d + t);   // (d is a multiple of 4)
+        norm = fmaf(x.x, x.x, fmaf(x.y, x.y, fmaf(x.z, x.z, fmaf(x.w, x.w, norm))));
+        const float v[4] = {x.x * s, x.y * s, x.z * s, x.w * s};
+        _Float16 hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hi[i] = (_Float16)v[i];
+            lo[i] = (_Float16)(v[i] - (float)hi[i]);
+        }
+        auto pack = [](_Float16 a, _Float16 b) {
+            return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+        };
+        out[c * 16 + seg] = make_uint2(pack(hi[0], hi[1]), pack(hi[2], hi[3]));       // hi: the first 64 bytes of the chunk
+        out[c * 16 + 8 + seg] = make_uint2(pack(lo[0], lo[1]), pack(lo[2], lo[3]));   // lo: the second
+    }
+    norm += __shfl_xor(norm, 1);
+    norm += __shfl_xor(norm, 2);
+    norm += __shfl_xor(norm, 4);
+    if (seg == 0) norms[row] = norm;
+}
+
+struct CoarseSplit16Args {
+    const lut_u32x4 *yh, *ch;       // [rows_pad][nch][8]: the split operands
+    const float *nyg, *ncg;         // squared norms
+    const unsigned int *maxbits;    // [2]: greatest magnitudes of the two matrices
+    int nq, k, nch;
+    int tiles_x, tiles_y, total;
+    const float *theta;             // [nq]
+    unsigned long long *cand_keys;  // [nq][cap]
+    unsigned int *cand_cnt;         // [nq], zero at the start
+    int cap;
+};
+
+__global__ __launch_bounds__(256, 2) void coarse_split16_filter_kernel(const CoarseSplit16Args A) {
+    __shared__ lut_u32x4 lds[2 * 2 * MT2 * HROW];   // [buffer][y | c][row][HROW]
+    __shared__ float ny[MT2], nc[MT2], th[MT2];
+    static_assert(4 * COARSE_WSTASH * 12 <= (int)sizeof(lut_u32x4) * 2 * 2 * MT2 * HROW, "the collected entries fit the operand buffers");
+    const unsigned int fy = split16_scale_field(A.maxbits[0]), fc = split16_scale_field(A.maxbits[1]);
+    if (fy == 0u || fc == 0u) return;   // (uniform: magnitudes that the halves do not serve)
+    const float unscale = __uint_as_float((381u - fy - fc) << 23);   // 1 / (s_y s_c) = 2^(254 - fy - fc): between 2^-106 and 2^54
+    const int nq = A.nq, k = A.k, nch = A.nch;
+    const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
+    const int die = blockIdx.x & 7;
+    int local = blockIdx.x >> 3;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    auto has_tile = [&](int l) { return l < per_die && die * per_die + l < A.total; };
+    if (!has_tile(local)) return;
+    // piece tid % 8 of rows tid / 8 + 32 * pass (the operands are padded to whole tiles)
+    const int srow = tid >> 3, seg = tid & 7;
+    lut_u32x4 rf[2][4];   // [y | c][pass]: the chunk after the one being multiplied
+    auto fetch = [&](const Tile128 &t, int c) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            rf[0][p] = A.yh[((size_t)(t.q0 + p * 32 + srow) * nch + c) * 8 + seg];
+            rf[1][p] = A.ch[((size_t)(t.c0 + p * 32 + srow) * nch + c) * 8 + seg];
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            lds[((buf * 2 + 0) * MT2 + p * 32 + srow) * HROW + seg] = rf[0][p];
+            lds[((buf * 2 + 1) * MT2 + p * 32 + srow) * HROW + seg] = rf[1][p];
+        }
+    };
+    coarse_floatx16 acc[2][2];
+    // lane l feeds row l % 32 of its matrix tiles, dimensions 16 * step + 8 * (l / 32) .. + 7 of the chunk
+    auto compute = [&](int buf) {
+        const lut_u32x4 *yt = lds + ((buf * 2 + 0) * MT2 + wy * 64 + (lane & 31)) * HROW + (lane >> 5);
+        const lut_u32x4 *ct = lds + ((buf * 2 + 1) * MT2 + wx * 64 + (lane & 31)) * HROW + (lane >> 5);
+#pragma unroll
+        for (int step = 0; step < HK / 16; ++step) {
+            lut_half8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                ah[t] = __builtin_bit_cast(lut_half8, yt[t * 32 * HROW + 2 * step]);
+                al[t] = __builtin_bit_cast(lut_half8, yt[t * 32 * HROW + 4 + 2 * step]);
+                bh[t] = __builtin_bit_cast(lut_half8, ct[t * 32 * HROW + 2 * step]);
+                bl[t] = __builtin_bit_cast(lut_half8, ct[t * 32 * HROW + 4 + 2 * step]);
+            }
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bh[tb], acc[ta][tb], 0, 0, 0);
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bl[tb], acc[ta][tb], 0, 0, 0);
+                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[ta], bh[tb], acc[ta][tb], 0, 0, 0);
+                }
+        }
+    };
+
+    Tile128 cur = tile128_of(die * per_die + local, A.tiles_x, A.tiles_y);
+    fetch(cur, 0);
+    for (;;) {
+        const bool more = has_tile(local + blocks_per_die);
+        const Tile128 next = more ? tile128_of(die * per_die + local + blocks_per_die, A.tiles_x, A.tiles_y) : cur;
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ta][tb][v] = 0.f;
+        if (tid < MT2) {
+            th[tid] = cur.q0 + tid < nq ? A.theta[cur.q0 + tid] : -__builtin_inff();
+            ny[tid] = A.nyg[cur.q0 + tid];
+            nc[tid] = A.ncg[cur.c0 + tid];
+        }
+        stage(0);
+        if (1 < nch) fetch(cur, 1);
+        else if (more) fetch(next, 0);
+        __syncthreads();
+        // chunk c is multiplied from buffer c % 2 while chunk c + 1 goes into the other one (which every wave has left:
+        // the barrier stands after the multiplications) and chunk c + 2 is on its way from memory
+        for (int c = 0; c < nch; ++c) {
+            if (c + 1 < nch) {
+                stage((c + 1) & 1);
+                if (c + 2 < nch) fetch(cur, c + 2);
+                else if (more) fetch(next, 0);
+            }
+            compute(c & 1);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[ta][tb][v] *= unscale;   // (a power of two: exact)
+        coarse_filter_tile(acc, lds, th, ny, nc, cur.q0, cur.c0, k, A.cand_keys, A.cand_cnt, A.cap);
+        if (!more) break;
+        __syncthreads();   // every wave has left its collected entries: the operand buffers are free again
+        local += blocks_per_die;
+        cur = next;
+    }
+}
+
+// Bound on |approximate - exact| / (||y||^2 + ||c||^2) for the kernel above.  The inner product is a sum of 3 dpad exact
+// products whose magnitudes add up to at most (1 + 2^-9) |y| |c|; each of the 3 dpad additions may lose one unit of
+// 2^-23 of that (whatever the order and the rounding of the matrix unit's adder), the representation 2^-19 in all (halves,
+// omitted products, fp16 values below the normal range); with 2 |y| |c| <= ||y||^2 + ||c||^2 the term 2 <y, c> is off by at
+// most (3 dpad 2^-23 + 2^-19) (||y||^2 + ||c||^2).  The two norms add d / 8 + 6 units of 2^-24 of themselves each, the final
+// combination three.  Doubled for good measure, like the bound of the fp32 form.
+float coarse_split16_error(int d) {
+    const int dpad = (d + HK - 1) / HK * HK;
+    return 2.f * ((float)(3 * dpad) * 1.1920929e-7f + 1.9073486e-6f + (float)(d / 8 + 12) * 5.9604645e-8f);
+}
+
+// The filtering pass of launch_coarse_f32_filter through split fp16 operands (shapes as coarse_f32_usable accepts them).
+int launch_coarse_split16_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
+                                 unsigned long long *cand_keys, unsigned int *cand_cnt, int cap) {
+    if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, queries)) return fail(ctx, PQ_EINVAL, "coarse_split16: shape not served");
+    CoarseSplit16Args A{};
+    A.nq = nq; A.k = k; A.nch = (d + HK - 1) / HK;
+    A.tiles_x = (k + MT2 - 1) / MT2; A.tiles_y = (nq + MT2 - 1) / MT2; A.total = A.tiles_x * A.tiles_y;
+    const size_t rows_y = (size_t)A.tiles_y * MT2, rows_c = (size_t)A.tiles_x * MT2;
+    const size_t row_bytes = (size_t)A.nch * 8 * sizeof(lut_u32x4);
+    const size_t bytes = (rows_y + rows_c) * (row_bytes + sizeof(float)) + 256;
+    const int rc = lut_ws_reserve(ctx, bytes);
+    if (rc) return rc;
+    lut_u32x4 *yh = (lut_u32x4 *)ctx->lut_ws, *ch = yh + rows_y * A.nch * 8;
+    float *nyg = (float *)(ch + rows_c * A.nch * 8), *ncg = nyg + rows_y;
+    unsigned int *maxbits = (unsigned int *)(ncg + rows_c);
+    split16_clear_kernel<<<1, 64, 0, ctx->stream>>>(maxbits);
+    split16_absmax_kernel<<<ctx->num_cu * 4, 256, 0, ctx->stream>>>(queries, (size_t)nq * d, cents, (size_t)k * d, maxbits);
+    split16_prep_kernel<<<(unsigned)((rows_y + 31) / 32), 256, 0, ctx->stream>>>(queries, nq, (int)rows_y, d, A.nch, maxbits, yh, nyg);
+    split16_prep_kernel<<<(unsigned)((rows_c + 31) / 32), 256, 0, ctx->stream>>>(cents, k, (int)rows_c, d, A.nch, maxbits + 1, ch, ncg);
+    A.yh = yh; A.ch = ch; A.nyg = nyg; A.ncg = ncg; A.maxbits = maxbits;
+    A.theta = theta; A.cand_keys = cand_keys; A.cand_cnt = cand_cnt; A.cap = cap;
+    const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
+    coarse_split16_filter_kernel<<<grid, 256, 0, ctx->stream>>>(A);
     PQ_HIP(ctx, hipGetLastError());
     return PQ_OK;
 }

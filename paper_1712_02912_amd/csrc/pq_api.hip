@@ -53,7 +53,7 @@ static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 static const char *const OPTION_NAMES[PQ_OPT_COUNT] = {"scan_prune", "scan_q8", "scan_force_general", "scan_blocks",
                                                        "scan_items_per_block", "scan_head", "lut_mfma", "ivf_prune",
                                                        "ivf_ws_gib", "ivf_block_waves", "scan_wide_seed", "ivf_short_max", "ivf_coarse_f32",
-                                                       "ivf_quick_chunk_rows"};
+                                                       "ivf_quick_chunk_rows", "ivf_coarse_f16"};
 
 static void options_from_environment(pq_ctx *ctx) {
     for (int i = 0; i < PQ_OPT_COUNT; ++i) {

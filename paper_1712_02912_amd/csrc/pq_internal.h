@@ -10,7 +10,7 @@
 // Tuning and test switches (pq_set_option).  PQ_OPT_UNSET = the kernel's own default.
 enum pq_option_id {
     PQ_OPT_SCAN_PRUNE = 0, PQ_OPT_SCAN_Q8, PQ_OPT_SCAN_FORCE_GENERAL, PQ_OPT_SCAN_BLOCKS, PQ_OPT_SCAN_ITEMS_PER_BLOCK,
-    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_IVF_COARSE_F32, PQ_OPT_IVF_QUICK_CHUNK_ROWS, PQ_OPT_COUNT
+    PQ_OPT_SCAN_HEAD, PQ_OPT_LUT_MFMA, PQ_OPT_IVF_PRUNE, PQ_OPT_IVF_WS_GIB, PQ_OPT_IVF_BLOCK_WAVES, PQ_OPT_SCAN_WIDE_SEED, PQ_OPT_IVF_SHORT_MAX, PQ_OPT_IVF_COARSE_F32, PQ_OPT_IVF_QUICK_CHUNK_ROWS, PQ_OPT_IVF_COARSE_F16, PQ_OPT_COUNT
 };
 constexpr int PQ_OPT_UNSET = -2147483647 - 1;
 
@@ -87,6 +87,11 @@ bool coarse_f32_usable(pq_ctx *ctx, const float *queries, const float *cents, in
 int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, size_t cent_stride, int nq, int d, int k, float *out);
 int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
                              unsigned long long *cand_keys, unsigned int *cand_cnt, int cap);
+// The same filtering pass on the fp16 matrix cores (operands split into two halves each), within coarse_split16_error(d) *
+// (||y||^2 + ||c||^2); magnitudes outside 2^-40 .. 2^40 keep nothing.
+float coarse_split16_error(int d);
+int launch_coarse_split16_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
+                                 unsigned long long *cand_keys, unsigned int *cand_cnt, int cap);
 int launch_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k, int cf,
                   uint8_t *codes);
 int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const float *derived_codebooks,

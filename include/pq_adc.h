@@ -86,7 +86,9 @@ const char *pq_version(void);
  *   scan_wide_seed (1)        0: first bounds of flat scans of few queries from the small sample only
  *   ivf_short_max (16384)     inverted lists of fewer codes take the kernel for short lists (0: none)
  *   ivf_coarse_f32 (1)        0: Index step of ivf_adc_search from exact distances to every list (default: lists
- *                             ranked by fp32 matrix-core distances, the nearest measured exactly; same lists)
+ *                             ranked by matrix-core distances, the nearest measured exactly; same lists)
+ *   ivf_coarse_f16 (1)        0: the ranking pass over all lists on the fp32 matrix cores (default: on the fp16 ones,
+ *                             every operand as the sum of two halves: the accuracy of fp32, a third of the time)
  *   ivf_quick_chunk_rows (1048576)  ivf_quick_adc_search: rows per work item at most (1024 ... 2^20); a list longer than
  *                             this is scanned in chunks, and a query's result lists (one per chunk of each of its
  *                             lists, at most nprobe + ntotal / this value) are part of the workspace */
@@ -254,9 +256,11 @@ typedef struct {
  * for short lists).
  * The probed lists are those with the smallest (distance from the plain definition, summed in double and
  * rounded to fp32 once; list id).  With many lists and queries they are found through approximate distances:
- * the lists are ranked on the fp32 matrix cores, the nprobe + 16 nearest are measured exactly, and a query whose
- * nprobe-th exact distance is not provably below that of every other list gets all its distances computed
- * exactly (option ivf_coarse_f32 = 0: exact distances to every list for every query). */
+ * the lists are ranked on the matrix cores (operands split into two fp16 halves each, fp32 accumulation; magnitudes of
+ * 2^-40 .. 2^40), the nprobe + 16 nearest are measured exactly, and a query whose nprobe-th exact distance is not
+ * provably below that of every other list gets first all the lists that the ranking pass kept for it (some hundreds)
+ * and then, if that does not settle it either, all its distances computed exactly (option ivf_coarse_f32 = 0: exact
+ * distances to every list for every query). */
 int ivf_adc_search(pq_ctx *ctx, const ivf_lists *lists, const float *codebooks, int m, int k, pq_code_fmt cf,
                    const float *queries, int nq, int nprobe, int topk, float *out_dist, int64_t *out_ids,
                    int32_t *probe_out);

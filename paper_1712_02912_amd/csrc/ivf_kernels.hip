@@ -501,31 +501,71 @@ __global__ __launch_bounds__(256) void ivf_max_norm_kernel(const float *__restri
     if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]))));
 }
 
-// Bound per query for the pass that keeps only near lists: the r-th smallest of the query's approximate distances to a
-// sample of the lists (sel[q][r - 1] is its column in the sample's matrix).
-__global__ void ivf_theta_kernel(const float *__restrict__ sample, int ks, const int32_t *__restrict__ sel, int r, int nq, float *theta) {
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q < nq) theta[q] = sample[(size_t)q * ks + sel[(size_t)q * r + r - 1]];
+// Bound per query for the pass that keeps only near lists, from the query's approximate distances to a sample of the
+// lists: one wave per query, lane l takes the smallest of the entries l, l + 64, ..., and the bound is the r-th smallest
+// of the 64 lane minima (r <= 64).  That is the value of rank about -64 ln(1 - r / 64) among all the entries (r minima at
+// or below it lie in r different lanes), and never below the r-th smallest entry.
+__global__ __launch_bounds__(256) void ivf_theta_kernel(const float *__restrict__ sample, int ks, int r, int nq, float *theta) {
+    const int q = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (q >= nq) return;
+    const float *row = sample + (size_t)q * ks;
+    float mine = __builtin_inff();
+    for (int i = lane; i < ks; i += 64) mine = fminf(mine, row[i]);
+    int before = 0;   // lanes whose minimum comes before this lane's (equal values by lane number)
+#pragma unroll
+    for (int l = 0; l < 64; ++l) {
+        const float other = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, mine), l));
+        before += (other < mine || (other == mine && l < lane)) ? 1 : 0;
+    }
+    if (before == r - 1) theta[q] = mine;
 }
 
-// The ncand smallest of the keys that the filtering pass kept for a query (sorted), and the approximate distance of
-// the last of them; queries with fewer than ncand keys or more than `cap` are flagged instead.
+// The keys that the filtering pass kept for a query are gathered from its places (`nslots` of them, ~0: unused) and
+// from the entries beyond the places (ov_keys[q][ov_cap], ov_cnt[q] of them), sorted, and written to kept_keys[q][] with
+// their number in kept_cnt[q] (0 if there are more than IVF_PICK_CAP or some were lost for lack of room).  The ncand
+// smallest are the query's candidates, far[q] the approximate distance of the last of them; queries with fewer than ncand
+// keys or more than IVF_PICK_CAP are flagged instead.
 constexpr int IVF_PICK_CAP = 2048;
-__global__ __launch_bounds__(256) void ivf_pick_candidates_kernel(const unsigned long long *__restrict__ keys_in, const unsigned int *__restrict__ cnt_in,
-                                                                  int ncand, int32_t *__restrict__ cand, float *__restrict__ far,
-                                                                  int32_t *__restrict__ flags) {
+constexpr int IVF_OV_CAP = 256;
+__global__ __launch_bounds__(256) void ivf_pick_candidates_kernel(const unsigned long long *__restrict__ slot_keys, int nslots,
+                                                                  const unsigned long long *__restrict__ ov_keys,
+                                                                  const unsigned int *__restrict__ ov_cnt, int ncand,
+                                                                  unsigned long long *__restrict__ kept_keys, unsigned int *__restrict__ kept_cnt,
+                                                                  int32_t *__restrict__ cand, float *__restrict__ far, int32_t *__restrict__ flags) {
     __shared__ uint64_t keys[IVF_PICK_CAP];
+    __shared__ unsigned int total;
     const int q = blockIdx.x, tid = threadIdx.x;
-    const unsigned int cnt = cnt_in[q];
-    if (cnt < (unsigned int)ncand || cnt > (unsigned int)IVF_PICK_CAP) {
-        if (tid == 0) flags[q] = 1;
+    if (tid == 0) total = 0u;
+    __syncthreads();
+    const unsigned int ov = ov_cnt[q];
+    const ulonglong2 *places = reinterpret_cast<const ulonglong2 *>(slot_keys + (size_t)q * nslots);   // (nslots is a multiple of 4)
+    for (int i = tid; i < nslots / 2; i += 256) {
+        const ulonglong2 two = places[i];
+        if (two.x != ~0ull) { const unsigned int at = atomicAdd(&total, 1u); if (at < (unsigned int)IVF_PICK_CAP) keys[at] = two.x; }
+        if (two.y != ~0ull) { const unsigned int at = atomicAdd(&total, 1u); if (at < (unsigned int)IVF_PICK_CAP) keys[at] = two.y; }
+    }
+    if (ov <= (unsigned int)IVF_OV_CAP)
+        for (int i = tid; i < (int)ov; i += 256) {
+            const unsigned int at = atomicAdd(&total, 1u);
+            if (at < (unsigned int)IVF_PICK_CAP) keys[at] = ov_keys[(size_t)q * IVF_OV_CAP + i];
+        }
+    __syncthreads();
+    const unsigned int cnt = total;
+    const bool whole = ov <= (unsigned int)IVF_OV_CAP && cnt <= (unsigned int)IVF_PICK_CAP;
+    if (!whole) {
+        if (tid == 0) { kept_cnt[q] = 0u; flags[q] = 1; }
         return;
     }
     int n2 = 128;
     while (n2 < (int)cnt) n2 <<= 1;
-    for (int i = tid; i < n2; i += 256) keys[i] = i < (int)cnt ? keys_in[(size_t)q * IVF_PICK_CAP + i] : ~0ull;
+    for (int i = (int)cnt + tid; i < n2; i += 256) keys[i] = ~0ull;
     block_bitonic_sort(keys, n2);
-    __syncthreads();
+    for (int i = tid; i < (int)cnt; i += 256) kept_keys[(size_t)q * IVF_PICK_CAP + i] = keys[i];
+    if (tid == 0) kept_cnt[q] = cnt;
+    if (cnt < (unsigned int)ncand) {
+        if (tid == 0) flags[q] = 1;
+        return;
+    }
     if (tid < ncand) cand[(size_t)q * ncand + tid] = (int32_t)(uint32_t)keys[tid];
     if (tid == 0) {
         far[q] = ord_to_f32((uint32_t)(keys[ncand - 1] >> 32));
@@ -720,6 +760,9 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
     const size_t o_far = take((size_t)qbatch * 4);
     const size_t o_ccnt = take((size_t)qbatch * 4);
     const size_t o_ckeys = take((size_t)qbatch * IVF_PICK_CAP * 8);
+    const size_t o_kcnt = take((size_t)qbatch * 4);
+    const size_t o_ovkeys = take((size_t)qbatch * IVF_OV_CAP * 8);
+    const size_t o_slots = take((size_t)qbatch * coarse_filter_slots(nlist) * 8);
     const size_t o_resid = take(npairs_max * d * 4);
     const size_t o_luts = take(npairs_max * m * k * 4);
     const size_t o_np = take((size_t)nlist * 4);
@@ -788,26 +831,28 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
             // 16th) gives each query a bound below which some hundreds of lists are expected, and the pass over all
             // lists keeps the entries at or below it (a query left with fewer than ncand of them takes the exact row).
             const int ks = (nlist + 15) / 16, rank = 6 * ncand / 16 > 8 ? 6 * ncand / 16 : 8;
+            const int lane_rank = (int)(64.0 * (1.0 - exp(-(double)rank / 64.0)) + 0.5);   // (of the 64 lane minima that ivf_theta_kernel ranks)
             if (nlist >= 16384 && rank <= ncand && coarse_f32_usable(ctx, qb, L->coarse_centroids, nqb, d, ks, dist)) {
                 float *theta = (float *)(ws + o_theta), *far = (float *)(ws + o_far);
                 unsigned int *ccnt = (unsigned int *)(ws + o_ccnt);
-                unsigned long long *ckeys = (unsigned long long *)(ws + o_ckeys);
+                unsigned long long *ckeys = (unsigned long long *)(ws + o_ckeys), *ovkeys = (unsigned long long *)(ws + o_ovkeys);
+                unsigned long long *slots = (unsigned long long *)(ws + o_slots);
+                unsigned int *kcnt = (unsigned int *)(ws + o_kcnt);
                 ivf_zero_kernel<<<64, 256, 0, s>>>(ccnt, (size_t)nqb);
                 rc = launch_coarse_f32(ctx, qb, L->coarse_centroids, (size_t)16 * d, nqb, d, ks, dist);
                 if (rc) return rc;
-                ivf_select_probes_kernel<<<nqb, 256, 0, s>>>(dist, ks, rank, cand, nullptr, nullptr);
-                ivf_theta_kernel<<<(nqb + 255) / 256, 256, 0, s>>>(dist, ks, cand, rank, nqb, theta);
+                ivf_theta_kernel<<<(nqb + 3) / 4, 256, 0, s>>>(dist, ks, lane_rank, nqb, theta);
                 PQ_HIP(ctx, hipGetLastError());
                 // (the pass over all lists on the fp16 matrix cores, every operand as two halves; option 0: on the fp32 ones)
                 const bool split16 = opt_int(ctx, PQ_OPT_IVF_COARSE_F16, 1) != 0;
-                rc = split16 ? launch_coarse_split16_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP)
-                             : launch_coarse_f32_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, ckeys, ccnt, IVF_PICK_CAP);
+                rc = split16 ? launch_coarse_split16_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, slots, ovkeys, ccnt, IVF_OV_CAP)
+                             : launch_coarse_f32_filter(ctx, qb, L->coarse_centroids, nqb, d, nlist, theta, slots, ovkeys, ccnt, IVF_OV_CAP);
                 if (rc) return rc;
-                ivf_pick_candidates_kernel<<<nqb, 256, 0, s>>>(ckeys, ccnt, ncand, cand, far, flags);
+                ivf_pick_candidates_kernel<<<nqb, 256, 0, s>>>(slots, coarse_filter_slots(nlist), ovkeys, ccnt, ncand, ckeys, kcnt, cand, far, flags);
                 ivf_refine_probes_kernel<<<nqb, IVF_REFINE_MAX, (size_t)d * 4, s>>>(qb, L->coarse_centroids, nullptr, cand, far, ncand, nlist, d,
                                                                                    nprobe, split16 ? coarse_split16_error(d) : coarse_f32_error(d),
                                                                                    maxnorm, probes, pout, flags);
-                ivf_refine_kept_kernel<<<nqb, 256, (size_t)d * 4, s>>>(qb, L->coarse_centroids, ckeys, ccnt, theta, d, nprobe,
+                ivf_refine_kept_kernel<<<nqb, 256, (size_t)d * 4, s>>>(qb, L->coarse_centroids, ckeys, kcnt, theta, d, nprobe,
                                                                       split16 ? coarse_split16_error(d) : coarse_f32_error(d), maxnorm,
                                                                       probes, pout, flags);
             } else {

@@ -618,9 +618,10 @@ static int launch_mfma128(pq_ctx *ctx, const float *queries, const float *codebo
 constexpr int MK3 = 32;        // dimensions per chunk (one barrier per chunk: 64 matrix instructions of 32 cycles are too few to hide it)
 constexpr int LS3 = MK3 + 2;   // operand row stride in floats
 constexpr int OS3 = 72;        // output row stride in floats (32 rows of 64 floats per wave at a time)
+constexpr int COARSE_SLOTS = 4; // places per row and tile of the filtering forms
 
-// FILTER: instead of the matrix, the entries at or below the row's bound theta[q] leave as keys (ordered value, column)
-// appended to the row's list cand_keys[q][cap]; cand_cnt[q] counts them all, also those that found no room.
+// FILTER: instead of the matrix, the entries at or below the row's bound theta[q] leave as keys (ordered value, column),
+// see coarse_filter_tile.
 struct CoarseF32Args {
     const float *queries, *cents;   // [nq][d], centroid i at cents + i * cent_stride
     size_t cent_stride;
@@ -628,62 +629,96 @@ struct CoarseF32Args {
     int nq, d, k;
     int tiles_x, tiles_y, total;
     const float *theta;             // FILTER: [nq]
-    unsigned long long *cand_keys;  // FILTER: [nq][cap]
-    unsigned int *cand_cnt;         // FILTER: [nq], zero at the start
-    int cap;
+    unsigned long long *slot_keys;  // FILTER: [nq][tiles_x][COARSE_SLOTS], every place written (~0: unused)
+    unsigned long long *ov_keys;    // FILTER: [nq][ov_cap]
+    unsigned int *ov_cnt;           // FILTER: [nq], zero at the start
+    int ov_cap;
 };
 
 typedef float coarse_floatx16 __attribute__((ext_vector_type(16)));
-constexpr int COARSE_WSTASH = 512;   // entries a wave collects per tile before it appends them
 
 // End of a 128 x 128 tile of the filtering forms: acc holds the inner products <y, c> of the wave's 64 x 64 outputs (lane l
 // of a matrix tile: rows 8 * (v / 4) + 4 * (l / 32) + v % 4, v = 0..15, of column l % 32), ny / nc / th the squared norms
-// and bounds of the tile's rows and columns.  The values ny + nc - 2 <y, c> at or below their row's bound leave as keys.
-// Such entries are rare: every wave collects its own in LDS first (`stash`: the operand buffers, free by now; position from
-// a count that the wave keeps in a register: no atomic operation, no waiting inside the unrolled code) and appends them to
-// the queries' lists afterwards, all of them at once.
-__device__ __forceinline__ void coarse_filter_tile(const coarse_floatx16 (&acc)[2][2], void *stash, const float *th, const float *ny,
-                                                   const float *nc, int q0, int c0, int k, unsigned long long *cand_keys,
-                                                   unsigned int *cand_cnt, int cap) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wy = wave >> 1, wx = wave & 1;
-    unsigned long long *wkeys = reinterpret_cast<unsigned long long *>(stash) + wave * COARSE_WSTASH;
-    unsigned int *wrow = reinterpret_cast<unsigned int *>(stash) + 2 * 4 * COARSE_WSTASH + wave * COARSE_WSTASH;
-    unsigned int wcount = 0;   // the same in every lane
+// and bounds of the tile's rows and columns (a bound of -inf for rows past the end, a norm of +inf for columns past the
+// end).  The values ny + nc - 2 <y, c> at or below their row's bound leave as keys (ordered value, column).  They are rare,
+// about one per row and tile, and nothing waits for global memory: every row has COARSE_SLOTS places per tile in LDS
+// (`stash`: the operand buffers, free by now), handed out by a counter in LDS, and the rows' places, used or not, leave
+// as 32 bytes per row to slot_keys[row][tile of columns][COARSE_SLOTS].  Only a row's entries beyond its places take an
+// atomic operation on global memory (ov_cnt[row], zero at the start, counts them; the first ov_cap go to ov_keys[row][]).
+// Every thread of the block calls this; the caller's barrier before the buffers are staged again ends it.
+// The wave holds rows wy * 64 .. + 63 and columns wcol .. wcol + 32 TB - 1 of the tile, as 2 x TB matrix tiles.
+template <int TB>
+__device__ __forceinline__ void coarse_filter_tile(const coarse_floatx16 (&acc)[2][TB], int wy, int wcol, void *stash, const float *th,
+                                                   const float *ny, const float *nc, int q0, int c0, int nq, int ctile, int tiles_x,
+                                                   unsigned long long *slot_keys, unsigned long long *ov_keys, unsigned int *ov_cnt,
+                                                   int ov_cap) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned long long *skeys = reinterpret_cast<unsigned long long *>(stash);          // [MT2][COARSE_SLOTS]
+    unsigned int *scnt = reinterpret_cast<unsigned int *>(skeys + MT2 * COARSE_SLOTS);   // [MT2]
+    // values of the wave on their way to the places: [output within a quarter of the lane's outputs][lane]
+    unsigned int *held = scnt + MT2 + wave * (16 * 64) + lane;
+    if (tid < 256) {
+        skeys[2 * tid] = ~0ull;
+        skeys[2 * tid + 1] = ~0ull;
+    }
+    if (tid < MT2) scnt[tid] = 0u;
+    float ncc[TB];
 #pragma unroll
-    for (int ta = 0; ta < 2; ++ta)
+    for (int tb = 0; tb < TB; ++tb) ncc[tb] = nc[wcol + tb * 32 + (lane & 31)];
+    __syncthreads();   // (the places are cleared)
+    // A quarter of the lane's outputs at a time (matrix tiles ta of both columns, 8 of their 16 registers).  Entries at or
+    // below the bound are noted first and placed afterwards: placing waits for a counter in LDS, and in the unrolled
+    // code every such wait would stand in the way of all 64 lanes.
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = wy * 64 + ta * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            const float bound = th[r], nyr = ny[r];   // (rows past the end have a bound of -inf)
+    for (int quarter = 0; quarter < 4; ++quarter) {
+        const int ta = quarter >> 1, g0 = (quarter & 1) * 2;   // registers 4 g0 .. 4 g0 + 7: rows 8 g + 4 (l / 32) + 0..3, g = g0, g0 + 1
+        const int rbase = wy * 64 + ta * 32 + 4 * (lane >> 5);
+        float4 bound4[2], nyr4[2];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb) {
-                const int c = wx * 64 + tb * 32 + (lane & 31);
-                const float val = fmaf(-2.f, acc[ta][tb][v], nyr + nc[c]);
-                const bool pass = val <= bound && c0 + c < k;
-                const unsigned long long m = __ballot(pass);
-                if (m != 0ull) {
-                    if (pass) {
-                        const unsigned long long key = ((unsigned long long)f32_to_ord(val) << 32) | (unsigned int)(c0 + c);
-                        const unsigned int slot = wcount + __builtin_amdgcn_mbcnt_hi((unsigned int)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned int)m, 0u));
-                        if (slot < (unsigned int)COARSE_WSTASH) {
-                            wkeys[slot] = key;
-                            wrow[slot] = (unsigned int)r;
-                        } else {   // (more than fit: straight to the query's list)
-                            const unsigned int pos = atomicAdd(&cand_cnt[q0 + r], 1u);
-                            if (pos < (unsigned int)cap) cand_keys[(size_t)(q0 + r) * cap + pos] = key;
-                        }
-                    }
-                    wcount += (unsigned int)__popcll(m);
+        for (int g = 0; g < 2; ++g) {
+            bound4[g] = *reinterpret_cast<const float4 *>(th + rbase + 8 * (g0 + g));
+            nyr4[g] = *reinterpret_cast<const float4 *>(ny + rbase + 8 * (g0 + g));
+        }
+        unsigned int noted = 0u;   // bit TB * vv + tb: output (register 4 g0 + vv, column tile tb)
+#pragma unroll
+        for (int vv = 0; vv < 8; ++vv) {
+            const float4 b4 = bound4[vv >> 2], n4 = nyr4[vv >> 2];
+            const float bound = (vv & 3) == 0 ? b4.x : (vv & 3) == 1 ? b4.y : (vv & 3) == 2 ? b4.z : b4.w;
+            const float nyr = (vv & 3) == 0 ? n4.x : (vv & 3) == 1 ? n4.y : (vv & 3) == 2 ? n4.z : n4.w;
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                const float val = fmaf(-2.f, acc[ta][tb][4 * g0 + vv], nyr + ncc[tb]);
+                if (val <= bound) {
+                    held[(TB * vv + tb) * 64] = __float_as_uint(val);
+                    noted |= 1u << (TB * vv + tb);
                 }
             }
         }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // within a wave LDS accesses take effect in program order
-    const unsigned int kept = wcount < (unsigned int)COARSE_WSTASH ? wcount : (unsigned int)COARSE_WSTASH;
-    for (unsigned int i = lane; i < kept; i += 64) {
-        const unsigned int q = (unsigned int)q0 + wrow[i];
-        const unsigned int pos = atomicAdd(&cand_cnt[q], 1u);
-        if (pos < (unsigned int)cap) cand_keys[(size_t)q * cap + pos] = wkeys[i];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // within a wave LDS accesses take effect in program order
+        while (noted != 0u) {
+            const int o = __builtin_ctz(noted);
+            noted &= noted - 1u;
+            const float val = __uint_as_float(held[o * 64]);
+            const int vv = o / TB, tb = o % TB;
+            const int r = rbase + 8 * (g0 + (vv >> 2)) + (vv & 3);
+            const unsigned int col = (unsigned int)(c0 + wcol + tb * 32 + (lane & 31));
+            const unsigned long long key = ((unsigned long long)f32_to_ord(val) << 32) | col;
+            const unsigned int pos = atomicAdd(&scnt[r], 1u);
+            if (pos < (unsigned int)COARSE_SLOTS) {
+                skeys[r * COARSE_SLOTS + pos] = key;
+            } else {
+                const unsigned int at = atomicAdd(&ov_cnt[q0 + r], 1u);
+                if (at < (unsigned int)ov_cap) ov_keys[(size_t)(q0 + r) * ov_cap + at] = key;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (the noted values are read before the next quarter's are written)
+    }
+    __syncthreads();
+    static_assert(COARSE_SLOTS == 4, "two threads per row, two places each");
+    const int row = tid >> 1, half = tid & 1;
+    if (tid < 256 && q0 + row < nq) {
+        const ulonglong2 two = *reinterpret_cast<const ulonglong2 *>(skeys + row * COARSE_SLOTS + 2 * half);
+        *reinterpret_cast<ulonglong2 *>(slot_keys + ((size_t)(q0 + row) * tiles_x + ctile) * COARSE_SLOTS + 2 * half) = two;
     }
 }
 
@@ -691,9 +726,9 @@ template <bool FILTER>
 __global__ __launch_bounds__(256, 2) void coarse_f32_kernel(const CoarseF32Args A) {
     typedef coarse_floatx16 floatx16;
     __shared__ __align__(16) float lds[2 * 2 * MT2 * LS3];   // [buffer][y | c][row][LS3]
-    __shared__ float ny[MT2], nc[MT2], th[MT2];
+    __shared__ __align__(16) float ny[MT2], nc[MT2], th[MT2];
     static_assert(4 * 32 * OS3 <= 2 * 2 * MT2 * LS3, "output staging fits the operand buffers");
-    static_assert(4 * COARSE_WSTASH * 12 <= (int)sizeof(float) * 2 * 2 * MT2 * LS3, "the collected entries fit the operand buffers");
+    static_assert(MT2 * (COARSE_SLOTS * 8 + 4) + 256 * 16 * 4 <= (int)sizeof(float) * 2 * 2 * MT2 * LS3, "the rows' places and the noted entries fit the operand buffers");
     const int nq = A.nq, d = A.d, k = A.k;
     const int per_die = (A.total + 7) >> 3, blocks_per_die = gridDim.x >> 3;
     const int die = blockIdx.x & 7;
@@ -825,14 +860,15 @@ __global__ __launch_bounds__(256, 2) void coarse_f32_kernel(const CoarseF32Args 
                 norm_y[p] += __shfl_xor(norm_y[p], o);
                 norm_c[p] += __shfl_xor(norm_c[p], o);
             }
-            if ((tid & 7) == 0) { ny[p * 32 + srow] = norm_y[p]; nc[p * 32 + srow] = norm_c[p]; }
+            // (columns past the end: with FILTER a norm that keeps them out)
+            if ((tid & 7) == 0) { ny[p * 32 + srow] = norm_y[p]; nc[p * 32 + srow] = FILTER && cur.c0 + p * 32 + srow >= k ? __builtin_inff() : norm_c[p]; }
         }
         __syncthreads();
         // lane l of a matrix tile holds rows 8 * (v / 4) + 4 * (l / 32) + v % 4 (v = 0..15) of column l % 32
         if (FILTER) {
-            coarse_filter_tile(acc, lds, th, ny, nc, cur.q0, cur.c0, k, A.cand_keys, A.cand_cnt, A.cap);
+            coarse_filter_tile<2>(acc, wy, wx * 64, lds, th, ny, nc, cur.q0, cur.c0, nq, cur.c0 / MT2, A.tiles_x, A.slot_keys, A.ov_keys, A.ov_cnt, A.ov_cap);
             if (!more) break;
-            __syncthreads();   // every wave has left its collected entries: the operand buffers are free again
+            __syncthreads();   // the rows' places have left: the operand buffers are free again
             local += blocks_per_die;
             cur = next;
             rows = next_rows;
@@ -900,15 +936,18 @@ int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, siz
     return PQ_OK;
 }
 
-// The same distances, but only those at or below theta[q] leave, as keys (ordered value << 32 | centroid) appended to
-// cand_keys[q][cap]; cand_cnt[q] (zero at the start) counts them all.
+// The same distances, but only those at or below theta[q] leave, as keys (ordered value << 32 | centroid): COARSE_SLOTS
+// places per query and 128 centroids in slot_keys[q][coarse_filter_slots(k)] (~0: unused), the entries beyond them in
+// ov_keys[q][ov_cap]; ov_cnt[q] (zero at the start) counts those.
+int coarse_filter_slots(int k) { return (k + MT2 - 1) / MT2 * COARSE_SLOTS; }
+
 int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
-                             unsigned long long *cand_keys, unsigned int *cand_cnt, int cap) {
+                             unsigned long long *slot_keys, unsigned long long *ov_keys, unsigned int *ov_cnt, int ov_cap) {
     if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, queries)) return fail(ctx, PQ_EINVAL, "coarse_f32: shape not served");
     CoarseF32Args A{};
     A.queries = queries; A.cents = cents; A.cent_stride = (size_t)d; A.out = nullptr; A.nq = nq; A.d = d; A.k = k;
     A.tiles_x = (k + MT2 - 1) / MT2; A.tiles_y = (nq + MT2 - 1) / MT2; A.total = A.tiles_x * A.tiles_y;
-    A.theta = theta; A.cand_keys = cand_keys; A.cand_cnt = cand_cnt; A.cap = cap;
+    A.theta = theta; A.slot_keys = slot_keys; A.ov_keys = ov_keys; A.ov_cnt = ov_cnt; A.ov_cap = ov_cap;
     const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
     coarse_f32_kernel<true><<<grid, 256, 0, ctx->stream>>>(A);
     PQ_HIP(ctx, hipGetLastError());
@@ -1013,15 +1052,25 @@ struct CoarseSplit16Args {
     int nq, k, nch;
     int tiles_x, tiles_y, total;
     const float *theta;             // [nq]
-    unsigned long long *cand_keys;  // [nq][cap]
-    unsigned int *cand_cnt;         // [nq], zero at the start
-    int cap;
+    unsigned long long *slot_keys;  // [nq][tiles_x][COARSE_SLOTS], every place written (~0: unused)
+    unsigned long long *ov_keys;    // [nq][ov_cap]
+    unsigned int *ov_cnt;           // [nq], zero at the start
+    int ov_cap;
 };
 
-__global__ __launch_bounds__(256, 2) void coarse_split16_filter_kernel(const CoarseSplit16Args A) {
+#ifdef PQ_SCAN_TIMING
+__device__ unsigned long long g_split16_ticks[8];
+#define H16_TICK(phase) do { const unsigned long long now__ = __builtin_amdgcn_s_memtime(); tick_acc[phase] += now__ - tick_last; tick_last = now__; } while (0)
+#else
+#define H16_TICK(phase) do { } while (0)
+#endif
+
+// Blocks of 8 waves, two per compute unit (4 waves per SIMD: the end of a tile and the staging are waits, mostly); wave
+// (wy, wx) holds rows 64 wy .. and columns 32 wx .. of the tile.
+__global__ __launch_bounds__(512, 4) void coarse_split16_filter_kernel(const CoarseSplit16Args A) {
     __shared__ lut_u32x4 lds[2 * 2 * MT2 * HROW];   // [buffer][y | c][row][HROW]
-    __shared__ float ny[MT2], nc[MT2], th[MT2];
-    static_assert(4 * COARSE_WSTASH * 12 <= (int)sizeof(lut_u32x4) * 2 * 2 * MT2 * HROW, "the collected entries fit the operand buffers");
+    __shared__ __align__(16) float ny[MT2], nc[MT2], th[MT2];
+    static_assert(MT2 * (COARSE_SLOTS * 8 + 4) + 512 * 16 * 4 <= (int)sizeof(lut_u32x4) * 2 * 2 * MT2 * HROW, "the rows' places and the noted entries fit the operand buffers");
     const unsigned int fy = split16_scale_field(A.maxbits[0]), fc = split16_scale_field(A.maxbits[1]);
     if (fy == 0u || fc == 0u) return;   // (uniform: magnitudes that the halves do not serve)
     const float unscale = __uint_as_float((381u - fy - fc) << 23);   // 1 / (s_y s_c) = 2^(254 - fy - fc): between 2^-106 and 2^54
@@ -1030,72 +1079,72 @@ __global__ __launch_bounds__(256, 2) void coarse_split16_filter_kernel(const Coa
     const int die = blockIdx.x & 7;
     int local = blockIdx.x >> 3;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wy = wave >> 1, wx = wave & 1;
+    const int wy = wave >> 2, wx = wave & 3;
     auto has_tile = [&](int l) { return l < per_die && die * per_die + l < A.total; };
     if (!has_tile(local)) return;
-    // piece tid % 8 of rows tid / 8 + 32 * pass (the operands are padded to whole tiles)
+    // piece tid % 8 of rows tid / 8 + 64 * pass (the operands are padded to whole tiles)
     const int srow = tid >> 3, seg = tid & 7;
-    lut_u32x4 rf[2][4];   // [y | c][pass]: the chunk after the one being multiplied
+    lut_u32x4 rf[2][2];   // [y | c][pass]: the chunk after the one being multiplied
     auto fetch = [&](const Tile128 &t, int c) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            rf[0][p] = A.yh[((size_t)(t.q0 + p * 32 + srow) * nch + c) * 8 + seg];
-            rf[1][p] = A.ch[((size_t)(t.c0 + p * 32 + srow) * nch + c) * 8 + seg];
+        for (int p = 0; p < 2; ++p) {
+            rf[0][p] = A.yh[((size_t)(t.q0 + p * 64 + srow) * nch + c) * 8 + seg];
+            rf[1][p] = A.ch[((size_t)(t.c0 + p * 64 + srow) * nch + c) * 8 + seg];
         }
     };
     auto stage = [&](int buf) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            lds[((buf * 2 + 0) * MT2 + p * 32 + srow) * HROW + seg] = rf[0][p];
-            lds[((buf * 2 + 1) * MT2 + p * 32 + srow) * HROW + seg] = rf[1][p];
+        for (int p = 0; p < 2; ++p) {
+            lds[((buf * 2 + 0) * MT2 + p * 64 + srow) * HROW + seg] = rf[0][p];
+            lds[((buf * 2 + 1) * MT2 + p * 64 + srow) * HROW + seg] = rf[1][p];
         }
     };
-    coarse_floatx16 acc[2][2];
+    coarse_floatx16 acc[2][1];
     // lane l feeds row l % 32 of its matrix tiles, dimensions 16 * step + 8 * (l / 32) .. + 7 of the chunk
     auto compute = [&](int buf) {
         const lut_u32x4 *yt = lds + ((buf * 2 + 0) * MT2 + wy * 64 + (lane & 31)) * HROW + (lane >> 5);
-        const lut_u32x4 *ct = lds + ((buf * 2 + 1) * MT2 + wx * 64 + (lane & 31)) * HROW + (lane >> 5);
+        const lut_u32x4 *ct = lds + ((buf * 2 + 1) * MT2 + wx * 32 + (lane & 31)) * HROW + (lane >> 5);
 #pragma unroll
         for (int step = 0; step < HK / 16; ++step) {
-            lut_half8 ah[2], al[2], bh[2], bl[2];
+            lut_half8 ah[2], al[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 ah[t] = __builtin_bit_cast(lut_half8, yt[t * 32 * HROW + 2 * step]);
                 al[t] = __builtin_bit_cast(lut_half8, yt[t * 32 * HROW + 4 + 2 * step]);
-                bh[t] = __builtin_bit_cast(lut_half8, ct[t * 32 * HROW + 2 * step]);
-                bl[t] = __builtin_bit_cast(lut_half8, ct[t * 32 * HROW + 4 + 2 * step]);
             }
+            const lut_half8 bh = __builtin_bit_cast(lut_half8, ct[2 * step]);
+            const lut_half8 bl = __builtin_bit_cast(lut_half8, ct[4 + 2 * step]);
 #pragma unroll
-            for (int ta = 0; ta < 2; ++ta)
-#pragma unroll
-                for (int tb = 0; tb < 2; ++tb) {
-                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bh[tb], acc[ta][tb], 0, 0, 0);
-                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bl[tb], acc[ta][tb], 0, 0, 0);
-                    acc[ta][tb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[ta], bh[tb], acc[ta][tb], 0, 0, 0);
-                }
+            for (int ta = 0; ta < 2; ++ta) {
+                acc[ta][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bh, acc[ta][0], 0, 0, 0);
+                acc[ta][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ah[ta], bl, acc[ta][0], 0, 0, 0);
+                acc[ta][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al[ta], bh, acc[ta][0], 0, 0, 0);
+            }
         }
     };
 
     Tile128 cur = tile128_of(die * per_die + local, A.tiles_x, A.tiles_y);
     fetch(cur, 0);
+#ifdef PQ_SCAN_TIMING
+    unsigned long long tick_acc[5] = {0, 0, 0, 0, 0}, tick_last = __builtin_amdgcn_s_memtime();
+#endif
     for (;;) {
         const bool more = has_tile(local + blocks_per_die);
         const Tile128 next = more ? tile128_of(die * per_die + local + blocks_per_die, A.tiles_x, A.tiles_y) : cur;
 #pragma unroll
         for (int ta = 0; ta < 2; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[ta][tb][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[ta][0][v] = 0.f;
         if (tid < MT2) {
             th[tid] = cur.q0 + tid < nq ? A.theta[cur.q0 + tid] : -__builtin_inff();
             ny[tid] = A.nyg[cur.q0 + tid];
-            nc[tid] = A.ncg[cur.c0 + tid];
+            nc[tid] = cur.c0 + tid < k ? A.ncg[cur.c0 + tid] : __builtin_inff();   // (columns past the end stay out)
         }
         stage(0);
         if (1 < nch) fetch(cur, 1);
         else if (more) fetch(next, 0);
         __syncthreads();
+        H16_TICK(0);
         // chunk c is multiplied from buffer c % 2 while chunk c + 1 goes into the other one (which every wave has left:
         // the barrier stands after the multiplications) and chunk c + 2 is on its way from memory
         for (int c = 0; c < nch; ++c) {
@@ -1104,21 +1153,26 @@ __global__ __launch_bounds__(256, 2) void coarse_split16_filter_kernel(const Coa
                 if (c + 2 < nch) fetch(cur, c + 2);
                 else if (more) fetch(next, 0);
             }
+            H16_TICK(1);
             compute(c & 1);
+            H16_TICK(2);
             __syncthreads();
+            H16_TICK(3);
         }
 #pragma unroll
         for (int ta = 0; ta < 2; ++ta)
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[ta][tb][v] *= unscale;   // (a power of two: exact)
-        coarse_filter_tile(acc, lds, th, ny, nc, cur.q0, cur.c0, k, A.cand_keys, A.cand_cnt, A.cap);
+            for (int v = 0; v < 16; ++v) acc[ta][0][v] *= unscale;   // (a power of two: exact)
+        coarse_filter_tile<1>(acc, wy, wx * 32, lds, th, ny, nc, cur.q0, cur.c0, nq, cur.c0 / MT2, A.tiles_x, A.slot_keys, A.ov_keys, A.ov_cnt, A.ov_cap);
         if (!more) break;
-        __syncthreads();   // every wave has left its collected entries: the operand buffers are free again
+        __syncthreads();   // the rows' places have left: the operand buffers are free again
+        H16_TICK(4);
         local += blocks_per_die;
         cur = next;
     }
+#ifdef PQ_SCAN_TIMING
+    if (lane == 0) for (int i = 0; i < 5; ++i) atomicAdd(&g_split16_ticks[i], tick_acc[i]);
+#endif
 }
 
 // Bound on |approximate - exact| / (||y||^2 + ||c||^2) for the kernel above.  The inner product is a sum of 3 dpad exact
@@ -1134,7 +1188,7 @@ float coarse_split16_error(int d) {
 
 // The filtering pass of launch_coarse_f32_filter through split fp16 operands (shapes as coarse_f32_usable accepts them).
 int launch_coarse_split16_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
-                                 unsigned long long *cand_keys, unsigned int *cand_cnt, int cap) {
+                                 unsigned long long *slot_keys, unsigned long long *ov_keys, unsigned int *ov_cnt, int ov_cap) {
     if (!coarse_f32_usable(ctx, queries, cents, nq, d, k, queries)) return fail(ctx, PQ_EINVAL, "coarse_split16: shape not served");
     CoarseSplit16Args A{};
     A.nq = nq; A.k = k; A.nch = (d + HK - 1) / HK;
@@ -1152,10 +1206,21 @@ int launch_coarse_split16_filter(pq_ctx *ctx, const float *queries, const float 
     split16_prep_kernel<<<(unsigned)((rows_y + 31) / 32), 256, 0, ctx->stream>>>(queries, nq, (int)rows_y, d, A.nch, maxbits, yh, nyg);
     split16_prep_kernel<<<(unsigned)((rows_c + 31) / 32), 256, 0, ctx->stream>>>(cents, k, (int)rows_c, d, A.nch, maxbits + 1, ch, ncg);
     A.yh = yh; A.ch = ch; A.nyg = nyg; A.ncg = ncg; A.maxbits = maxbits;
-    A.theta = theta; A.cand_keys = cand_keys; A.cand_cnt = cand_cnt; A.cap = cap;
+    A.theta = theta; A.slot_keys = slot_keys; A.ov_keys = ov_keys; A.ov_cnt = ov_cnt; A.ov_cap = ov_cap;
     const int grid = (2 * ctx->num_cu + 7) / 8 * 8;
-    coarse_split16_filter_kernel<<<grid, 256, 0, ctx->stream>>>(A);
+    coarse_split16_filter_kernel<<<grid, 512, 0, ctx->stream>>>(A);
     PQ_HIP(ctx, hipGetLastError());
+#ifdef PQ_SCAN_TIMING
+    {
+        unsigned long long t[8] = {0};
+        PQ_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        PQ_HIP(ctx, hipMemcpyFromSymbol(t, HIP_SYMBOL(g_split16_ticks), sizeof(t)));
+        fprintf(stderr, "split16 filter (wave ticks x 1e6): tile start %.1f stage %.1f multiply %.1f barrier %.1f end of tile %.1f\n", t[0] / 1e6,
+                t[1] / 1e6, t[2] / 1e6, t[3] / 1e6, t[4] / 1e6);
+        unsigned long long z[8] = {0};
+        PQ_HIP(ctx, hipMemcpyToSymbol(HIP_SYMBOL(g_split16_ticks), z, sizeof(z)));
+    }
+#endif
     return PQ_OK;
 }
 

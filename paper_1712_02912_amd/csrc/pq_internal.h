@@ -85,13 +85,14 @@ int launch_rotate(pq_ctx *ctx, const float *vectors, const float *rot, int64_t n
 float coarse_f32_error(int d);
 bool coarse_f32_usable(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *out);
 int launch_coarse_f32(pq_ctx *ctx, const float *queries, const float *cents, size_t cent_stride, int nq, int d, int k, float *out);
+int coarse_filter_slots(int k);   // places per query that the filtering forms write
 int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
-                             unsigned long long *cand_keys, unsigned int *cand_cnt, int cap);
+                             unsigned long long *slot_keys, unsigned long long *ov_keys, unsigned int *ov_cnt, int ov_cap);
 // The same filtering pass on the fp16 matrix cores (operands split into two halves each), within coarse_split16_error(d) *
 // (||y||^2 + ||c||^2); magnitudes outside 2^-40 .. 2^40 keep nothing.
 float coarse_split16_error(int d);
 int launch_coarse_split16_filter(pq_ctx *ctx, const float *queries, const float *cents, int nq, int d, int k, const float *theta,
-                                 unsigned long long *cand_keys, unsigned int *cand_cnt, int cap);
+                                 unsigned long long *slot_keys, unsigned long long *ov_keys, unsigned int *ov_cnt, int ov_cap);
 int launch_encode(pq_ctx *ctx, const float *vectors, const float *codebooks, int64_t n, int d, int m, int k, int cf,
                   uint8_t *codes);
 int launch_derived_search(pq_ctx *ctx, const uint16_t *codes16, int64_t n, const float *derived_codebooks,

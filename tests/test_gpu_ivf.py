@@ -303,8 +303,26 @@ def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, n
     gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
     ref, _ = orc.ivf_probe(queries, coarse, nprobe)
     assert np.array_equal(gp, ref)
+    opts.set("ivf_coarse_f16", 0)   # the pass over all lists on the fp32 matrix cores instead of split fp16 operands
+    assert np.array_equal(_probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe), ref)
     opts.set("ivf_coarse_f32", 0)   # the exact Tables step for the Index step gives the same lists
     assert np.array_equal(_probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe), ref)
+
+
+@pytest.mark.parametrize("scale", [2.0 ** 50, 2.0 ** -50, 0.0])
+def test_ivf_index_step_magnitudes_outside_the_split_operands(ctx, scale):
+    """The split fp16 operands serve magnitudes of 2^-40 .. 2^40: beyond them (and for all-zero queries) the pass over all
+    lists keeps nothing or its proof fails, and every query takes its exact row; the probed lists are the oracle's."""
+    nlist, nq, d, nprobe = 32768, 1030, 32, 20
+    coarse, offsets, codes, cb, queries = _many_lists_problem(5, nlist, nq, d)
+    if scale == 0.0:
+        queries = np.zeros_like(queries)
+    else:
+        coarse = (coarse * np.float32(scale)).astype(np.float32)
+        queries = (queries * np.float32(scale)).astype(np.float32)
+    gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
+    ref, _ = orc.ivf_probe(queries, coarse, nprobe)
+    assert np.array_equal(gp, ref)
 
 
 @pytest.mark.parametrize("nlist,nq,d", [(4096, 2100, 64), (32768, 4100, 32)])

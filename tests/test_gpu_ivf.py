@@ -295,9 +295,12 @@ def _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe):
     return p.cpu().numpy()
 
 
-# (the last case has lists and queries enough for the form that writes no matrix: a sample of the lists gives every query
-# a bound, and only the distances at or below it leave the kernel)
-@pytest.mark.parametrize("nlist,nq,d,nprobe", [(4096, 2100, 64, 16), (8192, 1100, 32, 64), (5000, 1700, 128, 3), (32768, 4100, 32, 20)])
+# (with lists and queries enough nothing like a matrix is written: a sample of the lists gives every query a bound, and only
+# the distances at or below it leave the kernel)
+# (the last two cases have lists and queries enough for the form that writes no matrix; the last one with a ragged last
+# tile of lists and sub-vectors that end inside a chunk of 32 dimensions)
+@pytest.mark.parametrize("nlist,nq,d,nprobe", [(4096, 2100, 64, 16), (8192, 1100, 32, 64), (5000, 1700, 128, 3), (32768, 4100, 32, 20),
+                                               (20000, 6700, 48, 10)])
 def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, nprobe):
     coarse, offsets, codes, cb, queries = _many_lists_problem(nlist + nq, nlist, nq, d)
     gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)

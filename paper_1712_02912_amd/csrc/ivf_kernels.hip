@@ -19,6 +19,7 @@
 #include "pq_internal.h"
 #include "scan_common.h"
 #include "topk_device.h"
+#include "lds_walk.h"
 
 namespace pq {
 
@@ -166,6 +167,18 @@ __global__ __launch_bounds__(256) void ivf_residual_kernel(const float *__restri
     const int p = (int)(i / d), t = (int)(i % d);
     const int q = p / nprobe, l = probes[p];
     resid[i] = queries[(size_t)q * d + t] - coarse[(size_t)l * d + t];
+}
+
+// the same, four dimensions per thread (d a multiple of 4, all rows on 16-byte boundaries); d4 = d / 4
+__global__ __launch_bounds__(256) void ivf_residual4_kernel(const float4 *__restrict__ queries, const float4 *__restrict__ coarse,
+                                                            const int32_t *__restrict__ probes, int npairs, int nprobe, int d4,
+                                                            float4 *__restrict__ resid) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)npairs * d4) return;
+    const int p = (int)(i / (unsigned int)d4), t = (int)(i - (size_t)p * d4);
+    const int q = p / nprobe, l = probes[p];
+    const float4 y = queries[(size_t)q * d4 + t], c = coarse[(size_t)l * d4 + t];
+    resid[i] = make_float4(y.x - c.x, y.y - c.y, y.z - c.z, y.w - c.w);
 }
 
 __global__ void ivf_zero_kernel(uint32_t *p, size_t n) {
@@ -351,7 +364,7 @@ __global__ void ivf_pair_abs_kernel(const uint32_t *__restrict__ qlist_off, size
     if (p < npairs) pair_out[p] += qlist_off[p / nprobe];
 }
 
-// First bound per query: float ADC (table order) of up to IVF_SEED_CODES codes taken from the
+// First bound per query: float ADC (the tables' entries added in an order that depends on the lane) of up to IVF_SEED_CODES codes taken from the
 // query's probed lists in probe order, each with the tables of its (query, list) pair.  The greatest
 // of the first topk distances is a bound already; the distances at or below it are counted in bins of
 // 2^HIST_SHIFT ordered-value units below it (0.2 % of the value each), and the smallest bin edge with
@@ -365,10 +378,11 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
                                                        const int64_t *__restrict__ list_offsets,
                                                        const int32_t *__restrict__ probes, const float *__restrict__ luts,
                                                        int nprobe, int topk, float *tau0) {
-    __shared__ float tab[M * 256];
+    __shared__ __align__(16) float tab[M * 256];
     __shared__ __align__(16) uint32_t hist[HIST_BINS];
     __shared__ uint32_t ref_s;
     const int q = blockIdx.x, tid = threadIdx.x;
+    const uint32_t rot = (uint32_t)tid & (M - 1);
     for (int i = tid; i < HIST_BINS; i += 256) hist[i] = 0;
     if (tid == 0) ref_s = 0;
     // f(ordered distance) for the first `limit` codes of the probed lists; returns how many there were
@@ -381,7 +395,15 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
             if (take <= 0) continue;
             const float *lut = luts + ((size_t)q * nprobe + r) * M * 256;
             __syncthreads();
-            for (int i = tid; i < M * 256; i += 256) tab[i] = lut[i];
+            // entry b of table j at word b * M + j: a lane walks the tables from its own first one (lane % M), so the lanes
+            // that the LDS serves together read M different columns of banks
+            {
+                float e[M];
+#pragma unroll
+                for (int j = 0; j < M; ++j) e[j] = lut[j * 256 + tid];
+#pragma unroll
+                for (int j = 0; j < M; j += 4) *reinterpret_cast<float4 *>(tab + tid * M + j) = make_float4(e[j], e[j + 1], e[j + 2], e[j + 3]);
+            }
             __syncthreads();
             struct Code { uint32_t w[M / 4]; };
             auto load_code = [&](int i) {
@@ -391,10 +413,12 @@ __global__ __launch_bounds__(256) void ivf_seed_kernel(const uint8_t *__restrict
                 else { const uint4 v = *reinterpret_cast<const uint4 *>(c); k.w[0] = v.x; k.w[1] = v.y; k.w[M / 4 - 2] = v.z; k.w[M / 4 - 1] = v.w; }
                 return k;
             };
-            auto eval = [&](const Code &k) {
-                float dist = 0.f;
+            auto eval = [&](Code k) {
+                if constexpr (M == 8) rot8(k.w[0], k.w[1], (rot & 4u) != 0u, rot & 3u);
+                else rot16(k.w, rot);
+                float dist = 0.f;   // (the entries of the code's M tables, added from table lane % M on)
 #pragma unroll
-                for (int j = 0; j < M; ++j) dist += tab[j * 256 + ((k.w[j >> 2] >> (8 * (j & 3))) & 255u)];
+                for (int st = 0; st < M; ++st) dist += tab[(((k.w[st >> 2] >> (8 * (st & 3))) & 255u) * M) | ((rot + st) & (M - 1))];
                 f(f32_to_ord(dist));
             };
             // four codes of a thread on their way at a time (the loop is otherwise a chain of load latencies)
@@ -893,8 +917,12 @@ int launch_ivf(pq_ctx *ctx, const ivf_lists *L, const float *codebooks, int m, i
         // Tables step on the residuals
         {
             const size_t n = (size_t)npairs * d;
-            ivf_residual_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(qb, L->coarse_centroids, probes, npairs,
-                                                                            nprobe, d, resid);
+            const bool by4 = (d & 3) == 0 && (((uintptr_t)qb | (uintptr_t)L->coarse_centroids | (uintptr_t)resid) & 15) == 0;
+            if (by4)
+                ivf_residual4_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, s>>>((const float4 *)qb, (const float4 *)L->coarse_centroids, probes,
+                                                                                     npairs, nprobe, d / 4, (float4 *)resid);
+            else
+                ivf_residual_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(qb, L->coarse_centroids, probes, npairs, nprobe, d, resid);
             PQ_HIP(ctx, hipGetLastError());
         }
         rc = launch_build_luts(ctx, resid, codebooks, npairs, d, m, k, luts);

@@ -84,7 +84,7 @@ const char *pq_version(void);
  *   ivf_ws_gib (24)           workspace limit of ivf_adc_search in GiB (1 ... 128)
  *   ivf_block_waves (8)       16: inverted lists scanned by blocks of 16 waves
  *   scan_wide_seed (1)        0: first bounds of flat scans of few queries from the small sample only
- *   ivf_short_max (16384)     inverted lists of fewer codes take the kernel for short lists (0: none)
+ *   ivf_short_max (12288)     inverted lists of fewer codes take the kernel for short lists (0: none)
  *   ivf_coarse_f32 (1)        0: Index step of ivf_adc_search from exact distances to every list (default: lists
  *                             ranked by matrix-core distances, the nearest measured exactly; same lists)
  *   ivf_coarse_f16 (1)        0: the ranking pass over all lists on the fp32 matrix cores (default: on the fp16 ones,

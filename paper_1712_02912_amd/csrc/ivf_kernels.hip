@@ -34,7 +34,7 @@ constexpr float IVF_PRUNE_RANGE = 3500.f;      // table units between the sum of
 constexpr int IVF_QB_PLAIN = 4;               // queries per work item: plain float loop
 constexpr int IVF_QB_PRUNED = 8;              // and the loop on 16-bit lower bounds
 constexpr int IVF_QB_QUICK = 8;               // Quick ADC: pairs whose 8-bit tables lie side by side
-constexpr int IVF_SHORT_MAX = 16384;          // lists of fewer codes are scanned by the kernel of short lists (8 tables, plain loop)
+constexpr int IVF_SHORT_MAX = 12288;          // lists of fewer codes are scanned by the kernel of short lists (8 tables, plain loop)
 
 // ------------------------------------------------------------------------------------------
 // nprobe smallest (distance, list id) of one row of coarse distances.  One block per query.

@@ -329,6 +329,17 @@ __global__ __launch_bounds__(1024) void merge_filtered_kernel(const uint64_t *__
         nshort = s_count;
         src = shortlist;
     }
+    if (nshort > 256) {
+        // long results: counting the smaller keys is nshort^2 broadcast reads (a thousand keys: 40 us of LDS time on a
+        // compute unit that holds four such blocks); the short list is sorted instead (at most 1024 keys: 55 stages)
+        uint64_t *buf = kept > topk ? shortlist : skeys;   // (nshort <= topk <= 1024 either way)
+        int n2 = 512;
+        while (n2 < nshort) n2 <<= 1;
+        for (int i = nshort + tid; i < n2; i += blockDim.x) buf[i] = KEY_EMPTY;
+        block_bitonic_sort(buf, n2);
+        for (int i = tid; i < topk; i += blockDim.x) emit(i, i < nshort ? buf[i] : KEY_EMPTY);
+        return;
+    }
     for (int i = tid; i < nshort; i += blockDim.x) {
         const uint64_t mine = src[i];
         int rank = 0;

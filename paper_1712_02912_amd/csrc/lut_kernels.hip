@@ -961,7 +961,7 @@ int launch_coarse_f32_filter(pq_ctx *ctx, const float *queries, const float *cen
 // its size), and <y, c> is accumulated in fp32 as hi hi + hi lo + lo hi (products of halves are exact in fp32; the
 // omitted lo lo is below 2^-22 of |y| |c|).  The operands are split once per call by split16_prep_kernel, [row][chunk
 // of 32 dimensions][32 hi | 32 lo] with the rows' squared norms beside them, so the kernel stages 16-byte pieces
-// as they are.  Same tiling, block numbering and end of tile as the fp32 form.
+// as they are.  Tiles of 128 x 128, block numbering and end of tile as in the fp32 form.
 // Magnitudes outside 2^-40 .. 2^40 (or not finite) are not served: the kernel keeps nothing then, and the caller's
 // queries, left without candidates, take their exact rows.
 constexpr int HK = 32;     // dimensions per chunk

@@ -312,6 +312,22 @@ def test_ivf_index_step_through_approximate_distances(ctx, opts, nlist, nq, d, n
     assert np.array_equal(_probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe), ref)
 
 
+def test_ivf_index_step_wide_dynamic_range(ctx):
+    """Coordinates whose scales differ by factors of e^3 per dimension (a few dimensions carry nearly all of the norms, so
+    the halves of the split operands lose most of the small ones' bits): the probed lists are still the oracle's."""
+    nlist, nq, d, nprobe = 40000, 3400, 96, 100
+    r = np.random.default_rng(103)
+    spread = np.exp(r.standard_normal((1, d)) * 3)
+    coarse = (r.standard_normal((nlist, d)) * spread).astype(np.float32)
+    queries = (r.standard_normal((nq, d)) * spread).astype(np.float32)
+    offsets = datagen.offsets_from_sizes(np.full(nlist, 2))
+    codes = r.integers(0, 256, (nlist * 2, 8), dtype=np.uint8)
+    cb = (r.random((8, 256, d // 8)) * 20).astype(np.float32)
+    gp = _probes_only(ctx, coarse, offsets, codes, cb, queries, nprobe)
+    ref, _ = orc.ivf_probe(queries, coarse, nprobe)
+    assert np.array_equal(gp, ref)
+
+
 @pytest.mark.parametrize("scale", [2.0 ** 50, 2.0 ** -50, 0.0])
 def test_ivf_index_step_magnitudes_outside_the_split_operands(ctx, scale):
     """The split fp16 operands serve magnitudes of 2^-40 .. 2^40: beyond them (and for all-zero queries) the pass over all

@@ -1677,7 +1677,8 @@ __global__ __launch_bounds__(64) void u4_seed_pick_kernel(const uint32_t *__rest
 // integer test dismisses): one block per four queries looks at the first `cnt` codes, counts the float distances at or
 // below the bound known so far (tau0 as handed in, or with self_ref the greatest distance of the first k codes)
 // in the bins the scan's histogram uses, and lowers tau0 to the smallest bin edge with at least k
-// distances at or below it.  Distances are summed in table order, as everywhere on this path.
+// distances at or below it, enlarged by 4e-6 of itself: the distances are summed from the lane's own first table on,
+// not in table order as in the scans (the tables' layout in LDS, see below).
 template <int M>
 __global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__restrict__ codes, int cnt,
                                                                const float *__restrict__ luts, int k, bool self_ref, int nq,
@@ -1690,12 +1691,15 @@ __global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__
     __shared__ uint32_t ref_s[SEED_QPB];
     const int q0 = blockIdx.x * SEED_QPB, tid = threadIdx.x;
     const int myq = tid >> 8, sub = tid & 255;   // 256 threads per query where the queries are handled apart
+    // entry b of table j at slot b * M + j: a lane walks the tables from its own first one (lane % M), so the 16 lanes that the
+    // LDS serves together read at least 8 different bank groups whatever their bytes are (all in one table: 16 random ones)
     for (int e = tid; e < M * 256; e += 1024) {
         float v[SEED_QPB];
 #pragma unroll
         for (int qq = 0; qq < SEED_QPB; ++qq) v[qq] = q0 + qq < nq ? luts[(size_t)(q0 + qq) * (M * 256) + e] : __builtin_inff();
-        tab[e] = make_float4(v[0], v[1], v[2], v[3]);
+        tab[(e & 255) * M + (e >> 8)] = make_float4(v[0], v[1], v[2], v[3]);
     }
+    const uint32_t rot = (uint32_t)tid & (M - 1);
     for (int i = tid; i < SEED_QPB * HIST_BINS; i += 1024) (&hist[0][0])[i] = 0;
     if (sub == 0) ref_s[myq] = self_ref || q0 + myq >= nq ? 0u : f32_to_ord(tau0[q0 + myq]);
     __syncthreads();
@@ -1711,12 +1715,14 @@ __global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__
         }
         return c;
     };
-    auto dist_ords = [&](const Code &c, uint32_t (&ord)[SEED_QPB]) {
-        const uint32_t (&w)[M / 4] = c.w;
-        float4 d = tab[w[0] & 255u];
+    auto dist_ords = [&](Code c, uint32_t (&ord)[SEED_QPB]) {
+        uint32_t (&w)[M / 4] = c.w;
+        if constexpr (M == 8) rot8(w[0], w[1], (rot & 4u) != 0u, rot & 3u);
+        else rot16(w, rot);
+        float4 d = tab[(w[0] & 255u) * M + rot];   // (step s: byte s of the rotated code, table (rot + s) % M)
 #pragma unroll
-        for (int j = 1; j < M; ++j) {
-            const float4 t = tab[j * 256 + ((w[j >> 2] >> (8 * (j & 3))) & 255u)];
+        for (int st = 1; st < M; ++st) {
+            const float4 t = tab[((w[st >> 2] >> (8 * (st & 3))) & 255u) * M + ((rot + st) & (M - 1))];
             d.x += t.x; d.y += t.y; d.z += t.z; d.w += t.w;
         }
         ord[0] = f32_to_ord(d.x); ord[1] = f32_to_ord(d.y); ord[2] = f32_to_ord(d.z); ord[3] = f32_to_ord(d.w);
@@ -1780,8 +1786,11 @@ __global__ __launch_bounds__(1024) void f32_seed_refine_kernel(const uint8_t *__
     kth_bins();
     if (sub == 0 && q0 + myq < nq) {
         const int q = q0 + myq;
-        if (bin_s[myq] < HIST_BINS) tau0[q] = ord_to_f32(edge_of(ref_s[myq], bin_s[myq]));
-        else if (self_ref) tau0[q] = cnt >= k ? ord_to_f32(ref_s[myq]) : __builtin_inff();
+        // (enlarged by a few units of fp32 rounding: the scans add a code's entries in table order, this kernel from
+        // the lane's own first table on)
+        auto enlarged = [](float x) { return x + fabsf(x) * 4e-6f; };
+        if (bin_s[myq] < HIST_BINS) tau0[q] = enlarged(ord_to_f32(edge_of(ref_s[myq], bin_s[myq])));
+        else if (self_ref) tau0[q] = cnt >= k ? enlarged(ord_to_f32(ref_s[myq])) : __builtin_inff();
     }
 }
 
